@@ -1,0 +1,362 @@
+"""Deterministic host-side index construction (Alg. 1 of the paper: AddVectors).
+
+Produces, from base vectors, everything the search path takes as input:
+coarse centroids (k-means), PQ codebook and 4-bit codes (Section 2.2), the two list ids per
+vector chosen by RairAssign (Alg. 3, AIR metric of Theorem 1), and the SEIL list layout written by
+SeilInsert (Alg. 4) for a single batch.  The result is a `HostIndex` in a canonical host layout
+that both the CPU oracle and the device upload consume; neither of them is imported here.
+
+Construction is not on the measured path.  It is plain numpy, seeded, and reproducible.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+BLK = 32  # items per block (BLK_SZ in Alg. 4)
+
+
+@dataclass
+class HostIndex:
+    d: int
+    M: int
+    nlist: int
+    ntotal: int
+    centroids: np.ndarray          # [nlist][d] f32
+    codebook: np.ndarray           # [M][16][d/M] f32
+    # SEIL layout (Section 5.1): a flat array of 32-item blocks; list L owns
+    # [shared_begin[L], +shared_cnt[L]) followed directly by [misc_begin[L], +misc_cnt[L]).
+    codes: np.ndarray              # [nblocks][32][M/2] u8, low nibble = even subspace
+    ids: np.ndarray                # [nblocks][32] i64, -1 = empty slot
+    other: np.ndarray              # [nblocks][32] i32, other-list id for misc items, -1 elsewhere
+    list_shared_begin: np.ndarray  # [nlist] i64
+    list_shared_cnt: np.ndarray    # [nlist] i32
+    list_misc_begin: np.ndarray    # [nlist] i64
+    list_misc_cnt: np.ndarray      # [nlist] i32
+    list_ref_begin: np.ndarray     # [nlist] i64
+    list_ref_cnt: np.ndarray       # [nlist] i32
+    ref_owner: np.ndarray          # [nrefs] i32
+    ref_block_begin: np.ndarray    # [nrefs] i64
+    ref_nblocks: np.ndarray        # [nrefs] i32
+    raw: np.ndarray                # [ntotal][d] f32 or u8
+    # per-vector view of the same index (the naive "every list holds its members" reading)
+    assign: np.ndarray             # [ntotal][2] i32, assign[:,0] <= assign[:,1]
+    vec_codes: np.ndarray          # [ntotal][M/2] u8
+    params: dict = field(default_factory=dict)
+
+    @property
+    def nblocks(self) -> int:
+        return int(self.ids.shape[0])
+
+    @property
+    def nrefs(self) -> int:
+        return int(self.ref_owner.shape[0])
+
+    @property
+    def raw_is_u8(self) -> bool:
+        return self.raw.dtype == np.uint8
+
+
+# ----------------------------------------------------------------------------------------------
+# k-means (Lloyd).  Any deterministic choice is valid: the index is an input to the search path.
+# ----------------------------------------------------------------------------------------------
+
+def _nearest(x: np.ndarray, c: np.ndarray, chunk: int = 65536):
+    """Index of and squared distance to the nearest row of c for every row of x (GEMM form)."""
+    cn = (c.astype(np.float64) ** 2).sum(1).astype(np.float32)
+    idx = np.empty(x.shape[0], dtype=np.int64)
+    dist = np.empty(x.shape[0], dtype=np.float32)
+    ct = np.ascontiguousarray(c.T)
+    for lo in range(0, x.shape[0], chunk):
+        xs = x[lo:lo + chunk].astype(np.float32, copy=False)
+        g = xs @ ct
+        g *= -2.0
+        g += cn
+        i = g.argmin(1)
+        idx[lo:lo + chunk] = i
+        dist[lo:lo + chunk] = g[np.arange(g.shape[0]), i] + (xs * xs).sum(1)
+    return idx, dist
+
+
+def kmeans(x: np.ndarray, k: int, iters: int, seed: int, max_train: int | None = None) -> np.ndarray:
+    g = np.random.Generator(np.random.PCG64(seed))
+    n = x.shape[0]
+    if max_train is not None and n > max_train:
+        x = x[np.sort(g.choice(n, size=max_train, replace=False))]
+        n = max_train
+    x = x.astype(np.float32, copy=False)
+    c = x[np.sort(g.choice(n, size=k, replace=False))].astype(np.float32).copy()
+    for _ in range(iters):
+        idx, dist = _nearest(x, c)
+        cnt = np.bincount(idx, minlength=k)
+        s = np.zeros((k, x.shape[1]), dtype=np.float64)
+        order = np.argsort(idx, kind="stable")
+        bounds = np.concatenate([[0], np.cumsum(cnt)])
+        xs = x[order].astype(np.float64)
+        nz = np.flatnonzero(cnt)
+        s[nz] = np.add.reduceat(xs, bounds[nz], axis=0)
+        newc = c.astype(np.float64)
+        newc[nz] = s[nz] / cnt[nz, None]
+        # an empty cluster restarts on the point currently worst served
+        empty = np.flatnonzero(cnt == 0)
+        if empty.size:
+            far = np.argsort(-dist, kind="stable")[:empty.size]
+            newc[empty] = x[far]
+        c = newc.astype(np.float32)
+    return c
+
+
+# ----------------------------------------------------------------------------------------------
+# Product quantisation with 16 codewords per sub-quantizer (Section 2.2)
+# ----------------------------------------------------------------------------------------------
+
+def train_pq(x: np.ndarray, M: int, iters: int, seed: int, max_train: int = 32768) -> np.ndarray:
+    g = np.random.Generator(np.random.PCG64(seed))
+    n, d = x.shape
+    dsub = d // M
+    if n > max_train:
+        x = x[np.sort(g.choice(n, size=max_train, replace=False))]
+        n = max_train
+    xs = np.ascontiguousarray(x.astype(np.float32).reshape(n, M, dsub).transpose(1, 0, 2))
+    init = np.sort(g.choice(n, size=16, replace=False))
+    cb = xs[:, init, :].astype(np.float64)                                     # [M][16][dsub]
+    # identical sub-vectors would give duplicate codewords; nudge them apart deterministically
+    cb += (np.arange(16, dtype=np.float64)[None, :, None] * 1e-6)
+    mb = max(1, (1 << 24) // (n * 16))                                         # subspaces per batch
+    for _ in range(iters):
+        for m0 in range(0, M, mb):
+            xb = xs[m0:m0 + mb]                                                # [b][n][dsub]
+            cbb = cb[m0:m0 + mb].astype(np.float32)
+            dist = np.zeros((xb.shape[0], n, 16), dtype=np.float32)
+            for t in range(dsub):
+                diff = xb[:, :, None, t] - cbb[:, None, :, t]
+                dist += diff * diff
+            a = dist.argmin(-1)                                                # [b][n]
+            key = (a + 16 * np.arange(xb.shape[0])[:, None]).ravel()
+            cnt = np.bincount(key, minlength=16 * xb.shape[0])
+            nz = cnt > 0
+            for t in range(dsub):
+                tot = np.bincount(key, weights=xb[:, :, t].ravel().astype(np.float64),
+                                  minlength=16 * xb.shape[0])
+                col = cb[m0:m0 + mb, :, t].reshape(-1).copy()
+                col[nz] = tot[nz] / cnt[nz]
+                cb[m0:m0 + mb, :, t] = col.reshape(-1, 16)
+    return cb.astype(np.float32)
+
+
+def pq_encode(x: np.ndarray, cb: np.ndarray, chunk: int = 32768) -> np.ndarray:
+    """PQEncoding: code[m] = nearest codeword of sub-vector m, first minimum on ties.
+    Returns the packed form [n][M/2] with subspace 2i in the low nibble of byte i."""
+    n, d = x.shape
+    M, _, dsub = cb.shape
+    out = np.empty((n, M // 2), dtype=np.uint8)
+    cb32 = cb.astype(np.float32)
+    for lo in range(0, n, chunk):
+        xs = x[lo:lo + chunk].astype(np.float32).reshape(-1, M, dsub)
+        dist = np.zeros((xs.shape[0], M, 16), dtype=np.float32)
+        for t in range(dsub):
+            diff = xs[:, :, None, t] - cb32[None, :, :, t]
+            dist += diff * diff
+        code = dist.argmin(-1).astype(np.uint8)                                # [chunk][M]
+        out[lo:lo + chunk] = code[:, 0::2] | (code[:, 1::2] << 4)
+    return out
+
+
+# ----------------------------------------------------------------------------------------------
+# RairAssign (Alg. 3)
+# ----------------------------------------------------------------------------------------------
+
+def air_loss(v: np.ndarray, cand_centroids: np.ndarray, lam: float) -> np.ndarray:
+    """loss[i] = ||r_i||^2 + lam * <r_0, r_i>, r_i = centroid_i - v  (Alg. 3, the loop body).
+    v: [n][d]; cand_centroids: [n][ncand][d] ordered by distance to v.  float64."""
+    r = cand_centroids.astype(np.float64) - v.astype(np.float64)[:, None, :]
+    return (r * r).sum(-1) + lam * (r * r[:, :1, :]).sum(-1)
+
+
+def rair_assign(x: np.ndarray, centroids: np.ndarray, lam: float = 0.5, n_cands: int = 10,
+                strict: bool = True, chunk: int = 16384) -> np.ndarray:
+    """Two list ids per vector, returned ordered (smaller id first) as Alg. 3 does.
+    With strict=False the secondary list may equal the primary one (the vector is then stored
+    once, cell (i,i)); with strict=True candidate 0 is excluded from the argmin (SRAIR)."""
+    n = x.shape[0]
+    nlist = centroids.shape[0]
+    n_cands = min(n_cands, nlist)
+    out = np.empty((n, 2), dtype=np.int32)
+    c32 = centroids.astype(np.float32)
+    cn = (c32.astype(np.float64) ** 2).sum(1).astype(np.float32)
+    ct = np.ascontiguousarray(c32.T)
+    c64 = centroids.astype(np.float64)
+    for lo in range(0, n, chunk):
+        xs = x[lo:lo + chunk].astype(np.float32)
+        g = xs @ ct
+        g *= -2.0
+        g += cn
+        if n_cands < nlist:
+            cand = np.argpartition(g, n_cands - 1, axis=1)[:, :n_cands]
+        else:
+            cand = np.tile(np.arange(nlist), (xs.shape[0], 1))
+        # exact distances of the candidates, then order by (distance, list id)
+        r = c64[cand] - xs.astype(np.float64)[:, None, :]
+        dist = (r * r).sum(-1)
+        key = np.argsort(cand, axis=1, kind="stable")
+        cand = np.take_along_axis(cand, key, 1)
+        dist = np.take_along_axis(dist, key, 1)
+        key = np.argsort(dist, axis=1, kind="stable")
+        cand = np.take_along_axis(cand, key, 1)
+        loss = air_loss(xs, c64[cand], lam)
+        start = 1 if strict else 0
+        if start >= n_cands:
+            second = cand[:, 0]
+        else:
+            second = cand[np.arange(cand.shape[0]), start + loss[:, start:].argmin(1)]
+        first = cand[:, 0]
+        out[lo:lo + chunk, 0] = np.minimum(first, second)
+        out[lo:lo + chunk, 1] = np.maximum(first, second)
+    return out
+
+
+# ----------------------------------------------------------------------------------------------
+# SeilInsert (Alg. 4), one batch
+# ----------------------------------------------------------------------------------------------
+
+def seil_insert(assign: np.ndarray, vec_codes: np.ndarray, vec_ids: np.ndarray, nlist: int):
+    """Lay the items out as Alg. 4 does for a single batch.
+
+    Items are sorted by {listID1, listID2, vec_id}; a cell (i,j) of `nitems` items yields
+    nitems // 32 full blocks stored once, in list i's shared area, and nitems % 32 leftovers that
+    go to the miscellaneous area of list i and, when j != i, also of list j, each tagged with the
+    other list id.  List j gets a reference entry (i, nblocks, first block) -- emitted only when
+    nblocks >= 1.  Within a list, shared blocks precede miscellaneous blocks; only the last
+    miscellaneous block of a list may be partly filled.
+    """
+    n = assign.shape[0]
+    hb = vec_codes.shape[1]
+    l1 = assign[:, 0].astype(np.int64)
+    l2 = assign[:, 1].astype(np.int64)
+    assert (l1 <= l2).all()
+    order = np.lexsort((vec_ids, l2, l1))
+    s1, s2 = l1[order], l2[order]
+    cell_key = s1 * nlist + s2
+    first = np.flatnonzero(np.concatenate([[True], cell_key[1:] != cell_key[:-1]])) if n else \
+        np.zeros(0, dtype=np.int64)
+    c_start = first
+    c_n = np.diff(np.concatenate([first, [n]]))
+    c_l1, c_l2 = s1[first], s2[first]
+    c_nb = c_n // BLK
+    c_nm = c_n % BLK
+    ncell = first.size
+
+    # pass 1: per-list block and leftover counts
+    list_nb = np.bincount(c_l1, weights=c_nb, minlength=nlist).astype(np.int64)
+    list_nm = np.bincount(c_l1, weights=c_nm, minlength=nlist).astype(np.int64)
+    two = c_l1 != c_l2
+    list_nm += np.bincount(c_l2[two], weights=c_nm[two], minlength=nlist).astype(np.int64)
+    list_mb = (list_nm + BLK - 1) // BLK
+    list_tot = list_nb + list_mb
+    list_begin = np.concatenate([[0], np.cumsum(list_tot)[:-1]]).astype(np.int64)
+    shared_begin = list_begin
+    misc_begin = list_begin + list_nb
+    nblocks = int(list_tot.sum())
+
+    codes = np.zeros((nblocks * BLK, hb), dtype=np.uint8)
+    ids = np.full(nblocks * BLK, -1, dtype=np.int64)
+    other = np.full(nblocks * BLK, -1, dtype=np.int32)
+
+    # pass 2a: full blocks of each cell, contiguous, in list l1's shared area
+    excl = np.cumsum(c_nb) - c_nb                      # blocks of earlier cells (global order)
+    list_first_cell_excl = np.zeros(nlist, dtype=np.int64)
+    # cells are sorted by l1, so the blocks of earlier cells of the same list are excl - (excl at
+    # the list's first cell)
+    firstcell_of_list = np.full(nlist, -1, dtype=np.int64)
+    if ncell:
+        fc = np.flatnonzero(np.concatenate([[True], c_l1[1:] != c_l1[:-1]]))
+        firstcell_of_list[c_l1[fc]] = fc
+        list_first_cell_excl[c_l1[fc]] = excl[fc]
+    c_bbegin = shared_begin[c_l1] + (excl - list_first_cell_excl[c_l1])
+
+    cell_of_item = np.repeat(np.arange(ncell), c_n)
+    off = np.arange(n) - c_start[cell_of_item]
+    in_shared = off < (c_nb[cell_of_item] * BLK)
+    src = order[in_shared]
+    dst = c_bbegin[cell_of_item[in_shared]] * BLK + off[in_shared]
+    codes[dst] = vec_codes[src]
+    ids[dst] = vec_ids[src]
+
+    # pass 2b: leftovers, appended to list l1 and (if different) list l2 in cell order
+    m_item = np.flatnonzero(~in_shared)                # positions in the sorted array
+    m_cell = cell_of_item[m_item]
+    a_dest = c_l1[m_cell]
+    a_tag = c_l2[m_cell]
+    sel2 = two[m_cell]
+    b_dest = c_l2[m_cell][sel2]
+    b_tag = c_l1[m_cell][sel2]
+    e_dest = np.concatenate([a_dest, b_dest])
+    e_tag = np.concatenate([a_tag, b_tag])
+    e_pos = np.concatenate([m_item, m_item[sel2]])     # sorted position = (cell, offset) order
+    eo = np.lexsort((e_pos, e_dest))
+    e_dest, e_tag, e_pos = e_dest[eo], e_tag[eo], e_pos[eo]
+    cnt = np.bincount(e_dest, minlength=nlist)
+    assert (cnt == list_nm).all()
+    rank = np.arange(e_dest.size) - np.repeat(np.cumsum(cnt) - cnt, cnt)
+    dst = misc_begin[e_dest] * BLK + rank
+    src = order[e_pos]
+    codes[dst] = vec_codes[src]
+    ids[dst] = vec_ids[src]
+    other[dst] = e_tag
+
+    # reference entries: list l2 of every two-list cell that has at least one full block
+    rsel = np.flatnonzero(two & (c_nb > 0))
+    ro = np.lexsort((rsel, c_l2[rsel]))
+    rsel = rsel[ro]
+    ref_owner = c_l1[rsel].astype(np.int32)
+    ref_block_begin = c_bbegin[rsel].astype(np.int64)
+    ref_nblocks = c_nb[rsel].astype(np.int32)
+    ref_cnt = np.bincount(c_l2[rsel], minlength=nlist).astype(np.int32)
+    ref_begin = (np.cumsum(ref_cnt) - ref_cnt).astype(np.int64)
+
+    return dict(
+        codes=codes.reshape(nblocks, BLK, hb), ids=ids.reshape(nblocks, BLK),
+        other=other.reshape(nblocks, BLK),
+        list_shared_begin=shared_begin.astype(np.int64), list_shared_cnt=list_nb.astype(np.int32),
+        list_misc_begin=misc_begin.astype(np.int64), list_misc_cnt=list_mb.astype(np.int32),
+        list_ref_begin=ref_begin, list_ref_cnt=ref_cnt,
+        ref_owner=ref_owner, ref_block_begin=ref_block_begin, ref_nblocks=ref_nblocks,
+    )
+
+
+# ----------------------------------------------------------------------------------------------
+# AddVectors (Alg. 1)
+# ----------------------------------------------------------------------------------------------
+
+def build_index(base: np.ndarray, nlist: int, M: int, *, lam: float = 0.5, n_cands: int = 10,
+                strict: bool = True, seed: int = 0, coarse_iters: int = 20, pq_iters: int = 25,
+                assign: np.ndarray | None = None) -> HostIndex:
+    """Train centroids and codebook on `base`, then add all of `base` as one batch.
+    `assign` overrides RairAssign (tests use it for random and adversarial cell structures)."""
+    n, d = base.shape
+    assert d % M == 0 and M % 2 == 0
+    centroids = kmeans(base, nlist, coarse_iters, seed * 7 + 1, max_train=256 * nlist)
+    codebook = train_pq(base, M, pq_iters, seed * 7 + 2)
+    return add_vectors(base, centroids, codebook, lam=lam, n_cands=n_cands, strict=strict,
+                       assign=assign)
+
+
+def add_vectors(base: np.ndarray, centroids: np.ndarray, codebook: np.ndarray, *,
+                lam: float = 0.5, n_cands: int = 10, strict: bool = True,
+                assign: np.ndarray | None = None) -> HostIndex:
+    n, d = base.shape
+    nlist = centroids.shape[0]
+    M = codebook.shape[0]
+    if assign is None:
+        assign = rair_assign(base, centroids, lam=lam, n_cands=n_cands, strict=strict)
+    assign = np.ascontiguousarray(assign, dtype=np.int32)
+    vec_codes = pq_encode(base, codebook)
+    vec_ids = np.arange(n, dtype=np.int64)
+    lay = seil_insert(assign, vec_codes, vec_ids, nlist)
+    return HostIndex(
+        d=d, M=M, nlist=nlist, ntotal=n,
+        centroids=np.ascontiguousarray(centroids, dtype=np.float32),
+        codebook=np.ascontiguousarray(codebook, dtype=np.float32),
+        raw=np.ascontiguousarray(base), assign=assign, vec_codes=vec_codes,
+        params=dict(lam=lam, n_cands=n_cands, strict=strict), **lay)

@@ -1,0 +1,311 @@
+"""Pins of the CPU oracle against things other than itself: brute force, closed forms,
+invariants stated by the paper, integer arithmetic.  No GPU."""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2601_07183_amd import datagen, index_build as ib
+
+from conftest import small_queries
+
+
+def _exact_knn(q, base, k):
+    """Textbook kNN in float64, ties by smaller id."""
+    d2 = ((q[:, None, :].astype(np.float64) - base[None].astype(np.float64)) ** 2).sum(-1)
+    order = np.lexsort((np.broadcast_to(np.arange(base.shape[0]), d2.shape), d2), axis=1)
+    return order[:, :k], np.take_along_axis(d2, order[:, :k], 1)
+
+
+# --- exact distance ------------------------------------------------------------------------
+
+@pytest.mark.parametrize("d", [1, 2, 31, 32, 63, 64, 65, 96, 128, 200, 960])
+def test_l2sqr_against_float64(d):
+    a = datagen.random_vectors(d, 4, d, -3, 3)
+    b = datagen.random_vectors(d + 1, 4, d, -3, 3)
+    for i in range(4):
+        want = ((a[i].astype(np.float64) - b[i].astype(np.float64)) ** 2).sum()
+        got = oracle.l2sqr(a[i], b[i])
+        assert abs(got - want) <= 1e-6 * want + 1e-30      # fp32 tree sum, d <= 960
+
+
+def test_l2sqr_summation_order_is_the_stated_tree():
+    # 64 interleaved partial sums, then p[j] += p[j^32], ^16, ... -- rebuilt here with numpy
+    # float32 scalars; a different order changes low bits on this input.
+    d = 200
+    a = (datagen.random_vectors(5, 1, d, -1, 1)[0] * np.float32(1000.123)).astype(np.float32)
+    b = datagen.random_vectors(6, 1, d, -1, 1)[0]
+    p = np.zeros(64, dtype=np.float32)
+    for i in range(d):
+        diff = np.float32(a[i] - b[i])
+        p[i % 64] = np.float32(p[i % 64] + np.float32(diff * diff))
+    for s in (32, 16, 8, 4, 2, 1):
+        p = (p + p[np.arange(64) ^ s]).astype(np.float32)
+    assert oracle.l2sqr(a, b) == float(p[0])
+    seq = np.float32(0)
+    for i in range(d):
+        diff = np.float32(a[i] - b[i])
+        seq = np.float32(seq + np.float32(diff * diff))
+    assert float(seq) != float(p[0])
+
+
+def test_l2sqr_integer_data_is_exact_and_u8_agrees():
+    g = np.random.Generator(np.random.PCG64(3))
+    a = g.integers(0, 256, size=128).astype(np.float32)
+    b8 = g.integers(0, 256, size=128).astype(np.uint8)
+    want = int(((a.astype(np.int64) - b8.astype(np.int64)) ** 2).sum())
+    assert want < 2 ** 24
+    assert oracle.l2sqr(a, b8.astype(np.float32)) == want
+    assert oracle.l2sqr(a, b8) == want
+
+
+# --- coarse quantizer ----------------------------------------------------------------------
+
+def test_coarse_is_the_nprobe_nearest_by_distance_then_id(small_index_int):
+    base, hx = small_index_int
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(1, 20, hx.d, integer=True)
+    # make two centroids identical so that a distance tie exists
+    hx2 = ib.add_vectors(base, np.vstack([hx.centroids[:-1], hx.centroids[:1]]), hx.codebook)
+    ox2 = oracle.OracleIndex(hx2)
+    for o, cents in ((ox, hx.centroids), (ox2, hx2.centroids)):
+        d2 = ((q[:, None, :].astype(np.float64) - cents[None].astype(np.float64)) ** 2).sum(-1)
+        for i in range(len(q)):
+            lists, dists = oracle.coarse(o, q[i], 5)
+            order = np.lexsort((np.arange(hx.nlist), d2[i].astype(np.float32)))
+            assert np.allclose(dists, d2[i][lists], rtol=1e-6)
+            assert (np.diff(dists) >= 0).all()
+            got = set(lists.tolist())
+            # float64 order can only differ from the fp32 one inside fp32 rounding
+            kth = np.sort(d2[i])[4]
+            assert all(d2[i][l] <= kth * (1 + 1e-6) for l in got)
+    lists, dists = oracle.coarse(ox2, q[0], hx.nlist)
+    pos0, posl = list(lists).index(0), list(lists).index(hx.nlist - 1)
+    assert posl == pos0 + 1 and dists[pos0] == dists[posl]   # equal distance: smaller id first
+
+
+# --- lookup table --------------------------------------------------------------------------
+
+def test_lut_pq_identity(small_index):
+    # Section 2.2: summing the table entries selected by a code gives the squared distance
+    # between the query and the decoded vector.
+    base, hx = small_index
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(2, 8, hx.d)
+    dsub = hx.d // hx.M
+    code = np.empty((hx.ntotal, hx.M), dtype=np.int64)
+    code[:, 0::2], code[:, 1::2] = hx.vec_codes & 15, hx.vec_codes >> 4
+    decoded = hx.codebook[np.arange(hx.M)[None, :], code].reshape(hx.ntotal, hx.M * dsub)
+    for i in range(len(q)):
+        T, u8, bias, scale = oracle.lut(ox, q[i])
+        est = T[np.arange(hx.M)[None, :], code[:200]].astype(np.float64).sum(1)
+        want = ((q[i].astype(np.float64) - decoded[:200].astype(np.float64)) ** 2).sum(1)
+        assert np.allclose(est, want, rtol=1e-5, atol=1e-6)
+
+
+def test_lut_quantisation_bound_and_range(small_index):
+    base, hx = small_index
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(3, 8, hx.d)
+    code = np.empty((hx.ntotal, hx.M), dtype=np.int64)
+    code[:, 0::2], code[:, 1::2] = hx.vec_codes & 15, hx.vec_codes >> 4
+    for i in range(len(q)):
+        T, u8, bias, scale = oracle.lut(ox, q[i])
+        assert (u8.min(1) == 0).all()                       # each row's minimum maps to 0
+        assert u8.max() == 255                              # the widest row reaches 255
+        span = (T.max(1) - T.min(1)).max()
+        assert np.isclose(scale, 255.0 / span, rtol=1e-6)
+        assert np.isclose(bias, T.min(1).astype(np.float64).sum(), rtol=1e-5)
+        acc = u8[np.arange(hx.M)[None, :], code[:500]].astype(np.int64).sum(1)
+        est = T[np.arange(hx.M)[None, :], code[:500]].astype(np.float64).sum(1)
+        err = np.abs(bias + acc / scale - est)
+        assert (err <= hx.M / (2 * scale) * (1 + 1e-4) + 1e-5 * est).all()
+        # rounding is to nearest: every entry within half a step
+        step = (T - T.min(1, keepdims=True)).astype(np.float64) * scale
+        assert (np.abs(step - u8) <= 0.5 + 1e-3).all()
+
+
+def test_lut_rounds_half_to_even():
+    # One worked table: M = 2, dsub = 1, query 0.  Codewords sqrt(t) give T = t exactly for the
+    # chosen t; the widest row spans 510, so s = 0.5 and (T - b) * s hits .5 cases.
+    class H:
+        pass
+    t0 = np.array([0, 1, 3, 5, 7, 9, 11, 510, 2, 4, 6, 8, 10, 12, 14, 16], dtype=np.float64)
+    t1 = np.array([4, 5, 7, 9, 11, 13, 15, 17, 19, 21, 23, 25, 27, 29, 31, 33], dtype=np.float64)
+    cb = np.sqrt(np.stack([t0, t1]))[:, :, None].astype(np.float32)
+    T_exact = (cb[:, :, 0].astype(np.float32) ** 2).astype(np.float32)
+    base = np.zeros((4, 2), dtype=np.float32)
+    hx = ib.add_vectors(base, np.zeros((2, 2), dtype=np.float32), cb,
+                        assign=np.array([[0, 1]] * 4, dtype=np.int32))
+    T, u8, bias, scale = oracle.lut(oracle.OracleIndex(hx), np.zeros(2, dtype=np.float32))
+    assert (T == T_exact).all()
+    # only check entries whose fp32 square is the exact integer (sqrt rounding may break some)
+    ok = T_exact == np.stack([t0, t1])
+    assert ok[0, [0, 1, 2, 3, 7]].all() and ok[1, 0]
+    assert scale == 0.5 and bias == float(T_exact[0].min() + T_exact[1].min())
+    want0 = {0: 0, 1: 0, 3: 2, 5: 2, 7: 4, 9: 4, 11: 6, 510: 255}   # x.5 goes to the even integer
+    for c in range(16):
+        if ok[0, c] and int(t0[c]) in want0:
+            assert u8[0, c] == want0[int(t0[c])]
+    # second row: (T - 4) * 0.5 = 0, .5, 1.5, 2.5, ... -> 0, 0, 2, 2, 4, 4, ...
+    for c in range(16):
+        if ok[1, c]:
+            x = (t1[c] - 4) * 0.5
+            assert u8[1, c] == int(np.rint(x))
+
+
+# --- whole path ----------------------------------------------------------------------------
+
+def test_brute_force_knn_when_everything_is_probed_and_refined(small_index_int):
+    # nprobe = nlist and bigK >= N: the path must return the exact kNN (recall 1).  Integer data
+    # makes every distance exact, so ids match including ties.
+    base, hx = small_index_int
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(4, 25, hx.d, integer=True)
+    want_ids, want_d = _exact_knn(q, base, 10)
+    for layout in ("seil", "naive"):
+        r = oracle.search(ox, q, 10, hx.nlist, hx.ntotal, layout=layout)
+        assert (r.ids == want_ids).all()
+        assert (r.dists.astype(np.float64) == want_d).all()
+
+
+def test_brute_force_knn_float_data(small_index):
+    base, hx = small_index
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(5, 25, hx.d)
+    want_ids, want_d = _exact_knn(q, base, 10)
+    r = oracle.search(ox, q, 10, hx.nlist, hx.ntotal)
+    assert np.allclose(r.dists, want_d, rtol=1e-5)
+    assert (r.ids == want_ids).mean() > 0.99               # only fp32 near-ties may swap
+    for i in range(len(q)):
+        assert set(r.ids[i]) == set(want_ids[i]) or \
+            np.allclose(np.sort(r.dists[i]), want_d[i], rtol=1e-5)
+
+
+def test_candidates_are_the_smallest_scores_by_definition(small_index):
+    # Independent numpy evaluation of steps 2-4 of the definition from the per-vector view.
+    base, hx = small_index
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(6, 10, hx.d)
+    code = np.empty((hx.ntotal, hx.M), dtype=np.int64)
+    code[:, 0::2], code[:, 1::2] = hx.vec_codes & 15, hx.vec_codes >> 4
+    for nprobe in (1, 3, 7, hx.nlist):
+        r = oracle.search(ox, q, 5, nprobe, 50)
+        for i in range(len(q)):
+            probed = np.zeros(hx.nlist, dtype=bool)
+            probed[r.probes[i]] = True
+            member = probed[hx.assign[:, 0]] | probed[hx.assign[:, 1]]
+            acc = r.lut[i][np.arange(hx.M)[None, :], code].astype(np.int64).sum(1)
+            ids = np.flatnonzero(member)
+            order = ids[np.lexsort((ids, acc[ids]))][:50]
+            n = len(order)
+            assert (r.cand_ids[i][:n] == order).all() and (r.cand_ids[i][n:] == -1).all()
+            assert (r.cand_acc[i][:n] == acc[order]).all()
+            # refine: exact distances of the candidates, K smallest by (distance, id)
+            d2 = np.array([oracle.l2sqr(q[i], base[v]) for v in order], dtype=np.float32)
+            top = order[np.lexsort((order, d2))][:5]
+            assert (r.ids[i][:len(top)] == top).all()
+
+
+@pytest.mark.parametrize("which", ["strict", "nonstrict", "int"])
+def test_seil_equals_naive_layout(which, small_index, small_index_nonstrict, small_index_int):
+    base, hx = {"strict": small_index, "nonstrict": small_index_nonstrict,
+                "int": small_index_int}[which]
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(7, 40, hx.d, integer=(which == "int"))
+    for nprobe in (1, 2, 5, 11, hx.nlist):
+        a = oracle.search(ox, q, 10, nprobe, 60, layout="seil")
+        b = oracle.search(ox, q, 10, nprobe, 60, layout="naive")
+        assert (a.cand_ids == b.cand_ids).all() and (a.cand_acc == b.cand_acc).all()
+        assert (a.ids == b.ids).all() and (a.dists == b.dists).all()
+
+
+def test_seil_equals_naive_on_adversarial_assignments():
+    x = datagen.random_vectors(31, 900, 8)
+    q = datagen.random_vectors(32, 30, 8)
+    cents = ib.kmeans(x, 8, 5, 1)
+    cb = ib.train_pq(x, 4, 5, 2)
+    g = np.random.Generator(np.random.PCG64(9))
+    cases = [
+        np.tile(np.array([[2, 5]], dtype=np.int32), (900, 1)),                # one huge cell
+        np.sort(g.integers(0, 8, size=(900, 2)), axis=1).astype(np.int32),     # random pairs
+        np.sort(np.array([[i % 8, (i // 8) % 8] for i in range(900)]), axis=1)[:300].astype(np.int32),
+        np.tile(np.array([[3, 3]], dtype=np.int32), (900, 1)),                # all single-assigned
+    ]
+    for asg in cases:
+        hx = ib.add_vectors(x[:len(asg)], cents, cb, assign=asg)
+        ox = oracle.OracleIndex(hx)
+        for nprobe in (1, 2, 4, 8):
+            a = oracle.search(ox, q, 5, nprobe, 40, layout="seil", trace=True)
+            b = oracle.search(ox, q, 5, nprobe, 40, layout="naive")
+            assert (a.cand_ids == b.cand_ids).all() and (a.ids == b.ids).all()
+            assert a.push_count.max() <= 1 and a.block_count.max() <= 1
+
+
+def test_each_vector_pushed_at_most_once_and_dco_identity(small_index, small_index_nonstrict):
+    for base, hx in (small_index, small_index_nonstrict):
+        ox = oracle.OracleIndex(hx)
+        q = small_queries(8, 30, hx.d)
+        a = hx.assign.astype(np.int64)
+        key = a[:, 0] * hx.nlist + a[:, 1]
+        cells, cnt = np.unique(key, return_counts=True)
+        c1, c2 = cells // hx.nlist, cells % hx.nlist
+        members = np.bincount(a[:, 0], minlength=hx.nlist) + \
+            np.bincount(a[:, 1][a[:, 0] != a[:, 1]], minlength=hx.nlist)
+        for nprobe in (1, 4, 9, hx.nlist):
+            r = oracle.search(ox, q, 10, nprobe, 50, trace=True)
+            assert r.push_count.max() <= 1                  # no id enters the queue twice
+            assert r.block_count.max() <= 1                 # no block is scored twice
+            for i in range(len(q)):
+                probed = np.zeros(hx.nlist, dtype=bool)
+                probed[r.probes[i]] = True
+                member = probed[a[:, 0]] | probed[a[:, 1]]
+                assert ((r.push_count[i] == 1) == member).all()
+                # cost analysis of Section 5.2: n_vec_selected - n_vec_shared
+                both = probed[c1] & probed[c2] & (c1 != c2)
+                want = members[probed].sum() - 32 * (cnt[both] // 32).sum()
+                assert r.dco[i] == want
+            if nprobe == hx.nlist:
+                assert (r.push_count == 1).all()
+
+
+def test_queries_are_independent(small_index):
+    # Alg. 2 keeps no state across queries: permuting or splitting the batch permutes or splits
+    # the output.
+    base, hx = small_index
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(9, 24, hx.d)
+    r = oracle.search(ox, q, 10, 4, 40)
+    perm = np.random.Generator(np.random.PCG64(1)).permutation(len(q))
+    rp = oracle.search(ox, q[perm], 10, 4, 40)
+    assert (rp.ids == r.ids[perm]).all() and (rp.dists == r.dists[perm]).all()
+    r1 = oracle.search(ox, q[:7], 10, 4, 40, nthreads=1)
+    assert (r1.ids == r.ids[:7]).all()
+
+
+def test_short_lists_are_padded(small_index):
+    base, hx = small_index
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(10, 5, hx.d)
+    r = oracle.search(ox, q, 10, 1, hx.ntotal)              # bigK larger than any list
+    n = (r.cand_ids >= 0).sum(1)
+    assert (n < hx.ntotal).all() and (n >= 10).all()
+    for i in range(len(q)):
+        assert (r.cand_ids[i][n[i]:] == -1).all()
+    with pytest.raises(ValueError):
+        oracle.search(ox, q, 10, 0, 40)
+    with pytest.raises(ValueError):
+        oracle.search(ox, q, 50, 1, 40)
+
+
+def test_tiny_workload_recall_is_monotone_and_layouts_agree(tiny_workload):
+    w, base, q, hx = tiny_workload
+    ox = oracle.OracleIndex(hx)
+    gt, _ = _exact_knn(q[:60], base, w.k)
+    last = -1.0
+    for nprobe in w.nprobes:
+        r = oracle.search(ox, q[:60], w.k, nprobe, w.refine_k)
+        n = oracle.search(ox, q[:60], w.k, nprobe, w.refine_k, layout="naive")
+        assert (r.ids == n.ids).all() and (r.cand_ids == n.cand_ids).all()
+        rec = np.mean([len(set(r.ids[i]) & set(gt[i])) / w.k for i in range(60)])
+        assert rec >= last - 0.02
+        last = rec
