@@ -1,0 +1,176 @@
+/*
+ * rairs.h -- C ABI of the MI355X (gfx950) RAIRS query path.
+ *
+ * The library implements Alg. 2 of the paper (RairsSearch) for a batch of queries on one GPU:
+ *   coarse quantizer (FindNearestLists, Section 2.2)  ->  lookup tables (ComputeLookupTable,
+ *   Section 2.2)  ->  SeilSearch over the SEIL list layout (Alg. 5, Section 5)  ->
+ *   top-bigK candidates  ->  Refine with exact distances (Section 2.2).
+ * Index construction (Alg. 1, 3, 4) happens on the host, outside this library; its output is
+ * handed over in the canonical host layout below.
+ *
+ * Conventions
+ *   - Every function returns 0 (RAIRS_OK) or a negative rairs_status; nothing throws, aborts or
+ *     exits.  rairs_last_error() gives a thread-local message for the last failure.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory on the
+ *     current device.  `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *   - Search calls only enqueue work on `hip_stream`; outputs are valid once the caller has
+ *     synchronised that stream.  One search at a time per handle (calls share its workspace).
+ *   - All distances are squared Euclidean distances in fp32.  Orders are total:
+ *     lists by (distance, list id), candidates by (16-bit score, vector id), results by
+ *     (distance, vector id).  Missing entries are id -1 / distance +inf / score -1.
+ */
+#ifndef RAIRS_H
+#define RAIRS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rairs_index rairs_index_t;   /* opaque device-resident index */
+
+typedef enum {
+    RAIRS_OK = 0,
+    RAIRS_EINVAL = -1,        /* bad argument (null pointer, size out of range, broken directory) */
+    RAIRS_ENOMEM = -2,        /* host or device allocation failed */
+    RAIRS_EHIP = -3,          /* a HIP runtime call failed */
+    RAIRS_EUNSUPPORTED = -4   /* valid request outside the built limits */
+} rairs_status;
+
+/* Built limits (rejected with RAIRS_EUNSUPPORTED beyond them). */
+#define RAIRS_MAX_M        256     /* 255 * M must fit 16 bits: M <= 257 */
+#define RAIRS_MAX_REFINE_K 1024
+#define RAIRS_MAX_NPROBE   4096
+#define RAIRS_MAX_D        2048
+
+/*
+ * Canonical host layout written by SeilInsert (Alg. 4) for one batch; all arrays are host
+ * memory owned by the caller and may be released as soon as rairs_index_upload returns.
+ *
+ * Blocks hold 32 items (BLK_SZ).  List L owns blocks [list_shared_begin[L], +list_shared_cnt[L])
+ * -- the full blocks of every cell (L, j), stored once -- and [list_misc_begin[L],
+ * +list_misc_cnt[L]) -- leftovers of all cells touching L; only the last of these may have empty
+ * slots (id -1).  Reference entries [list_ref_begin[L], +list_ref_cnt[L]) of list L each name the
+ * blocks of a cell (owner, L), owner < L, stored in list `owner` (Section 5.1).
+ */
+typedef struct {
+    int32_t d;               /* vector dimension */
+    int32_t M;               /* PQ sub-quantizers, d % M == 0, M even */
+    int32_t nbits;           /* must be 4 */
+    int32_t nlist;
+    int32_t blk;             /* must be 32 */
+    int32_t raw_is_u8;       /* raw vectors stored as uint8 (else fp32) */
+    int64_t ntotal;          /* vectors, < 2^32 - 1 */
+    int64_t nblocks;
+    int64_t nrefs;
+    const float *centroids;          /* [nlist][d] */
+    const float *codebook;           /* [M][16][d/M] */
+    const uint8_t *codes;            /* [nblocks][32][M/2]; byte i: subspace 2i low nibble,
+                                        2i+1 high nibble */
+    const int64_t *ids;              /* [nblocks][32]; -1 = empty slot */
+    const int32_t *other;            /* [nblocks][32]; misc items: the item's other list id
+                                        (its own list for a vector stored once); else -1 */
+    const int64_t *list_shared_begin;
+    const int32_t *list_shared_cnt;
+    const int64_t *list_misc_begin;
+    const int32_t *list_misc_cnt;
+    const int64_t *list_ref_begin;
+    const int32_t *list_ref_cnt;
+    const int32_t *ref_owner;        /* [nrefs] */
+    const int64_t *ref_block_begin;  /* [nrefs] */
+    const int32_t *ref_nblocks;      /* [nrefs], >= 1 */
+    const void *raw;                 /* [ntotal][d] fp32 or uint8: the refine module's vectors */
+} rairs_host_index_t;
+
+/*
+ * Copy an index to the current device in the library's device format (Fig. 3: centroids,
+ * inverted lists, vector data).  Validates sizes and every directory range; synchronises its own
+ * copies before returning.  *out receives the handle.
+ */
+int rairs_index_upload(const rairs_host_index_t *host, void *hip_stream, rairs_index_t **out);
+
+/*
+ * RairsSearch (Alg. 2) for nq queries with bigK = refine_k.
+ *   d_queries   device [nq][d] fp32
+ *   d_out_ids   device [nq][k] int64, ascending (distance, id)
+ *   d_out_dists device [nq][k] fp32 squared distances
+ * Requires 1 <= k <= refine_k <= RAIRS_MAX_REFINE_K, 1 <= nprobe <= min(nlist,
+ * RAIRS_MAX_NPROBE).  nq == 0 is a successful no-op.  The handle's internal workspace grows on
+ * demand (a growth synchronises the device; steady-state calls allocate nothing).
+ */
+int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
+                 int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream);
+
+/* Release the device copy.  NULL is accepted. */
+int rairs_free(rairs_index_t *h);
+
+/* ---- the stages of rairs_search, callable one by one (same kernels) ----------------------- */
+
+/*
+ * FindNearestLists for a query batch (Alg. 2 line 5): the nprobe nearest centroids per query.
+ *   d_probe_ids   device [nq][nprobe] int32 in (distance, list id) order
+ *   d_probe_dists device [nq][nprobe] fp32, may be NULL
+ */
+int rairs_coarse(rairs_index_t *h, const float *d_queries, int64_t nq, int nprobe,
+                 int32_t *d_probe_ids, float *d_probe_dists, void *hip_stream);
+
+/*
+ * ComputeLookupTable (Alg. 2 line 4) quantised to 8 bits:
+ *   T[m][c] = |q_m - codeword(m,c)|^2,  b_m = min_c T[m][c],  s = 255 / max_m(max_c T[m][c] - b_m)
+ *   lut[m][c] = min(255, rint((T[m][c] - b_m) * s))      (s = 0 if the span is 0)
+ *   d_lut device [nq][M][16] uint8; d_bias_sum [nq] = sum_m b_m; d_scale [nq] = s
+ *   (either of the last two may be NULL).  bias_sum + score / s approximates the distance.
+ */
+int rairs_lut(rairs_index_t *h, const float *d_queries, int64_t nq, uint8_t *d_lut,
+              float *d_bias_sum, float *d_scale, void *hip_stream);
+
+/*
+ * SeilSearch (Alg. 5) for given tables and probe lists, plus the top-bigK queue:
+ * every member of a probed list is scored once (shared cells once per query, miscellaneous
+ * duplicates removed) with score = sum_m lut[m][code_m] as an unsigned 16-bit integer.
+ *   d_lut        device [nq][M][16] uint8
+ *   d_probe_ids  device [nq][nprobe] int32, distinct valid list ids per row, any order
+ *   d_cand_ids   device [nq][refine_k] int64: the refine_k smallest (score, id), padded with -1
+ *   d_cand_score device [nq][refine_k] int32 (padded with -1), may be NULL
+ *   d_dco        device [nq] int64 items scored (one per valid slot of every scanned block),
+ *                may be NULL
+ */
+int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t *d_probe_ids, int64_t nq,
+               int nprobe, int refine_k, int64_t *d_cand_ids, int32_t *d_cand_score,
+               int64_t *d_dco, void *hip_stream);
+
+/*
+ * Refine (Alg. 2 line 7): exact distances of the candidates, K smallest by (distance, id).
+ *   d_cand_ids device [nq][refine_k] int64, entries < 0 are ignored.
+ */
+int rairs_refine(rairs_index_t *h, const float *d_queries, const int64_t *d_cand_ids, int64_t nq,
+                 int refine_k, int k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream);
+
+/* ---- measurement --------------------------------------------------------------------------- */
+
+enum { RAIRS_STAGE_COARSE = 0, RAIRS_STAGE_LUT = 1, RAIRS_STAGE_SCAN = 2, RAIRS_STAGE_REFINE = 3,
+       RAIRS_NSTAGES = 4 };
+
+/* When enabled, rairs_search brackets each stage with HIP events on the caller's stream. */
+int rairs_set_profiling(rairs_index_t *h, int enabled);
+
+/*
+ * Milliseconds per stage of the last rairs_search (host array of RAIRS_NSTAGES floats).
+ * Synchronises on the recorded events.  RAIRS_EINVAL if profiling was off.
+ */
+int rairs_get_stage_ms(rairs_index_t *h, float *ms);
+
+/* Items scored per query by the last rairs_search: device [nq] int64 copied to host `dco`. */
+int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq);
+
+/* Bytes of device memory held by the index (codes, ids, tags, directory, raw vectors, ...). */
+int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, int64_t *total_bytes);
+
+const char *rairs_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAIRS_H */

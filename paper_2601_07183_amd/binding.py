@@ -1,0 +1,204 @@
+"""Thin Python binding of librairs.so: argument marshalling only.
+
+Function names mirror include/rairs.h.  PyTorch supplies device memory and the stream; every
+step of the search runs in the library's HIP kernels.  There is no CPU fallback: if the shared
+library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librairs.so")
+_lib = None
+
+STAGES = ("coarse", "lut", "scan", "refine")
+MAX_REFINE_K = 1024
+MAX_NPROBE = 4096
+
+EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_coarse", "rairs_lut",
+           "rairs_scan", "rairs_refine", "rairs_set_profiling", "rairs_get_stage_ms",
+           "rairs_get_dco", "rairs_index_bytes", "rairs_last_error")
+
+
+class RairsError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"rairs error {code}: {msg}")
+        self.code = code
+
+
+class _HostIndex(C.Structure):
+    _fields_ = [
+        ("d", C.c_int32), ("M", C.c_int32), ("nbits", C.c_int32), ("nlist", C.c_int32),
+        ("blk", C.c_int32), ("raw_is_u8", C.c_int32),
+        ("ntotal", C.c_int64), ("nblocks", C.c_int64), ("nrefs", C.c_int64),
+        ("centroids", C.c_void_p), ("codebook", C.c_void_p), ("codes", C.c_void_p),
+        ("ids", C.c_void_p), ("other", C.c_void_p),
+        ("list_shared_begin", C.c_void_p), ("list_shared_cnt", C.c_void_p),
+        ("list_misc_begin", C.c_void_p), ("list_misc_cnt", C.c_void_p),
+        ("list_ref_begin", C.c_void_p), ("list_ref_cnt", C.c_void_p),
+        ("ref_owner", C.c_void_p), ("ref_block_begin", C.c_void_p), ("ref_nblocks", C.c_void_p),
+        ("raw", C.c_void_p),
+    ]
+
+
+def load() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with "
+                "`python -m paper_2601_07183_amd.build_ext` (there is no fallback path)")
+        lib = C.CDLL(LIB_PATH)
+        lib.rairs_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            getattr(lib, name)
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise RairsError(rc, load().rairs_last_error().decode())
+
+
+def _stream_ptr(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> C.c_void_p:
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{name}: expected a contiguous device tensor of {dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+_ARRAYS = [("centroids", np.float32), ("codebook", np.float32), ("codes", np.uint8),
+           ("ids", np.int64), ("other", np.int32), ("list_shared_begin", np.int64),
+           ("list_shared_cnt", np.int32), ("list_misc_begin", np.int64),
+           ("list_misc_cnt", np.int32), ("list_ref_begin", np.int64), ("list_ref_cnt", np.int32),
+           ("ref_owner", np.int32), ("ref_block_begin", np.int64), ("ref_nblocks", np.int32)]
+
+
+def host_struct(hx):
+    """ctypes view of a host index object (attributes named as in rairs_host_index_t)."""
+    keep = []
+    s = _HostIndex()
+    s.d, s.M, s.nbits, s.nlist, s.blk = hx.d, hx.M, 4, hx.nlist, 32
+    s.ntotal, s.nblocks, s.nrefs = hx.ntotal, hx.ids.shape[0], hx.ref_owner.shape[0]
+    for name, dt in _ARRAYS:
+        a = np.ascontiguousarray(getattr(hx, name), dtype=dt)
+        keep.append(a)
+        setattr(s, name, a.ctypes.data)
+    raw = np.ascontiguousarray(hx.raw)
+    if raw.dtype not in (np.float32, np.uint8):
+        raise TypeError("raw vectors must be float32 or uint8")
+    s.raw_is_u8 = int(raw.dtype == np.uint8)
+    s.raw = raw.ctypes.data
+    keep.append(raw)
+    return s, keep
+
+
+class Index:
+    """Device-resident RAIRS index (rairs_index_upload ... rairs_free)."""
+
+    def __init__(self, hx, stream=None):
+        self._h = C.c_void_p()
+        self._lib = load()
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the search path has no CPU implementation")
+        s, keep = host_struct(hx)
+        _check(self._lib.rairs_index_upload(C.byref(s), _stream_ptr(stream), C.byref(self._h)))
+        del keep
+        self.d, self.M, self.nlist, self.ntotal = hx.d, hx.M, hx.nlist, hx.ntotal
+
+    def free(self):
+        if self._h:
+            _check(self._lib.rairs_free(self._h))
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+    # --- rairs_search ---------------------------------------------------------------------
+    def search(self, queries: torch.Tensor, k: int, nprobe: int, refine_k: int, out_ids=None,
+               out_dists=None, stream=None):
+        nq = queries.shape[0]
+        if out_ids is None:
+            out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+        if out_dists is None:
+            out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+        _check(self._lib.rairs_search(
+            self._h, _dev(queries, torch.float32, "queries"), C.c_int64(nq), C.c_int(k),
+            C.c_int(nprobe), C.c_int(refine_k), _dev(out_ids, torch.int64, "out_ids"),
+            _dev(out_dists, torch.float32, "out_dists"), _stream_ptr(stream)))
+        return out_ids, out_dists
+
+    # --- stages ---------------------------------------------------------------------------
+    def coarse(self, queries: torch.Tensor, nprobe: int, stream=None):
+        nq = queries.shape[0]
+        ids = torch.empty((nq, nprobe), dtype=torch.int32, device=queries.device)
+        dists = torch.empty((nq, nprobe), dtype=torch.float32, device=queries.device)
+        _check(self._lib.rairs_coarse(self._h, _dev(queries, torch.float32, "queries"),
+                                      C.c_int64(nq), C.c_int(nprobe), _dev(ids, torch.int32, "ids"),
+                                      _dev(dists, torch.float32, "dists"), _stream_ptr(stream)))
+        return ids, dists
+
+    def lut(self, queries: torch.Tensor, stream=None):
+        nq = queries.shape[0]
+        lut = torch.empty((nq, self.M, 16), dtype=torch.uint8, device=queries.device)
+        bias = torch.empty((nq,), dtype=torch.float32, device=queries.device)
+        scale = torch.empty((nq,), dtype=torch.float32, device=queries.device)
+        _check(self._lib.rairs_lut(self._h, _dev(queries, torch.float32, "queries"), C.c_int64(nq),
+                                   _dev(lut, torch.uint8, "lut"), _dev(bias, torch.float32, "bias"),
+                                   _dev(scale, torch.float32, "scale"), _stream_ptr(stream)))
+        return lut, bias, scale
+
+    def scan(self, lut: torch.Tensor, probe_ids: torch.Tensor, refine_k: int, stream=None):
+        nq, nprobe = probe_ids.shape
+        cand = torch.empty((nq, refine_k), dtype=torch.int64, device=lut.device)
+        score = torch.empty((nq, refine_k), dtype=torch.int32, device=lut.device)
+        dco = torch.empty((nq,), dtype=torch.int64, device=lut.device)
+        _check(self._lib.rairs_scan(self._h, _dev(lut, torch.uint8, "lut"),
+                                    _dev(probe_ids, torch.int32, "probe_ids"), C.c_int64(nq),
+                                    C.c_int(nprobe), C.c_int(refine_k),
+                                    _dev(cand, torch.int64, "cand"), _dev(score, torch.int32, "score"),
+                                    _dev(dco, torch.int64, "dco"), _stream_ptr(stream)))
+        return cand, score, dco
+
+    def refine(self, queries: torch.Tensor, cand_ids: torch.Tensor, k: int, stream=None):
+        nq, refine_k = cand_ids.shape
+        ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+        dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+        _check(self._lib.rairs_refine(self._h, _dev(queries, torch.float32, "queries"),
+                                      _dev(cand_ids, torch.int64, "cand_ids"), C.c_int64(nq),
+                                      C.c_int(refine_k), C.c_int(k), _dev(ids, torch.int64, "ids"),
+                                      _dev(dists, torch.float32, "dists"), _stream_ptr(stream)))
+        return ids, dists
+
+    # --- measurement ----------------------------------------------------------------------
+    def set_profiling(self, enabled: bool):
+        _check(self._lib.rairs_set_profiling(self._h, C.c_int(int(enabled))))
+
+    def stage_ms(self) -> dict:
+        ms = (C.c_float * len(STAGES))()
+        _check(self._lib.rairs_get_stage_ms(self._h, ms))
+        return dict(zip(STAGES, [float(x) for x in ms]))
+
+    def dco(self, nq: int) -> np.ndarray:
+        out = np.empty(nq, dtype=np.int64)
+        _check(self._lib.rairs_get_dco(self._h, C.c_void_p(out.ctypes.data), C.c_int64(nq)))
+        return out
+
+    def bytes(self):
+        a, b = C.c_int64(), C.c_int64()
+        _check(self._lib.rairs_index_bytes(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value

@@ -1,0 +1,475 @@
+// C ABI of librairs: argument checks, index upload into the device format, workspace and the
+// stage sequence of RairsSearch (Alg. 2).  No kernel code here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "rairs_common.h"
+
+static thread_local char g_err[512] = "";
+
+void rairs_set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char *rairs_last_error(void) { return g_err; }
+
+#define FAIL(code, ...)              \
+    do {                             \
+        rairs_set_error(__VA_ARGS__); \
+        return (code);               \
+    } while (0)
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int dev_alloc(rairs_index *h, void **p, size_t bytes)
+{
+    if (bytes == 0) bytes = 16;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        FAIL(RAIRS_ENOMEM, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    }
+    h->dev_alloc[h->ndev_alloc++] = *p;
+    h->total_bytes += (int64_t)bytes;
+    return RAIRS_OK;
+}
+
+static void destroy(rairs_index *h)
+{
+    if (!h) return;
+    for (int i = 0; i < h->ndev_alloc; i++) (void)hipFree(h->dev_alloc[i]);
+    if (h->ws) (void)hipFree(h->ws);
+    if (h->dco) (void)hipFree(h->dco);
+    if (h->ev_ready)
+        for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) (void)hipEventDestroy(h->ev[i]);
+    delete h;
+}
+
+static int validate(const rairs_host_index_t *x)
+{
+    if (!x) FAIL(RAIRS_EINVAL, "host index is NULL");
+    if (x->nbits != 4) FAIL(RAIRS_EINVAL, "nbits must be 4, got %d", x->nbits);
+    if (x->blk != 32) FAIL(RAIRS_EINVAL, "blk must be 32, got %d", x->blk);
+    if (x->d <= 0 || x->M <= 0 || x->d % x->M != 0 || (x->M & 1))
+        FAIL(RAIRS_EINVAL, "need d > 0, M > 0 even, d %% M == 0 (d=%d M=%d)", x->d, x->M);
+    if (255 * (int64_t)x->M > 65535) FAIL(RAIRS_EINVAL, "255*M exceeds 16 bits (M=%d)", x->M);
+    if (x->M > RAIRS_MAX_M) FAIL(RAIRS_EUNSUPPORTED, "M=%d above the built limit %d", x->M, RAIRS_MAX_M);
+    if (x->d > RAIRS_MAX_D) FAIL(RAIRS_EUNSUPPORTED, "d=%d above the built limit %d", x->d, RAIRS_MAX_D);
+    if (x->nlist <= 0) FAIL(RAIRS_EINVAL, "nlist must be positive");
+    if (x->nlist > RAIRS_MAX_NLIST) FAIL(RAIRS_EUNSUPPORTED, "nlist=%d above the built limit %d", x->nlist, RAIRS_MAX_NLIST);
+    if (x->ntotal < 0 || x->ntotal >= 0xFFFFFFFFll) FAIL(RAIRS_EINVAL, "ntotal out of range");
+    if (x->nblocks < 0 || x->nblocks > 0x7FFFFFFFll / 64) FAIL(RAIRS_EINVAL, "nblocks out of range");
+    if (x->nrefs < 0 || x->nrefs > 0x7FFFFFFFll) FAIL(RAIRS_EINVAL, "nrefs out of range");
+    if (!x->centroids || !x->codebook || !x->list_shared_begin || !x->list_shared_cnt ||
+        !x->list_misc_begin || !x->list_misc_cnt || !x->list_ref_begin || !x->list_ref_cnt)
+        FAIL(RAIRS_EINVAL, "null array in host index");
+    if (x->nblocks > 0 && (!x->codes || !x->ids || !x->other)) FAIL(RAIRS_EINVAL, "null block arrays");
+    if (x->nrefs > 0 && (!x->ref_owner || !x->ref_block_begin || !x->ref_nblocks))
+        FAIL(RAIRS_EINVAL, "null reference arrays");
+    if (x->ntotal > 0 && !x->raw) FAIL(RAIRS_EINVAL, "null raw vectors");
+    for (int l = 0; l < x->nlist; l++) {
+        int64_t sb = x->list_shared_begin[l], mb = x->list_misc_begin[l], rb = x->list_ref_begin[l];
+        int64_t sc = x->list_shared_cnt[l], mc = x->list_misc_cnt[l], rc = x->list_ref_cnt[l];
+        if (sc < 0 || mc < 0 || rc < 0 || sb < 0 || sb + sc > x->nblocks || mb != sb + sc ||
+            mb + mc > x->nblocks || rb < 0 || rb + rc > x->nrefs)
+            FAIL(RAIRS_EINVAL, "directory of list %d out of bounds", l);
+    }
+    for (int64_t r = 0; r < x->nrefs; r++) {
+        int32_t o = x->ref_owner[r];
+        if (o < 0 || o >= x->nlist) FAIL(RAIRS_EINVAL, "reference %lld: owner out of range", (long long)r);
+        int64_t b = x->ref_block_begin[r], n = x->ref_nblocks[r];
+        int64_t ob = x->list_shared_begin[o], oc = x->list_shared_cnt[o];
+        if (n < 1 || b < ob || b + n > ob + oc)
+            FAIL(RAIRS_EINVAL, "reference %lld does not point into its owner's shared blocks", (long long)r);
+    }
+    const int64_t nslots = x->nblocks * 32;
+    for (int64_t i = 0; i < nslots; i++) {
+        int64_t id = x->ids[i];
+        if (id < -1 || id >= x->ntotal) FAIL(RAIRS_EINVAL, "id out of range in slot %lld", (long long)i);
+        int32_t o = x->other[i];
+        if (o < -1 || o >= x->nlist) FAIL(RAIRS_EINVAL, "list tag out of range in slot %lld", (long long)i);
+    }
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream, rairs_index_t **out)
+{
+    if (!out) FAIL(RAIRS_EINVAL, "out is NULL");
+    *out = nullptr;
+    int rc = validate(x);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    rairs_index *h = new (std::nothrow) rairs_index();
+    if (!h) FAIL(RAIRS_ENOMEM, "out of host memory");
+    memset(h, 0, sizeof(*h));
+    IndexView &v = h->v;
+    v.d = x->d; v.M = x->M; v.T = x->M / 2; v.nd = (v.T + 7) / 8; v.nlist = x->nlist;
+    v.raw_u8 = x->raw_is_u8 ? 1 : 0;
+    v.ntotal = x->ntotal; v.nblocks = x->nblocks; v.nrefs = x->nrefs;
+
+#define UP_CHECK(call)            \
+    do {                          \
+        int rc_ = (call);         \
+        if (rc_) { destroy(h); return rc_; } \
+    } while (0)
+#define UP_HIP(call)                                                                  \
+    do {                                                                              \
+        hipError_t e_ = (call);                                                       \
+        if (e_ != hipSuccess) {                                                       \
+            rairs_set_error("%s failed: %s", #call, hipGetErrorString(e_));           \
+            destroy(h);                                                               \
+            return RAIRS_EHIP;                                                        \
+        }                                                                             \
+    } while (0)
+
+    float *cent = nullptr, *cent_t = nullptr, *cb = nullptr;
+    uint32_t *codes = nullptr, *ids = nullptr;
+    int32_t *other = nullptr;
+    ListEntry *lists = nullptr;
+    RefEntry *refs = nullptr;
+    void *raw = nullptr;
+    const size_t cent_bytes = (size_t)x->nlist * x->d * sizeof(float);
+    const size_t cb_bytes = (size_t)x->M * 16 * (x->d / x->M) * sizeof(float);
+    h->code_bytes = (int64_t)x->nblocks * v.nd * 64 * 4;
+    const size_t raw_bytes = (size_t)x->ntotal * x->d * (v.raw_u8 ? 1 : 4);
+    UP_CHECK(dev_alloc(h, (void **)&cent_t, cent_bytes));
+    UP_CHECK(dev_alloc(h, (void **)&cb, cb_bytes));
+    UP_CHECK(dev_alloc(h, (void **)&codes, (size_t)h->code_bytes));
+    UP_CHECK(dev_alloc(h, (void **)&ids, (size_t)x->nblocks * 32 * 4));
+    UP_CHECK(dev_alloc(h, (void **)&other, (size_t)x->nblocks * 32 * 4));
+    UP_CHECK(dev_alloc(h, (void **)&lists, (size_t)x->nlist * sizeof(ListEntry)));
+    UP_CHECK(dev_alloc(h, (void **)&refs, (size_t)x->nrefs * sizeof(RefEntry)));
+    UP_CHECK(dev_alloc(h, &raw, raw_bytes));
+
+    // centroids: transposed to [d][nlist] so that lanes of the coarse kernel read coalesced
+    UP_HIP(hipMalloc((void **)&cent, cent_bytes));
+    hipError_t e = hipMemcpyAsync(cent, x->centroids, cent_bytes, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) {
+        int r2 = rairs_launch_transpose(cent, x->nlist, x->d, cent_t, s);
+        e = hipStreamSynchronize(s);
+        (void)hipFree(cent);
+        if (r2) { destroy(h); return r2; }
+    } else {
+        (void)hipFree(cent);
+    }
+    UP_HIP(e);
+    UP_HIP(hipMemcpyAsync(cb, x->codebook, cb_bytes, hipMemcpyHostToDevice, s));
+    if (x->nblocks)
+        UP_HIP(hipMemcpyAsync(other, x->other, (size_t)x->nblocks * 32 * 4, hipMemcpyHostToDevice, s));
+    if (raw_bytes) UP_HIP(hipMemcpyAsync(raw, x->raw, raw_bytes, hipMemcpyHostToDevice, s));
+
+    // directory
+    std::vector<ListEntry> hl((size_t)x->nlist);
+    for (int l = 0; l < x->nlist; l++) {
+        ListEntry &e2 = hl[(size_t)l];
+        e2.blk_begin = (int32_t)x->list_shared_begin[l];
+        e2.shared_cnt = x->list_shared_cnt[l];
+        e2.misc_cnt = x->list_misc_cnt[l];
+        e2.ref_begin = (int32_t)x->list_ref_begin[l];
+        e2.ref_cnt = x->list_ref_cnt[l];
+        int64_t valid = 0;
+        const int64_t b0 = x->list_shared_begin[l], b1 = b0 + x->list_shared_cnt[l] + x->list_misc_cnt[l];
+        for (int64_t i = b0 * 32; i < b1 * 32; i++) valid += x->ids[i] >= 0;
+        e2.valid_items = (int32_t)valid;
+    }
+    std::vector<RefEntry> hr((size_t)x->nrefs);
+    for (int64_t r = 0; r < x->nrefs; r++) {
+        hr[(size_t)r].owner = x->ref_owner[r];
+        hr[(size_t)r].blk_begin = (int32_t)x->ref_block_begin[r];
+        hr[(size_t)r].nblocks = x->ref_nblocks[r];
+    }
+    UP_HIP(hipMemcpyAsync(lists, hl.data(), hl.size() * sizeof(ListEntry), hipMemcpyHostToDevice, s));
+    if (x->nrefs)
+        UP_HIP(hipMemcpyAsync(refs, hr.data(), hr.size() * sizeof(RefEntry), hipMemcpyHostToDevice, s));
+
+    // blocks: staged in chunks in the canonical layout, repacked on the device
+    if (x->nblocks) {
+        const int64_t chunk = 1 << 16;   // blocks per staging chunk
+        const size_t cbytes = (size_t)chunk * 32 * v.T;
+        uint8_t *st_codes = nullptr;
+        int64_t *st_ids = nullptr;
+        UP_HIP(hipMalloc((void **)&st_codes, cbytes));
+        e = hipMalloc((void **)&st_ids, (size_t)chunk * 32 * 8);
+        if (e != hipSuccess) { (void)hipFree(st_codes); UP_HIP(e); }
+        int r2 = RAIRS_OK;
+        for (int64_t b0 = 0; b0 < x->nblocks && e == hipSuccess && r2 == RAIRS_OK; b0 += chunk) {
+            int64_t nb = x->nblocks - b0 < chunk ? x->nblocks - b0 : chunk;
+            e = hipMemcpyAsync(st_codes, x->codes + (size_t)b0 * 32 * v.T, (size_t)nb * 32 * v.T,
+                               hipMemcpyHostToDevice, s);
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(st_ids, x->ids + (size_t)b0 * 32, (size_t)nb * 32 * 8,
+                                   hipMemcpyHostToDevice, s);
+            if (e == hipSuccess) r2 = rairs_launch_pack(st_codes, st_ids, b0, nb, v.M, v.nd, codes, ids, s);
+            if (e == hipSuccess) e = hipStreamSynchronize(s);
+        }
+        (void)hipFree(st_codes);
+        (void)hipFree(st_ids);
+        if (r2) { destroy(h); return r2; }
+        UP_HIP(e);
+    }
+    UP_HIP(hipStreamSynchronize(s));
+
+    v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other;
+    v.lists = lists; v.refs = refs; v.raw = raw;
+    for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[i]));
+    h->ev_ready = 1;
+    *out = h;
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_free(rairs_index_t *h)
+{
+    destroy(h);
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, int64_t *total_bytes)
+{
+    if (!h) FAIL(RAIRS_EINVAL, "handle is NULL");
+    if (code_bytes) *code_bytes = h->code_bytes;
+    if (total_bytes) *total_bytes = h->total_bytes;
+    return RAIRS_OK;
+}
+
+// ---- workspace ------------------------------------------------------------------------------
+
+struct WsLayout {
+    size_t dmat, probe_ids, probe_dists, bitmap, lut, cand, total;
+    int bmwords;
+};
+
+static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine_k)
+{
+    WsLayout w;
+    w.bmwords = (v.nlist + 31) / 32;
+    size_t off = 0;
+    w.dmat = off;        off = align_up(off + (size_t)nq * v.nlist * 4, 256);
+    w.probe_ids = off;   off = align_up(off + (size_t)nq * nprobe * 4, 256);
+    w.probe_dists = off; off = align_up(off + (size_t)nq * nprobe * 4, 256);
+    w.bitmap = off;      off = align_up(off + (size_t)nq * w.bmwords * 4, 256);
+    w.lut = off;         off = align_up(off + (size_t)nq * v.M * 16, 256);
+    w.cand = off;        off = align_up(off + (size_t)nq * refine_k * 8, 256);
+    w.total = off;
+    return w;
+}
+
+static int ensure_ws(rairs_index *h, size_t bytes)
+{
+    if (h->ws_bytes >= bytes) return RAIRS_OK;
+    if (h->ws) { RAIRS_HIP(hipDeviceSynchronize()); (void)hipFree(h->ws); h->ws = nullptr; h->ws_bytes = 0; }
+    hipError_t e = hipMalloc(&h->ws, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        FAIL(RAIRS_ENOMEM, "workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
+    }
+    h->ws_bytes = bytes;
+    return RAIRS_OK;
+}
+
+static int ensure_dco(rairs_index *h, int64_t nq)
+{
+    if (h->dco_cap >= nq) return RAIRS_OK;
+    if (h->dco) { RAIRS_HIP(hipDeviceSynchronize()); (void)hipFree(h->dco); h->dco = nullptr; h->dco_cap = 0; }
+    hipError_t e = hipMalloc((void **)&h->dco, (size_t)nq * 8);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        FAIL(RAIRS_ENOMEM, "dco buffer: %s", hipGetErrorString(e));
+    }
+    h->dco_cap = nq;
+    return RAIRS_OK;
+}
+
+static int check_common(const rairs_index *h, int64_t nq)
+{
+    if (!h) FAIL(RAIRS_EINVAL, "handle is NULL");
+    if (nq < 0) FAIL(RAIRS_EINVAL, "nq is negative");
+    if (nq > 0x7FFFFFFFll / 4) FAIL(RAIRS_EUNSUPPORTED, "nq too large for one call");
+    return RAIRS_OK;
+}
+
+static int check_nprobe(const rairs_index *h, int nprobe)
+{
+    if (nprobe < 1 || nprobe > h->v.nlist) FAIL(RAIRS_EINVAL, "nprobe=%d outside [1, nlist=%d]", nprobe, h->v.nlist);
+    if (nprobe > RAIRS_MAX_NPROBE) FAIL(RAIRS_EUNSUPPORTED, "nprobe=%d above the built limit %d", nprobe, RAIRS_MAX_NPROBE);
+    return RAIRS_OK;
+}
+
+static int check_k(int k, int refine_k)
+{
+    if (k < 1 || k > refine_k) FAIL(RAIRS_EINVAL, "need 1 <= k <= refine_k (k=%d refine_k=%d)", k, refine_k);
+    if (refine_k > RAIRS_MAX_REFINE_K) FAIL(RAIRS_EUNSUPPORTED, "refine_k=%d above the built limit %d", refine_k, RAIRS_MAX_REFINE_K);
+    return RAIRS_OK;
+}
+
+// Queries per internal pass so that the distance matrix stays within ~1 GiB.
+static int64_t pass_size(const IndexView &v, int64_t nq)
+{
+    int64_t per_q = (int64_t)v.nlist * 4 + 65536;
+    int64_t cap = (1ll << 30) / per_q;
+    if (cap < 256) cap = 256;
+    return nq < cap ? nq : cap;
+}
+
+// ---- stages -----------------------------------------------------------------------------------
+
+extern "C" int rairs_coarse(rairs_index_t *h, const float *d_queries, int64_t nq, int nprobe,
+                            int32_t *d_probe_ids, float *d_probe_dists, void *hip_stream)
+{
+    int rc = check_common(h, nq);
+    if (rc) return rc;
+    if ((rc = check_nprobe(h, nprobe))) return rc;
+    if (nq == 0) return RAIRS_OK;
+    if (!d_queries || !d_probe_ids) FAIL(RAIRS_EINVAL, "null device pointer");
+    const int64_t step = pass_size(h->v, nq);
+    if ((rc = ensure_ws(h, ws_layout(h->v, step, nprobe, 1).total))) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    for (int64_t q0 = 0; q0 < nq; q0 += step) {
+        int64_t n = nq - q0 < step ? nq - q0 : step;
+        rc = rairs_launch_coarse(h->v, d_queries + (size_t)q0 * h->v.d, n, nprobe, (float *)h->ws,
+                                 d_probe_ids + (size_t)q0 * nprobe,
+                                 d_probe_dists ? d_probe_dists + (size_t)q0 * nprobe : nullptr, s);
+        if (rc) return rc;
+    }
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_lut(rairs_index_t *h, const float *d_queries, int64_t nq, uint8_t *d_lut,
+                         float *d_bias_sum, float *d_scale, void *hip_stream)
+{
+    int rc = check_common(h, nq);
+    if (rc) return rc;
+    if (nq == 0) return RAIRS_OK;
+    if (!d_queries || !d_lut) FAIL(RAIRS_EINVAL, "null device pointer");
+    return rairs_launch_lut(h->v, d_queries, nq, d_lut, d_bias_sum, d_scale, (hipStream_t)hip_stream);
+}
+
+static int scan_pass(rairs_index *h, const uint8_t *lut, const int32_t *probe_ids, uint32_t *bitmap,
+                     int bmwords, int64_t n, int nprobe, int refine_k, int64_t *cand_ids,
+                     int32_t *cand_score, int64_t *dco, hipStream_t s)
+{
+    int rc = rairs_launch_bitmap(h->v, probe_ids, n, nprobe, bitmap, bmwords, s);
+    if (rc) return rc;
+    return rairs_launch_scan_exact(h->v, lut, probe_ids, bitmap, bmwords, n, nprobe, refine_k,
+                                   cand_ids, cand_score, dco, s);
+}
+
+extern "C" int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t *d_probe_ids,
+                          int64_t nq, int nprobe, int refine_k, int64_t *d_cand_ids,
+                          int32_t *d_cand_score, int64_t *d_dco, void *hip_stream)
+{
+    int rc = check_common(h, nq);
+    if (rc) return rc;
+    if ((rc = check_nprobe(h, nprobe))) return rc;
+    if ((rc = check_k(1, refine_k))) return rc;
+    if (nq == 0) return RAIRS_OK;
+    if (!d_lut || !d_probe_ids || !d_cand_ids) FAIL(RAIRS_EINVAL, "null device pointer");
+    const int64_t step = pass_size(h->v, nq);
+    WsLayout w = ws_layout(h->v, step, nprobe, refine_k);
+    if ((rc = ensure_ws(h, w.total))) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)h->ws;
+    for (int64_t q0 = 0; q0 < nq; q0 += step) {
+        int64_t n = nq - q0 < step ? nq - q0 : step;
+        rc = scan_pass(h, d_lut + (size_t)q0 * h->v.M * 16, d_probe_ids + (size_t)q0 * nprobe,
+                       (uint32_t *)(ws + w.bitmap), w.bmwords, n, nprobe, refine_k,
+                       d_cand_ids + (size_t)q0 * refine_k,
+                       d_cand_score ? d_cand_score + (size_t)q0 * refine_k : nullptr,
+                       d_dco ? d_dco + q0 : nullptr, s);
+        if (rc) return rc;
+    }
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_refine(rairs_index_t *h, const float *d_queries, const int64_t *d_cand_ids,
+                            int64_t nq, int refine_k, int k, int64_t *d_out_ids,
+                            float *d_out_dists, void *hip_stream)
+{
+    int rc = check_common(h, nq);
+    if (rc) return rc;
+    if ((rc = check_k(k, refine_k))) return rc;
+    if (nq == 0) return RAIRS_OK;
+    if (!d_queries || !d_cand_ids || !d_out_ids || !d_out_dists) FAIL(RAIRS_EINVAL, "null device pointer");
+    return rairs_launch_refine(h->v, d_queries, d_cand_ids, nq, refine_k, k, d_out_ids, d_out_dists,
+                               (hipStream_t)hip_stream);
+}
+
+// ---- RairsSearch (Alg. 2) -----------------------------------------------------------------------
+
+extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
+                            int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream)
+{
+    int rc = check_common(h, nq);
+    if (rc) return rc;
+    if ((rc = check_nprobe(h, nprobe))) return rc;
+    if ((rc = check_k(k, refine_k))) return rc;
+    if (nq == 0) return RAIRS_OK;
+    if (!d_queries || !d_out_ids || !d_out_dists) FAIL(RAIRS_EINVAL, "null device pointer");
+    const IndexView &v = h->v;
+    const int64_t step = pass_size(v, nq);
+    WsLayout w = ws_layout(v, step, nprobe, refine_k);
+    if ((rc = ensure_ws(h, w.total))) return rc;
+    if ((rc = ensure_dco(h, nq))) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)h->ws;
+    // stage timing is only meaningful when the batch fits one pass
+    const bool prof = h->prof && step == nq;
+    h->prof_valid = 0;
+    for (int64_t q0 = 0; q0 < nq; q0 += step) {
+        int64_t n = nq - q0 < step ? nq - q0 : step;
+        const float *q = d_queries + (size_t)q0 * v.d;
+        int32_t *probe_ids = (int32_t *)(ws + w.probe_ids);
+        uint8_t *lut = (uint8_t *)(ws + w.lut);
+        int64_t *cand = (int64_t *)(ws + w.cand);
+        if (prof) RAIRS_HIP(hipEventRecord(h->ev[0], s));
+        if ((rc = rairs_launch_coarse(v, q, n, nprobe, (float *)(ws + w.dmat), probe_ids,
+                                      (float *)(ws + w.probe_dists), s))) return rc;
+        if (prof) { RAIRS_HIP(hipEventRecord(h->ev[1], s)); RAIRS_HIP(hipEventRecord(h->ev[2], s)); }
+        if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, s))) return rc;
+        if (prof) { RAIRS_HIP(hipEventRecord(h->ev[3], s)); RAIRS_HIP(hipEventRecord(h->ev[4], s)); }
+        if ((rc = scan_pass(h, lut, probe_ids, (uint32_t *)(ws + w.bitmap), w.bmwords, n, nprobe,
+                            refine_k, cand, nullptr, h->dco + q0, s))) return rc;
+        if (prof) { RAIRS_HIP(hipEventRecord(h->ev[5], s)); RAIRS_HIP(hipEventRecord(h->ev[6], s)); }
+        if ((rc = rairs_launch_refine(v, q, cand, n, refine_k, k, d_out_ids + (size_t)q0 * k,
+                                      d_out_dists + (size_t)q0 * k, s))) return rc;
+        if (prof) RAIRS_HIP(hipEventRecord(h->ev[7], s));
+    }
+    h->prof_valid = prof ? 1 : 0;
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_set_profiling(rairs_index_t *h, int enabled)
+{
+    if (!h) FAIL(RAIRS_EINVAL, "handle is NULL");
+    h->prof = enabled ? 1 : 0;
+    h->prof_valid = 0;
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_get_stage_ms(rairs_index_t *h, float *ms)
+{
+    if (!h || !ms) FAIL(RAIRS_EINVAL, "null argument");
+    if (!h->prof_valid) FAIL(RAIRS_EINVAL, "no profiled search recorded (profiling off, or the batch took several passes)");
+    for (int i = 0; i < RAIRS_NSTAGES; i++) {
+        RAIRS_HIP(hipEventSynchronize(h->ev[2 * i + 1]));
+        RAIRS_HIP(hipEventElapsedTime(&ms[i], h->ev[2 * i], h->ev[2 * i + 1]));
+    }
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq)
+{
+    if (!h || !dco) FAIL(RAIRS_EINVAL, "null argument");
+    if (nq < 0 || nq > h->dco_cap) FAIL(RAIRS_EINVAL, "nq exceeds the last search's batch");
+    if (nq == 0) return RAIRS_OK;
+    RAIRS_HIP(hipMemcpy(dco, h->dco, (size_t)nq * 8, hipMemcpyDeviceToHost));
+    return RAIRS_OK;
+}

@@ -1,0 +1,544 @@
+// HIP kernels (gfx950, wave64) of the RAIRS query path: coarse quantizer, lookup tables,
+// exact SEIL scan with a bounded top-bigK queue, refinement.  Built with -ffp-contract=off:
+// the fp32 operation order below is part of the result's definition.
+#include "rairs_common.h"
+
+#define WG 256
+
+static __device__ __forceinline__ int next_pow2(int x)
+{
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// Ascending bitonic sort of n (power of two) 64-bit keys in LDS by the whole workgroup.
+// Callers synchronise before; the array is consistent for all threads on return.
+static __device__ void bitonic_sort_lds(uint64_t *a, int n)
+{
+    for (int k = 2; k <= n; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = threadIdx.x; i < n; i += WG) {
+                int p = i ^ j;
+                if (p > i) {
+                    bool up = (i & k) == 0;
+                    uint64_t x = a[i], y = a[p];
+                    if ((x > y) == up) { a[i] = y; a[p] = x; }
+                }
+            }
+            __syncthreads();
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// upload helpers
+// ---------------------------------------------------------------------------------------------
+
+// canonical [blk][32 items][T bytes] (low nibble = even subspace) -> device dword layout
+__global__ void pack_codes_kernel(const uint8_t *in, int64_t nblk, int T, int nd, uint32_t *out)
+{
+    int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = nblk * nd * 64;
+    if (gid >= total) return;
+    int lane = (int)(gid & 63);
+    int64_t bw = gid >> 6;
+    int w = (int)(bw % nd);
+    int64_t b = bw / nd;
+    int g = lane >> 5, item = lane & 31;
+    const uint8_t *row = in + ((size_t)b * 32 + item) * T;
+    uint32_t v = 0;
+    for (int n = 0; n < 8; n++) {
+        int t = 8 * w + n;
+        if (t < T) {
+            uint32_t byte = row[t];
+            uint32_t nib = g ? (byte >> 4) : (byte & 15u);
+            v |= nib << (4 * n);
+        }
+    }
+    out[gid] = v;
+}
+
+__global__ void pack_ids_kernel(const int64_t *in, int64_t n, uint32_t *out)
+{
+    int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid < n) out[gid] = in[gid] < 0 ? RAIRS_EMPTY_ID : (uint32_t)in[gid];
+}
+
+int rairs_launch_pack(const uint8_t *d_codes, const int64_t *d_ids64, int64_t blk0, int64_t nblk,
+                      int M, int nd, uint32_t *codes, uint32_t *ids, hipStream_t s)
+{
+    if (nblk == 0) return RAIRS_OK;
+    int64_t total = nblk * nd * 64;
+    hipLaunchKernelGGL(pack_codes_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       d_codes, nblk, M / 2, nd, codes + (size_t)blk0 * nd * 64);
+    int64_t n = nblk * 32;
+    hipLaunchKernelGGL(pack_ids_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                       d_ids64, n, ids + (size_t)blk0 * 32);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+__global__ void transpose_kernel(const float *in, int rows, int cols, float *out)
+{
+    int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= (int64_t)rows * cols) return;
+    int r = (int)(gid / cols), c = (int)(gid % cols);
+    out[(size_t)c * rows + r] = in[gid];
+}
+
+int rairs_launch_transpose(const float *d_in, int rows, int cols, float *d_out, hipStream_t s)
+{
+    int64_t n = (int64_t)rows * cols;
+    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, d_in,
+                       rows, cols, d_out);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// coarse quantizer: FindNearestLists for the batch (Alg. 2 line 5)
+// ---------------------------------------------------------------------------------------------
+
+// One lane per (query, centroid).  The squared distance is summed as 64 interleaved partial
+// sums over the dimensions (class = dimension mod 64), folded pairwise at strides 32..1.
+__global__ __launch_bounds__(WG) void coarse_dist_kernel(const float *__restrict__ q,
+                                                         const float *__restrict__ ct, int d,
+                                                         int nlist, int groups,
+                                                         float *__restrict__ dmat)
+{
+    int qi = blockIdx.x / groups;
+    int l = (blockIdx.x % groups) * WG + threadIdx.x;
+    const float *qq = q + (size_t)qi * d;
+    int lc = l < nlist ? l : nlist - 1;
+    float p[64];
+#pragma unroll
+    for (int j = 0; j < 64; j++) p[j] = 0.0f;
+    for (int i0 = 0; i0 < d; i0 += 64) {
+#pragma unroll
+        for (int j = 0; j < 64; j++) {
+            int i = i0 + j;
+            if (i < d) {
+                float diff = qq[i] - ct[(size_t)i * nlist + lc];
+                float sq = diff * diff;
+                p[j] = p[j] + sq;
+            }
+        }
+    }
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) {
+#pragma unroll
+        for (int j = 0; j < s; j++) p[j] = p[j] + p[j + s];
+    }
+    if (l < nlist) dmat[(size_t)qi * nlist + l] = p[0];
+}
+
+// Per query: the nprobe smallest (distance, list id) by radix select on the fp32 bit pattern
+// (distances are >= +0, so the unsigned order of the bits is the numeric order), then sorted.
+__global__ __launch_bounds__(WG) void coarse_select_kernel(const float *__restrict__ dmat,
+                                                           int nlist, int nprobe,
+                                                           int32_t *__restrict__ probe_ids,
+                                                           float *__restrict__ probe_dists)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_prefix, s_remaining, s_cnt;
+    __shared__ int wcnt[WG / 64];
+    __shared__ uint64_t sel[RAIRS_MAX_NPROBE];
+    const int tid = threadIdx.x;
+    const uint32_t *row = (const uint32_t *)(dmat + (size_t)blockIdx.x * nlist);
+
+    uint32_t prefix = 0, mask = 0, remaining = (uint32_t)nprobe;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < nlist; i += WG) {
+            uint32_t key = row[i];
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t cum = 0;
+            for (int b = 0; b < 256; b++) {
+                uint32_t h = hist[b];
+                if (cum + h >= remaining) {
+                    s_prefix = prefix | ((uint32_t)b << shift);
+                    s_remaining = remaining - cum;
+                    break;
+                }
+                cum += h;
+            }
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        remaining = s_remaining;
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    // prefix is now the bit pattern of the nprobe-th smallest distance; `remaining` of the keys
+    // equal to it are needed, the ones with the smallest list ids.
+    const uint32_t kth = prefix;
+    if (tid == 0) s_cnt = 0;
+    __syncthreads();
+    for (int i = tid; i < nlist; i += WG) {
+        uint32_t key = row[i];
+        if (key < kth) {
+            uint32_t pos = atomicAdd(&s_cnt, 1u);
+            sel[pos] = ((uint64_t)key << 32) | (uint32_t)i;
+        }
+    }
+    __syncthreads();
+    const uint32_t base = s_cnt;
+    uint32_t running = 0;
+    const int wave = tid >> 6, lane = tid & 63;
+    for (int i0 = 0; i0 < nlist && running < remaining; i0 += WG) {
+        int i = i0 + tid;
+        bool flag = i < nlist && row[i] == kth;
+        unsigned long long b = __ballot(flag);
+        if (lane == 0) wcnt[wave] = __popcll(b);
+        __syncthreads();
+        uint32_t off = running + (uint32_t)__popcll(b & ((1ull << lane) - 1ull));
+        uint32_t tot = 0;
+        for (int w = 0; w < WG / 64; w++) {
+            if (w < wave) off += wcnt[w];
+            tot += wcnt[w];
+        }
+        if (flag && off < remaining) sel[base + off] = ((uint64_t)kth << 32) | (uint32_t)i;
+        running += tot;
+        __syncthreads();
+    }
+    const int n2 = next_pow2(nprobe);
+    for (int i = nprobe + tid; i < n2; i += WG) sel[i] = ~0ull;
+    __syncthreads();
+    bitonic_sort_lds(sel, n2);
+    for (int i = tid; i < nprobe; i += WG) {
+        uint64_t key = sel[i];
+        probe_ids[(size_t)blockIdx.x * nprobe + i] = (int32_t)(uint32_t)key;
+        if (probe_dists) probe_dists[(size_t)blockIdx.x * nprobe + i] = __uint_as_float((uint32_t)(key >> 32));
+    }
+}
+
+int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,
+                        int32_t *probe_ids, float *probe_dists, hipStream_t s)
+{
+    int groups = (v.nlist + WG - 1) / WG;
+    hipLaunchKernelGGL(coarse_dist_kernel, dim3((unsigned)(nq * groups)), dim3(WG), 0, s, q,
+                       v.centroids_t, v.d, v.nlist, groups, dmat);
+    hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist,
+                       nprobe, probe_ids, probe_dists);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// probe set of each query as a bitmap over list ids (listVisited of Alg. 5, made order-free)
+__global__ __launch_bounds__(WG) void bitmap_kernel(const int32_t *__restrict__ probe_ids,
+                                                    int nprobe, int nlist, int bmwords,
+                                                    uint32_t *__restrict__ bitmap)
+{
+    uint32_t *bm = bitmap + (size_t)blockIdx.x * bmwords;
+    for (int i = threadIdx.x; i < bmwords; i += WG) bm[i] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < nprobe; i += WG) {
+        int32_t l = probe_ids[(size_t)blockIdx.x * nprobe + i];
+        if (l >= 0 && l < nlist) atomicOr(&bm[l >> 5], 1u << (l & 31));
+    }
+}
+
+int rairs_launch_bitmap(const IndexView &v, const int32_t *probe_ids, int64_t nq, int nprobe,
+                        uint32_t *bitmap, int bmwords, hipStream_t s)
+{
+    hipLaunchKernelGGL(bitmap_kernel, dim3((unsigned)nq), dim3(WG), 0, s, probe_ids, nprobe,
+                       v.nlist, bmwords, bitmap);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// lookup tables: ComputeLookupTable (Alg. 2 line 4) + 8-bit quantisation
+// ---------------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(WG) void lut_kernel(const float *__restrict__ q,
+                                                 const float *__restrict__ codebook, int d, int M,
+                                                 uint8_t *__restrict__ lut,
+                                                 float *__restrict__ bias_sum,
+                                                 float *__restrict__ scale)
+{
+    __shared__ float Ts[RAIRS_MAX_M * 16];
+    __shared__ float bias[RAIRS_MAX_M];
+    __shared__ float width[RAIRS_MAX_M];
+    __shared__ float s_scale;
+    const int tid = threadIdx.x;
+    const int dsub = d / M;
+    const float *qq = q + (size_t)blockIdx.x * d;
+    for (int e = tid; e < M * 16; e += WG) {
+        int m = e >> 4;
+        const float *cw = codebook + (size_t)e * dsub;
+        float a = qq[m * dsub] - cw[0];
+        float acc = a * a;
+        for (int t = 1; t < dsub; t++) {
+            float b = qq[m * dsub + t] - cw[t];
+            float sq = b * b;
+            acc = acc + sq;
+        }
+        Ts[e] = acc;
+    }
+    __syncthreads();
+    for (int m = tid; m < M; m += WG) {
+        float lo = Ts[m * 16], hi = lo;
+        for (int c = 1; c < 16; c++) {
+            float x = Ts[m * 16 + c];
+            lo = x < lo ? x : lo;
+            hi = x > hi ? x : hi;
+        }
+        bias[m] = lo;
+        width[m] = hi - lo;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float span = 0.0f, bsum = 0.0f;
+        for (int m = 0; m < M; m++) {
+            span = width[m] > span ? width[m] : span;
+            bsum = bsum + bias[m];
+        }
+        float s = span > 0.0f ? __fdiv_rn(255.0f, span) : 0.0f;
+        s_scale = s;
+        if (bias_sum) bias_sum[blockIdx.x] = bsum;
+        if (scale) scale[blockIdx.x] = s;
+    }
+    __syncthreads();
+    const float s = s_scale;
+    for (int e = tid; e < M * 16; e += WG) {
+        float x = Ts[e] - bias[e >> 4];
+        float y = x * s;
+        float r = rintf(y);
+        r = r > 255.0f ? 255.0f : r;
+        lut[(size_t)blockIdx.x * M * 16 + e] = (uint8_t)r;
+    }
+}
+
+int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lut, float *bias_sum,
+                     float *scale, hipStream_t s)
+{
+    hipLaunchKernelGGL(lut_kernel, dim3((unsigned)nq), dim3(WG), 0, s, q, v.codebook, v.d, v.M,
+                       lut, bias_sum, scale);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// exact SEIL scan, one workgroup per query (SeilSearch, Alg. 5, with rqueue)
+// ---------------------------------------------------------------------------------------------
+//
+// listVisited is replaced by the order-free equivalent over the query's probe bitmap P:
+//   reference entry (owner i) of list j is scanned  iff  i not in P;
+//   own shared blocks are always scanned;
+//   a miscellaneous item of list L tagged with other list o is dropped  iff  o in P and o < L.
+// (Alg. 5 visits lists in ascending id, owners have the smaller id, hence "visited" == "in P and
+// smaller".)  Every (query, list) pair is then independent of all others.
+//
+// rqueue: survivors with key (score << 32 | id) below the current bound are appended to an LDS
+// buffer; when it fills, the buffer is sorted, cut to bigK entries and the bound tightened.
+
+#define SCAN_CAP 2048
+#define SCAN_ROUND 16     // blocks per workgroup between buffer checks (4 per wave)
+
+struct ScanShared {
+    uint64_t buf[SCAN_CAP];
+    uint32_t bm[RAIRS_MAX_NLIST / 32];
+    uint8_t lut[RAIRS_MAX_M * 16];
+    uint64_t tau;
+    uint32_t cnt;
+    unsigned long long dco;
+};
+
+static __device__ __forceinline__ void scan_prune(ScanShared &sh, int refine_k)
+{
+    // all threads arrive here together
+    __syncthreads();
+    int n = (int)sh.cnt;
+    int n2 = next_pow2(n < 2 ? 2 : n);
+    for (int i = n + threadIdx.x; i < n2; i += WG) sh.buf[i] = ~0ull;
+    __syncthreads();
+    bitonic_sort_lds(sh.buf, n2);
+    if (threadIdx.x == 0) {
+        int keep = n < refine_k ? n : refine_k;
+        sh.cnt = (uint32_t)keep;
+        sh.tau = keep == refine_k ? sh.buf[refine_k - 1] : ~0ull;
+    }
+    __syncthreads();
+}
+
+static __device__ __forceinline__ uint32_t scan_block_acc(const IndexView &v, const ScanShared &sh,
+                                                          int64_t blk, int lane)
+{
+    const int g = lane >> 5;
+    const uint32_t *cp = v.codes + (size_t)blk * v.nd * 64 + lane;
+    uint32_t part = 0;
+    for (int w = 0; w < v.nd; w++) {
+        uint32_t c = cp[(size_t)w * 64];
+        const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
+        for (int n = 0; n < tmax; n++) {
+            int m = 2 * (8 * w + n) + g;
+            part += sh.lut[m * 16 + ((c >> (4 * n)) & 15u)];
+        }
+    }
+    return part + (uint32_t)__shfl_xor((int)part, 32);
+}
+
+__global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v,
+                                                        const uint8_t *__restrict__ lut,
+                                                        const int32_t *__restrict__ probe_ids,
+                                                        const uint32_t *__restrict__ bitmap,
+                                                        int bmwords, int nprobe, int refine_k,
+                                                        int64_t *__restrict__ cand_ids,
+                                                        int32_t *__restrict__ cand_score,
+                                                        int64_t *__restrict__ dco)
+{
+    __shared__ ScanShared sh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t qi = blockIdx.x;
+    for (int i = tid; i < v.M * 16; i += WG) sh.lut[i] = lut[(size_t)qi * v.M * 16 + i];
+    for (int i = tid; i < bmwords; i += WG) sh.bm[i] = bitmap[(size_t)qi * bmwords + i];
+    if (tid == 0) { sh.tau = ~0ull; sh.cnt = 0; sh.dco = 0; }
+    __syncthreads();
+
+    unsigned long long my_dco = 0;
+    for (int p = 0; p < nprobe; p++) {
+        const int L = probe_ids[(size_t)qi * nprobe + p];
+        if (L < 0 || L >= v.nlist) continue;              // caller-supplied ids: never index with them unchecked
+        const ListEntry le = v.lists[L];
+        // segment -1: the list's own blocks; segments 0..ref_cnt-1: its reference entries
+        for (int seg = -1; seg < le.ref_cnt; seg++) {
+            int64_t begin;
+            int cnt, misc_from;
+            if (seg < 0) {
+                begin = le.blk_begin;
+                cnt = le.shared_cnt + le.misc_cnt;
+                misc_from = le.shared_cnt;
+            } else {
+                const RefEntry re = v.refs[le.ref_begin + seg];
+                if ((sh.bm[re.owner >> 5] >> (re.owner & 31)) & 1u) continue;   // scanned via owner
+                begin = re.blk_begin;
+                cnt = re.nblocks;
+                misc_from = cnt;
+            }
+            for (int base = 0; base < cnt; base += SCAN_ROUND) {
+                for (int j = 0; j < SCAN_ROUND / 4; j++) {
+                    int b = base + j * 4 + wave;
+                    if (b < cnt) {
+                        int64_t blk = begin + b;
+                        uint32_t acc = scan_block_acc(v, sh, blk, lane);
+                        bool push = false;
+                        uint32_t id = RAIRS_EMPTY_ID;
+                        if (lane < 32) {
+                            id = v.ids[(size_t)blk * 32 + lane];
+                            push = id != RAIRS_EMPTY_ID;
+                        }
+                        my_dco += (unsigned long long)__popcll(__ballot(push));
+                        if (push && b >= misc_from) {
+                            int o = v.other[(size_t)blk * 32 + lane];
+                            if (o >= 0 && o < L && ((sh.bm[o >> 5] >> (o & 31)) & 1u)) push = false;
+                        }
+                        if (push) {
+                            uint64_t key = ((uint64_t)acc << 32) | id;
+                            if (key < sh.tau) {
+                                uint32_t pos = atomicAdd(&sh.cnt, 1u);
+                                sh.buf[pos] = key;
+                            }
+                        }
+                    }
+                }
+                // snapshot the fill level between two barriers so that every thread takes the
+                // same branch (other waves resume pushing right after the second barrier)
+                __syncthreads();
+                const uint32_t fill = sh.cnt;
+                __syncthreads();
+                if (fill > SCAN_CAP - SCAN_ROUND * 32) scan_prune(sh, refine_k);
+            }
+        }
+    }
+    scan_prune(sh, refine_k);
+    const int n = (int)sh.cnt;
+    for (int i = tid; i < refine_k; i += WG) {
+        uint64_t key = sh.buf[i];
+        bool ok = i < n;
+        cand_ids[(size_t)qi * refine_k + i] = ok ? (int64_t)(uint32_t)key : -1;
+        if (cand_score) cand_score[(size_t)qi * refine_k + i] = ok ? (int32_t)(key >> 32) : -1;
+    }
+    if (dco) {
+        if (lane == 0) atomicAdd(&sh.dco, my_dco);
+        __syncthreads();
+        if (tid == 0) dco[qi] = (int64_t)sh.dco;
+    }
+}
+
+int rairs_launch_scan_exact(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
+                            const uint32_t *bitmap, int bmwords, int64_t nq, int nprobe,
+                            int refine_k, int64_t *cand_ids, int32_t *cand_score, int64_t *dco,
+                            hipStream_t s)
+{
+    hipLaunchKernelGGL(scan_exact_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, lut, probe_ids,
+                       bitmap, bmwords, nprobe, refine_k, cand_ids, cand_score, dco);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Refine (Alg. 2 line 7): exact distances of the candidates, K smallest by (distance, id)
+// ---------------------------------------------------------------------------------------------
+
+// One wave per candidate row: lane j sums the dimensions i = j (mod 64) in increasing order,
+// then the 64 partial sums are folded across lanes at strides 32..1.
+__global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__restrict__ q,
+                                                    const int64_t *__restrict__ cand_ids,
+                                                    int refine_k, int k,
+                                                    int64_t *__restrict__ out_ids,
+                                                    float *__restrict__ out_dists)
+{
+    __shared__ uint64_t keys[RAIRS_MAX_REFINE_K];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t qi = blockIdx.x;
+    const float *qq = q + (size_t)qi * v.d;
+    const int n2 = next_pow2(refine_k < 2 ? 2 : refine_k);
+    for (int c = wave; c < n2; c += WG / 64) {
+        int64_t id = c < refine_k ? cand_ids[(size_t)qi * refine_k + c] : -1;
+        uint64_t key = ~0ull;               // distance bits of NaN/inf region, id = empty
+        if (id >= 0 && id < v.ntotal) {
+            float p = 0.0f;
+            if (v.raw_u8) {
+                const uint8_t *row = (const uint8_t *)v.raw + (size_t)id * v.d;
+                for (int i = lane; i < v.d; i += 64) {
+                    float diff = qq[i] - (float)row[i];
+                    float sq = diff * diff;
+                    p = p + sq;
+                }
+            } else {
+                const float *row = (const float *)v.raw + (size_t)id * v.d;
+                for (int i = lane; i < v.d; i += 64) {
+                    float diff = qq[i] - row[i];
+                    float sq = diff * diff;
+                    p = p + sq;
+                }
+            }
+#pragma unroll
+            for (int s = 32; s >= 1; s >>= 1) p = p + __shfl_xor(p, s);
+            key = ((uint64_t)__float_as_uint(p) << 32) | (uint32_t)id;
+        }
+        if (lane == 0) keys[c] = key;
+    }
+    __syncthreads();
+    bitonic_sort_lds(keys, n2);
+    for (int i = tid; i < k; i += WG) {
+        uint64_t key = keys[i];
+        bool ok = key != ~0ull;
+        out_ids[(size_t)qi * k + i] = ok ? (int64_t)(uint32_t)key : -1;
+        out_dists[(size_t)qi * k + i] = ok ? __uint_as_float((uint32_t)(key >> 32)) : __builtin_inff();
+    }
+}
+
+int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,
+                        int refine_k, int k, int64_t *out_ids, float *out_dists, hipStream_t s)
+{
+    hipLaunchKernelGGL(refine_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, q, cand_ids, refine_k,
+                       k, out_ids, out_dists);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}

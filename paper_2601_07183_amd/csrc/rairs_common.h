@@ -1,0 +1,89 @@
+// Internal declarations shared by the translation units of librairs (device format + launchers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rairs.h"
+
+#define RAIRS_EMPTY_ID 0xFFFFFFFFu
+#define RAIRS_MAX_NLIST 65536
+
+// One list of the SEIL directory (Section 5.1): its own blocks are contiguous,
+// [blk_begin, blk_begin + shared_cnt) shared-cell blocks then misc_cnt miscellaneous blocks.
+struct ListEntry {
+    int32_t blk_begin;
+    int32_t shared_cnt;
+    int32_t misc_cnt;
+    int32_t ref_begin;
+    int32_t ref_cnt;
+    int32_t valid_items;   // non-empty slots in the list's own blocks
+};
+
+// Reference entry of list j to the blocks of cell (owner, j) stored in list `owner`.
+struct RefEntry {
+    int32_t owner;
+    int32_t blk_begin;
+    int32_t nblocks;
+};
+
+// Device view handed to kernels by value.
+struct IndexView {
+    int32_t d, M, T, nd, nlist, raw_u8;   // T = M / 2 nibbles per parity, nd = ceil(T / 8) dwords
+    int64_t ntotal, nblocks, nrefs;
+    const float *centroids_t;     // [d][nlist]
+    const float *codebook;        // [M][16][d/M]
+    // codes: per block nd x 64 dwords; lane = parity * 32 + item; dword w of lane (g, item) packs
+    // the codes of subspaces 2t+g, t = 8w .. 8w+7, nibble (t & 7) at bits 4*(t & 7)
+    const uint32_t *codes;
+    const uint32_t *ids;          // [nblocks][32], RAIRS_EMPTY_ID = empty slot
+    const int32_t *other;         // [nblocks][32]
+    const ListEntry *lists;       // [nlist]
+    const RefEntry *refs;         // [nrefs]
+    const void *raw;              // [ntotal][d] fp32 or u8
+};
+
+struct rairs_index {
+    IndexView v;
+    void *dev_alloc[16];
+    int ndev_alloc;
+    int64_t code_bytes, total_bytes;
+    // workspace (grown on demand)
+    void *ws;
+    size_t ws_bytes;
+    int64_t *dco;
+    int64_t dco_cap;
+    // profiling
+    int prof, prof_valid;
+    float stage_ms[RAIRS_NSTAGES];
+    hipEvent_t ev[2 * RAIRS_NSTAGES];
+    int ev_ready;
+};
+
+void rairs_set_error(const char *fmt, ...);
+
+#define RAIRS_HIP(call)                                                              \
+    do {                                                                             \
+        hipError_t e_ = (call);                                                      \
+        if (e_ != hipSuccess) {                                                      \
+            rairs_set_error("%s failed: %s", #call, hipGetErrorString(e_));          \
+            return RAIRS_EHIP;                                                       \
+        }                                                                            \
+    } while (0)
+
+// launchers (kernels.hip)
+int rairs_launch_pack(const uint8_t *d_codes_host_layout, const int64_t *d_ids64, int64_t blk0,
+                      int64_t nblk, int M, int nd, uint32_t *codes, uint32_t *ids,
+                      hipStream_t s);
+int rairs_launch_transpose(const float *d_in, int rows, int cols, float *d_out, hipStream_t s);
+int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,
+                        int32_t *probe_ids, float *probe_dists, hipStream_t s);
+int rairs_launch_bitmap(const IndexView &v, const int32_t *probe_ids, int64_t nq, int nprobe,
+                        uint32_t *bitmap, int bmwords, hipStream_t s);
+int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lut, float *bias_sum,
+                     float *scale, hipStream_t s);
+int rairs_launch_scan_exact(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
+                            const uint32_t *bitmap, int bmwords, int64_t nq, int nprobe,
+                            int refine_k, int64_t *cand_ids, int32_t *cand_score, int64_t *dco,
+                            hipStream_t s);
+int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,
+                        int refine_k, int k, int64_t *out_ids, float *out_dists, hipStream_t s);

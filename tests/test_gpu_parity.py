@@ -1,0 +1,192 @@
+"""HIP path vs CPU oracle, element by element, through the C ABI.  Needs an MI355X."""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2601_07183_amd import datagen, index_build as ib
+
+from conftest import small_queries
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2601_07183_amd import binding as b
+    b.load()
+    assert torch.cuda.is_available(), "gpu tests need a GPU"
+    return b
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _assert_dists(got, want):
+    # bar: 1e-5 relative (the two sides use the same summation order, so this is normally 0)
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    fin = np.isfinite(want)
+    assert (np.isfinite(got) == fin).all()
+    assert (np.abs(got[fin] - want[fin]) <= 1e-5 * np.abs(want[fin])).all()
+    assert (got[~fin] == want[~fin]).all()
+
+
+def _compare_all_stages(binding, hx, q, k, nprobe, refine_k):
+    print(f"case: n={hx.ntotal} d={hx.d} M={hx.M} nlist={hx.nlist} nq={len(q)} k={k} "
+          f"nprobe={nprobe} refine_k={refine_k}", flush=True)
+    ox = oracle.OracleIndex(hx)
+    want = oracle.search(ox, q, k, nprobe, refine_k)
+    ix = binding.Index(hx)
+    try:
+        dq = _dev(q)
+        # coarse quantizer: ids exactly; distances within 1e-4 absolute + 1e-5 relative
+        pid, pdist = ix.coarse(dq, nprobe)
+        torch.cuda.synchronize()
+        assert (pid.cpu().numpy() == want.probes).all()
+        for i in range(0, len(q), max(1, len(q) // 8)):
+            _, od = oracle.coarse(ox, q[i], nprobe)
+            assert (np.abs(pdist[i].cpu().numpy() - od) <= 1e-4 + 1e-5 * np.abs(od)).all()
+        # lookup tables: bit exact
+        lut, bias, scale = ix.lut(dq)
+        torch.cuda.synchronize()
+        assert (lut.cpu().numpy() == want.lut).all()
+        for i in range(0, len(q), max(1, len(q) // 8)):
+            _, _, ob, osc = oracle.lut(ox, q[i])
+            assert bias[i].item() == np.float32(ob) and scale[i].item() == np.float32(osc)
+        # scan on the ORACLE's tables and probe lists: integer work, bit exact
+        cand, score, dco = ix.scan(_dev(want.lut), _dev(want.probes), refine_k)
+        torch.cuda.synchronize()
+        assert (cand.cpu().numpy() == want.cand_ids).all()
+        assert (score.cpu().numpy() == want.cand_acc).all()
+        assert (dco.cpu().numpy() == want.dco).all()
+        # refine on the ORACLE's candidates
+        rid, rd = ix.refine(dq, _dev(want.cand_ids), k)
+        torch.cuda.synchronize()
+        assert (rid.cpu().numpy() == want.ids).all()
+        _assert_dists(rd.cpu().numpy(), want.dists)
+        # whole path
+        ids, dists = ix.search(dq, k, nprobe, refine_k)
+        torch.cuda.synchronize()
+        assert (ids.cpu().numpy() == want.ids).all()
+        _assert_dists(dists.cpu().numpy(), want.dists)
+        assert (ix.dco(len(q)) == want.dco).all()
+    finally:
+        ix.free()
+    return want
+
+
+@pytest.mark.parametrize("nprobe", [1, 4, 16, 64])
+def test_tiny_workload_all_stages(binding, tiny_workload, nprobe):
+    w, base, q, hx = tiny_workload
+    _compare_all_stages(binding, hx, q, w.k, nprobe, w.refine_k)
+
+
+@pytest.mark.parametrize("which", ["strict", "nonstrict", "int"])
+def test_small_indexes(binding, which, small_index, small_index_nonstrict, small_index_int):
+    base, hx = {"strict": small_index, "nonstrict": small_index_nonstrict,
+                "int": small_index_int}[which]
+    q = small_queries(40, 37, hx.d, integer=(which == "int"))     # ragged query count
+    for nprobe, refine_k, k in ((1, 50, 10), (5, 33, 33), (hx.nlist, 100, 1)):
+        _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
+
+
+def test_exact_knn_when_everything_is_probed(binding, small_index_int):
+    base, hx = small_index_int
+    q = small_queries(41, 16, hx.d, integer=True)
+    ix = binding.Index(hx)
+    try:
+        ids, dists = ix.search(_dev(q), 10, hx.nlist, 1024)
+        torch.cuda.synchronize()
+    finally:
+        ix.free()
+    # bigK = 1024 < N here, so compare against the oracle rather than brute force ...
+    want = oracle.search(oracle.OracleIndex(hx), q, 10, hx.nlist, 1024)
+    assert (ids.cpu().numpy() == want.ids).all()
+    # ... and the distances, being integers, against int64 arithmetic
+    d2 = ((q[:, None, :].astype(np.int64) - base[ids.cpu().numpy()].astype(np.int64)) ** 2).sum(-1)
+    assert (dists.cpu().numpy().astype(np.int64) == d2).all()
+
+
+def test_adversarial_layouts(binding):
+    x = datagen.random_vectors(31, 900, 8)
+    q = datagen.random_vectors(32, 30, 8)
+    cents = ib.kmeans(x, 8, 5, 1)
+    cb = ib.train_pq(x, 4, 5, 2)
+    g = np.random.Generator(np.random.PCG64(9))
+    cases = [
+        np.tile(np.array([[2, 5]], dtype=np.int32), (900, 1)),
+        np.sort(g.integers(0, 8, size=(900, 2)), axis=1).astype(np.int32),
+        np.sort(np.array([[i % 8, (i // 8) % 8] for i in range(900)]), axis=1)[:300].astype(np.int32),
+        np.tile(np.array([[3, 3]], dtype=np.int32), (900, 1)),
+        np.tile(np.array([[0, 7]], dtype=np.int32), (5, 1)),           # fewer items than k
+    ]
+    for asg in cases:
+        hx = ib.add_vectors(x[:len(asg)], cents, cb, assign=asg)
+        for nprobe in (1, 3, 8):
+            _compare_all_stages(binding, hx, q, 5, nprobe, 40)
+
+
+def test_identical_codes_tie_on_score(binding):
+    # every vector identical: all scores tie, the order is decided by vector id alone
+    x = np.tile(datagen.random_vectors(50, 1, 8), (600, 1))
+    q = datagen.random_vectors(51, 9, 8)
+    cents = datagen.random_vectors(52, 4, 8)
+    cb = ib.train_pq(datagen.random_vectors(53, 300, 8), 4, 5, 2)
+    g = np.random.Generator(np.random.PCG64(3))
+    asg = np.sort(g.integers(0, 4, size=(600, 2)), axis=1).astype(np.int32)
+    hx = ib.add_vectors(x, cents, cb, assign=asg)
+    _compare_all_stages(binding, hx, q, 10, 4, 64)
+
+
+def test_larger_dimensions_and_u8_raw(binding):
+    # d = 192 (three 64-dimension folds), M = 96 (6 code dwords per lane), uint8 raw vectors
+    g = np.random.Generator(np.random.PCG64(77))
+    base = g.integers(0, 256, size=(4000, 192)).astype(np.uint8)
+    q = g.integers(0, 256, size=(21, 192)).astype(np.float32)
+    hx = ib.build_index(base.astype(np.float32), 24, 96, seed=5, coarse_iters=4, pq_iters=4)
+    hx.raw = base
+    _compare_all_stages(binding, hx, q, 10, 6, 100)
+
+
+def test_batch_permutation_and_split(binding, small_index):
+    base, hx = small_index
+    q = small_queries(42, 50, hx.d)
+    ix = binding.Index(hx)
+    try:
+        ids, dists = ix.search(_dev(q), 10, 4, 40)
+        perm = np.random.Generator(np.random.PCG64(1)).permutation(len(q))
+        ids_p, dists_p = ix.search(_dev(q[perm]), 10, 4, 40)
+        ids_s, _ = ix.search(_dev(q[:7]), 10, 4, 40)
+        torch.cuda.synchronize()
+        assert (ids_p.cpu().numpy() == ids.cpu().numpy()[perm]).all()
+        assert (dists_p.cpu().numpy() == dists.cpu().numpy()[perm]).all()
+        assert (ids_s.cpu().numpy() == ids.cpu().numpy()[:7]).all()
+        # the same call twice gives the same bits
+        ids2, dists2 = ix.search(_dev(q), 10, 4, 40)
+        torch.cuda.synchronize()
+        assert (ids2 == ids).all() and (dists2 == dists).all()
+    finally:
+        ix.free()
+
+
+def test_argument_errors_and_empty_batch(binding, small_index):
+    base, hx = small_index
+    q = _dev(small_queries(43, 4, hx.d))
+    ix = binding.Index(hx)
+    try:
+        empty = torch.empty((0, hx.d), dtype=torch.float32, device="cuda")
+        ids, dists = ix.search(empty, 10, 4, 40)
+        assert ids.shape == (0, 10)
+        for kw in (dict(k=0, nprobe=4, refine_k=40), dict(k=50, nprobe=4, refine_k=40),
+                   dict(k=10, nprobe=0, refine_k=40), dict(k=10, nprobe=hx.nlist + 1, refine_k=40)):
+            with pytest.raises(binding.RairsError) as e:
+                ix.search(q, **kw)
+            assert e.value.code == -1
+        with pytest.raises(binding.RairsError) as e:
+            ix.search(q, 10, 4, binding.MAX_REFINE_K + 1)
+        assert e.value.code == -4
+    finally:
+        ix.free()
+    ix.free()                                               # second free is a no-op
