@@ -434,9 +434,12 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
                                       (float *)(ws + w.probe_dists), s))) return rc;
         if (prof) { RAIRS_HIP(hipEventRecord(h->ev[1], s)); RAIRS_HIP(hipEventRecord(h->ev[2], s)); }
         if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, s))) return rc;
+        if ((rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, (uint32_t *)(ws + w.bitmap),
+                                      w.bmwords, s))) return rc;
         if (prof) { RAIRS_HIP(hipEventRecord(h->ev[3], s)); RAIRS_HIP(hipEventRecord(h->ev[4], s)); }
-        if ((rc = scan_pass(h, lut, probe_ids, (uint32_t *)(ws + w.bitmap), w.bmwords, n, nprobe,
-                            refine_k, cand, nullptr, h->dco + q0, s))) return rc;
+        if ((rc = rairs_launch_scan_exact(v, lut, probe_ids, (uint32_t *)(ws + w.bitmap), w.bmwords,
+                                          n, nprobe, refine_k, cand, nullptr, h->dco + q0, s)))
+            return rc;
         if (prof) { RAIRS_HIP(hipEventRecord(h->ev[5], s)); RAIRS_HIP(hipEventRecord(h->ev[6], s)); }
         if ((rc = rairs_launch_refine(v, q, cand, n, refine_k, k, d_out_ids + (size_t)q0 * k,
                                       d_out_dists + (size_t)q0 * k, s))) return rc;

@@ -78,7 +78,7 @@ class Mixture:
             self.sigma = 0.1
         elif w.kind == "sift":
             zero = g.random(size=(c, d)) < 0.35
-            mag = np.minimum(40.0, g.exponential(8.0, size=(c, d)))
+            mag = np.minimum(50.0, g.exponential(10.0, size=(c, d)))
             self.mean = np.where(zero, 0.0, mag).astype(np.float32)
             self.sigma = 10.0
             self._low_rank(g, 16, 60.0)

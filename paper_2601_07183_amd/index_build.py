@@ -6,13 +6,15 @@ vector chosen by RairAssign (Alg. 3, AIR metric of Theorem 1), and the SEIL list
 SeilInsert (Alg. 4) for a single batch.  The result is a `HostIndex` in a canonical host layout
 that both the CPU oracle and the device upload consume; neither of them is imported here.
 
-Construction is not on the measured path.  It is plain numpy, seeded, and reproducible.
+Construction is not on the measured path.  It is numpy plus torch used as a dense-algebra
+library, seeded, and reproducible on a given machine.
 """
 from __future__ import annotations
 
 from dataclasses import dataclass, field
 
 import numpy as np
+import torch
 
 BLK = 32  # items per block (BLK_SZ in Alg. 4)
 
@@ -59,25 +61,33 @@ class HostIndex:
 
 
 # ----------------------------------------------------------------------------------------------
-# k-means (Lloyd).  Any deterministic choice is valid: the index is an input to the search path.
+# Dense helpers.  torch is used as a BLAS with threads (and the GPU when one is visible, which
+# only makes construction faster; the search path never sees torch).
 # ----------------------------------------------------------------------------------------------
 
-def _nearest(x: np.ndarray, c: np.ndarray, chunk: int = 65536):
+def _device():
+    return torch.device("cuda") if torch.cuda.is_available() else torch.device("cpu")
+
+
+def _nearest(x: np.ndarray, c: np.ndarray, chunk: int = 131072):
     """Index of and squared distance to the nearest row of c for every row of x (GEMM form)."""
-    cn = (c.astype(np.float64) ** 2).sum(1).astype(np.float32)
+    dev = _device()
+    ct = torch.from_numpy(np.ascontiguousarray(c, dtype=np.float32)).to(dev)
+    cn = (ct.double() ** 2).sum(1).float()
     idx = np.empty(x.shape[0], dtype=np.int64)
     dist = np.empty(x.shape[0], dtype=np.float32)
-    ct = np.ascontiguousarray(c.T)
     for lo in range(0, x.shape[0], chunk):
-        xs = x[lo:lo + chunk].astype(np.float32, copy=False)
-        g = xs @ ct
-        g *= -2.0
-        g += cn
-        i = g.argmin(1)
-        idx[lo:lo + chunk] = i
-        dist[lo:lo + chunk] = g[np.arange(g.shape[0]), i] + (xs * xs).sum(1)
+        xs = torch.from_numpy(np.ascontiguousarray(x[lo:lo + chunk], dtype=np.float32)).to(dev)
+        g = cn[None, :] - 2.0 * (xs @ ct.T)
+        dmin, i = g.min(1)
+        idx[lo:lo + chunk] = i.cpu().numpy()
+        dist[lo:lo + chunk] = (dmin + (xs * xs).sum(1)).cpu().numpy()
     return idx, dist
 
+
+# ----------------------------------------------------------------------------------------------
+# k-means (Lloyd).  Any deterministic choice is valid: the index is an input to the search path.
+# ----------------------------------------------------------------------------------------------
 
 def kmeans(x: np.ndarray, k: int, iters: int, seed: int, max_train: int | None = None) -> np.ndarray:
     g = np.random.Generator(np.random.PCG64(seed))
@@ -85,19 +95,17 @@ def kmeans(x: np.ndarray, k: int, iters: int, seed: int, max_train: int | None =
     if max_train is not None and n > max_train:
         x = x[np.sort(g.choice(n, size=max_train, replace=False))]
         n = max_train
-    x = x.astype(np.float32, copy=False)
-    c = x[np.sort(g.choice(n, size=k, replace=False))].astype(np.float32).copy()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    c = x[np.sort(g.choice(n, size=k, replace=False))].copy()
+    xt = torch.from_numpy(x).double()
     for _ in range(iters):
         idx, dist = _nearest(x, c)
         cnt = np.bincount(idx, minlength=k)
-        s = np.zeros((k, x.shape[1]), dtype=np.float64)
-        order = np.argsort(idx, kind="stable")
-        bounds = np.concatenate([[0], np.cumsum(cnt)])
-        xs = x[order].astype(np.float64)
-        nz = np.flatnonzero(cnt)
-        s[nz] = np.add.reduceat(xs, bounds[nz], axis=0)
+        s = torch.zeros((k, x.shape[1]), dtype=torch.float64)
+        s.index_add_(0, torch.from_numpy(idx), xt)
         newc = c.astype(np.float64)
-        newc[nz] = s[nz] / cnt[nz, None]
+        nz = cnt > 0
+        newc[nz] = s.numpy()[nz] / cnt[nz, None]
         # an empty cluster restarts on the point currently worst served
         empty = np.flatnonzero(cnt == 0)
         if empty.size:
@@ -111,6 +119,15 @@ def kmeans(x: np.ndarray, k: int, iters: int, seed: int, max_train: int | None =
 # Product quantisation with 16 codewords per sub-quantizer (Section 2.2)
 # ----------------------------------------------------------------------------------------------
 
+def _sub_dist(xs: "torch.Tensor", cb: "torch.Tensor") -> "torch.Tensor":
+    """xs [n][M][dsub], cb [M][16][dsub] -> squared distances [n][M][16], summed left to right."""
+    dist = None
+    for t in range(xs.shape[2]):
+        diff = xs[:, :, None, t] - cb[None, :, :, t]
+        dist = diff * diff if dist is None else dist + diff * diff
+    return dist
+
+
 def train_pq(x: np.ndarray, M: int, iters: int, seed: int, max_train: int = 32768) -> np.ndarray:
     g = np.random.Generator(np.random.PCG64(seed))
     n, d = x.shape
@@ -118,48 +135,43 @@ def train_pq(x: np.ndarray, M: int, iters: int, seed: int, max_train: int = 3276
     if n > max_train:
         x = x[np.sort(g.choice(n, size=max_train, replace=False))]
         n = max_train
-    xs = np.ascontiguousarray(x.astype(np.float32).reshape(n, M, dsub).transpose(1, 0, 2))
+    dev = _device()
+    xs = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(dev).reshape(n, M, dsub)
     init = np.sort(g.choice(n, size=16, replace=False))
-    cb = xs[:, init, :].astype(np.float64)                                     # [M][16][dsub]
+    cb = xs[torch.from_numpy(init).to(dev)].permute(1, 0, 2).double().contiguous()   # [M][16][dsub]
     # identical sub-vectors would give duplicate codewords; nudge them apart deterministically
-    cb += (np.arange(16, dtype=np.float64)[None, :, None] * 1e-6)
-    mb = max(1, (1 << 24) // (n * 16))                                         # subspaces per batch
+    cb += torch.arange(16, dtype=torch.float64, device=dev)[None, :, None] * 1e-6
+    xs64 = xs.double()
+    moff = (torch.arange(M, device=dev) * 16)[None, :]
     for _ in range(iters):
-        for m0 in range(0, M, mb):
-            xb = xs[m0:m0 + mb]                                                # [b][n][dsub]
-            cbb = cb[m0:m0 + mb].astype(np.float32)
-            dist = np.zeros((xb.shape[0], n, 16), dtype=np.float32)
-            for t in range(dsub):
-                diff = xb[:, :, None, t] - cbb[:, None, :, t]
-                dist += diff * diff
-            a = dist.argmin(-1)                                                # [b][n]
-            key = (a + 16 * np.arange(xb.shape[0])[:, None]).ravel()
-            cnt = np.bincount(key, minlength=16 * xb.shape[0])
-            nz = cnt > 0
-            for t in range(dsub):
-                tot = np.bincount(key, weights=xb[:, :, t].ravel().astype(np.float64),
-                                  minlength=16 * xb.shape[0])
-                col = cb[m0:m0 + mb, :, t].reshape(-1).copy()
-                col[nz] = tot[nz] / cnt[nz]
-                cb[m0:m0 + mb, :, t] = col.reshape(-1, 16)
-    return cb.astype(np.float32)
+        a = _sub_dist(xs, cb.float()).argmin(-1)                              # [n][M]
+        key = (a + moff).reshape(-1)
+        cnt = torch.bincount(key, minlength=16 * M).double()
+        tot = torch.zeros((16 * M, dsub), dtype=torch.float64, device=dev)
+        tot.index_add_(0, key, xs64.reshape(-1, dsub))
+        nz = cnt > 0
+        flat = cb.reshape(16 * M, dsub)
+        flat[nz] = tot[nz] / cnt[nz, None]
+    return cb.float().cpu().numpy()
 
 
-def pq_encode(x: np.ndarray, cb: np.ndarray, chunk: int = 32768) -> np.ndarray:
+def pq_encode(x: np.ndarray, cb: np.ndarray, chunk: int = 65536) -> np.ndarray:
     """PQEncoding: code[m] = nearest codeword of sub-vector m, first minimum on ties.
     Returns the packed form [n][M/2] with subspace 2i in the low nibble of byte i."""
     n, d = x.shape
     M, _, dsub = cb.shape
+    dev = _device()
     out = np.empty((n, M // 2), dtype=np.uint8)
-    cb32 = cb.astype(np.float32)
+    cbt = torch.from_numpy(np.ascontiguousarray(cb, dtype=np.float32)).to(dev)
+    chunk = max(1024, min(chunk, (1 << 27) // (M * 16)))
     for lo in range(0, n, chunk):
-        xs = x[lo:lo + chunk].astype(np.float32).reshape(-1, M, dsub)
-        dist = np.zeros((xs.shape[0], M, 16), dtype=np.float32)
-        for t in range(dsub):
-            diff = xs[:, :, None, t] - cb32[None, :, :, t]
-            dist += diff * diff
-        code = dist.argmin(-1).astype(np.uint8)                                # [chunk][M]
-        out[lo:lo + chunk] = code[:, 0::2] | (code[:, 1::2] << 4)
+        xs = torch.from_numpy(np.ascontiguousarray(x[lo:lo + chunk], dtype=np.float32)).to(dev)
+        dist = _sub_dist(xs.reshape(-1, M, dsub), cbt)
+        # first minimum: argmin of (distance, codeword id)
+        dmin = dist.min(-1, keepdim=True).values
+        ids = torch.arange(16, device=dev)[None, None, :].expand_as(dist)
+        code = torch.where(dist == dmin, ids, 16).min(-1).values.to(torch.uint8)
+        out[lo:lo + chunk] = (code[:, 0::2] | (code[:, 1::2] << 4)).cpu().numpy()
     return out
 
 
@@ -175,44 +187,44 @@ def air_loss(v: np.ndarray, cand_centroids: np.ndarray, lam: float) -> np.ndarra
 
 
 def rair_assign(x: np.ndarray, centroids: np.ndarray, lam: float = 0.5, n_cands: int = 10,
-                strict: bool = True, chunk: int = 16384) -> np.ndarray:
+                strict: bool = True, chunk: int = 32768) -> np.ndarray:
     """Two list ids per vector, returned ordered (smaller id first) as Alg. 3 does.
     With strict=False the secondary list may equal the primary one (the vector is then stored
-    once, cell (i,i)); with strict=True candidate 0 is excluded from the argmin (SRAIR)."""
+    once, cell (i,i)); with strict=True candidate 0 is excluded from the argmin (SRAIR).
+    FindNearestLists shortlists by a GEMM; the candidates are then re-scored directly in float64
+    and ordered by (distance, list id)."""
     n = x.shape[0]
     nlist = centroids.shape[0]
     n_cands = min(n_cands, nlist)
+    dev = _device()
     out = np.empty((n, 2), dtype=np.int32)
-    c32 = centroids.astype(np.float32)
-    cn = (c32.astype(np.float64) ** 2).sum(1).astype(np.float32)
-    ct = np.ascontiguousarray(c32.T)
-    c64 = centroids.astype(np.float64)
+    c32 = torch.from_numpy(np.ascontiguousarray(centroids, dtype=np.float32)).to(dev)
+    cn = (c32.double() ** 2).sum(1).float()
+    c64 = c32.double()
+    start = 1 if strict else 0
     for lo in range(0, n, chunk):
-        xs = x[lo:lo + chunk].astype(np.float32)
-        g = xs @ ct
-        g *= -2.0
-        g += cn
-        if n_cands < nlist:
-            cand = np.argpartition(g, n_cands - 1, axis=1)[:, :n_cands]
-        else:
-            cand = np.tile(np.arange(nlist), (xs.shape[0], 1))
-        # exact distances of the candidates, then order by (distance, list id)
-        r = c64[cand] - xs.astype(np.float64)[:, None, :]
+        xs = torch.from_numpy(np.ascontiguousarray(x[lo:lo + chunk], dtype=np.float32)).to(dev)
+        g = cn[None, :] - 2.0 * (xs @ c32.T)
+        cand = torch.topk(g, n_cands, dim=1, largest=False).indices
+        cand = torch.sort(cand, dim=1).values
+        r = c64[cand] - xs.double()[:, None, :]                # [chunk][ncand][d]
         dist = (r * r).sum(-1)
-        key = np.argsort(cand, axis=1, kind="stable")
-        cand = np.take_along_axis(cand, key, 1)
-        dist = np.take_along_axis(dist, key, 1)
-        key = np.argsort(dist, axis=1, kind="stable")
-        cand = np.take_along_axis(cand, key, 1)
-        loss = air_loss(xs, c64[cand], lam)
-        start = 1 if strict else 0
-        if start >= n_cands:
-            second = cand[:, 0]
-        else:
-            second = cand[np.arange(cand.shape[0]), start + loss[:, start:].argmin(1)]
+        key = torch.sort(dist, dim=1, stable=True).indices     # stable: ties keep the lower id
+        cand = torch.gather(cand, 1, key)
+        r = torch.gather(r, 1, key[:, :, None].expand_as(r))
+        loss = (r * r).sum(-1) + lam * (r * r[:, :1, :]).sum(-1)
         first = cand[:, 0]
-        out[lo:lo + chunk, 0] = np.minimum(first, second)
-        out[lo:lo + chunk, 1] = np.maximum(first, second)
+        if start >= n_cands:
+            second = first
+        else:
+            # first minimum of the loss over candidates start..
+            sub = loss[:, start:]
+            lmin = sub.min(1, keepdim=True).values
+            pos = torch.where(sub == lmin, torch.arange(sub.shape[1], device=dev)[None, :],
+                              sub.shape[1]).min(1).values
+            second = torch.gather(cand, 1, (pos + start)[:, None])[:, 0]
+        out[lo:lo + chunk, 0] = torch.minimum(first, second).cpu().numpy()
+        out[lo:lo + chunk, 1] = torch.maximum(first, second).cpu().numpy()
     return out
 
 
