@@ -121,10 +121,14 @@ def main():
         rec = recall_at_k(out_ids.cpu().numpy(), gt)
         sec, stage = run(nprobe, 3, profile=True)
         dco = ix.dco(nq)
+        st = ix.scan_stats()
         point = dict(nprobe=nprobe, recall_at_10=round(rec, 4), qps=round(3 * nq / sec, 1),
                      ms_per_batch=round(sec / 3 * 1e3, 3), dco_per_query=float(dco.mean()),
                      stage_ms={k: round(v, 4) for k, v in stage.items()},
-                     scan_algorithmic_GBs=round(float(dco.sum()) * (w.M // 2) / (stage["scan"] * 1e-3) / 1e9, 1))
+                     survivors_per_query=round(st["survivors"] / max(1, st["queries"]), 1),
+                     queries_redone_exactly=st["redone"],
+                     scan_stage_algorithmic_GBs=round(float(dco.sum()) * (w.M // 2) / (stage["scan"] * 1e-3) / 1e9, 1),
+                     scan_kernel_algorithmic_GBs=round(float(dco.sum()) * (w.M // 2) / (stage["scan_kernel"] * 1e-3) / 1e9, 1))
         sweep.append(point)
         log("[bench] " + json.dumps(point))
         if chosen is None and rec >= args.target_recall:

@@ -148,10 +148,22 @@ int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t *d_probe_id
 int rairs_refine(rairs_index_t *h, const float *d_queries, const int64_t *d_cand_ids, int64_t nq,
                  int refine_k, int k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream);
 
+/*
+ * Which kernels SeilSearch uses.  RAIRS_SCAN_AUTO (default): the first probed list of every query
+ * by the exact one-workgroup-per-query kernel, the other lists by the list-major MFMA kernel when
+ * it is built for the index's M (16, 48, 64), overflowing queries redone exactly.
+ * RAIRS_SCAN_EXACT: the exact kernel for everything.  Results are identical in both modes.
+ */
+enum { RAIRS_SCAN_AUTO = 0, RAIRS_SCAN_EXACT = 1 };
+int rairs_set_scan_mode(rairs_index_t *h, int mode);
+
 /* ---- measurement --------------------------------------------------------------------------- */
 
+/* SCAN is the whole SeilSearch stage (probe bitmap, first-list scan, grouping, main scan kernel,
+   selection, overflow redo); SCAN_KERNEL is its dominant kernel alone: the list-major MFMA scan,
+   or the exact scan when that one runs instead. */
 enum { RAIRS_STAGE_COARSE = 0, RAIRS_STAGE_LUT = 1, RAIRS_STAGE_SCAN = 2, RAIRS_STAGE_REFINE = 3,
-       RAIRS_NSTAGES = 4 };
+       RAIRS_STAGE_SCAN_KERNEL = 4, RAIRS_NSTAGES = 5 };
 
 /* When enabled, rairs_search brackets each stage with HIP events on the caller's stream. */
 int rairs_set_profiling(rairs_index_t *h, int enabled);
@@ -164,6 +176,13 @@ int rairs_get_stage_ms(rairs_index_t *h, float *ms);
 
 /* Items scored per query by the last rairs_search: device [nq] int64 copied to host `dco`. */
 int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq);
+
+/*
+ * Counters of the last rairs_search / rairs_scan pass (host array of 4): queries redone by the
+ * exact kernel after their survivor buffer overflowed; sum, maximum of survivors per query; number
+ * of queries in the pass.  Synchronises the device.  Zeros when the exact kernel ran alone.
+ */
+int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats);
 
 /* Bytes of device memory held by the index (codes, ids, tags, directory, raw vectors, ...). */
 int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, int64_t *total_bytes);

@@ -16,13 +16,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librairs.so")
 _lib = None
 
-STAGES = ("coarse", "lut", "scan", "refine")
+STAGES = ("coarse", "lut", "scan", "refine", "scan_kernel")
 MAX_REFINE_K = 1024
 MAX_NPROBE = 4096
 
 EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_coarse", "rairs_lut",
-           "rairs_scan", "rairs_refine", "rairs_set_profiling", "rairs_get_stage_ms",
-           "rairs_get_dco", "rairs_index_bytes", "rairs_last_error")
+           "rairs_scan", "rairs_refine", "rairs_set_scan_mode", "rairs_set_profiling", "rairs_get_stage_ms",
+           "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_last_error")
 
 
 class RairsError(RuntimeError):
@@ -184,6 +184,9 @@ class Index:
                                       _dev(dists, torch.float32, "dists"), _stream_ptr(stream)))
         return ids, dists
 
+    def set_scan_mode(self, exact: bool):
+        _check(self._lib.rairs_set_scan_mode(self._h, C.c_int(1 if exact else 0)))
+
     # --- measurement ----------------------------------------------------------------------
     def set_profiling(self, enabled: bool):
         _check(self._lib.rairs_set_profiling(self._h, C.c_int(int(enabled))))
@@ -197,6 +200,12 @@ class Index:
         out = np.empty(nq, dtype=np.int64)
         _check(self._lib.rairs_get_dco(self._h, C.c_void_p(out.ctypes.data), C.c_int64(nq)))
         return out
+
+    def scan_stats(self) -> dict:
+        st = (C.c_int64 * 4)()
+        _check(self._lib.rairs_get_scan_stats(self._h, st))
+        return dict(redone=int(st[0]), survivors=int(st[1]), max_survivors=int(st[2]),
+                    queries=int(st[3]))
 
     def bytes(self):
         a, b = C.c_int64(), C.c_int64()

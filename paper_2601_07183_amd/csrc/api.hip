@@ -187,6 +187,39 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
         hr[(size_t)r].blk_begin = (int32_t)x->ref_block_begin[r];
         hr[(size_t)r].nblocks = x->ref_nblocks[r];
     }
+    // scan segments: the list's own blocks, then each referenced cell, in runs of <= 16 blocks
+    std::vector<SegEntry> hs;
+    for (int l = 0; l < x->nlist; l++) {
+        ListEntry &e2 = hl[(size_t)l];
+        e2.seg_begin = (int32_t)hs.size();
+        const int own = e2.shared_cnt + e2.misc_cnt;
+        for (int b = 0; b < own; b += RAIRS_SEG_BLOCKS) {
+            SegEntry se;
+            se.blk_begin = e2.blk_begin + b;
+            se.nblk = own - b < RAIRS_SEG_BLOCKS ? own - b : RAIRS_SEG_BLOCKS;
+            int mf = e2.shared_cnt - b;
+            se.misc_from = mf < 0 ? 0 : (mf > se.nblk ? se.nblk : mf);
+            se.owner = -1;
+            hs.push_back(se);
+        }
+        for (int r = 0; r < e2.ref_cnt; r++) {
+            const RefEntry &re = hr[(size_t)e2.ref_begin + r];
+            for (int b = 0; b < re.nblocks; b += RAIRS_SEG_BLOCKS) {
+                SegEntry se;
+                se.blk_begin = re.blk_begin + b;
+                se.nblk = re.nblocks - b < RAIRS_SEG_BLOCKS ? re.nblocks - b : RAIRS_SEG_BLOCKS;
+                se.misc_from = se.nblk;
+                se.owner = re.owner;
+                hs.push_back(se);
+            }
+        }
+        e2.seg_cnt = (int32_t)hs.size() - e2.seg_begin;
+    }
+    h->nsegs = (int64_t)hs.size();
+    SegEntry *segs = nullptr;
+    UP_CHECK(dev_alloc(h, (void **)&segs, hs.size() * sizeof(SegEntry)));
+    if (!hs.empty())
+        UP_HIP(hipMemcpyAsync(segs, hs.data(), hs.size() * sizeof(SegEntry), hipMemcpyHostToDevice, s));
     UP_HIP(hipMemcpyAsync(lists, hl.data(), hl.size() * sizeof(ListEntry), hipMemcpyHostToDevice, s));
     if (x->nrefs)
         UP_HIP(hipMemcpyAsync(refs, hr.data(), hr.size() * sizeof(RefEntry), hipMemcpyHostToDevice, s));
@@ -219,7 +252,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_HIP(hipStreamSynchronize(s));
 
     v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other;
-    v.lists = lists; v.refs = refs; v.raw = raw;
+    v.lists = lists; v.refs = refs; v.segs = segs; v.raw = raw;
     for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[i]));
     h->ev_ready = 1;
     *out = h;
@@ -242,8 +275,11 @@ extern "C" int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, in
 
 // ---- workspace ------------------------------------------------------------------------------
 
+#define SURV_CAP 2048
+
 struct WsLayout {
-    size_t dmat, probe_ids, probe_dists, bitmap, lut, cand, total;
+    size_t dmat, probe_ids, probe_dists, bitmap, lut, cand;
+    size_t lcount, loff, lcursor, toff, next_task, qlist, tau, surv_cnt, flags, hist, surv_buf, total;
     int bmwords;
 };
 
@@ -252,12 +288,24 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     WsLayout w;
     w.bmwords = (v.nlist + 31) / 32;
     size_t off = 0;
-    w.dmat = off;        off = align_up(off + (size_t)nq * v.nlist * 4, 256);
-    w.probe_ids = off;   off = align_up(off + (size_t)nq * nprobe * 4, 256);
-    w.probe_dists = off; off = align_up(off + (size_t)nq * nprobe * 4, 256);
-    w.bitmap = off;      off = align_up(off + (size_t)nq * w.bmwords * 4, 256);
-    w.lut = off;         off = align_up(off + (size_t)nq * v.M * 16, 256);
-    w.cand = off;        off = align_up(off + (size_t)nq * refine_k * 8, 256);
+    auto take = [&off](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+    w.dmat = take((size_t)nq * v.nlist * 4);
+    w.probe_ids = take((size_t)nq * nprobe * 4);
+    w.probe_dists = take((size_t)nq * nprobe * 4);
+    w.bitmap = take((size_t)nq * w.bmwords * 4);
+    w.lut = take((size_t)nq * v.M * 16);
+    w.cand = take((size_t)nq * refine_k * 8);
+    w.lcount = take((size_t)v.nlist * 4);
+    w.loff = take((size_t)(v.nlist + 1) * 4);
+    w.lcursor = take((size_t)v.nlist * 4);
+    w.toff = take((size_t)(v.nlist + 1) * 4);
+    w.next_task = take(4);
+    w.qlist = take((size_t)nq * nprobe * 4);
+    w.tau = take((size_t)nq * 4);
+    w.surv_cnt = take((size_t)nq * 4);
+    w.flags = take((size_t)nq * 4);
+    w.hist = take((size_t)nq * RAIRS_HIST_BINS * 4);
+    w.surv_buf = take((size_t)nq * SURV_CAP * 8);
     w.total = off;
     return w;
 }
@@ -352,14 +400,56 @@ extern "C" int rairs_lut(rairs_index_t *h, const float *d_queries, int64_t nq, u
     return rairs_launch_lut(h->v, d_queries, nq, d_lut, d_bias_sum, d_scale, (hipStream_t)hip_stream);
 }
 
-static int scan_pass(rairs_index *h, const uint8_t *lut, const int32_t *probe_ids, uint32_t *bitmap,
-                     int bmwords, int64_t n, int nprobe, int refine_k, int64_t *cand_ids,
-                     int32_t *cand_score, int64_t *dco, hipStream_t s)
+// SeilSearch for one pass of n queries: bitmap, then either the exact kernel alone or
+// first list exact -> list-major MFMA scan of the other lists -> select -> exact redo of overflows.
+// ev (may be null) receives two events bracketing the dominant scan kernel.
+static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, const int32_t *probe_ids,
+                     int64_t n, int nprobe, int refine_k, int64_t *cand_ids, int32_t *cand_score,
+                     int64_t *dco, hipStream_t s, hipEvent_t *ev)
 {
-    int rc = rairs_launch_bitmap(h->v, probe_ids, n, nprobe, bitmap, bmwords, s);
+    const IndexView &v = h->v;
+    char *ws = (char *)h->ws;
+    uint32_t *bitmap = (uint32_t *)(ws + w.bitmap);
+    int rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, bitmap, w.bmwords, (uint32_t *)(ws + w.hist), s);
     if (rc) return rc;
-    return rairs_launch_scan_exact(h->v, lut, probe_ids, bitmap, bmwords, n, nprobe, refine_k,
-                                   cand_ids, cand_score, dco, s);
+    ExactScanArgs ea;
+    memset(&ea, 0, sizeof(ea));
+    ea.lut = lut; ea.probe_ids = probe_ids; ea.bitmap = bitmap; ea.bmwords = w.bmwords;
+    ea.nprobe = nprobe; ea.refine_k = refine_k; ea.dco = dco;
+    const bool mfma = rairs_mfma_supported(v) && nprobe > 1 && !h->force_exact;
+    h->last_pass_n = 0;
+    if (!mfma) {
+        ea.p_scan = nprobe; ea.cand_ids = cand_ids; ea.cand_score = cand_score;
+        if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
+        rc = rairs_launch_scan_exact(v, ea, n, s);
+        if (ev) RAIRS_HIP(hipEventRecord(ev[1], s));
+        return rc;
+    }
+    MfmaScanArgs ma;
+    memset(&ma, 0, sizeof(ma));
+    ma.lut = lut; ma.probe_ids = probe_ids; ma.bitmap = bitmap; ma.bmwords = w.bmwords;
+    ma.nprobe = nprobe; ma.refine_k = refine_k; ma.p_first = 1; ma.nq = n;
+    ma.lcount = (int32_t *)(ws + w.lcount); ma.loff = (int32_t *)(ws + w.loff);
+    ma.lcursor = (int32_t *)(ws + w.lcursor); ma.toff = (int32_t *)(ws + w.toff);
+    ma.next_task = (uint32_t *)(ws + w.next_task); ma.qlist = (int32_t *)(ws + w.qlist);
+    ma.tau = (int32_t *)(ws + w.tau); ma.surv_cnt = (uint32_t *)(ws + w.surv_cnt);
+    ma.surv_buf = (uint64_t *)(ws + w.surv_buf); ma.surv_cap = SURV_CAP;
+    ma.flags = (uint32_t *)(ws + w.flags); ma.cand_ids = cand_ids; ma.cand_score = cand_score;
+    ma.hist = (uint32_t *)(ws + w.hist);
+    h->last_pass_n = n; h->last_flags_off = w.flags; h->last_cnt_off = w.surv_cnt;
+    // first probed list of every query, exactly; leaves queue, bound and the DCO of all probes
+    ea.p_scan = 1; ea.surv_buf = ma.surv_buf; ea.surv_cnt = ma.surv_cnt;
+    ea.tau = (int32_t *)(ws + w.tau); ea.surv_cap = SURV_CAP; ea.hist = ma.hist;
+    if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
+    if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
+    if ((rc = rairs_launch_scan_mfma(v, ma, s))) return rc;
+    if (ev) RAIRS_HIP(hipEventRecord(ev[1], s));
+    if ((rc = rairs_launch_select(ma, s))) return rc;
+    // queries whose survivor buffer overflowed are redone by the exact kernel
+    ExactScanArgs fa = ea;
+    fa.p_scan = nprobe; fa.only_flagged = ma.flags; fa.surv_buf = nullptr; fa.surv_cnt = nullptr;
+    fa.tau = nullptr; fa.hist = nullptr; fa.cand_ids = cand_ids; fa.cand_score = cand_score;
+    return rairs_launch_scan_exact(v, fa, n, s);
 }
 
 extern "C" int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t *d_probe_ids,
@@ -376,14 +466,13 @@ extern "C" int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t 
     WsLayout w = ws_layout(h->v, step, nprobe, refine_k);
     if ((rc = ensure_ws(h, w.total))) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
-    char *ws = (char *)h->ws;
+    if (((uintptr_t)d_lut & 15) != 0) FAIL(RAIRS_EINVAL, "d_lut must be 16-byte aligned");
     for (int64_t q0 = 0; q0 < nq; q0 += step) {
         int64_t n = nq - q0 < step ? nq - q0 : step;
-        rc = scan_pass(h, d_lut + (size_t)q0 * h->v.M * 16, d_probe_ids + (size_t)q0 * nprobe,
-                       (uint32_t *)(ws + w.bitmap), w.bmwords, n, nprobe, refine_k,
-                       d_cand_ids + (size_t)q0 * refine_k,
+        rc = scan_pass(h, w, d_lut + (size_t)q0 * h->v.M * 16, d_probe_ids + (size_t)q0 * nprobe, n,
+                       nprobe, refine_k, d_cand_ids + (size_t)q0 * refine_k,
                        d_cand_score ? d_cand_score + (size_t)q0 * refine_k : nullptr,
-                       d_dco ? d_dco + q0 : nullptr, s);
+                       d_dco ? d_dco + q0 : nullptr, s, nullptr);
         if (rc) return rc;
     }
     return RAIRS_OK;
@@ -434,18 +523,23 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
                                       (float *)(ws + w.probe_dists), s))) return rc;
         if (prof) { RAIRS_HIP(hipEventRecord(h->ev[1], s)); RAIRS_HIP(hipEventRecord(h->ev[2], s)); }
         if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, s))) return rc;
-        if ((rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, (uint32_t *)(ws + w.bitmap),
-                                      w.bmwords, s))) return rc;
         if (prof) { RAIRS_HIP(hipEventRecord(h->ev[3], s)); RAIRS_HIP(hipEventRecord(h->ev[4], s)); }
-        if ((rc = rairs_launch_scan_exact(v, lut, probe_ids, (uint32_t *)(ws + w.bitmap), w.bmwords,
-                                          n, nprobe, refine_k, cand, nullptr, h->dco + q0, s)))
-            return rc;
+        if ((rc = scan_pass(h, w, lut, probe_ids, n, nprobe, refine_k, cand, nullptr, h->dco + q0, s,
+                            prof ? &h->ev[8] : nullptr))) return rc;
         if (prof) { RAIRS_HIP(hipEventRecord(h->ev[5], s)); RAIRS_HIP(hipEventRecord(h->ev[6], s)); }
         if ((rc = rairs_launch_refine(v, q, cand, n, refine_k, k, d_out_ids + (size_t)q0 * k,
                                       d_out_dists + (size_t)q0 * k, s))) return rc;
         if (prof) RAIRS_HIP(hipEventRecord(h->ev[7], s));
     }
     h->prof_valid = prof ? 1 : 0;
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_set_scan_mode(rairs_index_t *h, int mode)
+{
+    if (!h) FAIL(RAIRS_EINVAL, "handle is NULL");
+    if (mode != RAIRS_SCAN_AUTO && mode != RAIRS_SCAN_EXACT) FAIL(RAIRS_EINVAL, "unknown scan mode %d", mode);
+    h->force_exact = mode == RAIRS_SCAN_EXACT;
     return RAIRS_OK;
 }
 
@@ -464,6 +558,24 @@ extern "C" int rairs_get_stage_ms(rairs_index_t *h, float *ms)
     for (int i = 0; i < RAIRS_NSTAGES; i++) {
         RAIRS_HIP(hipEventSynchronize(h->ev[2 * i + 1]));
         RAIRS_HIP(hipEventElapsedTime(&ms[i], h->ev[2 * i], h->ev[2 * i + 1]));
+    }
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats)
+{
+    if (!h || !stats) FAIL(RAIRS_EINVAL, "null argument");
+    stats[0] = stats[1] = stats[2] = 0;
+    stats[3] = h->last_pass_n;
+    if (h->last_pass_n == 0) return RAIRS_OK;
+    std::vector<uint32_t> flags((size_t)h->last_pass_n), cnt((size_t)h->last_pass_n);
+    RAIRS_HIP(hipDeviceSynchronize());
+    RAIRS_HIP(hipMemcpy(flags.data(), (char *)h->ws + h->last_flags_off, flags.size() * 4, hipMemcpyDeviceToHost));
+    RAIRS_HIP(hipMemcpy(cnt.data(), (char *)h->ws + h->last_cnt_off, cnt.size() * 4, hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < flags.size(); i++) {
+        stats[0] += flags[i] != 0;
+        stats[1] += cnt[i];
+        if ((int64_t)cnt[i] > stats[2]) stats[2] = cnt[i];
     }
     return RAIRS_OK;
 }

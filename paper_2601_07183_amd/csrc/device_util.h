@@ -1,0 +1,31 @@
+// Small device helpers shared by the kernel files.
+#pragma once
+#include "rairs_common.h"
+
+#define WG 256
+
+static __device__ __forceinline__ int next_pow2(int x)
+{
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// Ascending bitonic sort of n (power of two) 64-bit keys in LDS by the whole workgroup.
+// Callers synchronise before; the array is consistent for all threads on return.
+static __device__ void bitonic_sort_lds(uint64_t *a, int n)
+{
+    for (int k = 2; k <= n; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = threadIdx.x; i < n; i += WG) {
+                int p = i ^ j;
+                if (p > i) {
+                    bool up = (i & k) == 0;
+                    uint64_t x = a[i], y = a[p];
+                    if ((x > y) == up) { a[i] = y; a[p] = x; }
+                }
+            }
+            __syncthreads();
+        }
+}
+

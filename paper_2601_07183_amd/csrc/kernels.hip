@@ -1,34 +1,7 @@
 // HIP kernels (gfx950, wave64) of the RAIRS query path: coarse quantizer, lookup tables,
 // exact SEIL scan with a bounded top-bigK queue, refinement.  Built with -ffp-contract=off:
 // the fp32 operation order below is part of the result's definition.
-#include "rairs_common.h"
-
-#define WG 256
-
-static __device__ __forceinline__ int next_pow2(int x)
-{
-    int p = 1;
-    while (p < x) p <<= 1;
-    return p;
-}
-
-// Ascending bitonic sort of n (power of two) 64-bit keys in LDS by the whole workgroup.
-// Callers synchronise before; the array is consistent for all threads on return.
-static __device__ void bitonic_sort_lds(uint64_t *a, int n)
-{
-    for (int k = 2; k <= n; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = threadIdx.x; i < n; i += WG) {
-                int p = i ^ j;
-                if (p > i) {
-                    bool up = (i & k) == 0;
-                    uint64_t x = a[i], y = a[p];
-                    if ((x > y) == up) { a[i] = y; a[p] = x; }
-                }
-            }
-            __syncthreads();
-        }
-}
+#include "device_util.h"
 
 // ---------------------------------------------------------------------------------------------
 // upload helpers
@@ -231,10 +204,13 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
 // probe set of each query as a bitmap over list ids (listVisited of Alg. 5, made order-free)
 __global__ __launch_bounds__(WG) void bitmap_kernel(const int32_t *__restrict__ probe_ids,
                                                     int nprobe, int nlist, int bmwords,
-                                                    uint32_t *__restrict__ bitmap)
+                                                    uint32_t *__restrict__ bitmap,
+                                                    uint32_t *__restrict__ hist)
 {
     uint32_t *bm = bitmap + (size_t)blockIdx.x * bmwords;
     for (int i = threadIdx.x; i < bmwords; i += WG) bm[i] = 0;
+    // the query's survivor histogram starts empty as well
+    if (hist && threadIdx.x < RAIRS_HIST_BINS) hist[(size_t)blockIdx.x * RAIRS_HIST_BINS + threadIdx.x] = 0;
     __syncthreads();
     for (int i = threadIdx.x; i < nprobe; i += WG) {
         int32_t l = probe_ids[(size_t)blockIdx.x * nprobe + i];
@@ -243,10 +219,10 @@ __global__ __launch_bounds__(WG) void bitmap_kernel(const int32_t *__restrict__ 
 }
 
 int rairs_launch_bitmap(const IndexView &v, const int32_t *probe_ids, int64_t nq, int nprobe,
-                        uint32_t *bitmap, int bmwords, hipStream_t s)
+                        uint32_t *bitmap, int bmwords, uint32_t *hist, hipStream_t s)
 {
     hipLaunchKernelGGL(bitmap_kernel, dim3((unsigned)nq), dim3(WG), 0, s, probe_ids, nprobe,
-                       v.nlist, bmwords, bitmap);
+                       v.nlist, bmwords, bitmap, hist);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
@@ -319,164 +295,6 @@ int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lu
 {
     hipLaunchKernelGGL(lut_kernel, dim3((unsigned)nq), dim3(WG), 0, s, q, v.codebook, v.d, v.M,
                        lut, bias_sum, scale);
-    RAIRS_HIP(hipGetLastError());
-    return RAIRS_OK;
-}
-
-// ---------------------------------------------------------------------------------------------
-// exact SEIL scan, one workgroup per query (SeilSearch, Alg. 5, with rqueue)
-// ---------------------------------------------------------------------------------------------
-//
-// listVisited is replaced by the order-free equivalent over the query's probe bitmap P:
-//   reference entry (owner i) of list j is scanned  iff  i not in P;
-//   own shared blocks are always scanned;
-//   a miscellaneous item of list L tagged with other list o is dropped  iff  o in P and o < L.
-// (Alg. 5 visits lists in ascending id, owners have the smaller id, hence "visited" == "in P and
-// smaller".)  Every (query, list) pair is then independent of all others.
-//
-// rqueue: survivors with key (score << 32 | id) below the current bound are appended to an LDS
-// buffer; when it fills, the buffer is sorted, cut to bigK entries and the bound tightened.
-
-#define SCAN_CAP 2048
-#define SCAN_ROUND 16     // blocks per workgroup between buffer checks (4 per wave)
-
-struct ScanShared {
-    uint64_t buf[SCAN_CAP];
-    uint32_t bm[RAIRS_MAX_NLIST / 32];
-    uint8_t lut[RAIRS_MAX_M * 16];
-    uint64_t tau;
-    uint32_t cnt;
-    unsigned long long dco;
-};
-
-static __device__ __forceinline__ void scan_prune(ScanShared &sh, int refine_k)
-{
-    // all threads arrive here together
-    __syncthreads();
-    int n = (int)sh.cnt;
-    int n2 = next_pow2(n < 2 ? 2 : n);
-    for (int i = n + threadIdx.x; i < n2; i += WG) sh.buf[i] = ~0ull;
-    __syncthreads();
-    bitonic_sort_lds(sh.buf, n2);
-    if (threadIdx.x == 0) {
-        int keep = n < refine_k ? n : refine_k;
-        sh.cnt = (uint32_t)keep;
-        sh.tau = keep == refine_k ? sh.buf[refine_k - 1] : ~0ull;
-    }
-    __syncthreads();
-}
-
-static __device__ __forceinline__ uint32_t scan_block_acc(const IndexView &v, const ScanShared &sh,
-                                                          int64_t blk, int lane)
-{
-    const int g = lane >> 5;
-    const uint32_t *cp = v.codes + (size_t)blk * v.nd * 64 + lane;
-    uint32_t part = 0;
-    for (int w = 0; w < v.nd; w++) {
-        uint32_t c = cp[(size_t)w * 64];
-        const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
-        for (int n = 0; n < tmax; n++) {
-            int m = 2 * (8 * w + n) + g;
-            part += sh.lut[m * 16 + ((c >> (4 * n)) & 15u)];
-        }
-    }
-    return part + (uint32_t)__shfl_xor((int)part, 32);
-}
-
-__global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v,
-                                                        const uint8_t *__restrict__ lut,
-                                                        const int32_t *__restrict__ probe_ids,
-                                                        const uint32_t *__restrict__ bitmap,
-                                                        int bmwords, int nprobe, int refine_k,
-                                                        int64_t *__restrict__ cand_ids,
-                                                        int32_t *__restrict__ cand_score,
-                                                        int64_t *__restrict__ dco)
-{
-    __shared__ ScanShared sh;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t qi = blockIdx.x;
-    for (int i = tid; i < v.M * 16; i += WG) sh.lut[i] = lut[(size_t)qi * v.M * 16 + i];
-    for (int i = tid; i < bmwords; i += WG) sh.bm[i] = bitmap[(size_t)qi * bmwords + i];
-    if (tid == 0) { sh.tau = ~0ull; sh.cnt = 0; sh.dco = 0; }
-    __syncthreads();
-
-    unsigned long long my_dco = 0;
-    for (int p = 0; p < nprobe; p++) {
-        const int L = probe_ids[(size_t)qi * nprobe + p];
-        if (L < 0 || L >= v.nlist) continue;              // caller-supplied ids: never index with them unchecked
-        const ListEntry le = v.lists[L];
-        // segment -1: the list's own blocks; segments 0..ref_cnt-1: its reference entries
-        for (int seg = -1; seg < le.ref_cnt; seg++) {
-            int64_t begin;
-            int cnt, misc_from;
-            if (seg < 0) {
-                begin = le.blk_begin;
-                cnt = le.shared_cnt + le.misc_cnt;
-                misc_from = le.shared_cnt;
-            } else {
-                const RefEntry re = v.refs[le.ref_begin + seg];
-                if ((sh.bm[re.owner >> 5] >> (re.owner & 31)) & 1u) continue;   // scanned via owner
-                begin = re.blk_begin;
-                cnt = re.nblocks;
-                misc_from = cnt;
-            }
-            for (int base = 0; base < cnt; base += SCAN_ROUND) {
-                for (int j = 0; j < SCAN_ROUND / 4; j++) {
-                    int b = base + j * 4 + wave;
-                    if (b < cnt) {
-                        int64_t blk = begin + b;
-                        uint32_t acc = scan_block_acc(v, sh, blk, lane);
-                        bool push = false;
-                        uint32_t id = RAIRS_EMPTY_ID;
-                        if (lane < 32) {
-                            id = v.ids[(size_t)blk * 32 + lane];
-                            push = id != RAIRS_EMPTY_ID;
-                        }
-                        my_dco += (unsigned long long)__popcll(__ballot(push));
-                        if (push && b >= misc_from) {
-                            int o = v.other[(size_t)blk * 32 + lane];
-                            if (o >= 0 && o < L && ((sh.bm[o >> 5] >> (o & 31)) & 1u)) push = false;
-                        }
-                        if (push) {
-                            uint64_t key = ((uint64_t)acc << 32) | id;
-                            if (key < sh.tau) {
-                                uint32_t pos = atomicAdd(&sh.cnt, 1u);
-                                sh.buf[pos] = key;
-                            }
-                        }
-                    }
-                }
-                // snapshot the fill level between two barriers so that every thread takes the
-                // same branch (other waves resume pushing right after the second barrier)
-                __syncthreads();
-                const uint32_t fill = sh.cnt;
-                __syncthreads();
-                if (fill > SCAN_CAP - SCAN_ROUND * 32) scan_prune(sh, refine_k);
-            }
-        }
-    }
-    scan_prune(sh, refine_k);
-    const int n = (int)sh.cnt;
-    for (int i = tid; i < refine_k; i += WG) {
-        uint64_t key = sh.buf[i];
-        bool ok = i < n;
-        cand_ids[(size_t)qi * refine_k + i] = ok ? (int64_t)(uint32_t)key : -1;
-        if (cand_score) cand_score[(size_t)qi * refine_k + i] = ok ? (int32_t)(key >> 32) : -1;
-    }
-    if (dco) {
-        if (lane == 0) atomicAdd(&sh.dco, my_dco);
-        __syncthreads();
-        if (tid == 0) dco[qi] = (int64_t)sh.dco;
-    }
-}
-
-int rairs_launch_scan_exact(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
-                            const uint32_t *bitmap, int bmwords, int64_t nq, int nprobe,
-                            int refine_k, int64_t *cand_ids, int32_t *cand_score, int64_t *dco,
-                            hipStream_t s)
-{
-    hipLaunchKernelGGL(scan_exact_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, lut, probe_ids,
-                       bitmap, bmwords, nprobe, refine_k, cand_ids, cand_score, dco);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }

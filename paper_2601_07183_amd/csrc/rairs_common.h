@@ -7,6 +7,7 @@
 
 #define RAIRS_EMPTY_ID 0xFFFFFFFFu
 #define RAIRS_MAX_NLIST 65536
+#define RAIRS_HIST_BINS 64
 
 // One list of the SEIL directory (Section 5.1): its own blocks are contiguous,
 // [blk_begin, blk_begin + shared_cnt) shared-cell blocks then misc_cnt miscellaneous blocks.
@@ -17,6 +18,17 @@ struct ListEntry {
     int32_t ref_begin;
     int32_t ref_cnt;
     int32_t valid_items;   // non-empty slots in the list's own blocks
+    int32_t seg_begin;     // scan segments of the list (own blocks in chunks, then references)
+    int32_t seg_cnt;
+};
+
+// A run of at most RAIRS_SEG_BLOCKS consecutive blocks that one wave scores for one query tile.
+#define RAIRS_SEG_BLOCKS 16
+struct SegEntry {
+    int32_t blk_begin;
+    int32_t nblk;
+    int32_t misc_from;     // blocks [misc_from, nblk) of the run are miscellaneous blocks
+    int32_t owner;         // -1: the list's own blocks; else the owning list of a referenced cell
 };
 
 // Reference entry of list j to the blocks of cell (owner, j) stored in list `owner`.
@@ -39,12 +51,14 @@ struct IndexView {
     const int32_t *other;         // [nblocks][32]
     const ListEntry *lists;       // [nlist]
     const RefEntry *refs;         // [nrefs]
+    const SegEntry *segs;         // [nsegs]
     const void *raw;              // [ntotal][d] fp32 or u8
 };
 
 struct rairs_index {
     IndexView v;
     void *dev_alloc[16];
+    int64_t nsegs;
     int ndev_alloc;
     int64_t code_bytes, total_bytes;
     // workspace (grown on demand)
@@ -53,6 +67,9 @@ struct rairs_index {
     int64_t *dco;
     int64_t dco_cap;
     // profiling
+    int force_exact;
+    int64_t last_pass_n;          // queries of the last MFMA pass (0: none)
+    size_t last_flags_off, last_cnt_off;
     int prof, prof_valid;
     float stage_ms[RAIRS_NSTAGES];
     hipEvent_t ev[2 * RAIRS_NSTAGES];
@@ -78,12 +95,54 @@ int rairs_launch_transpose(const float *d_in, int rows, int cols, float *d_out, 
 int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,
                         int32_t *probe_ids, float *probe_dists, hipStream_t s);
 int rairs_launch_bitmap(const IndexView &v, const int32_t *probe_ids, int64_t nq, int nprobe,
-                        uint32_t *bitmap, int bmwords, hipStream_t s);
+                        uint32_t *bitmap, int bmwords, uint32_t *hist, hipStream_t s);
 int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lut, float *bias_sum,
                      float *scale, hipStream_t s);
-int rairs_launch_scan_exact(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
-                            const uint32_t *bitmap, int bmwords, int64_t nq, int nprobe,
-                            int refine_k, int64_t *cand_ids, int32_t *cand_score, int64_t *dco,
-                            hipStream_t s);
+// arguments of the exact scan kernel (scan_exact.hip)
+struct ExactScanArgs {
+    const uint8_t *lut;           // [nq][M][16]
+    const int32_t *probe_ids;     // [nq][nprobe]
+    const uint32_t *bitmap;       // [nq][bmwords]
+    int bmwords, nprobe, refine_k;
+    int p_scan;                   // scan probes [0, p_scan); the rest only enter the DCO count
+    const uint32_t *only_flagged; // if set, queries with a zero flag are skipped
+    int64_t *cand_ids;            // [nq][refine_k]  (when surv_buf is null)
+    int32_t *cand_score;          // [nq][refine_k], may be null
+    uint64_t *surv_buf;           // [nq][surv_cap]: receive the queue instead of cand_ids
+    uint32_t *surv_cnt;           // [nq]
+    int32_t *tau;                 // [nq] largest score that can still matter
+    uint32_t *hist;               // [nq][RAIRS_HIST_BINS] survivor counts by score bin (see scan_mfma.hip)
+    int surv_cap;
+    int64_t *dco;                 // [nq], may be null
+};
+int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s);
+
+// list-major MFMA scan (scan_mfma.hip)
+struct MfmaScanArgs {
+    const uint8_t *lut;
+    const int32_t *probe_ids;
+    const uint32_t *bitmap;
+    int bmwords, nprobe, refine_k;
+    int p_first;                  // probes [p_first, nprobe) are scanned here
+    int64_t nq;
+    // workspace
+    int32_t *lcount;              // [nlist]   queries probing each list
+    int32_t *loff;                // [nlist+1] exclusive prefix of lcount
+    int32_t *lcursor;             // [nlist]
+    int32_t *qlist;               // [nq * nprobe] query ids grouped by list
+    int32_t *toff;                // [nlist+1] exclusive prefix of tasks per list
+    uint32_t *next_task;          // [1]
+    const int32_t *tau;           // [nq] bound from the first list (0xFFFF: none)
+    uint32_t *hist;               // [nq][RAIRS_HIST_BINS]
+    uint32_t *surv_cnt;           // [nq]
+    uint64_t *surv_buf;           // [nq][surv_cap]
+    int surv_cap;
+    uint32_t *flags;              // [nq] set when the survivor buffer overflowed
+    int64_t *cand_ids;            // [nq][refine_k]
+    int32_t *cand_score;          // may be null
+};
+bool rairs_mfma_supported(const IndexView &v);
+int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
+int rairs_launch_select(const MfmaScanArgs &a, hipStream_t s);
 int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,
                         int refine_k, int k, int64_t *out_ids, float *out_dists, hipStream_t s);

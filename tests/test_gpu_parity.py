@@ -55,23 +55,25 @@ def _compare_all_stages(binding, hx, q, k, nprobe, refine_k):
         for i in range(0, len(q), max(1, len(q) // 8)):
             _, _, ob, osc = oracle.lut(ox, q[i])
             assert bias[i].item() == np.float32(ob) and scale[i].item() == np.float32(osc)
-        # scan on the ORACLE's tables and probe lists: integer work, bit exact
-        cand, score, dco = ix.scan(_dev(want.lut), _dev(want.probes), refine_k)
-        torch.cuda.synchronize()
-        assert (cand.cpu().numpy() == want.cand_ids).all()
-        assert (score.cpu().numpy() == want.cand_acc).all()
-        assert (dco.cpu().numpy() == want.dco).all()
+        for exact in (False, True):                  # MFMA list-major path, then exact-only path
+            ix.set_scan_mode(exact)
+            # scan on the ORACLE's tables and probe lists: integer work, bit exact
+            cand, score, dco = ix.scan(_dev(want.lut), _dev(want.probes), refine_k)
+            torch.cuda.synchronize()
+            assert (cand.cpu().numpy() == want.cand_ids).all(), f"exact={exact}"
+            assert (score.cpu().numpy() == want.cand_acc).all(), f"exact={exact}"
+            assert (dco.cpu().numpy() == want.dco).all(), f"exact={exact}"
+            # whole path
+            ids, dists = ix.search(dq, k, nprobe, refine_k)
+            torch.cuda.synchronize()
+            assert (ids.cpu().numpy() == want.ids).all(), f"exact={exact}"
+            _assert_dists(dists.cpu().numpy(), want.dists)
+            assert (ix.dco(len(q)) == want.dco).all()
         # refine on the ORACLE's candidates
         rid, rd = ix.refine(dq, _dev(want.cand_ids), k)
         torch.cuda.synchronize()
         assert (rid.cpu().numpy() == want.ids).all()
         _assert_dists(rd.cpu().numpy(), want.dists)
-        # whole path
-        ids, dists = ix.search(dq, k, nprobe, refine_k)
-        torch.cuda.synchronize()
-        assert (ids.cpu().numpy() == want.ids).all()
-        _assert_dists(dists.cpu().numpy(), want.dists)
-        assert (ix.dco(len(q)) == want.dco).all()
     finally:
         ix.free()
     return want
@@ -89,6 +91,22 @@ def test_small_indexes(binding, which, small_index, small_index_nonstrict, small
                 "int": small_index_int}[which]
     q = small_queries(40, 37, hx.d, integer=(which == "int"))     # ragged query count
     for nprobe, refine_k, k in ((1, 50, 10), (5, 33, 33), (hx.nlist, 100, 1)):
+        _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
+
+
+@pytest.mark.parametrize("d,M", [(128, 64), (96, 48), (32, 16)])
+def test_table_shapes_of_the_mfma_scan(binding, d, M):
+    # the three table shapes the matrix-core scan is built for, on integer-valued data so that
+    # refine ties are real; nprobe = nlist with bigK = 1024 overflows the survivor buffers
+    # (first list shorter than bigK => no bound) and exercises the exact redo
+    g = np.random.Generator(np.random.PCG64(d))
+    centers = g.integers(30, 220, size=(12, d))
+    base = np.clip(centers[g.integers(0, 12, size=6000)] + g.normal(0, 25, size=(6000, d)), 0, 255)
+    base = np.rint(base).astype(np.float32)
+    q = np.rint(np.clip(centers[g.integers(0, 12, size=45)] + g.normal(0, 25, size=(45, d)), 0, 255))
+    q = q.astype(np.float32)
+    hx = ib.build_index(base, 20, M, seed=3, coarse_iters=5, pq_iters=5)
+    for nprobe, refine_k, k in ((2, 100, 10), (7, 100, 10), (20, 1024, 10), (20, 40, 40)):
         _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
 
 
