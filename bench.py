@@ -65,7 +65,20 @@ def main():
     ap.add_argument("--target-recall", type=float, default=0.9)
     ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0 = auto)")
     ap.add_argument("--sweep-out", default="")
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="only run a device-to-device copy of this many bytes three times (to "
+                         "calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        n = args.copy_calibration // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": n * 4, "copy_bytes_written": n * 4, "repeats": 3}))
+        return
     if args.gpus != 1:
         log("bench.py measures one GPU; this build has no multi-GPU path (see DESIGN.md). "
             "Run with --gpus 1.")
