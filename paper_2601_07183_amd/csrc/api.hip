@@ -91,6 +91,18 @@ static int validate(const rairs_host_index_t *x)
         if (n < 1 || b < ob || b + n > ob + oc)
             FAIL(RAIRS_EINVAL, "reference %lld does not point into its owner's shared blocks", (long long)r);
     }
+    // empty slots may only form the tail of a list's last block (the kernels rely on it)
+    for (int l = 0; l < x->nlist; l++) {
+        const int64_t b0 = x->list_shared_begin[l];
+        const int64_t b1 = b0 + x->list_shared_cnt[l] + x->list_misc_cnt[l];
+        bool seen_empty = false;
+        for (int64_t i = b0 * 32; i < b1 * 32; i++) {
+            const bool empty = x->ids[i] < 0;
+            if ((empty && i < (b1 - 1) * 32) || (!empty && seen_empty))
+                FAIL(RAIRS_EINVAL, "list %d: empty slots must be the tail of its last block", l);
+            seen_empty |= empty;
+        }
+    }
     const int64_t nslots = x->nblocks * 32;
     for (int64_t i = 0; i < nslots; i++) {
         int64_t id = x->ids[i];
@@ -200,6 +212,8 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
             int mf = e2.shared_cnt - b;
             se.misc_from = mf < 0 ? 0 : (mf > se.nblk ? se.nblk : mf);
             se.owner = -1;
+            // only the list's very last block may have empty slots, and they are filled from 0
+            se.tail_valid = b + se.nblk == own ? e2.valid_items - 32 * (own - 1) : 32;
             hs.push_back(se);
         }
         for (int r = 0; r < e2.ref_cnt; r++) {
@@ -210,6 +224,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
                 se.nblk = re.nblocks - b < RAIRS_SEG_BLOCKS ? re.nblocks - b : RAIRS_SEG_BLOCKS;
                 se.misc_from = se.nblk;
                 se.owner = re.owner;
+                se.tail_valid = 32;
                 hs.push_back(se);
             }
         }
@@ -275,11 +290,14 @@ extern "C" int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, in
 
 // ---- workspace ------------------------------------------------------------------------------
 
-#define SURV_CAP 2048
+#define SURV_CAP 4096
+#define RAIRS_SAMPLE_BLOCKS 16
+#define RAIRS_LOG_PER_QUERY 3072
 
 struct WsLayout {
     size_t dmat, probe_ids, probe_dists, bitmap, lut, cand;
-    size_t lcount, loff, lcursor, toff, next_task, qlist, tau, surv_cnt, flags, hist, surv_buf, total;
+    size_t lcount, loff, lcursor, toff, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, prof, total;
+    int log_chunks;
     int bmwords;
 };
 
@@ -302,10 +320,16 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     w.next_task = take(4);
     w.qlist = take((size_t)nq * nprobe * 4);
     w.tau = take((size_t)nq * 4);
+    w.bound = take((size_t)nq * 4);
     w.surv_cnt = take((size_t)nq * 4);
     w.flags = take((size_t)nq * 4);
     w.hist = take((size_t)nq * RAIRS_HIST_BINS * 4);
     w.surv_buf = take((size_t)nq * SURV_CAP * 8);
+    w.log_chunks = (int)((nq * RAIRS_LOG_PER_QUERY + 255) / 256) + 8192;   // + two per wave
+    w.log = take((size_t)w.log_chunks * 256 * 16);
+    w.chunk_fill = take((size_t)w.log_chunks * 4);
+    w.log_misc = take(64);
+    w.prof = take(2048 * 12 * 8);
     w.total = off;
     return w;
 }
@@ -416,7 +440,7 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     memset(&ea, 0, sizeof(ea));
     ea.lut = lut; ea.probe_ids = probe_ids; ea.bitmap = bitmap; ea.bmwords = w.bmwords;
     ea.nprobe = nprobe; ea.refine_k = refine_k; ea.dco = dco;
-    const bool mfma = rairs_mfma_supported(v) && nprobe > 1 && !h->force_exact;
+    const bool mfma = rairs_mfma_supported(v) && !h->force_exact;
     h->last_pass_n = 0;
     if (!mfma) {
         ea.p_scan = nprobe; ea.cand_ids = cand_ids; ea.cand_score = cand_score;
@@ -437,18 +461,31 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     ma.flags = (uint32_t *)(ws + w.flags); ma.cand_ids = cand_ids; ma.cand_score = cand_score;
     ma.hist = (uint32_t *)(ws + w.hist);
     h->last_pass_n = n; h->last_flags_off = w.flags; h->last_cnt_off = w.surv_cnt;
-    // first probed list of every query, exactly; leaves queue, bound and the DCO of all probes
-    ea.p_scan = 1; ea.surv_buf = ma.surv_buf; ea.surv_cnt = ma.surv_cnt;
-    ea.tau = (int32_t *)(ws + w.tau); ea.surv_cap = SURV_CAP; ea.hist = ma.hist;
+    ma.log = (uint4 *)(ws + w.log); ma.chunk_fill = (uint32_t *)(ws + w.chunk_fill);
+    ma.log_cursor = (uint32_t *)(ws + w.log_misc); ma.log_overflow = ma.log_cursor + 1;
+    ma.log_chunks = w.log_chunks;
+#ifdef RAIRS_PROFILE_CYCLES
+    ma.prof = (long long *)(ws + w.prof);
+    h->last_prof_off = w.prof;
+#endif
+    {
+        // tasks per draw: enough draws to keep all 2048 waves busy, at most 8
+        const int64_t est = (n * (int64_t)nprobe / 32 + v.nlist) * 4;
+        ma.grab = est / (2048 * 4) < 1 ? 1 : (est / (2048 * 4) > 8 ? 8 : (int)(est / (2048 * 4)));
+    }
+    // bound of every query from a sample (the head of its first list); also the DCO of all probes
+    ma.p_first = 0;
+    ea.sample_blocks = RAIRS_SAMPLE_BLOCKS; ea.tau = (int32_t *)(ws + w.tau);
+    ea.bound = (int32_t *)(ws + w.bound); ma.bound = ea.bound;
     if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
     if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
     if ((rc = rairs_launch_scan_mfma(v, ma, s))) return rc;
     if (ev) RAIRS_HIP(hipEventRecord(ev[1], s));
-    if ((rc = rairs_launch_select(ma, s))) return rc;
+    if ((rc = rairs_launch_select(v, ma, s))) return rc;
     // queries whose survivor buffer overflowed are redone by the exact kernel
     ExactScanArgs fa = ea;
-    fa.p_scan = nprobe; fa.only_flagged = ma.flags; fa.surv_buf = nullptr; fa.surv_cnt = nullptr;
-    fa.tau = nullptr; fa.hist = nullptr; fa.cand_ids = cand_ids; fa.cand_score = cand_score;
+    fa.p_scan = nprobe; fa.sample_blocks = 0; fa.only_flagged = ma.flags; fa.surv_buf = nullptr; fa.surv_cnt = nullptr;
+    fa.tau = nullptr; fa.bound = nullptr; fa.hist = nullptr; fa.cand_ids = cand_ids; fa.cand_score = cand_score;
     return rairs_launch_scan_exact(v, fa, n, s);
 }
 
@@ -579,6 +616,16 @@ extern "C" int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats)
     }
     return RAIRS_OK;
 }
+
+#ifdef RAIRS_PROFILE_CYCLES
+// profiling builds only: per-wave cycle counters of the last MFMA scan, 2048 x 12 int64
+extern "C" int rairs_debug_cycles(rairs_index_t *h, long long *out)
+{
+    RAIRS_HIP(hipDeviceSynchronize());
+    RAIRS_HIP(hipMemcpy(out, (char *)h->ws + h->last_prof_off, 2048 * 12 * 8, hipMemcpyDeviceToHost));
+    return RAIRS_OK;
+}
+#endif
 
 extern "C" int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq)
 {

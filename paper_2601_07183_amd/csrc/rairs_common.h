@@ -29,6 +29,7 @@ struct SegEntry {
     int32_t nblk;
     int32_t misc_from;     // blocks [misc_from, nblk) of the run are miscellaneous blocks
     int32_t owner;         // -1: the list's own blocks; else the owning list of a referenced cell
+    int32_t tail_valid;    // item slots in use in the run's last block (32 unless it ends the list)
 };
 
 // Reference entry of list j to the blocks of cell (owner, j) stored in list `owner`.
@@ -69,7 +70,7 @@ struct rairs_index {
     // profiling
     int force_exact;
     int64_t last_pass_n;          // queries of the last MFMA pass (0: none)
-    size_t last_flags_off, last_cnt_off;
+    size_t last_flags_off, last_cnt_off, last_prof_off;
     int prof, prof_valid;
     float stage_ms[RAIRS_NSTAGES];
     hipEvent_t ev[2 * RAIRS_NSTAGES];
@@ -105,12 +106,15 @@ struct ExactScanArgs {
     const uint32_t *bitmap;       // [nq][bmwords]
     int bmwords, nprobe, refine_k;
     int p_scan;                   // scan probes [0, p_scan); the rest only enter the DCO count
+    int sample_blocks;            // > 0: bound-only mode -- score just the first sample_blocks own
+                                  // blocks of probe 0 and write tau (no candidates, no survivors)
     const uint32_t *only_flagged; // if set, queries with a zero flag are skipped
     int64_t *cand_ids;            // [nq][refine_k]  (when surv_buf is null)
     int32_t *cand_score;          // [nq][refine_k], may be null
     uint64_t *surv_buf;           // [nq][surv_cap]: receive the queue instead of cand_ids
     uint32_t *surv_cnt;           // [nq]
     int32_t *tau;                 // [nq] largest score that can still matter
+    int32_t *bound;               // [nq] receives the same value in sample mode (may be null)
     uint32_t *hist;               // [nq][RAIRS_HIST_BINS] survivor counts by score bin (see scan_mfma.hip)
     int surv_cap;
     int64_t *dco;                 // [nq], may be null
@@ -132,17 +136,25 @@ struct MfmaScanArgs {
     int32_t *qlist;               // [nq * nprobe] query ids grouped by list
     int32_t *toff;                // [nlist+1] exclusive prefix of tasks per list
     uint32_t *next_task;          // [1]
-    const int32_t *tau;           // [nq] bound from the first list (0xFFFF: none)
+    const int32_t *tau;           // [nq] bound from the sample (0xFFFF: none); fixes the histogram range
+    int32_t *bound;               // [nq] current bound, starts at tau, only decreases
     uint32_t *hist;               // [nq][RAIRS_HIST_BINS]
     uint32_t *surv_cnt;           // [nq]
     uint64_t *surv_buf;           // [nq][surv_cap]
     int surv_cap;
     uint32_t *flags;              // [nq] set when the survivor buffer overflowed
+    uint4 *log;                   // [log_chunks][256] survivor log {slot, score<<16|list, query, 0}
+    uint32_t *chunk_fill;         // [log_chunks] entries written to each chunk
+    uint32_t *log_cursor;         // [1] chunks handed out
+    uint32_t *log_overflow;       // [1] set if the log ran out of chunks
+    int log_chunks;
+    int grab;                     // consecutive tasks a wave draws at once
+    long long *prof;              // cycle counters per wave (profiling builds only), may be null
     int64_t *cand_ids;            // [nq][refine_k]
     int32_t *cand_score;          // may be null
 };
 bool rairs_mfma_supported(const IndexView &v);
 int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
-int rairs_launch_select(const MfmaScanArgs &a, hipStream_t s);
+int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
 int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,
                         int refine_k, int k, int64_t *out_ids, float *out_dists, hipStream_t s);

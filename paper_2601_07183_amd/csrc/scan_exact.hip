@@ -75,7 +75,7 @@ __global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanAr
     // items that the probes beyond p_scan will score (they are scanned by another kernel):
     // every valid slot of the list's own blocks plus 32 per block of each unskipped reference
     unsigned long long my_dco = 0;
-    for (int p = a.p_scan + tid; p < nprobe; p += WG) {
+    for (int p = (a.sample_blocks > 0 ? 0 : a.p_scan) + tid; p < nprobe; p += WG) {
         const int L = a.probe_ids[(size_t)qi * nprobe + p];
         if (L < 0 || L >= v.nlist) continue;
         const ListEntry le = v.lists[L];
@@ -89,19 +89,27 @@ __global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanAr
     if (my_dco) atomicAdd(&sh.dco, my_dco);
     my_dco = 0;
 
-    const int p_scan = a.p_scan < nprobe ? a.p_scan : nprobe;
+    const bool sample = a.sample_blocks > 0;
+    const int p_scan = sample ? 1 : (a.p_scan < nprobe ? a.p_scan : nprobe);
     for (int p = 0; p < p_scan; p++) {
         const int L = a.probe_ids[(size_t)qi * nprobe + p];
         if (L < 0 || L >= v.nlist) continue;              // caller-supplied ids: never index with them unchecked
         const ListEntry le = v.lists[L];
         // segment -1: the list's own blocks; segments 0..ref_cnt-1: its reference entries
-        for (int seg = -1; seg < le.ref_cnt; seg++) {
+        const int nseg = sample ? 0 : le.ref_cnt;
+        for (int seg = -1; seg < nseg; seg++) {
             int64_t begin;
             int cnt, misc_from;
             if (seg < 0) {
                 begin = le.blk_begin;
                 cnt = le.shared_cnt + le.misc_cnt;
                 misc_from = le.shared_cnt;
+                if (sample) {
+                    // any valid item of the list's own blocks is a distinct member of the probed
+                    // set, duplicate rule or not: enough for a bound
+                    cnt = cnt < a.sample_blocks ? cnt : a.sample_blocks;
+                    misc_from = cnt;
+                }
             } else {
                 const RefEntry re = v.refs[le.ref_begin + seg];
                 if ((sh.bm[re.owner >> 5] >> (re.owner & 31)) & 1u) continue;   // scanned via owner
@@ -146,7 +154,14 @@ __global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanAr
     }
     scan_prune(sh, refine_k);
     const int n = (int)sh.cnt;
-    if (a.surv_buf) {
+    if (sample) {
+        if (tid == 0) {
+            const int32_t t = n == refine_k ? (int32_t)(sh.buf[refine_k - 1] >> 32) : 0xFFFF;
+            a.tau[qi] = t;
+            if (a.bound) a.bound[qi] = t;
+        }
+        my_dco = 0;                                  // the sampled blocks are scored again, and counted, by the main scan
+    } else if (a.surv_buf) {
         // hand the queue over to the MFMA scan: its entries seed the query's survivor buffer and
         // the bigK-th smallest score bounds what any other item needs to reach
         const uint32_t tau0 = n == refine_k ? (uint32_t)(sh.buf[refine_k - 1] >> 32) : 0xFFFFu;

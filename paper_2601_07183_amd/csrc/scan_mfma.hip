@@ -17,12 +17,13 @@
 // the order-free ones of scan_exact.hip.  A score passes when it is <= the query's bound tau;
 // survivors go to the query's buffer and are cut to bigK afterwards by select_kernel.
 //
-// The bound.  tau0 = bigK-th smallest score in the query's first list (exact kernel).  Every
+// The bound.  tau0 = bigK-th smallest score in a sample, the head of the query's first list.  Every
 // survivor is also counted in a per-query histogram of RAIRS_HIST_BINS equal score bins over
 // [0, tau0] (over [0, 255*M] when the first list had fewer than bigK items).  Survivors are
 // distinct members of the query's probed lists, so once bins 0..b hold >= bigK of them, no item
 // scoring above the top edge of bin b can be among the bigK best: that edge is a valid, tighter
-// bound.  Waves re-derive it whenever they load a tile; a stale view is only looser, never wrong.
+// bound.  The lane that files a survivor re-derives the query's bound and lowers it with an
+// atomic minimum; scanning waves re-read it for every block.  A stale view is only looser.
 #include <limits.h>
 
 #include "device_util.h"
@@ -30,16 +31,19 @@
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-#define GRAB 8              // consecutive tasks drawn at once (keeps a tile's tables in registers)
-#define SURV_CAP_MAX 2048   // survivor buffer entries per query (select_kernel sorts them in LDS)
+#define SURV_CAP_MAX 4096   // survivor buffer entries per query (select_kernel sorts them in LDS)
 
 // ---- grouping queries by list ----------------------------------------------------------------
 
-__global__ void lm_zero_kernel(int32_t *lcount, int nlist, uint32_t *next_task)
+__global__ void lm_zero_kernel(int32_t *lcount, int nlist, uint32_t *next_task, uint32_t *surv_cnt,
+                               int64_t nq, uint32_t *chunk_fill, int log_chunks, uint32_t *log_cursor,
+                               uint32_t *log_overflow)
 {
-    int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < nlist) lcount[gid] = 0;
-    if (gid == 0) *next_task = 0;
+    if (gid < nq) surv_cnt[gid] = 0;
+    if (gid < log_chunks) chunk_fill[gid] = 0;
+    if (gid == 0) { *next_task = 0; *log_cursor = 0; *log_overflow = 0; }
 }
 
 __global__ void lm_count_kernel(const int32_t *__restrict__ probe_ids, int64_t nq, int nprobe,
@@ -115,101 +119,102 @@ __global__ void lm_fill_kernel(const int32_t *__restrict__ probe_ids, int64_t nq
 
 // ---- the scan ----------------------------------------------------------------------------------
 
-static __device__ __forceinline__ v4i onehot16(uint32_t nib)
+// Tightest bound the histogram of query `qid` proves.  The histogram counts scored item slots,
+// and a vector can sit in at most two scanned slots (the miscellaneous areas of its two lists),
+// so once bins 0..b hold >= 2 * bigK slots they hold >= bigK distinct members: nothing scoring
+// above the top edge of bin b can be among the bigK best.
+static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a, int qid,
+                                                           uint32_t range)
 {
-    // 16-byte one-hot: byte `nib` = 1
-    uint32_t sh = 1u << ((nib & 3u) << 3);
-    uint32_t w = nib >> 2;
-    v4i r;
-    r.x = w == 0 ? (int)sh : 0;
-    r.y = w == 1 ? (int)sh : 0;
-    r.z = w == 2 ? (int)sh : 0;
-    r.w = w == 3 ? (int)sh : 0;
-    return r;
+    const uint4 *hq = (const uint4 *)(a.hist + (size_t)qid * RAIRS_HIST_BINS);
+    const uint32_t need = 2u * (uint32_t)a.refine_k;
+    uint4 h[RAIRS_HIST_BINS / 4];
+#pragma unroll
+    for (int i = 0; i < RAIRS_HIST_BINS / 4; i++) h[i] = hq[i];      // all loads in flight at once
+    uint32_t cum = 0;
+    int b = RAIRS_HIST_BINS;
+#pragma unroll
+    for (int i = 0; i < RAIRS_HIST_BINS / 4; i++) {
+        cum += h[i].x; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i : b;
+        cum += h[i].y; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i + 1 : b;
+        cum += h[i].z; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i + 2 : b;
+        cum += h[i].w; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i + 3 : b;
+    }
+    if (b == RAIRS_HIST_BINS) return 0xFFFFu;
+    return ((uint32_t)(b + 1) * (range + 1u) - 1u) / RAIRS_HIST_BINS;
 }
 
-// Bound of one query from its first-list bound tau0 and its survivor histogram.  Lanes (j, 0)
-// and (j, 1) hold the same query and split the bins.  Called by all lanes of the wave.
-static __device__ __forceinline__ int current_bound(const MfmaScanArgs &a, int qid, uint32_t tau0,
-                                                    uint32_t range, int g, int bias)
-{
-    uint32_t part = 0, cum_here[RAIRS_HIST_BINS / 2];
-    if (qid >= 0) {
-        const uint4 *hq = (const uint4 *)(a.hist + (size_t)qid * RAIRS_HIST_BINS + g * (RAIRS_HIST_BINS / 2));
-#pragma unroll
-        for (int i = 0; i < RAIRS_HIST_BINS / 8; i++) {
-            uint4 h4 = hq[i];
-            part += h4.x; cum_here[4 * i] = part;
-            part += h4.y; cum_here[4 * i + 1] = part;
-            part += h4.z; cum_here[4 * i + 2] = part;
-            part += h4.w; cum_here[4 * i + 3] = part;
-        }
-    }
-    const uint32_t other = (uint32_t)__shfl_xor((int)part, 32);
-    const uint32_t before = g ? other : 0u;
-    int bfound = RAIRS_HIST_BINS;
-    if (qid >= 0) {
-#pragma unroll
-        for (int i = RAIRS_HIST_BINS / 2 - 1; i >= 0; i--)
-            if (before + cum_here[i] >= (uint32_t)a.refine_k) bfound = g * (RAIRS_HIST_BINS / 2) + i;
-    }
-    const int bo = __shfl_xor(bfound, 32);
-    const int b = bfound < bo ? bfound : bo;
-    if (qid < 0) return INT_MIN;
-    uint32_t tau = tau0;
-    if (b < RAIRS_HIST_BINS) {
-        // every item counted in bins <= b has score <= this
-        uint32_t tb = ((uint32_t)(b + 1) * (range + 1u) - 1u) / RAIRS_HIST_BINS;
-        tau = tb < tau ? tb : tau;
-    }
-    return (int)tau - bias;
-}
-
-// A passing (item, query) pair waits in a per-wave LDS queue until 64 or more have gathered;
-// then every lane finishes one: id load, duplicate rule, slot in the query's survivor buffer.
-// This keeps the global-memory round trips out of the per-block path.
-#define STAGE_CAP 192
+// A passing (item, query) pair waits in a per-wave LDS queue until enough have gathered; then the
+// wave appends them to its current chunk of a global survivor log with plain stores, counts them
+// in the queries' histograms and, for some, lowers the query's bound.  Nothing on this path
+// waits for a returning atomic: the wave owns its chunk, and the next chunk's number is requested
+// long before it is needed.  Ids, tags and the duplicate rule are resolved afterwards, in bulk,
+// by collect_kernel and select_kernel.
+#define STAGE_CAP 128
+#define LOG_CHUNK 256
 struct StageQueue {
     uint32_t slot[STAGE_CAP];      // block * 32 + item
-    uint32_t score[STAGE_CAP];
+    uint32_t score_list[STAGE_CAP];// score << 16 | probed list
     int32_t qid[STAGE_CAP];
     uint32_t lrange[STAGE_CAP];    // score range of the query's histogram
-    int32_t list[STAGE_CAP];       // probed list, bit 31 set for items of miscellaneous blocks
 };
 
-static __device__ __forceinline__ void stage_flush(const IndexView &v, const MfmaScanArgs &a,
-                                                   StageQueue &sq, int n, int lane)
+struct LogCursor {
+    uint32_t chunk, used, next_chunk;   // wave-uniform
+};
+
+static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQueue &sq, int n,
+                                                   int lane, LogCursor &lc)
 {
-    for (int i = lane; i < n; i += 64) {
-        const uint32_t slot = sq.slot[i];
-        const int qid = sq.qid[i];
-        const uint32_t id = v.ids[slot];
-        bool push = id != RAIRS_EMPTY_ID;
-        const int lm = sq.list[i];
-        if (push && lm < 0) {
-            const int L = lm & 0x7FFFFFFF;
-            const int o = v.other[slot];
-            if (o >= 0 && o < L) {
-                uint32_t wbits = a.bitmap[(size_t)qid * a.bmwords + (o >> 5)];
-                if ((wbits >> (o & 31)) & 1u) push = false;
-            }
-        }
-        if (push) {
-            const uint32_t score = sq.score[i];
-            uint32_t pos = atomicAdd(&a.surv_cnt[qid], 1u);
-            if (pos < (uint32_t)a.surv_cap)
-                a.surv_buf[(size_t)qid * a.surv_cap + pos] = ((uint64_t)score << 32) | id;
-            atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + (score * RAIRS_HIST_BINS) / (sq.lrange[i] + 1u)], 1u);
+    if (lc.used + (uint32_t)n > LOG_CHUNK) {
+        // close the chunk, move to the one reserved earlier, reserve another
+        if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
+        lc.chunk = lc.next_chunk;
+        lc.used = 0;
+        uint32_t nx = 0;
+        if (lane == 0) nx = atomicAdd(a.log_cursor, 1u);
+        lc.next_chunk = (uint32_t)__builtin_amdgcn_readfirstlane((int)nx);
+    }
+    const bool room = lc.chunk < (uint32_t)a.log_chunks;
+    if (!room && lane == 0) *a.log_overflow = 1u;      // every query is then redone exactly
+#pragma unroll
+    for (int u = 0; u < STAGE_CAP / 64; u++) {
+        const int i = lane + 64 * u;
+        if (i < n) {
+            const int qid = sq.qid[i];
+            const uint32_t sl = sq.score_list[i], range = sq.lrange[i];
+            if (room)
+                a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint4(sq.slot[i], sl, (uint32_t)qid, 0u);
+            atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + ((sl >> 16) * RAIRS_HIST_BINS) / (range + 1u)], 1u);
         }
     }
+    if (lane < n && (lane & 3) == 0) {
+        // every fourth entry of the first row also refreshes its query's bound.  A stale
+        // histogram only gives a looser bound; the bound itself only ever shrinks.
+        const int qid = sq.qid[lane];
+        const uint32_t nb = histogram_bound(a, qid, sq.lrange[lane]);
+        if (nb < 0xFFFFu) atomicMin(&a.bound[qid], (int32_t)nb);
+    }
+    lc.used += (uint32_t)n;
 }
 
 template <int T>
-__global__ __launch_bounds__(WG) void scan_mfma_kernel(IndexView v, MfmaScanArgs a)
+__global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanArgs a)
 {
     constexpr int ND = (T + 7) / 8;
     constexpr int M = 2 * T;
     __shared__ StageQueue stage[WG / 64];
+    __shared__ v4i onehot[16];                         // onehot[c]: 16 bytes, byte c = 1
+    if (threadIdx.x < 16) {
+        v4i r = {0, 0, 0, 0};
+        const int sh = 1 << ((threadIdx.x & 3) * 8);
+        if ((threadIdx.x >> 2) == 0) r.x = sh;
+        if ((threadIdx.x >> 2) == 1) r.y = sh;
+        if ((threadIdx.x >> 2) == 2) r.z = sh;
+        if ((threadIdx.x >> 2) == 3) r.w = sh;
+        onehot[threadIdx.x] = r;
+    }
+    __syncthreads();
     const int lane = threadIdx.x & 63, g = lane >> 5, j = lane & 31;
     StageQueue &sq = stage[threadIdx.x >> 6];
     const uint32_t ntasks = (uint32_t)a.toff[v.nlist];
@@ -220,15 +225,35 @@ __global__ __launch_bounds__(WG) void scan_mfma_kernel(IndexView v, MfmaScanArgs
 #pragma unroll
     for (int t = 0; t < T; t++) B[t] = (v4i){0, 0, 0, 0};
     int cur_L = -1, cur_tile = -1, qid = -1;
-    uint32_t range = 0, tau0 = 0;
+    uint32_t range = 0;
     int nstaged = 0;                                   // wave-uniform fill of the stage queue
+    LogCursor lc;
+    {
+        uint32_t c0 = 0;
+        if (lane == 0) c0 = atomicAdd(a.log_cursor, 2u);
+        c0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)c0);
+        lc.chunk = c0;
+        lc.next_chunk = c0 + 1;
+        lc.used = 0;
+    }
+    const uint32_t grab = (uint32_t)a.grab;
+#ifdef RAIRS_PROFILE_CYCLES
+    long long pc_t0 = clock64(), pc_tile = 0, pc_blocks = 0, pc_slow = 0, pc_flush = 0, pc_decode = 0, pc_mark;
+    long long pc_nblk = 0, pc_nslow = 0, pc_nflush = 0, pc_ntile = 0, pc_ntask = 0;
+#define PC_MARK() pc_mark = clock64()
+#define PC_ADD(x) x += clock64() - pc_mark
+#else
+#define PC_MARK()
+#define PC_ADD(x)
+#endif
 
     for (;;) {
+        PC_MARK();
         uint32_t t0 = 0;
-        if (lane == 0) t0 = atomicAdd(a.next_task, (uint32_t)GRAB);
+        if (lane == 0) t0 = atomicAdd(a.next_task, grab);
         t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)t0);
         if (t0 >= ntasks) break;                      // every wave gets here: the counter only grows
-        const uint32_t t1 = t0 + GRAB < ntasks ? t0 + GRAB : ntasks;
+        const uint32_t t1 = t0 + grab < ntasks ? t0 + grab : ntasks;
         // list of task t0: the last L with toff[L] <= t0 (lists without tasks are skipped over)
         int lo = 0, hi = v.nlist;
         while (hi - lo > 1) {
@@ -241,6 +266,7 @@ __global__ __launch_bounds__(WG) void scan_mfma_kernel(IndexView v, MfmaScanArgs
         int rem = (int)(t0 - (uint32_t)a.toff[L]);
         int tile = __builtin_amdgcn_readfirstlane(rem / le.seg_cnt);
         int seg = __builtin_amdgcn_readfirstlane(rem % le.seg_cnt);
+        PC_ADD(pc_decode);
 
         for (uint32_t tt = t0; tt < t1; tt++) {
             if (tt >= lend) {
@@ -253,11 +279,12 @@ __global__ __launch_bounds__(WG) void scan_mfma_kernel(IndexView v, MfmaScanArgs
                 seg = 0;
             }
             if (L != cur_L || tile != cur_tile) {
+                PC_MARK();
                 // new tile: query of this lane's column and its tables
                 const int base = a.loff[L], n = a.loff[L + 1] - base;
                 const int qi = tile * 32 + j;
                 qid = qi < n ? a.qlist[base + qi] : -1;
-                tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
+                const uint32_t tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
                 range = tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0;
                 const uint8_t *lq = a.lut + (size_t)(qid >= 0 ? qid : 0) * (M * 16) + g * 16;
 #pragma unroll
@@ -268,62 +295,98 @@ __global__ __launch_bounds__(WG) void scan_mfma_kernel(IndexView v, MfmaScanArgs
                 }
                 cur_L = L;
                 cur_tile = tile;
+#ifdef RAIRS_PROFILE_CYCLES
+                { int sink = B[0].x ^ B[T - 1].w; asm volatile("" :: "v"(sink)); pc_ntile++; }
+#endif
+                PC_ADD(pc_tile);
             }
+#ifdef RAIRS_PROFILE_CYCLES
+            pc_ntask++;
+#endif
             const SegEntry se = v.segs[le.seg_begin + seg];
-            int th = current_bound(a, qid, tau0, range, g, bias);
+            bool live = qid >= 0;
             if (se.owner >= 0 && qid >= 0) {
                 // cell (owner, L) is scored through list `owner` for queries that probe it
                 uint32_t wbits = a.bitmap[(size_t)qid * a.bmwords + (se.owner >> 5)];
-                if ((wbits >> (se.owner & 31)) & 1u) th = INT_MIN;
+                if ((wbits >> (se.owner & 31)) & 1u) live = false;
             }
-            if (__ballot(th != INT_MIN) != 0ull) {
+            if (__ballot(live) != 0ull) {
+                // the query's bound: other waves keep lowering it, so it is looked up again for
+                // every block, one block ahead (a stale bound is only looser)
+                const int32_t *bq = a.bound + (live ? qid : 0);
+                int bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 const uint32_t *cp = v.codes + (size_t)se.blk_begin * ND * 64 + lane;
                 uint32_t cn[ND];
 #pragma unroll
                 for (int w = 0; w < ND; w++) cn[w] = cp[w * 64];
                 for (int b = 0; b < se.nblk; b++) {
+                    PC_MARK();
                     uint32_t c[ND];
 #pragma unroll
                     for (int w = 0; w < ND; w++) c[w] = cn[w];
+                    const int th = live ? bound_next - bias : INT_MIN;
                     if (b + 1 < se.nblk) {             // fetch the next block while this one is scored
 #pragma unroll
                         for (int w = 0; w < ND; w++) cn[w] = cp[(size_t)(b + 1) * ND * 64 + w * 64];
+                        bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     }
                     v16i acc;
 #pragma unroll
                     for (int r = 0; r < 16; r++) acc[r] = 0;
 #pragma unroll
                     for (int t = 0; t < T; t++) {
-                        uint32_t nib = (c[t >> 3] >> (4 * (t & 7))) & 15u;
-                        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(onehot16(nib), B[t], acc, 0, 0, 0);
+                        const uint32_t nib = (c[t >> 3] >> (4 * (t & 7))) & 15u;
+                        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(onehot[nib], B[t], acc, 0, 0, 0);
                     }
                     // acc[r]: item row 8*(r/4) + 4*g + (r%4), query column j
-                    int m = acc[0];
+                    uint32_t pm = 0;                   // rows of this lane that pass
 #pragma unroll
-                    for (int r = 1; r < 16; r++) m = acc[r] < m ? acc[r] : m;
-                    if (__ballot(m <= th) != 0ull) {
+                    for (int r = 0; r < 16; r++) pm |= acc[r] <= th ? (1u << r) : 0u;
+                    PC_ADD(pc_blocks);
+#ifdef RAIRS_PROFILE_CYCLES
+                    pc_nblk++;
+#endif
+                    if (__ballot(pm != 0u) != 0ull) {
+                        PC_MARK();
+#ifdef RAIRS_PROFILE_CYCLES
+                        pc_nslow++;
+#endif
                         const uint32_t slot0 = (uint32_t)(se.blk_begin + b) * 32u + 4u * g;
-                        const int lm = b >= se.misc_from ? (L | (int)0x80000000) : L;
+                        if (b == se.nblk - 1 && se.tail_valid < 32) {
+                            // the list's last block: drop rows whose slot holds no item
 #pragma unroll
-                        for (int r = 0; r < 16; r++) {
-                            const bool pass = acc[r] <= th;
-                            const unsigned long long mask = __ballot(pass);
-                            if (mask != 0ull) {
-                                if (pass) {
-                                    const int pos = nstaged + __popcll(mask & lt_mask);
-                                    sq.slot[pos] = slot0 + 8u * (r >> 2) + (r & 3);
-                                    sq.score[pos] = (uint32_t)(acc[r] + bias);
-                                    sq.qid[pos] = qid;
-                                    sq.lrange[pos] = range;
-                                    sq.list[pos] = lm;
-                                }
-                                nstaged += __popcll(mask);
-                                if (nstaged > STAGE_CAP - 64) {
-                                    stage_flush(v, a, sq, nstaged, lane);
-                                    nstaged = 0;
-                                }
+                            for (int r = 0; r < 16; r++)
+                                if (8 * (r >> 2) + 4 * g + (r & 3) >= se.tail_valid) pm &= ~(1u << r);
+                        }
+                        for (;;) {
+                            const bool has = pm != 0u;
+                            const unsigned long long mask = __ballot(has);
+                            if (mask == 0ull) break;
+                            if (has) {
+                                const int r = __builtin_ctz(pm);
+                                pm &= pm - 1u;
+                                int sc = acc[0];
+#pragma unroll
+                                for (int k = 1; k < 16; k++) sc = r == k ? acc[k] : sc;
+                                const int pos = nstaged + __popcll(mask & lt_mask);
+                                sq.slot[pos] = slot0 + 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);
+                                sq.score_list[pos] = ((uint32_t)(sc + bias) << 16) | (uint32_t)L;
+                                sq.qid[pos] = qid;
+                                sq.lrange[pos] = range;
+                            }
+                            nstaged += __popcll(mask);
+                            if (nstaged > STAGE_CAP - 64) {
+#ifdef RAIRS_PROFILE_CYCLES
+                                long long f0 = clock64();
+#endif
+                                stage_flush(a, sq, nstaged, lane, lc);
+                                nstaged = 0;
+#ifdef RAIRS_PROFILE_CYCLES
+                                pc_flush += clock64() - f0; pc_nflush++;
+#endif
                             }
                         }
+                        PC_ADD(pc_slow);
                     }
                 }
             }
@@ -331,33 +394,144 @@ __global__ __launch_bounds__(WG) void scan_mfma_kernel(IndexView v, MfmaScanArgs
             if (seg == le.seg_cnt) { seg = 0; tile++; }
         }
         // do not sit on survivors for long: their histogram counts tighten everyone's bound
-        if (nstaged >= 64) {
-            stage_flush(v, a, sq, nstaged, lane);
+        if (nstaged >= 32) {
+            stage_flush(a, sq, nstaged, lane, lc);
             nstaged = 0;
         }
     }
-    if (nstaged > 0) stage_flush(v, a, sq, nstaged, lane);
+    if (nstaged > 0) stage_flush(a, sq, nstaged, lane, lc);
+    if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
+#ifdef RAIRS_PROFILE_CYCLES
+    if (lane == 0 && a.prof) {
+        long long *o = a.prof + (size_t)(blockIdx.x * (WG / 64) + (threadIdx.x >> 6)) * 12;
+        o[0] = clock64() - pc_t0; o[1] = pc_decode; o[2] = pc_tile; o[3] = pc_blocks; o[4] = pc_slow;
+        o[5] = pc_flush; o[6] = pc_nblk; o[7] = pc_nslow; o[8] = pc_nflush; o[9] = pc_ntile; o[10] = pc_ntask;
+    }
+#endif
 }
 
-// per query: sort the survivors and keep the bigK smallest (score, id); flag overflowed buffers
-__global__ __launch_bounds__(WG) void select_kernel(MfmaScanArgs a)
+// Distribute the survivor log to the per-query buffers (one workgroup per chunk).  A chunk holds
+// entries of a few dozen queries; they are grouped in LDS first so that each query's counter is
+// bumped once per chunk, not once per entry.
+#define COLLECT_SLOTS 128
+__global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
+{
+    __shared__ int32_t key[COLLECT_SLOTS];
+    __shared__ uint32_t cnt[COLLECT_SLOTS], base[COLLECT_SLOTS];
+    const uint32_t c = blockIdx.x;
+    const uint32_t n = a.chunk_fill[c];
+    if (n == 0) return;
+    const int tid = threadIdx.x;
+    if (tid < COLLECT_SLOTS) { key[tid] = -1; cnt[tid] = 0; }
+    __syncthreads();
+    uint4 e = make_uint4(0, 0, 0, 0);
+    int slot = -1;
+    uint32_t rank = 0;
+    if (tid < (int)n) {
+        e = a.log[(size_t)c * LOG_CHUNK + tid];
+        const int qid = (int)e.z;
+        // open addressing on the query id; a full table falls back to a direct atomic below
+        int h = (int)(((uint32_t)qid * 2654435761u) >> 25);          // 7 bits
+        for (int probe = 0; probe < COLLECT_SLOTS; probe++) {
+            const int prev = atomicCAS(&key[h], -1, qid);
+            if (prev == -1 || prev == qid) { slot = h; break; }
+            h = (h + 1) & (COLLECT_SLOTS - 1);
+        }
+        if (slot >= 0) rank = atomicAdd(&cnt[slot], 1u);
+    }
+    __syncthreads();
+    if (tid < COLLECT_SLOTS && cnt[tid] > 0) base[tid] = atomicAdd(&a.surv_cnt[key[tid]], cnt[tid]);
+    __syncthreads();
+    if (tid < (int)n) {
+        const uint32_t qid = e.z;
+        const uint32_t pos = slot >= 0 ? base[slot] + rank : atomicAdd(&a.surv_cnt[qid], 1u);
+        if (pos < (uint32_t)a.surv_cap) a.surv_buf[(size_t)qid * a.surv_cap + pos] = ((uint64_t)e.y << 32) | e.x;
+    }
+}
+
+// Per query: resolve the survivors (id, duplicate rule of the miscellaneous area) and keep the
+// bigK smallest (score, id).  A two-pass radix select on the 16-bit score finds the score of the
+// bigK-th survivor; only entries up to that score are sorted.  Overflowed buffers are flagged for
+// the exact redo.
+#define SELECT_SORT_MAX 2048
+__global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a)
 {
     __shared__ uint64_t keys[SURV_CAP_MAX];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_prefix, s_need, s_kept;
     const int tid = threadIdx.x;
     const int64_t q = blockIdx.x;
     const uint32_t n = a.surv_cnt[q];
-    if (n > (uint32_t)a.surv_cap) {
+    if (n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) {
         if (tid == 0) a.flags[q] = 1;       // the exact kernel redoes this query
         return;
     }
     if (tid == 0) a.flags[q] = 0;
-    const int n2 = next_pow2(n < 2 ? 2 : (int)n);
-    for (int i = tid; i < n2; i += WG) keys[i] = i < (int)n ? a.surv_buf[(size_t)q * a.surv_cap + i] : ~0ull;
+    for (int i = tid; i < (int)n; i += WG) {
+        uint64_t key = ~0ull;
+        const uint64_t e = a.surv_buf[(size_t)q * a.surv_cap + i];
+        const uint32_t slot = (uint32_t)e, score = (uint32_t)(e >> 48), L = (uint32_t)(e >> 32) & 0xFFFFu;
+        const uint32_t id = v.ids[slot];
+        const int o = v.other[slot];
+        bool keep = id != RAIRS_EMPTY_ID;
+        if (keep && o >= 0 && (uint32_t)o < L) {
+            // RemoveVectorIfVisited: the item was already taken from list o
+            const uint32_t wbits = a.bitmap[(size_t)q * a.bmwords + (o >> 5)];
+            if ((wbits >> (o & 31)) & 1u) keep = false;
+        }
+        if (keep) key = ((uint64_t)score << 32) | id;
+        keys[i] = key;
+    }
+    // score of the bigK-th smallest kept key: radix select, high byte then low byte
+    uint32_t prefix = 0, need = (uint32_t)a.refine_k;
+    bool all = false;                       // fewer than bigK kept: everything is sorted
+    for (int pass = 0; pass < 2 && !all; pass++) {
+        const int shift = pass == 0 ? 8 : 0;
+        hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < (int)n; i += WG) {
+            const uint64_t key = keys[i];
+            if (key != ~0ull) {
+                const uint32_t sc = (uint32_t)(key >> 32);
+                if (pass == 0 || (sc >> 8) == prefix) atomicAdd(&hist[(sc >> shift) & 255u], 1u);
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t cum = 0;
+            s_need = 0xFFFFFFFFu;
+            for (int b = 0; b < 256; b++) {
+                if (cum + hist[b] >= need) { s_prefix = (uint32_t)b; s_need = need - cum; break; }
+                cum += hist[b];
+            }
+        }
+        __syncthreads();
+        if (s_need == 0xFFFFFFFFu) all = true;
+        else { prefix = pass == 0 ? s_prefix : ((prefix << 8) | s_prefix); need = s_need; }
+        __syncthreads();
+    }
+    const uint32_t cut = all ? 0xFFFFu : prefix;          // keep scores <= cut
+    // compact the kept keys with score <= cut to the front (order is irrelevant before the sort)
+    if (tid == 0) s_kept = 0;
+    __syncthreads();
+    uint64_t mine[SURV_CAP_MAX / WG];
+    int nm = 0;
+    for (int i = tid; i < (int)n; i += WG) {
+        const uint64_t key = keys[i];
+        if (key != ~0ull && (uint32_t)(key >> 32) <= cut) mine[nm++] = key;
+    }
+    __syncthreads();
+    uint32_t at = nm ? atomicAdd(&s_kept, (uint32_t)nm) : 0u;
+    for (int i = 0; i < nm; i++) keys[at + i] = mine[i];
+    __syncthreads();
+    const int kept = (int)s_kept;
+    const int n2 = next_pow2(kept < 2 ? 2 : kept);
+    for (int i = kept + tid; i < n2; i += WG) keys[i] = ~0ull;
     __syncthreads();
     bitonic_sort_lds(keys, n2);
     for (int i = tid; i < a.refine_k; i += WG) {
-        bool ok = i < (int)n;
-        uint64_t key = ok ? keys[i] : 0;
+        const uint64_t key = i < n2 ? keys[i] : ~0ull;
+        const bool ok = key != ~0ull;
         a.cand_ids[(size_t)q * a.refine_k + i] = ok ? (int64_t)(uint32_t)key : -1;
         if (a.cand_score) a.cand_score[(size_t)q * a.refine_k + i] = ok ? (int32_t)(key >> 32) : -1;
     }
@@ -377,8 +551,11 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
         return RAIRS_EINVAL;
     }
     const int64_t pairs = a.nq * np;
-    hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((v.nlist + 255) / 256)), dim3(256), 0, s,
-                       a.lcount, v.nlist, a.next_task);
+    int64_t nz = v.nlist > a.nq ? v.nlist : a.nq;
+    nz = nz > a.log_chunks ? nz : a.log_chunks;
+    hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
+                       v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
+                       a.log_cursor, a.log_overflow);
     hipLaunchKernelGGL(lm_count_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                        a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount);
     hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
@@ -399,9 +576,10 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     return RAIRS_OK;
 }
 
-int rairs_launch_select(const MfmaScanArgs &a, hipStream_t s)
+int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(select_kernel, dim3((unsigned)a.nq), dim3(WG), 0, s, a);
+    hipLaunchKernelGGL(collect_kernel, dim3((unsigned)a.log_chunks), dim3(LOG_CHUNK), 0, s, a);
+    hipLaunchKernelGGL(select_kernel, dim3((unsigned)a.nq), dim3(WG), 0, s, v, a);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
