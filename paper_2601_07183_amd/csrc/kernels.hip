@@ -189,14 +189,176 @@ __global__ __launch_bounds__(WG) void coarse_select_kernel(const float *__restri
     }
 }
 
+// Same distances with the lane's centroid held in registers and a block of queries streamed past
+// it: the centroid matrix is then read once per 32 queries instead of once per query.
+#define COARSE_QB 32
+template <int D>
+__global__ __launch_bounds__(WG) void coarse_dist_reg_kernel(const float *__restrict__ q,
+                                                             const float *__restrict__ ct,
+                                                             int nlist, int groups, int64_t nq,
+                                                             float *__restrict__ dmat)
+{
+    constexpr int NP = D < 64 ? D : 64;      // partial-sum classes in use
+    const int64_t q0 = (int64_t)(blockIdx.x / groups) * COARSE_QB;
+    const int l = (blockIdx.x % groups) * WG + threadIdx.x;
+    const int lc = l < nlist ? l : nlist - 1;
+    float c[D];
+#pragma unroll
+    for (int i = 0; i < D; i++) c[i] = ct[(size_t)i * nlist + lc];
+    const int64_t q1 = q0 + COARSE_QB < nq ? q0 + COARSE_QB : nq;
+    for (int64_t qi = q0; qi < q1; qi++) {
+        const float *qq = q + (size_t)qi * D;
+        float p[NP];
+#pragma unroll
+        for (int j = 0; j < NP; j++) {
+            float diff = qq[j] - c[j];
+            p[j] = diff * diff;
+        }
+#pragma unroll
+        for (int i = NP; i < D; i++) {
+            float diff = qq[i] - c[i];
+            float sq = diff * diff;
+            p[i & 63] = p[i & 63] + sq;
+        }
+        // classes NP..63 are +0 and adding +0 changes nothing (all terms are >= +0)
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+#pragma unroll
+            for (int j = 0; j < s; j++)
+                if (j + s < NP) p[j] = p[j] + p[j + s];
+        }
+        if (l < nlist) dmat[(size_t)qi * nlist + l] = p[0];
+    }
+}
+
+// One wave per query (four queries per workgroup): same selection as coarse_select_kernel for
+// nprobe <= 1024.  All loops have trip counts that depend only on nlist and nprobe, so the
+// workgroup barriers are reached uniformly.
+#define SELW_MAX_NPROBE 1024
+__global__ __launch_bounds__(WG) void coarse_select_wave_kernel(const float *__restrict__ dmat,
+                                                                int nlist, int nprobe, int64_t nq,
+                                                                int32_t *__restrict__ probe_ids,
+                                                                float *__restrict__ probe_dists)
+{
+    __shared__ uint32_t hist_s[WG / 64][256];
+    __shared__ uint64_t sel_s[WG / 64][SELW_MAX_NPROBE];
+    __shared__ uint32_t cnt_s[WG / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t qi0 = (int64_t)blockIdx.x * (WG / 64) + wave;
+    const int64_t qi = qi0 < nq ? qi0 : nq - 1;          // surplus waves redo the last query
+    const uint32_t *row = (const uint32_t *)(dmat + (size_t)qi * nlist);
+    uint32_t *hist = hist_s[wave];
+    uint64_t *sel = sel_s[wave];
+
+    uint32_t prefix = 0, mask = 0, remaining = (uint32_t)nprobe;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int i = lane; i < 256; i += 64) hist[i] = 0;
+        __syncthreads();
+        for (int i = lane; i < nlist; i += 64) {
+            uint32_t key = row[i];
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        // the bin where the running count reaches `remaining`: four bins per lane + wave scan
+        uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+        uint32_t tot = h0 + h1 + h2 + h3, incl = tot;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            uint32_t up = (uint32_t)__shfl_up((int)incl, off);
+            if (lane >= off) incl += up;
+        }
+        const uint32_t excl = incl - tot;
+        const bool here = excl < remaining && incl >= remaining;       // exactly one lane
+        uint32_t bin = 0, rem = 0;
+        if (here) {
+            uint32_t cum = excl;
+            if (cum + h0 >= remaining) { bin = 4 * lane; rem = remaining - cum; }
+            else if (cum + h0 + h1 >= remaining) { bin = 4 * lane + 1; rem = remaining - cum - h0; }
+            else if (cum + h0 + h1 + h2 >= remaining) { bin = 4 * lane + 2; rem = remaining - cum - h0 - h1; }
+            else { bin = 4 * lane + 3; rem = remaining - cum - h0 - h1 - h2; }
+        }
+        const unsigned long long who = __ballot(here);
+        const int src = __ffsll((long long)who) - 1;
+        bin = (uint32_t)__shfl((int)bin, src);
+        rem = (uint32_t)__shfl((int)rem, src);
+        prefix |= bin << shift;
+        remaining = rem;
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    const uint32_t kth = prefix;
+    // keys below the nprobe-th distance in any order, then `remaining` keys equal to it, the ones
+    // with the smallest list ids (lists are walked in increasing id)
+    uint32_t nless = 0, neq = 0;
+    for (int i0 = 0; i0 < nlist; i0 += 64) {
+        const int i = i0 + lane;
+        const uint32_t key = i < nlist ? row[i] : 0xFFFFFFFFu;
+        const bool less = i < nlist && key < kth;
+        const bool eq = i < nlist && key == kth;
+        const unsigned long long ml = __ballot(less), me = __ballot(eq);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (less) sel[nless + __popcll(ml & below)] = ((uint64_t)key << 32) | (uint32_t)i;
+        nless += (uint32_t)__popcll(ml);
+        if (eq) {
+            const uint32_t r = neq + (uint32_t)__popcll(me & below);
+            // slots after the (nprobe - remaining) smaller keys
+            if (r < remaining) sel[(uint32_t)nprobe - remaining + r] = ((uint64_t)kth << 32) | (uint32_t)i;
+        }
+        neq += (uint32_t)__popcll(me);
+    }
+    const int n2 = next_pow2(nprobe < 2 ? 2 : nprobe);
+    for (int i = nprobe + lane; i < n2; i += 64) sel[i] = ~0ull;
+    __syncthreads();
+    // bitonic sort by the wave alone
+    for (int k = 2; k <= n2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = lane; i < n2; i += 64) {
+                int p = i ^ j;
+                if (p > i) {
+                    bool up = (i & k) == 0;
+                    uint64_t x = sel[i], y = sel[p];
+                    if ((x > y) == up) { sel[i] = y; sel[p] = x; }
+                }
+            }
+            __syncthreads();
+        }
+    if (qi0 < nq)
+        for (int i = lane; i < nprobe; i += 64) {
+            uint64_t key = sel[i];
+            probe_ids[(size_t)qi * nprobe + i] = (int32_t)(uint32_t)key;
+            if (probe_dists) probe_dists[(size_t)qi * nprobe + i] = __uint_as_float((uint32_t)(key >> 32));
+        }
+    (void)cnt_s;
+}
+
 int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,
                         int32_t *probe_ids, float *probe_dists, hipStream_t s)
 {
     int groups = (v.nlist + WG - 1) / WG;
-    hipLaunchKernelGGL(coarse_dist_kernel, dim3((unsigned)(nq * groups)), dim3(WG), 0, s, q,
-                       v.centroids_t, v.d, v.nlist, groups, dmat);
-    hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist,
-                       nprobe, probe_ids, probe_dists);
+    const unsigned qblocks = (unsigned)((nq + COARSE_QB - 1) / COARSE_QB);
+    switch (v.d) {
+    case 32:
+        hipLaunchKernelGGL(coarse_dist_reg_kernel<32>, dim3(qblocks * groups), dim3(WG), 0, s, q,
+                           v.centroids_t, v.nlist, groups, nq, dmat);
+        break;
+    case 96:
+        hipLaunchKernelGGL(coarse_dist_reg_kernel<96>, dim3(qblocks * groups), dim3(WG), 0, s, q,
+                           v.centroids_t, v.nlist, groups, nq, dmat);
+        break;
+    case 128:
+        hipLaunchKernelGGL(coarse_dist_reg_kernel<128>, dim3(qblocks * groups), dim3(WG), 0, s, q,
+                           v.centroids_t, v.nlist, groups, nq, dmat);
+        break;
+    default:
+        hipLaunchKernelGGL(coarse_dist_kernel, dim3((unsigned)(nq * groups)), dim3(WG), 0, s, q,
+                           v.centroids_t, v.d, v.nlist, groups, dmat);
+    }
+    if (nprobe <= SELW_MAX_NPROBE)
+        hipLaunchKernelGGL(coarse_select_wave_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))),
+                           dim3(WG), 0, s, dmat, v.nlist, nprobe, nq, probe_ids, probe_dists);
+    else
+        hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist,
+                           nprobe, probe_ids, probe_dists);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
