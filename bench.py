@@ -23,6 +23,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# Bytes that left L2 per launch of the scan kernel, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0
+# and WRITE_SIZE x 1.0, factors from the same counters on a 1 GiB copy); see profiles/.  Keyed by
+# (workload, nprobe); other configurations report null.
+MEASURED_TRAFFIC = {}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -165,7 +170,7 @@ def main():
     scan_bytes = float(dco.sum()) * (w.M // 2)         # algorithmic: M/2 code bytes per item scored
     scan_gbs = scan_bytes / (stage["scan"] * 1e-3) / 1e9
     log(f"[bench] nprobe={chosen} recall@10={rec_chosen} {qps:.0f} QPS, {ms_per_step:.3f} ms/step, "
-        f"stages {stage}, scan {scan_gbs:.1f} GB/s algorithmic")
+        f"stages {stage}, scan stage {scan_gbs:.1f} GB/s algorithmic")
 
     # --- CPU baseline: the oracle as it stands, on a bounded sample of the same batch --------
     from oracle import oracle
@@ -185,13 +190,17 @@ def main():
     log(f"[bench] oracle: {ncpu} queries in {cpu_sec:.2f}s on {threads} threads; "
         f"GPU ids identical on the sample: {same}")
 
+    # Matrix-core view of the same kernel: one table lookup is 16 int8 multiply-adds (the one-hot
+    # K dimension) = 32 ops, so useful ops = items x M x 32.
+    useful_pops = float(dco.sum()) * w.M * 32 / (stage["scan_kernel"] * 1e-3) / 1e15
+    kernel_gbs = scan_bytes / (stage["scan_kernel"] * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC.get((w.name, chosen))
     result = {
         "metric": "QPS at recall@10>=0.9 (1Mx128, 1 GPU)" if w.name == "sift1m"
                   else f"QPS at recall@10>={args.target_recall} ({w.name}, 1 GPU)",
         "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "u8 lookups / u16 sums / f32 distances",
-        "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
         "config": {
             "workload": f"{w.name}: N={w.n} d={w.d} nq={nq} nlist={w.nlist} M={w.M}x4bit k={w.k} "
                         f"refine_k={w.refine_k} strict AIR lambda=0.5 + SEIL",
@@ -201,11 +210,22 @@ def main():
             "dco_per_query": float(dco.mean()), "index_code_bytes": code_bytes,
             "index_total_bytes": total_bytes, "vectors_in_shared_blocks": round(shared_frac, 4),
             "ids_identical_to_oracle_on_sample": same,
+            "scan_stage_algorithmic_GBs": round(scan_gbs, 1),
         },
+        # dominant kernel: the list-major scan.  achieved = algorithmic code bytes (M/2 per item
+        # scored, after SEIL dedup) / its mean launch time over the timed steps (HIP events on the
+        # caller's stream).  It exceeds the HBM peak because a block fetched once serves a tile
+        # of 32 queries; "traffic" is what rocprofv3 counted leaving L2 (see profiles/).
         "roofline": {
-            "kernel": "scan", "bound": "hbm", "achieved": round(scan_gbs, 1), "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": round(scan_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-            "algorithmic_bytes_per_launch": scan_bytes, "avg_launch_ms": round(stage["scan"], 4),
+            "kernel": "scan_mfma_kernel", "bound": "hbm", "achieved": round(kernel_gbs, 1),
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(kernel_gbs / HBM_PEAK_GBS, 4),
+            "traffic": traffic, "algorithmic_bytes_per_launch": scan_bytes,
+            "avg_launch_ms": round(stage["scan_kernel"], 4),
+        },
+        "roofline_mfma": {
+            "kernel": "scan_mfma_kernel", "bound": "mfma", "achieved": round(useful_pops, 4),
+            "peak": 5.0, "unit": "POP/s", "frac": round(useful_pops / 5.0, 4),
+            "note": "useful int8 ops = items x M lookups x 32 ops per 16-wide one-hot lookup",
         },
         "cpu_baseline": {
             "value": round(ncpu / cpu_sec, 1), "unit": "queries/s", "cores": threads,

@@ -231,6 +231,9 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
         e2.seg_cnt = (int32_t)hs.size() - e2.seg_begin;
     }
     h->nsegs = (int64_t)hs.size();
+    h->max_parts = 1;
+    for (int l = 0; l < x->nlist; l++)
+        if (hl[(size_t)l].seg_cnt > h->max_parts) h->max_parts = hl[(size_t)l].seg_cnt;
     SegEntry *segs = nullptr;
     UP_CHECK(dev_alloc(h, (void **)&segs, hs.size() * sizeof(SegEntry)));
     if (!hs.empty())
@@ -296,12 +299,12 @@ extern "C" int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, in
 
 struct WsLayout {
     size_t dmat, probe_ids, probe_dists, bitmap, lut, cand;
-    size_t lcount, loff, lcursor, toff, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, prof, total;
+    size_t lcount, loff, lcursor, toff, unit_list, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, prof, total;
     int log_chunks;
     int bmwords;
 };
 
-static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine_k)
+static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine_k, int max_parts = 1)
 {
     WsLayout w;
     w.bmwords = (v.nlist + 31) / 32;
@@ -318,6 +321,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     w.lcursor = take((size_t)v.nlist * 4);
     w.toff = take((size_t)(v.nlist + 1) * 4);
     w.next_task = take(4);
+    w.unit_list = take(((size_t)nq * nprobe / 32 + (size_t)v.nlist) * (size_t)max_parts * 4);   // max_parts = most segments in a list
     w.qlist = take((size_t)nq * nprobe * 4);
     w.tau = take((size_t)nq * 4);
     w.bound = take((size_t)nq * 4);
@@ -455,6 +459,14 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     ma.nprobe = nprobe; ma.refine_k = refine_k; ma.p_first = 1; ma.nq = n;
     ma.lcount = (int32_t *)(ws + w.lcount); ma.loff = (int32_t *)(ws + w.loff);
     ma.lcursor = (int32_t *)(ws + w.lcursor); ma.toff = (int32_t *)(ws + w.toff);
+    ma.unit_list = (int32_t *)(ws + w.unit_list);
+    {
+        // segments per unit: large units save table reloads, small ones keep 2048 waves busy
+        const int64_t tiles = n * (int64_t)nprobe / 32 + v.nlist;
+        const int64_t segs_total = tiles * (h->nsegs / (v.nlist > 0 ? v.nlist : 1) + 1);
+        int us = (int)(segs_total / (2048 * 6));
+        ma.unit_segs = us < 1 ? 1 : (us > 8 ? 8 : us);
+    }
     ma.next_task = (uint32_t *)(ws + w.next_task); ma.qlist = (int32_t *)(ws + w.qlist);
     ma.tau = (int32_t *)(ws + w.tau); ma.surv_cnt = (uint32_t *)(ws + w.surv_cnt);
     ma.surv_buf = (uint64_t *)(ws + w.surv_buf); ma.surv_cap = SURV_CAP;
@@ -468,19 +480,12 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     ma.prof = (long long *)(ws + w.prof);
     h->last_prof_off = w.prof;
 #endif
-    {
-        // tasks per draw: enough draws to keep all 2048 waves busy, at most 8
-        const int64_t est = (n * (int64_t)nprobe / 32 + v.nlist) * 4;
-        ma.grab = est / (2048 * 4) < 1 ? 1 : (est / (2048 * 4) > 8 ? 8 : (int)(est / (2048 * 4)));
-    }
     // bound of every query from a sample (the head of its first list); also the DCO of all probes
     ma.p_first = 0;
     ea.sample_blocks = RAIRS_SAMPLE_BLOCKS; ea.tau = (int32_t *)(ws + w.tau);
     ea.bound = (int32_t *)(ws + w.bound); ma.bound = ea.bound;
     if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
-    if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
-    if ((rc = rairs_launch_scan_mfma(v, ma, s))) return rc;
-    if (ev) RAIRS_HIP(hipEventRecord(ev[1], s));
+    if ((rc = rairs_launch_scan_mfma(v, ma, s, ev))) return rc;
     if ((rc = rairs_launch_select(v, ma, s))) return rc;
     // queries whose survivor buffer overflowed are redone by the exact kernel
     ExactScanArgs fa = ea;
@@ -500,7 +505,7 @@ extern "C" int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t 
     if (nq == 0) return RAIRS_OK;
     if (!d_lut || !d_probe_ids || !d_cand_ids) FAIL(RAIRS_EINVAL, "null device pointer");
     const int64_t step = pass_size(h->v, nq);
-    WsLayout w = ws_layout(h->v, step, nprobe, refine_k);
+    WsLayout w = ws_layout(h->v, step, nprobe, refine_k, h->max_parts);
     if ((rc = ensure_ws(h, w.total))) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     if (((uintptr_t)d_lut & 15) != 0) FAIL(RAIRS_EINVAL, "d_lut must be 16-byte aligned");
@@ -541,7 +546,7 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
     if (!d_queries || !d_out_ids || !d_out_dists) FAIL(RAIRS_EINVAL, "null device pointer");
     const IndexView &v = h->v;
     const int64_t step = pass_size(v, nq);
-    WsLayout w = ws_layout(v, step, nprobe, refine_k);
+    WsLayout w = ws_layout(v, step, nprobe, refine_k, h->max_parts);
     if ((rc = ensure_ws(h, w.total))) return rc;
     if ((rc = ensure_dco(h, nq))) return rc;
     hipStream_t s = (hipStream_t)hip_stream;

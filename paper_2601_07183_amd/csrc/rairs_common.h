@@ -60,6 +60,7 @@ struct rairs_index {
     IndexView v;
     void *dev_alloc[16];
     int64_t nsegs;
+    int max_parts;                // most segments in any list (bounds the work-unit table)
     int ndev_alloc;
     int64_t code_bytes, total_bytes;
     // workspace (grown on demand)
@@ -134,7 +135,9 @@ struct MfmaScanArgs {
     int32_t *loff;                // [nlist+1] exclusive prefix of lcount
     int32_t *lcursor;             // [nlist]
     int32_t *qlist;               // [nq * nprobe] query ids grouped by list
-    int32_t *toff;                // [nlist+1] exclusive prefix of tasks per list
+    int32_t *toff;                // [nlist+1] exclusive prefix of work units per list
+    int32_t *unit_list;           // [units] list of every work unit
+    int unit_segs;                // segments per unit, 1..8
     uint32_t *next_task;          // [1]
     const int32_t *tau;           // [nq] bound from the sample (0xFFFF: none); fixes the histogram range
     int32_t *bound;               // [nq] current bound, starts at tau, only decreases
@@ -148,13 +151,12 @@ struct MfmaScanArgs {
     uint32_t *log_cursor;         // [1] chunks handed out
     uint32_t *log_overflow;       // [1] set if the log ran out of chunks
     int log_chunks;
-    int grab;                     // consecutive tasks a wave draws at once
     long long *prof;              // cycle counters per wave (profiling builds only), may be null
     int64_t *cand_ids;            // [nq][refine_k]
     int32_t *cand_score;          // may be null
 };
 bool rairs_mfma_supported(const IndexView &v);
-int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
+int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev);
 int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
 int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,
                         int refine_k, int k, int64_t *out_ids, float *out_dists, hipStream_t s);

@@ -58,11 +58,19 @@ __global__ void lm_count_kernel(const int32_t *__restrict__ probe_ids, int64_t n
     if (L >= 0 && L < nlist) atomicAdd(&lcount[L], 1);
 }
 
-// exclusive prefixes over lists: queries (loff) and tasks (toff); one workgroup of 1024
+// A unit of work is (list, tile of <= 32 of the queries probing it, part = up to unit_segs
+// consecutive segments of the list; unit_segs is 1..8, smaller when there is little work).  Exclusive prefixes over lists of queries (loff) and units
+// (toff), and the list of every unit; one workgroup of 1024.
+static __device__ __forceinline__ int units_of(int nqueries, int seg_cnt, int unit_segs)
+{
+    return ((nqueries + 31) >> 5) * ((seg_cnt + unit_segs - 1) / unit_segs);
+}
+
 __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
                                                          const int32_t *__restrict__ lcount,
                                                          int32_t *loff, int32_t *lcursor,
-                                                         int32_t *toff)
+                                                         int32_t *toff, int32_t *unit_list,
+                                                         int unit_segs)
 {
     __shared__ int sc[1024], st[1024];
     const int tid = threadIdx.x;
@@ -73,7 +81,7 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
     for (int L = lo; L < hi; L++) {
         int n = lcount[L];
         c += n;
-        t += ((n + 31) >> 5) * v.lists[L].seg_cnt;
+        t += units_of(n, v.lists[L].seg_cnt, unit_segs);
     }
     sc[tid] = c;
     st[tid] = t;
@@ -92,8 +100,10 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
         loff[L] = cb;
         toff[L] = tb;
         lcursor[L] = 0;
+        const int nu = units_of(n, v.lists[L].seg_cnt, unit_segs);
+        for (int u = 0; u < nu; u++) unit_list[tb + u] = L;
         cb += n;
-        tb += ((n + 31) >> 5) * v.lists[L].seg_cnt;
+        tb += nu;
     }
     if (tid == 1023) {
         loff[v.nlist] = sc[1023];
@@ -164,7 +174,7 @@ struct LogCursor {
 };
 
 static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQueue &sq, int n,
-                                                   int lane, LogCursor &lc)
+                                                   int lane, LogCursor &lc, bool refresh)
 {
     if (lc.used + (uint32_t)n > LOG_CHUNK) {
         // close the chunk, move to the one reserved earlier, reserve another
@@ -188,7 +198,7 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
             atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + ((sl >> 16) * RAIRS_HIST_BINS) / (range + 1u)], 1u);
         }
     }
-    if (lane < n && (lane & 3) == 0) {
+    if (refresh && lane < n && (lane & 3) == 0) {
         // every fourth entry of the first row also refreshes its query's bound.  A stale
         // histogram only gives a looser bound; the bound itself only ever shrinks.
         const int qid = sq.qid[lane];
@@ -217,15 +227,12 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
     __syncthreads();
     const int lane = threadIdx.x & 63, g = lane >> 5, j = lane & 31;
     StageQueue &sq = stage[threadIdx.x >> 6];
-    const uint32_t ntasks = (uint32_t)a.toff[v.nlist];
     const int bias = 128 * M;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
     v4i B[T];
 #pragma unroll
     for (int t = 0; t < T; t++) B[t] = (v4i){0, 0, 0, 0};
-    int cur_L = -1, cur_tile = -1, qid = -1;
-    uint32_t range = 0;
     int nstaged = 0;                                   // wave-uniform fill of the stage queue
     LogCursor lc;
     {
@@ -236,7 +243,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         lc.next_chunk = c0 + 1;
         lc.used = 0;
     }
-    const uint32_t grab = (uint32_t)a.grab;
+    uint32_t nflush = 0;
 #ifdef RAIRS_PROFILE_CYCLES
     long long pc_t0 = clock64(), pc_tile = 0, pc_blocks = 0, pc_slow = 0, pc_flush = 0, pc_decode = 0, pc_mark;
     long long pc_nblk = 0, pc_nslow = 0, pc_nflush = 0, pc_ntile = 0, pc_ntask = 0;
@@ -246,89 +253,93 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #define PC_MARK()
 #define PC_ADD(x)
 #endif
+#define FLUSH_STAGE()                                                   \
+    do {                                                                \
+        stage_flush(a, sq, nstaged, lane, lc, (nflush & 1u) == 0u);     \
+        nstaged = 0;                                                    \
+        nflush++;                                                       \
+    } while (0)
 
-    for (;;) {
+    const uint32_t nunits = (uint32_t)a.toff[v.nlist];
+    uint32_t u = 0;
+    if (lane == 0) u = atomicAdd(a.next_task, 1u);
+    u = (uint32_t)__builtin_amdgcn_readfirstlane((int)u);
+    while (u < nunits) {                               // every wave leaves: the counter only grows
         PC_MARK();
-        uint32_t t0 = 0;
-        if (lane == 0) t0 = atomicAdd(a.next_task, grab);
-        t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)t0);
-        if (t0 >= ntasks) break;                      // every wave gets here: the counter only grows
-        const uint32_t t1 = t0 + grab < ntasks ? t0 + grab : ntasks;
-        // list of task t0: the last L with toff[L] <= t0 (lists without tasks are skipped over)
-        int lo = 0, hi = v.nlist;
-        while (hi - lo > 1) {
-            int mid = (lo + hi) >> 1;
-            if ((uint32_t)a.toff[mid] <= t0) lo = mid; else hi = mid;
-        }
-        int L = __builtin_amdgcn_readfirstlane(lo);
-        uint32_t lend = (uint32_t)__builtin_amdgcn_readfirstlane(a.toff[L + 1]);
-        ListEntry le = v.lists[L];
-        int rem = (int)(t0 - (uint32_t)a.toff[L]);
-        int tile = __builtin_amdgcn_readfirstlane(rem / le.seg_cnt);
-        int seg = __builtin_amdgcn_readfirstlane(rem % le.seg_cnt);
+        // ask for the unit after this one now; the answer is not needed before this one is done
+        uint32_t u_next = 0;
+        if (lane == 0) u_next = atomicAdd(a.next_task, 1u);
+        const int L = __builtin_amdgcn_readfirstlane(a.unit_list[u]);
+        const ListEntry le = v.lists[L];
+        const int rem = (int)u - __builtin_amdgcn_readfirstlane(a.toff[L]);
+        const int parts = (le.seg_cnt + a.unit_segs - 1) / a.unit_segs;
+        const int tile = __builtin_amdgcn_readfirstlane(rem / parts);
+        const int seg0 = __builtin_amdgcn_readfirstlane((rem % parts) * a.unit_segs);
+        const int seg1 = seg0 + a.unit_segs < le.seg_cnt ? seg0 + a.unit_segs : le.seg_cnt;
         PC_ADD(pc_decode);
-
-        for (uint32_t tt = t0; tt < t1; tt++) {
-            if (tt >= lend) {
-                do {
-                    L++;
-                    lend = (uint32_t)__builtin_amdgcn_readfirstlane(a.toff[L + 1]);
-                } while (tt >= lend);                 // ends: tt < ntasks = toff[nlist]
-                le = v.lists[L];
-                tile = 0;
-                seg = 0;
-            }
-            if (L != cur_L || tile != cur_tile) {
-                PC_MARK();
-                // new tile: query of this lane's column and its tables
-                const int base = a.loff[L], n = a.loff[L + 1] - base;
-                const int qi = tile * 32 + j;
-                qid = qi < n ? a.qlist[base + qi] : -1;
-                const uint32_t tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
-                range = tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0;
-                const uint8_t *lq = a.lut + (size_t)(qid >= 0 ? qid : 0) * (M * 16) + g * 16;
+        PC_MARK();
+        int qid;
+        uint32_t range;
+        {
+            // the tile: query of this lane's column and its tables
+            const int base = a.loff[L], n = a.loff[L + 1] - base;
+            const int qi = tile * 32 + j;
+            qid = qi < n ? a.qlist[base + qi] : -1;
+            const uint32_t tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
+            range = tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0;
+            const uint8_t *lq = a.lut + (size_t)(qid >= 0 ? qid : 0) * (M * 16) + g * 16;
 #pragma unroll
-                for (int t = 0; t < T; t++) {
-                    v4i x = *(const v4i *)(lq + t * 32);
-                    x ^= (v4i){(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
-                    B[t] = qid >= 0 ? x : (v4i){0, 0, 0, 0};
-                }
-                cur_L = L;
-                cur_tile = tile;
-#ifdef RAIRS_PROFILE_CYCLES
-                { int sink = B[0].x ^ B[T - 1].w; asm volatile("" :: "v"(sink)); pc_ntile++; }
-#endif
-                PC_ADD(pc_tile);
+            for (int t = 0; t < T; t++) {
+                v4i x = *(const v4i *)(lq + t * 32);
+                x ^= (v4i){(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
+                B[t] = qid >= 0 ? x : (v4i){0, 0, 0, 0};
             }
+#ifdef RAIRS_PROFILE_CYCLES
+            { int sink = B[0].x ^ B[T - 1].w; asm volatile("" :: "v"(sink)); pc_ntile++; }
+#endif
+        }
+        PC_ADD(pc_tile);
+        // the query's bound: other waves keep lowering it, so it is looked up again for every
+        // block, one block ahead (a stale bound is only looser)
+        const int32_t *bq = a.bound + (qid >= 0 ? qid : 0);
+        int bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const uint32_t *bmq = a.bitmap + (size_t)(qid >= 0 ? qid : 0) * a.bmwords;
+        SegEntry se = v.segs[le.seg_begin + seg0];
+        uint32_t owner_bits = se.owner >= 0 ? bmq[se.owner >> 5] : 0u;
+        const uint32_t *cp = v.codes + (size_t)se.blk_begin * ND * 64 + lane;
+        uint32_t cn[ND];
+#pragma unroll
+        for (int w = 0; w < ND; w++) cn[w] = cp[w * 64];
+        for (int seg = seg0; seg < seg1; seg++) {
 #ifdef RAIRS_PROFILE_CYCLES
             pc_ntask++;
 #endif
-            const SegEntry se = v.segs[le.seg_begin + seg];
-            bool live = qid >= 0;
-            if (se.owner >= 0 && qid >= 0) {
-                // cell (owner, L) is scored through list `owner` for queries that probe it
-                uint32_t wbits = a.bitmap[(size_t)qid * a.bmwords + (se.owner >> 5)];
-                if ((wbits >> (se.owner & 31)) & 1u) live = false;
-            }
-            if (__ballot(live) != 0ull) {
-                // the query's bound: other waves keep lowering it, so it is looked up again for
-                // every block, one block ahead (a stale bound is only looser)
-                const int32_t *bq = a.bound + (live ? qid : 0);
-                int bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                const uint32_t *cp = v.codes + (size_t)se.blk_begin * ND * 64 + lane;
-                uint32_t cn[ND];
+            const bool has_next = seg + 1 < seg1;
+            const SegEntry sen = v.segs[le.seg_begin + (has_next ? seg + 1 : seg)];
+            const uint32_t *cpn = v.codes + (size_t)sen.blk_begin * ND * 64 + lane;
+            // cell (owner, L) is scored through list `owner` for queries that probe it
+            const bool live = qid >= 0 && !(se.owner >= 0 && ((owner_bits >> (se.owner & 31)) & 1u));
+            owner_bits = has_next && sen.owner >= 0 ? bmq[sen.owner >> 5] : 0u;
+            if (__ballot(live) == 0ull) {
+                // nobody needs this run; keep the prefetch chain going
+                if (has_next) {
 #pragma unroll
-                for (int w = 0; w < ND; w++) cn[w] = cp[w * 64];
+                    for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64];
+                }
+            } else {
                 for (int b = 0; b < se.nblk; b++) {
                     PC_MARK();
                     uint32_t c[ND];
 #pragma unroll
                     for (int w = 0; w < ND; w++) c[w] = cn[w];
                     const int th = live ? bound_next - bias : INT_MIN;
+                    bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     if (b + 1 < se.nblk) {             // fetch the next block while this one is scored
 #pragma unroll
                         for (int w = 0; w < ND; w++) cn[w] = cp[(size_t)(b + 1) * ND * 64 + w * 64];
-                        bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    } else if (has_next) {             // ... or the first block of the next run
+#pragma unroll
+                        for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64];
                     }
                     v16i acc;
 #pragma unroll
@@ -379,8 +390,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #ifdef RAIRS_PROFILE_CYCLES
                                 long long f0 = clock64();
 #endif
-                                stage_flush(a, sq, nstaged, lane, lc);
-                                nstaged = 0;
+                                FLUSH_STAGE();
 #ifdef RAIRS_PROFILE_CYCLES
                                 pc_flush += clock64() - f0; pc_nflush++;
 #endif
@@ -390,16 +400,14 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                     }
                 }
             }
-            seg++;
-            if (seg == le.seg_cnt) { seg = 0; tile++; }
+            se = sen;
+            cp = cpn;
         }
         // do not sit on survivors for long: their histogram counts tighten everyone's bound
-        if (nstaged >= 32) {
-            stage_flush(a, sq, nstaged, lane, lc);
-            nstaged = 0;
-        }
+        if (nstaged >= 32) FLUSH_STAGE();
+        u = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_next);
     }
-    if (nstaged > 0) stage_flush(a, sq, nstaged, lane, lc);
+    if (nstaged > 0) FLUSH_STAGE();
     if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
 #ifdef RAIRS_PROFILE_CYCLES
     if (lane == 0 && a.prof) {
@@ -542,7 +550,7 @@ bool rairs_mfma_supported(const IndexView &v)
     return v.T == 8 || v.T == 24 || v.T == 32;
 }
 
-int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
+int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev)
 {
     const int np = a.nprobe - a.p_first;
     if (np <= 0) return RAIRS_OK;
@@ -559,11 +567,12 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     hipLaunchKernelGGL(lm_count_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                        a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount);
     hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
-                       a.toff);
+                       a.toff, a.unit_list, a.unit_segs);
     hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                        a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist);
     // persistent grid: 256 compute units x 2 workgroups of 4 waves
     const dim3 grid(512);
+    if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
     switch (v.T) {
     case 8: hipLaunchKernelGGL(scan_mfma_kernel<8>, grid, dim3(WG), 0, s, v, a); break;
     case 24: hipLaunchKernelGGL(scan_mfma_kernel<24>, grid, dim3(WG), 0, s, v, a); break;
@@ -572,6 +581,7 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
         rairs_set_error("MFMA scan not built for M=%d", v.M);
         return RAIRS_EUNSUPPORTED;
     }
+    if (ev) RAIRS_HIP(hipEventRecord(ev[1], s));
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
