@@ -34,20 +34,31 @@ def log(*a):
 
 
 def ground_truth(base: np.ndarray, queries: np.ndarray, k: int):
-    """Exact kNN ids by brute force; a GPU matmul used as a tool, re-checked on a few queries."""
+    """Exact kNN ids by brute force, ties by smaller id.  A GPU matmul (used as a tool) shortlists
+    k + 54 candidates per query; they are re-ranked by direct float64 distances, and a few
+    queries are re-checked against a full float64 scan."""
     import torch
     b = torch.from_numpy(base).cuda().float()
     bn = (b * b).sum(1)
+    short = k + 54
     out = []
-    for lo in range(0, len(queries), 500):
-        q = torch.from_numpy(queries[lo:lo + 500]).cuda()
-        d2 = bn[None, :] - 2.0 * (q @ b.T)
-        out.append(torch.topk(d2, k, dim=1, largest=False).indices.cpu().numpy())
+    step = max(1, min(500, (1 << 30) // max(1, len(base))))     # keep every tensor below 2^31 elements
+    for lo in range(0, len(queries), step):
+        q = torch.from_numpy(queries[lo:lo + step]).cuda()
+        # (b @ q.T) rather than (q @ b.T): the latter returned garbage here for 10M-row b
+        d2 = bn[:, None] - 2.0 * (b @ q.T)                                   # [n][nq]
+        cand = torch.topk(d2, short, dim=0, largest=False).indices.T.contiguous()   # [nq][short]
+        diff = b[cand].double() - q.double()[:, None, :]
+        exact = (diff * diff).sum(-1)
+        cand_sorted, perm = torch.sort(cand, dim=1)                         # ties: smaller id first
+        exact = torch.gather(exact, 1, perm)
+        order = torch.sort(exact, dim=1, stable=True).indices[:, :k]
+        out.append(torch.gather(cand_sorted, 1, order).cpu().numpy())
     gt = np.concatenate(out)
     for i in range(0, len(queries), max(1, len(queries) // 5)):
         d2 = ((queries[i].astype(np.float64) - base.astype(np.float64)) ** 2).sum(1)
         kth = np.sort(d2)[k - 1]
-        assert (d2[gt[i]] <= kth * (1 + 1e-6)).all(), "ground truth check failed"
+        assert (d2[gt[i]] <= kth * (1 + 1e-9)).all(), "ground truth check failed"
     del b, bn
     torch.cuda.empty_cache()
     return gt

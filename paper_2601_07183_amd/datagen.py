@@ -6,7 +6,7 @@ the single piece of code that the CPU oracle's tests and the HIP path's tests bo
 
 Each workload is a Gaussian mixture: a vector is
 `transform(mean[c] + sigma * z + spread * z_r @ basis[c])`, i.e. every component has an isotropic
-part and (except for the tiny workload) a rank-16 part, so that neighbourhoods have a low
+part and (except for the tiny workload) a low-rank part, so that neighbourhoods have a low
 intrinsic dimension as real descriptor data does and components overlap.  Base
 vectors and queries come from the same mixture through independent streams; queries are never
 members of the base set.  Streams: seed*16 + 0 mixture parameters, + 1 base vectors, + 2 queries.
@@ -84,11 +84,13 @@ class Mixture:
             self._low_rank(g, 16, 60.0)
         elif w.kind == "dense":
             self.scale = g.uniform(0.01, 0.2, size=(d,)).astype(np.float32)
-            self.mean = g.uniform(0.0, 2.0, size=(c, d)).astype(np.float32)
-            self.sigma = 0.5
+            self.mean = (1.0 + 0.03 * g.uniform(-1.0, 1.0, size=(c, d))).astype(np.float32)
+            self.sigma = 0.05
+            self._low_rank(g, 24, 0.5)
         elif w.kind == "sphere":
-            self.mean = g.standard_normal(size=(c, d)).astype(np.float32)
-            self.sigma = 0.25
+            self.mean = (0.25 * g.standard_normal(size=(c, d))).astype(np.float32)
+            self.sigma = 0.1
+            self._low_rank(g, 24, 1.0)
         else:
             raise ValueError(w.kind)
 
