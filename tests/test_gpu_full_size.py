@@ -1,0 +1,72 @@
+"""Parity at the full sizes of the workloads, in the configuration bench.py times: the whole
+query batch goes through rairs_search; a seeded sample of queries is recomputed by the CPU oracle
+one by one and compared bit for bit; the rest is checked through properties that hold for any
+correct result."""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2601_07183_amd import datagen, index_build
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+CASES = [("sift1m", 32, 400), ("sift1m", 1, 200), ("sphere10m", 64, 150), ("gist1m", 16, 100)]
+_cache = {}
+
+
+def _workload(name):
+    if name not in _cache:
+        _cache.clear()                                   # one large index in memory at a time
+        w = datagen.WORKLOADS[name]
+        base = datagen.make_base(w)
+        q = datagen.make_queries(w)
+        hx = index_build.build_index(base, w.nlist, w.M, seed=w.seed)
+        _cache[name] = (w, base, q, hx)
+    return _cache[name]
+
+
+@pytest.mark.parametrize("name,nprobe,nsample", CASES)
+def test_full_size_against_sampled_oracle(name, nprobe, nsample):
+    from paper_2601_07183_amd import binding
+    print(f"case: workload={name} nprobe={nprobe} oracle sample={nsample}", flush=True)
+    w, base, q, hx = _workload(name)
+    ix = binding.Index(hx)
+    try:
+        dq = torch.from_numpy(q).cuda()
+        ids, dists = ix.search(dq, w.k, nprobe, w.refine_k)
+        torch.cuda.synchronize()
+        ids, dists = ids.cpu().numpy(), dists.cpu().numpy()
+        dco = ix.dco(len(q))
+        stats = ix.scan_stats()
+    finally:
+        ix.free()
+    # properties of any correct result
+    assert (ids >= 0).all() and (ids < hx.ntotal).all()           # lists are far longer than k
+    assert (np.diff(dists, axis=1) >= 0).all()
+    srt = np.sort(ids, axis=1)
+    assert (srt[:, 1:] != srt[:, :-1]).all()                      # no id twice in a row
+    tie = np.diff(dists, axis=1) == 0
+    assert (np.diff(ids, axis=1)[tie] > 0).all()                  # equal distance: smaller id first
+    a = hx.assign
+    probes_ok = 0
+    # the sampled queries, recomputed by the oracle
+    g = np.random.Generator(np.random.PCG64(7))
+    pick = np.sort(g.choice(len(q), size=min(nsample, len(q)), replace=False))
+    want = oracle.search(oracle.OracleIndex(hx), q[pick], w.k, nprobe, w.refine_k)
+    assert (ids[pick] == want.ids).all()
+    assert (np.abs(dists[pick] - want.dists) <= 1e-5 * np.abs(want.dists)).all()
+    assert (dco[pick] == want.dco).all()
+    # every returned id is a member of a list the oracle probed for that query, and its distance
+    # is the exact one (float64 check within fp32 rounding)
+    for j, i in enumerate(pick[:50]):
+        probed = np.zeros(hx.nlist, dtype=bool)
+        probed[want.probes[j]] = True
+        assert (probed[a[ids[i], 0]] | probed[a[ids[i], 1]]).all()
+        d2 = ((q[i].astype(np.float64) - base[ids[i]].astype(np.float64)) ** 2).sum(1)
+        assert np.allclose(dists[i], d2, rtol=2e-6 * np.sqrt(hx.d) + 1e-6)
+        probes_ok += 1
+    assert probes_ok > 0
+    print(f"   survivors/query={stats['survivors'] / max(1, stats['queries']):.0f} "
+          f"redone exactly={stats['redone']} dco/query={dco.mean():.0f}", flush=True)
