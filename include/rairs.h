@@ -150,8 +150,9 @@ int rairs_refine(rairs_index_t *h, const float *d_queries, const int64_t *d_cand
 
 /*
  * Which kernels SeilSearch uses.  RAIRS_SCAN_AUTO (default): the first probed list of every query
- * by the exact one-workgroup-per-query kernel, the other lists by the list-major MFMA kernel when
- * it is built for the index's M (16, 48, 64), overflowing queries redone exactly.
+ * by the exact one-workgroup-per-query kernel, the other lists by the list-major MFMA kernel
+ * (tables in registers for M = 16, 48, 64, in LDS for any other M), overflowing queries redone
+ * exactly.
  * RAIRS_SCAN_EXACT: the exact kernel for everything.  Results are identical in both modes.
  */
 enum { RAIRS_SCAN_AUTO = 0, RAIRS_SCAN_EXACT = 1 };

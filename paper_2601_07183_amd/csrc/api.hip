@@ -487,6 +487,13 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
     if ((rc = rairs_launch_scan_mfma(v, ma, s, ev))) return rc;
     if ((rc = rairs_launch_select(v, ma, s))) return rc;
+    // Second pass for queries whose survivor buffer overflowed (loose sample bound, slow start):
+    // their bound is now the converged one, so the same scan restricted to them fits.  Normally
+    // no query is flagged and these launches find no work.
+    MfmaScanArgs m2 = ma;
+    m2.only_flagged = ma.flags; m2.fixed_bound = 1;
+    if ((rc = rairs_launch_scan_mfma(v, m2, s, nullptr))) return rc;
+    if ((rc = rairs_launch_select(v, m2, s))) return rc;
     // queries whose survivor buffer overflowed are redone by the exact kernel
     ExactScanArgs fa = ea;
     fa.p_scan = nprobe; fa.sample_blocks = 0; fa.only_flagged = ma.flags; fa.surv_buf = nullptr; fa.surv_cnt = nullptr;

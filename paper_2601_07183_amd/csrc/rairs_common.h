@@ -146,6 +146,8 @@ struct MfmaScanArgs {
     uint64_t *surv_buf;           // [nq][surv_cap]
     int surv_cap;
     uint32_t *flags;              // [nq] set when the survivor buffer overflowed
+    const uint32_t *only_flagged; // second pass: only queries with a non-zero entry take part
+    int fixed_bound;              // second pass: bounds are final, no histogram work
     uint4 *log;                   // [log_chunks][256] survivor log {slot, score<<16|list, query, 0}
     uint32_t *chunk_fill;         // [log_chunks] entries written to each chunk
     uint32_t *log_cursor;         // [1] chunks handed out

@@ -37,22 +37,24 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 __global__ void lm_zero_kernel(int32_t *lcount, int nlist, uint32_t *next_task, uint32_t *surv_cnt,
                                int64_t nq, uint32_t *chunk_fill, int log_chunks, uint32_t *log_cursor,
-                               uint32_t *log_overflow)
+                               uint32_t *log_overflow, const uint32_t *only_flagged)
 {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < nlist) lcount[gid] = 0;
-    if (gid < nq) surv_cnt[gid] = 0;
+    if (gid < nq && (!only_flagged || only_flagged[gid])) surv_cnt[gid] = 0;
     if (gid < log_chunks) chunk_fill[gid] = 0;
     if (gid == 0) { *next_task = 0; *log_cursor = 0; *log_overflow = 0; }
 }
 
 __global__ void lm_count_kernel(const int32_t *__restrict__ probe_ids, int64_t nq, int nprobe,
-                                int p_first, int nlist, int32_t *lcount)
+                                int p_first, int nlist, int32_t *lcount,
+                                const uint32_t *__restrict__ only_flagged)
 {
     const int np = nprobe - p_first;
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= nq * np) return;
     int64_t q = gid / np;
+    if (only_flagged && only_flagged[q] == 0) return;
     int p = p_first + (int)(gid % np);
     int L = probe_ids[q * nprobe + p];
     if (L >= 0 && L < nlist) atomicAdd(&lcount[L], 1);
@@ -113,12 +115,14 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
 
 __global__ void lm_fill_kernel(const int32_t *__restrict__ probe_ids, int64_t nq, int nprobe,
                                int p_first, int nlist, const int32_t *__restrict__ loff,
-                               int32_t *lcursor, int32_t *qlist)
+                               int32_t *lcursor, int32_t *qlist,
+                               const uint32_t *__restrict__ only_flagged)
 {
     const int np = nprobe - p_first;
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= nq * np) return;
     int64_t q = gid / np;
+    if (only_flagged && only_flagged[q] == 0) return;
     int p = p_first + (int)(gid % np);
     int L = probe_ids[q * nprobe + p];
     if (L >= 0 && L < nlist) {
@@ -195,10 +199,11 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
             const uint32_t sl = sq.score_list[i], range = sq.lrange[i];
             if (room)
                 a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint4(sq.slot[i], sl, (uint32_t)qid, 0u);
-            atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + ((sl >> 16) * RAIRS_HIST_BINS) / (range + 1u)], 1u);
+            if (!a.fixed_bound)
+                atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + ((sl >> 16) * RAIRS_HIST_BINS) / (range + 1u)], 1u);
         }
     }
-    if (refresh && lane < n && (lane & 3) == 0) {
+    if (refresh && !a.fixed_bound && lane < n && (lane & 3) == 0) {
         // every fourth entry of the first row also refreshes its query's bound.  A stale
         // histogram only gives a looser bound; the bound itself only ever shrinks.
         const int qid = sq.qid[lane];
@@ -469,6 +474,7 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a)
     __shared__ uint32_t s_prefix, s_need, s_kept;
     const int tid = threadIdx.x;
     const int64_t q = blockIdx.x;
+    if (a.only_flagged && a.only_flagged[q] == 0) return;      // settled in the first pass
     const uint32_t n = a.surv_cnt[q];
     if (n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) {
         if (tid == 0) a.flags[q] = 1;       // the exact kernel redoes this query
@@ -545,9 +551,153 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a)
     }
 }
 
+// ---- the same scan with the tile's tables in LDS (any M up to 256) ----------------------------
+//
+// For tables too large for registers (M = 240: 30 KB per query pair of lanes) the four waves of a
+// workgroup share one tile: its tables sit in LDS as [K-step][lane] 16-byte operands, zero beyond
+// the last subspace, and the waves take the unit's blocks round robin.  Each MFMA then reads both
+// operands from LDS (one-hot row and table row), which holds it to about half the matrix-core
+// rate; survivors, bounds and the log work exactly as in scan_mfma_kernel.
+__global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaScanArgs a)
+{
+    extern __shared__ __align__(16) unsigned char dyn_lds[];
+    __shared__ StageQueue stage[WG / 64];
+    __shared__ v4i onehot[16];
+    __shared__ uint32_t s_unit;
+    const int ND = v.nd, KS = ND * 8;                   // K-steps incl. zero padding
+    v4i *Bl = (v4i *)dyn_lds;                           // [KS][64]
+    if (threadIdx.x < 16) {
+        v4i r = {0, 0, 0, 0};
+        const int sh = 1 << ((threadIdx.x & 3) * 8);
+        if ((threadIdx.x >> 2) == 0) r.x = sh;
+        if ((threadIdx.x >> 2) == 1) r.y = sh;
+        if ((threadIdx.x >> 2) == 2) r.z = sh;
+        if ((threadIdx.x >> 2) == 3) r.w = sh;
+        onehot[threadIdx.x] = r;
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5, j = lane & 31;
+    StageQueue &sq = stage[wave];
+    const int M = v.M, T = v.T;
+    const int bias = 128 * M;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    int nstaged = 0;
+    uint32_t nflush = 0;
+    LogCursor lc;
+    {
+        uint32_t c0 = 0;
+        if (lane == 0) c0 = atomicAdd(a.log_cursor, 2u);
+        c0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)c0);
+        lc.chunk = c0;
+        lc.next_chunk = c0 + 1;
+        lc.used = 0;
+    }
+    const uint32_t nunits = (uint32_t)a.toff[v.nlist];
+    for (;;) {
+        __syncthreads();                               // everyone is done with the previous tile
+        if (threadIdx.x == 0) s_unit = atomicAdd(a.next_task, 1u);
+        __syncthreads();
+        const uint32_t u = s_unit;
+        if (u >= nunits) break;                        // uniform for the workgroup; the counter only grows
+        const int L = a.unit_list[u];
+        const ListEntry le = v.lists[L];
+        const int rem = (int)u - a.toff[L];
+        const int parts = (le.seg_cnt + a.unit_segs - 1) / a.unit_segs;
+        const int tile = rem / parts;
+        const int seg0 = (rem % parts) * a.unit_segs;
+        const int seg1 = seg0 + a.unit_segs < le.seg_cnt ? seg0 + a.unit_segs : le.seg_cnt;
+        const int base = a.loff[L], nql = a.loff[L + 1] - base;
+        // tables of the tile into LDS: operand (t, lane (j, g)) = lut[q_j][2t+g][0..15] - 128
+        for (int e = threadIdx.x; e < KS * 64; e += WG) {
+            const int t = e >> 6, ln = e & 63, jj = ln & 31, gg = ln >> 5;
+            const int qi = tile * 32 + jj;
+            v4i x = {0, 0, 0, 0};
+            if (t < T && qi < nql) {
+                const int qq = a.qlist[base + qi];
+                x = *(const v4i *)(a.lut + (size_t)qq * (M * 16) + (size_t)(2 * t + gg) * 16);
+                x ^= (v4i){(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
+            }
+            Bl[e] = x;
+        }
+        const int qi = tile * 32 + j;
+        const int qid = qi < nql ? a.qlist[base + qi] : -1;
+        const uint32_t tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
+        const uint32_t range = tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0;
+        const int32_t *bq = a.bound + (qid >= 0 ? qid : 0);
+        const uint32_t *bmq = a.bitmap + (size_t)(qid >= 0 ? qid : 0) * a.bmwords;
+        __syncthreads();
+        for (int seg = seg0; seg < seg1; seg++) {
+            const SegEntry se = v.segs[le.seg_begin + seg];
+            // cell (owner, L) is scored through list `owner` for queries that probe it
+            bool live = qid >= 0;
+            if (se.owner >= 0 && qid >= 0 && ((bmq[se.owner >> 5] >> (se.owner & 31)) & 1u)) live = false;
+            if (__ballot(live) == 0ull) continue;
+            for (int b = wave; b < se.nblk; b += WG / 64) {
+                const int th = live ? __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - bias
+                                    : INT_MIN;
+                const uint32_t *cp = v.codes + (size_t)(se.blk_begin + b) * ND * 64 + lane;
+                v16i acc;
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[r] = 0;
+                uint32_t c = cp[0];
+                for (int w = 0; w < ND; w++) {
+                    const uint32_t cnext = w + 1 < ND ? cp[(size_t)(w + 1) * 64] : 0u;
+                    const v4i *Bw = Bl + (size_t)w * 8 * 64 + lane;
+#pragma unroll
+                    for (int n = 0; n < 8; n++) {
+                        const uint32_t nib = (c >> (4 * n)) & 15u;
+                        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(onehot[nib], Bw[n * 64], acc, 0, 0, 0);
+                    }
+                    c = cnext;
+                }
+                uint32_t pm = 0;
+#pragma unroll
+                for (int r = 0; r < 16; r++) pm |= acc[r] <= th ? (1u << r) : 0u;
+                if (__ballot(pm != 0u) != 0ull) {
+                    const uint32_t slot0 = (uint32_t)(se.blk_begin + b) * 32u + 4u * g;
+                    if (b == se.nblk - 1 && se.tail_valid < 32) {
+#pragma unroll
+                        for (int r = 0; r < 16; r++)
+                            if (8 * (r >> 2) + 4 * g + (r & 3) >= se.tail_valid) pm &= ~(1u << r);
+                    }
+                    for (;;) {
+                        const bool has = pm != 0u;
+                        const unsigned long long mask = __ballot(has);
+                        if (mask == 0ull) break;
+                        if (has) {
+                            const int r = __builtin_ctz(pm);
+                            pm &= pm - 1u;
+                            int sc = acc[0];
+#pragma unroll
+                            for (int k = 1; k < 16; k++) sc = r == k ? acc[k] : sc;
+                            const int pos = nstaged + __popcll(mask & lt_mask);
+                            sq.slot[pos] = slot0 + 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);
+                            sq.score_list[pos] = ((uint32_t)(sc + bias) << 16) | (uint32_t)L;
+                            sq.qid[pos] = qid;
+                            sq.lrange[pos] = range;
+                        }
+                        nstaged += __popcll(mask);
+                        if (nstaged > STAGE_CAP - 64) {
+                            stage_flush(a, sq, nstaged, lane, lc, (nflush & 1u) == 0u);
+                            nstaged = 0;
+                            nflush++;
+                        }
+                    }
+                }
+            }
+        }
+        if (nstaged >= 32) {
+            stage_flush(a, sq, nstaged, lane, lc, (nflush & 1u) == 0u);
+            nstaged = 0;
+            nflush++;
+        }
+    }
+    if (nstaged > 0) stage_flush(a, sq, nstaged, lane, lc, true);
+    if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
+}
+
 bool rairs_mfma_supported(const IndexView &v)
 {
-    return v.T == 8 || v.T == 24 || v.T == 32;
+    return v.T >= 1 && v.nd * 8 * 64 * 16 <= 128 * 1024;    // tables of a tile must fit 128 KB of LDS
 }
 
 int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev)
@@ -563,13 +713,14 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     nz = nz > a.log_chunks ? nz : a.log_chunks;
     hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
                        v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
-                       a.log_cursor, a.log_overflow);
+                       a.log_cursor, a.log_overflow, a.only_flagged);
     hipLaunchKernelGGL(lm_count_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
-                       a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount);
+                       a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount, a.only_flagged);
     hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
                        a.toff, a.unit_list, a.unit_segs);
     hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
-                       a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist);
+                       a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist,
+                       a.only_flagged);
     // persistent grid: 256 compute units x 2 workgroups of 4 waves
     const dim3 grid(512);
     if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
@@ -577,9 +728,13 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     case 8: hipLaunchKernelGGL(scan_mfma_kernel<8>, grid, dim3(WG), 0, s, v, a); break;
     case 24: hipLaunchKernelGGL(scan_mfma_kernel<24>, grid, dim3(WG), 0, s, v, a); break;
     case 32: hipLaunchKernelGGL(scan_mfma_kernel<32>, grid, dim3(WG), 0, s, v, a); break;
-    default:
-        rairs_set_error("MFMA scan not built for M=%d", v.M);
-        return RAIRS_EUNSUPPORTED;
+    default: {
+        // tables in LDS: one workgroup per compute unit
+        const size_t lds = (size_t)v.nd * 8 * 64 * 16;
+        RAIRS_HIP(hipFuncSetAttribute((const void *)scan_mfma_lds_kernel,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(scan_mfma_lds_kernel, dim3(256), dim3(WG), lds, s, v, a);
+    }
     }
     if (ev) RAIRS_HIP(hipEventRecord(ev[1], s));
     RAIRS_HIP(hipGetLastError());
