@@ -38,7 +38,9 @@ def ground_truth(base: np.ndarray, queries: np.ndarray, k: int):
     k + 54 candidates per query; they are re-ranked by direct float64 distances, and a few
     queries are re-checked against a full float64 scan."""
     import torch
-    b = torch.from_numpy(base).cuda().float()
+    b = torch.empty((len(base), base.shape[1]), dtype=torch.float32, device="cuda")
+    for lo in range(0, len(base), 1 << 22):               # uint8 bases are converted piecewise
+        b[lo:lo + (1 << 22)] = torch.from_numpy(base[lo:lo + (1 << 22)]).cuda().float()
     bn = (b * b).sum(1)
     short = k + 54
     out = []
@@ -56,9 +58,15 @@ def ground_truth(base: np.ndarray, queries: np.ndarray, k: int):
         out.append(torch.gather(cand_sorted, 1, order).cpu().numpy())
     gt = np.concatenate(out)
     for i in range(0, len(queries), max(1, len(queries) // 5)):
-        d2 = ((queries[i].astype(np.float64) - base.astype(np.float64)) ** 2).sum(1)
-        kth = np.sort(d2)[k - 1]
-        assert (d2[gt[i]] <= kth * (1 + 1e-9)).all(), "ground truth check failed"
+        d2 = (b.double() - torch.from_numpy(queries[i]).cuda().double()[None, :]).pow(2).sum(1) \
+            if len(base) <= (1 << 24) else None
+        if d2 is None:                                        # very large base: check in pieces
+            parts = [(b[lo:lo + (1 << 24)].double() - torch.from_numpy(queries[i]).cuda().double()[None, :])
+                     .pow(2).sum(1) for lo in range(0, len(base), 1 << 24)]
+            d2 = torch.cat(parts)
+        kth = torch.sort(d2).values[k - 1].item()
+        assert (d2[torch.from_numpy(gt[i]).cuda()] <= kth * (1 + 1e-9)).all().item(), \
+            "ground truth check failed"
     del b, bn
     torch.cuda.empty_cache()
     return gt
@@ -81,6 +89,11 @@ def main():
     ap.add_argument("--target-recall", type=float, default=0.9)
     ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0 = auto)")
     ap.add_argument("--sweep-out", default="")
+    ap.add_argument("--base-size", type=int, default=0,
+                    help="use the workload's generator and parameters at this smaller base size "
+                         "(for profiling; the headline numbers are quoted at full size)")
+    ap.add_argument("--recall-queries", type=int, default=0,
+                    help="measure recall on the first N queries only (0 = all); for very large bases")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="only run a device-to-device copy of this many bytes three times (to "
                          "calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -106,6 +119,8 @@ def main():
     binding.load()
 
     w = datagen.WORKLOADS[args.workload]
+    if args.base_size:
+        w = datagen.scaled(w, args.base_size)
     t0 = time.time()
     base = datagen.make_base(w)
     queries = datagen.make_queries(w)
@@ -117,8 +132,9 @@ def main():
     log(f"[bench] index built in {time.time() - t0:.1f}s: nblocks={hx.nblocks} nrefs={hx.nrefs} "
         f"vectors in shared blocks={shared_frac:.3f}")
     t0 = time.time()
-    gt = ground_truth(base.astype(np.float32), queries, w.k)
-    log(f"[bench] ground truth in {time.time() - t0:.1f}s")
+    nrec = min(len(queries), args.recall_queries) if args.recall_queries else len(queries)
+    gt = ground_truth(base, queries[:nrec], w.k)
+    log(f"[bench] ground truth for {nrec} queries in {time.time() - t0:.1f}s")
 
     ix = binding.Index(hx)
     code_bytes, total_bytes = ix.bytes()
@@ -147,7 +163,7 @@ def main():
     chosen = args.nprobe or None
     for nprobe in ((args.nprobe,) if args.nprobe else w.nprobes):
         run(nprobe, 1)
-        rec = recall_at_k(out_ids.cpu().numpy(), gt)
+        rec = recall_at_k(out_ids.cpu().numpy()[:nrec], gt)
         sec, stage = run(nprobe, 3, profile=True)
         dco = ix.dco(nq)
         st = ix.scan_stats()

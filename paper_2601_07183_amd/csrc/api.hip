@@ -386,11 +386,11 @@ static int check_k(int k, int refine_k)
     return RAIRS_OK;
 }
 
-// Queries per internal pass so that the distance matrix stays within ~1 GiB.
+// Queries per internal pass so that the distance matrix and buffers stay within ~4 GiB.
 static int64_t pass_size(const IndexView &v, int64_t nq)
 {
     int64_t per_q = (int64_t)v.nlist * 4 + 65536;
-    int64_t cap = (1ll << 30) / per_q;
+    int64_t cap = (4ll << 30) / per_q;
     if (cap < 256) cap = 256;
     return nq < cap ? nq : cap;
 }
