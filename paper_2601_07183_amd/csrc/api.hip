@@ -444,10 +444,10 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     memset(&ea, 0, sizeof(ea));
     ea.lut = lut; ea.probe_ids = probe_ids; ea.bitmap = bitmap; ea.bmwords = w.bmwords;
     ea.nprobe = nprobe; ea.refine_k = refine_k; ea.dco = dco;
+    ea.cand_ids = cand_ids; ea.cand_score = cand_score;
     const bool mfma = rairs_mfma_supported(v) && !h->force_exact;
     h->last_pass_n = 0;
     if (!mfma) {
-        ea.p_scan = nprobe; ea.cand_ids = cand_ids; ea.cand_score = cand_score;
         if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
         rc = rairs_launch_scan_exact(v, ea, n, s);
         if (ev) RAIRS_HIP(hipEventRecord(ev[1], s));
@@ -480,11 +480,12 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     ma.prof = (long long *)(ws + w.prof);
     h->last_prof_off = w.prof;
 #endif
-    // bound of every query from a sample (the head of its first list); also the DCO of all probes
+    // bound of every query from a sample (the head of its first list), and the DCO of all probes
     ma.p_first = 0;
-    ea.sample_blocks = RAIRS_SAMPLE_BLOCKS; ea.tau = (int32_t *)(ws + w.tau);
-    ea.bound = (int32_t *)(ws + w.bound); ma.bound = ea.bound;
-    if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
+    ma.bound = (int32_t *)(ws + w.bound);
+    if ((rc = rairs_launch_sample_bound(v, lut, probe_ids, nprobe, refine_k, RAIRS_SAMPLE_BLOCKS, n,
+                                        (int32_t *)(ws + w.tau), ma.bound, s))) return rc;
+    if (dco && (rc = rairs_launch_dco(v, probe_ids, bitmap, w.bmwords, nprobe, n, dco, s))) return rc;
     if ((rc = rairs_launch_scan_mfma(v, ma, s, ev))) return rc;
     if ((rc = rairs_launch_select(v, ma, s))) return rc;
     // Second pass for queries whose survivor buffer overflowed (loose sample bound, slow start):
@@ -495,10 +496,8 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     if ((rc = rairs_launch_scan_mfma(v, m2, s, nullptr))) return rc;
     if ((rc = rairs_launch_select(v, m2, s))) return rc;
     // queries whose survivor buffer overflowed are redone by the exact kernel
-    ExactScanArgs fa = ea;
-    fa.p_scan = nprobe; fa.sample_blocks = 0; fa.only_flagged = ma.flags; fa.surv_buf = nullptr; fa.surv_cnt = nullptr;
-    fa.tau = nullptr; fa.bound = nullptr; fa.hist = nullptr; fa.cand_ids = cand_ids; fa.cand_score = cand_score;
-    return rairs_launch_scan_exact(v, fa, n, s);
+    ea.only_flagged = ma.flags;
+    return rairs_launch_scan_exact(v, ea, n, s);
 }
 
 extern "C" int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t *d_probe_ids,

@@ -106,21 +106,18 @@ struct ExactScanArgs {
     const int32_t *probe_ids;     // [nq][nprobe]
     const uint32_t *bitmap;       // [nq][bmwords]
     int bmwords, nprobe, refine_k;
-    int p_scan;                   // scan probes [0, p_scan); the rest only enter the DCO count
-    int sample_blocks;            // > 0: bound-only mode -- score just the first sample_blocks own
-                                  // blocks of probe 0 and write tau (no candidates, no survivors)
     const uint32_t *only_flagged; // if set, queries with a zero flag are skipped
-    int64_t *cand_ids;            // [nq][refine_k]  (when surv_buf is null)
+    int64_t *cand_ids;            // [nq][refine_k]
     int32_t *cand_score;          // [nq][refine_k], may be null
-    uint64_t *surv_buf;           // [nq][surv_cap]: receive the queue instead of cand_ids
-    uint32_t *surv_cnt;           // [nq]
-    int32_t *tau;                 // [nq] largest score that can still matter
-    int32_t *bound;               // [nq] receives the same value in sample mode (may be null)
-    uint32_t *hist;               // [nq][RAIRS_HIST_BINS] survivor counts by score bin (see scan_mfma.hip)
-    int surv_cap;
     int64_t *dco;                 // [nq], may be null
 };
 int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s);
+// bound of every query from the head of its first probed list; DCO of every query
+int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
+                              int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,
+                              int32_t *bound, hipStream_t s);
+int rairs_launch_dco(const IndexView &v, const int32_t *probe_ids, const uint32_t *bitmap, int bmwords,
+                     int nprobe, int64_t nq, int64_t *dco, hipStream_t s);
 
 // list-major MFMA scan (scan_mfma.hip)
 struct MfmaScanArgs {

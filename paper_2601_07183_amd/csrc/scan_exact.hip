@@ -1,7 +1,7 @@
 // Exact SEIL scan with a bounded top-bigK queue, one workgroup per query (SeilSearch, Alg. 5,
-// with rqueue).  Used for the first probed list of every query (which also yields the score bound
-// for the MFMA scan), as the whole scan for table shapes the MFMA kernel is not built for, and as
-// the fallback for queries whose survivor buffer overflowed.
+// with rqueue).  Used as the whole scan for table shapes the MFMA kernel is not built for and as
+// the fallback for queries whose survivor buffer overflowed twice.  Two small helpers of the MFMA
+// scan live here too: the bound from a sample of each query's first list, and the DCO count.
 //
 // listVisited is replaced by the order-free equivalent over the query's probe bitmap P:
 //   reference entry (owner i) of list j is scanned  iff  i not in P;
@@ -72,44 +72,19 @@ __global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanAr
     if (tid == 0) { sh.tau = ~0ull; sh.cnt = 0; sh.dco = 0; }
     __syncthreads();
 
-    // items that the probes beyond p_scan will score (they are scanned by another kernel):
-    // every valid slot of the list's own blocks plus 32 per block of each unskipped reference
     unsigned long long my_dco = 0;
-    for (int p = (a.sample_blocks > 0 ? 0 : a.p_scan) + tid; p < nprobe; p += WG) {
-        const int L = a.probe_ids[(size_t)qi * nprobe + p];
-        if (L < 0 || L >= v.nlist) continue;
-        const ListEntry le = v.lists[L];
-        unsigned long long c = (unsigned long long)le.valid_items;
-        for (int r = 0; r < le.ref_cnt; r++) {
-            const RefEntry re = v.refs[le.ref_begin + r];
-            if (!((sh.bm[re.owner >> 5] >> (re.owner & 31)) & 1u)) c += 32ull * re.nblocks;
-        }
-        my_dco += c;
-    }
-    if (my_dco) atomicAdd(&sh.dco, my_dco);
-    my_dco = 0;
-
-    const bool sample = a.sample_blocks > 0;
-    const int p_scan = sample ? 1 : (a.p_scan < nprobe ? a.p_scan : nprobe);
-    for (int p = 0; p < p_scan; p++) {
+    for (int p = 0; p < nprobe; p++) {
         const int L = a.probe_ids[(size_t)qi * nprobe + p];
         if (L < 0 || L >= v.nlist) continue;              // caller-supplied ids: never index with them unchecked
         const ListEntry le = v.lists[L];
         // segment -1: the list's own blocks; segments 0..ref_cnt-1: its reference entries
-        const int nseg = sample ? 0 : le.ref_cnt;
-        for (int seg = -1; seg < nseg; seg++) {
+        for (int seg = -1; seg < le.ref_cnt; seg++) {
             int64_t begin;
             int cnt, misc_from;
             if (seg < 0) {
                 begin = le.blk_begin;
                 cnt = le.shared_cnt + le.misc_cnt;
                 misc_from = le.shared_cnt;
-                if (sample) {
-                    // any valid item of the list's own blocks is a distinct member of the probed
-                    // set, duplicate rule or not: enough for a bound
-                    cnt = cnt < a.sample_blocks ? cnt : a.sample_blocks;
-                    misc_from = cnt;
-                }
             } else {
                 const RefEntry re = v.refs[le.ref_begin + seg];
                 if ((sh.bm[re.owner >> 5] >> (re.owner & 31)) & 1u) continue;   // scanned via owner
@@ -154,35 +129,11 @@ __global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanAr
     }
     scan_prune(sh, refine_k);
     const int n = (int)sh.cnt;
-    if (sample) {
-        if (tid == 0) {
-            const int32_t t = n == refine_k ? (int32_t)(sh.buf[refine_k - 1] >> 32) : 0xFFFF;
-            a.tau[qi] = t;
-            if (a.bound) a.bound[qi] = t;
-        }
-        my_dco = 0;                                  // the sampled blocks are scored again, and counted, by the main scan
-    } else if (a.surv_buf) {
-        // hand the queue over to the MFMA scan: its entries seed the query's survivor buffer and
-        // the bigK-th smallest score bounds what any other item needs to reach
-        const uint32_t tau0 = n == refine_k ? (uint32_t)(sh.buf[refine_k - 1] >> 32) : 0xFFFFu;
-        const uint32_t range = tau0 == 0xFFFFu ? 255u * (uint32_t)v.M : tau0;
-        for (int i = tid; i < n; i += WG) {
-            uint64_t key = sh.buf[i];
-            a.surv_buf[(size_t)qi * a.surv_cap + i] = key;
-            uint32_t bin = (((uint32_t)(key >> 32)) * RAIRS_HIST_BINS) / (range + 1u);
-            atomicAdd(&a.hist[(size_t)qi * RAIRS_HIST_BINS + bin], 1u);
-        }
-        if (tid == 0) {
-            a.surv_cnt[qi] = (uint32_t)n;
-            a.tau[qi] = (int32_t)tau0;
-        }
-    } else {
-        for (int i = tid; i < refine_k; i += WG) {
-            uint64_t key = sh.buf[i];
-            bool ok = i < n;
-            a.cand_ids[(size_t)qi * refine_k + i] = ok ? (int64_t)(uint32_t)key : -1;
-            if (a.cand_score) a.cand_score[(size_t)qi * refine_k + i] = ok ? (int32_t)(key >> 32) : -1;
-        }
+    for (int i = tid; i < refine_k; i += WG) {
+        uint64_t key = sh.buf[i];
+        bool ok = i < n;
+        a.cand_ids[(size_t)qi * refine_k + i] = ok ? (int64_t)(uint32_t)key : -1;
+        if (a.cand_score) a.cand_score[(size_t)qi * refine_k + i] = ok ? (int32_t)(key >> 32) : -1;
     }
     if (a.dco) {
         if (lane == 0 && my_dco) atomicAdd(&sh.dco, my_dco);
@@ -194,6 +145,129 @@ __global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanAr
 int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s)
 {
     hipLaunchKernelGGL(scan_exact_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, a);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// ---- bound from a sample ------------------------------------------------------------------------
+//
+// tau[q] = bigK-th smallest score among the items of the first `sample_blocks` own blocks of the
+// query's first probed list (0xFFFF when they hold fewer than bigK items).  Any valid item there
+// is a distinct member of the probed set, duplicate rule or not, so the bigK best of the whole
+// probed set all score <= tau.  One wave per query; the sample's scores stay in registers and the
+// rank is found by bisection on the 16 score bits with wave ballots.
+#define SAMPLE_MAX_BLOCKS 16
+__global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uint8_t *__restrict__ lut,
+                                                          const int32_t *__restrict__ probe_ids,
+                                                          int nprobe, int refine_k, int sample_blocks,
+                                                          int64_t nq, int32_t *__restrict__ tau,
+                                                          int32_t *__restrict__ bound)
+{
+    __shared__ __align__(16) uint8_t lut_s[WG / 64][RAIRS_MAX_M * 16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+    const int64_t qi0 = (int64_t)blockIdx.x * (WG / 64) + wave;
+    const int64_t qi = qi0 < nq ? qi0 : nq - 1;          // surplus waves redo the last query
+    {
+        const uint4 *src = (const uint4 *)(lut + (size_t)qi * v.M * 16);
+        uint4 *dst = (uint4 *)lut_s[wave];
+        for (int i = lane; i < v.M; i += 64) dst[i] = src[i];
+    }
+    __syncthreads();
+    const uint8_t *lq = lut_s[wave];
+    const int L = probe_ids[(size_t)qi * nprobe];
+    int cnt = 0;
+    int64_t begin = 0;
+    if (L >= 0 && L < v.nlist) {
+        const ListEntry le = v.lists[L];
+        begin = le.blk_begin;
+        cnt = le.shared_cnt + le.misc_cnt;
+        cnt = cnt < sample_blocks ? cnt : sample_blocks;
+    }
+    uint32_t sc[SAMPLE_MAX_BLOCKS];
+    uint32_t nvalid = 0;
+#pragma unroll
+    for (int b = 0; b < SAMPLE_MAX_BLOCKS; b++) {
+        sc[b] = 0xFFFFFFFFu;
+        if (b < cnt) {                                  // wave-uniform
+            const int64_t blk = begin + b;
+            const uint32_t *cp = v.codes + (size_t)blk * v.nd * 64 + lane;
+            uint32_t part = 0;
+            for (int w = 0; w < v.nd; w++) {
+                const uint32_t c = cp[(size_t)w * 64];
+                const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
+                for (int n = 0; n < tmax; n++) {
+                    const int m = 2 * (8 * w + n) + g;
+                    part += lq[m * 16 + ((c >> (4 * n)) & 15u)];
+                }
+            }
+            const uint32_t acc = part + (uint32_t)__shfl_xor((int)part, 32);
+            const bool valid = lane < 32 && v.ids[(size_t)blk * 32 + lane] != RAIRS_EMPTY_ID;
+            if (valid) sc[b] = acc;
+            nvalid += (uint32_t)__popcll(__ballot(valid));
+        }
+    }
+    uint32_t t = 0xFFFFu;
+    if (nvalid >= (uint32_t)refine_k) {
+        // largest t with fewer than bigK scores below it == the bigK-th smallest score
+        t = 0;
+        for (int bit = 15; bit >= 0; bit--) {
+            const uint32_t cand = t | (1u << bit);
+            uint32_t below = 0;
+#pragma unroll
+            for (int b = 0; b < SAMPLE_MAX_BLOCKS; b++) below += (uint32_t)__popcll(__ballot(sc[b] < cand));
+            if (below < (uint32_t)refine_k) t = cand;
+        }
+    }
+    if (lane == 0 && qi0 < nq) {
+        tau[qi] = (int32_t)t;
+        if (bound) bound[qi] = (int32_t)t;
+    }
+}
+
+int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
+                              int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,
+                              int32_t *bound, hipStream_t s)
+{
+    if (sample_blocks > SAMPLE_MAX_BLOCKS) sample_blocks = SAMPLE_MAX_BLOCKS;
+    hipLaunchKernelGGL(sample_bound_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
+                       0, s, v, lut, probe_ids, nprobe, refine_k, sample_blocks, nq, tau, bound);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// ---- DCO of a query (distance computations of the scan, Section 6.1) ----------------------------
+//
+// Every valid slot of the own blocks of each probed list, plus 32 per block of each reference
+// entry whose owner is not probed.  One wave per query, lanes over the probes.
+__global__ __launch_bounds__(WG) void dco_kernel(IndexView v, const int32_t *__restrict__ probe_ids,
+                                                 const uint32_t *__restrict__ bitmap, int bmwords,
+                                                 int nprobe, int64_t nq, int64_t *__restrict__ dco)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + (threadIdx.x >> 6);
+    if (qi >= nq) return;
+    const uint32_t *bm = bitmap + (size_t)qi * bmwords;
+    unsigned long long c = 0;
+    for (int p = lane; p < nprobe; p += 64) {
+        const int L = probe_ids[(size_t)qi * nprobe + p];
+        if (L < 0 || L >= v.nlist) continue;
+        const ListEntry le = v.lists[L];
+        c += (unsigned long long)le.valid_items;
+        for (int r = 0; r < le.ref_cnt; r++) {
+            const RefEntry re = v.refs[le.ref_begin + r];
+            if (!((bm[re.owner >> 5] >> (re.owner & 31)) & 1u)) c += 32ull * re.nblocks;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) c += (unsigned long long)__shfl_xor((long long)c, off);
+    if (lane == 0) dco[qi] = (int64_t)c;
+}
+
+int rairs_launch_dco(const IndexView &v, const int32_t *probe_ids, const uint32_t *bitmap, int bmwords,
+                     int nprobe, int64_t nq, int64_t *dco, hipStream_t s)
+{
+    hipLaunchKernelGGL(dco_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG), 0, s, v,
+                       probe_ids, bitmap, bmwords, nprobe, nq, dco);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }

@@ -35,15 +35,18 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 // ---- grouping queries by list ----------------------------------------------------------------
 
+// The scanning waves start on unit and log chunks numbered by their own index (a second chunk each
+// at index + nwaves), so the counters start behind those.
 __global__ void lm_zero_kernel(int32_t *lcount, int nlist, uint32_t *next_task, uint32_t *surv_cnt,
                                int64_t nq, uint32_t *chunk_fill, int log_chunks, uint32_t *log_cursor,
-                               uint32_t *log_overflow, const uint32_t *only_flagged)
+                               uint32_t *log_overflow, const uint32_t *only_flagged,
+                               uint32_t first_task, uint32_t first_chunk)
 {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < nlist) lcount[gid] = 0;
     if (gid < nq && (!only_flagged || only_flagged[gid])) surv_cnt[gid] = 0;
     if (gid < log_chunks) chunk_fill[gid] = 0;
-    if (gid == 0) { *next_task = 0; *log_cursor = 0; *log_overflow = 0; }
+    if (gid == 0) { *next_task = first_task; *log_cursor = first_chunk; *log_overflow = 0; }
 }
 
 __global__ void lm_count_kernel(const int32_t *__restrict__ probe_ids, int64_t nq, int nprobe,
@@ -129,6 +132,79 @@ __global__ void lm_fill_kernel(const int32_t *__restrict__ probe_ids, int64_t nq
         int pos = atomicAdd(&lcursor[L], 1);
         qlist[loff[L] + pos] = (int32_t)q;
     }
+}
+
+// The same two steps for directories of up to LM_LDS_NLIST lists: a workgroup first groups its
+// LM_PAIRS (query, probe) pairs by list in LDS and then touches each list's global counter once,
+// instead of once per pair (a list is probed by hundreds of queries of a batch).
+#define LM_PAIRS 4096
+#define LM_LDS_NLIST 8192
+__global__ __launch_bounds__(256) void lm_count_lds_kernel(const int32_t *__restrict__ probe_ids,
+                                                           int64_t nq, int nprobe, int p_first,
+                                                           int nlist, int32_t *lcount,
+                                                           const uint32_t *__restrict__ only_flagged,
+                                                           int qb)
+{
+    extern __shared__ int32_t lm_hist[];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < nlist; i += 256) lm_hist[i] = 0;
+    __syncthreads();
+    const int np = nprobe - p_first;
+    const int64_t q0 = (int64_t)blockIdx.x * qb;
+    const int pairs = qb * np;
+    for (int i = tid; i < pairs; i += 256) {
+        const int64_t q = q0 + i / np;
+        if (q >= nq || (only_flagged && only_flagged[q] == 0)) continue;
+        const int L = probe_ids[q * nprobe + p_first + i % np];
+        if (L >= 0 && L < nlist) atomicAdd(&lm_hist[L], 1);
+    }
+    __syncthreads();
+    for (int i = tid; i < nlist; i += 256) {
+        const int c = lm_hist[i];
+        if (c) atomicAdd(&lcount[i], c);
+    }
+}
+
+__global__ __launch_bounds__(256) void lm_fill_lds_kernel(const int32_t *__restrict__ probe_ids,
+                                                          int64_t nq, int nprobe, int p_first,
+                                                          int nlist, const int32_t *__restrict__ loff,
+                                                          int32_t *lcursor, int32_t *qlist,
+                                                          const uint32_t *__restrict__ only_flagged,
+                                                          int qb)
+{
+    extern __shared__ int32_t lm_hist[];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < nlist; i += 256) lm_hist[i] = 0;
+    __syncthreads();
+    const int np = nprobe - p_first;
+    const int64_t q0 = (int64_t)blockIdx.x * qb;
+    const int pairs = qb * np;                         // <= LM_PAIRS
+    int myL[LM_PAIRS / 256], myr[LM_PAIRS / 256];
+#pragma unroll
+    for (int k = 0; k < LM_PAIRS / 256; k++) {
+        const int i = tid + 256 * k;
+        myL[k] = -1;
+        myr[k] = 0;
+        if (i < pairs) {
+            const int64_t q = q0 + i / np;
+            if (q < nq && !(only_flagged && only_flagged[q] == 0)) {
+                const int L = probe_ids[q * nprobe + p_first + i % np];
+                if (L >= 0 && L < nlist) {
+                    myL[k] = L;
+                    myr[k] = atomicAdd(&lm_hist[L], 1);        // rank within this workgroup
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < nlist; i += 256) {
+        const int c = lm_hist[i];
+        if (c) lm_hist[i] = loff[i] + atomicAdd(&lcursor[i], c);   // where this workgroup's run starts
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < LM_PAIRS / 256; k++)
+        if (myL[k] >= 0) qlist[lm_hist[myL[k]] + myr[k]] = (int32_t)(q0 + (tid + 256 * k) / np);
 }
 
 // ---- the scan ----------------------------------------------------------------------------------
@@ -239,15 +315,14 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #pragma unroll
     for (int t = 0; t < T; t++) B[t] = (v4i){0, 0, 0, 0};
     int nstaged = 0;                                   // wave-uniform fill of the stage queue
+    const uint32_t nunits = (uint32_t)a.toff[v.nlist];
+    if (nunits == 0u) return;                          // nothing was written: all chunk fills stay 0
+    // first unit and first two log chunks by wave index; the counters start behind them
+    const uint32_t gwave = blockIdx.x * (WG / 64) + (threadIdx.x >> 6), nwaves = gridDim.x * (WG / 64);
     LogCursor lc;
-    {
-        uint32_t c0 = 0;
-        if (lane == 0) c0 = atomicAdd(a.log_cursor, 2u);
-        c0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)c0);
-        lc.chunk = c0;
-        lc.next_chunk = c0 + 1;
-        lc.used = 0;
-    }
+    lc.chunk = gwave;
+    lc.next_chunk = gwave + nwaves;
+    lc.used = 0;
     uint32_t nflush = 0;
 #ifdef RAIRS_PROFILE_CYCLES
     long long pc_t0 = clock64(), pc_tile = 0, pc_blocks = 0, pc_slow = 0, pc_flush = 0, pc_decode = 0, pc_mark;
@@ -265,10 +340,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         nflush++;                                                       \
     } while (0)
 
-    const uint32_t nunits = (uint32_t)a.toff[v.nlist];
-    uint32_t u = 0;
-    if (lane == 0) u = atomicAdd(a.next_task, 1u);
-    u = (uint32_t)__builtin_amdgcn_readfirstlane((int)u);
+    uint32_t u = gwave;
     while (u < nunits) {                               // every wave leaves: the counter only grows
         PC_MARK();
         // ask for the unit after this one now; the answer is not needed before this one is done
@@ -423,7 +495,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #endif
 }
 
-// Distribute the survivor log to the per-query buffers (one workgroup per chunk).  A chunk holds
+// Distribute the survivor log to the per-query buffers (a workgroup takes one chunk at a time).  A chunk holds
 // entries of a few dozen queries; they are grouped in LDS first so that each query's counter is
 // bumped once per chunk, not once per entry.
 #define COLLECT_SLOTS 128
@@ -431,10 +503,12 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
 {
     __shared__ int32_t key[COLLECT_SLOTS];
     __shared__ uint32_t cnt[COLLECT_SLOTS], base[COLLECT_SLOTS];
-    const uint32_t c = blockIdx.x;
-    const uint32_t n = a.chunk_fill[c];
-    if (n == 0) return;
     const int tid = threadIdx.x;
+    uint32_t lim = *a.log_cursor;                       // chunks handed out
+    lim = lim < (uint32_t)a.log_chunks ? lim : (uint32_t)a.log_chunks;
+    for (uint32_t c = blockIdx.x; c < lim; c += gridDim.x) {
+    const uint32_t n = a.chunk_fill[c];
+    if (n == 0) continue;                               // uniform
     if (tid < COLLECT_SLOTS) { key[tid] = -1; cnt[tid] = 0; }
     __syncthreads();
     uint4 e = make_uint4(0, 0, 0, 0);
@@ -459,6 +533,8 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
         const uint32_t qid = e.z;
         const uint32_t pos = slot >= 0 ? base[slot] + rank : atomicAdd(&a.surv_cnt[qid], 1u);
         if (pos < (uint32_t)a.surv_cap) a.surv_buf[(size_t)qid * a.surv_cap + pos] = ((uint64_t)e.y << 32) | e.x;
+    }
+    __syncthreads();                                    // the tables are reused for the next chunk
     }
 }
 
@@ -582,19 +658,16 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int nstaged = 0;
     uint32_t nflush = 0;
-    LogCursor lc;
-    {
-        uint32_t c0 = 0;
-        if (lane == 0) c0 = atomicAdd(a.log_cursor, 2u);
-        c0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)c0);
-        lc.chunk = c0;
-        lc.next_chunk = c0 + 1;
-        lc.used = 0;
-    }
     const uint32_t nunits = (uint32_t)a.toff[v.nlist];
-    for (;;) {
+    if (nunits == 0u) return;                          // uniform; nothing was written
+    const uint32_t gwave = blockIdx.x * (WG / 64) + wave, nwaves = gridDim.x * (WG / 64);
+    LogCursor lc;
+    lc.chunk = gwave;
+    lc.next_chunk = gwave + nwaves;
+    lc.used = 0;
+    for (bool first = true;; first = false) {
         __syncthreads();                               // everyone is done with the previous tile
-        if (threadIdx.x == 0) s_unit = atomicAdd(a.next_task, 1u);
+        if (threadIdx.x == 0) s_unit = first ? blockIdx.x : atomicAdd(a.next_task, 1u);
         __syncthreads();
         const uint32_t u = s_unit;
         if (u >= nunits) break;                        // uniform for the workgroup; the counter only grows
@@ -711,18 +784,37 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     const int64_t pairs = a.nq * np;
     int64_t nz = v.nlist > a.nq ? v.nlist : a.nq;
     nz = nz > a.log_chunks ? nz : a.log_chunks;
+    // persistent grid: 256 compute units x 2 workgroups of 4 waves, or one when the tables are in LDS
+    const bool reg_tables = v.T == 8 || v.T == 24 || v.T == 32;
+    const dim3 grid(reg_tables ? 512 : 256);
+    const uint32_t nwaves = grid.x * (WG / 64);
+    if (a.log_chunks < (int)(2 * nwaves)) {
+        rairs_set_error("survivor log of %d chunks is below %u", a.log_chunks, 2 * nwaves);
+        return RAIRS_EINVAL;
+    }
     hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
                        v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
-                       a.log_cursor, a.log_overflow, a.only_flagged);
-    hipLaunchKernelGGL(lm_count_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
-                       a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount, a.only_flagged);
+                       a.log_cursor, a.log_overflow, a.only_flagged, reg_tables ? nwaves : grid.x,
+                       2 * nwaves);
+    const bool lds_group = v.nlist <= LM_LDS_NLIST;
+    const int qb = LM_PAIRS / np > 0 ? LM_PAIRS / np : 1;
+    const unsigned lgrid = (unsigned)((a.nq + qb - 1) / qb);
+    if (lds_group)
+        hipLaunchKernelGGL(lm_count_lds_kernel, dim3(lgrid), dim3(256), (size_t)v.nlist * 4, s,
+                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount, a.only_flagged, qb);
+    else
+        hipLaunchKernelGGL(lm_count_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
+                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount, a.only_flagged);
     hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
                        a.toff, a.unit_list, a.unit_segs);
-    hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
-                       a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist,
-                       a.only_flagged);
-    // persistent grid: 256 compute units x 2 workgroups of 4 waves
-    const dim3 grid(512);
+    if (lds_group)
+        hipLaunchKernelGGL(lm_fill_lds_kernel, dim3(lgrid), dim3(256), (size_t)v.nlist * 4, s,
+                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor,
+                           a.qlist, a.only_flagged, qb);
+    else
+        hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
+                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist,
+                           a.only_flagged);
     if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
     switch (v.T) {
     case 8: hipLaunchKernelGGL(scan_mfma_kernel<8>, grid, dim3(WG), 0, s, v, a); break;
@@ -733,7 +825,7 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
         const size_t lds = (size_t)v.nd * 8 * 64 * 16;
         RAIRS_HIP(hipFuncSetAttribute((const void *)scan_mfma_lds_kernel,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(scan_mfma_lds_kernel, dim3(256), dim3(WG), lds, s, v, a);
+        hipLaunchKernelGGL(scan_mfma_lds_kernel, grid, dim3(WG), lds, s, v, a);
     }
     }
     if (ev) RAIRS_HIP(hipEventRecord(ev[1], s));
@@ -743,7 +835,8 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
 
 int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(collect_kernel, dim3((unsigned)a.log_chunks), dim3(LOG_CHUNK), 0, s, a);
+    hipLaunchKernelGGL(collect_kernel, dim3((unsigned)(a.log_chunks < 4096 ? a.log_chunks : 4096)),
+                       dim3(LOG_CHUNK), 0, s, a);
     hipLaunchKernelGGL(select_kernel, dim3((unsigned)a.nq), dim3(WG), 0, s, v, a);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
