@@ -153,7 +153,10 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     const size_t cb_bytes = (size_t)x->M * 16 * (x->d / x->M) * sizeof(float);
     h->code_bytes = (int64_t)x->nblocks * v.nd * 64 * 4;
     const size_t raw_bytes = (size_t)x->ntotal * x->d * (v.raw_u8 ? 1 : 4);
+    float *cnorm = nullptr;
+    UP_CHECK(dev_alloc(h, (void **)&cent, cent_bytes));
     UP_CHECK(dev_alloc(h, (void **)&cent_t, cent_bytes));
+    UP_CHECK(dev_alloc(h, (void **)&cnorm, (size_t)x->nlist * sizeof(float)));
     UP_CHECK(dev_alloc(h, (void **)&cb, cb_bytes));
     UP_CHECK(dev_alloc(h, (void **)&codes, (size_t)h->code_bytes));
     UP_CHECK(dev_alloc(h, (void **)&ids, (size_t)x->nblocks * 32 * 4));
@@ -162,18 +165,25 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_CHECK(dev_alloc(h, (void **)&refs, (size_t)x->nrefs * sizeof(RefEntry)));
     UP_CHECK(dev_alloc(h, &raw, raw_bytes));
 
-    // centroids: transposed to [d][nlist] so that lanes of the coarse kernel read coalesced
-    UP_HIP(hipMalloc((void **)&cent, cent_bytes));
-    hipError_t e = hipMemcpyAsync(cent, x->centroids, cent_bytes, hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) {
-        int r2 = rairs_launch_transpose(cent, x->nlist, x->d, cent_t, s);
-        e = hipStreamSynchronize(s);
-        (void)hipFree(cent);
-        if (r2) { destroy(h); return r2; }
-    } else {
-        (void)hipFree(cent);
+    // centroids: row-major for the re-scoring of shortlisted lists, transposed to [d][nlist] so
+    // that lanes walking over lists read coalesced, and their squared norms for the GEMM form
+    std::vector<float> hn((size_t)x->nlist);
+    double nmax = 0.0;
+    for (int l = 0; l < x->nlist; l++) {
+        double n2 = 0.0;
+        for (int i = 0; i < x->d; i++) {
+            const double c = (double)x->centroids[(size_t)l * x->d + i];
+            n2 += c * c;
+        }
+        hn[(size_t)l] = (float)n2;
+        if (n2 > nmax) nmax = n2;
     }
-    UP_HIP(e);
+    v.cmax2 = (float)nmax;
+    hipError_t e = hipSuccess;
+    UP_HIP(hipMemcpyAsync(cent, x->centroids, cent_bytes, hipMemcpyHostToDevice, s));
+    UP_HIP(hipMemcpyAsync(cnorm, hn.data(), hn.size() * sizeof(float), hipMemcpyHostToDevice, s));
+    UP_CHECK(rairs_launch_transpose(cent, x->nlist, x->d, cent_t, s));
+    UP_HIP(hipStreamSynchronize(s));
     UP_HIP(hipMemcpyAsync(cb, x->codebook, cb_bytes, hipMemcpyHostToDevice, s));
     if (x->nblocks)
         UP_HIP(hipMemcpyAsync(other, x->other, (size_t)x->nblocks * 32 * 4, hipMemcpyHostToDevice, s));
@@ -269,7 +279,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     }
     UP_HIP(hipStreamSynchronize(s));
 
-    v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other;
+    v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other;
     v.lists = lists; v.refs = refs; v.segs = segs; v.raw = raw;
     for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[i]));
     h->ev_ready = 1;
@@ -298,7 +308,7 @@ extern "C" int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, in
 #define RAIRS_LOG_PER_QUERY 3072
 
 struct WsLayout {
-    size_t dmat, probe_ids, probe_dists, bitmap, lut, cand;
+    size_t dmat, cflags, probe_ids, probe_dists, bitmap, lut, cand;
     size_t lcount, loff, lcursor, toff, unit_list, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, prof, total;
     int log_chunks;
     int bmwords;
@@ -311,6 +321,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     size_t off = 0;
     auto take = [&off](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
     w.dmat = take((size_t)nq * v.nlist * 4);
+    w.cflags = take((size_t)nq * 4);
     w.probe_ids = take((size_t)nq * nprobe * 4);
     w.probe_dists = take((size_t)nq * nprobe * 4);
     w.bitmap = take((size_t)nq * w.bmwords * 4);
@@ -406,13 +417,15 @@ extern "C" int rairs_coarse(rairs_index_t *h, const float *d_queries, int64_t nq
     if (nq == 0) return RAIRS_OK;
     if (!d_queries || !d_probe_ids) FAIL(RAIRS_EINVAL, "null device pointer");
     const int64_t step = pass_size(h->v, nq);
-    if ((rc = ensure_ws(h, ws_layout(h->v, step, nprobe, 1).total))) return rc;
+    const WsLayout w = ws_layout(h->v, step, nprobe, 1);
+    if ((rc = ensure_ws(h, w.total))) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     for (int64_t q0 = 0; q0 < nq; q0 += step) {
         int64_t n = nq - q0 < step ? nq - q0 : step;
-        rc = rairs_launch_coarse(h->v, d_queries + (size_t)q0 * h->v.d, n, nprobe, (float *)h->ws,
-                                 d_probe_ids + (size_t)q0 * nprobe,
-                                 d_probe_dists ? d_probe_dists + (size_t)q0 * nprobe : nullptr, s);
+        rc = rairs_launch_coarse(h->v, d_queries + (size_t)q0 * h->v.d, n, nprobe,
+                                 (float *)((char *)h->ws + w.dmat), d_probe_ids + (size_t)q0 * nprobe,
+                                 d_probe_dists ? d_probe_dists + (size_t)q0 * nprobe : nullptr,
+                                 (uint32_t *)((char *)h->ws + w.cflags), s);
         if (rc) return rc;
     }
     return RAIRS_OK;
@@ -568,7 +581,8 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
         int64_t *cand = (int64_t *)(ws + w.cand);
         if (prof) RAIRS_HIP(hipEventRecord(h->ev[0], s));
         if ((rc = rairs_launch_coarse(v, q, n, nprobe, (float *)(ws + w.dmat), probe_ids,
-                                      (float *)(ws + w.probe_dists), s))) return rc;
+                                      (float *)(ws + w.probe_dists), (uint32_t *)(ws + w.cflags), s)))
+            return rc;
         if (prof) { RAIRS_HIP(hipEventRecord(h->ev[1], s)); RAIRS_HIP(hipEventRecord(h->ev[2], s)); }
         if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, s))) return rc;
         if (prof) { RAIRS_HIP(hipEventRecord(h->ev[3], s)); RAIRS_HIP(hipEventRecord(h->ev[4], s)); }

@@ -4,7 +4,7 @@
 
 #define WG 256
 
-static __device__ __forceinline__ int next_pow2(int x)
+static __host__ __device__ __forceinline__ int next_pow2(int x)
 {
     int p = 1;
     while (p < x) p <<= 1;

@@ -71,52 +71,79 @@ int rairs_launch_transpose(const float *d_in, int rows, int cols, float *d_out, 
 // ---------------------------------------------------------------------------------------------
 // coarse quantizer: FindNearestLists for the batch (Alg. 2 line 5)
 // ---------------------------------------------------------------------------------------------
+//
+// The result is defined by the direct form: dist(q, l) = sum_i (q_i - c_li)^2 in fp32, summed as 64
+// interleaved partial sums over the dimensions (class = dimension mod 64) folded pairwise at
+// strides 32..1; the nprobe smallest (dist, list id) win.  Two routes compute it:
+//   full:      every (query, list) distance in the direct form, then a selection;
+//   shortlist: s(q, l) = |c_l|^2 - 2 q.c_l for all pairs on the fp32 matrix cores, the lists whose
+//              s is within a rounding-error margin of the nprobe-th smallest s are re-scored in the
+//              direct form, and the selection is made among those.  The margin makes the shortlist
+//              a superset of the true winners, so both routes return the same bits; a query whose
+//              shortlist does not fit falls back to the full route.
 
-// One lane per (query, centroid).  The squared distance is summed as 64 interleaved partial
-// sums over the dimensions (class = dimension mod 64), folded pairwise at strides 32..1.
-__global__ __launch_bounds__(WG) void coarse_dist_kernel(const float *__restrict__ q,
-                                                         const float *__restrict__ ct, int d,
-                                                         int nlist, int groups,
-                                                         float *__restrict__ dmat)
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// order-preserving map of an fp32 value to an unsigned key, and back
+static __device__ __forceinline__ uint32_t f32_key(float x)
 {
-    int qi = blockIdx.x / groups;
-    int l = (blockIdx.x % groups) * WG + threadIdx.x;
-    const float *qq = q + (size_t)qi * d;
-    int lc = l < nlist ? l : nlist - 1;
-    float p[64];
-#pragma unroll
-    for (int j = 0; j < 64; j++) p[j] = 0.0f;
-    for (int i0 = 0; i0 < d; i0 += 64) {
-#pragma unroll
-        for (int j = 0; j < 64; j++) {
-            int i = i0 + j;
-            if (i < d) {
-                float diff = qq[i] - ct[(size_t)i * nlist + lc];
-                float sq = diff * diff;
-                p[j] = p[j] + sq;
-            }
-        }
-    }
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) {
-#pragma unroll
-        for (int j = 0; j < s; j++) p[j] = p[j] + p[j + s];
-    }
-    if (l < nlist) dmat[(size_t)qi * nlist + l] = p[0];
+    const uint32_t b = __float_as_uint(x);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+static __device__ __forceinline__ float key_f32(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
 }
 
-// Per query: the nprobe smallest (distance, list id) by radix select on the fp32 bit pattern
-// (distances are >= +0, so the unsigned order of the bits is the numeric order), then sorted.
+// Full route, distances: one lane per (query, list), lists strided over the y dimension of the
+// grid.  With only_flagged set, queries whose flag is zero are left alone.
+__global__ __launch_bounds__(WG) void coarse_dist_kernel(const float *__restrict__ q,
+                                                         const float *__restrict__ ct, int d,
+                                                         int nlist, float *__restrict__ dmat,
+                                                         const uint32_t *__restrict__ only_flagged)
+{
+    const int64_t qi = blockIdx.x;
+    if (only_flagged && only_flagged[qi] == 0) return;
+    const float *qq = q + (size_t)qi * d;
+    for (int l = blockIdx.y * WG + threadIdx.x; l < nlist; l += gridDim.y * WG) {
+        float p[64];
+#pragma unroll
+        for (int j = 0; j < 64; j++) p[j] = 0.0f;
+        for (int i0 = 0; i0 < d; i0 += 64) {
+#pragma unroll
+            for (int j = 0; j < 64; j++) {
+                int i = i0 + j;
+                if (i < d) {
+                    float diff = qq[i] - ct[(size_t)i * nlist + l];
+                    float sq = diff * diff;
+                    p[j] = p[j] + sq;
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+#pragma unroll
+            for (int j = 0; j < s; j++) p[j] = p[j] + p[j + s];
+        }
+        dmat[(size_t)qi * nlist + l] = p[0];
+    }
+}
+
+// Full route, selection: the nprobe smallest (distance, list id) of a row by radix select on the
+// fp32 bit pattern (distances are >= +0, so the unsigned order of the bits is the numeric order),
+// then sorted.  One workgroup per query.
 __global__ __launch_bounds__(WG) void coarse_select_kernel(const float *__restrict__ dmat,
                                                            int nlist, int nprobe,
                                                            int32_t *__restrict__ probe_ids,
-                                                           float *__restrict__ probe_dists)
+                                                           float *__restrict__ probe_dists,
+                                                           const uint32_t *__restrict__ only_flagged)
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_cnt;
     __shared__ int wcnt[WG / 64];
     __shared__ uint64_t sel[RAIRS_MAX_NPROBE];
     const int tid = threadIdx.x;
+    if (only_flagged && only_flagged[blockIdx.x] == 0) return;
     const uint32_t *row = (const uint32_t *)(dmat + (size_t)blockIdx.x * nlist);
 
     uint32_t prefix = 0, mask = 0, remaining = (uint32_t)nprobe;
@@ -189,73 +216,132 @@ __global__ __launch_bounds__(WG) void coarse_select_kernel(const float *__restri
     }
 }
 
-// Same distances with the lane's centroid held in registers and a block of queries streamed past
-// it: the centroid matrix is then read once per 32 queries instead of once per query.
-#define COARSE_QB 32
+// Shortlist route, scores: keys[q][l] = f32_key(|c_l|^2 - 2 q.c_l) with v_mfma_f32_32x32x2f32.
+// A workgroup takes 128 queries (32 per wave, kept in registers: lane (row i, half k) holds
+// q_i[k*D/2 + s], s < D/2) and walks over tiles of 32 lists.  A tile's centroids are staged in LDS
+// in operand order, element (s, k, j) = ct[k*D/2 + s][l0 + j] at s*64 + k*32 + j, so that the B
+// operand of step s is one conflict-free 4-byte read per lane; the next tile is fetched into
+// registers while the current one is multiplied (two LDS buffers, one barrier per tile).
+// Result register r of lane (k, j) is row 8*(r/4) + 4*k + r%4, column j.
+#define GEMM_QWG 128
 template <int D>
-__global__ __launch_bounds__(WG) void coarse_dist_reg_kernel(const float *__restrict__ q,
-                                                             const float *__restrict__ ct,
-                                                             int nlist, int groups, int64_t nq,
-                                                             float *__restrict__ dmat)
+__global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict__ q,
+                                                         const float *__restrict__ ct,
+                                                         const float *__restrict__ cnorm, int nlist,
+                                                         int csplits, int tiles_per_split, int64_t nq,
+                                                         uint32_t *__restrict__ keys)
 {
-    constexpr int NP = D < 64 ? D : 64;      // partial-sum classes in use
-    const int64_t q0 = (int64_t)(blockIdx.x / groups) * COARSE_QB;
-    const int l = (blockIdx.x % groups) * WG + threadIdx.x;
-    const int lc = l < nlist ? l : nlist - 1;
-    float c[D];
+    constexpr int H = D / 2;
+    constexpr int PER = D * 32 / WG;                    // staged elements per thread and tile
+    __shared__ float Bs[2][D * 32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = lane & 31, k = lane >> 5;
+    // workgroups that share an L2 (consecutive ids go round the 8 dies) take the same lists
+    int qblock, csplit;
+    if ((csplits & 7) == 0) {
+        const int per = csplits >> 3, x = blockIdx.x & 7, y = blockIdx.x >> 3;
+        csplit = x * per + y % per;
+        qblock = y / per;
+    } else {
+        csplit = blockIdx.x % csplits;
+        qblock = blockIdx.x / csplits;
+    }
+    const int64_t q0 = (int64_t)qblock * GEMM_QWG + wave * 32;
+    const int64_t qrow = q0 + i < nq ? q0 + i : nq - 1;
+    float A[H];
+    {
+        const float4 *src = (const float4 *)(q + (size_t)qrow * D + k * H);
 #pragma unroll
-    for (int i = 0; i < D; i++) c[i] = ct[(size_t)i * nlist + lc];
-    const int64_t q1 = q0 + COARSE_QB < nq ? q0 + COARSE_QB : nq;
-    for (int64_t qi = q0; qi < q1; qi++) {
-        const float *qq = q + (size_t)qi * D;
-        float p[NP];
-#pragma unroll
-        for (int j = 0; j < NP; j++) {
-            float diff = qq[j] - c[j];
-            p[j] = diff * diff;
+        for (int s4 = 0; s4 < H / 4; s4++) {
+            const float4 x = src[s4];
+            A[4 * s4] = x.x; A[4 * s4 + 1] = x.y; A[4 * s4 + 2] = x.z; A[4 * s4 + 3] = x.w;
         }
+    }
+    const int ntiles = (nlist + 31) >> 5;
+    const int t_begin = csplit * tiles_per_split;
+    const int t_end = t_begin + tiles_per_split < ntiles ? t_begin + tiles_per_split : ntiles;
+    if (t_begin >= t_end) return;                       // uniform for the workgroup
+    // staging: thread -> column sj, rows sr + 8 * e (row = dimension k*H + s)
+    const int sj = threadIdx.x & 31, sr = threadIdx.x >> 5;
+    float st[PER];
+    auto fetch = [&](int t) {
+        const int l = t * 32 + sj;
+        const float *src = ct + (l < nlist ? l : nlist - 1);
 #pragma unroll
-        for (int i = NP; i < D; i++) {
-            float diff = qq[i] - c[i];
-            float sq = diff * diff;
-            p[i & 63] = p[i & 63] + sq;
+        for (int e = 0; e < PER; e++) st[e] = src[(size_t)(sr + 8 * e) * nlist];
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int e = 0; e < PER; e++) {
+            const int row = sr + 8 * e, kk = row >= H ? 1 : 0, ss = row - kk * H;
+            Bs[buf][ss * 64 + kk * 32 + sj] = st[e];
         }
-        // classes NP..63 are +0 and adding +0 changes nothing (all terms are >= +0)
+    };
+    fetch(t_begin);
+    stage(0);
+    __syncthreads();
+    int buf = 0;
+    for (int t = t_begin; t < t_end; t++) {
+        const bool more = t + 1 < t_end;
+        if (more) fetch(t + 1);
+        v16f acc;
 #pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) {
+        for (int r = 0; r < 16; r++) acc[r] = 0.0f;
+        const float *bl = &Bs[buf][lane];
 #pragma unroll
-            for (int j = 0; j < s; j++)
-                if (j + s < NP) p[j] = p[j] + p[j + s];
+        for (int s = 0; s < H; s++)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(A[s], bl[s * 64], acc, 0, 0, 0);
+        const int l = t * 32 + i;
+        if (l < nlist) {
+            const float cn = cnorm[l];
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const int64_t qq = q0 + 8 * (r >> 2) + 4 * k + (r & 3);
+                const float two = 2.0f * acc[r];
+                if (qq < nq) keys[(size_t)qq * nlist + l] = f32_key(cn - two);
+            }
         }
-        if (l < nlist) dmat[(size_t)qi * nlist + l] = p[0];
+        if (more) stage(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
     }
 }
 
-// One wave per query (four queries per workgroup): same selection as coarse_select_kernel for
-// nprobe <= 1024.  All loops have trip counts that depend only on nlist and nprobe, so the
-// workgroup barriers are reached uniformly.
-#define SELW_MAX_NPROBE 1024
-__global__ __launch_bounds__(WG) void coarse_select_wave_kernel(const float *__restrict__ dmat,
-                                                                int nlist, int nprobe, int64_t nq,
-                                                                int32_t *__restrict__ probe_ids,
-                                                                float *__restrict__ probe_dists)
+// Shortlist route, selection.  One wave per query (four per workgroup): radix select of the
+// nprobe-th smallest key, widen it by the margin, gather the lists up to there, re-score them in
+// the direct form, sort by (distance, list id), keep nprobe.
+//
+// Margin.  With u = 2^-24 and exact values D = |q - c|^2: the direct form is within (d + 2) u D of
+// D, D <= 2 (|q|^2 + |c|^2); the GEMM form's dot product is within d u |q||c|, the norm within
+// u |c|^2 and the final subtraction within u |s|.  Together |direct - (s + |q|^2)| stays below
+// 4 (d + 2) u (|q|^2 + max |c|^2) =: e, and every list among the nprobe best by the direct form has
+// s <= (nprobe-th smallest s) + 2 e.  The kernel uses 16 (d + 2) u (|q|^2 + max |c|^2), twice that,
+// against accumulation orders inside the matrix core that are not documented.
+//
+// All loops that contain workgroup barriers have trip counts fixed by nlist, nprobe and cap.
+__global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__restrict__ keys,
+                                                              const float *__restrict__ q,
+                                                              const float *__restrict__ cent, int d,
+                                                              int nlist, int nprobe, int cap,
+                                                              float cmax2, int64_t nq,
+                                                              int32_t *__restrict__ probe_ids,
+                                                              float *__restrict__ probe_dists,
+                                                              uint32_t *__restrict__ flags)
 {
     __shared__ uint32_t hist_s[WG / 64][256];
-    __shared__ uint64_t sel_s[WG / 64][SELW_MAX_NPROBE];
-    __shared__ uint32_t cnt_s[WG / 64];
+    extern __shared__ __align__(16) uint64_t sel_dyn[];      // [WG / 64][cap], cap a power of two
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t qi0 = (int64_t)blockIdx.x * (WG / 64) + wave;
-    const int64_t qi = qi0 < nq ? qi0 : nq - 1;          // surplus waves redo the last query
-    const uint32_t *row = (const uint32_t *)(dmat + (size_t)qi * nlist);
+    const int64_t qi = __builtin_amdgcn_readfirstlane((int)(qi0 < nq ? qi0 : nq - 1));   // surplus waves redo the last query
+    const uint32_t *row = keys + (size_t)qi * nlist;
     uint32_t *hist = hist_s[wave];
-    uint64_t *sel = sel_s[wave];
+    uint64_t *sel = sel_dyn + (size_t)wave * cap;
 
     uint32_t prefix = 0, mask = 0, remaining = (uint32_t)nprobe;
     for (int shift = 24; shift >= 0; shift -= 8) {
-        for (int i = lane; i < 256; i += 64) hist[i] = 0;
+        for (int b = lane; b < 256; b += 64) hist[b] = 0;
         __syncthreads();
-        for (int i = lane; i < nlist; i += 64) {
-            uint32_t key = row[i];
+        for (int l = lane; l < nlist; l += 64) {
+            uint32_t key = row[l];
             if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
         }
         __syncthreads();
@@ -286,79 +372,142 @@ __global__ __launch_bounds__(WG) void coarse_select_wave_kernel(const float *__r
         mask |= 255u << shift;
         __syncthreads();
     }
-    const uint32_t kth = prefix;
-    // keys below the nprobe-th distance in any order, then `remaining` keys equal to it, the ones
-    // with the smallest list ids (lists are walked in increasing id)
-    uint32_t nless = 0, neq = 0;
-    for (int i0 = 0; i0 < nlist; i0 += 64) {
-        const int i = i0 + lane;
-        const uint32_t key = i < nlist ? row[i] : 0xFFFFFFFFu;
-        const bool less = i < nlist && key < kth;
-        const bool eq = i < nlist && key == kth;
-        const unsigned long long ml = __ballot(less), me = __ballot(eq);
-        const unsigned long long below = (1ull << lane) - 1ull;
-        if (less) sel[nless + __popcll(ml & below)] = ((uint64_t)key << 32) | (uint32_t)i;
-        nless += (uint32_t)__popcll(ml);
-        if (eq) {
-            const uint32_t r = neq + (uint32_t)__popcll(me & below);
-            // slots after the (nprobe - remaining) smaller keys
-            if (r < remaining) sel[(uint32_t)nprobe - remaining + r] = ((uint64_t)kth << 32) | (uint32_t)i;
-        }
-        neq += (uint32_t)__popcll(me);
+    // |q|^2 and the widened threshold
+    const float *qq = q + (size_t)qi * d;
+    float qn = 0.0f;
+    for (int t = lane; t < d; t += 64) qn += qq[t] * qq[t];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) qn += __shfl_xor(qn, off);
+    const float margin = 16.0f * (float)(d + 2) * 5.9604645e-8f * (qn + cmax2);
+    const uint32_t thr = f32_key(key_f32(prefix) + margin);
+    // gather the shortlist
+    uint32_t nc = 0;
+    for (int l0 = 0; l0 < nlist; l0 += 64) {
+        const int l = l0 + lane;
+        const bool in = l < nlist && row[l] <= thr;
+        const unsigned long long m = __ballot(in);
+        const uint32_t pos = nc + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+        if (in && pos < (uint32_t)cap) sel[pos] = (uint64_t)(uint32_t)l;
+        nc += (uint32_t)__popcll(m);
     }
-    const int n2 = next_pow2(nprobe < 2 ? 2 : nprobe);
-    for (int i = nprobe + lane; i < n2; i += 64) sel[i] = ~0ull;
+    const bool fits = nc <= (uint32_t)cap && !(margin != margin) && margin < 3.0e38f;
+    if (lane == 0 && qi0 < nq) flags[qi] = fits ? 0u : 1u;
+    if (!fits) nc = 0;
     __syncthreads();
-    // bitonic sort by the wave alone
-    for (int k = 2; k <= n2; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = lane; i < n2; i += 64) {
-                int p = i ^ j;
-                if (p > i) {
-                    bool up = (i & k) == 0;
-                    uint64_t x = sel[i], y = sel[p];
-                    if ((x > y) == up) { sel[i] = y; sel[p] = x; }
+    // re-score in the direct form: the wave takes one list at a time, lane j sums the dimensions
+    // of class j and the fold is a butterfly over the lanes (lane 0 ends with the defined value)
+    float qr[4];
+#pragma unroll
+    for (int c = 0; c < 4; c++) qr[c] = 64 * c + lane < d ? qq[64 * c + lane] : 0.0f;
+    for (uint32_t c0 = 0; c0 < nc; c0 += 4) {
+        float p[4];
+        uint32_t ls[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            ls[u] = (uint32_t)sel[c0 + u < nc ? c0 + u : nc - 1];
+            const float *cr = cent + (size_t)ls[u] * d;
+            p[u] = 0.0f;
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                if (64 * c + lane < d) {
+                    float diff = qr[c] - cr[64 * c + lane];
+                    float sq = diff * diff;
+                    p[u] = p[u] + sq;
+                }
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+            for (int u = 0; u < 4; u++) p[u] = p[u] + __shfl_down(p[u], off);
+        }
+        // all four lists were read before any entry is rewritten
+#pragma unroll
+        for (int u = 0; u < 4; u++)
+            if (lane == 0 && c0 + u < nc) sel[c0 + u] = ((uint64_t)__float_as_uint(p[u]) << 32) | ls[u];
+    }
+    for (uint32_t c = nc + (uint32_t)lane; c < (uint32_t)cap; c += 64) sel[c] = ~0ull;
+    __syncthreads();
+    // bitonic sort of the wave's `cap` entries
+    for (int kk = 2; kk <= cap; kk <<= 1)
+        for (int jj = kk >> 1; jj > 0; jj >>= 1) {
+            for (int e = lane; e < cap; e += 64) {
+                int p = e ^ jj;
+                if (p > e) {
+                    bool up = (e & kk) == 0;
+                    uint64_t x = sel[e], y = sel[p];
+                    if ((x > y) == up) { sel[e] = y; sel[p] = x; }
                 }
             }
             __syncthreads();
         }
-    if (qi0 < nq)
-        for (int i = lane; i < nprobe; i += 64) {
-            uint64_t key = sel[i];
-            probe_ids[(size_t)qi * nprobe + i] = (int32_t)(uint32_t)key;
-            if (probe_dists) probe_dists[(size_t)qi * nprobe + i] = __uint_as_float((uint32_t)(key >> 32));
+    if (qi0 < nq && fits)
+        for (int e = lane; e < nprobe; e += 64) {
+            uint64_t key = sel[e];
+            probe_ids[(size_t)qi * nprobe + e] = (int32_t)(uint32_t)key;
+            if (probe_dists) probe_dists[(size_t)qi * nprobe + e] = __uint_as_float((uint32_t)(key >> 32));
         }
-    (void)cnt_s;
+}
+
+#define SHORTLIST_MAX_NPROBE 1024
+static bool coarse_shortlist_ok(const IndexView &v, int nprobe)
+{
+    return (v.d == 32 || v.d == 64 || v.d == 96 || v.d == 128 || v.d == 256) &&
+           nprobe <= SHORTLIST_MAX_NPROBE && v.nlist >= 64;
 }
 
 int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,
-                        int32_t *probe_ids, float *probe_dists, hipStream_t s)
+                        int32_t *probe_ids, float *probe_dists, uint32_t *flags, hipStream_t s)
 {
-    int groups = (v.nlist + WG - 1) / WG;
-    const unsigned qblocks = (unsigned)((nq + COARSE_QB - 1) / COARSE_QB);
-    switch (v.d) {
-    case 32:
-        hipLaunchKernelGGL(coarse_dist_reg_kernel<32>, dim3(qblocks * groups), dim3(WG), 0, s, q,
-                           v.centroids_t, v.nlist, groups, nq, dmat);
-        break;
-    case 96:
-        hipLaunchKernelGGL(coarse_dist_reg_kernel<96>, dim3(qblocks * groups), dim3(WG), 0, s, q,
-                           v.centroids_t, v.nlist, groups, nq, dmat);
-        break;
-    case 128:
-        hipLaunchKernelGGL(coarse_dist_reg_kernel<128>, dim3(qblocks * groups), dim3(WG), 0, s, q,
-                           v.centroids_t, v.nlist, groups, nq, dmat);
-        break;
-    default:
-        hipLaunchKernelGGL(coarse_dist_kernel, dim3((unsigned)(nq * groups)), dim3(WG), 0, s, q,
-                           v.centroids_t, v.d, v.nlist, groups, dmat);
-    }
-    if (nprobe <= SELW_MAX_NPROBE)
-        hipLaunchKernelGGL(coarse_select_wave_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))),
-                           dim3(WG), 0, s, dmat, v.nlist, nprobe, nq, probe_ids, probe_dists);
-    else
+    const int groups = (v.nlist + WG - 1) / WG;
+    if (!coarse_shortlist_ok(v, nprobe) || !flags || ((uintptr_t)q & 15) != 0) {
+        hipLaunchKernelGGL(coarse_dist_kernel, dim3((unsigned)nq, groups), dim3(WG), 0, s, q,
+                           v.centroids_t, v.d, v.nlist, dmat, nullptr);
         hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist,
-                           nprobe, probe_ids, probe_dists);
+                           nprobe, probe_ids, probe_dists, nullptr);
+        RAIRS_HIP(hipGetLastError());
+        return RAIRS_OK;
+    }
+    // each workgroup: 128 queries x a run of list tiles; enough workgroups to fill the chip twice
+    // over, but at least 4 tiles per run so that the query registers are loaded rarely
+    const int ntiles = (v.nlist + 31) / 32;
+    const unsigned qblocks = (unsigned)((nq + GEMM_QWG - 1) / GEMM_QWG);
+    int csplits = (int)((1024 + qblocks - 1) / qblocks);
+    if (csplits > (ntiles + 3) / 4) csplits = (ntiles + 3) / 4;
+    if (csplits >= 8) csplits = csplits / 8 * 8;
+    if (csplits < 1) csplits = 1;
+    const int tiles_per_split = (ntiles + csplits - 1) / csplits;
+    const dim3 grid(qblocks * csplits);
+    uint32_t *keys = (uint32_t *)dmat;
+#define GEMM_CASE(D)                                                                              \
+    case D:                                                                                       \
+        hipLaunchKernelGGL(coarse_gemm_kernel<D>, grid, dim3(WG), 0, s, q, v.centroids_t, v.cnorm, \
+                           v.nlist, csplits, tiles_per_split, nq, keys);                          \
+        break
+    switch (v.d) {
+        GEMM_CASE(32);
+        GEMM_CASE(64);
+        GEMM_CASE(96);
+        GEMM_CASE(128);
+        GEMM_CASE(256);
+    }
+#undef GEMM_CASE
+    // room for the lists inside the margin: a quarter more than nprobe, at least 32
+    const int extra = nprobe / 4 > 32 ? nprobe / 4 : 32;
+    int cap = next_pow2(nprobe + extra);
+    if (cap < 64) cap = 64;
+    const size_t sel_bytes = (size_t)cap * 8 * (WG / 64);
+    if (sel_bytes > 32 * 1024)
+        RAIRS_HIP(hipFuncSetAttribute((const void *)coarse_shortlist_kernel,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_bytes));
+    hipLaunchKernelGGL(coarse_shortlist_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))),
+                       dim3(WG), sel_bytes, s, keys, q, v.centroids, v.d, v.nlist,
+                       nprobe, cap, v.cmax2, nq, probe_ids, probe_dists, flags);
+    // queries whose shortlist did not fit (many lists at nearly the same distance): full route
+    hipLaunchKernelGGL(coarse_dist_kernel, dim3((unsigned)nq, groups < 8 ? groups : 8), dim3(WG), 0, s,
+                       q, v.centroids_t, v.d, v.nlist, dmat, flags);
+    hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist, nprobe,
+                       probe_ids, probe_dists, flags);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }

@@ -43,7 +43,10 @@ struct RefEntry {
 struct IndexView {
     int32_t d, M, T, nd, nlist, raw_u8;   // T = M / 2 nibbles per parity, nd = ceil(T / 8) dwords
     int64_t ntotal, nblocks, nrefs;
+    const float *centroids;       // [nlist][d]
     const float *centroids_t;     // [d][nlist]
+    const float *cnorm;           // [nlist] squared norms
+    float cmax2;                  // largest squared norm of a centroid
     const float *codebook;        // [M][16][d/M]
     // codes: per block nd x 64 dwords; lane = parity * 32 + item; dword w of lane (g, item) packs
     // the codes of subspaces 2t+g, t = 8w .. 8w+7, nibble (t & 7) at bits 4*(t & 7)
@@ -94,8 +97,9 @@ int rairs_launch_pack(const uint8_t *d_codes_host_layout, const int64_t *d_ids64
                       int64_t nblk, int M, int nd, uint32_t *codes, uint32_t *ids,
                       hipStream_t s);
 int rairs_launch_transpose(const float *d_in, int rows, int cols, float *d_out, hipStream_t s);
+// dmat: [nq][nlist] words of scratch; flags: [nq] words of scratch (null: full route only)
 int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,
-                        int32_t *probe_ids, float *probe_dists, hipStream_t s);
+                        int32_t *probe_ids, float *probe_dists, uint32_t *flags, hipStream_t s);
 int rairs_launch_bitmap(const IndexView &v, const int32_t *probe_ids, int64_t nq, int nprobe,
                         uint32_t *bitmap, int bmwords, uint32_t *hist, hipStream_t s);
 int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lut, float *bias_sum,

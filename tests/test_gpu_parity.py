@@ -168,6 +168,41 @@ def test_larger_dimensions_and_u8_raw(binding):
     _compare_all_stages(binding, hx, q, 10, 6, 100)
 
 
+@pytest.mark.parametrize("d", [32, 64, 96, 128, 256])
+def test_coarse_shortlist_and_its_fallback(binding, d):
+    # Lists at (nearly) the same distance: the matrix-core shortlist has to hand such queries to
+    # the direct-form route, and ties are decided by list id on both sides.
+    g = np.random.Generator(np.random.PCG64(200 + d))
+    nlist, nq = 203, 77
+    x = datagen.random_vectors(60 + d, 700, d)
+    q = datagen.random_vectors(61 + d, nq, d)
+    cb = ib.train_pq(x, d // 2, 2, 2)
+    asg = np.sort(g.integers(0, nlist, size=(len(x), 2)), axis=1).astype(np.int32)
+    base_c = datagen.random_vectors(62 + d, nlist, d)
+    dup = base_c.copy()
+    dup[1::3] = dup[0::3][:len(dup[1::3])]                          # every third list repeats its neighbour
+    near = (base_c[:1] + 1e-6 * g.standard_normal((nlist, d))).astype(np.float32)
+    same = np.tile(base_c[:1], (nlist, 1))
+    big = (base_c * 200.0 + 100.0).astype(np.float32)               # SIFT-like magnitudes
+    for name, cents in (("random", base_c), ("dup", dup), ("near", near), ("same", same), ("big", big)):
+        hx = ib.add_vectors(x, np.ascontiguousarray(cents), cb, assign=asg)
+        ox = oracle.OracleIndex(hx)
+        ix = binding.Index(hx)
+        try:
+            for nprobe in (1, 7, 64, nlist):
+                print(f"case: coarse d={d} centroids={name} nprobe={nprobe}", flush=True)
+                qq = q * 200.0 + 100.0 if name == "big" else q
+                pid, pdist = ix.coarse(_dev(qq.astype(np.float32)), nprobe)
+                torch.cuda.synchronize()
+                pid, pdist = pid.cpu().numpy(), pdist.cpu().numpy()
+                for i in range(nq):
+                    oi, od = oracle.coarse(ox, qq[i].astype(np.float32), nprobe)
+                    assert (pid[i] == oi).all(), (name, nprobe, i)
+                    assert (pdist[i] == od.astype(np.float32)).all()
+        finally:
+            ix.free()
+
+
 def test_batch_permutation_and_split(binding, small_index):
     base, hx = small_index
     q = small_queries(42, 50, hx.d)
