@@ -340,9 +340,18 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
     for (int shift = 24; shift >= 0; shift -= 8) {
         for (int b = lane; b < 256; b += 64) hist[b] = 0;
         __syncthreads();
-        for (int l = lane; l < nlist; l += 64) {
-            uint32_t key = row[l];
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        // sixteen keys per lane are fetched together so that their latencies overlap
+        for (int l0 = 0; l0 < nlist; l0 += 64 * 16) {
+            uint32_t kk[16];
+#pragma unroll
+            for (int u = 0; u < 16; u++) {
+                const int l = l0 + 64 * u + lane;
+                kk[u] = row[l < nlist ? l : nlist - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; u++)
+                if (l0 + 64 * u + lane < nlist && (kk[u] & mask) == prefix)
+                    atomicAdd(&hist[(kk[u] >> shift) & 255u], 1u);
         }
         __syncthreads();
         // the bin where the running count reaches `remaining`: four bins per lane + wave scan
@@ -382,13 +391,22 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
     const uint32_t thr = f32_key(key_f32(prefix) + margin);
     // gather the shortlist
     uint32_t nc = 0;
-    for (int l0 = 0; l0 < nlist; l0 += 64) {
-        const int l = l0 + lane;
-        const bool in = l < nlist && row[l] <= thr;
-        const unsigned long long m = __ballot(in);
-        const uint32_t pos = nc + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-        if (in && pos < (uint32_t)cap) sel[pos] = (uint64_t)(uint32_t)l;
-        nc += (uint32_t)__popcll(m);
+    for (int l0 = 0; l0 < nlist; l0 += 64 * 16) {
+        uint32_t kk[16];
+#pragma unroll
+        for (int u = 0; u < 16; u++) {
+            const int l = l0 + 64 * u + lane;
+            kk[u] = row[l < nlist ? l : nlist - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < 16; u++) {
+            const int l = l0 + 64 * u + lane;
+            const bool in = l < nlist && kk[u] <= thr;
+            const unsigned long long m = __ballot(in);
+            const uint32_t pos = nc + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            if (in && pos < (uint32_t)cap) sel[pos] = (uint64_t)(uint32_t)l;
+            nc += (uint32_t)__popcll(m);
+        }
     }
     const bool fits = nc <= (uint32_t)cap && !(margin != margin) && margin < 3.0e38f;
     if (lane == 0 && qi0 < nq) flags[qi] = fits ? 0u : 1u;

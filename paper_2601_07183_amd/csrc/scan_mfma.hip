@@ -514,8 +514,14 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
     uint4 e = make_uint4(0, 0, 0, 0);
     int slot = -1;
     uint32_t rank = 0;
+    // an entry logged under an earlier, looser bound is dropped when its score is above the
+    // query's final bound: it cannot be among the bigK best
+    bool live = false;
     if (tid < (int)n) {
         e = a.log[(size_t)c * LOG_CHUNK + tid];
+        live = (int32_t)(e.y >> 16) <= a.bound[e.z];
+    }
+    if (live) {
         const int qid = (int)e.z;
         // open addressing on the query id; a full table falls back to a direct atomic below
         int h = (int)(((uint32_t)qid * 2654435761u) >> 25);          // 7 bits
@@ -529,7 +535,7 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
     __syncthreads();
     if (tid < COLLECT_SLOTS && cnt[tid] > 0) base[tid] = atomicAdd(&a.surv_cnt[key[tid]], cnt[tid]);
     __syncthreads();
-    if (tid < (int)n) {
+    if (live) {
         const uint32_t qid = e.z;
         const uint32_t pos = slot >= 0 ? base[slot] + rank : atomicAdd(&a.surv_cnt[qid], 1u);
         if (pos < (uint32_t)a.surv_cap) a.surv_buf[(size_t)qid * a.surv_cap + pos] = ((uint64_t)e.y << 32) | e.x;
@@ -538,7 +544,83 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
     }
 }
 
-// Per query: resolve the survivors (id, duplicate rule of the miscellaneous area) and keep the
+// Per query with at most SELW_CAP survivors (the usual case): one wave resolves them (id,
+// duplicate rule of the miscellaneous area), sorts them by (score, id) in its own LDS region and
+// writes the bigK smallest.  No workgroup barrier is used: a wave only touches its own region, and
+// LDS operations of one wave complete in issue order.
+#define SELW_CAP 1024
+static __device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanArgs a)
+{
+    __shared__ uint64_t keys_s[WG / 64][SELW_CAP];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t q = (int64_t)blockIdx.x * (WG / 64) + wave;
+    if (q >= a.nq) return;
+    if (a.only_flagged && a.only_flagged[q] == 0) return;      // settled in the first pass
+    const uint32_t n = a.surv_cnt[q];
+    if (n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) {
+        if (lane == 0) a.flags[q] = 1;      // redone by the second pass or the exact kernel
+        return;
+    }
+    if (n > SELW_CAP) return;               // select_kernel's case
+    if (lane == 0) a.flags[q] = 0;
+    uint64_t *keys = keys_s[wave];
+    const uint64_t *sb = a.surv_buf + (size_t)q * a.surv_cap;
+    const uint32_t *bm = a.bitmap + (size_t)q * a.bmwords;
+    for (uint32_t i0 = 0; i0 < n; i0 += 256) {
+        uint64_t e[4];
+        uint32_t id[4];
+        int o[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const uint32_t i = i0 + 64 * u + lane;
+            e[u] = sb[i < n ? i : n - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            id[u] = v.ids[(uint32_t)e[u]];
+            o[u] = v.other[(uint32_t)e[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const uint32_t i = i0 + 64 * u + lane;
+            const uint32_t score = (uint32_t)(e[u] >> 48), L = (uint32_t)(e[u] >> 32) & 0xFFFFu;
+            bool keep = id[u] != RAIRS_EMPTY_ID;
+            // RemoveVectorIfVisited: the item was already taken from list o
+            if (keep && o[u] >= 0 && (uint32_t)o[u] < L && ((bm[o[u] >> 5] >> (o[u] & 31)) & 1u)) keep = false;
+            if (i < n) keys[i] = keep ? (((uint64_t)score << 32) | id[u]) : ~0ull;
+        }
+    }
+    const int n2 = next_pow2(n < 2 ? 2 : (int)n);
+    for (int i = (int)n + lane; i < n2; i += 64) keys[i] = ~0ull;
+    wave_lds_sync();
+    for (int k = 2; k <= n2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = lane; i < n2; i += 64) {
+                const int p = i ^ j;
+                if (p > i) {
+                    const bool up = (i & k) == 0;
+                    const uint64_t x = keys[i], y = keys[p];
+                    if ((x > y) == up) { keys[i] = y; keys[p] = x; }
+                }
+            }
+            wave_lds_sync();
+        }
+    for (int i = lane; i < a.refine_k; i += 64) {
+        const uint64_t key = i < n2 ? keys[i] : ~0ull;
+        const bool ok = key != ~0ull;
+        a.cand_ids[(size_t)q * a.refine_k + i] = ok ? (int64_t)(uint32_t)key : -1;
+        if (a.cand_score) a.cand_score[(size_t)q * a.refine_k + i] = ok ? (int32_t)(key >> 32) : -1;
+    }
+}
+
+// The same for a query with more survivors, by a whole workgroup: resolve the survivors and keep the
 // bigK smallest (score, id).  A two-pass radix select on the 16-bit score finds the score of the
 // bigK-th survivor; only entries up to that score are sorted.  Overflowed buffers are flagged for
 // the exact redo.
@@ -552,10 +634,7 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a)
     const int64_t q = blockIdx.x;
     if (a.only_flagged && a.only_flagged[q] == 0) return;      // settled in the first pass
     const uint32_t n = a.surv_cnt[q];
-    if (n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) {
-        if (tid == 0) a.flags[q] = 1;       // the exact kernel redoes this query
-        return;
-    }
+    if (n <= SELW_CAP || n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) return;   // select_wave_kernel's cases
     if (tid == 0) a.flags[q] = 0;
     for (int i = tid; i < (int)n; i += WG) {
         uint64_t key = ~0ull;
@@ -837,6 +916,8 @@ int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s
 {
     hipLaunchKernelGGL(collect_kernel, dim3((unsigned)(a.log_chunks < 4096 ? a.log_chunks : 4096)),
                        dim3(LOG_CHUNK), 0, s, a);
+    hipLaunchKernelGGL(select_wave_kernel, dim3((unsigned)((a.nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
+                       0, s, v, a);
     hipLaunchKernelGGL(select_kernel, dim3((unsigned)a.nq), dim3(WG), 0, s, v, a);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;

@@ -146,14 +146,17 @@ def test_adversarial_layouts(binding):
             _compare_all_stages(binding, hx, q, 5, nprobe, 40)
 
 
-def test_identical_codes_tie_on_score(binding):
-    # every vector identical: all scores tie, the order is decided by vector id alone
-    x = np.tile(datagen.random_vectors(50, 1, 8), (600, 1))
+@pytest.mark.parametrize("count", [600, 3000, 6000])
+def test_identical_codes_tie_on_score(binding, count):
+    # every vector identical: all scores tie, the order is decided by vector id alone, and every
+    # scanned item survives any bound (the three sizes end in the wave select, the workgroup
+    # select and the exact redo after an overflow)
+    x = np.tile(datagen.random_vectors(50, 1, 8), (count, 1))
     q = datagen.random_vectors(51, 9, 8)
     cents = datagen.random_vectors(52, 4, 8)
     cb = ib.train_pq(datagen.random_vectors(53, 300, 8), 4, 5, 2)
     g = np.random.Generator(np.random.PCG64(3))
-    asg = np.sort(g.integers(0, 4, size=(600, 2)), axis=1).astype(np.int32)
+    asg = np.sort(g.integers(0, 4, size=(count, 2)), axis=1).astype(np.int32)
     hx = ib.add_vectors(x, cents, cb, assign=asg)
     _compare_all_stages(binding, hx, q, 10, 4, 64)
 
