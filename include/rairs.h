@@ -54,6 +54,9 @@ typedef enum {
  * +list_misc_cnt[L]) -- leftovers of all cells touching L; only the last of these may have empty
  * slots (id -1).  Reference entries [list_ref_begin[L], +list_ref_cnt[L]) of list L each name the
  * blocks of a cell (owner, L), owner < L, stored in list `owner` (Section 5.1).
+ * The leftover items of a cell (i, j), i != j, sit in the miscellaneous areas of BOTH lists, with
+ * the same code, tagged with the other list (Section 5.1); the scan relies on this pairing when
+ * it bounds scores from a sample of a list.  It is not checked at upload.
  */
 typedef struct {
     int32_t d;               /* vector dimension */
@@ -149,10 +152,11 @@ int rairs_refine(rairs_index_t *h, const float *d_queries, const int64_t *d_cand
                  int refine_k, int k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream);
 
 /*
- * Which kernels SeilSearch uses.  RAIRS_SCAN_AUTO (default): the first probed list of every query
- * by the exact one-workgroup-per-query kernel, the other lists by the list-major MFMA kernel
- * (tables in registers for M = 16, 48, 64, in LDS for any other M), overflowing queries redone
- * exactly.
+ * Which kernels SeilSearch uses.  RAIRS_SCAN_AUTO (default): a score bound per query from a
+ * sample of its first probed list, then the list-major MFMA kernel over all probed lists (tables
+ * in registers for M = 16, 48, 64, in LDS for any other M), selection of the bigK best survivors,
+ * a second restricted pass for queries whose survivor buffer overflowed, and the exact
+ * one-workgroup-per-query kernel for any that overflow again.
  * RAIRS_SCAN_EXACT: the exact kernel for everything.  Results are identical in both modes.
  */
 enum { RAIRS_SCAN_AUTO = 0, RAIRS_SCAN_EXACT = 1 };
@@ -160,8 +164,8 @@ int rairs_set_scan_mode(rairs_index_t *h, int mode);
 
 /* ---- measurement --------------------------------------------------------------------------- */
 
-/* SCAN is the whole SeilSearch stage (probe bitmap, first-list scan, grouping, main scan kernel,
-   selection, overflow redo); SCAN_KERNEL is its dominant kernel alone: the list-major MFMA scan,
+/* SCAN is the whole SeilSearch stage (probe bitmap, sample bound, grouping, main scan kernel,
+   selection, overflow passes); SCAN_KERNEL is its dominant kernel alone: the list-major MFMA scan,
    or the exact scan when that one runs instead. */
 enum { RAIRS_STAGE_COARSE = 0, RAIRS_STAGE_LUT = 1, RAIRS_STAGE_SCAN = 2, RAIRS_STAGE_REFINE = 3,
        RAIRS_STAGE_SCAN_KERNEL = 4, RAIRS_NSTAGES = 5 };

@@ -203,6 +203,21 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
         for (int64_t i = b0 * 32; i < b1 * 32; i++) valid += x->ids[i] >= 0;
         e2.valid_items = (int32_t)valid;
     }
+    std::vector<uint32_t> hm((size_t)x->nblocks, 0u);
+    for (int l = 0; l < x->nlist; l++) {
+        const int64_t b0 = x->list_shared_begin[l], bs = b0 + x->list_shared_cnt[l];
+        const int64_t b1 = bs + x->list_misc_cnt[l];
+        for (int64_t b = b0; b < b1; b++) {
+            uint32_t m = 0;
+            for (int i = 0; i < 32; i++) {
+                const int64_t at = b * 32 + i;
+                if (x->ids[at] < 0) continue;
+                const int32_t o = x->other[at];
+                if (b < bs || o < 0 || o >= l) m |= 1u << i;
+            }
+            hm[(size_t)b] = m;
+        }
+    }
     std::vector<RefEntry> hr((size_t)x->nrefs);
     for (int64_t r = 0; r < x->nrefs; r++) {
         hr[(size_t)r].owner = x->ref_owner[r];
@@ -248,6 +263,10 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_CHECK(dev_alloc(h, (void **)&segs, hs.size() * sizeof(SegEntry)));
     if (!hs.empty())
         UP_HIP(hipMemcpyAsync(segs, hs.data(), hs.size() * sizeof(SegEntry), hipMemcpyHostToDevice, s));
+    uint32_t *cmask = nullptr;
+    UP_CHECK(dev_alloc(h, (void **)&cmask, (size_t)x->nblocks * 4));
+    if (x->nblocks)
+        UP_HIP(hipMemcpyAsync(cmask, hm.data(), hm.size() * 4, hipMemcpyHostToDevice, s));
     UP_HIP(hipMemcpyAsync(lists, hl.data(), hl.size() * sizeof(ListEntry), hipMemcpyHostToDevice, s));
     if (x->nrefs)
         UP_HIP(hipMemcpyAsync(refs, hr.data(), hr.size() * sizeof(RefEntry), hipMemcpyHostToDevice, s));
@@ -279,7 +298,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     }
     UP_HIP(hipStreamSynchronize(s));
 
-    v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other;
+    v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask;
     v.lists = lists; v.refs = refs; v.segs = segs; v.raw = raw;
     for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[i]));
     h->ev_ready = 1;
@@ -496,7 +515,10 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     // bound of every query from a sample (the head of its first list), and the DCO of all probes
     ma.p_first = 0;
     ma.bound = (int32_t *)(ws + w.bound);
-    if ((rc = rairs_launch_sample_bound(v, lut, probe_ids, nprobe, refine_k, RAIRS_SAMPLE_BLOCKS, n,
+    // about five times bigK items, so that the bigK-th smallest of them is a low quantile
+    int sample_blocks = (5 * refine_k + 31) / 32;
+    if (sample_blocks < RAIRS_SAMPLE_BLOCKS) sample_blocks = RAIRS_SAMPLE_BLOCKS;
+    if ((rc = rairs_launch_sample_bound(v, lut, probe_ids, nprobe, refine_k, sample_blocks, n,
                                         (int32_t *)(ws + w.tau), ma.bound, s))) return rc;
     if (dco && (rc = rairs_launch_dco(v, probe_ids, bitmap, w.bmwords, nprobe, n, dco, s))) return rc;
     if ((rc = rairs_launch_scan_mfma(v, ma, s, ev))) return rc;

@@ -53,6 +53,9 @@ struct IndexView {
     const uint32_t *codes;
     const uint32_t *ids;          // [nblocks][32], RAIRS_EMPTY_ID = empty slot
     const int32_t *other;         // [nblocks][32]
+    // [nblocks] bit i: slot i holds an item that the duplicate rule can never drop (a shared
+    // block's item, or a miscellaneous item whose other list has no smaller id than the list)
+    const uint32_t *cmask;
     const ListEntry *lists;       // [nlist]
     const RefEntry *refs;         // [nrefs]
     const SegEntry *segs;         // [nsegs]

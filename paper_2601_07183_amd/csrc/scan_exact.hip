@@ -152,28 +152,32 @@ int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t 
 // ---- bound from a sample ------------------------------------------------------------------------
 //
 // tau[q] = bigK-th smallest score among the items of the first `sample_blocks` own blocks of the
-// query's first probed list (0xFFFF when they hold fewer than bigK items).  Any valid item there
-// is a distinct member of the probed set, duplicate rule or not, so the bigK best of the whole
-// probed set all score <= tau.  One wave per query; the sample's scores stay in registers and the
-// rank is found by bisection on the 16 score bits with wave ballots.
-#define SAMPLE_MAX_BLOCKS 16
+// query's first probed list (0xFFFF when they hold fewer than bigK items).  Every item there is
+// either an entry of the query's candidate queue or, when the duplicate rule drops it, the twin of
+// an entry with the same code that is queued from its other list (SEIL keeps the remainder of a
+// cell in the miscellaneous areas of both lists, Section 5.1); so at least bigK entries of the
+// queue score <= tau.  One wave per query; the sample's scores sit in LDS and the rank is found by
+// bisection on the 16 score bits.
+#define SAMPLE_MAX_BLOCKS 128
 __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uint8_t *__restrict__ lut,
                                                           const int32_t *__restrict__ probe_ids,
                                                           int nprobe, int refine_k, int sample_blocks,
                                                           int64_t nq, int32_t *__restrict__ tau,
                                                           int32_t *__restrict__ bound)
 {
-    __shared__ __align__(16) uint8_t lut_s[WG / 64][RAIRS_MAX_M * 16];
+    extern __shared__ __align__(16) uint8_t sample_lds[];  // per wave: M*16 table bytes, then sample_blocks*32 scores
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
     const int64_t qi0 = (int64_t)blockIdx.x * (WG / 64) + wave;
     const int64_t qi = qi0 < nq ? qi0 : nq - 1;          // surplus waves redo the last query
+    const size_t per_wave = (size_t)v.M * 16 + (size_t)sample_blocks * 64;
+    uint8_t *lq = sample_lds + wave * per_wave;
+    uint16_t *sc = (uint16_t *)(lq + (size_t)v.M * 16);
     {
         const uint4 *src = (const uint4 *)(lut + (size_t)qi * v.M * 16);
-        uint4 *dst = (uint4 *)lut_s[wave];
+        uint4 *dst = (uint4 *)lq;
         for (int i = lane; i < v.M; i += 64) dst[i] = src[i];
     }
     __syncthreads();
-    const uint8_t *lq = lut_s[wave];
     const int L = probe_ids[(size_t)qi * nprobe];
     int cnt = 0;
     int64_t begin = 0;
@@ -183,38 +187,45 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
         cnt = le.shared_cnt + le.misc_cnt;
         cnt = cnt < sample_blocks ? cnt : sample_blocks;
     }
-    uint32_t sc[SAMPLE_MAX_BLOCKS];
     uint32_t nvalid = 0;
+    for (int b0 = 0; b0 < cnt; b0 += 4) {               // four blocks in flight
+        uint32_t part[4];
+        bool valid[4];
 #pragma unroll
-    for (int b = 0; b < SAMPLE_MAX_BLOCKS; b++) {
-        sc[b] = 0xFFFFFFFFu;
-        if (b < cnt) {                                  // wave-uniform
-            const int64_t blk = begin + b;
+        for (int u = 0; u < 4; u++) {
+            const int64_t blk = begin + (b0 + u < cnt ? b0 + u : cnt - 1);
             const uint32_t *cp = v.codes + (size_t)blk * v.nd * 64 + lane;
-            uint32_t part = 0;
+            part[u] = 0;
             for (int w = 0; w < v.nd; w++) {
                 const uint32_t c = cp[(size_t)w * 64];
                 const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
                 for (int n = 0; n < tmax; n++) {
                     const int m = 2 * (8 * w + n) + g;
-                    part += lq[m * 16 + ((c >> (4 * n)) & 15u)];
+                    part[u] += lq[m * 16 + ((c >> (4 * n)) & 15u)];
                 }
             }
-            const uint32_t acc = part + (uint32_t)__shfl_xor((int)part, 32);
-            const bool valid = lane < 32 && v.ids[(size_t)blk * 32 + lane] != RAIRS_EMPTY_ID;
-            if (valid) sc[b] = acc;
-            nvalid += (uint32_t)__popcll(__ballot(valid));
+            valid[u] = lane < 32 && b0 + u < cnt && v.ids[(size_t)blk * 32 + lane] != RAIRS_EMPTY_ID;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const uint32_t acc = part[u] + (uint32_t)__shfl_xor((int)part[u], 32);
+            if (lane < 32 && b0 + u < cnt) sc[(b0 + u) * 32 + lane] = valid[u] ? (uint16_t)acc : (uint16_t)0xFFFFu;
+            nvalid += (uint32_t)__popcll(__ballot(valid[u]));
         }
     }
+    __syncthreads();
     uint32_t t = 0xFFFFu;
     if (nvalid >= (uint32_t)refine_k) {
         // largest t with fewer than bigK scores below it == the bigK-th smallest score
+        // (empty slots hold 0xFFFF, which no candidate t exceeds)
+        const int n = cnt * 32;
         t = 0;
         for (int bit = 15; bit >= 0; bit--) {
             const uint32_t cand = t | (1u << bit);
             uint32_t below = 0;
+            for (int e = lane; e < n; e += 64) below += sc[e] < cand ? 1u : 0u;
 #pragma unroll
-            for (int b = 0; b < SAMPLE_MAX_BLOCKS; b++) below += (uint32_t)__popcll(__ballot(sc[b] < cand));
+            for (int off = 32; off >= 1; off >>= 1) below += (uint32_t)__shfl_xor((int)below, off);
             if (below < (uint32_t)refine_k) t = cand;
         }
     }
@@ -229,8 +240,10 @@ int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int3
                               int32_t *bound, hipStream_t s)
 {
     if (sample_blocks > SAMPLE_MAX_BLOCKS) sample_blocks = SAMPLE_MAX_BLOCKS;
+    if (sample_blocks < 1) sample_blocks = 1;
+    const size_t lds = (size_t)(WG / 64) * ((size_t)v.M * 16 + (size_t)sample_blocks * 64);
     hipLaunchKernelGGL(sample_bound_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
-                       0, s, v, lut, probe_ids, nprobe, refine_k, sample_blocks, nq, tau, bound);
+                       lds, s, v, lut, probe_ids, nprobe, refine_k, sample_blocks, nq, tau, bound);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }

@@ -18,12 +18,14 @@
 // survivors go to the query's buffer and are cut to bigK afterwards by select_kernel.
 //
 // The bound.  tau0 = bigK-th smallest score in a sample, the head of the query's first list.  Every
-// survivor is also counted in a per-query histogram of RAIRS_HIST_BINS equal score bins over
-// [0, tau0] (over [0, 255*M] when the first list had fewer than bigK items).  Survivors are
-// distinct members of the query's probed lists, so once bins 0..b hold >= bigK of them, no item
-// scoring above the top edge of bin b can be among the bigK best: that edge is a valid, tighter
-// bound.  The lane that files a survivor re-derives the query's bound and lowers it with an
-// atomic minimum; scanning waves re-read it for every block.  A stale view is only looser.
+// survivor that the duplicate rule can never drop (an item of a shared block, or a miscellaneous
+// item whose other list has the larger id; the index keeps one bit per slot for this) is counted in
+// a per-query histogram of RAIRS_HIST_BINS equal score bins over [0, tau0] (over [0, 255*M] when
+// the sample had fewer than bigK items).  Each counted slot is an entry of the query's candidate
+// queue, so once bins 0..b hold >= bigK of them, no item scoring above the top edge of bin b can be
+// among the bigK best: that edge is a valid, tighter bound.  Lanes that file survivors re-derive
+// the query's bound now and then and lower it with an atomic minimum; scanning waves re-read it
+// for every block.  A stale view is only looser.
 #include <limits.h>
 
 #include "device_util.h"
@@ -209,15 +211,22 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(const int32_t *__restr
 
 // ---- the scan ----------------------------------------------------------------------------------
 
-// Tightest bound the histogram of query `qid` proves.  The histogram counts scored item slots,
-// and a vector can sit in at most two scanned slots (the miscellaneous areas of its two lists),
-// so once bins 0..b hold >= 2 * bigK slots they hold >= bigK distinct members: nothing scoring
-// above the top edge of bin b can be among the bigK best.
+// Bin of a score: floor(score * mul / 2^32) with mul = floor(2^38 / (range + 1)), range >= 64, so
+// that scores 0..range fall into bins 0..63 without a division on the hot path.
+static __device__ __forceinline__ uint32_t hist_mul(uint32_t range)
+{
+    const uint32_t r = range < 64u ? 64u : range;
+    return (uint32_t)((1ull << 38) / (uint64_t)(r + 1u));
+}
+
+// Tightest bound the histogram of query `qid` proves: the histogram counts queue entries, so once
+// bins 0..b hold >= bigK of them nothing scoring above the top edge of bin b can be among the
+// bigK best.
 static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a, int qid,
-                                                           uint32_t range)
+                                                           uint32_t mul)
 {
     const uint4 *hq = (const uint4 *)(a.hist + (size_t)qid * RAIRS_HIST_BINS);
-    const uint32_t need = 2u * (uint32_t)a.refine_k;
+    const uint32_t need = (uint32_t)a.refine_k;
     uint4 h[RAIRS_HIST_BINS / 4];
 #pragma unroll
     for (int i = 0; i < RAIRS_HIST_BINS / 4; i++) h[i] = hq[i];      // all loads in flight at once
@@ -231,7 +240,9 @@ static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a
         cum += h[i].w; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i + 3 : b;
     }
     if (b == RAIRS_HIST_BINS) return 0xFFFFu;
-    return ((uint32_t)(b + 1) * (range + 1u) - 1u) / RAIRS_HIST_BINS;
+    // largest score whose bin is <= b
+    const uint64_t edge = ((((uint64_t)(b + 1)) << 32) - 1ull) / (uint64_t)mul;
+    return edge < 0xFFFFull ? (uint32_t)edge : 0xFFFFu;
 }
 
 // A passing (item, query) pair waits in a per-wave LDS queue until enough have gathered; then the
@@ -245,8 +256,8 @@ static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a
 struct StageQueue {
     uint32_t slot[STAGE_CAP];      // block * 32 + item
     uint32_t score_list[STAGE_CAP];// score << 16 | probed list
-    int32_t qid[STAGE_CAP];
-    uint32_t lrange[STAGE_CAP];    // score range of the query's histogram
+    uint32_t qid[STAGE_CAP];       // bit 31: the entry counts in the histogram
+    uint32_t hmul[STAGE_CAP];      // hist_mul of the query's score range
 };
 
 struct LogCursor {
@@ -254,7 +265,7 @@ struct LogCursor {
 };
 
 static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQueue &sq, int n,
-                                                   int lane, LogCursor &lc, bool refresh)
+                                                   int lane, LogCursor &lc, uint32_t nflush)
 {
     if (lc.used + (uint32_t)n > LOG_CHUNK) {
         // close the chunk, move to the one reserved earlier, reserve another
@@ -271,19 +282,20 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
     for (int u = 0; u < STAGE_CAP / 64; u++) {
         const int i = lane + 64 * u;
         if (i < n) {
-            const int qid = sq.qid[i];
-            const uint32_t sl = sq.score_list[i], range = sq.lrange[i];
+            const uint32_t qraw = sq.qid[i], qid = qraw & 0x7FFFFFFFu;
+            const uint32_t sl = sq.score_list[i];
             if (room)
-                a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint4(sq.slot[i], sl, (uint32_t)qid, 0u);
-            if (!a.fixed_bound)
-                atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + ((sl >> 16) * RAIRS_HIST_BINS) / (range + 1u)], 1u);
+                a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint4(sq.slot[i], sl, qid, 0u);
+            if (!a.fixed_bound && (qraw >> 31))
+                atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + __umulhi(sl >> 16, sq.hmul[i])], 1u);
         }
     }
-    if (refresh && !a.fixed_bound && lane < n && (lane & 3) == 0) {
-        // every fourth entry of the first row also refreshes its query's bound.  A stale
-        // histogram only gives a looser bound; the bound itself only ever shrinks.
-        const int qid = sq.qid[lane];
-        const uint32_t nb = histogram_bound(a, qid, sq.lrange[lane]);
+    if ((nflush & 1u) == 0u && !a.fixed_bound && lane < n && ((lane + (nflush >> 1)) & 3) == 0) {
+        // at every other flush a quarter of the first row's entries, a different quarter each
+        // time, also refresh their query's bound.  A stale histogram only gives a looser bound;
+        // the bound itself only ever shrinks.
+        const int qid = (int)(sq.qid[lane] & 0x7FFFFFFFu);
+        const uint32_t nb = histogram_bound(a, qid, sq.hmul[lane]);
         if (nb < 0xFFFFu) atomicMin(&a.bound[qid], (int32_t)nb);
     }
     lc.used += (uint32_t)n;
@@ -335,7 +347,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #endif
 #define FLUSH_STAGE()                                                   \
     do {                                                                \
-        stage_flush(a, sq, nstaged, lane, lc, (nflush & 1u) == 0u);     \
+        stage_flush(a, sq, nstaged, lane, lc, nflush);     \
         nstaged = 0;                                                    \
         nflush++;                                                       \
     } while (0)
@@ -356,14 +368,14 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         PC_ADD(pc_decode);
         PC_MARK();
         int qid;
-        uint32_t range;
+        uint32_t hmul;
         {
             // the tile: query of this lane's column and its tables
             const int base = a.loff[L], n = a.loff[L + 1] - base;
             const int qi = tile * 32 + j;
             qid = qi < n ? a.qlist[base + qi] : -1;
             const uint32_t tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
-            range = tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0;
+            hmul = hist_mul(tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0);
             const uint8_t *lq = a.lut + (size_t)(qid >= 0 ? qid : 0) * (M * 16) + g * 16;
 #pragma unroll
             for (int t = 0; t < T; t++) {
@@ -387,6 +399,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         uint32_t cn[ND];
 #pragma unroll
         for (int w = 0; w < ND; w++) cn[w] = cp[w * 64];
+        uint32_t cmn = v.cmask[se.blk_begin];          // countable slots of the block, fetched with its codes
         for (int seg = seg0; seg < seg1; seg++) {
 #ifdef RAIRS_PROFILE_CYCLES
             pc_ntask++;
@@ -402,6 +415,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                 if (has_next) {
 #pragma unroll
                     for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64];
+                    cmn = v.cmask[sen.blk_begin];
                 }
             } else {
                 for (int b = 0; b < se.nblk; b++) {
@@ -409,14 +423,17 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                     uint32_t c[ND];
 #pragma unroll
                     for (int w = 0; w < ND; w++) c[w] = cn[w];
+                    const uint32_t cmask = cmn;
                     const int th = live ? bound_next - bias : INT_MIN;
                     bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     if (b + 1 < se.nblk) {             // fetch the next block while this one is scored
 #pragma unroll
                         for (int w = 0; w < ND; w++) cn[w] = cp[(size_t)(b + 1) * ND * 64 + w * 64];
+                        cmn = v.cmask[se.blk_begin + b + 1];
                     } else if (has_next) {             // ... or the first block of the next run
 #pragma unroll
                         for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64];
+                        cmn = v.cmask[sen.blk_begin];
                     }
                     v16i acc;
 #pragma unroll
@@ -457,10 +474,11 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #pragma unroll
                                 for (int k = 1; k < 16; k++) sc = r == k ? acc[k] : sc;
                                 const int pos = nstaged + __popcll(mask & lt_mask);
-                                sq.slot[pos] = slot0 + 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);
+                                const uint32_t item = 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);   // + 4 g
+                                sq.slot[pos] = slot0 + item;
                                 sq.score_list[pos] = ((uint32_t)(sc + bias) << 16) | (uint32_t)L;
-                                sq.qid[pos] = qid;
-                                sq.lrange[pos] = range;
+                                sq.qid[pos] = (uint32_t)qid | (((cmask >> (item + 4u * g)) & 1u) << 31);
+                                sq.hmul[pos] = hmul;
                             }
                             nstaged += __popcll(mask);
                             if (nstaged > STAGE_CAP - 64) {
@@ -773,7 +791,7 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
         const int qi = tile * 32 + j;
         const int qid = qi < nql ? a.qlist[base + qi] : -1;
         const uint32_t tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
-        const uint32_t range = tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0;
+        const uint32_t hmul = hist_mul(tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0);
         const int32_t *bq = a.bound + (qid >= 0 ? qid : 0);
         const uint32_t *bmq = a.bitmap + (size_t)(qid >= 0 ? qid : 0) * a.bmwords;
         __syncthreads();
@@ -787,6 +805,7 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
                 const int th = live ? __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - bias
                                     : INT_MIN;
                 const uint32_t *cp = v.codes + (size_t)(se.blk_begin + b) * ND * 64 + lane;
+                const uint32_t cmask = v.cmask[se.blk_begin + b];
                 v16i acc;
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[r] = 0;
@@ -822,14 +841,15 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
 #pragma unroll
                             for (int k = 1; k < 16; k++) sc = r == k ? acc[k] : sc;
                             const int pos = nstaged + __popcll(mask & lt_mask);
-                            sq.slot[pos] = slot0 + 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);
+                            const uint32_t item = 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);   // + 4 g
+                            sq.slot[pos] = slot0 + item;
                             sq.score_list[pos] = ((uint32_t)(sc + bias) << 16) | (uint32_t)L;
-                            sq.qid[pos] = qid;
-                            sq.lrange[pos] = range;
+                            sq.qid[pos] = (uint32_t)qid | (((cmask >> (item + 4u * g)) & 1u) << 31);
+                            sq.hmul[pos] = hmul;
                         }
                         nstaged += __popcll(mask);
                         if (nstaged > STAGE_CAP - 64) {
-                            stage_flush(a, sq, nstaged, lane, lc, (nflush & 1u) == 0u);
+                            stage_flush(a, sq, nstaged, lane, lc, nflush);
                             nstaged = 0;
                             nflush++;
                         }
@@ -838,12 +858,12 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
             }
         }
         if (nstaged >= 32) {
-            stage_flush(a, sq, nstaged, lane, lc, (nflush & 1u) == 0u);
+            stage_flush(a, sq, nstaged, lane, lc, nflush);
             nstaged = 0;
             nflush++;
         }
     }
-    if (nstaged > 0) stage_flush(a, sq, nstaged, lane, lc, true);
+    if (nstaged > 0) stage_flush(a, sq, nstaged, lane, lc, 0u);
     if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
 }
 
