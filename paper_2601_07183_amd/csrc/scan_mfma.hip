@@ -261,7 +261,10 @@ struct StageQueue {
 };
 
 struct LogCursor {
-    uint32_t chunk, used, next_chunk;   // wave-uniform
+    uint32_t chunk, used;               // wave-uniform
+    uint32_t next_v;                    // lane 0: the chunk reserved for later (left in a vector
+                                        // register so that nobody waits for the atomic's answer
+                                        // before the chunk is needed)
 };
 
 static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQueue &sq, int n,
@@ -270,11 +273,11 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
     if (lc.used + (uint32_t)n > LOG_CHUNK) {
         // close the chunk, move to the one reserved earlier, reserve another
         if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
-        lc.chunk = lc.next_chunk;
+        lc.chunk = (uint32_t)__builtin_amdgcn_readfirstlane((int)lc.next_v);
         lc.used = 0;
         uint32_t nx = 0;
         if (lane == 0) nx = atomicAdd(a.log_cursor, 1u);
-        lc.next_chunk = (uint32_t)__builtin_amdgcn_readfirstlane((int)nx);
+        lc.next_v = nx;
     }
     const bool room = lc.chunk < (uint32_t)a.log_chunks;
     if (!room && lane == 0) *a.log_overflow = 1u;      // every query is then redone exactly
@@ -333,7 +336,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
     const uint32_t gwave = blockIdx.x * (WG / 64) + (threadIdx.x >> 6), nwaves = gridDim.x * (WG / 64);
     LogCursor lc;
     lc.chunk = gwave;
-    lc.next_chunk = gwave + nwaves;
+    lc.next_v = gwave + nwaves;
     lc.used = 0;
     uint32_t nflush = 0;
 #ifdef RAIRS_PROFILE_CYCLES
@@ -377,11 +380,14 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
             const uint32_t tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
             hmul = hist_mul(tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0);
             const uint8_t *lq = a.lut + (size_t)(qid >= 0 ? qid : 0) * (M * 16) + g * 16;
+            // every lane loads (an absent column reads query 0's rows and masks them to zero): a
+            // conditional load would be waited for one by one
+            const int keep = qid >= 0 ? -1 : 0;
 #pragma unroll
             for (int t = 0; t < T; t++) {
                 v4i x = *(const v4i *)(lq + t * 32);
                 x ^= (v4i){(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
-                B[t] = qid >= 0 ? x : (v4i){0, 0, 0, 0};
+                B[t] = x & (v4i){keep, keep, keep, keep};
             }
 #ifdef RAIRS_PROFILE_CYCLES
             { int sink = B[0].x ^ B[T - 1].w; asm volatile("" :: "v"(sink)); pc_ntile++; }
@@ -393,8 +399,11 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         const int32_t *bq = a.bound + (qid >= 0 ? qid : 0);
         int bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const uint32_t *bmq = a.bitmap + (size_t)(qid >= 0 ? qid : 0) * a.bmwords;
+        // segment entries run two ahead and the owner's bitmap word one ahead, so that neither
+        // is waited for at the head of a segment
         SegEntry se = v.segs[le.seg_begin + seg0];
-        uint32_t owner_bits = se.owner >= 0 ? bmq[se.owner >> 5] : 0u;
+        SegEntry sen = v.segs[le.seg_begin + (seg0 + 1 < seg1 ? seg0 + 1 : seg0)];
+        uint32_t owner_bits = bmq[se.owner >= 0 ? se.owner >> 5 : 0];
         const uint32_t *cp = v.codes + (size_t)se.blk_begin * ND * 64 + lane;
         uint32_t cn[ND];
 #pragma unroll
@@ -405,11 +414,11 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
             pc_ntask++;
 #endif
             const bool has_next = seg + 1 < seg1;
-            const SegEntry sen = v.segs[le.seg_begin + (has_next ? seg + 1 : seg)];
+            const SegEntry sen2 = v.segs[le.seg_begin + (seg + 2 < seg1 ? seg + 2 : seg1 - 1)];
+            const uint32_t ob_next = bmq[sen.owner >= 0 ? sen.owner >> 5 : 0];
             const uint32_t *cpn = v.codes + (size_t)sen.blk_begin * ND * 64 + lane;
             // cell (owner, L) is scored through list `owner` for queries that probe it
             const bool live = qid >= 0 && !(se.owner >= 0 && ((owner_bits >> (se.owner & 31)) & 1u));
-            owner_bits = has_next && sen.owner >= 0 ? bmq[sen.owner >> 5] : 0u;
             if (__ballot(live) == 0ull) {
                 // nobody needs this run; keep the prefetch chain going
                 if (has_next) {
@@ -496,6 +505,8 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                 }
             }
             se = sen;
+            sen = sen2;
+            owner_bits = ob_next;
             cp = cpn;
         }
         // do not sit on survivors for long: their histogram counts tighten everyone's bound
@@ -760,7 +771,7 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
     const uint32_t gwave = blockIdx.x * (WG / 64) + wave, nwaves = gridDim.x * (WG / 64);
     LogCursor lc;
     lc.chunk = gwave;
-    lc.next_chunk = gwave + nwaves;
+    lc.next_v = gwave + nwaves;
     lc.used = 0;
     for (bool first = true;; first = false) {
         __syncthreads();                               // everyone is done with the previous tile
