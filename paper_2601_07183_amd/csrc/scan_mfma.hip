@@ -479,9 +479,14 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                             if (has) {
                                 const int r = __builtin_ctz(pm);
                                 pm &= pm - 1u;
-                                int sc = acc[0];
+                                // acc[r] by a four-level selection on the bits of r
+                                int s8[8], s4[4];
 #pragma unroll
-                                for (int k = 1; k < 16; k++) sc = r == k ? acc[k] : sc;
+                                for (int k = 0; k < 8; k++) s8[k] = (r & 1) ? acc[2 * k + 1] : acc[2 * k];
+#pragma unroll
+                                for (int k = 0; k < 4; k++) s4[k] = (r & 2) ? s8[2 * k + 1] : s8[2 * k];
+                                const int s2a = (r & 4) ? s4[1] : s4[0], s2b = (r & 4) ? s4[3] : s4[2];
+                                const int sc = (r & 8) ? s2b : s2a;
                                 const int pos = nstaged + __popcll(mask & lt_mask);
                                 const uint32_t item = 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);   // + 4 g
                                 sq.slot[pos] = slot0 + item;
@@ -848,9 +853,13 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
                         if (has) {
                             const int r = __builtin_ctz(pm);
                             pm &= pm - 1u;
-                            int sc = acc[0];
+                            int s8[8], s4[4];
 #pragma unroll
-                            for (int k = 1; k < 16; k++) sc = r == k ? acc[k] : sc;
+                            for (int k = 0; k < 8; k++) s8[k] = (r & 1) ? acc[2 * k + 1] : acc[2 * k];
+#pragma unroll
+                            for (int k = 0; k < 4; k++) s4[k] = (r & 2) ? s8[2 * k + 1] : s8[2 * k];
+                            const int s2a = (r & 4) ? s4[1] : s4[0], s2b = (r & 4) ? s4[3] : s4[2];
+                            const int sc = (r & 8) ? s2b : s2a;
                             const int pos = nstaged + __popcll(mask & lt_mask);
                             const uint32_t item = 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);   // + 4 g
                             sq.slot[pos] = slot0 + item;
