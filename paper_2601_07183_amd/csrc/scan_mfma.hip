@@ -742,19 +742,20 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a)
 
 // ---- the same scan with the tile's tables in LDS (any M up to 256) ----------------------------
 //
-// For tables too large for registers (M = 240: 30 KB per query pair of lanes) the four waves of a
-// workgroup share one tile: its tables sit in LDS as [K-step][lane] 16-byte operands, zero beyond
+// For tables too large for registers (M = 240: 30 KB per query pair of lanes) the waves of a
+// workgroup (as many as LDS leaves room for, up to 16) share one tile: its tables sit in LDS as [K-step][lane] 16-byte operands, zero beyond
 // the last subspace, and the waves take the unit's blocks round robin.  Each MFMA then reads both
 // operands from LDS (one-hot row and table row), which holds it to about half the matrix-core
 // rate; survivors, bounds and the log work exactly as in scan_mfma_kernel.
-__global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaScanArgs a)
+__global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, MfmaScanArgs a)
 {
     extern __shared__ __align__(16) unsigned char dyn_lds[];
-    __shared__ StageQueue stage[WG / 64];
     __shared__ v4i onehot[16];
     __shared__ uint32_t s_unit;
     const int ND = v.nd, KS = ND * 8;                   // K-steps incl. zero padding
+    const int nthreads = blockDim.x, nwave = nthreads >> 6;
     v4i *Bl = (v4i *)dyn_lds;                           // [KS][64]
+    StageQueue *stage = (StageQueue *)(dyn_lds + (size_t)KS * 64 * 16);   // [nwave]
     if (threadIdx.x < 16) {
         v4i r = {0, 0, 0, 0};
         const int sh = 1 << ((threadIdx.x & 3) * 8);
@@ -773,7 +774,7 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
     uint32_t nflush = 0;
     const uint32_t nunits = (uint32_t)a.toff[v.nlist];
     if (nunits == 0u) return;                          // uniform; nothing was written
-    const uint32_t gwave = blockIdx.x * (WG / 64) + wave, nwaves = gridDim.x * (WG / 64);
+    const uint32_t gwave = blockIdx.x * nwave + wave, nwaves = gridDim.x * nwave;
     LogCursor lc;
     lc.chunk = gwave;
     lc.next_v = gwave + nwaves;
@@ -793,7 +794,7 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
         const int seg1 = seg0 + a.unit_segs < le.seg_cnt ? seg0 + a.unit_segs : le.seg_cnt;
         const int base = a.loff[L], nql = a.loff[L + 1] - base;
         // tables of the tile into LDS: operand (t, lane (j, g)) = lut[q_j][2t+g][0..15] - 128
-        for (int e = threadIdx.x; e < KS * 64; e += WG) {
+        for (int e = threadIdx.x; e < KS * 64; e += nthreads) {
             const int t = e >> 6, ln = e & 63, jj = ln & 31, gg = ln >> 5;
             const int qi = tile * 32 + jj;
             v4i x = {0, 0, 0, 0};
@@ -817,7 +818,7 @@ __global__ __launch_bounds__(WG, 1) void scan_mfma_lds_kernel(IndexView v, MfmaS
             bool live = qid >= 0;
             if (se.owner >= 0 && qid >= 0 && ((bmq[se.owner >> 5] >> (se.owner & 31)) & 1u)) live = false;
             if (__ballot(live) == 0ull) continue;
-            for (int b = wave; b < se.nblk; b += WG / 64) {
+            for (int b = wave; b < se.nblk; b += nwave) {
                 const int th = live ? __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - bias
                                     : INT_MIN;
                 const uint32_t *cp = v.codes + (size_t)(se.blk_begin + b) * ND * 64 + lane;
@@ -906,7 +907,11 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     // persistent grid: 256 compute units x 2 workgroups of 4 waves, or one when the tables are in LDS
     const bool reg_tables = v.T == 8 || v.T == 24 || v.T == 32;
     const dim3 grid(reg_tables ? 512 : 256);
-    const uint32_t nwaves = grid.x * (WG / 64);
+    // tables in LDS: one workgroup per compute unit with as many waves as LDS leaves room for
+    const size_t table_bytes = (size_t)v.nd * 8 * 64 * 16;
+    int lds_waves = 16;
+    while (lds_waves > 4 && table_bytes + (size_t)lds_waves * sizeof(StageQueue) > 158 * 1024) lds_waves >>= 1;
+    const uint32_t nwaves = grid.x * (reg_tables ? WG / 64 : lds_waves);
     if (a.log_chunks < (int)(2 * nwaves)) {
         rairs_set_error("survivor log of %d chunks is below %u", a.log_chunks, 2 * nwaves);
         return RAIRS_EINVAL;
@@ -940,11 +945,10 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     case 24: hipLaunchKernelGGL(scan_mfma_kernel<24>, grid, dim3(WG), 0, s, v, a); break;
     case 32: hipLaunchKernelGGL(scan_mfma_kernel<32>, grid, dim3(WG), 0, s, v, a); break;
     default: {
-        // tables in LDS: one workgroup per compute unit
-        const size_t lds = (size_t)v.nd * 8 * 64 * 16;
+        const size_t lds = table_bytes + (size_t)lds_waves * sizeof(StageQueue);
         RAIRS_HIP(hipFuncSetAttribute((const void *)scan_mfma_lds_kernel,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(scan_mfma_lds_kernel, grid, dim3(WG), lds, s, v, a);
+        hipLaunchKernelGGL(scan_mfma_lds_kernel, grid, dim3(64 * lds_waves), lds, s, v, a);
     }
     }
     if (ev) RAIRS_HIP(hipEventRecord(ev[1], s));
