@@ -498,6 +498,9 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
         const int64_t segs_total = tiles * (h->nsegs / (v.nlist > 0 ? v.nlist : 1) + 1);
         int us = (int)(segs_total / (2048 * 6));
         ma.unit_segs = us < 1 ? 1 : (us > 8 ? 8 : us);
+        // with the tables in LDS a whole workgroup shares a unit and reloads up to 128 KB of
+        // tables for each: always the longest units
+        if (!(v.T == 8 || v.T == 24 || v.T == 32)) ma.unit_segs = 8;
     }
     ma.next_task = (uint32_t *)(ws + w.next_task); ma.qlist = (int32_t *)(ws + w.qlist);
     ma.tau = (int32_t *)(ws + w.tau); ma.surv_cnt = (uint32_t *)(ws + w.surv_cnt);

@@ -747,12 +747,15 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a)
 // the last subspace, and the waves take the unit's blocks round robin.  Each MFMA then reads both
 // operands from LDS (one-hot row and table row), which holds it to about half the matrix-core
 // rate; survivors, bounds and the log work exactly as in scan_mfma_kernel.
+#define LDSK_MAX_ND 16      // code dwords per lane and block: M <= 256
+#define LDSK_MAX_SEGS 8     // segments per unit
 __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, MfmaScanArgs a)
 {
     extern __shared__ __align__(16) unsigned char dyn_lds[];
     __shared__ v4i onehot[16];
+    __shared__ SegEntry segs_s[LDSK_MAX_SEGS];
     __shared__ uint32_t s_unit;
-    const int ND = v.nd, KS = ND * 8;                   // K-steps incl. zero padding
+    const int ND = v.nd, KS = ND * 8;                   // K-steps incl. zero padding, ND <= LDSK_MAX_ND
     const int nthreads = blockDim.x, nwave = nthreads >> 6;
     v4i *Bl = (v4i *)dyn_lds;                           // [KS][64]
     StageQueue *stage = (StageQueue *)(dyn_lds + (size_t)KS * 64 * 16);   // [nwave]
@@ -793,6 +796,8 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
         const int seg0 = (rem % parts) * a.unit_segs;
         const int seg1 = seg0 + a.unit_segs < le.seg_cnt ? seg0 + a.unit_segs : le.seg_cnt;
         const int base = a.loff[L], nql = a.loff[L + 1] - base;
+        const int nseg = seg1 - seg0;                  // <= LDSK_MAX_SEGS
+        if ((int)threadIdx.x < nseg) segs_s[threadIdx.x] = v.segs[le.seg_begin + seg0 + threadIdx.x];
         // tables of the tile into LDS: operand (t, lane (j, g)) = lut[q_j][2t+g][0..15] - 128
         for (int e = threadIdx.x; e < KS * 64; e += nthreads) {
             const int t = e >> 6, ln = e & 63, jj = ln & 31, gg = ln >> 5;
@@ -812,40 +817,73 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
         const int32_t *bq = a.bound + (qid >= 0 ? qid : 0);
         const uint32_t *bmq = a.bitmap + (size_t)(qid >= 0 ? qid : 0) * a.bmwords;
         __syncthreads();
-        for (int seg = seg0; seg < seg1; seg++) {
-            const SegEntry se = v.segs[le.seg_begin + seg];
-            // cell (owner, L) is scored through list `owner` for queries that probe it
-            bool live = qid >= 0;
-            if (se.owner >= 0 && qid >= 0 && ((bmq[se.owner >> 5] >> (se.owner & 31)) & 1u)) live = false;
-            if (__ballot(live) == 0ull) continue;
-            for (int b = wave; b < se.nblk; b += nwave) {
-                const int th = live ? __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - bias
-                                    : INT_MIN;
-                const uint32_t *cp = v.codes + (size_t)(se.blk_begin + b) * ND * 64 + lane;
-                const uint32_t cmask = v.cmask[se.blk_begin + b];
+        // The unit's blocks, numbered through its segments, are dealt to the waves in turn; a wave
+        // fetches all code dwords of its next block (and that block's segment facts) while it
+        // multiplies the current one.
+        struct Blk { int valid, seg, b, blk, last; bool live; };
+        int fpos = wave;                               // number of this wave's next block in the unit
+        int wseg = 0, wbase = 0;                       // segment that holds it, blocks before that segment
+        auto locate = [&]() {
+            Blk r;
+            r.valid = 0; r.seg = 0; r.b = 0; r.blk = 0; r.last = 0; r.live = false;
+            while (wseg < nseg && fpos >= wbase + segs_s[wseg].nblk) { wbase += segs_s[wseg].nblk; wseg++; }
+            if (wseg < nseg) {
+                const int owner = segs_s[wseg].owner;
+                r.valid = 1; r.seg = wseg; r.b = fpos - wbase;
+                r.blk = segs_s[wseg].blk_begin + r.b;
+                r.last = r.b == segs_s[wseg].nblk - 1;
+                // cell (owner, L) is scored through list `owner` for queries that probe it
+                const uint32_t ob = bmq[owner >= 0 ? owner >> 5 : 0];
+                r.live = qid >= 0 && !(owner >= 0 && ((ob >> (owner & 31)) & 1u));
+            }
+            return r;
+        };
+        uint32_t cn[LDSK_MAX_ND], cmn = 0;
+        int bound_next = 0;
+        auto fetch = [&](const Blk &bk) {
+            const uint32_t *cp = v.codes + (size_t)bk.blk * ND * 64 + lane;
+#pragma unroll
+            for (int w = 0; w < LDSK_MAX_ND; w++)
+                if (w < ND) cn[w] = cp[(size_t)w * 64];
+            cmn = v.cmask[bk.blk];
+            bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        };
+        Blk cur = locate();
+        if (cur.valid) fetch(cur);
+        while (cur.valid) {
+            uint32_t c[LDSK_MAX_ND];
+#pragma unroll
+            for (int w = 0; w < LDSK_MAX_ND; w++) c[w] = cn[w];
+            const uint32_t cmask = cmn;
+            const int th = cur.live ? bound_next - bias : INT_MIN;
+            fpos += nwave;
+            const Blk nxt = locate();
+            if (nxt.valid) fetch(nxt);
+            if (__ballot(cur.live) != 0ull) {
                 v16i acc;
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[r] = 0;
-                uint32_t c = cp[0];
-                for (int w = 0; w < ND; w++) {
-                    const uint32_t cnext = w + 1 < ND ? cp[(size_t)(w + 1) * 64] : 0u;
-                    const v4i *Bw = Bl + (size_t)w * 8 * 64 + lane;
 #pragma unroll
-                    for (int n = 0; n < 8; n++) {
-                        const uint32_t nib = (c >> (4 * n)) & 15u;
-                        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(onehot[nib], Bw[n * 64], acc, 0, 0, 0);
+                for (int w = 0; w < LDSK_MAX_ND; w++) {
+                    if (w < ND) {                      // uniform
+                        const v4i *Bw = Bl + (size_t)w * 8 * 64 + lane;
+#pragma unroll
+                        for (int n = 0; n < 8; n++) {
+                            const uint32_t nib = (c[w] >> (4 * n)) & 15u;
+                            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(onehot[nib], Bw[n * 64], acc, 0, 0, 0);
+                        }
                     }
-                    c = cnext;
                 }
                 uint32_t pm = 0;
 #pragma unroll
                 for (int r = 0; r < 16; r++) pm |= acc[r] <= th ? (1u << r) : 0u;
                 if (__ballot(pm != 0u) != 0ull) {
-                    const uint32_t slot0 = (uint32_t)(se.blk_begin + b) * 32u + 4u * g;
-                    if (b == se.nblk - 1 && se.tail_valid < 32) {
+                    const uint32_t slot0 = (uint32_t)cur.blk * 32u + 4u * g;
+                    const int tail_valid = segs_s[cur.seg].tail_valid;
+                    if (cur.last && tail_valid < 32) {
 #pragma unroll
                         for (int r = 0; r < 16; r++)
-                            if (8 * (r >> 2) + 4 * g + (r & 3) >= se.tail_valid) pm &= ~(1u << r);
+                            if (8 * (r >> 2) + 4 * g + (r & 3) >= tail_valid) pm &= ~(1u << r);
                     }
                     for (;;) {
                         const bool has = pm != 0u;
@@ -877,6 +915,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
                     }
                 }
             }
+            cur = nxt;
         }
         if (nstaged >= 32) {
             stage_flush(a, sq, nstaged, lane, lc, nflush);
