@@ -645,31 +645,58 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
     const int64_t qi = blockIdx.x;
     const float *qq = q + (size_t)qi * v.d;
     const int n2 = next_pow2(refine_k < 2 ? 2 : refine_k);
-    for (int c = wave; c < n2; c += WG / 64) {
-        int64_t id = c < refine_k ? cand_ids[(size_t)qi * refine_k + c] : -1;
-        uint64_t key = ~0ull;               // distance bits of NaN/inf region, id = empty
-        if (id >= 0 && id < v.ntotal) {
-            float p = 0.0f;
-            if (v.raw_u8) {
-                const uint8_t *row = (const uint8_t *)v.raw + (size_t)id * v.d;
-                for (int i = lane; i < v.d; i += 64) {
-                    float diff = qq[i] - (float)row[i];
+    // four candidates per wave at a time, so that their id and row loads are in flight together
+    for (int c0 = wave; c0 < n2; c0 += 4 * (WG / 64)) {
+        int64_t id[4];
+        bool ok[4];
+        float p[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int c = c0 + u * (WG / 64);
+            id[u] = c < refine_k ? cand_ids[(size_t)qi * refine_k + c] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            ok[u] = id[u] >= 0 && id[u] < v.ntotal;
+            if (!ok[u]) id[u] = 0;                       // row 0 is read and discarded
+            p[u] = 0.0f;
+        }
+        const bool any = ok[0] || ok[1] || ok[2] || ok[3];       // wave-uniform
+        if (!any) {
+            // nothing to read (also keeps an empty index untouched)
+        } else if (v.raw_u8) {
+            for (int i = lane; i < v.d; i += 64) {
+                const float qv = qq[i];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    float diff = qv - (float)((const uint8_t *)v.raw)[(size_t)id[u] * v.d + i];
                     float sq = diff * diff;
-                    p = p + sq;
-                }
-            } else {
-                const float *row = (const float *)v.raw + (size_t)id * v.d;
-                for (int i = lane; i < v.d; i += 64) {
-                    float diff = qq[i] - row[i];
-                    float sq = diff * diff;
-                    p = p + sq;
+                    p[u] = p[u] + sq;
                 }
             }
+        } else {
+            for (int i = lane; i < v.d; i += 64) {
+                const float qv = qq[i];
 #pragma unroll
-            for (int s = 32; s >= 1; s >>= 1) p = p + __shfl_xor(p, s);
-            key = ((uint64_t)__float_as_uint(p) << 32) | (uint32_t)id;
+                for (int u = 0; u < 4; u++) {
+                    float diff = qv - ((const float *)v.raw)[(size_t)id[u] * v.d + i];
+                    float sq = diff * diff;
+                    p[u] = p[u] + sq;
+                }
+            }
         }
-        if (lane == 0) keys[c] = key;
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+#pragma unroll
+            for (int u = 0; u < 4; u++) p[u] = p[u] + __shfl_xor(p[u], s);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int c = c0 + u * (WG / 64);
+            // empty: distance bits in the NaN region, id = all ones
+            if (lane == 0 && c < n2)
+                keys[c] = ok[u] ? (((uint64_t)__float_as_uint(p[u]) << 32) | (uint32_t)id[u]) : ~0ull;
+        }
     }
     __syncthreads();
     bitonic_sort_lds(keys, n2);
