@@ -296,8 +296,12 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
         if (r2) { destroy(h); return r2; }
         UP_HIP(e);
     }
+    uint2 *idtag = nullptr;
+    UP_CHECK(dev_alloc(h, (void **)&idtag, (size_t)x->nblocks * 32 * 8));
+    UP_CHECK(rairs_launch_pair_ids(ids, other, x->nblocks * 32, idtag, s));
     UP_HIP(hipStreamSynchronize(s));
 
+    v.idtag = idtag;
     v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask;
     v.lists = lists; v.refs = refs; v.segs = segs; v.raw = raw;
     for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[i]));

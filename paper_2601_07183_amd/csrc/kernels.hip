@@ -37,6 +37,22 @@ __global__ void pack_ids_kernel(const int64_t *in, int64_t n, uint32_t *out)
     if (gid < n) out[gid] = in[gid] < 0 ? RAIRS_EMPTY_ID : (uint32_t)in[gid];
 }
 
+// (id, other-list tag) of every slot side by side, so that the selection gathers one 8-byte word
+// per survivor instead of two 4-byte words from different arrays
+__global__ void pair_ids_kernel(const uint32_t *ids, const int32_t *other, int64_t n, uint2 *out)
+{
+    int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid < n) out[gid] = make_uint2(ids[gid], (uint32_t)other[gid]);
+}
+
+int rairs_launch_pair_ids(const uint32_t *ids, const int32_t *other, int64_t n, uint2 *out, hipStream_t s)
+{
+    if (n == 0) return RAIRS_OK;
+    hipLaunchKernelGGL(pair_ids_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ids, other, n, out);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
 int rairs_launch_pack(const uint8_t *d_codes, const int64_t *d_ids64, int64_t blk0, int64_t nblk,
                       int M, int nd, uint32_t *codes, uint32_t *ids, hipStream_t s)
 {

@@ -53,6 +53,7 @@ struct IndexView {
     const uint32_t *codes;
     const uint32_t *ids;          // [nblocks][32], RAIRS_EMPTY_ID = empty slot
     const int32_t *other;         // [nblocks][32]
+    const uint2 *idtag;           // [nblocks][32] {id, other} of each slot side by side
     // [nblocks] bit i: slot i holds an item that the duplicate rule can never drop (a shared
     // block's item, or a miscellaneous item whose other list has no smaller id than the list)
     const uint32_t *cmask;
@@ -99,6 +100,7 @@ void rairs_set_error(const char *fmt, ...);
 int rairs_launch_pack(const uint8_t *d_codes_host_layout, const int64_t *d_ids64, int64_t blk0,
                       int64_t nblk, int M, int nd, uint32_t *codes, uint32_t *ids,
                       hipStream_t s);
+int rairs_launch_pair_ids(const uint32_t *ids, const int32_t *other, int64_t n, uint2 *out, hipStream_t s);
 int rairs_launch_transpose(const float *d_in, int rows, int cols, float *d_out, hipStream_t s);
 // dmat: [nq][nlist] words of scratch; flags: [nq] words of scratch (null: full route only)
 int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,

@@ -179,38 +179,63 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
     }
     __syncthreads();
     const int L = probe_ids[(size_t)qi * nprobe];
-    int cnt = 0;
+    int cnt = 0, nitems = 0;
     int64_t begin = 0;
     if (L >= 0 && L < v.nlist) {
         const ListEntry le = v.lists[L];
         begin = le.blk_begin;
         cnt = le.shared_cnt + le.misc_cnt;
         cnt = cnt < sample_blocks ? cnt : sample_blocks;
+        nitems = le.valid_items;                        // item slots in use in the list's own blocks
     }
     uint32_t nvalid = 0;
-    for (int b0 = 0; b0 < cnt; b0 += 4) {               // four blocks in flight
-        uint32_t part[4];
-        bool valid[4];
+    if (v.nd <= 4) {
+        // four blocks at a time with all their code dwords fetched before the first lookup
+        for (int b0 = 0; b0 < cnt; b0 += 4) {
+            uint32_t c[4][4];
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-            const int64_t blk = begin + (b0 + u < cnt ? b0 + u : cnt - 1);
-            const uint32_t *cp = v.codes + (size_t)blk * v.nd * 64 + lane;
-            part[u] = 0;
+            for (int u = 0; u < 4; u++) {
+                const int64_t blk = begin + (b0 + u < cnt ? b0 + u : cnt - 1);
+                const uint32_t *cp = v.codes + (size_t)blk * v.nd * 64 + lane;
+#pragma unroll
+                for (int w = 0; w < 4; w++) c[u][w] = cp[(size_t)(w < v.nd ? w : 0) * 64];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                uint32_t part = 0;
+#pragma unroll
+                for (int w = 0; w < 4; w++) {
+                    if (w < v.nd) {
+                        const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
+                        for (int n = 0; n < tmax; n++) {
+                            const int m = 2 * (8 * w + n) + g;
+                            part += lq[m * 16 + ((c[u][w] >> (4 * n)) & 15u)];
+                        }
+                    }
+                }
+                const uint32_t acc = part + (uint32_t)__shfl_xor((int)part, 32);
+                // only the tail of a list's last block can be empty: slot s is in use iff s < valid_items
+                const bool valid = lane < 32 && b0 + u < cnt && (b0 + u) * 32 + lane < nitems;
+                if (lane < 32 && b0 + u < cnt) sc[(b0 + u) * 32 + lane] = valid ? (uint16_t)acc : (uint16_t)0xFFFFu;
+                nvalid += (uint32_t)__popcll(__ballot(valid));
+            }
+        }
+    } else {
+        for (int b = 0; b < cnt; b++) {
+            const uint32_t *cp = v.codes + (size_t)(begin + b) * v.nd * 64 + lane;
+            uint32_t part = 0;
             for (int w = 0; w < v.nd; w++) {
                 const uint32_t c = cp[(size_t)w * 64];
                 const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
                 for (int n = 0; n < tmax; n++) {
                     const int m = 2 * (8 * w + n) + g;
-                    part[u] += lq[m * 16 + ((c >> (4 * n)) & 15u)];
+                    part += lq[m * 16 + ((c >> (4 * n)) & 15u)];
                 }
             }
-            valid[u] = lane < 32 && b0 + u < cnt && v.ids[(size_t)blk * 32 + lane] != RAIRS_EMPTY_ID;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-            const uint32_t acc = part[u] + (uint32_t)__shfl_xor((int)part[u], 32);
-            if (lane < 32 && b0 + u < cnt) sc[(b0 + u) * 32 + lane] = valid[u] ? (uint16_t)acc : (uint16_t)0xFFFFu;
-            nvalid += (uint32_t)__popcll(__ballot(valid[u]));
+            const uint32_t acc = part + (uint32_t)__shfl_xor((int)part, 32);
+            const bool valid = lane < 32 && b * 32 + lane < nitems;
+            if (lane < 32) sc[b * 32 + lane] = valid ? (uint16_t)acc : (uint16_t)0xFFFFu;
+            nvalid += (uint32_t)__popcll(__ballot(valid));
         }
     }
     __syncthreads();

@@ -578,11 +578,11 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
     }
 }
 
-// Per query with at most SELW_CAP survivors (the usual case): one wave resolves them (id,
+// Per query with at most `cap` survivors (the usual case): one wave resolves them (id,
 // duplicate rule of the miscellaneous area), sorts them by (score, id) in its own LDS region and
 // writes the bigK smallest.  No workgroup barrier is used: a wave only touches its own region, and
 // LDS operations of one wave complete in issue order.
-#define SELW_CAP 1024
+#define SELW_CAP_MAX 1024
 static __device__ __forceinline__ void wave_lds_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -590,9 +590,9 @@ static __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanArgs a)
+__global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanArgs a, int cap)
 {
-    __shared__ uint64_t keys_s[WG / 64][SELW_CAP];
+    extern __shared__ __align__(16) uint64_t selw_keys[];      // [WG / 64][cap]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t q = (int64_t)blockIdx.x * (WG / 64) + wave;
     if (q >= a.nq) return;
@@ -602,9 +602,9 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
         if (lane == 0) a.flags[q] = 1;      // redone by the second pass or the exact kernel
         return;
     }
-    if (n > SELW_CAP) return;               // select_kernel's case
+    if (n > (uint32_t)cap) return;          // select_kernel's case
     if (lane == 0) a.flags[q] = 0;
-    uint64_t *keys = keys_s[wave];
+    uint64_t *keys = selw_keys + (size_t)wave * cap;
     const uint64_t *sb = a.surv_buf + (size_t)q * a.surv_cap;
     const uint32_t *bm = a.bitmap + (size_t)q * a.bmwords;
     for (uint32_t i0 = 0; i0 < n; i0 += 256) {
@@ -618,16 +618,20 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
         }
 #pragma unroll
         for (int u = 0; u < 4; u++) {
-            id[u] = v.ids[(uint32_t)e[u]];
-            o[u] = v.other[(uint32_t)e[u]];
+            const uint2 it = v.idtag[(uint32_t)e[u]];
+            id[u] = it.x;
+            o[u] = (int)it.y;
         }
+        uint32_t bw[4];                     // the tags' probe-bitmap words, all fetched together
+#pragma unroll
+        for (int u = 0; u < 4; u++) bw[u] = bm[o[u] >= 0 ? o[u] >> 5 : 0];
 #pragma unroll
         for (int u = 0; u < 4; u++) {
             const uint32_t i = i0 + 64 * u + lane;
             const uint32_t score = (uint32_t)(e[u] >> 48), L = (uint32_t)(e[u] >> 32) & 0xFFFFu;
             bool keep = id[u] != RAIRS_EMPTY_ID;
             // RemoveVectorIfVisited: the item was already taken from list o
-            if (keep && o[u] >= 0 && (uint32_t)o[u] < L && ((bm[o[u] >> 5] >> (o[u] & 31)) & 1u)) keep = false;
+            if (keep && o[u] >= 0 && (uint32_t)o[u] < L && ((bw[u] >> (o[u] & 31)) & 1u)) keep = false;
             if (i < n) keys[i] = keep ? (((uint64_t)score << 32) | id[u]) : ~0ull;
         }
     }
@@ -659,7 +663,7 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
 // bigK-th survivor; only entries up to that score are sorted.  Overflowed buffers are flagged for
 // the exact redo.
 #define SELECT_SORT_MAX 2048
-__global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a)
+__global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a, int wave_cap)
 {
     __shared__ uint64_t keys[SURV_CAP_MAX];
     __shared__ uint32_t hist[256];
@@ -668,14 +672,15 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a)
     const int64_t q = blockIdx.x;
     if (a.only_flagged && a.only_flagged[q] == 0) return;      // settled in the first pass
     const uint32_t n = a.surv_cnt[q];
-    if (n <= SELW_CAP || n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) return;   // select_wave_kernel's cases
+    if (n <= (uint32_t)wave_cap || n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) return;   // select_wave_kernel's cases
     if (tid == 0) a.flags[q] = 0;
     for (int i = tid; i < (int)n; i += WG) {
         uint64_t key = ~0ull;
         const uint64_t e = a.surv_buf[(size_t)q * a.surv_cap + i];
         const uint32_t slot = (uint32_t)e, score = (uint32_t)(e >> 48), L = (uint32_t)(e >> 32) & 0xFFFFu;
-        const uint32_t id = v.ids[slot];
-        const int o = v.other[slot];
+        const uint2 it = v.idtag[slot];
+        const uint32_t id = it.x;
+        const int o = (int)it.y;
         bool keep = id != RAIRS_EMPTY_ID;
         if (keep && o >= 0 && (uint32_t)o < L) {
             // RemoveVectorIfVisited: the item was already taken from list o
@@ -999,9 +1004,12 @@ int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s
 {
     hipLaunchKernelGGL(collect_kernel, dim3((unsigned)(a.log_chunks < 4096 ? a.log_chunks : 4096)),
                        dim3(LOG_CHUNK), 0, s, a);
+    // the wave kernel's room per query: four times bigK, within [256, SELW_CAP_MAX]
+    int cap = next_pow2(4 * a.refine_k);
+    cap = cap < 256 ? 256 : (cap > SELW_CAP_MAX ? SELW_CAP_MAX : cap);
     hipLaunchKernelGGL(select_wave_kernel, dim3((unsigned)((a.nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
-                       0, s, v, a);
-    hipLaunchKernelGGL(select_kernel, dim3((unsigned)a.nq), dim3(WG), 0, s, v, a);
+                       (size_t)cap * 8 * (WG / 64), s, v, a, cap);
+    hipLaunchKernelGGL(select_kernel, dim3((unsigned)a.nq), dim3(WG), 0, s, v, a, cap);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
