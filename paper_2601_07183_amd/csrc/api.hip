@@ -328,7 +328,7 @@ extern "C" int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, in
 
 #define SURV_CAP 4096
 #define RAIRS_SAMPLE_BLOCKS 16
-#define RAIRS_LOG_PER_QUERY 3072
+#define RAIRS_LOG_PER_QUERY 8192
 
 struct WsLayout {
     size_t dmat, cflags, probe_ids, probe_dists, bitmap, lut, cand;
@@ -423,7 +423,7 @@ static int check_k(int k, int refine_k)
 // Queries per internal pass so that the distance matrix and buffers stay within ~4 GiB.
 static int64_t pass_size(const IndexView &v, int64_t nq)
 {
-    int64_t per_q = (int64_t)v.nlist * 4 + 65536;
+    int64_t per_q = (int64_t)v.nlist * 4 + 196608;
     int64_t cap = (4ll << 30) / per_q;
     if (cap < 256) cap = 256;
     return nq < cap ? nq : cap;
@@ -526,18 +526,13 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     int sample_blocks = (5 * refine_k + 31) / 32;
     if (sample_blocks < RAIRS_SAMPLE_BLOCKS) sample_blocks = RAIRS_SAMPLE_BLOCKS;
     if ((rc = rairs_launch_sample_bound(v, lut, probe_ids, nprobe, refine_k, sample_blocks, n,
-                                        (int32_t *)(ws + w.tau), ma.bound, s))) return rc;
-    if (dco && (rc = rairs_launch_dco(v, probe_ids, bitmap, w.bmwords, nprobe, n, dco, s))) return rc;
+                                        (int32_t *)(ws + w.tau), ma.bound, bitmap, w.bmwords, dco, s)))
+        return rc;
     if ((rc = rairs_launch_scan_mfma(v, ma, s, ev))) return rc;
     if ((rc = rairs_launch_select(v, ma, s))) return rc;
-    // Second pass for queries whose survivor buffer overflowed (loose sample bound, slow start):
-    // their bound is now the converged one, so the same scan restricted to them fits.  Normally
-    // no query is flagged and these launches find no work.
-    MfmaScanArgs m2 = ma;
-    m2.only_flagged = ma.flags; m2.fixed_bound = 1;
-    if ((rc = rairs_launch_scan_mfma(v, m2, s, nullptr))) return rc;
-    if ((rc = rairs_launch_select(v, m2, s))) return rc;
-    // queries whose survivor buffer overflowed are redone by the exact kernel
+    // a query with more entries at or below its final bound than the buffer holds (thousands of
+    // items with the same score), or every query if the log ran out of chunks, is redone by the
+    // exact kernel; normally none is flagged and every workgroup of that launch exits at once
     ea.only_flagged = ma.flags;
     return rairs_launch_scan_exact(v, ea, n, s);
 }

@@ -111,6 +111,32 @@ static __device__ __forceinline__ float key_f32(uint32_t k)
     return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
 }
 
+// direct-form distance of a query to list l of the transposed centroid matrix ct[d][nlist]
+static __device__ __forceinline__ float direct_l2_t(const float *__restrict__ qq,
+                                                    const float *__restrict__ ct, int d, int nlist, int l)
+{
+    float p[64];
+#pragma unroll
+    for (int j = 0; j < 64; j++) p[j] = 0.0f;
+    for (int i0 = 0; i0 < d; i0 += 64) {
+#pragma unroll
+        for (int j = 0; j < 64; j++) {
+            int i = i0 + j;
+            if (i < d) {
+                float diff = qq[i] - ct[(size_t)i * nlist + l];
+                float sq = diff * diff;
+                p[j] = p[j] + sq;
+            }
+        }
+    }
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) {
+#pragma unroll
+        for (int j = 0; j < s; j++) p[j] = p[j] + p[j + s];
+    }
+    return p[0];
+}
+
 // Full route, distances: one lane per (query, list), lists strided over the y dimension of the
 // grid.  With only_flagged set, queries whose flag is zero are left alone.
 __global__ __launch_bounds__(WG) void coarse_dist_kernel(const float *__restrict__ q,
@@ -121,38 +147,20 @@ __global__ __launch_bounds__(WG) void coarse_dist_kernel(const float *__restrict
     const int64_t qi = blockIdx.x;
     if (only_flagged && only_flagged[qi] == 0) return;
     const float *qq = q + (size_t)qi * d;
-    for (int l = blockIdx.y * WG + threadIdx.x; l < nlist; l += gridDim.y * WG) {
-        float p[64];
-#pragma unroll
-        for (int j = 0; j < 64; j++) p[j] = 0.0f;
-        for (int i0 = 0; i0 < d; i0 += 64) {
-#pragma unroll
-            for (int j = 0; j < 64; j++) {
-                int i = i0 + j;
-                if (i < d) {
-                    float diff = qq[i] - ct[(size_t)i * nlist + l];
-                    float sq = diff * diff;
-                    p[j] = p[j] + sq;
-                }
-            }
-        }
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) {
-#pragma unroll
-            for (int j = 0; j < s; j++) p[j] = p[j] + p[j + s];
-        }
-        dmat[(size_t)qi * nlist + l] = p[0];
-    }
+    for (int l = blockIdx.y * WG + threadIdx.x; l < nlist; l += gridDim.y * WG)
+        dmat[(size_t)qi * nlist + l] = direct_l2_t(qq, ct, d, nlist, l);
 }
 
 // Full route, selection: the nprobe smallest (distance, list id) of a row by radix select on the
 // fp32 bit pattern (distances are >= +0, so the unsigned order of the bits is the numeric order),
 // then sorted.  One workgroup per query.
-__global__ __launch_bounds__(WG) void coarse_select_kernel(const float *__restrict__ dmat,
+__global__ __launch_bounds__(WG) void coarse_select_kernel(float *dmat,
                                                            int nlist, int nprobe,
                                                            int32_t *__restrict__ probe_ids,
                                                            float *__restrict__ probe_dists,
-                                                           const uint32_t *__restrict__ only_flagged)
+                                                           const uint32_t *__restrict__ only_flagged,
+                                                           const float *__restrict__ q,
+                                                           const float *__restrict__ ct, int d)
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_cnt;
@@ -160,6 +168,14 @@ __global__ __launch_bounds__(WG) void coarse_select_kernel(const float *__restri
     __shared__ uint64_t sel[RAIRS_MAX_NPROBE];
     const int tid = threadIdx.x;
     if (only_flagged && only_flagged[blockIdx.x] == 0) return;
+    if (q) {
+        // the row's distances first (same arithmetic as coarse_dist_kernel), by this workgroup
+        float *drow = dmat + (size_t)blockIdx.x * nlist;
+        const float *qq = q + (size_t)blockIdx.x * d;
+        for (int l = tid; l < nlist; l += WG) drow[l] = direct_l2_t(qq, ct, d, nlist, l);
+        __threadfence_block();
+        __syncthreads();
+    }
     const uint32_t *row = (const uint32_t *)(dmat + (size_t)blockIdx.x * nlist);
 
     uint32_t prefix = 0, mask = 0, remaining = (uint32_t)nprobe;
@@ -498,7 +514,7 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
         hipLaunchKernelGGL(coarse_dist_kernel, dim3((unsigned)nq, groups), dim3(WG), 0, s, q,
                            v.centroids_t, v.d, v.nlist, dmat, nullptr);
         hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist,
-                           nprobe, probe_ids, probe_dists, nullptr);
+                           nprobe, probe_ids, probe_dists, nullptr, nullptr, nullptr, 0);
         RAIRS_HIP(hipGetLastError());
         return RAIRS_OK;
     }
@@ -537,11 +553,10 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
     hipLaunchKernelGGL(coarse_shortlist_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))),
                        dim3(WG), sel_bytes, s, keys, q, v.centroids, v.d, v.nlist,
                        nprobe, cap, v.cmax2, nq, probe_ids, probe_dists, flags);
-    // queries whose shortlist did not fit (many lists at nearly the same distance): full route
-    hipLaunchKernelGGL(coarse_dist_kernel, dim3((unsigned)nq, groups < 8 ? groups : 8), dim3(WG), 0, s,
-                       q, v.centroids_t, v.d, v.nlist, dmat, flags);
+    // queries whose shortlist did not fit (many lists at nearly the same distance): full route,
+    // both steps by the query's own workgroup
     hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist, nprobe,
-                       probe_ids, probe_dists, flags);
+                       probe_ids, probe_dists, flags, q, v.centroids_t, v.d);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }

@@ -121,12 +121,11 @@ struct ExactScanArgs {
     int64_t *dco;                 // [nq], may be null
 };
 int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s);
-// bound of every query from the head of its first probed list; DCO of every query
+// bound of every query from the head of its first probed list and, when dco is given, its DCO
 int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
                               int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,
-                              int32_t *bound, hipStream_t s);
-int rairs_launch_dco(const IndexView &v, const int32_t *probe_ids, const uint32_t *bitmap, int bmwords,
-                     int nprobe, int64_t nq, int64_t *dco, hipStream_t s);
+                              int32_t *bound, const uint32_t *bitmap, int bmwords, int64_t *dco,
+                              hipStream_t s);
 
 // list-major MFMA scan (scan_mfma.hip)
 struct MfmaScanArgs {
@@ -152,8 +151,6 @@ struct MfmaScanArgs {
     uint64_t *surv_buf;           // [nq][surv_cap]
     int surv_cap;
     uint32_t *flags;              // [nq] set when the survivor buffer overflowed
-    const uint32_t *only_flagged; // second pass: only queries with a non-zero entry take part
-    int fixed_bound;              // second pass: bounds are final, no histogram work
     uint4 *log;                   // [log_chunks][256] survivor log {slot, score<<16|list, query, 0}
     uint32_t *chunk_fill;         // [log_chunks] entries written to each chunk
     uint32_t *log_cursor;         // [1] chunks handed out

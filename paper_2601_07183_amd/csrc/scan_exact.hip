@@ -163,7 +163,9 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
                                                           const int32_t *__restrict__ probe_ids,
                                                           int nprobe, int refine_k, int sample_blocks,
                                                           int64_t nq, int32_t *__restrict__ tau,
-                                                          int32_t *__restrict__ bound)
+                                                          int32_t *__restrict__ bound,
+                                                          const uint32_t *__restrict__ bitmap,
+                                                          int bmwords, int64_t *__restrict__ dco)
 {
     extern __shared__ __align__(16) uint8_t sample_lds[];  // per wave: M*16 table bytes, then sample_blocks*32 scores
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
@@ -258,54 +260,39 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
         tau[qi] = (int32_t)t;
         if (bound) bound[qi] = (int32_t)t;
     }
+    // DCO of the query (distance computations of the scan, Section 6.1): every valid slot of the
+    // own blocks of each probed list, plus 32 per block of each reference entry whose owner is not
+    // probed.  Lanes over the probes.
+    if (dco) {
+        const uint32_t *bm = bitmap + (size_t)qi * bmwords;
+        unsigned long long c = 0;
+        for (int p = lane; p < nprobe; p += 64) {
+            const int Lp = probe_ids[(size_t)qi * nprobe + p];
+            if (Lp < 0 || Lp >= v.nlist) continue;
+            const ListEntry le = v.lists[Lp];
+            c += (unsigned long long)le.valid_items;
+            for (int r = 0; r < le.ref_cnt; r++) {
+                const RefEntry re = v.refs[le.ref_begin + r];
+                if (!((bm[re.owner >> 5] >> (re.owner & 31)) & 1u)) c += 32ull * re.nblocks;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) c += (unsigned long long)__shfl_xor((long long)c, off);
+        if (lane == 0 && qi0 < nq) dco[qi] = (int64_t)c;
+    }
 }
 
 int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
                               int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,
-                              int32_t *bound, hipStream_t s)
+                              int32_t *bound, const uint32_t *bitmap, int bmwords, int64_t *dco,
+                              hipStream_t s)
 {
     if (sample_blocks > SAMPLE_MAX_BLOCKS) sample_blocks = SAMPLE_MAX_BLOCKS;
     if (sample_blocks < 1) sample_blocks = 1;
     const size_t lds = (size_t)(WG / 64) * ((size_t)v.M * 16 + (size_t)sample_blocks * 64);
     hipLaunchKernelGGL(sample_bound_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
-                       lds, s, v, lut, probe_ids, nprobe, refine_k, sample_blocks, nq, tau, bound);
-    RAIRS_HIP(hipGetLastError());
-    return RAIRS_OK;
-}
-
-// ---- DCO of a query (distance computations of the scan, Section 6.1) ----------------------------
-//
-// Every valid slot of the own blocks of each probed list, plus 32 per block of each reference
-// entry whose owner is not probed.  One wave per query, lanes over the probes.
-__global__ __launch_bounds__(WG) void dco_kernel(IndexView v, const int32_t *__restrict__ probe_ids,
-                                                 const uint32_t *__restrict__ bitmap, int bmwords,
-                                                 int nprobe, int64_t nq, int64_t *__restrict__ dco)
-{
-    const int lane = threadIdx.x & 63;
-    const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + (threadIdx.x >> 6);
-    if (qi >= nq) return;
-    const uint32_t *bm = bitmap + (size_t)qi * bmwords;
-    unsigned long long c = 0;
-    for (int p = lane; p < nprobe; p += 64) {
-        const int L = probe_ids[(size_t)qi * nprobe + p];
-        if (L < 0 || L >= v.nlist) continue;
-        const ListEntry le = v.lists[L];
-        c += (unsigned long long)le.valid_items;
-        for (int r = 0; r < le.ref_cnt; r++) {
-            const RefEntry re = v.refs[le.ref_begin + r];
-            if (!((bm[re.owner >> 5] >> (re.owner & 31)) & 1u)) c += 32ull * re.nblocks;
-        }
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) c += (unsigned long long)__shfl_xor((long long)c, off);
-    if (lane == 0) dco[qi] = (int64_t)c;
-}
-
-int rairs_launch_dco(const IndexView &v, const int32_t *probe_ids, const uint32_t *bitmap, int bmwords,
-                     int nprobe, int64_t nq, int64_t *dco, hipStream_t s)
-{
-    hipLaunchKernelGGL(dco_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG), 0, s, v,
-                       probe_ids, bitmap, bmwords, nprobe, nq, dco);
+                       lds, s, v, lut, probe_ids, nprobe, refine_k, sample_blocks, nq, tau, bound, bitmap, bmwords,
+                       dco);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }

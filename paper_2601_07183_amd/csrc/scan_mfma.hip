@@ -41,25 +41,22 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 // at index + nwaves), so the counters start behind those.
 __global__ void lm_zero_kernel(int32_t *lcount, int nlist, uint32_t *next_task, uint32_t *surv_cnt,
                                int64_t nq, uint32_t *chunk_fill, int log_chunks, uint32_t *log_cursor,
-                               uint32_t *log_overflow, const uint32_t *only_flagged,
-                               uint32_t first_task, uint32_t first_chunk)
+                               uint32_t *log_overflow, uint32_t first_task, uint32_t first_chunk)
 {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < nlist) lcount[gid] = 0;
-    if (gid < nq && (!only_flagged || only_flagged[gid])) surv_cnt[gid] = 0;
+    if (gid < nq) surv_cnt[gid] = 0;
     if (gid < log_chunks) chunk_fill[gid] = 0;
     if (gid == 0) { *next_task = first_task; *log_cursor = first_chunk; *log_overflow = 0; }
 }
 
 __global__ void lm_count_kernel(const int32_t *__restrict__ probe_ids, int64_t nq, int nprobe,
-                                int p_first, int nlist, int32_t *lcount,
-                                const uint32_t *__restrict__ only_flagged)
+                                int p_first, int nlist, int32_t *lcount)
 {
     const int np = nprobe - p_first;
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= nq * np) return;
     int64_t q = gid / np;
-    if (only_flagged && only_flagged[q] == 0) return;
     int p = p_first + (int)(gid % np);
     int L = probe_ids[q * nprobe + p];
     if (L >= 0 && L < nlist) atomicAdd(&lcount[L], 1);
@@ -120,14 +117,12 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
 
 __global__ void lm_fill_kernel(const int32_t *__restrict__ probe_ids, int64_t nq, int nprobe,
                                int p_first, int nlist, const int32_t *__restrict__ loff,
-                               int32_t *lcursor, int32_t *qlist,
-                               const uint32_t *__restrict__ only_flagged)
+                               int32_t *lcursor, int32_t *qlist)
 {
     const int np = nprobe - p_first;
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= nq * np) return;
     int64_t q = gid / np;
-    if (only_flagged && only_flagged[q] == 0) return;
     int p = p_first + (int)(gid % np);
     int L = probe_ids[q * nprobe + p];
     if (L >= 0 && L < nlist) {
@@ -143,9 +138,7 @@ __global__ void lm_fill_kernel(const int32_t *__restrict__ probe_ids, int64_t nq
 #define LM_LDS_NLIST 8192
 __global__ __launch_bounds__(256) void lm_count_lds_kernel(const int32_t *__restrict__ probe_ids,
                                                            int64_t nq, int nprobe, int p_first,
-                                                           int nlist, int32_t *lcount,
-                                                           const uint32_t *__restrict__ only_flagged,
-                                                           int qb)
+                                                           int nlist, int32_t *lcount, int qb)
 {
     extern __shared__ int32_t lm_hist[];
     const int tid = threadIdx.x;
@@ -156,7 +149,7 @@ __global__ __launch_bounds__(256) void lm_count_lds_kernel(const int32_t *__rest
     const int pairs = qb * np;
     for (int i = tid; i < pairs; i += 256) {
         const int64_t q = q0 + i / np;
-        if (q >= nq || (only_flagged && only_flagged[q] == 0)) continue;
+        if (q >= nq) continue;
         const int L = probe_ids[q * nprobe + p_first + i % np];
         if (L >= 0 && L < nlist) atomicAdd(&lm_hist[L], 1);
     }
@@ -170,9 +163,7 @@ __global__ __launch_bounds__(256) void lm_count_lds_kernel(const int32_t *__rest
 __global__ __launch_bounds__(256) void lm_fill_lds_kernel(const int32_t *__restrict__ probe_ids,
                                                           int64_t nq, int nprobe, int p_first,
                                                           int nlist, const int32_t *__restrict__ loff,
-                                                          int32_t *lcursor, int32_t *qlist,
-                                                          const uint32_t *__restrict__ only_flagged,
-                                                          int qb)
+                                                          int32_t *lcursor, int32_t *qlist, int qb)
 {
     extern __shared__ int32_t lm_hist[];
     const int tid = threadIdx.x;
@@ -189,7 +180,7 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(const int32_t *__restr
         myr[k] = 0;
         if (i < pairs) {
             const int64_t q = q0 + i / np;
-            if (q < nq && !(only_flagged && only_flagged[q] == 0)) {
+            if (q < nq) {
                 const int L = probe_ids[q * nprobe + p_first + i % np];
                 if (L >= 0 && L < nlist) {
                     myL[k] = L;
@@ -289,11 +280,11 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
             const uint32_t sl = sq.score_list[i];
             if (room)
                 a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint4(sq.slot[i], sl, qid, 0u);
-            if (!a.fixed_bound && (qraw >> 31))
+            if (qraw >> 31)
                 atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + __umulhi(sl >> 16, sq.hmul[i])], 1u);
         }
     }
-    if ((nflush & 1u) == 0u && !a.fixed_bound && lane < n && ((lane + (nflush >> 1)) & 3) == 0) {
+    if ((nflush & 1u) == 0u && lane < n && ((lane + (nflush >> 1)) & 3) == 0) {
         // at every other flush a quarter of the first row's entries, a different quarter each
         // time, also refresh their query's bound.  A stale histogram only gives a looser bound;
         // the bound itself only ever shrinks.
@@ -596,7 +587,6 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t q = (int64_t)blockIdx.x * (WG / 64) + wave;
     if (q >= a.nq) return;
-    if (a.only_flagged && a.only_flagged[q] == 0) return;      // settled in the first pass
     const uint32_t n = a.surv_cnt[q];
     if (n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) {
         if (lane == 0) a.flags[q] = 1;      // redone by the second pass or the exact kernel
@@ -670,7 +660,6 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a,
     __shared__ uint32_t s_prefix, s_need, s_kept;
     const int tid = threadIdx.x;
     const int64_t q = blockIdx.x;
-    if (a.only_flagged && a.only_flagged[q] == 0) return;      // settled in the first pass
     const uint32_t n = a.surv_cnt[q];
     if (n <= (uint32_t)wave_cap || n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) return;   // select_wave_kernel's cases
     if (tid == 0) a.flags[q] = 0;
@@ -962,27 +951,26 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     }
     hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
                        v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
-                       a.log_cursor, a.log_overflow, a.only_flagged, reg_tables ? nwaves : grid.x,
+                       a.log_cursor, a.log_overflow, reg_tables ? nwaves : grid.x,
                        2 * nwaves);
     const bool lds_group = v.nlist <= LM_LDS_NLIST;
     const int qb = LM_PAIRS / np > 0 ? LM_PAIRS / np : 1;
     const unsigned lgrid = (unsigned)((a.nq + qb - 1) / qb);
     if (lds_group)
         hipLaunchKernelGGL(lm_count_lds_kernel, dim3(lgrid), dim3(256), (size_t)v.nlist * 4, s,
-                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount, a.only_flagged, qb);
+                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount, qb);
     else
         hipLaunchKernelGGL(lm_count_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
-                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount, a.only_flagged);
+                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount);
     hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
                        a.toff, a.unit_list, a.unit_segs);
     if (lds_group)
         hipLaunchKernelGGL(lm_fill_lds_kernel, dim3(lgrid), dim3(256), (size_t)v.nlist * 4, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor,
-                           a.qlist, a.only_flagged, qb);
+                           a.qlist, qb);
     else
         hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
-                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist,
-                           a.only_flagged);
+                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist);
     if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
     switch (v.T) {
     case 8: hipLaunchKernelGGL(scan_mfma_kernel<8>, grid, dim3(WG), 0, s, v, a); break;
