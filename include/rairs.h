@@ -155,8 +155,7 @@ int rairs_refine(rairs_index_t *h, const float *d_queries, const int64_t *d_cand
  * Which kernels SeilSearch uses.  RAIRS_SCAN_AUTO (default): a score bound per query from a
  * sample of its first probed list, then the list-major MFMA kernel over all probed lists (tables
  * in registers for M = 16, 48, 64, in LDS for any other M), selection of the bigK best survivors,
- * a second restricted pass for queries whose survivor buffer overflowed, and the exact
- * one-workgroup-per-query kernel for any that overflow again.
+ * and the exact one-workgroup-per-query kernel for queries whose survivors do not fit their buffer.
  * RAIRS_SCAN_EXACT: the exact kernel for everything.  Results are identical in both modes.
  */
 enum { RAIRS_SCAN_AUTO = 0, RAIRS_SCAN_EXACT = 1 };
@@ -165,7 +164,7 @@ int rairs_set_scan_mode(rairs_index_t *h, int mode);
 /* ---- measurement --------------------------------------------------------------------------- */
 
 /* SCAN is the whole SeilSearch stage (probe bitmap, sample bound, grouping, main scan kernel,
-   selection, overflow passes); SCAN_KERNEL is its dominant kernel alone: the list-major MFMA scan,
+   selection, overflow redo); SCAN_KERNEL is its dominant kernel alone: the list-major MFMA scan,
    or the exact scan when that one runs instead. */
 enum { RAIRS_STAGE_COARSE = 0, RAIRS_STAGE_LUT = 1, RAIRS_STAGE_SCAN = 2, RAIRS_STAGE_REFINE = 3,
        RAIRS_STAGE_SCAN_KERNEL = 4, RAIRS_NSTAGES = 5 };
