@@ -338,9 +338,9 @@ __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict
     }
 }
 
-// Shortlist route, selection.  One wave per query (four per workgroup): radix select of the
-// nprobe-th smallest key, widen it by the margin, gather the lists up to there, re-score them in
-// the direct form, sort by (distance, list id), keep nprobe.
+// Shortlist route, selection.  One wave per query (four per workgroup, each with its own LDS
+// region and no workgroup barrier): find the nprobe-th smallest key, widen it by the margin, gather
+// the lists up to there, re-score them in the direct form, sort by (distance, list id), keep nprobe.
 //
 // Margin.  With u = 2^-24 and exact values D = |q - c|^2: the direct form is within (d + 2) u D of
 // D, D <= 2 (|q|^2 + |c|^2); the GEMM form's dot product is within d u |q||c|, the norm within
@@ -349,11 +349,18 @@ __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict
 // s <= (nprobe-th smallest s) + 2 e.  The kernel uses 16 (d + 2) u (|q|^2 + max |c|^2), twice that,
 // against accumulation orders inside the matrix core that are not documented.
 //
-// All loops that contain workgroup barriers have trip counts fixed by nlist, nprobe and cap.
+// The nprobe-th smallest key is found in one pass over the row when a sample allows it: the
+// ksamp-th smallest key `est` of the row's first `nsamp` keys is, with ksamp chosen well above the
+// sample's share of nprobe, above the nprobe-th smallest of the row; every key <= est is gathered
+// (with its list) and sorted, which yields the nprobe-th smallest exactly.  If fewer than nprobe
+// keys were gathered, or they do not fit, or est is below the widened threshold, the wave falls back
+// to a radix select over the whole row (four passes), which always works.
+#define SHORTLIST_SAMPLE 512
 __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__restrict__ keys,
                                                               const float *__restrict__ q,
                                                               const float *__restrict__ cent, int d,
                                                               int nlist, int nprobe, int cap,
+                                                              int nsamp, int ksamp,
                                                               float cmax2, int64_t nq,
                                                               int32_t *__restrict__ probe_ids,
                                                               float *__restrict__ probe_dists,
@@ -362,17 +369,42 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
     __shared__ uint32_t hist_s[WG / 64][256];
     extern __shared__ __align__(16) uint64_t sel_dyn[];      // [WG / 64][cap], cap a power of two
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t qi0 = (int64_t)blockIdx.x * (WG / 64) + wave;
-    const int64_t qi = __builtin_amdgcn_readfirstlane((int)(qi0 < nq ? qi0 : nq - 1));   // surplus waves redo the last query
+    const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + wave;
+    if (qi >= nq) return;                                // no workgroup barrier below
     const uint32_t *row = keys + (size_t)qi * nlist;
     uint32_t *hist = hist_s[wave];
     uint64_t *sel = sel_dyn + (size_t)wave * cap;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
-    uint32_t prefix = 0, mask = 0, remaining = (uint32_t)nprobe;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        for (int b = lane; b < 256; b += 64) hist[b] = 0;
-        __syncthreads();
-        // sixteen keys per lane are fetched together so that their latencies overlap
+    // |q|^2 and the margin
+    const float *qq = q + (size_t)qi * d;
+    float qn = 0.0f;
+    for (int t = lane; t < d; t += 64) qn += qq[t] * qq[t];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) qn += __shfl_xor(qn, off);
+    const float margin = 16.0f * (float)(d + 2) * 5.9604645e-8f * (qn + cmax2);
+    const bool margin_ok = !(margin != margin) && margin < 3.0e38f;
+
+    uint32_t nc = 0;                                     // lists in the shortlist (their ids in sel[0..nc))
+    bool have = false;
+    if (nsamp > 0 && margin_ok) {
+        // est: the ksamp-th smallest of the sample, by bisection on the key bits (keys in registers)
+        uint32_t ks[SHORTLIST_SAMPLE / 64];
+#pragma unroll
+        for (int u = 0; u < SHORTLIST_SAMPLE / 64; u++) {
+            const int l = 64 * u + lane;
+            ks[u] = l < nsamp ? row[l] : 0xFFFFFFFFu;
+        }
+        uint32_t est = 0;
+        for (int bit = 31; bit >= 0; bit--) {
+            const uint32_t cand = est | (1u << bit);
+            uint32_t below = 0;
+#pragma unroll
+            for (int u = 0; u < SHORTLIST_SAMPLE / 64; u++) below += (uint32_t)__popcll(__ballot(ks[u] < cand));
+            if (below < (uint32_t)ksamp) est = cand;
+        }
+        // every key <= est, with its list
+        uint32_t ng = 0;
         for (int l0 = 0; l0 < nlist; l0 += 64 * 16) {
             uint32_t kk[16];
 #pragma unroll
@@ -381,69 +413,104 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
                 kk[u] = row[l < nlist ? l : nlist - 1];
             }
 #pragma unroll
-            for (int u = 0; u < 16; u++)
-                if (l0 + 64 * u + lane < nlist && (kk[u] & mask) == prefix)
-                    atomicAdd(&hist[(kk[u] >> shift) & 255u], 1u);
+            for (int u = 0; u < 16; u++) {
+                const int l = l0 + 64 * u + lane;
+                const bool in = l < nlist && kk[u] <= est;
+                const unsigned long long m = __ballot(in);
+                const uint32_t pos = ng + (uint32_t)__popcll(m & lt_mask);
+                if (in && pos < (uint32_t)cap) sel[pos] = ((uint64_t)kk[u] << 32) | (uint32_t)l;
+                ng += (uint32_t)__popcll(m);
+            }
         }
-        __syncthreads();
-        // the bin where the running count reaches `remaining`: four bins per lane + wave scan
-        uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-        uint32_t tot = h0 + h1 + h2 + h3, incl = tot;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            uint32_t up = (uint32_t)__shfl_up((int)incl, off);
-            if (lane >= off) incl += up;
-        }
-        const uint32_t excl = incl - tot;
-        const bool here = excl < remaining && incl >= remaining;       // exactly one lane
-        uint32_t bin = 0, rem = 0;
-        if (here) {
-            uint32_t cum = excl;
-            if (cum + h0 >= remaining) { bin = 4 * lane; rem = remaining - cum; }
-            else if (cum + h0 + h1 >= remaining) { bin = 4 * lane + 1; rem = remaining - cum - h0; }
-            else if (cum + h0 + h1 + h2 >= remaining) { bin = 4 * lane + 2; rem = remaining - cum - h0 - h1; }
-            else { bin = 4 * lane + 3; rem = remaining - cum - h0 - h1 - h2; }
-        }
-        const unsigned long long who = __ballot(here);
-        const int src = __ffsll((long long)who) - 1;
-        bin = (uint32_t)__shfl((int)bin, src);
-        rem = (uint32_t)__shfl((int)rem, src);
-        prefix |= bin << shift;
-        remaining = rem;
-        mask |= 255u << shift;
-        __syncthreads();
-    }
-    // |q|^2 and the widened threshold
-    const float *qq = q + (size_t)qi * d;
-    float qn = 0.0f;
-    for (int t = lane; t < d; t += 64) qn += qq[t] * qq[t];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) qn += __shfl_xor(qn, off);
-    const float margin = 16.0f * (float)(d + 2) * 5.9604645e-8f * (qn + cmax2);
-    const uint32_t thr = f32_key(key_f32(prefix) + margin);
-    // gather the shortlist
-    uint32_t nc = 0;
-    for (int l0 = 0; l0 < nlist; l0 += 64 * 16) {
-        uint32_t kk[16];
-#pragma unroll
-        for (int u = 0; u < 16; u++) {
-            const int l = l0 + 64 * u + lane;
-            kk[u] = row[l < nlist ? l : nlist - 1];
-        }
-#pragma unroll
-        for (int u = 0; u < 16; u++) {
-            const int l = l0 + 64 * u + lane;
-            const bool in = l < nlist && kk[u] <= thr;
-            const unsigned long long m = __ballot(in);
-            const uint32_t pos = nc + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-            if (in && pos < (uint32_t)cap) sel[pos] = (uint64_t)(uint32_t)l;
-            nc += (uint32_t)__popcll(m);
+        if (ng >= (uint32_t)nprobe && ng <= (uint32_t)cap) {
+            const int n2 = next_pow2((int)ng < 2 ? 2 : (int)ng);
+            for (int e = (int)ng + lane; e < n2; e += 64) sel[e] = ~0ull;
+            wave_lds_sync();
+            wave_bitonic_sort_lds(sel, n2, lane);
+            const uint32_t kth = (uint32_t)(sel[nprobe - 1] >> 32);
+            const uint32_t thr = f32_key(key_f32(kth) + margin);
+            if (thr <= est) {
+                // the sorted entries up to thr are the shortlist
+                for (int e0 = 0; e0 < (int)ng; e0 += 64) {
+                    const int e = e0 + lane;
+                    nc += (uint32_t)__popcll(__ballot(e < (int)ng && (uint32_t)(sel[e] >> 32) <= thr));
+                }
+                have = true;
+            }
         }
     }
-    const bool fits = nc <= (uint32_t)cap && !(margin != margin) && margin < 3.0e38f;
-    if (lane == 0 && qi0 < nq) flags[qi] = fits ? 0u : 1u;
-    if (!fits) nc = 0;
-    __syncthreads();
+    bool fits = true;
+    if (!have) {
+        // radix select of the nprobe-th smallest key over the whole row
+        uint32_t prefix = 0, mask = 0, remaining = (uint32_t)nprobe;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            for (int b = lane; b < 256; b += 64) hist[b] = 0;
+            wave_lds_sync();
+            // sixteen keys per lane are fetched together so that their latencies overlap
+            for (int l0 = 0; l0 < nlist; l0 += 64 * 16) {
+                uint32_t kk[16];
+#pragma unroll
+                for (int u = 0; u < 16; u++) {
+                    const int l = l0 + 64 * u + lane;
+                    kk[u] = row[l < nlist ? l : nlist - 1];
+                }
+#pragma unroll
+                for (int u = 0; u < 16; u++)
+                    if (l0 + 64 * u + lane < nlist && (kk[u] & mask) == prefix)
+                        atomicAdd(&hist[(kk[u] >> shift) & 255u], 1u);
+            }
+            wave_lds_sync();
+            // the bin where the running count reaches `remaining`: four bins per lane + wave scan
+            uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+            uint32_t tot = h0 + h1 + h2 + h3, incl = tot;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                uint32_t up = (uint32_t)__shfl_up((int)incl, off);
+                if (lane >= off) incl += up;
+            }
+            const uint32_t excl = incl - tot;
+            const bool here = excl < remaining && incl >= remaining;       // exactly one lane
+            uint32_t bin = 0, rem = 0;
+            if (here) {
+                uint32_t cum = excl;
+                if (cum + h0 >= remaining) { bin = 4 * lane; rem = remaining - cum; }
+                else if (cum + h0 + h1 >= remaining) { bin = 4 * lane + 1; rem = remaining - cum - h0; }
+                else if (cum + h0 + h1 + h2 >= remaining) { bin = 4 * lane + 2; rem = remaining - cum - h0 - h1; }
+                else { bin = 4 * lane + 3; rem = remaining - cum - h0 - h1 - h2; }
+            }
+            const unsigned long long who = __ballot(here);
+            const int src = __ffsll((long long)who) - 1;
+            bin = (uint32_t)__shfl((int)bin, src);
+            rem = (uint32_t)__shfl((int)rem, src);
+            prefix |= bin << shift;
+            remaining = rem;
+            mask |= 255u << shift;
+            wave_lds_sync();
+        }
+        const uint32_t thr = f32_key(key_f32(prefix) + margin);
+        // gather the shortlist
+        for (int l0 = 0; l0 < nlist; l0 += 64 * 16) {
+            uint32_t kk[16];
+#pragma unroll
+            for (int u = 0; u < 16; u++) {
+                const int l = l0 + 64 * u + lane;
+                kk[u] = row[l < nlist ? l : nlist - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; u++) {
+                const int l = l0 + 64 * u + lane;
+                const bool in = l < nlist && kk[u] <= thr;
+                const unsigned long long m = __ballot(in);
+                const uint32_t pos = nc + (uint32_t)__popcll(m & lt_mask);
+                if (in && pos < (uint32_t)cap) sel[pos] = (uint64_t)(uint32_t)l;
+                nc += (uint32_t)__popcll(m);
+            }
+        }
+        fits = nc <= (uint32_t)cap && margin_ok;
+        if (!fits) nc = 0;
+    }
+    if (lane == 0) flags[qi] = fits ? 0u : 1u;
+    wave_lds_sync();
     // re-score in the direct form: the wave takes one list at a time, lane j sums the dimensions
     // of class j and the fold is a butterfly over the lanes (lane 0 ends with the defined value)
     float qr[4];
@@ -471,27 +538,17 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
 #pragma unroll
             for (int u = 0; u < 4; u++) p[u] = p[u] + __shfl_down(p[u], off);
         }
-        // all four lists were read before any entry is rewritten
+        wave_lds_sync();                                 // all four lists were read before any entry is rewritten
 #pragma unroll
         for (int u = 0; u < 4; u++)
             if (lane == 0 && c0 + u < nc) sel[c0 + u] = ((uint64_t)__float_as_uint(p[u]) << 32) | ls[u];
+        wave_lds_sync();
     }
-    for (uint32_t c = nc + (uint32_t)lane; c < (uint32_t)cap; c += 64) sel[c] = ~0ull;
-    __syncthreads();
-    // bitonic sort of the wave's `cap` entries
-    for (int kk = 2; kk <= cap; kk <<= 1)
-        for (int jj = kk >> 1; jj > 0; jj >>= 1) {
-            for (int e = lane; e < cap; e += 64) {
-                int p = e ^ jj;
-                if (p > e) {
-                    bool up = (e & kk) == 0;
-                    uint64_t x = sel[e], y = sel[p];
-                    if ((x > y) == up) { sel[e] = y; sel[p] = x; }
-                }
-            }
-            __syncthreads();
-        }
-    if (qi0 < nq && fits)
+    const int n2 = next_pow2((int)nc < 2 ? 2 : (int)nc);
+    for (int e = (int)nc + lane; e < n2; e += 64) sel[e] = ~0ull;
+    wave_lds_sync();
+    wave_bitonic_sort_lds(sel, n2, lane);
+    if (fits)
         for (int e = lane; e < nprobe; e += 64) {
             uint64_t key = sel[e];
             probe_ids[(size_t)qi * nprobe + e] = (int32_t)(uint32_t)key;
@@ -542,17 +599,28 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
         GEMM_CASE(256);
     }
 #undef GEMM_CASE
-    // room for the lists inside the margin: a quarter more than nprobe, at least 32
+    // LDS room per query: the lists inside the margin (a quarter more than nprobe, at least 32), or,
+    // when the sample route is used, the keys up to the sample's estimate (about 2-4 x nprobe)
     const int extra = nprobe / 4 > 32 ? nprobe / 4 : 32;
     int cap = next_pow2(nprobe + extra);
     if (cap < 64) cap = 64;
+    int nsamp = 0, ksamp = 0;
+    if (nprobe <= 496 && v.nlist >= 4 * SHORTLIST_SAMPLE / 2 && 8 * nprobe <= v.nlist) {
+        nsamp = SHORTLIST_SAMPLE;
+        // the sample's expected share of the nprobe best, plus three standard deviations and a bit
+        const double share = (double)nprobe * nsamp / v.nlist;
+        ksamp = (int)(share + 3.0 * sqrt(share) + 4.0);
+        if (ksamp > nsamp) ksamp = nsamp;
+        const int cap2 = next_pow2(4 * nprobe + 64);
+        if (cap2 > cap) cap = cap2;
+    }
     const size_t sel_bytes = (size_t)cap * 8 * (WG / 64);
     if (sel_bytes > 32 * 1024)
         RAIRS_HIP(hipFuncSetAttribute((const void *)coarse_shortlist_kernel,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_bytes));
     hipLaunchKernelGGL(coarse_shortlist_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))),
                        dim3(WG), sel_bytes, s, keys, q, v.centroids, v.d, v.nlist,
-                       nprobe, cap, v.cmax2, nq, probe_ids, probe_dists, flags);
+                       nprobe, cap, nsamp, ksamp, v.cmax2, nq, probe_ids, probe_dists, flags);
     // queries whose shortlist did not fit (many lists at nearly the same distance): full route,
     // both steps by the query's own workgroup
     hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist, nprobe,

@@ -574,13 +574,6 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
 // writes the bigK smallest.  No workgroup barrier is used: a wave only touches its own region, and
 // LDS operations of one wave complete in issue order.
 #define SELW_CAP_MAX 1024
-static __device__ __forceinline__ void wave_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanArgs a, int cap)
 {
     extern __shared__ __align__(16) uint64_t selw_keys[];      // [WG / 64][cap]
@@ -589,7 +582,7 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
     if (q >= a.nq) return;
     const uint32_t n = a.surv_cnt[q];
     if (n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) {
-        if (lane == 0) a.flags[q] = 1;      // redone by the second pass or the exact kernel
+        if (lane == 0) a.flags[q] = 1;      // redone by the exact kernel
         return;
     }
     if (n > (uint32_t)cap) return;          // select_kernel's case

@@ -171,12 +171,14 @@ def test_larger_dimensions_and_u8_raw(binding):
     _compare_all_stages(binding, hx, q, 10, 6, 100)
 
 
-@pytest.mark.parametrize("d", [32, 64, 96, 128, 256])
-def test_coarse_shortlist_and_its_fallback(binding, d):
+@pytest.mark.parametrize("d,nlist", [(32, 203), (64, 203), (96, 203), (128, 203), (256, 203),
+                                     (32, 1100), (128, 2051)])
+def test_coarse_shortlist_and_its_fallback(binding, d, nlist):
     # Lists at (nearly) the same distance: the matrix-core shortlist has to hand such queries to
-    # the direct-form route, and ties are decided by list id on both sides.
+    # the direct-form route, and ties are decided by list id on both sides.  From 1024 lists on,
+    # the threshold comes from a sample of the row when that works, else from the radix select.
     g = np.random.Generator(np.random.PCG64(200 + d))
-    nlist, nq = 203, 77
+    nq = 77
     x = datagen.random_vectors(60 + d, 700, d)
     q = datagen.random_vectors(61 + d, nq, d)
     cb = ib.train_pq(x, d // 2, 2, 2)
@@ -192,8 +194,8 @@ def test_coarse_shortlist_and_its_fallback(binding, d):
         ox = oracle.OracleIndex(hx)
         ix = binding.Index(hx)
         try:
-            for nprobe in (1, 7, 64, nlist):
-                print(f"case: coarse d={d} centroids={name} nprobe={nprobe}", flush=True)
+            for nprobe in (1, 7, 64, nlist // 8, nlist):
+                print(f"case: coarse d={d} nlist={nlist} centroids={name} nprobe={nprobe}", flush=True)
                 qq = q * 200.0 + 100.0 if name == "big" else q
                 pid, pdist = ix.coarse(_dev(qq.astype(np.float32)), nprobe)
                 torch.cuda.synchronize()
