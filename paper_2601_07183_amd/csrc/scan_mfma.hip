@@ -618,21 +618,44 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
             if (i < n) keys[i] = keep ? (((uint64_t)score << 32) | id[u]) : ~0ull;
         }
     }
-    const int n2 = next_pow2(n < 2 ? 2 : (int)n);
-    for (int i = (int)n + lane; i < n2; i += 64) keys[i] = ~0ull;
     wave_lds_sync();
-    for (int k = 2; k <= n2; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = lane; i < n2; i += 64) {
-                const int p = i ^ j;
-                if (p > i) {
-                    const bool up = (i & k) == 0;
-                    const uint64_t x = keys[i], y = keys[p];
-                    if ((x > y) == up) { keys[i] = y; keys[p] = x; }
-                }
-            }
-            wave_lds_sync();
+    // Only entries up to the score of the bigK-th best need sorting: take the kept keys back into
+    // registers, find that score by bisection on its 16 bits, and pack the entries up to it.
+    uint64_t mine[SELW_CAP_MAX / 64];
+#pragma unroll
+    for (int u = 0; u < SELW_CAP_MAX / 64; u++) {
+        mine[u] = ~0ull;
+        if (64 * u < (int)n) {                          // uniform
+            const uint32_t i = 64 * u + lane;
+            if (i < n) mine[u] = keys[i];
         }
+    }
+    uint32_t cut = 0;                                   // largest t with fewer than bigK scores below it
+    for (int bit = 15; bit >= 0; bit--) {
+        const uint32_t cand = cut | (1u << bit);
+        uint32_t below = 0;
+#pragma unroll
+        for (int u = 0; u < SELW_CAP_MAX / 64; u++)
+            if (64 * u < (int)n) below += (uint32_t)__popcll(__ballot((uint32_t)(mine[u] >> 32) < cand));
+        if (below < (uint32_t)a.refine_k) cut = cand;
+    }
+    // (dropped entries carry score 0xFFFFFFFF and are never below a candidate; with fewer than bigK
+    // kept entries cut ends at 0xFFFF and everything kept is packed)
+    wave_lds_sync();                                    // every lane has its keys in registers
+    uint32_t m = 0;
+#pragma unroll
+    for (int u = 0; u < SELW_CAP_MAX / 64; u++) {
+        if (64 * u < (int)n) {
+            const bool in = (uint32_t)(mine[u] >> 32) <= cut;
+            const unsigned long long bal = __ballot(in);
+            if (in) keys[m + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull))] = mine[u];
+            m += (uint32_t)__popcll(bal);
+        }
+    }
+    const int n2 = next_pow2(m < 2 ? 2 : (int)m);
+    for (int i = (int)m + lane; i < n2; i += 64) keys[i] = ~0ull;
+    wave_lds_sync();
+    wave_bitonic_sort_lds(keys, n2, lane);
     for (int i = lane; i < a.refine_k; i += 64) {
         const uint64_t key = i < n2 ? keys[i] : ~0ull;
         const bool ok = key != ~0ull;
