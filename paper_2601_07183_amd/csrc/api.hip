@@ -165,25 +165,39 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_CHECK(dev_alloc(h, (void **)&refs, (size_t)x->nrefs * sizeof(RefEntry)));
     UP_CHECK(dev_alloc(h, &raw, raw_bytes));
 
-    // centroids: row-major for the re-scoring of shortlisted lists, transposed to [d][nlist] so
-    // that lanes walking over lists read coalesced, and their squared norms for the GEMM form
-    std::vector<float> hn((size_t)x->nlist);
+    // centroids: row-major for the re-scoring of shortlisted lists and transposed to [d][nlist] so
+    // that lanes walking over lists read coalesced.  The GEMM form works on centred copies,
+    // c' = fl(c - mean of the centroids): distances do not change, but the rounding-error margin
+    // scales with |q'|^2 + |c'|^2, which centring makes as small as the data allow.
+    std::vector<float> hmean((size_t)x->d), hct((size_t)x->nlist * x->d), hn((size_t)x->nlist);
+    for (int i = 0; i < x->d; i++) {
+        double m = 0.0;
+        for (int l = 0; l < x->nlist; l++) m += (double)x->centroids[(size_t)l * x->d + i];
+        hmean[(size_t)i] = (float)(m / x->nlist);
+    }
     double nmax = 0.0;
     for (int l = 0; l < x->nlist; l++) {
         double n2 = 0.0;
         for (int i = 0; i < x->d; i++) {
-            const double c = (double)x->centroids[(size_t)l * x->d + i];
-            n2 += c * c;
+            const float c = x->centroids[(size_t)l * x->d + i] - hmean[(size_t)i];
+            hct[(size_t)i * x->nlist + l] = c;
+            n2 += (double)c * (double)c;
         }
         hn[(size_t)l] = (float)n2;
         if (n2 > nmax) nmax = n2;
     }
     v.cmax2 = (float)nmax;
+    float *cent_ct = nullptr, *cmean = nullptr;
+    UP_CHECK(dev_alloc(h, (void **)&cent_ct, cent_bytes));
+    UP_CHECK(dev_alloc(h, (void **)&cmean, (size_t)x->d * sizeof(float)));
     hipError_t e = hipSuccess;
     UP_HIP(hipMemcpyAsync(cent, x->centroids, cent_bytes, hipMemcpyHostToDevice, s));
+    UP_HIP(hipMemcpyAsync(cent_ct, hct.data(), cent_bytes, hipMemcpyHostToDevice, s));
+    UP_HIP(hipMemcpyAsync(cmean, hmean.data(), (size_t)x->d * sizeof(float), hipMemcpyHostToDevice, s));
     UP_HIP(hipMemcpyAsync(cnorm, hn.data(), hn.size() * sizeof(float), hipMemcpyHostToDevice, s));
     UP_CHECK(rairs_launch_transpose(cent, x->nlist, x->d, cent_t, s));
     UP_HIP(hipStreamSynchronize(s));
+    v.centroids_ct = cent_ct; v.cmean = cmean;
     UP_HIP(hipMemcpyAsync(cb, x->codebook, cb_bytes, hipMemcpyHostToDevice, s));
     if (x->nblocks)
         UP_HIP(hipMemcpyAsync(other, x->other, (size_t)x->nblocks * 32 * 4, hipMemcpyHostToDevice, s));

@@ -248,7 +248,8 @@ __global__ __launch_bounds__(WG) void coarse_select_kernel(float *dmat,
     }
 }
 
-// Shortlist route, scores: keys[q][l] = f32_key(|c_l|^2 - 2 q.c_l) with v_mfma_f32_32x32x2f32.
+// Shortlist route, scores: keys[q][l] = f32_key(|c'_l|^2 - 2 q'.c'_l) with v_mfma_f32_32x32x2f32,
+// where q' = fl(q - cmean) and c' = fl(c - cmean) are the centred query and centroid.
 // A workgroup takes 128 queries (32 per wave, kept in registers: lane (row i, half k) holds
 // q_i[k*D/2 + s], s < D/2) and walks over tiles of 32 lists.  A tile's centroids are staged in LDS
 // in operand order, element (s, k, j) = ct[k*D/2 + s][l0 + j] at s*64 + k*32 + j, so that the B
@@ -259,6 +260,7 @@ __global__ __launch_bounds__(WG) void coarse_select_kernel(float *dmat,
 template <int D>
 __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict__ q,
                                                          const float *__restrict__ ct,
+                                                         const float *__restrict__ cmean,
                                                          const float *__restrict__ cnorm, int nlist,
                                                          int csplits, int tiles_per_split, int64_t nq,
                                                          uint32_t *__restrict__ keys)
@@ -279,13 +281,14 @@ __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict
     }
     const int64_t q0 = (int64_t)qblock * GEMM_QWG + wave * 32;
     const int64_t qrow = q0 + i < nq ? q0 + i : nq - 1;
-    float A[H];
+    float A[H];                                         // centred: fl(q - cmean)
     {
         const float4 *src = (const float4 *)(q + (size_t)qrow * D + k * H);
+        const float4 *mu = (const float4 *)(cmean + k * H);
 #pragma unroll
         for (int s4 = 0; s4 < H / 4; s4++) {
-            const float4 x = src[s4];
-            A[4 * s4] = x.x; A[4 * s4 + 1] = x.y; A[4 * s4 + 2] = x.z; A[4 * s4 + 3] = x.w;
+            const float4 x = src[s4], m = mu[s4];
+            A[4 * s4] = x.x - m.x; A[4 * s4 + 1] = x.y - m.y; A[4 * s4 + 2] = x.z - m.z; A[4 * s4 + 3] = x.w - m.w;
         }
     }
     const int ntiles = (nlist + 31) >> 5;
@@ -338,16 +341,92 @@ __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict
     }
 }
 
+// The same scores for any dimension that is a multiple of 8: the dimensions are taken in chunks of
+// GEMM_CD; a wave holds the chunk of its 32 queries in registers, the chunk of a list tile is staged
+// in LDS, and the NT tiles of the workgroup keep their accumulators across the chunks.
+#define GEMM_CD 128
+template <int NT>
+__global__ __launch_bounds__(WG) void coarse_gemm_chunk_kernel(const float *__restrict__ q,
+                                                               const float *__restrict__ ct,
+                                                               const float *__restrict__ cmean,
+                                                               const float *__restrict__ cnorm, int d,
+                                                               int nlist, int ngroups, int64_t nq,
+                                                               uint32_t *__restrict__ keys)
+{
+    __shared__ float Bs[GEMM_CD * 32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = lane & 31, k = lane >> 5;
+    const int qblock = blockIdx.x / ngroups, grp = blockIdx.x % ngroups;
+    const int64_t q0 = (int64_t)qblock * GEMM_QWG + wave * 32;
+    const int64_t qrow = q0 + i < nq ? q0 + i : nq - 1;
+    const int ntiles = (nlist + 31) >> 5;
+    const int sj = threadIdx.x & 31, sr = threadIdx.x >> 5;
+    v16f acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[t][r] = 0.0f;
+    for (int c0 = 0; c0 < d; c0 += GEMM_CD) {
+        const int cd = d - c0 < GEMM_CD ? d - c0 : GEMM_CD;      // multiple of 8
+        const int h = cd >> 1;                                   // multiple of 4
+        float A[GEMM_CD / 2];
+        {
+            const float4 *src = (const float4 *)(q + (size_t)qrow * d + c0 + k * h);
+            const float4 *mu = (const float4 *)(cmean + c0 + k * h);
+#pragma unroll
+            for (int s4 = 0; s4 < GEMM_CD / 8; s4++) {
+                float4 x = make_float4(0.0f, 0.0f, 0.0f, 0.0f), m = x;
+                if (4 * s4 < h) { x = src[s4]; m = mu[s4]; }
+                A[4 * s4] = x.x - m.x; A[4 * s4 + 1] = x.y - m.y; A[4 * s4 + 2] = x.z - m.z; A[4 * s4 + 3] = x.w - m.w;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NT; t++) {
+            const int tile = grp * NT + t;
+            if (tile < ntiles) {                                 // uniform for the workgroup
+                __syncthreads();                                 // the previous chunk has been consumed
+                const int l = tile * 32 + sj;
+                const float *src = ct + (size_t)c0 * nlist + (l < nlist ? l : nlist - 1);
+#pragma unroll
+                for (int e = 0; e < GEMM_CD / 8; e++) {
+                    const int row = sr + 8 * e;
+                    if (row < cd) {
+                        const int kk = row >= h ? 1 : 0, ss = row - kk * h;
+                        Bs[ss * 64 + kk * 32 + sj] = src[(size_t)row * nlist];
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int s = 0; s < GEMM_CD / 2; s++)
+                    if (s < h) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[s], Bs[s * 64 + lane], acc[t], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; t++) {
+        const int l = (grp * NT + t) * 32 + i;
+        if (l < nlist) {
+            const float cn = cnorm[l];
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const int64_t qq = q0 + 8 * (r >> 2) + 4 * k + (r & 3);
+                const float two = 2.0f * acc[t][r];
+                if (qq < nq) keys[(size_t)qq * nlist + l] = f32_key(cn - two);
+            }
+        }
+    }
+}
+
 // Shortlist route, selection.  One wave per query (four per workgroup, each with its own LDS
 // region and no workgroup barrier): find the nprobe-th smallest key, widen it by the margin, gather
 // the lists up to there, re-score them in the direct form, sort by (distance, list id), keep nprobe.
 //
-// Margin.  With u = 2^-24 and exact values D = |q - c|^2: the direct form is within (d + 2) u D of
-// D, D <= 2 (|q|^2 + |c|^2); the GEMM form's dot product is within d u |q||c|, the norm within
-// u |c|^2 and the final subtraction within u |s|.  Together |direct - (s + |q|^2)| stays below
-// 4 (d + 2) u (|q|^2 + max |c|^2) =: e, and every list among the nprobe best by the direct form has
-// s <= (nprobe-th smallest s) + 2 e.  The kernel uses 16 (d + 2) u (|q|^2 + max |c|^2), twice that,
-// against accumulation orders inside the matrix core that are not documented.
+// Margin.  With u = 2^-24, a = q - cmean, b = c - cmean, N = |a|^2 + max |b|^2 and the exact
+// D = |q - c|^2 = |a - b|^2 <= 2 N: the direct form is within (d + 2) u D of D; rounding a and b
+// to fp32 moves |a - b|^2 by at most about 4 u N; the GEMM form's dot product is within
+// d u |a'||b'|, the norm within u |b'|^2 and the final subtraction within u |s|.  Together
+// |direct - (s + |a'|^2)| stays below 4 (d + 4) u N =: e, and every list among the nprobe best by
+// the direct form has s <= (nprobe-th smallest s) + 2 e.  The kernel uses 16 (d + 4) u N, twice
+// that, against accumulation orders inside the matrix core that are not documented.
 //
 // The nprobe-th smallest key is found in one pass over the row when a sample allows it: the
 // ksamp-th smallest key `est` of the row's first `nsamp` keys is, with ksamp chosen well above the
@@ -361,6 +440,7 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
                                                               const float *__restrict__ cent, int d,
                                                               int nlist, int nprobe, int cap,
                                                               int nsamp, int ksamp,
+                                                              const float *__restrict__ cmean,
                                                               float cmax2, int64_t nq,
                                                               int32_t *__restrict__ probe_ids,
                                                               float *__restrict__ probe_dists,
@@ -379,10 +459,13 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
     // |q|^2 and the margin
     const float *qq = q + (size_t)qi * d;
     float qn = 0.0f;
-    for (int t = lane; t < d; t += 64) qn += qq[t] * qq[t];
+    for (int t = lane; t < d; t += 64) {
+        const float a = qq[t] - cmean[t];
+        qn += a * a;
+    }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) qn += __shfl_xor(qn, off);
-    const float margin = 16.0f * (float)(d + 2) * 5.9604645e-8f * (qn + cmax2);
+    const float margin = 16.0f * (float)(d + 4) * 5.9604645e-8f * (qn + cmax2);
     const bool margin_ok = !(margin != margin) && margin < 3.0e38f;
 
     uint32_t nc = 0;                                     // lists in the shortlist (their ids in sel[0..nc))
@@ -513,24 +596,21 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
     wave_lds_sync();
     // re-score in the direct form: the wave takes one list at a time, lane j sums the dimensions
     // of class j and the fold is a butterfly over the lanes (lane 0 ends with the defined value)
-    float qr[4];
-#pragma unroll
-    for (int c = 0; c < 4; c++) qr[c] = 64 * c + lane < d ? qq[64 * c + lane] : 0.0f;
     for (uint32_t c0 = 0; c0 < nc; c0 += 4) {
         float p[4];
         uint32_t ls[4];
 #pragma unroll
         for (int u = 0; u < 4; u++) {
             ls[u] = (uint32_t)sel[c0 + u < nc ? c0 + u : nc - 1];
-            const float *cr = cent + (size_t)ls[u] * d;
             p[u] = 0.0f;
+        }
+        for (int t = lane; t < d; t += 64) {            // class `lane`, dimensions increasing
+            const float qv = qq[t];
 #pragma unroll
-            for (int c = 0; c < 4; c++) {
-                if (64 * c + lane < d) {
-                    float diff = qr[c] - cr[64 * c + lane];
-                    float sq = diff * diff;
-                    p[u] = p[u] + sq;
-                }
+            for (int u = 0; u < 4; u++) {
+                float diff = qv - cent[(size_t)ls[u] * d + t];
+                float sq = diff * diff;
+                p[u] = p[u] + sq;
             }
         }
 #pragma unroll
@@ -559,8 +639,7 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
 #define SHORTLIST_MAX_NPROBE 1024
 static bool coarse_shortlist_ok(const IndexView &v, int nprobe)
 {
-    return (v.d == 32 || v.d == 64 || v.d == 96 || v.d == 128 || v.d == 256) &&
-           nprobe <= SHORTLIST_MAX_NPROBE && v.nlist >= 64;
+    return v.d % 8 == 0 && nprobe <= SHORTLIST_MAX_NPROBE && v.nlist >= 64;
 }
 
 int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,
@@ -588,7 +667,7 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
     uint32_t *keys = (uint32_t *)dmat;
 #define GEMM_CASE(D)                                                                              \
     case D:                                                                                       \
-        hipLaunchKernelGGL(coarse_gemm_kernel<D>, grid, dim3(WG), 0, s, q, v.centroids_t, v.cnorm, \
+        hipLaunchKernelGGL(coarse_gemm_kernel<D>, grid, dim3(WG), 0, s, q, v.centroids_ct, v.cmean, v.cnorm, \
                            v.nlist, csplits, tiles_per_split, nq, keys);                          \
         break
     switch (v.d) {
@@ -597,11 +676,22 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
         GEMM_CASE(96);
         GEMM_CASE(128);
         GEMM_CASE(256);
+    default: {
+        // any other multiple of 8: chunked kernel, four list tiles per workgroup when that still
+        // gives the chip enough workgroups, else one
+        const int g4 = (ntiles + 3) / 4;
+        if ((int64_t)qblocks * g4 >= 512)
+            hipLaunchKernelGGL(coarse_gemm_chunk_kernel<4>, dim3(qblocks * g4), dim3(WG), 0, s, q,
+                               v.centroids_ct, v.cmean, v.cnorm, v.d, v.nlist, g4, nq, keys);
+        else
+            hipLaunchKernelGGL(coarse_gemm_chunk_kernel<1>, dim3(qblocks * ntiles), dim3(WG), 0, s, q,
+                               v.centroids_ct, v.cmean, v.cnorm, v.d, v.nlist, ntiles, nq, keys);
+    }
     }
 #undef GEMM_CASE
-    // LDS room per query: the lists inside the margin (a quarter more than nprobe, at least 32), or,
+    // LDS room per query: the lists inside the margin (half more than nprobe, at least 64), or,
     // when the sample route is used, the keys up to the sample's estimate (about 2-4 x nprobe)
-    const int extra = nprobe / 4 > 32 ? nprobe / 4 : 32;
+    const int extra = nprobe / 2 > 64 ? nprobe / 2 : 64;
     int cap = next_pow2(nprobe + extra);
     if (cap < 64) cap = 64;
     int nsamp = 0, ksamp = 0;
@@ -620,7 +710,7 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_bytes));
     hipLaunchKernelGGL(coarse_shortlist_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))),
                        dim3(WG), sel_bytes, s, keys, q, v.centroids, v.d, v.nlist,
-                       nprobe, cap, nsamp, ksamp, v.cmax2, nq, probe_ids, probe_dists, flags);
+                       nprobe, cap, nsamp, ksamp, v.cmean, v.cmax2, nq, probe_ids, probe_dists, flags);
     // queries whose shortlist did not fit (many lists at nearly the same distance): full route,
     // both steps by the query's own workgroup
     hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist, nprobe,

@@ -45,8 +45,10 @@ struct IndexView {
     int64_t ntotal, nblocks, nrefs;
     const float *centroids;       // [nlist][d]
     const float *centroids_t;     // [d][nlist]
-    const float *cnorm;           // [nlist] squared norms
-    float cmax2;                  // largest squared norm of a centroid
+    const float *centroids_ct;    // [d][nlist] centred: fl(c - cmean)
+    const float *cmean;           // [d] mean of the centroids
+    const float *cnorm;           // [nlist] squared norms of the centred centroids
+    float cmax2;                  // largest of them
     const float *codebook;        // [M][16][d/M]
     // codes: per block nd x 64 dwords; lane = parity * 32 + item; dword w of lane (g, item) packs
     // the codes of subspaces 2t+g, t = 8w .. 8w+7, nibble (t & 7) at bits 4*(t & 7)
@@ -65,7 +67,7 @@ struct IndexView {
 
 struct rairs_index {
     IndexView v;
-    void *dev_alloc[16];
+    void *dev_alloc[24];
     int64_t nsegs;
     int max_parts;                // most segments in any list (bounds the work-unit table)
     int ndev_alloc;

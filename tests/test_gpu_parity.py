@@ -172,7 +172,7 @@ def test_larger_dimensions_and_u8_raw(binding):
 
 
 @pytest.mark.parametrize("d,nlist", [(32, 203), (64, 203), (96, 203), (128, 203), (256, 203),
-                                     (32, 1100), (128, 2051)])
+                                     (32, 1100), (128, 2051), (200, 203), (528, 300)])
 def test_coarse_shortlist_and_its_fallback(binding, d, nlist):
     # Lists at (nearly) the same distance: the matrix-core shortlist has to hand such queries to
     # the direct-form route, and ties are decided by list id on both sides.  From 1024 lists on,
@@ -181,7 +181,7 @@ def test_coarse_shortlist_and_its_fallback(binding, d, nlist):
     nq = 77
     x = datagen.random_vectors(60 + d, 700, d)
     q = datagen.random_vectors(61 + d, nq, d)
-    cb = ib.train_pq(x, d // 2, 2, 2)
+    cb = ib.train_pq(x, d // 2 if d <= 256 else d // 8, 2, 2)
     asg = np.sort(g.integers(0, nlist, size=(len(x), 2)), axis=1).astype(np.int32)
     base_c = datagen.random_vectors(62 + d, nlist, d)
     dup = base_c.copy()
