@@ -223,21 +223,34 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
             }
         }
     } else {
-        for (int b = 0; b < cnt; b++) {
-            const uint32_t *cp = v.codes + (size_t)(begin + b) * v.nd * 64 + lane;
-            uint32_t part = 0;
-            for (int w = 0; w < v.nd; w++) {
-                const uint32_t c = cp[(size_t)w * 64];
-                const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
-                for (int n = 0; n < tmax; n++) {
-                    const int m = 2 * (8 * w + n) + g;
-                    part += lq[m * 16 + ((c >> (4 * n)) & 15u)];
-                }
+        // up to 16 code dwords per block: two blocks at a time, all dwords fetched before the lookups
+        for (int b0 = 0; b0 < cnt; b0 += 2) {
+            uint32_t c[2][16];
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int64_t blk = begin + (b0 + u < cnt ? b0 + u : cnt - 1);
+                const uint32_t *cp = v.codes + (size_t)blk * v.nd * 64 + lane;
+#pragma unroll
+                for (int w = 0; w < 16; w++) c[u][w] = cp[(size_t)(w < v.nd ? w : 0) * 64];
             }
-            const uint32_t acc = part + (uint32_t)__shfl_xor((int)part, 32);
-            const bool valid = lane < 32 && b * 32 + lane < nitems;
-            if (lane < 32) sc[b * 32 + lane] = valid ? (uint16_t)acc : (uint16_t)0xFFFFu;
-            nvalid += (uint32_t)__popcll(__ballot(valid));
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                uint32_t part = 0;
+#pragma unroll
+                for (int w = 0; w < 16; w++) {
+                    if (w < v.nd) {
+                        const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
+                        for (int n = 0; n < tmax; n++) {
+                            const int m = 2 * (8 * w + n) + g;
+                            part += lq[m * 16 + ((c[u][w] >> (4 * n)) & 15u)];
+                        }
+                    }
+                }
+                const uint32_t acc = part + (uint32_t)__shfl_xor((int)part, 32);
+                const bool valid = lane < 32 && b0 + u < cnt && (b0 + u) * 32 + lane < nitems;
+                if (lane < 32 && b0 + u < cnt) sc[(b0 + u) * 32 + lane] = valid ? (uint16_t)acc : (uint16_t)0xFFFFu;
+                nvalid += (uint32_t)__popcll(__ballot(valid));
+            }
         }
     }
     __syncthreads();
