@@ -94,6 +94,9 @@ def main():
                          "(for profiling; the headline numbers are quoted at full size)")
     ap.add_argument("--recall-queries", type=int, default=0,
                     help="measure recall on the first N queries only (0 = all); for very large bases")
+    ap.add_argument("--k", type=int, default=0, help="override K of the workload (second workloads: K = 1, 100)")
+    ap.add_argument("--refine-k", type=int, default=0, help="override bigK = K * K_FACTOR")
+    ap.add_argument("--nq", type=int, default=0, help="queries per step (default: the workload's batch)")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="only run a device-to-device copy of this many bytes three times (to "
                          "calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -121,6 +124,9 @@ def main():
     w = datagen.WORKLOADS[args.workload]
     if args.base_size:
         w = datagen.scaled(w, args.base_size)
+    if args.k or args.refine_k or args.nq:
+        from dataclasses import replace
+        w = replace(w, k=args.k or w.k, refine_k=args.refine_k or w.refine_k, nq=args.nq or w.nq)
     t0 = time.time()
     base = datagen.make_base(w)
     queries = datagen.make_queries(w)

@@ -151,8 +151,9 @@ int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t 
 
 // ---- bound from a sample ------------------------------------------------------------------------
 //
-// tau[q] = bigK-th smallest score among the items of the first `sample_blocks` own blocks of the
-// query's first probed list (0xFFFF when they hold fewer than bigK items).  Every item there is
+// bound[q] = bigK-th smallest score among the items of the first `sample_blocks` own blocks of the
+// query's first probed list (0xFFFF when they hold fewer than bigK items); tau[q] = the range of
+// the query's score histogram (the same value when it exists).  Every item there is
 // either an entry of the query's candidate queue or, when the duplicate rule drops it, the twin of
 // an entry with the same code that is queued from its other list (SEIL keeps the remainder of a
 // cell in the miscellaneous areas of both lists, Section 5.1); so at least bigK entries of the
@@ -269,8 +270,26 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
             if (below < (uint32_t)refine_k) t = cand;
         }
     }
+    // Range of the query's score histogram: tau when there is one; else (the sample held fewer than
+    // bigK items, so there is no bound yet) twice the largest sampled score -- a guess that only
+    // sets the width of the bins, scores beyond it share the last bin, which never yields a bound.
+    uint32_t range = t;
+    if (t == 0xFFFFu) {
+        uint32_t smax = 0;
+        for (int e = lane; e < cnt * 32; e += 64) {
+            const uint32_t x = sc[e];
+            if (x != 0xFFFFu && x > smax) smax = x;
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)smax, off);
+            smax = o > smax ? o : smax;
+        }
+        const uint32_t full = 255u * (uint32_t)v.M;
+        range = nvalid > 0 && 2u * smax + 64u < full ? 2u * smax + 64u : full;
+    }
     if (lane == 0 && qi0 < nq) {
-        tau[qi] = (int32_t)t;
+        tau[qi] = (int32_t)range;
         if (bound) bound[qi] = (int32_t)t;
     }
     // DCO of the query (distance computations of the scan, Section 6.1): every valid slot of the

@@ -20,8 +20,9 @@
 // The bound.  tau0 = bigK-th smallest score in a sample, the head of the query's first list.  Every
 // survivor that the duplicate rule can never drop (an item of a shared block, or a miscellaneous
 // item whose other list has the larger id; the index keeps one bit per slot for this) is counted in
-// a per-query histogram of RAIRS_HIST_BINS equal score bins over [0, tau0] (over [0, 255*M] when
-// the sample had fewer than bigK items).  Each counted slot is an entry of the query's candidate
+// a per-query histogram of RAIRS_HIST_BINS equal score bins over [0, tau0] (over a guessed range
+// when the sample had fewer than bigK items; scores beyond it share the last bin, which proves
+// nothing).  Each counted slot is an entry of the query's candidate
 // queue, so once bins 0..b hold >= bigK of them, no item scoring above the top edge of bin b can be
 // among the bigK best: that edge is a valid, tighter bound.  Lanes that file survivors re-derive
 // the query's bound now and then and lower it with an atomic minimum; scanning waves re-read it
@@ -203,7 +204,8 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(const int32_t *__restr
 // ---- the scan ----------------------------------------------------------------------------------
 
 // Bin of a score: floor(score * mul / 2^32) with mul = floor(2^38 / (range + 1)), range >= 64, so
-// that scores 0..range fall into bins 0..63 without a division on the hot path.
+// that scores 0..range fall into bins 0..63 without a division on the hot path (larger scores are
+// put into bin 63 by the caller).
 static __device__ __forceinline__ uint32_t hist_mul(uint32_t range)
 {
     const uint32_t r = range < 64u ? 64u : range;
@@ -230,7 +232,7 @@ static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a
         cum += h[i].z; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i + 2 : b;
         cum += h[i].w; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i + 3 : b;
     }
-    if (b == RAIRS_HIST_BINS) return 0xFFFFu;
+    if (b >= RAIRS_HIST_BINS - 1) return 0xFFFFu;      // the last bin also holds scores beyond the range
     // largest score whose bin is <= b
     const uint64_t edge = ((((uint64_t)(b + 1)) << 32) - 1ull) / (uint64_t)mul;
     return edge < 0xFFFFull ? (uint32_t)edge : 0xFFFFu;
@@ -281,7 +283,11 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
             if (room)
                 a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint4(sq.slot[i], sl, qid, 0u);
             if (qraw >> 31)
-                atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + __umulhi(sl >> 16, sq.hmul[i])], 1u);
+            {
+                // scores beyond the histogram's range share the last bin
+                const uint32_t bin = __umulhi(sl >> 16, sq.hmul[i]);
+                atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + (bin < RAIRS_HIST_BINS - 1 ? bin : RAIRS_HIST_BINS - 1)], 1u);
+            }
         }
     }
     if ((nflush & 1u) == 0u && lane < n && ((lane + (nflush >> 1)) & 3) == 0) {
@@ -368,8 +374,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
             const int base = a.loff[L], n = a.loff[L + 1] - base;
             const int qi = tile * 32 + j;
             qid = qi < n ? a.qlist[base + qi] : -1;
-            const uint32_t tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
-            hmul = hist_mul(tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0);
+            hmul = hist_mul(qid >= 0 ? (uint32_t)a.tau[qid] : 0u);
             const uint8_t *lq = a.lut + (size_t)(qid >= 0 ? qid : 0) * (M * 16) + g * 16;
             // every lane loads (an absent column reads query 0's rows and masks them to zero): a
             // conditional load would be waited for one by one
@@ -822,8 +827,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
         }
         const int qi = tile * 32 + j;
         const int qid = qi < nql ? a.qlist[base + qi] : -1;
-        const uint32_t tau0 = qid >= 0 ? (uint32_t)a.tau[qid] : 0u;
-        const uint32_t hmul = hist_mul(tau0 == 0xFFFFu ? 255u * (uint32_t)M : tau0);
+        const uint32_t hmul = hist_mul(qid >= 0 ? (uint32_t)a.tau[qid] : 0u);
         const int32_t *bq = a.bound + (qid >= 0 ? qid : 0);
         const uint32_t *bmq = a.bitmap + (size_t)(qid >= 0 ? qid : 0) * a.bmwords;
         __syncthreads();

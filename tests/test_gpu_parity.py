@@ -161,6 +161,27 @@ def test_identical_codes_tie_on_score(binding, count):
     _compare_all_stages(binding, hx, q, 10, 4, 64)
 
 
+def test_survivor_log_runs_out_of_chunks(binding):
+    # 120,000 identical vectors: every scanned item passes any bound, the survivor log of a small
+    # batch runs out of chunks, every query is flagged and the exact kernel redoes them all
+    count = 120_000
+    x = np.tile(datagen.random_vectors(54, 1, 8), (count, 1))
+    q = datagen.random_vectors(55, 30, 8)
+    cents = datagen.random_vectors(56, 4, 8)
+    cb = ib.train_pq(datagen.random_vectors(57, 300, 8), 4, 5, 2)
+    g = np.random.Generator(np.random.PCG64(4))
+    asg = np.sort(g.integers(0, 4, size=(count, 2)), axis=1).astype(np.int32)
+    hx = ib.add_vectors(x, cents, cb, assign=asg)
+    _compare_all_stages(binding, hx, q, 10, 4, 64)
+    ix = binding.Index(hx)
+    try:
+        ix.search(_dev(q), 10, 4, 64)
+        torch.cuda.synchronize()
+        assert ix.scan_stats()["redone"] == len(q)       # the log did run out
+    finally:
+        ix.free()
+
+
 def test_larger_dimensions_and_u8_raw(binding):
     # d = 192 (three 64-dimension folds), M = 96 (6 code dwords per lane), uint8 raw vectors
     g = np.random.Generator(np.random.PCG64(77))
