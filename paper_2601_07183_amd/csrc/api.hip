@@ -240,6 +240,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     }
     // scan segments: the list's own blocks, then each referenced cell, in runs of <= 16 blocks
     std::vector<SegEntry> hs;
+    std::vector<int32_t> hp;
     for (int l = 0; l < x->nlist; l++) {
         ListEntry &e2 = hl[(size_t)l];
         e2.seg_begin = (int32_t)hs.size();
@@ -268,11 +269,31 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
             }
         }
         e2.seg_cnt = (int32_t)hs.size() - e2.seg_begin;
+        // parts: consecutive segments of about RAIRS_PART_BLOCKS blocks, the scan's unit of work
+        e2.part_begin = (int32_t)hp.size();
+        int in_blocks = 0, in_segs = 0;
+        for (int sidx = e2.seg_begin; sidx < e2.seg_begin + e2.seg_cnt; sidx++) {
+            const int nb = hs[(size_t)sidx].nblk;
+            if (in_segs == 0 || in_blocks + nb > RAIRS_PART_BLOCKS || in_segs == RAIRS_PART_SEGS) {
+                hp.push_back(sidx);
+                in_blocks = 0;
+                in_segs = 0;
+            }
+            in_blocks += nb;
+            in_segs++;
+        }
+        e2.part_cnt = (int32_t)hp.size() - e2.part_begin;
+        hp.push_back(e2.seg_begin + e2.seg_cnt);
     }
     h->nsegs = (int64_t)hs.size();
     h->max_parts = 1;
     for (int l = 0; l < x->nlist; l++)
-        if (hl[(size_t)l].seg_cnt > h->max_parts) h->max_parts = hl[(size_t)l].seg_cnt;
+        if (hl[(size_t)l].part_cnt > h->max_parts) h->max_parts = hl[(size_t)l].part_cnt;
+    int32_t *parts = nullptr;
+    UP_CHECK(dev_alloc(h, (void **)&parts, hp.size() * sizeof(int32_t)));
+    if (!hp.empty())
+        UP_HIP(hipMemcpyAsync(parts, hp.data(), hp.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    h->nparts = (int64_t)hp.size() - x->nlist;
     SegEntry *segs = nullptr;
     UP_CHECK(dev_alloc(h, (void **)&segs, hs.size() * sizeof(SegEntry)));
     if (!hs.empty())
@@ -317,7 +338,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
 
     v.idtag = idtag;
     v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask;
-    v.lists = lists; v.refs = refs; v.segs = segs; v.raw = raw;
+    v.lists = lists; v.refs = refs; v.segs = segs; v.parts = parts; v.raw = raw;
     for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[i]));
     h->ev_ready = 1;
     *out = h;
@@ -369,7 +390,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     w.lcursor = take((size_t)v.nlist * 4);
     w.toff = take((size_t)(v.nlist + 1) * 4);
     w.next_task = take(4);
-    w.unit_list = take(((size_t)nq * nprobe / 32 + (size_t)v.nlist) * (size_t)max_parts * 4);   // max_parts = most segments in a list
+    w.unit_list = take(((size_t)nq * nprobe / 32 + (size_t)v.nlist) * (size_t)max_parts * 4);   // max_parts = most parts in a list
     w.qlist = take((size_t)nq * nprobe * 4);
     w.tau = take((size_t)nq * 4);
     w.bound = take((size_t)nq * 4);
@@ -511,14 +532,15 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     ma.lcursor = (int32_t *)(ws + w.lcursor); ma.toff = (int32_t *)(ws + w.toff);
     ma.unit_list = (int32_t *)(ws + w.unit_list);
     {
-        // segments per unit: large units save table reloads, small ones keep 2048 waves busy
+        // parts per unit: large units save table reloads, small ones keep 2048 waves busy and the
+        // tail of the kernel short
         const int64_t tiles = n * (int64_t)nprobe / 32 + v.nlist;
-        const int64_t segs_total = tiles * (h->nsegs / (v.nlist > 0 ? v.nlist : 1) + 1);
-        int us = (int)(segs_total / (2048 * 6));
-        ma.unit_segs = us < 1 ? 1 : (us > 8 ? 8 : us);
+        const int64_t parts_total = tiles * (h->nparts / (v.nlist > 0 ? v.nlist : 1) + 1);
+        int up = (int)(parts_total / (2048 * 12));
+        ma.unit_parts = up < 1 ? 1 : (up > 4 ? 4 : up);
         // with the tables in LDS a whole workgroup shares a unit and reloads up to 128 KB of
         // tables for each: always the longest units
-        if (!(v.T == 8 || v.T == 24 || v.T == 32)) ma.unit_segs = 8;
+        if (!(v.T == 8 || v.T == 24 || v.T == 32)) ma.unit_parts = 4;
     }
     ma.next_task = (uint32_t *)(ws + w.next_task); ma.qlist = (int32_t *)(ws + w.qlist);
     ma.tau = (int32_t *)(ws + w.tau); ma.surv_cnt = (uint32_t *)(ws + w.surv_cnt);

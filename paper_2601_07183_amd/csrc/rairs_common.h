@@ -20,10 +20,14 @@ struct ListEntry {
     int32_t valid_items;   // non-empty slots in the list's own blocks
     int32_t seg_begin;     // scan segments of the list (own blocks in chunks, then references)
     int32_t seg_cnt;
+    int32_t part_begin;    // parts of the list: runs of consecutive segments of about equal work
+    int32_t part_cnt;
 };
 
 // A run of at most RAIRS_SEG_BLOCKS consecutive blocks that one wave scores for one query tile.
 #define RAIRS_SEG_BLOCKS 16
+#define RAIRS_PART_BLOCKS 32
+#define RAIRS_PART_SEGS 8
 struct SegEntry {
     int32_t blk_begin;
     int32_t nblk;
@@ -62,14 +66,19 @@ struct IndexView {
     const ListEntry *lists;       // [nlist]
     const RefEntry *refs;         // [nrefs]
     const SegEntry *segs;         // [nsegs]
+    // first segment (absolute) of every part, list by list, each list's run closed by the index
+    // one past its last segment: part p of list L is segments [parts[L.part_begin + p],
+    // parts[L.part_begin + p + 1]).  A part holds at most RAIRS_PART_SEGS segments and, unless a
+    // single segment is larger, at most RAIRS_PART_BLOCKS blocks.
+    const int32_t *parts;
     const void *raw;              // [ntotal][d] fp32 or u8
 };
 
 struct rairs_index {
     IndexView v;
     void *dev_alloc[24];
-    int64_t nsegs;
-    int max_parts;                // most segments in any list (bounds the work-unit table)
+    int64_t nsegs, nparts;
+    int max_parts;                // most parts in any list (bounds the work-unit table)
     int ndev_alloc;
     int64_t code_bytes, total_bytes;
     // workspace (grown on demand)
@@ -144,7 +153,7 @@ struct MfmaScanArgs {
     int32_t *qlist;               // [nq * nprobe] query ids grouped by list
     int32_t *toff;                // [nlist+1] exclusive prefix of work units per list
     int32_t *unit_list;           // [units] list of every work unit
-    int unit_segs;                // segments per unit, 1..8
+    int unit_parts;               // parts per unit, 1..4
     uint32_t *next_task;          // [1]
     const int32_t *tau;           // [nq] bound from the sample (0xFFFF: none); fixes the histogram range
     int32_t *bound;               // [nq] current bound, starts at tau, only decreases

@@ -63,19 +63,20 @@ __global__ void lm_count_kernel(const int32_t *__restrict__ probe_ids, int64_t n
     if (L >= 0 && L < nlist) atomicAdd(&lcount[L], 1);
 }
 
-// A unit of work is (list, tile of <= 32 of the queries probing it, part = up to unit_segs
-// consecutive segments of the list; unit_segs is 1..8, smaller when there is little work).  Exclusive prefixes over lists of queries (loff) and units
+// A unit of work is (list, tile of <= 32 of the queries probing it, run of unit_parts consecutive
+// parts of the list; a part is about 32 blocks, unit_parts is 1..4, smaller when there is little
+// work).  Exclusive prefixes over lists of queries (loff) and units
 // (toff), and the list of every unit; one workgroup of 1024.
-static __device__ __forceinline__ int units_of(int nqueries, int seg_cnt, int unit_segs)
+static __device__ __forceinline__ int units_of(int nqueries, int part_cnt, int unit_parts)
 {
-    return ((nqueries + 31) >> 5) * ((seg_cnt + unit_segs - 1) / unit_segs);
+    return ((nqueries + 31) >> 5) * ((part_cnt + unit_parts - 1) / unit_parts);
 }
 
 __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
                                                          const int32_t *__restrict__ lcount,
                                                          int32_t *loff, int32_t *lcursor,
                                                          int32_t *toff, int32_t *unit_list,
-                                                         int unit_segs)
+                                                         int unit_parts)
 {
     __shared__ int sc[1024], st[1024];
     const int tid = threadIdx.x;
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
     for (int L = lo; L < hi; L++) {
         int n = lcount[L];
         c += n;
-        t += units_of(n, v.lists[L].seg_cnt, unit_segs);
+        t += units_of(n, v.lists[L].part_cnt, unit_parts);
     }
     sc[tid] = c;
     st[tid] = t;
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
         loff[L] = cb;
         toff[L] = tb;
         lcursor[L] = 0;
-        const int nu = units_of(n, v.lists[L].seg_cnt, unit_segs);
+        const int nu = units_of(n, v.lists[L].part_cnt, unit_parts);
         for (int u = 0; u < nu; u++) unit_list[tb + u] = L;
         cb += n;
         tb += nu;
@@ -361,10 +362,13 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         const int L = __builtin_amdgcn_readfirstlane(a.unit_list[u]);
         const ListEntry le = v.lists[L];
         const int rem = (int)u - __builtin_amdgcn_readfirstlane(a.toff[L]);
-        const int parts = (le.seg_cnt + a.unit_segs - 1) / a.unit_segs;
-        const int tile = __builtin_amdgcn_readfirstlane(rem / parts);
-        const int seg0 = __builtin_amdgcn_readfirstlane((rem % parts) * a.unit_segs);
-        const int seg1 = seg0 + a.unit_segs < le.seg_cnt ? seg0 + a.unit_segs : le.seg_cnt;
+        const int runs = (le.part_cnt + a.unit_parts - 1) / a.unit_parts;
+        const int tile = __builtin_amdgcn_readfirstlane(rem / runs);
+        const int p0 = __builtin_amdgcn_readfirstlane((rem % runs) * a.unit_parts);
+        const int p1 = p0 + a.unit_parts < le.part_cnt ? p0 + a.unit_parts : le.part_cnt;
+        // the run's segments, as offsets into the list's segment table
+        const int seg0 = __builtin_amdgcn_readfirstlane(v.parts[le.part_begin + p0]) - le.seg_begin;
+        const int seg1 = __builtin_amdgcn_readfirstlane(v.parts[le.part_begin + p1]) - le.seg_begin;
         PC_ADD(pc_decode);
         PC_MARK();
         int qid;
@@ -763,7 +767,7 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a,
 // operands from LDS (one-hot row and table row), which holds it to about half the matrix-core
 // rate; survivors, bounds and the log work exactly as in scan_mfma_kernel.
 #define LDSK_MAX_ND 16      // code dwords per lane and block: M <= 256
-#define LDSK_MAX_SEGS 8     // segments per unit
+#define LDSK_MAX_SEGS 32    // segments per unit: up to 4 parts of RAIRS_PART_SEGS segments
 __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, MfmaScanArgs a)
 {
     extern __shared__ __align__(16) unsigned char dyn_lds[];
@@ -806,10 +810,12 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
         const int L = a.unit_list[u];
         const ListEntry le = v.lists[L];
         const int rem = (int)u - a.toff[L];
-        const int parts = (le.seg_cnt + a.unit_segs - 1) / a.unit_segs;
-        const int tile = rem / parts;
-        const int seg0 = (rem % parts) * a.unit_segs;
-        const int seg1 = seg0 + a.unit_segs < le.seg_cnt ? seg0 + a.unit_segs : le.seg_cnt;
+        const int runs = (le.part_cnt + a.unit_parts - 1) / a.unit_parts;
+        const int tile = rem / runs;
+        const int p0 = (rem % runs) * a.unit_parts;
+        const int p1 = p0 + a.unit_parts < le.part_cnt ? p0 + a.unit_parts : le.part_cnt;
+        const int seg0 = v.parts[le.part_begin + p0] - le.seg_begin;
+        const int seg1 = v.parts[le.part_begin + p1] - le.seg_begin;
         const int base = a.loff[L], nql = a.loff[L + 1] - base;
         const int nseg = seg1 - seg0;                  // <= LDSK_MAX_SEGS
         if ((int)threadIdx.x < nseg) segs_s[threadIdx.x] = v.segs[le.seg_begin + seg0 + threadIdx.x];
@@ -983,7 +989,7 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
         hipLaunchKernelGGL(lm_count_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount);
     hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
-                       a.toff, a.unit_list, a.unit_segs);
+                       a.toff, a.unit_list, a.unit_parts);
     if (lds_group)
         hipLaunchKernelGGL(lm_fill_lds_kernel, dim3(lgrid), dim3(256), (size_t)v.nlist * 4, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor,
