@@ -160,6 +160,7 @@ int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t 
 // queue score <= tau.  One wave per query; the sample's scores sit in LDS and the rank is found by
 // bisection on the 16 score bits.
 #define SAMPLE_MAX_BLOCKS 128
+template <bool SMALL_ND>                                 // at most 4 code dwords per block and lane
 __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uint8_t *__restrict__ lut,
                                                           const int32_t *__restrict__ probe_ids,
                                                           int nprobe, int refine_k, int sample_blocks,
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
         nitems = le.valid_items;                        // item slots in use in the list's own blocks
     }
     uint32_t nvalid = 0;
-    if (v.nd <= 4) {
+    if (SMALL_ND) {
         // four blocks at a time with all their code dwords fetched before the first lookup
         for (int b0 = 0; b0 < cnt; b0 += 4) {
             uint32_t c[4][4];
@@ -322,9 +323,13 @@ int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int3
     if (sample_blocks > SAMPLE_MAX_BLOCKS) sample_blocks = SAMPLE_MAX_BLOCKS;
     if (sample_blocks < 1) sample_blocks = 1;
     const size_t lds = (size_t)(WG / 64) * ((size_t)v.M * 16 + (size_t)sample_blocks * 64);
-    hipLaunchKernelGGL(sample_bound_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
-                       lds, s, v, lut, probe_ids, nprobe, refine_k, sample_blocks, nq, tau, bound, bitmap, bmwords,
-                       dco);
+    const dim3 grid((unsigned)((nq + WG / 64 - 1) / (WG / 64)));
+    if (v.nd <= 4)
+        hipLaunchKernelGGL(sample_bound_kernel<true>, grid, dim3(WG), lds, s, v, lut, probe_ids, nprobe,
+                           refine_k, sample_blocks, nq, tau, bound, bitmap, bmwords, dco);
+    else
+        hipLaunchKernelGGL(sample_bound_kernel<false>, grid, dim3(WG), lds, s, v, lut, probe_ids, nprobe,
+                           refine_k, sample_blocks, nq, tau, bound, bitmap, bmwords, dco);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
