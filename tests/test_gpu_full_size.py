@@ -12,14 +12,22 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-CASES = [("sift1m", 32, 400), ("sift1m", 1, 200), ("sphere10m", 64, 150), ("gist1m", 16, 100)]
+# "sift100m@5M": the 100M x 128 uint8 workload's generator, storage (uint8 raw vectors), bigK = 200 and
+# list length (about 10,000 items per list), at 5M vectors and 1024 lists so that the case fits a
+# test run; the full size is exercised by bench.py --workload sift100m, which compares a sample of
+# queries with the oracle as well.
+CASES = [("sift1m", 32, 400), ("sift1m", 1, 200), ("sphere10m", 64, 150), ("gist1m", 16, 100),
+         ("sift100m@5M", 64, 60)]
 _cache = {}
 
 
 def _workload(name):
     if name not in _cache:
         _cache.clear()                                   # one large index in memory at a time
-        w = datagen.WORKLOADS[name]
+        if name == "sift100m@5M":
+            w = datagen.scaled(datagen.WORKLOADS["sift100m"], 5_000_000, nq=2000, nlist=1024)
+        else:
+            w = datagen.WORKLOADS[name]
         base = datagen.make_base(w)
         q = datagen.make_queries(w)
         hx = index_build.build_index(base, w.nlist, w.M, seed=w.seed)
