@@ -178,6 +178,13 @@ int rairs_set_profiling(rairs_index_t *h, int enabled);
  */
 int rairs_get_stage_ms(rairs_index_t *h, float *ms);
 
+/*
+ * The same, averaged over the last `last_n` profiled searches (1 <= last_n <= 64 and no more than
+ * were recorded since profiling was switched on): each search records into its own slot of a ring
+ * of events, so a timed loop needs no host synchronisation between its steps.
+ */
+int rairs_get_stage_ms_mean(rairs_index_t *h, int last_n, float *ms);
+
 /* Items scored per query by the last rairs_search: device [nq] int64 copied to host `dco`. */
 int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq);
 

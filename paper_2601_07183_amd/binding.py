@@ -22,6 +22,7 @@ MAX_NPROBE = 4096
 
 EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_coarse", "rairs_lut",
            "rairs_scan", "rairs_refine", "rairs_set_scan_mode", "rairs_set_profiling", "rairs_get_stage_ms",
+           "rairs_get_stage_ms_mean",
            "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_last_error")
 
 
@@ -194,6 +195,11 @@ class Index:
     def stage_ms(self) -> dict:
         ms = (C.c_float * len(STAGES))()
         _check(self._lib.rairs_get_stage_ms(self._h, ms))
+        return dict(zip(STAGES, [float(x) for x in ms]))
+
+    def stage_ms_mean(self, last_n: int) -> dict:
+        ms = (C.c_float * len(STAGES))()
+        _check(self._lib.rairs_get_stage_ms_mean(self._h, C.c_int(last_n), ms))
         return dict(zip(STAGES, [float(x) for x in ms]))
 
     def dco(self, nq: int) -> np.ndarray:

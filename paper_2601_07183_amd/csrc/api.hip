@@ -50,7 +50,13 @@ static void destroy(rairs_index *h)
     if (h->ws) (void)hipFree(h->ws);
     if (h->dco) (void)hipFree(h->dco);
     if (h->ev_ready)
-        for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) (void)hipEventDestroy(h->ev[i]);
+        for (int r = 0; r < RAIRS_EV_RING; r++)
+            for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) (void)hipEventDestroy(h->ev[r][i]);
+    if (h->side_ready) {
+        (void)hipEventDestroy(h->ev_fork); (void)hipEventDestroy(h->ev_lut);
+        (void)hipEventDestroy(h->ev_probe); (void)hipEventDestroy(h->ev_group);
+        (void)hipStreamDestroy(h->side);
+    }
     delete h;
 }
 
@@ -339,8 +345,16 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     v.idtag = idtag;
     v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask;
     v.lists = lists; v.refs = refs; v.segs = segs; v.parts = parts; v.raw = raw;
-    for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[i]));
+    for (int r = 0; r < RAIRS_EV_RING; r++)
+        for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[r][i]));
     h->ev_ready = 1;
+    // default priority, like every stream here
+    UP_HIP(hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));
+    UP_HIP(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
+    UP_HIP(hipEventCreateWithFlags(&h->ev_lut, hipEventDisableTiming));
+    UP_HIP(hipEventCreateWithFlags(&h->ev_probe, hipEventDisableTiming));
+    UP_HIP(hipEventCreateWithFlags(&h->ev_group, hipEventDisableTiming));
+    h->side_ready = 1;
     *out = h;
     return RAIRS_OK;
 }
@@ -504,13 +518,16 @@ extern "C" int rairs_lut(rairs_index_t *h, const float *d_queries, int64_t nq, u
 // ev (may be null) receives two events bracketing the dominant scan kernel.
 static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, const int32_t *probe_ids,
                      int64_t n, int nprobe, int refine_k, int64_t *cand_ids, int32_t *cand_score,
-                     int64_t *dco, hipStream_t s, hipEvent_t *ev)
+                     int64_t *dco, hipStream_t s, hipEvent_t *ev, bool overlap)
 {
+    // overlap: the tables were built on the side stream (ev_lut marks them done) and the side
+    // stream already waits for the probe lists; the grouping runs there next to the sample bound
     const IndexView &v = h->v;
     char *ws = (char *)h->ws;
     uint32_t *bitmap = (uint32_t *)(ws + w.bitmap);
     int rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, bitmap, w.bmwords, (uint32_t *)(ws + w.hist), s);
     if (rc) return rc;
+    if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, h->ev_lut, 0));
     ExactScanArgs ea;
     memset(&ea, 0, sizeof(ea));
     ea.lut = lut; ea.probe_ids = probe_ids; ea.bitmap = bitmap; ea.bmwords = w.bmwords;
@@ -561,9 +578,15 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     // about five times bigK items, so that the bigK-th smallest of them is a low quantile
     int sample_blocks = (5 * refine_k + 31) / 32;
     if (sample_blocks < RAIRS_SAMPLE_BLOCKS) sample_blocks = RAIRS_SAMPLE_BLOCKS;
+    if (overlap) {
+        if ((rc = rairs_launch_group(v, ma, h->side))) return rc;
+        RAIRS_HIP(hipEventRecord(h->ev_group, h->side));
+    }
     if ((rc = rairs_launch_sample_bound(v, lut, probe_ids, nprobe, refine_k, sample_blocks, n,
                                         (int32_t *)(ws + w.tau), ma.bound, bitmap, w.bmwords, dco, s)))
         return rc;
+    if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, h->ev_group, 0));
+    else if ((rc = rairs_launch_group(v, ma, s))) return rc;
     if ((rc = rairs_launch_scan_mfma(v, ma, s, ev))) return rc;
     if ((rc = rairs_launch_select(v, ma, s))) return rc;
     // a query with more entries at or below its final bound than the buffer holds (thousands of
@@ -593,7 +616,7 @@ extern "C" int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t 
         rc = scan_pass(h, w, d_lut + (size_t)q0 * h->v.M * 16, d_probe_ids + (size_t)q0 * nprobe, n,
                        nprobe, refine_k, d_cand_ids + (size_t)q0 * refine_k,
                        d_cand_score ? d_cand_score + (size_t)q0 * refine_k : nullptr,
-                       d_dco ? d_dco + q0 : nullptr, s, nullptr);
+                       d_dco ? d_dco + q0 : nullptr, s, nullptr, false);
         if (rc) return rc;
     }
     return RAIRS_OK;
@@ -633,26 +656,49 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
     // stage timing is only meaningful when the batch fits one pass
     const bool prof = h->prof && step == nq;
     h->prof_valid = 0;
+    hipEvent_t *ev = h->ev[h->ev_count % RAIRS_EV_RING];
+    // the table build depends only on the queries and the grouping only on the probe lists, so
+    // both run on the handle's side stream next to the coarse quantizer and the sample bound
+    const bool overlap = h->side_ready != 0;
+    hipStream_t side = overlap ? h->side : s;
     for (int64_t q0 = 0; q0 < nq; q0 += step) {
         int64_t n = nq - q0 < step ? nq - q0 : step;
         const float *q = d_queries + (size_t)q0 * v.d;
         int32_t *probe_ids = (int32_t *)(ws + w.probe_ids);
         uint8_t *lut = (uint8_t *)(ws + w.lut);
         int64_t *cand = (int64_t *)(ws + w.cand);
-        if (prof) RAIRS_HIP(hipEventRecord(h->ev[0], s));
+        if (overlap) {
+            // everything earlier on the caller's stream (the previous pass reads the same
+            // workspace) comes before the side stream's work
+            RAIRS_HIP(hipEventRecord(h->ev_fork, s));
+            RAIRS_HIP(hipStreamWaitEvent(side, h->ev_fork, 0));
+            if (prof) RAIRS_HIP(hipEventRecord(ev[2], side));
+            if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, side))) return rc;
+            if (prof) RAIRS_HIP(hipEventRecord(ev[3], side));
+            RAIRS_HIP(hipEventRecord(h->ev_lut, side));
+        }
+        if (prof) RAIRS_HIP(hipEventRecord(ev[0], s));
         if ((rc = rairs_launch_coarse(v, q, n, nprobe, (float *)(ws + w.dmat), probe_ids,
                                       (float *)(ws + w.probe_dists), (uint32_t *)(ws + w.cflags), s)))
             return rc;
-        if (prof) { RAIRS_HIP(hipEventRecord(h->ev[1], s)); RAIRS_HIP(hipEventRecord(h->ev[2], s)); }
-        if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, s))) return rc;
-        if (prof) { RAIRS_HIP(hipEventRecord(h->ev[3], s)); RAIRS_HIP(hipEventRecord(h->ev[4], s)); }
+        if (prof) RAIRS_HIP(hipEventRecord(ev[1], s));
+        if (overlap) {
+            RAIRS_HIP(hipEventRecord(h->ev_probe, s));
+            RAIRS_HIP(hipStreamWaitEvent(side, h->ev_probe, 0));
+        } else {
+            if (prof) RAIRS_HIP(hipEventRecord(ev[2], s));
+            if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, s))) return rc;
+            if (prof) RAIRS_HIP(hipEventRecord(ev[3], s));
+        }
+        if (prof) RAIRS_HIP(hipEventRecord(ev[4], s));
         if ((rc = scan_pass(h, w, lut, probe_ids, n, nprobe, refine_k, cand, nullptr, h->dco + q0, s,
-                            prof ? &h->ev[8] : nullptr))) return rc;
-        if (prof) { RAIRS_HIP(hipEventRecord(h->ev[5], s)); RAIRS_HIP(hipEventRecord(h->ev[6], s)); }
+                            prof ? &ev[8] : nullptr, overlap))) return rc;
+        if (prof) { RAIRS_HIP(hipEventRecord(ev[5], s)); RAIRS_HIP(hipEventRecord(ev[6], s)); }
         if ((rc = rairs_launch_refine(v, q, cand, n, refine_k, k, d_out_ids + (size_t)q0 * k,
                                       d_out_dists + (size_t)q0 * k, s))) return rc;
-        if (prof) RAIRS_HIP(hipEventRecord(h->ev[7], s));
+        if (prof) RAIRS_HIP(hipEventRecord(ev[7], s));
     }
+    if (prof) h->ev_count++;
     h->prof_valid = prof ? 1 : 0;
     return RAIRS_OK;
 }
@@ -670,6 +716,7 @@ extern "C" int rairs_set_profiling(rairs_index_t *h, int enabled)
     if (!h) FAIL(RAIRS_EINVAL, "handle is NULL");
     h->prof = enabled ? 1 : 0;
     h->prof_valid = 0;
+    h->ev_count = 0;
     return RAIRS_OK;
 }
 
@@ -677,10 +724,27 @@ extern "C" int rairs_get_stage_ms(rairs_index_t *h, float *ms)
 {
     if (!h || !ms) FAIL(RAIRS_EINVAL, "null argument");
     if (!h->prof_valid) FAIL(RAIRS_EINVAL, "no profiled search recorded (profiling off, or the batch took several passes)");
-    for (int i = 0; i < RAIRS_NSTAGES; i++) {
-        RAIRS_HIP(hipEventSynchronize(h->ev[2 * i + 1]));
-        RAIRS_HIP(hipEventElapsedTime(&ms[i], h->ev[2 * i], h->ev[2 * i + 1]));
+    return rairs_get_stage_ms_mean(h, 1, ms);
+}
+
+extern "C" int rairs_get_stage_ms_mean(rairs_index_t *h, int last_n, float *ms)
+{
+    if (!h || !ms) FAIL(RAIRS_EINVAL, "null argument");
+    if (!h->prof_valid || h->ev_count == 0)
+        FAIL(RAIRS_EINVAL, "no profiled search recorded (profiling off, or the batch took several passes)");
+    if (last_n < 1 || last_n > RAIRS_EV_RING) FAIL(RAIRS_EINVAL, "last_n must be in [1, %d]", RAIRS_EV_RING);
+    if ((int64_t)last_n > h->ev_count) FAIL(RAIRS_EINVAL, "only %lld profiled searches recorded", (long long)h->ev_count);
+    double sum[RAIRS_NSTAGES] = {0};
+    for (int64_t c = h->ev_count - last_n; c < h->ev_count; c++) {
+        hipEvent_t *ev = h->ev[c % RAIRS_EV_RING];
+        for (int i = 0; i < RAIRS_NSTAGES; i++) {
+            float t;
+            RAIRS_HIP(hipEventSynchronize(ev[2 * i + 1]));
+            RAIRS_HIP(hipEventElapsedTime(&t, ev[2 * i], ev[2 * i + 1]));
+            sum[i] += t;
+        }
     }
+    for (int i = 0; i < RAIRS_NSTAGES; i++) ms[i] = (float)(sum[i] / last_n);
     return RAIRS_OK;
 }
 

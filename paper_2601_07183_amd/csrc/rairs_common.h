@@ -8,6 +8,7 @@
 #define RAIRS_EMPTY_ID 0xFFFFFFFFu
 #define RAIRS_MAX_NLIST 65536
 #define RAIRS_HIST_BINS 64
+#define RAIRS_EV_RING 64
 
 // One list of the SEIL directory (Section 5.1): its own blocks are contiguous,
 // [blk_begin, blk_begin + shared_cnt) shared-cell blocks then misc_cnt miscellaneous blocks.
@@ -92,8 +93,15 @@ struct rairs_index {
     size_t last_flags_off, last_cnt_off, last_prof_off;
     int prof, prof_valid;
     float stage_ms[RAIRS_NSTAGES];
-    hipEvent_t ev[2 * RAIRS_NSTAGES];
+    // stage events of the last RAIRS_EV_RING profiled searches (slot = search number mod ring)
+    hipEvent_t ev[RAIRS_EV_RING][2 * RAIRS_NSTAGES];
     int ev_ready;
+    int64_t ev_count;             // profiled single-pass searches recorded so far
+    // a second stream for the steps that do not depend on each other (tables next to the coarse
+    // quantizer, grouping next to the sample bound), forked from and joined to the caller's stream
+    hipStream_t side;
+    hipEvent_t ev_fork, ev_lut, ev_probe, ev_group;
+    int side_ready;
 };
 
 void rairs_set_error(const char *fmt, ...);
@@ -172,6 +180,8 @@ struct MfmaScanArgs {
     int32_t *cand_score;          // may be null
 };
 bool rairs_mfma_supported(const IndexView &v);
+// grouping of the (query, probed list) pairs by list and the unit table, then the scan itself
+int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
 int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev);
 int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
 int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,

@@ -952,33 +952,39 @@ bool rairs_mfma_supported(const IndexView &v)
     return v.T >= 1 && v.nd * 8 * 64 * 16 <= 128 * 1024;    // tables of a tile must fit 128 KB of LDS
 }
 
-int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev)
+// persistent grids: 256 compute units x 2 workgroups of 4 waves with the tables in registers; one
+// workgroup per compute unit, with as many waves as LDS leaves room for, with the tables in LDS
+static void scan_launch_shape(const IndexView &v, bool *reg_tables, unsigned *grid, int *lds_waves,
+                              size_t *table_bytes)
+{
+    *reg_tables = v.T == 8 || v.T == 24 || v.T == 32;
+    *grid = *reg_tables ? 512u : 256u;
+    *table_bytes = (size_t)v.nd * 8 * 64 * 16;
+    int w = 16;
+    while (w > 4 && *table_bytes + (size_t)w * sizeof(StageQueue) > 158 * 1024) w >>= 1;
+    *lds_waves = w;
+}
+
+int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
 {
     const int np = a.nprobe - a.p_first;
     if (np <= 0) return RAIRS_OK;
-    if (a.surv_cap > SURV_CAP_MAX) {
-        rairs_set_error("survivor capacity %d above %d", a.surv_cap, SURV_CAP_MAX);
+    bool reg_tables;
+    unsigned gridx;
+    int lds_waves;
+    size_t table_bytes;
+    scan_launch_shape(v, &reg_tables, &gridx, &lds_waves, &table_bytes);
+    const uint32_t nwaves = gridx * (reg_tables ? WG / 64 : lds_waves);
+    if (a.log_chunks < (int)(2 * nwaves)) {
+        rairs_set_error("survivor log of %d chunks is below %u", a.log_chunks, 2 * nwaves);
         return RAIRS_EINVAL;
     }
     const int64_t pairs = a.nq * np;
     int64_t nz = v.nlist > a.nq ? v.nlist : a.nq;
     nz = nz > a.log_chunks ? nz : a.log_chunks;
-    // persistent grid: 256 compute units x 2 workgroups of 4 waves, or one when the tables are in LDS
-    const bool reg_tables = v.T == 8 || v.T == 24 || v.T == 32;
-    const dim3 grid(reg_tables ? 512 : 256);
-    // tables in LDS: one workgroup per compute unit with as many waves as LDS leaves room for
-    const size_t table_bytes = (size_t)v.nd * 8 * 64 * 16;
-    int lds_waves = 16;
-    while (lds_waves > 4 && table_bytes + (size_t)lds_waves * sizeof(StageQueue) > 158 * 1024) lds_waves >>= 1;
-    const uint32_t nwaves = grid.x * (reg_tables ? WG / 64 : lds_waves);
-    if (a.log_chunks < (int)(2 * nwaves)) {
-        rairs_set_error("survivor log of %d chunks is below %u", a.log_chunks, 2 * nwaves);
-        return RAIRS_EINVAL;
-    }
     hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
                        v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
-                       a.log_cursor, a.log_overflow, reg_tables ? nwaves : grid.x,
-                       2 * nwaves);
+                       a.log_cursor, a.log_overflow, reg_tables ? nwaves : gridx, 2 * nwaves);
     const bool lds_group = v.nlist <= LM_LDS_NLIST;
     const int qb = LM_PAIRS / np > 0 ? LM_PAIRS / np : 1;
     const unsigned lgrid = (unsigned)((a.nq + qb - 1) / qb);
@@ -997,6 +1003,23 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     else
         hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev)
+{
+    if (a.nprobe - a.p_first <= 0) return RAIRS_OK;
+    if (a.surv_cap > SURV_CAP_MAX) {
+        rairs_set_error("survivor capacity %d above %d", a.surv_cap, SURV_CAP_MAX);
+        return RAIRS_EINVAL;
+    }
+    bool reg_tables;
+    unsigned gridx;
+    int lds_waves;
+    size_t table_bytes;
+    scan_launch_shape(v, &reg_tables, &gridx, &lds_waves, &table_bytes);
+    const dim3 grid(gridx);
     if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
     switch (v.T) {
     case 8: hipLaunchKernelGGL(scan_mfma_kernel<8>, grid, dim3(WG), 0, s, v, a); break;
