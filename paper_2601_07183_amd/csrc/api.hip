@@ -513,12 +513,18 @@ extern "C" int rairs_lut(rairs_index_t *h, const float *d_queries, int64_t nq, u
     return rairs_launch_lut(h->v, d_queries, nq, d_lut, d_bias_sum, d_scale, (hipStream_t)hip_stream);
 }
 
+// Slots of one search's stage events (rairs_index::ev[slot]): stage boundaries on the caller's
+// stream, the table build on the side stream, the scan kernel itself.
+enum { EV_START = 0, EV_PROBED = 1, EV_LUT0 = 2, EV_LUT1 = 3, EV_SCANNED = 4, EV_END = 5,
+       EV_KERNEL0 = 6, EV_KERNEL1 = 7 };
+static_assert(EV_KERNEL1 < 2 * RAIRS_NSTAGES, "event slots");
+
 // SeilSearch for one pass of n queries: bitmap, then either the exact kernel alone or
-// first list exact -> list-major MFMA scan of the other lists -> select -> exact redo of overflows.
+// sample bound -> list-major MFMA scan -> collect / select -> exact redo of overflows.
 // ev (may be null) receives two events bracketing the dominant scan kernel.
 static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, const int32_t *probe_ids,
                      int64_t n, int nprobe, int refine_k, int64_t *cand_ids, int32_t *cand_score,
-                     int64_t *dco, hipStream_t s, hipEvent_t *ev, bool overlap)
+                     int64_t *dco, hipStream_t s, hipEvent_t *ev, bool overlap, hipEvent_t lut_done)
 {
     // overlap: the tables were built on the side stream (ev_lut marks them done) and the side
     // stream already waits for the probe lists; the grouping runs there next to the sample bound
@@ -527,7 +533,7 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     uint32_t *bitmap = (uint32_t *)(ws + w.bitmap);
     int rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, bitmap, w.bmwords, (uint32_t *)(ws + w.hist), s);
     if (rc) return rc;
-    if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, h->ev_lut, 0));
+    if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, lut_done, 0));
     ExactScanArgs ea;
     memset(&ea, 0, sizeof(ea));
     ea.lut = lut; ea.probe_ids = probe_ids; ea.bitmap = bitmap; ea.bmwords = w.bmwords;
@@ -616,7 +622,7 @@ extern "C" int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t 
         rc = scan_pass(h, w, d_lut + (size_t)q0 * h->v.M * 16, d_probe_ids + (size_t)q0 * nprobe, n,
                        nprobe, refine_k, d_cand_ids + (size_t)q0 * refine_k,
                        d_cand_score ? d_cand_score + (size_t)q0 * refine_k : nullptr,
-                       d_dco ? d_dco + q0 : nullptr, s, nullptr, false);
+                       d_dco ? d_dco + q0 : nullptr, s, nullptr, false, nullptr);
         if (rc) return rc;
     }
     return RAIRS_OK;
@@ -667,36 +673,38 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
         int32_t *probe_ids = (int32_t *)(ws + w.probe_ids);
         uint8_t *lut = (uint8_t *)(ws + w.lut);
         int64_t *cand = (int64_t *)(ws + w.cand);
+        // Every event recorded on a stream delays the kernel behind it by some microseconds, so a
+        // stage boundary is one event: it ends a stage, starts the next and, where the side stream
+        // has to wait for that point, is the event it waits on (see EV_* above).
+        hipEvent_t start = prof ? ev[EV_START] : h->ev_fork;
+        if (overlap || prof) RAIRS_HIP(hipEventRecord(start, s));
         if (overlap) {
             // everything earlier on the caller's stream (the previous pass reads the same
             // workspace) comes before the side stream's work
-            RAIRS_HIP(hipEventRecord(h->ev_fork, s));
-            RAIRS_HIP(hipStreamWaitEvent(side, h->ev_fork, 0));
-            if (prof) RAIRS_HIP(hipEventRecord(ev[2], side));
+            RAIRS_HIP(hipStreamWaitEvent(side, start, 0));
+            if (prof) RAIRS_HIP(hipEventRecord(ev[EV_LUT0], side));
             if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, side))) return rc;
-            if (prof) RAIRS_HIP(hipEventRecord(ev[3], side));
-            RAIRS_HIP(hipEventRecord(h->ev_lut, side));
+            RAIRS_HIP(hipEventRecord(prof ? ev[EV_LUT1] : h->ev_lut, side));
         }
-        if (prof) RAIRS_HIP(hipEventRecord(ev[0], s));
         if ((rc = rairs_launch_coarse(v, q, n, nprobe, (float *)(ws + w.dmat), probe_ids,
                                       (float *)(ws + w.probe_dists), (uint32_t *)(ws + w.cflags), s)))
             return rc;
-        if (prof) RAIRS_HIP(hipEventRecord(ev[1], s));
+        hipEvent_t probed = prof ? ev[EV_PROBED] : h->ev_probe;
+        if (overlap || prof) RAIRS_HIP(hipEventRecord(probed, s));
         if (overlap) {
-            RAIRS_HIP(hipEventRecord(h->ev_probe, s));
-            RAIRS_HIP(hipStreamWaitEvent(side, h->ev_probe, 0));
+            RAIRS_HIP(hipStreamWaitEvent(side, probed, 0));
         } else {
-            if (prof) RAIRS_HIP(hipEventRecord(ev[2], s));
+            // one stream: the table build is timed between the coarse stage and the scan stage
             if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, s))) return rc;
-            if (prof) RAIRS_HIP(hipEventRecord(ev[3], s));
+            if (prof) RAIRS_HIP(hipEventRecord(ev[EV_LUT1], s));
         }
-        if (prof) RAIRS_HIP(hipEventRecord(ev[4], s));
         if ((rc = scan_pass(h, w, lut, probe_ids, n, nprobe, refine_k, cand, nullptr, h->dco + q0, s,
-                            prof ? &ev[8] : nullptr, overlap))) return rc;
-        if (prof) { RAIRS_HIP(hipEventRecord(ev[5], s)); RAIRS_HIP(hipEventRecord(ev[6], s)); }
+                            prof ? &ev[EV_KERNEL0] : nullptr, overlap,
+                            prof ? ev[EV_LUT1] : h->ev_lut))) return rc;
+        if (prof) RAIRS_HIP(hipEventRecord(ev[EV_SCANNED], s));
         if ((rc = rairs_launch_refine(v, q, cand, n, refine_k, k, d_out_ids + (size_t)q0 * k,
                                       d_out_dists + (size_t)q0 * k, s))) return rc;
-        if (prof) RAIRS_HIP(hipEventRecord(ev[7], s));
+        if (prof) RAIRS_HIP(hipEventRecord(ev[EV_END], s));
     }
     if (prof) h->ev_count++;
     h->prof_valid = prof ? 1 : 0;
@@ -737,10 +745,16 @@ extern "C" int rairs_get_stage_ms_mean(rairs_index_t *h, int last_n, float *ms)
     double sum[RAIRS_NSTAGES] = {0};
     for (int64_t c = h->ev_count - last_n; c < h->ev_count; c++) {
         hipEvent_t *ev = h->ev[c % RAIRS_EV_RING];
+        const bool one_stream = !h->side_ready;
+        const int pair[RAIRS_NSTAGES][2] = {{EV_START, EV_PROBED},
+                                            {one_stream ? EV_PROBED : EV_LUT0, EV_LUT1},
+                                            {one_stream ? EV_LUT1 : EV_PROBED, EV_SCANNED},
+                                            {EV_SCANNED, EV_END},
+                                            {EV_KERNEL0, EV_KERNEL1}};
         for (int i = 0; i < RAIRS_NSTAGES; i++) {
             float t;
-            RAIRS_HIP(hipEventSynchronize(ev[2 * i + 1]));
-            RAIRS_HIP(hipEventElapsedTime(&t, ev[2 * i], ev[2 * i + 1]));
+            RAIRS_HIP(hipEventSynchronize(ev[pair[i][1]]));
+            RAIRS_HIP(hipEventElapsedTime(&t, ev[pair[i][0]], ev[pair[i][1]]));
             sum[i] += t;
         }
     }

@@ -79,6 +79,9 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
                                                          int unit_parts)
 {
     __shared__ int sc[1024], st[1024];
+    // one workgroup on the critical path of the grouping, usually next to a kernel that fills the
+    // chip: let its waves issue first on the compute unit they share
+    __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x;
     const int per = (v.nlist + 1023) / 1024;
     const int lo = tid * per < v.nlist ? tid * per : v.nlist;
