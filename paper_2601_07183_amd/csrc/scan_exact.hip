@@ -160,7 +160,23 @@ int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t 
 // queue score <= tau.  One wave per query; the sample's scores sit in LDS and the rank is found by
 // bisection on the 16 score bits.
 #define SAMPLE_MAX_BLOCKS 128
-template <bool SMALL_ND>                                 // at most 4 code dwords per block and lane
+// Scores of one block for this lane: `part` sums the table entries of the lane's half of the
+// sub-quantizer pairs; ND code dwords with 8 four-bit codes each.  No branch per lookup, so the
+// LDS reads of a block are all in flight together.
+template <int ND>
+static __device__ __forceinline__ uint32_t sample_block_part(const uint8_t *lq, const uint32_t (&c)[ND], int g)
+{
+    uint32_t part = 0;
+#pragma unroll
+    for (int w = 0; w < ND; w++)
+#pragma unroll
+        for (int n = 0; n < 8; n++) part += lq[(2 * (8 * w + n) + g) * 16 + ((c[w] >> (4 * n)) & 15u)];
+    return part;
+}
+
+// ND > 0: exactly ND code dwords per block and lane (T = 8 ND), blocks taken 4 or 2 at a time with
+// all their dwords fetched before the first lookup.  ND == 0: any T, dwords in groups of four.
+template <int ND>
 __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uint8_t *__restrict__ lut,
                                                           const int32_t *__restrict__ probe_ids,
                                                           int nprobe, int refine_k, int sample_blocks,
@@ -193,81 +209,75 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
         nitems = le.valid_items;                        // item slots in use in the list's own blocks
     }
     uint32_t nvalid = 0;
-    if (SMALL_ND) {
-        // four blocks at a time with all their code dwords fetched before the first lookup
-        for (int b0 = 0; b0 < cnt; b0 += 4) {
-            uint32_t c[4][4];
+    // only the tail of a list's last block can be empty: slot s is in use iff s < valid_items
+#define SAMPLE_STORE(blk_, part_)                                                              \
+    do {                                                                                       \
+        const uint32_t acc_ = (part_) + (uint32_t)__shfl_xor((int)(part_), 32);                \
+        const bool valid_ = lane < 32 && (blk_) < cnt && (blk_) * 32 + lane < nitems;          \
+        if (lane < 32 && (blk_) < cnt) sc[(blk_) * 32 + lane] = valid_ ? (uint16_t)acc_ : (uint16_t)0xFFFFu; \
+        nvalid += (uint32_t)__popcll(__ballot(valid_));                                        \
+    } while (0)
+    if (ND > 0) {
+        constexpr int NDS = ND > 0 ? ND : 1, U = NDS <= 4 ? 4 : 2;
+        for (int b0 = 0; b0 < cnt; b0 += U) {
+            uint32_t c[U][NDS];
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
+            for (int u = 0; u < U; u++) {
                 const int64_t blk = begin + (b0 + u < cnt ? b0 + u : cnt - 1);
-                const uint32_t *cp = v.codes + (size_t)blk * v.nd * 64 + lane;
+                const uint32_t *cp = v.codes + (size_t)blk * NDS * 64 + lane;
 #pragma unroll
-                for (int w = 0; w < 4; w++) c[u][w] = cp[(size_t)(w < v.nd ? w : 0) * 64];
+                for (int w = 0; w < NDS; w++) c[u][w] = cp[w * 64];
             }
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
-                uint32_t part = 0;
-#pragma unroll
-                for (int w = 0; w < 4; w++) {
-                    if (w < v.nd) {
-                        const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
-                        for (int n = 0; n < tmax; n++) {
-                            const int m = 2 * (8 * w + n) + g;
-                            part += lq[m * 16 + ((c[u][w] >> (4 * n)) & 15u)];
-                        }
-                    }
-                }
-                const uint32_t acc = part + (uint32_t)__shfl_xor((int)part, 32);
-                // only the tail of a list's last block can be empty: slot s is in use iff s < valid_items
-                const bool valid = lane < 32 && b0 + u < cnt && (b0 + u) * 32 + lane < nitems;
-                if (lane < 32 && b0 + u < cnt) sc[(b0 + u) * 32 + lane] = valid ? (uint16_t)acc : (uint16_t)0xFFFFu;
-                nvalid += (uint32_t)__popcll(__ballot(valid));
+            for (int u = 0; u < U; u++) {
+                const uint32_t part = sample_block_part<NDS>(lq, c[u], g);
+                SAMPLE_STORE(b0 + u, part);
             }
         }
     } else {
-        // up to 16 code dwords per block: two blocks at a time, all dwords fetched before the lookups
-        for (int b0 = 0; b0 < cnt; b0 += 2) {
-            uint32_t c[2][16];
+        for (int b = 0; b < cnt; b++) {
+            const uint32_t *cp = v.codes + (size_t)(begin + b) * v.nd * 64 + lane;
+            uint32_t part = 0;
+            for (int w0 = 0; w0 < v.nd; w0 += 4) {
+                uint32_t c[4];
 #pragma unroll
-            for (int u = 0; u < 2; u++) {
-                const int64_t blk = begin + (b0 + u < cnt ? b0 + u : cnt - 1);
-                const uint32_t *cp = v.codes + (size_t)blk * v.nd * 64 + lane;
+                for (int w = 0; w < 4; w++) c[w] = cp[(size_t)(w0 + w < v.nd ? w0 + w : v.nd - 1) * 64];
 #pragma unroll
-                for (int w = 0; w < 16; w++) c[u][w] = cp[(size_t)(w < v.nd ? w : 0) * 64];
-            }
+                for (int w = 0; w < 4; w++) {
+                    const int t0 = 8 * (w0 + w);            // first code pair of this dword
+                    if (t0 + 8 <= v.T) {                    // uniform: a full dword
 #pragma unroll
-            for (int u = 0; u < 2; u++) {
-                uint32_t part = 0;
-#pragma unroll
-                for (int w = 0; w < 16; w++) {
-                    if (w < v.nd) {
-                        const int tmax = v.T - 8 * w < 8 ? v.T - 8 * w : 8;
-                        for (int n = 0; n < tmax; n++) {
-                            const int m = 2 * (8 * w + n) + g;
-                            part += lq[m * 16 + ((c[u][w] >> (4 * n)) & 15u)];
-                        }
+                        for (int n = 0; n < 8; n++)
+                            part += lq[(2 * (t0 + n) + g) * 16 + ((c[w] >> (4 * n)) & 15u)];
+                    } else {
+                        for (int n = 0; t0 + n < v.T; n++)
+                            part += lq[(2 * (t0 + n) + g) * 16 + ((c[w] >> (4 * n)) & 15u)];
                     }
                 }
-                const uint32_t acc = part + (uint32_t)__shfl_xor((int)part, 32);
-                const bool valid = lane < 32 && b0 + u < cnt && (b0 + u) * 32 + lane < nitems;
-                if (lane < 32 && b0 + u < cnt) sc[(b0 + u) * 32 + lane] = valid ? (uint16_t)acc : (uint16_t)0xFFFFu;
-                nvalid += (uint32_t)__popcll(__ballot(valid));
             }
+            SAMPLE_STORE(b, part);
         }
     }
+#undef SAMPLE_STORE
     __syncthreads();
     uint32_t t = 0xFFFFu;
     if (nvalid >= (uint32_t)refine_k) {
         // largest t with fewer than bigK scores below it == the bigK-th smallest score
         // (empty slots hold 0xFFFF, which no candidate t exceeds)
+        // The first 512 scores stay in registers; counting is a ballot and a scalar population
+        // count per 64 scores, so no lane waits for another.
         const int n = cnt * 32;
+        uint32_t mine[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) mine[u] = lane + 64 * u < n ? (uint32_t)sc[lane + 64 * u] : 0xFFFFu;
         t = 0;
         for (int bit = 15; bit >= 0; bit--) {
             const uint32_t cand = t | (1u << bit);
-            uint32_t below = 0;
-            for (int e = lane; e < n; e += 64) below += sc[e] < cand ? 1u : 0u;
+            uint32_t below = 0;                          // wave-uniform
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) below += (uint32_t)__shfl_xor((int)below, off);
+            for (int u = 0; u < 8; u++) below += (uint32_t)__popcll(__ballot(mine[u] < cand));
+            for (int e0 = 512; e0 < n; e0 += 64)
+                below += (uint32_t)__popcll(__ballot(e0 + lane < n && sc[e0 + lane] < cand));
             if (below < (uint32_t)refine_k) t = cand;
         }
     }
@@ -324,12 +334,20 @@ int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int3
     if (sample_blocks < 1) sample_blocks = 1;
     const size_t lds = (size_t)(WG / 64) * ((size_t)v.M * 16 + (size_t)sample_blocks * 64);
     const dim3 grid((unsigned)((nq + WG / 64 - 1) / (WG / 64)));
-    if (v.nd <= 4)
-        hipLaunchKernelGGL(sample_bound_kernel<true>, grid, dim3(WG), lds, s, v, lut, probe_ids, nprobe,
-                           refine_k, sample_blocks, nq, tau, bound, bitmap, bmwords, dco);
-    else
-        hipLaunchKernelGGL(sample_bound_kernel<false>, grid, dim3(WG), lds, s, v, lut, probe_ids, nprobe,
-                           refine_k, sample_blocks, nq, tau, bound, bitmap, bmwords, dco);
+#define SAMPLE_LAUNCH(ND_)                                                                        \
+    hipLaunchKernelGGL(sample_bound_kernel<ND_>, grid, dim3(WG), lds, s, v, lut, probe_ids, nprobe, \
+                       refine_k, sample_blocks, nq, tau, bound, bitmap, bmwords, dco)
+    const int nd = v.T % 8 == 0 ? v.nd : 0;
+    switch (nd) {
+    case 1: SAMPLE_LAUNCH(1); break;
+    case 2: SAMPLE_LAUNCH(2); break;
+    case 3: SAMPLE_LAUNCH(3); break;
+    case 4: SAMPLE_LAUNCH(4); break;
+    case 6: SAMPLE_LAUNCH(6); break;
+    case 8: SAMPLE_LAUNCH(8); break;
+    default: SAMPLE_LAUNCH(0); break;
+    }
+#undef SAMPLE_LAUNCH
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
