@@ -33,6 +33,7 @@
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 
 #define SURV_CAP_MAX 4096   // survivor buffer entries per query (select_kernel sorts them in LDS)
 
@@ -305,31 +306,58 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
     lc.used += (uint32_t)n;
 }
 
+// Bit r of the result: acc[r] <= th.  Built in three groups whose bit values are all inline
+// constants (1 .. 64) and joined by shifts, so that no register has to hold a larger power of two
+// through the scan loop.
+static __device__ __forceinline__ uint32_t passing_rows(const v16i &acc, int th)
+{
+    uint32_t p0 = 0, p1 = 0, p2 = 0;
+#pragma unroll
+    for (int r = 0; r < 7; r++) p0 |= acc[r] <= th ? (1u << r) : 0u;
+#pragma unroll
+    for (int r = 7; r < 14; r++) p1 |= acc[r] <= th ? (1u << (r - 7)) : 0u;
+#pragma unroll
+    for (int r = 14; r < 16; r++) p2 |= acc[r] <= th ? (1u << (r - 14)) : 0u;
+    asm volatile("" : "+v"(p1), "+v"(p2));             // keep the compiler from folding the shifts back in
+    return p0 | (p1 << 7) | (p2 << 14);
+}
+
+// Number of set bits of `mask` below this lane.
+static __device__ __forceinline__ int lanes_below(unsigned long long mask)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
 template <int T>
 __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanArgs a)
 {
     constexpr int ND = (T + 7) / 8;
     constexpr int M = 2 * T;
+    constexpr int TS = T / 2;                          // sparse matrix instructions per block
+    static_assert(T % 2 == 0, "a sparse instruction takes four sub-quantizers");
     __shared__ StageQueue stage[WG / 64];
-    __shared__ v4i onehot[16];                         // onehot[c]: 16 bytes, byte c = 1
+    // A code byte holds the codes (c1, c2) of two sub-quantizers of one instruction; their one-hot
+    // rows of 16 + 16 zeros and ones are 2:4 sparse, so the matrix core takes them compressed:
+    // per group of four positions two kept values and their 2-bit positions.  Entry of a code c:
+    // its 8 kept values (a one in the first slot of group c >> 2) and its 8 positions (c & 3 in
+    // that slot), the latter once as the low and once as the high half of the position word.
+    // Sixteen entries of 16 bytes: lanes reading the same entry share one access, different
+    // entries sit in different banks.
+    __shared__ uint4 sparse_tab[16];
     if (threadIdx.x < 16) {
-        v4i r = {0, 0, 0, 0};
-        const int sh = 1 << ((threadIdx.x & 3) * 8);
-        if ((threadIdx.x >> 2) == 0) r.x = sh;
-        if ((threadIdx.x >> 2) == 1) r.y = sh;
-        if ((threadIdx.x >> 2) == 2) r.z = sh;
-        if ((threadIdx.x >> 2) == 3) r.w = sh;
-        onehot[threadIdx.x] = r;
+        const int c = threadIdx.x;
+        const unsigned long long val = 1ull << (16 * (c >> 2));
+        const uint32_t pos = (uint32_t)(c & 3) << (4 * (c >> 2));
+        sparse_tab[c] = make_uint4((uint32_t)val, (uint32_t)(val >> 32), pos, pos << 16);
     }
     __syncthreads();
     const int lane = threadIdx.x & 63, g = lane >> 5, j = lane & 31;
     StageQueue &sq = stage[threadIdx.x >> 6];
     const int bias = 128 * M;
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
-    v4i B[T];
+    v8i B[TS];
 #pragma unroll
-    for (int t = 0; t < T; t++) B[t] = (v4i){0, 0, 0, 0};
+    for (int t = 0; t < TS; t++) B[t] = (v8i){0, 0, 0, 0, 0, 0, 0, 0};
     int nstaged = 0;                                   // wave-uniform fill of the stage queue
     const uint32_t nunits = (uint32_t)a.toff[v.nlist];
     if (nunits == 0u) return;                          // nothing was written: all chunk fills stay 0
@@ -382,18 +410,22 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
             const int qi = tile * 32 + j;
             qid = qi < n ? a.qlist[base + qi] : -1;
             hmul = hist_mul(qid >= 0 ? (uint32_t)a.tau[qid] : 0u);
-            const uint8_t *lq = a.lut + (size_t)(qid >= 0 ? qid : 0) * (M * 16) + g * 16;
+            // instruction t takes sub-quantizers 4t .. 4t+3; this lane's half of its 64 positions
+            // is the 16 + 16 table entries of sub-quantizers 4t + 2g and 4t + 2g + 1
+            const uint8_t *lq = a.lut + (size_t)(qid >= 0 ? qid : 0) * (M * 16) + g * 32;
             // every lane loads (an absent column reads query 0's rows and masks them to zero): a
             // conditional load would be waited for one by one
             const int keep = qid >= 0 ? -1 : 0;
+            const v4i flip = {(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
+            const v4i keep4 = {keep, keep, keep, keep};
 #pragma unroll
-            for (int t = 0; t < T; t++) {
-                v4i x = *(const v4i *)(lq + t * 32);
-                x ^= (v4i){(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
-                B[t] = x & (v4i){keep, keep, keep, keep};
+            for (int t = 0; t < TS; t++) {
+                const v4i x = (*(const v4i *)(lq + t * 64) ^ flip) & keep4;
+                const v4i y = (*(const v4i *)(lq + t * 64 + 16) ^ flip) & keep4;
+                B[t] = (v8i){x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
             }
 #ifdef RAIRS_PROFILE_CYCLES
-            { int sink = B[0].x ^ B[T - 1].w; asm volatile("" :: "v"(sink)); pc_ntile++; }
+            { int sink = B[0][0] ^ B[TS - 1][7]; asm volatile("" :: "v"(sink)); pc_ntile++; }
 #endif
         }
         PC_ADD(pc_tile);
@@ -450,15 +482,38 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                     v16i acc;
 #pragma unroll
                     for (int r = 0; r < 16; r++) acc[r] = 0;
+                    // The table reads of an instruction (values, positions) go out two
+                    // instructions ahead of it, so that an LDS round trip hides behind matrix
+                    // work; the scheduling fences keep the compiler from moving them either way
+                    // (all at the front costs 80 registers, none ahead stalls every instruction).
+#define CODE_LO(t_) ((c[(t_) >> 2] >> (8 * ((t_) & 3))) & 15u)
+#define CODE_HI(t_) ((c[(t_) >> 2] >> (8 * ((t_) & 3) + 4)) & 15u)
+#define LOAD_A(t_)                                                                        \
+    do {                                                                                  \
+        const uint32_t *e1_ = (const uint32_t *)&sparse_tab[CODE_LO(t_)];                 \
+        const uint32_t *e2_ = (const uint32_t *)&sparse_tab[CODE_HI(t_)];                 \
+        v1[t_] = *(const uint2 *)e1_; v2[t_] = *(const uint2 *)e2_;                       \
+        p1[t_] = e1_[2]; p2[t_] = e2_[3];                                                 \
+    } while (0)
+                    // raw table words; they are put together where they are used, not where
+                    // they are loaded, so that nothing waits for a load in its own stage
+                    uint2 v1[TS], v2[TS];
+                    uint32_t p1[TS], p2[TS];
+                    LOAD_A(0);
+                    if (TS > 1) LOAD_A(1);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int t = 0; t < T; t++) {
-                        const uint32_t nib = (c[t >> 3] >> (4 * (t & 7))) & 15u;
-                        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(onehot[nib], B[t], acc, 0, 0, 0);
+                    for (int t = 0; t < TS; t++) {
+                        const v4i av = {(int)v1[t].x, (int)v1[t].y, (int)v2[t].x, (int)v2[t].y};
+                        acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, B[t], acc, (int)(p1[t] | p2[t]), 0, 0);
+                        if (t + 2 < TS) LOAD_A(t + 2);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
+#undef LOAD_A
+#undef CODE_LO
+#undef CODE_HI
                     // acc[r]: item row 8*(r/4) + 4*g + (r%4), query column j
-                    uint32_t pm = 0;                   // rows of this lane that pass
-#pragma unroll
-                    for (int r = 0; r < 16; r++) pm |= acc[r] <= th ? (1u << r) : 0u;
+                    uint32_t pm = passing_rows(acc, th);  // rows of this lane that pass
                     PC_ADD(pc_blocks);
 #ifdef RAIRS_PROFILE_CYCLES
                     pc_nblk++;
@@ -490,7 +545,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                                 for (int k = 0; k < 4; k++) s4[k] = (r & 2) ? s8[2 * k + 1] : s8[2 * k];
                                 const int s2a = (r & 4) ? s4[1] : s4[0], s2b = (r & 4) ? s4[3] : s4[2];
                                 const int sc = (r & 8) ? s2b : s2a;
-                                const int pos = nstaged + __popcll(mask & lt_mask);
+                                const int pos = nstaged + lanes_below(mask);
                                 const uint32_t item = 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);   // + 4 g
                                 sq.slot[pos] = slot0 + item;
                                 sq.score_list[pos] = ((uint32_t)(sc + bias) << 16) | (uint32_t)L;
@@ -794,7 +849,6 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
     StageQueue &sq = stage[wave];
     const int M = v.M, T = v.T;
     const int bias = 128 * M;
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int nstaged = 0;
     uint32_t nflush = 0;
     const uint32_t nunits = (uint32_t)a.toff[v.nlist];
@@ -897,9 +951,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
                         }
                     }
                 }
-                uint32_t pm = 0;
-#pragma unroll
-                for (int r = 0; r < 16; r++) pm |= acc[r] <= th ? (1u << r) : 0u;
+                uint32_t pm = passing_rows(acc, th);
                 if (__ballot(pm != 0u) != 0ull) {
                     const uint32_t slot0 = (uint32_t)cur.blk * 32u + 4u * g;
                     const int tail_valid = segs_s[cur.seg].tail_valid;
@@ -922,7 +974,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
                             for (int k = 0; k < 4; k++) s4[k] = (r & 2) ? s8[2 * k + 1] : s8[2 * k];
                             const int s2a = (r & 4) ? s4[1] : s4[0], s2b = (r & 4) ? s4[3] : s4[2];
                             const int sc = (r & 8) ? s2b : s2a;
-                            const int pos = nstaged + __popcll(mask & lt_mask);
+                            const int pos = nstaged + lanes_below(mask);
                             const uint32_t item = 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);   // + 4 g
                             sq.slot[pos] = slot0 + item;
                             sq.score_list[pos] = ((uint32_t)(sc + bias) << 16) | (uint32_t)L;
