@@ -328,6 +328,20 @@ static __device__ __forceinline__ int lanes_below(unsigned long long mask)
     return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// acc[r] for a row index that differs from lane to lane: four levels of bitwise selection on the
+// bits of r, in registers (an indexed array would go through memory).
+static __device__ __forceinline__ int select_row(const v16i &acc, int r)
+{
+    const int m0 = -(r & 1), m1 = -((r >> 1) & 1), m2 = -((r >> 2) & 1), m3 = -((r >> 3) & 1);
+    int s8[8], s4[4];
+#pragma unroll
+    for (int k = 0; k < 8; k++) s8[k] = (acc[2 * k + 1] & m0) | (acc[2 * k] & ~m0);
+#pragma unroll
+    for (int k = 0; k < 4; k++) s4[k] = (s8[2 * k + 1] & m1) | (s8[2 * k] & ~m1);
+    const int s2a = (s4[1] & m2) | (s4[0] & ~m2), s2b = (s4[3] & m2) | (s4[2] & ~m2);
+    return (s2b & m3) | (s2a & ~m3);
+}
+
 template <int T>
 __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanArgs a)
 {
@@ -534,17 +548,11 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                             const bool has = pm != 0u;
                             const unsigned long long mask = __ballot(has);
                             if (mask == 0ull) break;
+                            // every lane selects (lanes without a row select row 0 and drop it)
+                            const int r = has ? __builtin_ctz(pm) : 0;
+                            pm &= pm - 1u;
+                            const int sc = select_row(acc, r);
                             if (has) {
-                                const int r = __builtin_ctz(pm);
-                                pm &= pm - 1u;
-                                // acc[r] by a four-level selection on the bits of r
-                                int s8[8], s4[4];
-#pragma unroll
-                                for (int k = 0; k < 8; k++) s8[k] = (r & 1) ? acc[2 * k + 1] : acc[2 * k];
-#pragma unroll
-                                for (int k = 0; k < 4; k++) s4[k] = (r & 2) ? s8[2 * k + 1] : s8[2 * k];
-                                const int s2a = (r & 4) ? s4[1] : s4[0], s2b = (r & 4) ? s4[3] : s4[2];
-                                const int sc = (r & 8) ? s2b : s2a;
                                 const int pos = nstaged + lanes_below(mask);
                                 const uint32_t item = 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);   // + 4 g
                                 sq.slot[pos] = slot0 + item;
