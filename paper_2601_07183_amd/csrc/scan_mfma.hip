@@ -265,8 +265,15 @@ struct LogCursor {
                                         // before the chunk is needed)
 };
 
+// When a wave refreshes bounds: every `gap`-th flush.  The gap starts at 2, doubles (up to 16)
+// each time a refresh lowers no bound -- late in the scan the bounds have settled and reading
+// histograms is wasted time -- and returns to 2 when one does.
+struct RefreshPace {
+    uint32_t gap, since, turn;          // wave-uniform
+};
+
 static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQueue &sq, int n,
-                                                   int lane, LogCursor &lc, uint32_t nflush)
+                                                   int lane, LogCursor &lc, RefreshPace &rp)
 {
     if (lc.used + (uint32_t)n > LOG_CHUNK) {
         // close the chunk, move to the one reserved earlier, reserve another
@@ -295,13 +302,23 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
             }
         }
     }
-    if ((nflush & 1u) == 0u && lane < n && ((lane + (nflush >> 1)) & 3) == 0) {
-        // at every other flush a quarter of the first row's entries, a different quarter each
-        // time, also refresh their query's bound.  A stale histogram only gives a looser bound;
-        // the bound itself only ever shrinks.
-        const int qid = (int)(sq.qid[lane] & 0x7FFFFFFFu);
-        const uint32_t nb = histogram_bound(a, qid, sq.hmul[lane]);
-        if (nb < 0xFFFFu) atomicMin(&a.bound[qid], (int32_t)nb);
+    if (++rp.since >= rp.gap) {
+        // a quarter of the first row's entries, a different quarter each time, refresh their
+        // query's bound.  A stale histogram only gives a looser bound; the bound itself only
+        // ever shrinks.
+        rp.since = 0;
+        bool lowered = false;
+        if (lane < n && ((lane + rp.turn) & 3) == 0) {
+            const int qid = (int)(sq.qid[lane] & 0x7FFFFFFFu);
+            const int32_t cur = __hip_atomic_load(&a.bound[qid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t nb = histogram_bound(a, qid, sq.hmul[lane]);
+            if (nb < 0xFFFFu && (int32_t)nb < cur) {
+                atomicMin(&a.bound[qid], (int32_t)nb);
+                lowered = true;
+            }
+        }
+        rp.turn++;
+        rp.gap = __ballot(lowered) != 0ull ? 2u : (rp.gap < 16u ? rp.gap * 2u : 16u);
     }
     lc.used += (uint32_t)n;
 }
@@ -381,7 +398,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
     lc.chunk = gwave;
     lc.next_v = gwave + nwaves;
     lc.used = 0;
-    uint32_t nflush = 0;
+    RefreshPace pace = {2u, 1u, 0u};
 #ifdef RAIRS_PROFILE_CYCLES
     long long pc_t0 = clock64(), pc_tile = 0, pc_blocks = 0, pc_slow = 0, pc_flush = 0, pc_decode = 0, pc_mark;
     long long pc_nblk = 0, pc_nslow = 0, pc_nflush = 0, pc_ntile = 0, pc_ntask = 0;
@@ -393,9 +410,8 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #endif
 #define FLUSH_STAGE()                                                   \
     do {                                                                \
-        stage_flush(a, sq, nstaged, lane, lc, nflush);     \
+        stage_flush(a, sq, nstaged, lane, lc, pace);     \
         nstaged = 0;                                                    \
-        nflush++;                                                       \
     } while (0)
 
     uint32_t u = gwave;
@@ -858,7 +874,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
     const int M = v.M, T = v.T;
     const int bias = 128 * M;
     int nstaged = 0;
-    uint32_t nflush = 0;
+    RefreshPace pace = {2u, 1u, 0u};
     const uint32_t nunits = (uint32_t)a.toff[v.nlist];
     if (nunits == 0u) return;                          // uniform; nothing was written
     const uint32_t gwave = blockIdx.x * nwave + wave, nwaves = gridDim.x * nwave;
@@ -991,9 +1007,8 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
                         }
                         nstaged += __popcll(mask);
                         if (nstaged > STAGE_CAP - 64) {
-                            stage_flush(a, sq, nstaged, lane, lc, nflush);
+                            stage_flush(a, sq, nstaged, lane, lc, pace);
                             nstaged = 0;
-                            nflush++;
                         }
                     }
                 }
@@ -1001,12 +1016,11 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
             cur = nxt;
         }
         if (nstaged >= 32) {
-            stage_flush(a, sq, nstaged, lane, lc, nflush);
+            stage_flush(a, sq, nstaged, lane, lc, pace);
             nstaged = 0;
-            nflush++;
         }
     }
-    if (nstaged > 0) stage_flush(a, sq, nstaged, lane, lc, 0u);
+    if (nstaged > 0) stage_flush(a, sq, nstaged, lane, lc, pace);
     if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
 }
 
