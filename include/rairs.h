@@ -64,7 +64,9 @@ typedef struct {
     int32_t nbits;           /* must be 4 */
     int32_t nlist;
     int32_t blk;             /* must be 32 */
-    int32_t raw_is_u8;       /* raw vectors stored as uint8 (else fp32) */
+    int32_t raw_is_u8;       /* raw vectors given as uint8 (else fp32; fp32 data whose components
+                                are all integers in [0, 255] is stored as uint8 on the device,
+                                which changes no result) */
     int64_t ntotal;          /* vectors, < 2^32 - 1 */
     int64_t nblocks;
     int64_t nrefs;

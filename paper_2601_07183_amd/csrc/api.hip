@@ -158,6 +158,26 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     const size_t cent_bytes = (size_t)x->nlist * x->d * sizeof(float);
     const size_t cb_bytes = (size_t)x->M * 16 * (x->d / x->M) * sizeof(float);
     h->code_bytes = (int64_t)x->nblocks * v.nd * 64 * 4;
+    // fp32 raw vectors whose components are all integers in [0, 255] (SIFT-like data) are kept
+    // as bytes: the conversion back is exact, so refined distances do not change, and a
+    // candidate row is a quarter of the bytes to gather
+    std::vector<uint8_t> narrow;
+    const void *raw_src = x->raw;
+    if (!v.raw_u8 && x->ntotal > 0) {
+        const float *rf = (const float *)x->raw;
+        const size_t n = (size_t)x->ntotal * x->d;
+        bool bytes_ok = true;
+        for (size_t i = 0; i < n && bytes_ok; i++) {
+            const float f = rf[i];
+            bytes_ok = f >= 0.0f && f <= 255.0f && f == (float)(int)f;
+        }
+        if (bytes_ok) {
+            narrow.resize(n);
+            for (size_t i = 0; i < n; i++) narrow[i] = (uint8_t)(int)rf[i];
+            raw_src = narrow.data();
+            v.raw_u8 = 1;
+        }
+    }
     const size_t raw_bytes = (size_t)x->ntotal * x->d * (v.raw_u8 ? 1 : 4);
     float *cnorm = nullptr;
     UP_CHECK(dev_alloc(h, (void **)&cent, cent_bytes));
@@ -207,7 +227,11 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_HIP(hipMemcpyAsync(cb, x->codebook, cb_bytes, hipMemcpyHostToDevice, s));
     if (x->nblocks)
         UP_HIP(hipMemcpyAsync(other, x->other, (size_t)x->nblocks * 32 * 4, hipMemcpyHostToDevice, s));
-    if (raw_bytes) UP_HIP(hipMemcpyAsync(raw, x->raw, raw_bytes, hipMemcpyHostToDevice, s));
+    if (raw_bytes) UP_HIP(hipMemcpyAsync(raw, raw_src, raw_bytes, hipMemcpyHostToDevice, s));
+    if (!narrow.empty()) {
+        UP_HIP(hipStreamSynchronize(s));               // the staging copy goes away
+        std::vector<uint8_t>().swap(narrow);
+    }
 
     // directory
     std::vector<ListEntry> hl((size_t)x->nlist);
