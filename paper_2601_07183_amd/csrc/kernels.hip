@@ -834,15 +834,27 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
     const int64_t qi = blockIdx.x;
     const float *qq = q + (size_t)qi * v.d;
     const int n2 = next_pow2(refine_k < 2 ? 2 : refine_k);
-    // four candidates per wave at a time, so that their id and row loads are in flight together
-    for (int c0 = wave; c0 < n2; c0 += 4 * (WG / 64)) {
+    // Candidate wave + 4 m is the wave's m-th; lane l first fetches the id of the (mb + l)-th
+    // for 64 of them at once, so that the row loads below do not wait for an id load each time.
+    // Four candidates at a time, so that their row loads are in flight together.
+    const int per_wave = n2 / (WG / 64);                 // n2 is a power of two >= 2; 0 for n2 = 2
+    for (int mb = 0; mb < (per_wave > 0 ? per_wave : 1); mb += 64) {
+    int64_t myid = -1;
+    {
+        const int c = wave + (WG / 64) * (mb + lane);
+        if (c < refine_k) myid = cand_ids[(size_t)qi * refine_k + c];
+    }
+    for (int m0 = mb; m0 < mb + 64 && wave + (WG / 64) * m0 < n2; m0 += 4) {
+        const int c0 = wave + (WG / 64) * m0;
         int64_t id[4];
         bool ok[4];
         float p[4];
 #pragma unroll
         for (int u = 0; u < 4; u++) {
-            const int c = c0 + u * (WG / 64);
-            id[u] = c < refine_k ? cand_ids[(size_t)qi * refine_k + c] : -1;
+            const int src = m0 - mb + u;                 // < 64: four at a time from a multiple of four
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)myid, src);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)myid >> 32), src);
+            id[u] = (int64_t)(((uint64_t)hi << 32) | lo);
         }
 #pragma unroll
         for (int u = 0; u < 4; u++) {
@@ -886,6 +898,7 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
             if (lane == 0 && c < n2)
                 keys[c] = ok[u] ? (((uint64_t)__float_as_uint(p[u]) << 32) | (uint32_t)id[u]) : ~0ull;
         }
+    }
     }
     __syncthreads();
     bitonic_sort_lds(keys, n2);
