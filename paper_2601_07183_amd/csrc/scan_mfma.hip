@@ -41,12 +41,12 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 
 // The scanning waves start on unit and log chunks numbered by their own index (a second chunk each
 // at index + nwaves), so the counters start behind those.
-__global__ void lm_zero_kernel(int32_t *lcount, int nlist, uint32_t *next_task, uint32_t *surv_cnt,
+__global__ void lm_zero_kernel(int32_t *lcount, int32_t *lcursor, int nlist, uint32_t *next_task, uint32_t *surv_cnt,
                                int64_t nq, uint32_t *chunk_fill, int log_chunks, uint32_t *log_cursor,
                                uint32_t *log_overflow, uint32_t first_task, uint32_t first_chunk)
 {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (gid < nlist) lcount[gid] = 0;
+    if (gid < nlist) { lcount[gid] = 0; lcursor[gid] = 0; }
     if (gid < nq) surv_cnt[gid] = 0;
     if (gid < log_chunks) chunk_fill[gid] = 0;
     if (gid == 0) { *next_task = first_task; *log_cursor = first_chunk; *log_overflow = 0; }
@@ -142,6 +142,7 @@ __global__ void lm_fill_kernel(const int32_t *__restrict__ probe_ids, int64_t nq
 // instead of once per pair (a list is probed by hundreds of queries of a batch).
 #define LM_PAIRS 4096
 #define LM_LDS_NLIST 8192
+#define LM_UNIT_WGS 8        // workgroups of the fill kernel that build the unit table
 __global__ __launch_bounds__(256) void lm_count_lds_kernel(const int32_t *__restrict__ probe_ids,
                                                            int64_t nq, int nprobe, int p_first,
                                                            int nlist, int32_t *lcount, int qb)
@@ -166,13 +167,96 @@ __global__ __launch_bounds__(256) void lm_count_lds_kernel(const int32_t *__rest
     }
 }
 
-__global__ __launch_bounds__(256) void lm_fill_lds_kernel(const int32_t *__restrict__ probe_ids,
-                                                          int64_t nq, int nprobe, int p_first,
-                                                          int nlist, const int32_t *__restrict__ loff,
-                                                          int32_t *lcursor, int32_t *qlist, int qb)
+// Exclusive prefix sums, by a workgroup of 256 threads, of x[0 .. n): thread t owns the contiguous
+// run [t per, (t+1) per); `mine` is the sum over its run.  Returns the sum over the runs before
+// this thread's and leaves the total in *total (LDS).  wsum: LDS, 4 words.
+static __device__ __forceinline__ int wg256_exclusive(int mine, int32_t *wsum, int32_t *total)
 {
-    extern __shared__ int32_t lm_hist[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int x = __shfl_up(incl, off);
+        if (lane >= off) incl += x;
+    }
+    __syncthreads();                                   // wsum may still be read from an earlier call
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+        const int x = wsum[w];
+        if (w < wave) before += x;
+        all += x;
+    }
+    if (tid == 0) *total = all;
+    return before + incl - mine;
+}
+
+// Second step for directories of up to LM_LDS_NLIST lists.  No separate prefix kernel sits between
+// counting and filling: every workgroup derives the list offsets from the counts itself (a few KB,
+// from L2), and LM_UNIT_WGS extra workgroups (the last ones) write them out for the scan together
+// with the unit table (toff, unit_list).
+__global__ __launch_bounds__(256) void lm_fill_lds_kernel(IndexView v, const int32_t *__restrict__ probe_ids,
+                                                          int64_t nq, int nprobe, int p_first,
+                                                          const int32_t *__restrict__ lcount,
+                                                          int32_t *loff, int32_t *lcursor, int32_t *qlist,
+                                                          int qb, int32_t *toff, int32_t *unit_list,
+                                                          int unit_parts)
+{
+    extern __shared__ int32_t lm_lds[];                // [nlist] ranks / run starts, [nlist + 1] offsets
+    __shared__ int32_t wsum[4], total;
+    const int nlist = v.nlist;
+    int32_t *lm_hist = lm_lds, *loff_s = lm_lds + nlist;
     const int tid = threadIdx.x;
+    const int per = (nlist + 255) / 256;
+    const int lo = tid * per < nlist ? tid * per : nlist;
+    const int hi = lo + per < nlist ? lo + per : nlist;
+    {
+        int mine = 0;
+        for (int L = lo; L < hi; L++) mine += lcount[L];
+        int run = wg256_exclusive(mine, wsum, &total);
+        for (int L = lo; L < hi; L++) {
+            loff_s[L] = run;
+            run += lcount[L];
+        }
+    }
+    __syncthreads();
+    const int nfill = (int)gridDim.x - LM_UNIT_WGS;
+    if ((int)blockIdx.x >= nfill) {
+        // The unit table: every one of these workgroups derives the unit offsets of all lists
+        // (into LDS), the first writes the offsets out, and each fills its share of unit_list,
+        // finding a unit's list by bisection on the offsets.
+        const int ub = (int)blockIdx.x - nfill;
+        int32_t *toff_s = lm_hist;                     // [nlist]
+        if (ub == 0) {
+            if (tid == 0) loff[nlist] = total;
+            for (int L = lo; L < hi; L++) loff[L] = loff_s[L];
+        }
+        int mine = 0;
+        for (int L = lo; L < hi; L++) mine += units_of(lcount[L], v.lists[L].part_cnt, unit_parts);
+        int run = wg256_exclusive(mine, wsum, &total);
+        for (int L = lo; L < hi; L++) {
+            toff_s[L] = run;
+            if (ub == 0) toff[L] = run;
+            run += units_of(lcount[L], v.lists[L].part_cnt, unit_parts);
+        }
+        __syncthreads();
+        const int nunits = total;
+        if (ub == 0 && tid == 0) toff[nlist] = nunits;
+        const int share = (nunits + LM_UNIT_WGS - 1) / LM_UNIT_WGS;
+        const int e1 = (ub + 1) * share < nunits ? (ub + 1) * share : nunits;
+        for (int e = ub * share + tid; e < e1; e += 256) {
+            // the last list whose first unit is <= e (lists without units share their successor's offset)
+            int a0 = 0, b0 = nlist - 1;
+            while (a0 < b0) {
+                const int mid = (a0 + b0 + 1) >> 1;
+                if (toff_s[mid] <= e) a0 = mid; else b0 = mid - 1;
+            }
+            unit_list[e] = a0;
+        }
+        return;
+    }
     for (int i = tid; i < nlist; i += 256) lm_hist[i] = 0;
     __syncthreads();
     const int np = nprobe - p_first;
@@ -198,7 +282,7 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(const int32_t *__restr
     __syncthreads();
     for (int i = tid; i < nlist; i += 256) {
         const int c = lm_hist[i];
-        if (c) lm_hist[i] = loff[i] + atomicAdd(&lcursor[i], c);   // where this workgroup's run starts
+        if (c) lm_hist[i] = loff_s[i] + atomicAdd(&lcursor[i], c);   // where this workgroup's run starts
     }
     __syncthreads();
 #pragma unroll
@@ -1060,7 +1144,7 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
     int64_t nz = v.nlist > a.nq ? v.nlist : a.nq;
     nz = nz > a.log_chunks ? nz : a.log_chunks;
     hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
-                       v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
+                       a.lcursor, v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
                        a.log_cursor, a.log_overflow, reg_tables ? nwaves : gridx, 2 * nwaves);
     const bool lds_group = v.nlist <= LM_LDS_NLIST;
     const int qb = LM_PAIRS / np > 0 ? LM_PAIRS / np : 1;
@@ -1071,15 +1155,20 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
     else
         hipLaunchKernelGGL(lm_count_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount);
-    hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
-                       a.toff, a.unit_list, a.unit_parts);
-    if (lds_group)
-        hipLaunchKernelGGL(lm_fill_lds_kernel, dim3(lgrid), dim3(256), (size_t)v.nlist * 4, s,
-                           a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor,
-                           a.qlist, qb);
-    else
+    if (lds_group) {
+        const size_t lds = ((size_t)2 * v.nlist + 1) * 4;
+        if (lds > 48 * 1024)
+            RAIRS_HIP(hipFuncSetAttribute((const void *)lm_fill_lds_kernel,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(lm_fill_lds_kernel, dim3(lgrid + LM_UNIT_WGS), dim3(256), lds, s, v, a.probe_ids, a.nq,
+                           a.nprobe, a.p_first, a.lcount, a.loff, a.lcursor, a.qlist, qb, a.toff,
+                           a.unit_list, a.unit_parts);
+    } else {
+        hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
+                           a.toff, a.unit_list, a.unit_parts);
         hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist);
+    }
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
