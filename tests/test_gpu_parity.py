@@ -192,6 +192,15 @@ def test_larger_dimensions_and_u8_raw(binding):
     _compare_all_stages(binding, hx, q, 10, 6, 100)
 
 
+def test_more_lists_than_the_lds_grouping_takes(binding):
+    # 8300 lists (> 8192): queries are grouped by list with global counters and the separate
+    # prefix kernel instead of the LDS route; the lists are short (one block each)
+    base = datagen.random_vectors(91, 30000, 32)
+    q = datagen.random_vectors(92, 70, 32)
+    hx = ib.build_index(base, 8300, 16, seed=9, coarse_iters=2, pq_iters=4)
+    _compare_all_stages(binding, hx, q, 10, 128, 60)
+
+
 @pytest.mark.parametrize("d,nlist", [(32, 203), (64, 203), (96, 203), (128, 203), (256, 203),
                                      (32, 1100), (128, 2051), (200, 203), (528, 300)])
 def test_coarse_shortlist_and_its_fallback(binding, d, nlist):
