@@ -292,13 +292,13 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(IndexView v, const int
 
 // ---- the scan ----------------------------------------------------------------------------------
 
-// Bin of a score: floor(score * mul / 2^32) with mul = floor(2^38 / (range + 1)), range >= 64, so
-// that scores 0..range fall into bins 0..63 without a division on the hot path (larger scores are
-// put into bin 63 by the caller).
+// Bin of a score: floor(score * mul / 2^32) with mul = floor(BINS 2^32 / (range + 1)), range >=
+// BINS, so that scores 0..range fall into bins 0..BINS-1 without a division on the hot path
+// (larger scores are put into the last bin by the caller).
 static __device__ __forceinline__ uint32_t hist_mul(uint32_t range)
 {
-    const uint32_t r = range < 64u ? 64u : range;
-    return (uint32_t)((1ull << 38) / (uint64_t)(r + 1u));
+    const uint32_t r = range < (uint32_t)RAIRS_HIST_BINS ? (uint32_t)RAIRS_HIST_BINS : range;
+    return (uint32_t)(((unsigned long long)RAIRS_HIST_BINS << 32) / (uint64_t)(r + 1u));
 }
 
 // Tightest bound the histogram of query `qid` proves: the histogram counts queue entries, so once
@@ -309,17 +309,20 @@ static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a
 {
     const uint4 *hq = (const uint4 *)(a.hist + (size_t)qid * RAIRS_HIST_BINS);
     const uint32_t need = (uint32_t)a.refine_k;
-    uint4 h[RAIRS_HIST_BINS / 4];
-#pragma unroll
-    for (int i = 0; i < RAIRS_HIST_BINS / 4; i++) h[i] = hq[i];      // all loads in flight at once
     uint32_t cum = 0;
     int b = RAIRS_HIST_BINS;
+    constexpr int HB = RAIRS_HIST_BINS / 4 < 16 ? RAIRS_HIST_BINS / 4 : 16;   // loads in flight at once
+    for (int i0 = 0; i0 < RAIRS_HIST_BINS / 4; i0 += HB) {
+        uint4 h[HB];
 #pragma unroll
-    for (int i = 0; i < RAIRS_HIST_BINS / 4; i++) {
-        cum += h[i].x; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i : b;
-        cum += h[i].y; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i + 1 : b;
-        cum += h[i].z; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i + 2 : b;
-        cum += h[i].w; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * i + 3 : b;
+        for (int i = 0; i < HB; i++) h[i] = hq[i0 + i];
+#pragma unroll
+        for (int i = 0; i < HB; i++) {
+            cum += h[i].x; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * (i0 + i) : b;
+            cum += h[i].y; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * (i0 + i) + 1 : b;
+            cum += h[i].z; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * (i0 + i) + 2 : b;
+            cum += h[i].w; b = (cum >= need && b == RAIRS_HIST_BINS) ? 4 * (i0 + i) + 3 : b;
+        }
     }
     if (b >= RAIRS_HIST_BINS - 1) return 0xFFFFu;      // the last bin also holds scores beyond the range
     // largest score whose bin is <= b
