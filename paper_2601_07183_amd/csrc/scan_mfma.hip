@@ -355,6 +355,11 @@ struct LogCursor {
 // When a wave refreshes bounds: every `gap`-th flush.  The gap starts at 2, doubles (up to 16)
 // each time a refresh lowers no bound -- late in the scan the bounds have settled and reading
 // histograms is wasted time -- and returns to 2 when one does.
+// (measured on the 1M x 128 workload: all or half of the lanes refreshing, at any pacing, is slower
+// than a quarter -- a refresh costs memory traffic per lane, not only latency)
+#define REFRESH_LANES_MASK 3
+#define REFRESH_GAP_MIN 2u
+#define REFRESH_GAP_MAX 16u
 struct RefreshPace {
     uint32_t gap, since, turn;          // wave-uniform
 };
@@ -395,7 +400,7 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
         // ever shrinks.
         rp.since = 0;
         bool lowered = false;
-        if (lane < n && ((lane + rp.turn) & 3) == 0) {
+        if (lane < n && ((lane + rp.turn) & (REFRESH_LANES_MASK)) == 0) {
             const int qid = (int)(sq.qid[lane] & 0x7FFFFFFFu);
             const int32_t cur = __hip_atomic_load(&a.bound[qid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const uint32_t nb = histogram_bound(a, qid, sq.hmul[lane]);
@@ -405,7 +410,7 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
             }
         }
         rp.turn++;
-        rp.gap = __ballot(lowered) != 0ull ? 2u : (rp.gap < 16u ? rp.gap * 2u : 16u);
+        rp.gap = __ballot(lowered) != 0ull ? REFRESH_GAP_MIN : (rp.gap < REFRESH_GAP_MAX ? rp.gap * 2u : REFRESH_GAP_MAX);
     }
     lc.used += (uint32_t)n;
 }
@@ -485,7 +490,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
     lc.chunk = gwave;
     lc.next_v = gwave + nwaves;
     lc.used = 0;
-    RefreshPace pace = {2u, 1u, 0u};
+    RefreshPace pace = {REFRESH_GAP_MIN, REFRESH_GAP_MIN - 1u, 0u};
 #ifdef RAIRS_PROFILE_CYCLES
     long long pc_t0 = clock64(), pc_tile = 0, pc_blocks = 0, pc_slow = 0, pc_flush = 0, pc_decode = 0, pc_mark;
     long long pc_nblk = 0, pc_nslow = 0, pc_nflush = 0, pc_ntile = 0, pc_ntask = 0;
@@ -961,7 +966,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
     const int M = v.M, T = v.T;
     const int bias = 128 * M;
     int nstaged = 0;
-    RefreshPace pace = {2u, 1u, 0u};
+    RefreshPace pace = {REFRESH_GAP_MIN, REFRESH_GAP_MIN - 1u, 0u};
     const uint32_t nunits = (uint32_t)a.toff[v.nlist];
     if (nunits == 0u) return;                          // uniform; nothing was written
     const uint32_t gwave = blockIdx.x * nwave + wave, nwaves = gridDim.x * nwave;
