@@ -171,8 +171,14 @@ int rairs_set_scan_mode(rairs_index_t *h, int mode);
 enum { RAIRS_STAGE_COARSE = 0, RAIRS_STAGE_LUT = 1, RAIRS_STAGE_SCAN = 2, RAIRS_STAGE_REFINE = 3,
        RAIRS_STAGE_SCAN_KERNEL = 4, RAIRS_NSTAGES = 5 };
 
-/* When enabled, rairs_search brackets each stage with HIP events on the caller's stream. */
-int rairs_set_profiling(rairs_index_t *h, int enabled);
+/*
+ * Stage timing of rairs_search with HIP events: 0 = off; RAIRS_PROFILE_STAGES = every stage is
+ * bracketed; RAIRS_PROFILE_SCAN_KERNEL = only the dominant scan kernel (every event recorded
+ * between two kernels delays the second by some microseconds; this level adds two).
+ * Stages that were not timed read -1 in rairs_get_stage_ms.
+ */
+enum { RAIRS_PROFILE_STAGES = 1, RAIRS_PROFILE_SCAN_KERNEL = 2 };
+int rairs_set_profiling(rairs_index_t *h, int level);
 
 /*
  * Milliseconds per stage of the last rairs_search (host array of RAIRS_NSTAGES floats).

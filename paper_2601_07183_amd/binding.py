@@ -26,6 +26,9 @@ EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_coarse", "
            "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_last_error")
 
 
+PROFILE_STAGES, PROFILE_SCAN_KERNEL = 1, 2
+
+
 class RairsError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"rairs error {code}: {msg}")
@@ -189,8 +192,9 @@ class Index:
         _check(self._lib.rairs_set_scan_mode(self._h, C.c_int(1 if exact else 0)))
 
     # --- measurement ----------------------------------------------------------------------
-    def set_profiling(self, enabled: bool):
-        _check(self._lib.rairs_set_profiling(self._h, C.c_int(int(enabled))))
+    def set_profiling(self, level):
+        """False / 0: off; True / PROFILE_STAGES: every stage; PROFILE_SCAN_KERNEL: the scan kernel only."""
+        _check(self._lib.rairs_set_profiling(self._h, C.c_int(int(level))))
 
     def stage_ms(self) -> dict:
         ms = (C.c_float * len(STAGES))()

@@ -684,7 +684,9 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
     hipStream_t s = (hipStream_t)hip_stream;
     char *ws = (char *)h->ws;
     // stage timing is only meaningful when the batch fits one pass
-    const bool prof = h->prof && step == nq;
+    const int plevel = step == nq ? h->prof : 0;
+    const bool prof = plevel == RAIRS_PROFILE_STAGES;  // every stage; otherwise at most the scan kernel
+    const bool profk = plevel != 0;
     h->prof_valid = 0;
     hipEvent_t *ev = h->ev[h->ev_count % RAIRS_EV_RING];
     // the table build depends only on the queries and the grouping only on the probe lists, so
@@ -723,15 +725,15 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
             if (prof) RAIRS_HIP(hipEventRecord(ev[EV_LUT1], s));
         }
         if ((rc = scan_pass(h, w, lut, probe_ids, n, nprobe, refine_k, cand, nullptr, h->dco + q0, s,
-                            prof ? &ev[EV_KERNEL0] : nullptr, overlap,
+                            profk ? &ev[EV_KERNEL0] : nullptr, overlap,
                             prof ? ev[EV_LUT1] : h->ev_lut))) return rc;
         if (prof) RAIRS_HIP(hipEventRecord(ev[EV_SCANNED], s));
         if ((rc = rairs_launch_refine(v, q, cand, n, refine_k, k, d_out_ids + (size_t)q0 * k,
                                       d_out_dists + (size_t)q0 * k, s))) return rc;
         if (prof) RAIRS_HIP(hipEventRecord(ev[EV_END], s));
     }
-    if (prof) h->ev_count++;
-    h->prof_valid = prof ? 1 : 0;
+    if (profk) h->ev_count++;
+    h->prof_valid = profk ? 1 : 0;
     return RAIRS_OK;
 }
 
@@ -746,7 +748,9 @@ extern "C" int rairs_set_scan_mode(rairs_index_t *h, int mode)
 extern "C" int rairs_set_profiling(rairs_index_t *h, int enabled)
 {
     if (!h) FAIL(RAIRS_EINVAL, "handle is NULL");
-    h->prof = enabled ? 1 : 0;
+    if (enabled != 0 && enabled != RAIRS_PROFILE_STAGES && enabled != RAIRS_PROFILE_SCAN_KERNEL)
+        FAIL(RAIRS_EINVAL, "unknown profiling level %d", enabled);
+    h->prof = enabled;
     h->prof_valid = 0;
     h->ev_count = 0;
     return RAIRS_OK;
@@ -776,6 +780,7 @@ extern "C" int rairs_get_stage_ms_mean(rairs_index_t *h, int last_n, float *ms)
                                             {EV_SCANNED, EV_END},
                                             {EV_KERNEL0, EV_KERNEL1}};
         for (int i = 0; i < RAIRS_NSTAGES; i++) {
+            if (h->prof != RAIRS_PROFILE_STAGES && i != RAIRS_STAGE_SCAN_KERNEL) { sum[i] = -(double)last_n; continue; }
             float t;
             RAIRS_HIP(hipEventSynchronize(ev[pair[i][1]]));
             RAIRS_HIP(hipEventElapsedTime(&t, ev[pair[i][0]], ev[pair[i][1]]));

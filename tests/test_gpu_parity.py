@@ -278,3 +278,36 @@ def test_argument_errors_and_empty_batch(binding, small_index):
     finally:
         ix.free()
     ix.free()                                               # second free is a no-op
+
+
+def test_stage_timers(binding, tiny_workload):
+    # the stage timers are measurement helpers: levels, the ring of recorded searches, errors
+    w, base, q, hx = tiny_workload
+    ix = binding.Index(hx)
+    try:
+        dq = _dev(q)
+        with pytest.raises(binding.RairsError):
+            ix.stage_ms()                                    # nothing recorded yet
+        with pytest.raises(binding.RairsError):
+            ix.set_profiling(7)
+        ix.set_profiling(binding.PROFILE_SCAN_KERNEL)
+        ix.search(dq, w.k, 16, w.refine_k)
+        ms = ix.stage_ms()
+        assert ms["scan_kernel"] > 0 and all(ms[k] == -1 for k in ms if k != "scan_kernel")
+        ix.set_profiling(binding.PROFILE_STAGES)
+        for _ in range(3):
+            ids, _ = ix.search(dq, w.k, 16, w.refine_k)
+        one, mean = ix.stage_ms(), ix.stage_ms_mean(3)
+        assert all(v > 0 for v in one.values()) and all(v > 0 for v in mean.values())
+        assert one["scan_kernel"] <= one["scan"]
+        with pytest.raises(binding.RairsError):
+            ix.stage_ms_mean(4)                              # only three recorded at this level
+        ix.set_profiling(False)
+        ids2, _ = ix.search(dq, w.k, 16, w.refine_k)
+        torch.cuda.synchronize()
+        assert (ids.cpu().numpy() == ids2.cpu().numpy()).all()
+        with pytest.raises(binding.RairsError):
+            ix.stage_ms()
+    finally:
+        ix.free()
+
