@@ -104,6 +104,10 @@ int rairs_index_upload(const rairs_host_index_t *host, void *hip_stream, rairs_i
  * Requires 1 <= k <= refine_k <= RAIRS_MAX_REFINE_K, 1 <= nprobe <= min(nlist,
  * RAIRS_MAX_NPROBE).  nq == 0 is a successful no-op.  The handle's internal workspace grows on
  * demand (a growth synchronises the device; steady-state calls allocate nothing).
+ * Everything is ordered after the earlier work of hip_stream and complete when hip_stream is;
+ * inside, the table build and the grouping of queries by list run on a second stream that the
+ * handle owns (default priority), forked from and joined to hip_stream with events.  Calls on one
+ * handle share its workspace and that stream: they must not overlap.
  */
 int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
                  int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream);
