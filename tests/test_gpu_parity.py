@@ -192,12 +192,14 @@ def test_larger_dimensions_and_u8_raw(binding):
     _compare_all_stages(binding, hx, q, 10, 6, 100)
 
 
-def test_more_lists_than_the_lds_grouping_takes(binding):
-    # 8300 lists (> 8192): queries are grouped by list with global counters and the separate
-    # prefix kernel instead of the LDS route; the lists are short (one block each)
+@pytest.mark.parametrize("nlist", [6100, 8300])
+def test_many_short_lists(binding, nlist):
+    # 6100 lists: the LDS grouping route with more than 48 KB of LDS per workgroup; 8300 lists
+    # (> 8192): queries are grouped by list with global counters and the separate prefix kernel.
+    # The lists are short (one block each).
     base = datagen.random_vectors(91, 30000, 32)
     q = datagen.random_vectors(92, 70, 32)
-    hx = ib.build_index(base, 8300, 16, seed=9, coarse_iters=2, pq_iters=4)
+    hx = ib.build_index(base, nlist, 16, seed=9, coarse_iters=2, pq_iters=4)
     _compare_all_stages(binding, hx, q, 10, 128, 60)
 
 
