@@ -55,3 +55,28 @@ static __device__ __forceinline__ void wave_bitonic_sort_lds(uint64_t *a, int n,
             wave_lds_sync();
         }
 }
+
+// Totals of four rows of 64 per-lane partial sums, each folded across the lanes at strides
+// 32, 16, 8, 4, 2, 1 with own + partner at every stride -- the butterfly whose result is the same
+// in every lane -- with 7 lane exchanges instead of 24: after stride 32 lanes 0..31 go on with
+// rows 0 and 1 and lanes 32..63 with rows 2 and 3, after stride 16 each group of 16 lanes has one
+// row.  Returns, in every lane of group u = lane >> 4, the total of row u, bit-identical to the
+// separate butterflies (a + b = b + a).
+static __device__ __forceinline__ float fold_four_rows(float p0, float p1, float p2, float p3, int lane)
+{
+    const bool h32 = (lane & 32) != 0;
+    float a = h32 ? p2 : p0, b = h32 ? p3 : p1;                  // rows this half keeps
+    const float sa = h32 ? p0 : p2, sb = h32 ? p1 : p3;          // rows the other half keeps
+    a = a + __shfl_xor(sa, 32);
+    b = b + __shfl_xor(sb, 32);
+    const bool h16 = (lane & 16) != 0;
+    float c = h16 ? b : a;
+    const float sc = h16 ? a : b;
+    c = c + __shfl_xor(sc, 16);
+    c = c + __shfl_xor(c, 8);
+    c = c + __shfl_xor(c, 4);
+    c = c + __shfl_xor(c, 2);
+    c = c + __shfl_xor(c, 1);
+    return c;
+}
+

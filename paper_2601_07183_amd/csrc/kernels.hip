@@ -613,15 +613,13 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
                 p[u] = p[u] + sq;
             }
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-#pragma unroll
-            for (int u = 0; u < 4; u++) p[u] = p[u] + __shfl_down(p[u], off);
-        }
+        const float dist = fold_four_rows(p[0], p[1], p[2], p[3], lane);       // list lane >> 4
         wave_lds_sync();                                 // all four lists were read before any entry is rewritten
-#pragma unroll
-        for (int u = 0; u < 4; u++)
-            if (lane == 0 && c0 + u < nc) sel[c0 + u] = ((uint64_t)__float_as_uint(p[u]) << 32) | ls[u];
+        {
+            const int u = lane >> 4;
+            const uint32_t lu = u == 0 ? ls[0] : (u == 1 ? ls[1] : (u == 2 ? ls[2] : ls[3]));
+            if ((lane & 15) == 0 && c0 + u < nc) sel[c0 + u] = ((uint64_t)__float_as_uint(dist) << 32) | lu;
+        }
         wave_lds_sync();
     }
     const int n2 = next_pow2((int)nc < 2 ? 2 : (int)nc);
@@ -821,90 +819,85 @@ int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lu
 // Refine (Alg. 2 line 7): exact distances of the candidates, K smallest by (distance, id)
 // ---------------------------------------------------------------------------------------------
 
-// One wave per candidate row: lane j sums the dimensions i = j (mod 64) in increasing order,
-// then the 64 partial sums are folded across lanes at strides 32..1.
+// One wave per query, no workgroup barrier: the wave takes the query's candidates four rows at a
+// time (lane j sums the dimensions i = j (mod 64) in increasing order, then the 64 partial sums are
+// folded across lanes at strides 32..1), keeps their keys in its own LDS region and sorts them there.
 __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__restrict__ q,
-                                                    const int64_t *__restrict__ cand_ids,
+                                                    const int64_t *__restrict__ cand_ids, int64_t nq,
                                                     int refine_k, int k,
                                                     int64_t *__restrict__ out_ids,
                                                     float *__restrict__ out_dists)
 {
-    __shared__ uint64_t keys[RAIRS_MAX_REFINE_K];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t qi = blockIdx.x;
+    extern __shared__ __align__(16) uint64_t refine_keys[];      // [WG / 64][n2]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + wave;
+    if (qi >= nq) return;                                // waves are independent of each other
     const float *qq = q + (size_t)qi * v.d;
     const int n2 = next_pow2(refine_k < 2 ? 2 : refine_k);
-    // Candidate wave + 4 m is the wave's m-th; lane l first fetches the id of the (mb + l)-th
-    // for 64 of them at once, so that the row loads below do not wait for an id load each time.
-    // Four candidates at a time, so that their row loads are in flight together.
-    const int per_wave = n2 / (WG / 64);                 // n2 is a power of two >= 2; 0 for n2 = 2
-    for (int mb = 0; mb < (per_wave > 0 ? per_wave : 1); mb += 64) {
-    int64_t myid = -1;
-    {
-        const int c = wave + (WG / 64) * (mb + lane);
-        if (c < refine_k) myid = cand_ids[(size_t)qi * refine_k + c];
-    }
-    for (int m0 = mb; m0 < mb + 64 && wave + (WG / 64) * m0 < n2; m0 += 4) {
-        const int c0 = wave + (WG / 64) * m0;
-        int64_t id[4];
-        bool ok[4];
-        float p[4];
+    uint64_t *keys = refine_keys + (size_t)wave * n2;
+    // lane l first fetches the id of candidate mb + l for 64 of them at once, so that the row
+    // loads below do not wait for an id load each time; then four candidates at a time, so that
+    // their row loads are in flight together
+    for (int mb = 0; mb < n2; mb += 64) {
+        int64_t myid = -1;
+        if (mb + lane < refine_k) myid = cand_ids[(size_t)qi * refine_k + mb + lane];
+        for (int c0 = mb; c0 < mb + 64 && c0 < n2; c0 += 4) {
+            int64_t id[4];
+            bool ok[4];
+            float p[4];
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-            const int src = m0 - mb + u;                 // < 64: four at a time from a multiple of four
-            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)myid, src);
-            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)myid >> 32), src);
-            id[u] = (int64_t)(((uint64_t)hi << 32) | lo);
-        }
+            for (int u = 0; u < 4; u++) {
+                const int src = (c0 - mb + u) & 63;          // c0 + u >= n2 only when n2 = 2: lanes without a candidate hold -1
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)myid, src);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)myid >> 32), src);
+                id[u] = (int64_t)(((uint64_t)hi << 32) | lo);
+            }
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-            ok[u] = id[u] >= 0 && id[u] < v.ntotal;
-            if (!ok[u]) id[u] = 0;                       // row 0 is read and discarded
-            p[u] = 0.0f;
-        }
-        const bool any = ok[0] || ok[1] || ok[2] || ok[3];       // wave-uniform
-        if (!any) {
-            // nothing to read (also keeps an empty index untouched)
-        } else if (v.raw_u8) {
-            for (int i = lane; i < v.d; i += 64) {
-                const float qv = qq[i];
+            for (int u = 0; u < 4; u++) {
+                ok[u] = id[u] >= 0 && id[u] < v.ntotal;
+                if (!ok[u]) id[u] = 0;                       // row 0 is read and discarded
+                p[u] = 0.0f;
+            }
+            const bool any = ok[0] || ok[1] || ok[2] || ok[3];       // wave-uniform
+            if (!any) {
+                // nothing to read (also keeps an empty index untouched)
+            } else if (v.raw_u8) {
+                for (int i = lane; i < v.d; i += 64) {
+                    const float qv = qq[i];
 #pragma unroll
-                for (int u = 0; u < 4; u++) {
-                    float diff = qv - (float)((const uint8_t *)v.raw)[(size_t)id[u] * v.d + i];
-                    float sq = diff * diff;
-                    p[u] = p[u] + sq;
+                    for (int u = 0; u < 4; u++) {
+                        float diff = qv - (float)((const uint8_t *)v.raw)[(size_t)id[u] * v.d + i];
+                        float sq = diff * diff;
+                        p[u] = p[u] + sq;
+                    }
+                }
+            } else {
+                for (int i = lane; i < v.d; i += 64) {
+                    const float qv = qq[i];
+#pragma unroll
+                    for (int u = 0; u < 4; u++) {
+                        float diff = qv - ((const float *)v.raw)[(size_t)id[u] * v.d + i];
+                        float sq = diff * diff;
+                        p[u] = p[u] + sq;
+                    }
                 }
             }
-        } else {
-            for (int i = lane; i < v.d; i += 64) {
-                const float qv = qq[i];
-#pragma unroll
-                for (int u = 0; u < 4; u++) {
-                    float diff = qv - ((const float *)v.raw)[(size_t)id[u] * v.d + i];
-                    float sq = diff * diff;
-                    p[u] = p[u] + sq;
-                }
+            const float dist = fold_four_rows(p[0], p[1], p[2], p[3], lane);   // row lane >> 4
+            {
+                const int u = lane >> 4, c = c0 + u;
+                const bool oku = u == 0 ? ok[0] : (u == 1 ? ok[1] : (u == 2 ? ok[2] : ok[3]));
+                const int64_t idu = u == 0 ? id[0] : (u == 1 ? id[1] : (u == 2 ? id[2] : id[3]));
+                // empty: distance bits in the NaN region, id = all ones
+                if ((lane & 15) == 0 && c < n2)
+                    keys[c] = oku ? (((uint64_t)__float_as_uint(dist) << 32) | (uint32_t)idu) : ~0ull;
             }
         }
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) {
-#pragma unroll
-            for (int u = 0; u < 4; u++) p[u] = p[u] + __shfl_xor(p[u], s);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-            const int c = c0 + u * (WG / 64);
-            // empty: distance bits in the NaN region, id = all ones
-            if (lane == 0 && c < n2)
-                keys[c] = ok[u] ? (((uint64_t)__float_as_uint(p[u]) << 32) | (uint32_t)id[u]) : ~0ull;
-        }
     }
-    }
-    __syncthreads();
-    bitonic_sort_lds(keys, n2);
-    for (int i = tid; i < k; i += WG) {
-        uint64_t key = keys[i];
-        bool ok = key != ~0ull;
+    wave_lds_sync();
+    wave_bitonic_sort_lds(keys, n2, lane);
+    for (int i = lane; i < k; i += 64) {
+        const uint64_t key = keys[i];
+        const bool ok = key != ~0ull;
         out_ids[(size_t)qi * k + i] = ok ? (int64_t)(uint32_t)key : -1;
         out_dists[(size_t)qi * k + i] = ok ? __uint_as_float((uint32_t)(key >> 32)) : __builtin_inff();
     }
@@ -913,8 +906,9 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
 int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,
                         int refine_k, int k, int64_t *out_ids, float *out_dists, hipStream_t s)
 {
-    hipLaunchKernelGGL(refine_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, q, cand_ids, refine_k,
-                       k, out_ids, out_dists);
+    const int n2 = next_pow2(refine_k < 2 ? 2 : refine_k);
+    hipLaunchKernelGGL(refine_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
+                       (size_t)(WG / 64) * n2 * 8, s, v, q, cand_ids, nq, refine_k, k, out_ids, out_dists);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
