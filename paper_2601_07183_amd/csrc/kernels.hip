@@ -784,16 +784,25 @@ __global__ __launch_bounds__(WG) void lut_kernel(const float *__restrict__ q,
         width[m] = hi - lo;
     }
     __syncthreads();
-    if (tid == 0) {
-        float span = 0.0f, bsum = 0.0f;
-        for (int m = 0; m < M; m++) {
-            span = width[m] > span ? width[m] : span;
-            bsum = bsum + bias[m];
+    if (tid < 64) {
+        // the largest width: a maximum does not depend on the order it is taken in
+        float span = 0.0f;
+        for (int m = tid; m < M; m += 64) span = width[m] > span ? width[m] : span;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float o = __shfl_xor(span, off);
+            span = o > span ? o : span;
         }
-        float s = span > 0.0f ? __fdiv_rn(255.0f, span) : 0.0f;
-        s_scale = s;
-        if (bias_sum) bias_sum[blockIdx.x] = bsum;
-        if (scale) scale[blockIdx.x] = s;
+        if (tid == 0) {
+            const float s = span > 0.0f ? __fdiv_rn(255.0f, span) : 0.0f;
+            s_scale = s;
+            if (scale) scale[blockIdx.x] = s;
+        }
+    } else if (tid == 64 && bias_sum) {
+        // the sum of the offsets is defined in sub-quantizer order; only the stage call asks for it
+        float bsum = 0.0f;
+        for (int m = 0; m < M; m++) bsum = bsum + bias[m];
+        bias_sum[blockIdx.x] = bsum;
     }
     __syncthreads();
     const float s = s_scale;
