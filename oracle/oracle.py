@@ -127,6 +127,19 @@ def lut(ox: OracleIndex, q: np.ndarray):
     return T, u8, bias.value, scale.value
 
 
+def pq_encode(codebook: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """PQEncoding (Alg. 1): packed codes [n][M/2] of the rows of x for codebook [M][16][d/M]."""
+    lib = _load()
+    cb = np.ascontiguousarray(codebook, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    M, ksub, dsub = cb.shape
+    assert ksub == 16 and x.shape[1] == M * dsub and M % 2 == 0
+    out = np.empty((x.shape[0], M // 2), dtype=np.uint8)
+    lib.oracle_pq_encode(C.c_void_p(cb.ctypes.data), C.c_int(M * dsub), C.c_int(M),
+                         C.c_void_p(x.ctypes.data), C.c_int64(x.shape[0]), C.c_void_p(out.ctypes.data))
+    return out
+
+
 def search(ox: OracleIndex, queries: np.ndarray, k: int, nprobe: int, refine_k: int,
            layout: str = "seil", nthreads: int = 0, trace: bool = False) -> OracleResult:
     """layout "seil": Alg. 5 on the SEIL directory; "naive": union of probed lists' members."""

@@ -353,6 +353,40 @@ int oracle_search(const oracle_index *ix, const float *queries, int64_t nq, int 
     return 0;
 }
 
+/* ---- PQEncoding (Alg. 1, Section 2.2): the code of a vector ------------------------------- */
+
+/*
+ * code[m] = index of the codeword of sub-quantizer m nearest to sub-vector m; the first one on a
+ * tie.  The distances are the entries of the lookup table the vector would get as a query (same
+ * fp32 arithmetic: sequential over the sub-vector's dimensions, no fused multiply-add), since
+ * floating point decides an integer here and both sides must decide in one precision.
+ * Packed like the index: byte i holds sub-quantizer 2i in the low nibble, 2i+1 in the high one.
+ */
+void oracle_pq_encode(const float *codebook, int d, int M, const float *x, int64_t n, uint8_t *codes)
+{
+    const int dsub = d / M;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n; v++) {
+        const float *xv = x + (size_t)v * d;
+        for (int m = 0; m < M; m++) {
+            int best = 0;
+            float bestd = 0.0f;
+            for (int c = 0; c < 16; c++) {
+                const float *cw = codebook + ((size_t)m * 16 + c) * dsub;
+                float acc = 0.0f;
+                for (int t = 0; t < dsub; t++) {
+                    float a = xv[m * dsub + t] - cw[t];
+                    float sq = a * a;
+                    if (t == 0) acc = sq; else acc = acc + sq;
+                }
+                if (c == 0 || acc < bestd) { best = c; bestd = acc; }
+            }
+            uint8_t *o = codes + (size_t)v * (M / 2) + m / 2;
+            if (m % 2 == 0) *o = (uint8_t)best; else *o = (uint8_t)(*o | (best << 4));
+        }
+    }
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -309,3 +309,60 @@ def test_tiny_workload_recall_is_monotone_and_layouts_agree(tiny_workload):
         rec = np.mean([len(set(r.ids[i]) & set(gt[i])) / w.k for i in range(60)])
         assert rec >= last - 0.02
         last = rec
+
+
+# --- PQ encoding ---------------------------------------------------------------------------
+
+def _unpack(codes, M):
+    out = np.empty((codes.shape[0], M), dtype=np.int64)
+    out[:, 0::2], out[:, 1::2] = codes & 15, codes >> 4
+    return out
+
+
+def test_pq_encode_is_the_nearest_codeword():
+    # Alg. 1 / Section 2.2: against a float64 argmin wherever float64 separates the two best
+    # codewords clearly; a transposed codebook axis, a swapped nibble or a wrong sub-vector
+    # offset all fail here
+    g = np.random.Generator(np.random.PCG64(5))
+    for d, M in ((32, 16), (96, 48), (60, 6)):
+        dsub = d // M
+        cb = g.standard_normal((M, 16, dsub)).astype(np.float32)
+        x = g.standard_normal((300, d)).astype(np.float32)
+        got = _unpack(oracle.pq_encode(cb, x), M)
+        d2 = ((x.reshape(300, M, 1, dsub).astype(np.float64) - cb[None].astype(np.float64)) ** 2).sum(-1)
+        best = d2.argmin(-1)
+        two = np.sort(d2, axis=-1)[..., :2]
+        clear = two[..., 1] - two[..., 0] > 1e-5 * (1.0 + two[..., 1])
+        assert clear.mean() > 0.99
+        assert (got[clear] == best[clear]).all()
+        # and where it is not clear, the chosen codeword is still a nearest one up to rounding
+        chosen = np.take_along_axis(d2, got[..., None], -1)[..., 0]
+        assert (chosen <= two[..., 0] + 1e-5 * (1.0 + two[..., 1])).all()
+
+
+def test_pq_encode_codewords_encode_to_themselves_and_ties_take_the_first():
+    g = np.random.Generator(np.random.PCG64(6))
+    M, dsub = 8, 4
+    cb = g.standard_normal((M, 16, dsub)).astype(np.float32)
+    cb[:, 9] = cb[:, 3]                                   # codeword 9 duplicates codeword 3
+    # vector j is made of codeword (j + m) % 16 of every sub-quantizer m
+    pick = (np.arange(16)[:, None] + np.arange(M)[None, :]) % 16
+    x = cb[np.arange(M)[None, :], pick].reshape(16, M * dsub)
+    got = _unpack(oracle.pq_encode(cb, x), M)
+    want = np.where(pick == 9, 3, pick)                   # distance 0 twice: the first wins
+    assert (got == want).all()
+
+
+def test_pq_encode_packing_matches_the_index_layout(small_index):
+    # byte i of a code holds sub-quantizer 2i in the low nibble: re-encoding the base vectors with
+    # the index's codebook gives codes whose decoded vectors are as close as the stored codes'
+    base, hx = small_index
+    dsub = hx.d // hx.M
+    codes = oracle.pq_encode(hx.codebook, base[:500])
+    def err(c):
+        dec = hx.codebook[np.arange(hx.M)[None, :], _unpack(c, hx.M)].reshape(len(c), hx.M * dsub)
+        return ((base[:len(c)].astype(np.float64) - dec) ** 2).sum(1)
+    stored = hx.vec_codes[:500]
+    assert np.allclose(err(codes), err(stored), rtol=1e-6, atol=1e-9)
+    assert (codes == stored).mean() > 0.999               # the builder's own encoder, other arithmetic
+
