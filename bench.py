@@ -79,6 +79,56 @@ def recall_at_k(ids: np.ndarray, gt: np.ndarray) -> float:
     return hits / gt.size
 
 
+def bench_pq_encode(args):
+    """PQEncoding of the workload's base vectors with a codebook trained on them: vectors/s, the
+    algorithmic HBM rate (vectors read once, codes written once) and the oracle's rate."""
+    import torch
+    from oracle import oracle
+    from paper_2601_07183_amd import binding, datagen, index_build
+    binding.load()
+    w = datagen.WORKLOADS[args.workload]
+    if args.base_size:
+        w = datagen.scaled(w, args.base_size)
+    base = datagen.make_base(w).astype(np.float32, copy=False)
+    cb = index_build.train_pq(base, w.M, 8, w.seed * 7 + 2)
+    dx, dcb = torch.from_numpy(base).cuda(), torch.from_numpy(cb).cuda()
+    n, d = base.shape
+    for _ in range(max(1, args.warmup)):
+        codes = binding.pq_encode(dcb, dx)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(args.steps):
+        codes = binding.pq_encode(dcb, dx)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / args.steps
+    ns = min(n, 200_000)
+    t = time.perf_counter()
+    want = oracle.pq_encode(cb, base[:ns])
+    cpu_s = time.perf_counter() - t
+    same = bool((codes[:ns].cpu().numpy() == want).all())
+    bytes_per_launch = float(n) * d * 4 + float(n) * (w.M // 2)
+    gbs = bytes_per_launch / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "PQ encode rate", "value": round(n / (ms * 1e-3), 1), "unit": "vectors/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={n} d={d} M={w.M}x4bit", "codes_identical_to_oracle_on_sample": same},
+        "roofline": {"kernel": "pq_encode_kernel", "bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0,
+                     "unit": "GB/s", "frac": round(gbs / 8000.0, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": bytes_per_launch},
+        # what bounds it: per (vector, sub-quantizer, codeword) dsub subtractions, dsub products,
+        # dsub - 1 additions and three compare/select operations, none of them fused or packed,
+        # against one 64-lane operation per compute unit and cycle (256 CUs, 2.4 GHz)
+        "roofline_alu": {"kernel": "pq_encode_kernel", "bound": "alu",
+                         "achieved": round(n / (ms * 1e-3) * w.M * 16 * (3 * (d // w.M) + 2) / 1e12, 2),
+                         "peak": round(256 * 64 * 2.4e9 / 1e12, 2), "unit": "T lane-ops/s",
+                         "frac": round(n / (ms * 1e-3) * w.M * 16 * (3 * (d // w.M) + 2) / (256 * 64 * 2.4e9), 4)},
+        "cpu_baseline": {"value": round(ns / cpu_s, 1), "unit": "vectors/s", "cores": oracle.num_threads(),
+                         "kind": "oracle", "sample": f"first {ns} vectors"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -100,7 +150,12 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="only run a device-to-device copy of this many bytes three times (to "
                          "calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--pq-encode", action="store_true",
+                    help="measure rairs_pq_encode (a step of index construction) on the workload's base "
+                         "vectors instead of the search path; prints a JSON line of its own")
     args = ap.parse_args()
+    if args.pq_encode:
+        return bench_pq_encode(args)
     if args.copy_calibration:
         import torch
         n = args.copy_calibration // 4

@@ -210,6 +210,19 @@ int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats);
 /* Bytes of device memory held by the index (codes, ids, tags, directory, raw vectors, ...). */
 int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, int64_t *total_bytes);
 
+/*
+ * PQEncoding (Alg. 1; Section 2.2), a step of index construction: the 4-bit codes of n vectors.
+ *   d_codebook device [M][16][d/M] fp32;  d_vectors device [n][d] fp32;
+ *   d_codes    device [n][M/2] uint8, byte i: sub-quantizer 2i in the low nibble, 2i+1 in the high
+ * code[m] is the nearest of the 16 codewords of sub-quantizer m to sub-vector m, the first one on
+ * a tie, with the distances computed as the lookup-table entries of rairs_lut are (fp32, summed
+ * in dimension order, no fused multiply-add).  Needs M even, 2 <= M <= RAIRS_MAX_M, d % M == 0 and
+ * 64 d bytes of LDS for sub-vectors that are not 1, 2 or 4 long.  No handle, no allocation; the
+ * caller owns all three buffers.  n == 0 is a successful no-op.
+ */
+int rairs_pq_encode(const float *d_codebook, int d, int M, const float *d_vectors, int64_t n,
+                    uint8_t *d_codes, void *hip_stream);
+
 const char *rairs_last_error(void);
 
 #ifdef __cplusplus

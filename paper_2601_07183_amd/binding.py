@@ -23,7 +23,8 @@ MAX_NPROBE = 4096
 EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_coarse", "rairs_lut",
            "rairs_scan", "rairs_refine", "rairs_set_scan_mode", "rairs_set_profiling", "rairs_get_stage_ms",
            "rairs_get_stage_ms_mean",
-           "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_last_error")
+           "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_pq_encode",
+           "rairs_last_error")
 
 
 PROFILE_STAGES, PROFILE_SCAN_KERNEL = 1, 2
@@ -87,6 +88,21 @@ _ARRAYS = [("centroids", np.float32), ("codebook", np.float32), ("codes", np.uin
            ("list_shared_cnt", np.int32), ("list_misc_begin", np.int64),
            ("list_misc_cnt", np.int32), ("list_ref_begin", np.int64), ("list_ref_cnt", np.int32),
            ("ref_owner", np.int32), ("ref_block_begin", np.int64), ("ref_nblocks", np.int32)]
+
+
+def pq_encode(codebook: torch.Tensor, vectors: torch.Tensor, stream=None) -> torch.Tensor:
+    """rairs_pq_encode: packed codes [n][M/2] of device vectors [n][d] for a device codebook [M][16][d/M]."""
+    lib = load()
+    M, ksub, dsub = codebook.shape
+    if ksub != 16 or vectors.ndim != 2 or vectors.shape[1] != M * dsub:
+        raise ValueError("codebook must be [M][16][d/M] and vectors [n][d]")
+    n = vectors.shape[0]
+    codes = torch.empty((n, M // 2), dtype=torch.uint8, device=vectors.device)
+    _check(lib.rairs_pq_encode(_dev(codebook, torch.float32, "codebook"), C.c_int(M * dsub), C.c_int(M),
+                               _dev(vectors, torch.float32, "vectors") if n else C.c_void_p(0),
+                               C.c_int64(n), _dev(codes, torch.uint8, "codes") if n else C.c_void_p(0),
+                               _stream_ptr(stream)))
+    return codes
 
 
 def host_struct(hx):

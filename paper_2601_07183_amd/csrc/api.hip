@@ -819,6 +819,18 @@ extern "C" int rairs_debug_cycles(rairs_index_t *h, long long *out)
 }
 #endif
 
+extern "C" int rairs_pq_encode(const float *d_codebook, int d, int M, const float *d_vectors, int64_t n,
+                               uint8_t *d_codes, void *hip_stream)
+{
+    if (d < 1 || M < 2 || M > RAIRS_MAX_M || M % 2 != 0 || d % M != 0)
+        FAIL(RAIRS_EINVAL, "PQ shape d=%d M=%d: need M even, 2 <= M <= %d, d a multiple of M", d, M, RAIRS_MAX_M);
+    if ((size_t)16 * d * sizeof(float) > 160 * 1024 - 1024) FAIL(RAIRS_EINVAL, "d=%d: the codebook does not fit LDS", d);
+    if (n < 0) FAIL(RAIRS_EINVAL, "n is negative");
+    if (n == 0) return RAIRS_OK;
+    if (!d_codebook || !d_vectors || !d_codes) FAIL(RAIRS_EINVAL, "null device pointer");
+    return rairs_launch_pq_encode(d_codebook, d, M, d_vectors, n, d_codes, (hipStream_t)hip_stream);
+}
+
 extern "C" int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq)
 {
     if (!h || !dco) FAIL(RAIRS_EINVAL, "null argument");

@@ -825,6 +825,129 @@ int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lu
 }
 
 // ---------------------------------------------------------------------------------------------
+// PQEncoding (Alg. 1, Section 2.2): codes of a batch of vectors (index construction)
+// ---------------------------------------------------------------------------------------------
+
+// code[m] = the nearest of the 16 codewords of sub-quantizer m, the first one on a tie; distances
+// in the table build's arithmetic (fp32, sequential over the sub-vector, no fused multiply-add).
+// One thread per output byte -- sub-quantizers 2b and 2b+1 of one vector -- and the thread keeps
+// the 32 codewords of its byte position b in registers for all its vectors: the grid's stride over
+// (vector, byte) pairs is a multiple of M/2, so b never changes.  Adjacent threads read adjacent
+// sub-vectors and write adjacent bytes; the kernel streams the vectors once (HBM bound).
+template <int DSUB>
+__global__ __launch_bounds__(WG) void pq_encode_reg_kernel(const float *__restrict__ cb, int M,
+                                                           const float *__restrict__ x, int64_t n,
+                                                           uint8_t *__restrict__ codes)
+{
+    const int hb = M / 2, d = M * DSUB;
+    const int64_t gtid = (int64_t)blockIdx.x * WG + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * WG;       // a multiple of hb (the launcher sees to it)
+    const int b = (int)(gtid % hb);
+    float cw[2][16][DSUB];
+#pragma unroll
+    for (int h = 0; h < 2; h++)
+#pragma unroll
+        for (int c = 0; c < 16; c++)
+#pragma unroll
+            for (int t = 0; t < DSUB; t++) cw[h][c][t] = cb[((size_t)(2 * b + h) * 16 + c) * DSUB + t];
+    const int64_t vstep = stride / hb;
+#pragma unroll 2
+    for (int64_t v = gtid / hb; v < n; v += vstep) {
+        float xs[2 * DSUB];
+        const float *xv = x + (size_t)v * d + (size_t)b * 2 * DSUB;
+#pragma unroll
+        for (int t = 0; t < 2 * DSUB; t++) xs[t] = xv[t];
+        uint32_t out = 0;
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            int best = 0;
+            float bestd = 0.0f;
+#pragma unroll
+            for (int c = 0; c < 16; c++) {
+                const float a0 = xs[h * DSUB] - cw[h][c][0];
+                float acc = a0 * a0;
+#pragma unroll
+                for (int t = 1; t < DSUB; t++) {
+                    const float a = xs[h * DSUB + t] - cw[h][c][t];
+                    const float sq = a * a;
+                    acc = acc + sq;
+                }
+                if (c == 0 || acc < bestd) { best = c; bestd = acc; }
+            }
+            out |= (uint32_t)best << (4 * h);
+        }
+        codes[(size_t)v * hb + b] = (uint8_t)out;
+    }
+}
+
+// Any sub-vector length: the codebook sits in LDS as [half][codeword][dimension][byte position], so
+// that the lanes of a wave (adjacent byte positions) read adjacent words.
+__global__ __launch_bounds__(WG) void pq_encode_lds_kernel(const float *__restrict__ cb, int d, int M,
+                                                           const float *__restrict__ x, int64_t n,
+                                                           uint8_t *__restrict__ codes)
+{
+    extern __shared__ float pq_cb[];                     // 16 d floats
+    const int hb = M / 2, dsub = d / M;
+    for (int i = threadIdx.x; i < 16 * d; i += WG) {
+        const int t = i % dsub, c = (i / dsub) % 16, m = i / (dsub * 16);
+        pq_cb[(((m & 1) * 16 + c) * dsub + t) * hb + (m >> 1)] = cb[i];
+    }
+    __syncthreads();
+    const int64_t total = n * hb;
+    for (int64_t e = (int64_t)blockIdx.x * WG + threadIdx.x; e < total; e += (int64_t)gridDim.x * WG) {
+        const int64_t v = e / hb;
+        const int b = (int)(e % hb);
+        const float *xv = x + (size_t)v * d + (size_t)b * 2 * dsub;
+        uint32_t out = 0;
+        for (int h = 0; h < 2; h++) {
+            int best = 0;
+            float bestd = 0.0f;
+            for (int c = 0; c < 16; c++) {
+                const float *cwp = pq_cb + (size_t)((h * 16 + c) * dsub) * hb + b;
+                const float a0 = xv[h * dsub] - cwp[0];
+                float acc = a0 * a0;
+                for (int t = 1; t < dsub; t++) {
+                    const float a = xv[h * dsub + t] - cwp[(size_t)t * hb];
+                    const float sq = a * a;
+                    acc = acc + sq;
+                }
+                if (c == 0 || acc < bestd) { best = c; bestd = acc; }
+            }
+            out |= (uint32_t)best << (4 * h);
+        }
+        codes[e] = (uint8_t)out;
+    }
+}
+
+int rairs_launch_pq_encode(const float *cb, int d, int M, const float *x, int64_t n, uint8_t *codes,
+                           hipStream_t s)
+{
+    const int hb = M / 2, dsub = d / M;
+    // threads in the grid: a multiple of lcm(WG, hb), about eight workgroups per compute unit
+    int g = hb, r = WG;
+    while (r) { const int tmp = g % r; g = r; r = tmp; }             // gcd(hb, WG)
+    const int64_t unit = (int64_t)hb / g;                // workgroups per lcm(WG, hb) threads
+    int64_t grid = (2048 + unit - 1) / unit * unit;
+    const int64_t need = (n * hb + WG - 1) / WG;
+    if (need < grid) grid = (need + unit - 1) / unit * unit;
+    if (grid < unit) grid = unit;
+    switch (dsub) {
+    case 1: hipLaunchKernelGGL(pq_encode_reg_kernel<1>, dim3((unsigned)grid), dim3(WG), 0, s, cb, M, x, n, codes); break;
+    case 2: hipLaunchKernelGGL(pq_encode_reg_kernel<2>, dim3((unsigned)grid), dim3(WG), 0, s, cb, M, x, n, codes); break;
+    case 4: hipLaunchKernelGGL(pq_encode_reg_kernel<4>, dim3((unsigned)grid), dim3(WG), 0, s, cb, M, x, n, codes); break;
+    default: {
+        const size_t lds = (size_t)16 * d * sizeof(float);
+        if (lds > 48 * 1024)
+            RAIRS_HIP(hipFuncSetAttribute((const void *)pq_encode_lds_kernel,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(pq_encode_lds_kernel, dim3((unsigned)grid), dim3(WG), lds, s, cb, d, M, x, n, codes);
+    }
+    }
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Refine (Alg. 2 line 7): exact distances of the candidates, K smallest by (distance, id)
 // ---------------------------------------------------------------------------------------------
 

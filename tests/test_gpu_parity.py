@@ -313,3 +313,24 @@ def test_stage_timers(binding, tiny_workload):
     finally:
         ix.free()
 
+
+@pytest.mark.parametrize("d,M", [(32, 16), (128, 64), (96, 48), (960, 240), (64, 64), (60, 6), (24, 2)])
+def test_pq_encode_matches_the_oracle(binding, d, M):
+    # sub-vectors of 2, 2, 2, 4, 1 (codebook in registers), 10 and 12 (codebook in LDS) dimensions;
+    # ragged vector counts around the grid's stride; bit exact
+    g = np.random.Generator(np.random.PCG64(d * 1000 + M))
+    cb = g.standard_normal((M, 16, d // M)).astype(np.float32)
+    cb[:, 11] = cb[:, 2]                                  # a tie in every sub-quantizer
+    for n in (0, 1, 777, 20011):
+        print(f"case: pq_encode d={d} M={M} n={n}", flush=True)
+        x = g.standard_normal((n, d)).astype(np.float32)
+        x[: n // 3] = np.round(x[: n // 3])              # integer-valued rows: more exact ties
+        if n > 5:
+            x[5] = cb[np.arange(M), (np.arange(M) * 7) % 16].reshape(-1)   # a vector made of codewords
+        got = binding.pq_encode(_dev(cb), _dev(x) if n else torch.empty((0, d), device="cuda"))
+        torch.cuda.synchronize()
+        want = oracle.pq_encode(cb, x) if n else np.empty((0, M // 2), dtype=np.uint8)
+        assert got.shape == want.shape and (got.cpu().numpy() == want).all()
+    with pytest.raises(binding.RairsError):
+        binding.pq_encode(_dev(np.zeros((3, 16, 2), dtype=np.float32)), _dev(np.zeros((4, 6), dtype=np.float32)))
+
