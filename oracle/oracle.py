@@ -140,6 +140,20 @@ def pq_encode(codebook: np.ndarray, x: np.ndarray) -> np.ndarray:
     return out
 
 
+def rair_assign(centroids: np.ndarray, x: np.ndarray, n_cands: int = 10, lam: float = 0.5,
+                strict: bool = True) -> np.ndarray:
+    """RairAssign (Alg. 3): [n][2] list ids per vector, the smaller id first."""
+    lib = _load()
+    c = np.ascontiguousarray(centroids, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert c.shape[1] == x.shape[1] and n_cands >= 1
+    out = np.empty((x.shape[0], 2), dtype=np.int32)
+    lib.oracle_rair_assign(C.c_void_p(c.ctypes.data), C.c_int(c.shape[0]), C.c_int(c.shape[1]),
+                           C.c_void_p(x.ctypes.data), C.c_int64(x.shape[0]), C.c_int(n_cands),
+                           C.c_double(lam), C.c_int(int(strict)), C.c_void_p(out.ctypes.data))
+    return out
+
+
 def search(ox: OracleIndex, queries: np.ndarray, k: int, nprobe: int, refine_k: int,
            layout: str = "seil", nthreads: int = 0, trace: bool = False) -> OracleResult:
     """layout "seil": Alg. 5 on the SEIL directory; "naive": union of probed lists' members."""

@@ -387,6 +387,54 @@ void oracle_pq_encode(const float *codebook, int d, int M, const float *x, int64
     }
 }
 
+/* ---- RairAssign (Alg. 3): the two lists of a vector ---------------------------------------- */
+
+/*
+ * FindNearestLists is the coarse quantizer of the search path (same fp32 distances, order by
+ * (distance, list id)); the loss of candidate i, loss[i] = ||r_i||^2 + lambda <r_0, r_i> with
+ * r_i = centroid_i - v, is taken in float64, both sums sequential over the dimensions, no fused
+ * multiply-add (the paper does not fix a precision; the decision is an argmin, so one is fixed
+ * here).  The secondary list is the first minimum of the loss over candidates 1.. (strict) or 0..
+ * (not strict: it may equal the primary list, the vector is then stored once).  n_cands is
+ * clamped to nlist.  out[v] = the pair ordered by list id.
+ */
+void oracle_rair_assign(const float *centroids, int nlist, int d, const float *x, int64_t n,
+                        int n_cands, double lambda, int strict, int32_t *out)
+{
+    if (n_cands > nlist) n_cands = nlist;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n; v++) {
+        const float *xv = x + (size_t)v * d;
+        dist_id *all = (dist_id *)malloc(sizeof(dist_id) * (size_t)nlist);
+        for (int l = 0; l < nlist; l++) {
+            all[l].dist = oracle_l2sqr(xv, centroids + (size_t)l * d, d);
+            all[l].id = l;
+        }
+        qsort(all, (size_t)nlist, sizeof(dist_id), cmp_dist_id);
+        const float *c0 = centroids + (size_t)all[0].id * d;
+        int best = -1;
+        double bestloss = 0.0;
+        for (int i = strict ? 1 : 0; i < n_cands; i++) {
+            const float *ci = centroids + (size_t)all[i].id * d;
+            double l2 = 0.0, ip = 0.0;
+            for (int t = 0; t < d; t++) {
+                double r0 = (double)c0[t] - (double)xv[t];
+                double r = (double)ci[t] - (double)xv[t];
+                double rr = r * r, r0r = r0 * r;
+                l2 = l2 + rr;
+                ip = ip + r0r;
+            }
+            double scaled = lambda * ip;
+            double loss = l2 + scaled;
+            if (best < 0 || loss < bestloss) { best = i; bestloss = loss; }
+        }
+        const int32_t first = (int32_t)all[0].id, second = best < 0 ? first : (int32_t)all[best].id;
+        out[2 * v] = first < second ? first : second;
+        out[2 * v + 1] = first < second ? second : first;
+        free(all);
+    }
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

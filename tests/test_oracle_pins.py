@@ -366,3 +366,67 @@ def test_pq_encode_packing_matches_the_index_layout(small_index):
     assert np.allclose(err(codes), err(stored), rtol=1e-6, atol=1e-9)
     assert (codes == stored).mean() > 0.999               # the builder's own encoder, other arithmetic
 
+
+# --- RairAssign ----------------------------------------------------------------------------
+
+def _assign_float64(c, x, n_cands, lam, strict):
+    """Alg. 3 written out in float64 numpy; also returns how clearly each decision is separated."""
+    d2 = ((x[:, None, :].astype(np.float64) - c[None].astype(np.float64)) ** 2).sum(-1)
+    order = np.argsort(d2, axis=1, kind="stable")
+    n_cands = min(n_cands, c.shape[0])
+    cand = order[:, :n_cands]
+    srt = np.take_along_axis(d2, order, 1)
+    gap_c = (srt[:, 1:n_cands + 1] - srt[:, :n_cands][:, : srt[:, 1:n_cands + 1].shape[1]]).min(1) if c.shape[0] > 1 else np.ones(len(x))
+    r = c[cand].astype(np.float64) - x[:, None, :].astype(np.float64)
+    loss = (r * r).sum(-1) + lam * (r * r[:, :1, :]).sum(-1)
+    start = 1 if strict else 0
+    if start >= n_cands:
+        second, gap_l = cand[:, 0], np.ones(len(x))
+    else:
+        sub = loss[:, start:]
+        pos = sub.argmin(1)
+        second = cand[np.arange(len(x)), pos + start]
+        two = np.sort(sub, axis=1)[:, :2]
+        gap_l = two[:, 1] - two[:, 0] if sub.shape[1] > 1 else np.ones(len(x))
+    first = cand[:, 0]
+    pair = np.stack([np.minimum(first, second), np.maximum(first, second)], 1).astype(np.int32)
+    return pair, (gap_c > 1e-4) & (gap_l > 1e-4)
+
+
+@pytest.mark.parametrize("strict", [True, False])
+@pytest.mark.parametrize("lam", [0.0, 0.5, 2.0])
+def test_rair_assign_against_float64(strict, lam):
+    g = np.random.Generator(np.random.PCG64(17))
+    c = g.standard_normal((40, 24)).astype(np.float32)
+    x = (c[g.integers(0, 40, 500)] + 0.7 * g.standard_normal((500, 24))).astype(np.float32)
+    want, clear = _assign_float64(c, x, 10, lam, strict)
+    got = oracle.rair_assign(c, x, 10, lam, strict)
+    assert clear.mean() > 0.95
+    assert (got[clear] == want[clear]).all()
+    assert (got[:, 0] <= got[:, 1]).all()
+
+
+def test_rair_assign_special_cases():
+    g = np.random.Generator(np.random.PCG64(18))
+    c = g.standard_normal((30, 16)).astype(np.float32)
+    x = g.standard_normal((200, 16)).astype(np.float32)
+    d2 = ((x[:, None, :].astype(np.float64) - c[None].astype(np.float64)) ** 2).sum(-1)
+    near = np.argsort(d2, axis=1, kind="stable")
+    # lambda = 0, strict: the loss is the distance, so the secondary list is the second nearest
+    got = oracle.rair_assign(c, x, 10, 0.0, True)
+    assert (np.sort(near[:, :2], axis=1) == got).all()
+    # lambda = 0, not strict: the primary list minimises its own loss, the vector is stored once
+    got = oracle.rair_assign(c, x, 10, 0.0, False)
+    assert (got[:, 0] == near[:, 0]).all() and (got[:, 1] == near[:, 0]).all()
+    # one candidate only: nothing to choose, also when strict
+    got = oracle.rair_assign(c, x, 1, 0.5, True)
+    assert (got[:, 0] == near[:, 0]).all() and (got[:, 1] == near[:, 0]).all()
+    # more candidates asked for than lists: all lists are candidates
+    assert (oracle.rair_assign(c, x, 100, 0.5, True) == oracle.rair_assign(c, x, 30, 0.5, True)).all()
+    # hand-worked: v at the origin, c0 = (1, 0) nearest, c1 = (1.1, 0.1) on the same side, c2 =
+    # (-1.5, 0) on the far side.  lambda = 0: second nearest (c1).  lambda = 1: loss1 = 1.22 + 1.1,
+    # loss2 = 2.25 - 1.5, so the list on the far side wins -- the point of the AIR metric.
+    c3 = np.array([[1.0, 0.0], [1.1, 0.1], [-1.5, 0.0]], dtype=np.float32)
+    v0 = np.zeros((1, 2), dtype=np.float32)
+    assert oracle.rair_assign(c3, v0, 3, 0.0, True).tolist() == [[0, 1]]
+    assert oracle.rair_assign(c3, v0, 3, 1.0, True).tolist() == [[0, 2]]
