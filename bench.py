@@ -129,6 +129,49 @@ def bench_pq_encode(args):
                          "kind": "oracle", "sample": f"first {ns} vectors"}}))
 
 
+def bench_assign(args):
+    """RairAssign of the workload's base vectors against the index's centroids: vectors/s and the
+    oracle's rate; the lists chosen are compared with the oracle's on a sample."""
+    import torch
+    from oracle import oracle
+    from paper_2601_07183_amd import binding, datagen, index_build
+    binding.load()
+    w = datagen.WORKLOADS[args.workload]
+    if args.base_size:
+        w = datagen.scaled(w, args.base_size)
+    base = datagen.make_base(w).astype(np.float32, copy=False)
+    # a small index supplies the handle: its centroids are trained on the whole base
+    hx = index_build.build_index(base[: min(len(base), 200_000)], w.nlist, w.M, seed=w.seed, coarse_iters=4,
+                                 pq_iters=2)
+    hx.centroids = index_build.kmeans(base, w.nlist, 20, w.seed * 7 + 1, max_train=256 * w.nlist)
+    ix = binding.Index(hx)
+    dx = torch.from_numpy(base).cuda()
+    n, d = base.shape
+    for _ in range(max(1, args.warmup)):
+        pairs = ix.assign(dx, 10, 0.5, True)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(args.steps):
+        pairs = ix.assign(dx, 10, 0.5, True)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / args.steps
+    ns = min(n, 20_000)
+    t = time.perf_counter()
+    want = oracle.rair_assign(hx.centroids, base[:ns], 10, 0.5, True)
+    cpu_s = time.perf_counter() - t
+    same = bool((pairs[:ns].cpu().numpy() == want).all())
+    print(json.dumps({
+        "metric": "RairAssign rate", "value": round(n / (ms * 1e-3), 1), "unit": "vectors/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "dtype": "f32 coarse, f64 loss", "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={n} d={d} nlist={w.nlist} n_cands=10 lambda=0.5 strict",
+                   "pairs_identical_to_oracle_on_sample": same},
+        "cpu_baseline": {"value": round(ns / cpu_s, 1), "unit": "vectors/s", "cores": oracle.num_threads(),
+                         "kind": "oracle", "sample": f"first {ns} vectors"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,9 +196,14 @@ def main():
     ap.add_argument("--pq-encode", action="store_true",
                     help="measure rairs_pq_encode (a step of index construction) on the workload's base "
                          "vectors instead of the search path; prints a JSON line of its own")
+    ap.add_argument("--assign", action="store_true",
+                    help="measure rairs_assign (RairAssign, a step of index construction) on the "
+                         "workload's base vectors; prints a JSON line of its own")
     args = ap.parse_args()
     if args.pq_encode:
         return bench_pq_encode(args)
+    if args.assign:
+        return bench_assign(args)
     if args.copy_calibration:
         import torch
         n = args.copy_calibration // 4

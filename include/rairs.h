@@ -211,6 +211,21 @@ int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats);
 int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, int64_t *total_bytes);
 
 /*
+ * RairAssign (Alg. 3), a step of index construction: the two lists of each of n vectors.
+ *   d_vectors device [n][d] fp32;  d_pairs device [n][2] int32, the smaller list id first
+ * The candidates are the min(n_cands, nlist) nearest lists as rairs_coarse orders them
+ * (FindNearestLists); loss[i] = ||r_i||^2 + lambda <r_0, r_i> with r_i = centroid_i - v is taken
+ * in float64, both sums in dimension order, no fused multiply-add; the secondary list is the
+ * first minimum over candidates 1.. (strict != 0; the primary list itself when there is no other
+ * candidate) or 0.. (strict == 0: both ids may be equal, the vector is then stored once).
+ * Uses the handle's centroids and workspace (calls on one handle must not overlap); needs
+ * 1 <= n_cands and min(n_cands, nlist) <= RAIRS_MAX_NCANDS.  n == 0 is a successful no-op.
+ */
+#define RAIRS_MAX_NCANDS 32
+int rairs_assign(rairs_index_t *h, const float *d_vectors, int64_t n, int n_cands, double lambda,
+                 int strict, int32_t *d_pairs, void *hip_stream);
+
+/*
  * PQEncoding (Alg. 1; Section 2.2), a step of index construction: the 4-bit codes of n vectors.
  *   d_codebook device [M][16][d/M] fp32;  d_vectors device [n][d] fp32;
  *   d_codes    device [n][M/2] uint8, byte i: sub-quantizer 2i in the low nibble, 2i+1 in the high

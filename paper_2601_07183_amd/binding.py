@@ -23,7 +23,7 @@ MAX_NPROBE = 4096
 EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_coarse", "rairs_lut",
            "rairs_scan", "rairs_refine", "rairs_set_scan_mode", "rairs_set_profiling", "rairs_get_stage_ms",
            "rairs_get_stage_ms_mean",
-           "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_pq_encode",
+           "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_pq_encode", "rairs_assign",
            "rairs_last_error")
 
 
@@ -221,6 +221,17 @@ class Index:
         ms = (C.c_float * len(STAGES))()
         _check(self._lib.rairs_get_stage_ms_mean(self._h, C.c_int(last_n), ms))
         return dict(zip(STAGES, [float(x) for x in ms]))
+
+    def assign(self, vectors: torch.Tensor, n_cands: int = 10, lam: float = 0.5, strict: bool = True,
+               stream=None) -> torch.Tensor:
+        """rairs_assign: [n][2] list ids (smaller first) of device vectors [n][d]."""
+        n = vectors.shape[0]
+        out = torch.empty((n, 2), dtype=torch.int32, device=vectors.device)
+        _check(self._lib.rairs_assign(self._h, _dev(vectors, torch.float32, "vectors") if n else C.c_void_p(0),
+                                      C.c_int64(n), C.c_int(n_cands), C.c_double(lam), C.c_int(int(strict)),
+                                      _dev(out, torch.int32, "pairs") if n else C.c_void_p(0),
+                                      _stream_ptr(stream)))
+        return out
 
     def dco(self, nq: int) -> np.ndarray:
         out = np.empty(nq, dtype=np.int64)

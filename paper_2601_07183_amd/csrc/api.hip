@@ -819,6 +819,34 @@ extern "C" int rairs_debug_cycles(rairs_index_t *h, long long *out)
 }
 #endif
 
+extern "C" int rairs_assign(rairs_index_t *h, const float *d_vectors, int64_t n, int n_cands,
+                            double lambda, int strict, int32_t *d_pairs, void *hip_stream)
+{
+    int rc = check_common(h, n);
+    if (rc) return rc;
+    if (n_cands < 1) FAIL(RAIRS_EINVAL, "n_cands=%d: at least one candidate list", n_cands);
+    const int nc = n_cands < h->v.nlist ? n_cands : h->v.nlist;
+    if (nc > RAIRS_MAX_NCANDS) FAIL(RAIRS_EUNSUPPORTED, "n_cands=%d above the built limit %d", nc, RAIRS_MAX_NCANDS);
+    if (!(lambda == lambda)) FAIL(RAIRS_EINVAL, "lambda is not a number");
+    if (n == 0) return RAIRS_OK;
+    if (!d_vectors || !d_pairs) FAIL(RAIRS_EINVAL, "null device pointer");
+    const int64_t step = pass_size(h->v, n);
+    const WsLayout w = ws_layout(h->v, step, nc, 1);
+    if ((rc = ensure_ws(h, w.total))) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    for (int64_t q0 = 0; q0 < n; q0 += step) {
+        const int64_t m = n - q0 < step ? n - q0 : step;
+        const float *x = d_vectors + (size_t)q0 * h->v.d;
+        int32_t *cand = (int32_t *)((char *)h->ws + w.probe_ids);
+        // FindNearestLists is the search path's coarse quantizer
+        if ((rc = rairs_launch_coarse(h->v, x, m, nc, (float *)((char *)h->ws + w.dmat), cand, nullptr,
+                                      (uint32_t *)((char *)h->ws + w.cflags), s))) return rc;
+        if ((rc = rairs_launch_air_assign(h->v, x, m, nc, lambda, strict ? 1 : 0, cand,
+                                          d_pairs + (size_t)q0 * 2, s))) return rc;
+    }
+    return RAIRS_OK;
+}
+
 extern "C" int rairs_pq_encode(const float *d_codebook, int d, int M, const float *d_vectors, int64_t n,
                                uint8_t *d_codes, void *hip_stream)
 {

@@ -948,6 +948,66 @@ int rairs_launch_pq_encode(const float *cb, int d, int M, const float *x, int64_
 }
 
 // ---------------------------------------------------------------------------------------------
+// RairAssign (Alg. 3): the AIR loss over the nearest lists of a vector (index construction)
+// ---------------------------------------------------------------------------------------------
+
+// cand[v][0 .. nc) are the vector's nearest lists from the coarse quantizer.  One thread per
+// (vector, candidate): loss = ||r_i||^2 + lambda <r_0, r_i>, r_i = centroid_i - v, in float64 with
+// both sums sequential over the dimensions; the first thread of a vector's group then takes the
+// first minimum over candidates 1.. (strict) or 0.. and writes the pair ordered by list id.
+__global__ __launch_bounds__(WG) void air_assign_kernel(IndexView v, const float *__restrict__ x,
+                                                        int64_t n, int nc, int group, double lambda,
+                                                        int strict, const int32_t *__restrict__ cand,
+                                                        int32_t *__restrict__ out)
+{
+    __shared__ double loss_s[WG];
+    const int tid = threadIdx.x, g = tid / group, i = tid % group;
+    const int64_t vec = (int64_t)blockIdx.x * (WG / group) + g;
+    const int d = v.d;
+    double loss = 0.0;
+    if (vec < n && i < nc) {
+        const float *xv = x + (size_t)vec * d;
+        const float *p0 = v.centroids + (size_t)cand[(size_t)vec * nc] * d;
+        const float *pi = v.centroids + (size_t)cand[(size_t)vec * nc + i] * d;
+        double l2 = 0.0, ip = 0.0;
+        for (int t = 0; t < d; t++) {
+            const double xt = (double)xv[t];
+            const double r0 = (double)p0[t] - xt, r = (double)pi[t] - xt;
+            const double rr = r * r, r0r = r0 * r;
+            l2 = l2 + rr;
+            ip = ip + r0r;
+        }
+        const double scaled = lambda * ip;
+        loss = l2 + scaled;
+    }
+    loss_s[tid] = loss;
+    __syncthreads();
+    if (vec < n && i == 0) {
+        const int32_t first = cand[(size_t)vec * nc];
+        int best = -1;
+        double bestloss = 0.0;
+        for (int j = strict ? 1 : 0; j < nc; j++) {
+            const double lj = loss_s[g * group + j];
+            if (best < 0 || lj < bestloss) { best = j; bestloss = lj; }
+        }
+        const int32_t second = best < 0 ? first : cand[(size_t)vec * nc + best];
+        out[2 * vec] = first < second ? first : second;
+        out[2 * vec + 1] = first < second ? second : first;
+    }
+}
+
+int rairs_launch_air_assign(const IndexView &v, const float *x, int64_t n, int nc, double lambda,
+                            int strict, const int32_t *cand, int32_t *out, hipStream_t s)
+{
+    const int group = next_pow2(nc);                     // <= 32: several vectors per workgroup
+    const int per_wg = WG / group;
+    hipLaunchKernelGGL(air_assign_kernel, dim3((unsigned)((n + per_wg - 1) / per_wg)), dim3(WG), 0, s, v, x,
+                       n, nc, group, lambda, strict, cand, out);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Refine (Alg. 2 line 7): exact distances of the candidates, K smallest by (distance, id)
 // ---------------------------------------------------------------------------------------------
 

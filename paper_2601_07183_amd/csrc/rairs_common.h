@@ -182,6 +182,8 @@ struct MfmaScanArgs {
 bool rairs_mfma_supported(const IndexView &v);
 // grouping of the (query, probed list) pairs by list and the unit table, then the scan itself
 int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
+int rairs_launch_air_assign(const IndexView &v, const float *x, int64_t n, int nc, double lambda,
+                            int strict, const int32_t *cand, int32_t *out, hipStream_t s);
 int rairs_launch_pq_encode(const float *cb, int d, int M, const float *x, int64_t n, uint8_t *codes,
                            hipStream_t s);
 int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev);

@@ -334,3 +334,30 @@ def test_pq_encode_matches_the_oracle(binding, d, M):
     with pytest.raises(binding.RairsError):
         binding.pq_encode(_dev(np.zeros((3, 16, 2), dtype=np.float32)), _dev(np.zeros((4, 6), dtype=np.float32)))
 
+
+def test_rair_assign_matches_the_oracle(binding, small_index, small_index_int, tiny_workload):
+    # Alg. 3 on the GPU: candidates from the coarse kernels (full route for 16 lists, matrix-core
+    # shortlist for 64), float64 loss; bit exact, also on integer data with its exact distance ties
+    for which, (base, hx) in (("float", small_index), ("int", small_index_int),
+                              ("tiny", (tiny_workload[1], tiny_workload[3]))):
+        ix = binding.Index(hx)
+        try:
+            g = np.random.Generator(np.random.PCG64(23))
+            x = np.concatenate([base[:700], small_queries(41, 333, hx.d, integer=(which == "int"))])
+            x[3] = hx.centroids[5]                           # a vector that is a centroid: r_0 = 0
+            for n_cands, lam, strict in ((10, 0.5, True), (10, 0.5, False), (1, 0.5, True), (7, 0.0, True),
+                                         (32, 2.0, True), (hx.nlist + 5 if hx.nlist < 28 else 32, 0.25, False)):
+                print(f"case: assign {which} n_cands={n_cands} lambda={lam} strict={strict}", flush=True)
+                got = ix.assign(_dev(x), n_cands, lam, strict)
+                torch.cuda.synchronize()
+                want = oracle.rair_assign(hx.centroids, x, n_cands, lam, strict)
+                assert (got.cpu().numpy() == want).all()
+            assert ix.assign(torch.empty((0, hx.d), device="cuda"), 10, 0.5, True).shape == (0, 2)
+            with pytest.raises(binding.RairsError):
+                ix.assign(_dev(x), 0, 0.5, True)
+            if hx.nlist > 32:
+                with pytest.raises(binding.RairsError):
+                    ix.assign(_dev(x), 33, 0.5, True)
+        finally:
+            ix.free()
+
