@@ -970,7 +970,26 @@ __global__ __launch_bounds__(WG) void air_assign_kernel(IndexView v, const float
         const float *p0 = v.centroids + (size_t)cand[(size_t)vec * nc] * d;
         const float *pi = v.centroids + (size_t)cand[(size_t)vec * nc + i] * d;
         double l2 = 0.0, ip = 0.0;
-        for (int t = 0; t < d; t++) {
+        int t = 0;
+        if ((d & 3) == 0) {
+            // four dimensions per load (rows of d floats, d a multiple of 4, are 16-byte aligned);
+            // the sums still run over the dimensions one after the other
+            for (; t < d; t += 4) {
+                const float4 xa = *(const float4 *)(xv + t), a0 = *(const float4 *)(p0 + t),
+                             ai = *(const float4 *)(pi + t);
+                const float xs[4] = {xa.x, xa.y, xa.z, xa.w}, c0[4] = {a0.x, a0.y, a0.z, a0.w},
+                            ci[4] = {ai.x, ai.y, ai.z, ai.w};
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const double xt = (double)xs[u];
+                    const double r0 = (double)c0[u] - xt, r = (double)ci[u] - xt;
+                    const double rr = r * r, r0r = r0 * r;
+                    l2 = l2 + rr;
+                    ip = ip + r0r;
+                }
+            }
+        }
+        for (; t < d; t++) {
             const double xt = (double)xv[t];
             const double r0 = (double)p0[t] - xt, r = (double)pi[t] - xt;
             const double rr = r * r, r0r = r0 * r;
