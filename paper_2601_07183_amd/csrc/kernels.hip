@@ -1114,12 +1114,104 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
     }
 }
 
+#define REFINE_WAVE_MIN_QUERIES 4096        // batches from this size on: one wave per query
+// The same for small batches: one workgroup per query, its four waves share the candidates (wave w
+// takes candidates w, w + 4, ...) and the workgroup sorts the keys.  With few queries this keeps
+// four times as many waves at work, which is what counts when every wave waits for its row loads.
+__global__ __launch_bounds__(WG) void refine_wg_kernel(IndexView v, const float *__restrict__ q,
+                                                    const int64_t *__restrict__ cand_ids,
+                                                    int refine_k, int k,
+                                                    int64_t *__restrict__ out_ids,
+                                                    float *__restrict__ out_dists)
+{
+    __shared__ uint64_t keys[RAIRS_MAX_REFINE_K];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t qi = blockIdx.x;
+    const float *qq = q + (size_t)qi * v.d;
+    const int n2 = next_pow2(refine_k < 2 ? 2 : refine_k);
+    // Candidate wave + 4 m is the wave's m-th; lane l first fetches the id of the (mb + l)-th
+    // for 64 of them at once, so that the row loads below do not wait for an id load each time.
+    // Four candidates at a time, so that their row loads are in flight together.
+    const int per_wave = n2 / (WG / 64);                 // n2 is a power of two >= 2; 0 for n2 = 2
+    for (int mb = 0; mb < (per_wave > 0 ? per_wave : 1); mb += 64) {
+    int64_t myid = -1;
+    {
+        const int c = wave + (WG / 64) * (mb + lane);
+        if (c < refine_k) myid = cand_ids[(size_t)qi * refine_k + c];
+    }
+    for (int m0 = mb; m0 < mb + 64 && wave + (WG / 64) * m0 < n2; m0 += 4) {
+        const int c0 = wave + (WG / 64) * m0;
+        int64_t id[4];
+        bool ok[4];
+        float p[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int src = m0 - mb + u;                 // < 64: four at a time from a multiple of four
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)myid, src);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)myid >> 32), src);
+            id[u] = (int64_t)(((uint64_t)hi << 32) | lo);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            ok[u] = id[u] >= 0 && id[u] < v.ntotal;
+            if (!ok[u]) id[u] = 0;                       // row 0 is read and discarded
+            p[u] = 0.0f;
+        }
+        const bool any = ok[0] || ok[1] || ok[2] || ok[3];       // wave-uniform
+        if (!any) {
+            // nothing to read (also keeps an empty index untouched)
+        } else if (v.raw_u8) {
+            for (int i = lane; i < v.d; i += 64) {
+                const float qv = qq[i];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    float diff = qv - (float)((const uint8_t *)v.raw)[(size_t)id[u] * v.d + i];
+                    float sq = diff * diff;
+                    p[u] = p[u] + sq;
+                }
+            }
+        } else {
+            for (int i = lane; i < v.d; i += 64) {
+                const float qv = qq[i];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    float diff = qv - ((const float *)v.raw)[(size_t)id[u] * v.d + i];
+                    float sq = diff * diff;
+                    p[u] = p[u] + sq;
+                }
+            }
+        }
+        const float dist = fold_four_rows(p[0], p[1], p[2], p[3], lane);       // row lane >> 4
+        {
+            const int u = lane >> 4, c = c0 + u * (WG / 64);
+            const bool oku = u == 0 ? ok[0] : (u == 1 ? ok[1] : (u == 2 ? ok[2] : ok[3]));
+            const int64_t idu = u == 0 ? id[0] : (u == 1 ? id[1] : (u == 2 ? id[2] : id[3]));
+            // empty: distance bits in the NaN region, id = all ones
+            if ((lane & 15) == 0 && c < n2)
+                keys[c] = oku ? (((uint64_t)__float_as_uint(dist) << 32) | (uint32_t)idu) : ~0ull;
+        }
+    }
+    }
+    __syncthreads();
+    bitonic_sort_lds(keys, n2);
+    for (int i = tid; i < k; i += WG) {
+        uint64_t key = keys[i];
+        bool ok = key != ~0ull;
+        out_ids[(size_t)qi * k + i] = ok ? (int64_t)(uint32_t)key : -1;
+        out_dists[(size_t)qi * k + i] = ok ? __uint_as_float((uint32_t)(key >> 32)) : __builtin_inff();
+    }
+}
+
 int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,
                         int refine_k, int k, int64_t *out_ids, float *out_dists, hipStream_t s)
 {
     const int n2 = next_pow2(refine_k < 2 ? 2 : refine_k);
-    hipLaunchKernelGGL(refine_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
-                       (size_t)(WG / 64) * n2 * 8, s, v, q, cand_ids, nq, refine_k, k, out_ids, out_dists);
+    if (nq >= REFINE_WAVE_MIN_QUERIES)
+        hipLaunchKernelGGL(refine_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
+                           (size_t)(WG / 64) * n2 * 8, s, v, q, cand_ids, nq, refine_k, k, out_ids, out_dists);
+    else
+        hipLaunchKernelGGL(refine_wg_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, q, cand_ids, refine_k,
+                           k, out_ids, out_dists);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
