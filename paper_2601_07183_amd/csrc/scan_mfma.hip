@@ -4,18 +4,25 @@
 //
 // score(query, item) = sum_m lut[query][m][code[item][m]] is a contraction of the lookup tables
 // with the one-hot expansion of the codes:  sum_m sum_c lut[q][m][c] * [code[item][m] == c].
-// One v_mfma_i32_32x32x32_i8 covers 32 items x 32 queries x 2 subspaces (K = 2 x 16 codewords):
-//   A (rows = items):   lane (item, g) holds the 16-byte one-hot of the item's code in subspace
-//                       2t+g, built in registers from the packed nibble;
-//   B (cols = queries): lane (query, g) holds the 16 table bytes lut[q][2t+g][0..15] as signed
-//                       bytes (value - 128; 128 * M is added back after the sum), kept in
-//                       registers for the whole tile.
+// A one-hot row of 16 has one non-zero, so the expansion is 2:4 sparse and the register-table
+// kernel uses the sparse matrix instruction: one v_smfmac_i32_32x32x64_i8 covers 32 items x 32
+// queries x 4 sub-quantizers (K = 4 x 16 codewords):
+//   A (rows = items):   lane (item, h) passes, compressed, positions [16h, 16h+16) and
+//                       [32+16h, 48+16h) of the 64 -- sub-quantizers 4t+h and 4t+2+h, the two
+//                       nibbles of one code byte: 16 kept values and 16 two-bit positions, looked
+//                       up per nibble in a 16-entry LDS table;
+//   B (cols = queries): lane (query, g) holds the 32 table bytes lut[q][4t+2g .. 4t+2g+1][0..15]
+//                       as signed bytes (value - 128; 128 * M is added back after the sum), kept
+//                       in registers for the whole tile.
+// The LDS-table kernel (any M) uses the dense v_mfma_i32_32x32x32_i8, two sub-quantizers per
+// instruction with both operands from LDS.
 // Integer arithmetic throughout, so the scores equal the plain 16-bit sums bit for bit.
 //
-// Work is cut into tasks (list L, tile of <= 32 queries probing L, segment of <= 16 blocks);
-// waves of a persistent grid draw runs of consecutive tasks from a counter.  The dedup rules are
-// the order-free ones of scan_exact.hip.  A score passes when it is <= the query's bound tau;
-// survivors go to the query's buffer and are cut to bigK afterwards by select_kernel.
+// Work is cut into units (list L, tile of <= 32 queries probing L, run of parts of the list; a part
+// is a run of segments of about 32 blocks); waves of a persistent grid draw units from a counter.
+// The dedup rules are the order-free ones of scan_exact.hip.  A score passes when it is <= the
+// query's bound; passing pairs are staged per wave, logged in bulk and cut to bigK afterwards by
+// collect_kernel and the select kernels.
 //
 // The bound.  tau0 = bigK-th smallest score in a sample, the head of the query's first list.  Every
 // survivor that the duplicate rule can never drop (an item of a shared block, or a miscellaneous
