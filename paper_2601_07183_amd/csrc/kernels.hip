@@ -1,6 +1,7 @@
 // HIP kernels (gfx950, wave64) of the RAIRS query path: coarse quantizer, lookup tables,
-// exact SEIL scan with a bounded top-bigK queue, refinement.  Built with -ffp-contract=off:
-// the fp32 operation order below is part of the result's definition.
+// refinement (the scans are in scan_mfma.hip and scan_exact.hip), and of two steps of index
+// construction: PQ encoding and the AIR loss of RairAssign.  Built with -ffp-contract=off: the
+// floating-point operation order below is part of the results' definition.
 #include "device_util.h"
 
 // ---------------------------------------------------------------------------------------------
