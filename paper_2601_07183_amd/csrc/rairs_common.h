@@ -128,6 +128,12 @@ int rairs_launch_bitmap(const IndexView &v, const int32_t *probe_ids, int64_t nq
                         uint32_t *bitmap, int bmwords, uint32_t *hist, hipStream_t s);
 int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lut, float *bias_sum,
                      float *scale, hipStream_t s);
+// construction side (kernels.hip): PQ codes of n vectors (Section 2.1), and the two lists of every
+// vector from its nc nearest centroids `cand` by the AIR loss (Section 4.2, Equation 2)
+int rairs_launch_pq_encode(const float *cb, int d, int M, const float *x, int64_t n, uint8_t *codes,
+                           hipStream_t s);
+int rairs_launch_air_assign(const IndexView &v, const float *x, int64_t n, int nc, double lambda,
+                            int strict, const int32_t *cand, int32_t *out, hipStream_t s);
 // arguments of the exact scan kernel (scan_exact.hip)
 struct ExactScanArgs {
     const uint8_t *lut;           // [nq][M][16]
@@ -182,10 +188,6 @@ struct MfmaScanArgs {
 bool rairs_mfma_supported(const IndexView &v);
 // grouping of the (query, probed list) pairs by list and the unit table, then the scan itself
 int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
-int rairs_launch_air_assign(const IndexView &v, const float *x, int64_t n, int nc, double lambda,
-                            int strict, const int32_t *cand, int32_t *out, hipStream_t s);
-int rairs_launch_pq_encode(const float *cb, int d, int M, const float *x, int64_t n, uint8_t *codes,
-                           hipStream_t s);
 int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev);
 int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
 int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,
