@@ -2,14 +2,67 @@
 single assignment, naive redundant assignment (lambda = 0: the two nearest lists), SRAIR (strict)
 and RAIR (not strict) at a given lambda, all on the same centroids and codebook and all through the
 same GPU search path.  Prints recall@K, distance computations per query (DCO, deterministic) and a
-quick rate per nprobe, as a markdown table.
+quick rate per nprobe, as a markdown table.  With --sweep it varies lambda and N_CANDS instead
+(Figure 14's axes) and prints, per setting, the share of vectors stored twice, the blocks SEIL
+stores against two plain copies (Section 5's saving), and the cheapest nprobe that reaches the
+target recall with its DCO.
 
     python -m paper_2601_07183_amd.ablation --workload sift1m
+    python -m paper_2601_07183_amd.ablation --workload sift1m --sweep
 """
 import argparse
 import time
 
 import numpy as np
+
+
+def plain_blocks(assign: np.ndarray, nlist: int) -> int:
+    """32-item blocks that two plain copies would take: every list stores all of its items itself."""
+    a = np.asarray(assign)
+    cnt = np.bincount(a[:, 0], minlength=nlist)
+    two = a[:, 0] != a[:, 1]
+    cnt = cnt + np.bincount(a[two, 1], minlength=nlist)
+    return int(((cnt + 31) // 32).sum())
+
+
+def cheapest_nprobe(ix, dq, gt, w, target, recall_at_k, top=256):
+    """Smallest nprobe whose recall reaches target (recall grows with nprobe), by bisection."""
+    def at(nprobe):
+        ids, _ = ix.search(dq, w.k, nprobe, w.refine_k)
+        return recall_at_k(ids.cpu().numpy(), gt), float(ix.dco(dq.shape[0]).mean())
+    lo, hi = 0, 1
+    while hi < top and at(hi)[0] < target:
+        lo, hi = hi, hi * 2
+    hi = min(hi, top)
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if at(mid)[0] >= target:
+            hi = mid
+        else:
+            lo = mid
+    return (hi,) + at(hi)
+
+
+def sweep(args, w, base, q, gt, centroids, codebook):
+    import torch
+    from . import binding, index_build as ib
+    import bench
+    dq = torch.from_numpy(q).cuda()
+    print("| lambda | N_CANDS | strict | vectors stored twice | SEIL blocks | two plain copies | saved | "
+          "nprobe for recall %.2f | recall@%d | DCO per query |" % (args.target, w.k))
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    settings = [(lam, 10, True) for lam in (0.0, 0.25, 0.5, 0.75, 1.0)]
+    settings += [(0.5, nc, True) for nc in (2, 5, 20)]
+    settings += [(0.5, 10, False)]
+    for lam, nc, strict in settings:
+        hx = ib.add_vectors(base, centroids, codebook, lam=lam, n_cands=nc, strict=strict)
+        twice = float((hx.assign[:, 0] != hx.assign[:, 1]).mean())
+        plain = plain_blocks(hx.assign, w.nlist)
+        ix = binding.Index(hx)
+        nprobe, rec, dco = cheapest_nprobe(ix, dq, gt, w, args.target, bench.recall_at_k)
+        print(f"| {lam} | {nc} | {strict} | {twice:.3f} | {hx.nblocks:,} | {plain:,} | "
+              f"{1 - hx.nblocks / plain:.1%} | {nprobe} | {rec:.4f} | {dco:,.0f} |", flush=True)
+        ix.free()
 
 
 def main():
@@ -22,6 +75,8 @@ def main():
     ap.add_argument("--base-size", type=int, default=0)
     ap.add_argument("--lam", type=float, default=0.5)
     ap.add_argument("--nprobes", default="4,8,16,32,64")
+    ap.add_argument("--sweep", action="store_true", help="vary lambda and N_CANDS instead")
+    ap.add_argument("--target", type=float, default=0.9, help="recall the sweep searches to")
     args = ap.parse_args()
     binding.load()
     w = datagen.WORKLOADS[args.workload]
@@ -31,6 +86,8 @@ def main():
     gt = bench.ground_truth(base, q, w.k)
     centroids = ib.kmeans(base, w.nlist, 20, w.seed * 7 + 1, max_train=256 * w.nlist)
     codebook = ib.train_pq(base, w.M, 25, w.seed * 7 + 2)
+    if args.sweep:
+        return sweep(args, w, base, q, gt, centroids, codebook)
     near = ib.rair_assign(base, centroids, lam=0.0, n_cands=1, strict=False)       # (nearest, nearest)
     variants = [("single", dict(assign=near)),
                 ("naive RA (lambda 0)", dict(lam=0.0, strict=True)),
