@@ -66,7 +66,7 @@ typedef struct {
     const int64_t *ref_block_begin;
     const int32_t *ref_nblocks;
     const void *raw;                   /* [ntotal][d] f32 or u8 */
-    const int32_t *assign;             /* [ntotal][2] */
+    const int32_t *assign;             /* [ntotal][2]; (-1, -1): the vector was deleted */
     const uint8_t *vec_codes;          /* [ntotal][M/2] */
 } oracle_index;
 
@@ -277,6 +277,7 @@ static int64_t naive_search(const oracle_index *ix, const uint8_t *lut, const in
     const int hb = ix->M / 2;
     int64_t n = 0;
     for (int64_t v = 0; v < ix->ntotal; v++) {
+        if (ix->assign[2 * v] < 0) continue;                /* deleted: in no list */
         if (!probed[ix->assign[2 * v]] && !probed[ix->assign[2 * v + 1]]) continue;
         kv_push(rq, score_code(lut, ix->vec_codes + (size_t)v * hb, ix->M), v);
         if (tr) tr->push_count[v]++;

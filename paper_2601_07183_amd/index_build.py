@@ -372,3 +372,198 @@ def add_vectors(base: np.ndarray, centroids: np.ndarray, codebook: np.ndarray, *
         codebook=np.ascontiguousarray(codebook, dtype=np.float32),
         raw=np.ascontiguousarray(base), assign=assign, vec_codes=vec_codes,
         params=dict(lam=lam, n_cands=n_cands, strict=strict), **lay)
+
+
+# ----------------------------------------------------------------------------------------------
+# Later batches and deletion (Section 5.1's second-batch rules; the deletion rule of Section 6.1)
+# ----------------------------------------------------------------------------------------------
+
+def _block_owner(hx: HostIndex):
+    """Per block: the list that stores it and whether it is a miscellaneous block (-1: unused)."""
+    nb = hx.nblocks
+    owner = np.full(nb, -1, dtype=np.int64)
+    is_misc = np.zeros(nb, dtype=bool)
+    for begin, cnt, misc in ((hx.list_shared_begin, hx.list_shared_cnt, False),
+                             (hx.list_misc_begin, hx.list_misc_cnt, True)):
+        cnt = cnt.astype(np.int64)
+        lists = np.repeat(np.arange(hx.nlist), cnt)
+        blk = np.repeat(begin.astype(np.int64) - (np.cumsum(cnt) - cnt), cnt) + np.arange(int(cnt.sum()))
+        owner[blk] = lists
+        is_misc[blk] = misc
+    return owner, is_misc
+
+
+def append_batch(hx: HostIndex, new: np.ndarray, *, lam: float = 0.5, n_cands: int = 10,
+                 strict: bool = True, assign: np.ndarray | None = None) -> HostIndex:
+    """Add a further batch of vectors to an index; their ids continue after the existing ones.
+
+    The batch is grouped into cells on its own (Alg. 4).  The full blocks of its cells are appended
+    to the shared blocks of the list that stores them and get a NEW reference entry in the other
+    list, after that list's existing entries -- a list may then hold several entries to one owner.
+    Its leftovers are appended to the miscellaneous items of their lists, so the partly filled
+    last block of the earlier batches fills up before a new block starts.  Existing items keep
+    their order.  The result is again one shared range and one miscellaneous range per list, the
+    form the search side reads; block numbers change, ids do not.
+    """
+    n0, nlist = hx.ntotal, hx.nlist
+    new = np.ascontiguousarray(new, dtype=hx.raw.dtype)
+    if assign is None:
+        assign = rair_assign(new, hx.centroids, lam=lam, n_cands=n_cands, strict=strict)
+    assign = np.ascontiguousarray(assign, dtype=np.int32)
+    new_codes = pq_encode(new, hx.codebook)
+    new_ids = np.arange(n0, n0 + new.shape[0], dtype=np.int64)
+    lay = seil_insert(assign, new_codes, new_ids, nlist)
+    hb = hx.codes.shape[2]
+
+    o_sb, o_sc = hx.list_shared_begin.astype(np.int64), hx.list_shared_cnt.astype(np.int64)
+    b_sb, b_sc = lay["list_shared_begin"].astype(np.int64), lay["list_shared_cnt"].astype(np.int64)
+
+    def misc_items(ids, other, codes, mb, mc):
+        """Valid miscellaneous items in list order: (list, flat slot) of each."""
+        mc = mc.astype(np.int64)
+        lists = np.repeat(np.arange(nlist), mc)
+        blk = np.repeat(mb.astype(np.int64) - (np.cumsum(mc) - mc), mc) + np.arange(int(mc.sum()))
+        slots = (blk[:, None] * BLK + np.arange(BLK)[None, :]).reshape(-1)
+        lists = np.repeat(lists, BLK)
+        ok = ids.reshape(-1)[slots] >= 0
+        return lists[ok], slots[ok]
+
+    o_ml, o_ms = misc_items(hx.ids, hx.other, hx.codes, hx.list_misc_begin, hx.list_misc_cnt)
+    b_ml, b_ms = misc_items(lay["ids"], lay["other"], lay["codes"], lay["list_misc_begin"],
+                            lay["list_misc_cnt"])
+    o_mn = np.bincount(o_ml, minlength=nlist).astype(np.int64)
+    b_mn = np.bincount(b_ml, minlength=nlist).astype(np.int64)
+
+    sc = o_sc + b_sc
+    mc = (o_mn + b_mn + BLK - 1) // BLK
+    tot = sc + mc
+    begin = np.concatenate([[0], np.cumsum(tot)[:-1]]).astype(np.int64)
+    sb, mb = begin, begin + sc
+    nblocks = int(tot.sum())
+    codes = np.zeros((nblocks * BLK, hb), dtype=np.uint8)
+    ids = np.full(nblocks * BLK, -1, dtype=np.int64)
+    other = np.full(nblocks * BLK, -1, dtype=np.int32)
+
+    def copy_shared(src, src_sb, src_sc, dst_first):
+        lists = np.repeat(np.arange(nlist), src_sc)
+        k = np.arange(int(src_sc.sum())) - np.repeat(np.cumsum(src_sc) - src_sc, src_sc)
+        s_blk = src_sb[lists] + k
+        d_blk = dst_first[lists] + k
+        s = (s_blk[:, None] * BLK + np.arange(BLK)[None, :]).reshape(-1)
+        t = (d_blk[:, None] * BLK + np.arange(BLK)[None, :]).reshape(-1)
+        codes[t] = src["codes"].reshape(-1, hb)[s]
+        ids[t] = src["ids"].reshape(-1)[s]
+        other[t] = src["other"].reshape(-1)[s]
+
+    old = dict(codes=hx.codes, ids=hx.ids, other=hx.other)
+    copy_shared(old, o_sb, o_sc, sb)
+    copy_shared(lay, b_sb, b_sc, sb + o_sc)
+
+    def copy_misc(src, lists, slots, first_rank):
+        cnt = np.bincount(lists, minlength=nlist)
+        rank = np.arange(lists.size) - np.repeat(np.cumsum(cnt) - cnt, cnt)
+        t = mb[lists] * BLK + first_rank[lists] + rank
+        codes[t] = src["codes"].reshape(-1, hb)[slots]
+        ids[t] = src["ids"].reshape(-1)[slots]
+        other[t] = src["other"].reshape(-1)[slots]
+
+    copy_misc(old, o_ml, o_ms, np.zeros(nlist, dtype=np.int64))
+    copy_misc(lay, b_ml, b_ms, o_mn)
+
+    # reference entries: each list keeps its entries and gets the batch's after them
+    o_rc, b_rc = hx.list_ref_cnt.astype(np.int64), lay["list_ref_cnt"].astype(np.int64)
+    rc = o_rc + b_rc
+    rb = (np.cumsum(rc) - rc).astype(np.int64)
+    nrefs = int(rc.sum())
+    ref_owner = np.zeros(nrefs, dtype=np.int32)
+    ref_block_begin = np.zeros(nrefs, dtype=np.int64)
+    ref_nblocks = np.zeros(nrefs, dtype=np.int32)
+
+    def copy_refs(r_begin, r_cnt, owner, bbegin, nblk, src_sb, dst_first, first_rank):
+        lists = np.repeat(np.arange(nlist), r_cnt)
+        k = np.arange(int(r_cnt.sum())) - np.repeat(np.cumsum(r_cnt) - r_cnt, r_cnt)
+        s = r_begin.astype(np.int64)[lists] + k
+        t = rb[lists] + first_rank[lists] + k
+        own = owner[s].astype(np.int64)
+        ref_owner[t] = own
+        ref_block_begin[t] = dst_first[own] + (bbegin[s].astype(np.int64) - src_sb[own])
+        ref_nblocks[t] = nblk[s]
+
+    copy_refs(hx.list_ref_begin, o_rc, hx.ref_owner, hx.ref_block_begin, hx.ref_nblocks, o_sb, sb,
+              np.zeros(nlist, dtype=np.int64))
+    copy_refs(lay["list_ref_begin"], b_rc, lay["ref_owner"], lay["ref_block_begin"],
+              lay["ref_nblocks"], b_sb, sb + o_sc, o_rc)
+
+    return HostIndex(
+        d=hx.d, M=hx.M, nlist=nlist, ntotal=n0 + new.shape[0], centroids=hx.centroids,
+        codebook=hx.codebook, codes=codes.reshape(nblocks, BLK, hb), ids=ids.reshape(nblocks, BLK),
+        other=other.reshape(nblocks, BLK), list_shared_begin=sb, list_shared_cnt=sc.astype(np.int32),
+        list_misc_begin=mb, list_misc_cnt=mc.astype(np.int32), list_ref_begin=rb,
+        list_ref_cnt=rc.astype(np.int32), ref_owner=ref_owner, ref_block_begin=ref_block_begin,
+        ref_nblocks=ref_nblocks, raw=np.concatenate([hx.raw, new]),
+        assign=np.concatenate([hx.assign, assign]), vec_codes=np.concatenate([hx.vec_codes, new_codes]),
+        params=dict(hx.params))
+
+
+def delete_ids(hx: HostIndex, ids_to_delete) -> HostIndex:
+    """Remove vectors by id, in the order given, one position after the other.
+
+    Every id has up to two positions (one per assigned list that stores it: a shared block is
+    stored once).  A position in a shared block is invalidated in place (id -1; the block stays
+    and is still scored, minus that slot).  A position in a miscellaneous block takes over the
+    last miscellaneous item of the same list, which shrinks the area by one item; a last block
+    that runs empty leaves the list's range (its storage is not reclaimed here).  Ids of other
+    vectors, raw vectors and block numbers do not change; a deleted vector's row of `assign`
+    becomes (-1, -1).
+    """
+    codes = hx.codes.reshape(-1, hx.codes.shape[2]).copy()
+    ids = hx.ids.reshape(-1).copy()
+    other = hx.other.reshape(-1).copy()
+    assign = hx.assign.copy()
+    misc_cnt = hx.list_misc_cnt.copy()
+    owner, is_misc = _block_owner(hx)
+    # id -> its positions
+    slots = np.flatnonzero(ids >= 0)
+    order = np.argsort(ids[slots], kind="stable")
+    slots = slots[order]
+    start = np.searchsorted(ids[slots], np.arange(hx.ntotal + 1))
+    pos = {}                                            # positions of items that were moved
+    misc_n = np.zeros(hx.nlist, dtype=np.int64)         # items in each list's miscellaneous area
+    m_l = owner[slots // BLK][is_misc[slots // BLK]]
+    misc_n += np.bincount(m_l, minlength=hx.nlist)
+    misc_begin = hx.list_misc_begin.astype(np.int64)
+    for x in np.asarray(ids_to_delete, dtype=np.int64).reshape(-1):
+        if x < 0 or x >= hx.ntotal or assign[x, 0] < 0:
+            raise KeyError(f"id {int(x)} is not in the index")
+        where = pos.pop(int(x), None)
+        if where is None:
+            where = [int(p) for p in slots[start[x]:start[x + 1]]]
+        for p in where:
+            assert ids[p] == x
+            if not is_misc[p // BLK]:
+                ids[p] = -1
+                continue
+            L = int(owner[p // BLK])
+            last = int(misc_begin[L] * BLK + misc_n[L] - 1)
+            if last != p:
+                y = int(ids[last])
+                codes[p], ids[p], other[p] = codes[last], y, other[last]
+                wy = pos.get(y)
+                if wy is None:
+                    wy = [int(t) for t in slots[start[y]:start[y + 1]]]
+                pos[y] = [p if t == last else t for t in wy]
+            ids[last], other[last] = -1, -1
+            codes[last] = 0
+            misc_n[L] -= 1
+            misc_cnt[L] = (misc_n[L] + BLK - 1) // BLK
+        assign[x] = -1
+    nb = hx.nblocks
+    return HostIndex(
+        d=hx.d, M=hx.M, nlist=hx.nlist, ntotal=hx.ntotal, centroids=hx.centroids,
+        codebook=hx.codebook, codes=codes.reshape(nb, BLK, -1), ids=ids.reshape(nb, BLK),
+        other=other.reshape(nb, BLK), list_shared_begin=hx.list_shared_begin,
+        list_shared_cnt=hx.list_shared_cnt, list_misc_begin=hx.list_misc_begin,
+        list_misc_cnt=misc_cnt.astype(np.int32), list_ref_begin=hx.list_ref_begin,
+        list_ref_cnt=hx.list_ref_cnt, ref_owner=hx.ref_owner, ref_block_begin=hx.ref_block_begin,
+        ref_nblocks=hx.ref_nblocks, raw=hx.raw, assign=assign, vec_codes=hx.vec_codes,
+        params=dict(hx.params))
