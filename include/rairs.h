@@ -46,14 +46,16 @@ typedef enum {
 #define RAIRS_MAX_D        2048
 
 /*
- * Canonical host layout written by SeilInsert (Alg. 4) for one batch; all arrays are host
- * memory owned by the caller and may be released as soon as rairs_index_upload returns.
+ * Canonical host layout written by SeilInsert (Alg. 4); all arrays are host memory owned by the
+ * caller and may be released as soon as rairs_index_upload returns.
  *
  * Blocks hold 32 items (BLK_SZ).  List L owns blocks [list_shared_begin[L], +list_shared_cnt[L])
  * -- the full blocks of every cell (L, j), stored once -- and [list_misc_begin[L],
- * +list_misc_cnt[L]) -- leftovers of all cells touching L; only the last of these may have empty
- * slots (id -1).  Reference entries [list_ref_begin[L], +list_ref_cnt[L]) of list L each name the
- * blocks of a cell (owner, L), owner < L, stored in list `owner` (Section 5.1).
+ * +list_misc_cnt[L]) -- leftovers of all cells touching L; of these only the last may have empty
+ * slots (id -1), at its end.  Reference entries [list_ref_begin[L], +list_ref_cnt[L]) of list L
+ * each name blocks of a cell (owner, L), owner < L, stored in list `owner` (Section 5.1); after
+ * several insertion batches a list may hold more than one entry to the same owner.  A slot of a
+ * shared block whose item was deleted holds id -1 (Section 6.1's deletion rule) and is skipped.
  * The leftover items of a cell (i, j), i != j, sit in the miscellaneous areas of BOTH lists, with
  * the same code, tagged with the other list (Section 5.1); the scan relies on this pairing when
  * it bounds scores from a sample of a list.  It is not checked at upload.

@@ -97,15 +97,16 @@ static int validate(const rairs_host_index_t *x)
         if (n < 1 || b < ob || b + n > ob + oc)
             FAIL(RAIRS_EINVAL, "reference %lld does not point into its owner's shared blocks", (long long)r);
     }
-    // empty slots may only form the tail of a list's last block (the kernels rely on it)
+    // a shared block may hold invalidated slots anywhere (deletion leaves them); the miscellaneous
+    // items of a list are dense: only the tail of its last block is empty
     for (int l = 0; l < x->nlist; l++) {
-        const int64_t b0 = x->list_shared_begin[l];
-        const int64_t b1 = b0 + x->list_shared_cnt[l] + x->list_misc_cnt[l];
+        const int64_t b0 = x->list_misc_begin[l];
+        const int64_t b1 = b0 + x->list_misc_cnt[l];
         bool seen_empty = false;
         for (int64_t i = b0 * 32; i < b1 * 32; i++) {
             const bool empty = x->ids[i] < 0;
             if ((empty && i < (b1 - 1) * 32) || (!empty && seen_empty))
-                FAIL(RAIRS_EINVAL, "list %d: empty slots must be the tail of its last block", l);
+                FAIL(RAIRS_EINVAL, "list %d: empty miscellaneous slots must be the tail of its last block", l);
             seen_empty |= empty;
         }
     }
@@ -247,7 +248,12 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
         for (int64_t i = b0 * 32; i < b1 * 32; i++) valid += x->ids[i] >= 0;
         e2.valid_items = (int32_t)valid;
     }
-    std::vector<uint32_t> hm((size_t)x->nblocks, 0u);
+    std::vector<uint32_t> hm((size_t)x->nblocks, 0u), hv((size_t)x->nblocks, 0u);
+    for (int64_t b = 0; b < x->nblocks; b++) {
+        uint32_t m = 0;
+        for (int i = 0; i < 32; i++) m |= (uint32_t)(x->ids[b * 32 + i] >= 0) << i;
+        hv[(size_t)b] = m;
+    }
     for (int l = 0; l < x->nlist; l++) {
         const int64_t b0 = x->list_shared_begin[l], bs = b0 + x->list_shared_cnt[l];
         const int64_t b1 = bs + x->list_misc_cnt[l];
@@ -267,6 +273,10 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
         hr[(size_t)r].owner = x->ref_owner[r];
         hr[(size_t)r].blk_begin = (int32_t)x->ref_block_begin[r];
         hr[(size_t)r].nblocks = x->ref_nblocks[r];
+        int32_t valid = 0;
+        for (int64_t b = x->ref_block_begin[r]; b < x->ref_block_begin[r] + x->ref_nblocks[r]; b++)
+            valid += __builtin_popcount(hv[(size_t)b]);
+        hr[(size_t)r].valid = valid;
     }
     // scan segments: the list's own blocks, then each referenced cell, in runs of <= 16 blocks
     std::vector<SegEntry> hs;
@@ -282,8 +292,13 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
             int mf = e2.shared_cnt - b;
             se.misc_from = mf < 0 ? 0 : (mf > se.nblk ? se.nblk : mf);
             se.owner = -1;
-            // only the list's very last block may have empty slots, and they are filled from 0
-            se.tail_valid = b + se.nblk == own ? e2.valid_items - 32 * (own - 1) : 32;
+            // the list's very last block usually ends in empty slots: the scan drops those rows
+            // early; any other empty slot (an invalidated item) is dropped when ids are read
+            se.tail_valid = 32;
+            if (b + se.nblk == own) {
+                const uint32_t m = hv[(size_t)(e2.blk_begin + own - 1)];
+                if ((m & (m + 1u)) == 0u) se.tail_valid = __builtin_popcount(m);
+            }
             hs.push_back(se);
         }
         for (int r = 0; r < e2.ref_cnt; r++) {
@@ -328,10 +343,13 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_CHECK(dev_alloc(h, (void **)&segs, hs.size() * sizeof(SegEntry)));
     if (!hs.empty())
         UP_HIP(hipMemcpyAsync(segs, hs.data(), hs.size() * sizeof(SegEntry), hipMemcpyHostToDevice, s));
-    uint32_t *cmask = nullptr;
+    uint32_t *cmask = nullptr, *vmask = nullptr;
     UP_CHECK(dev_alloc(h, (void **)&cmask, (size_t)x->nblocks * 4));
-    if (x->nblocks)
+    UP_CHECK(dev_alloc(h, (void **)&vmask, (size_t)x->nblocks * 4));
+    if (x->nblocks) {
         UP_HIP(hipMemcpyAsync(cmask, hm.data(), hm.size() * 4, hipMemcpyHostToDevice, s));
+        UP_HIP(hipMemcpyAsync(vmask, hv.data(), hv.size() * 4, hipMemcpyHostToDevice, s));
+    }
     UP_HIP(hipMemcpyAsync(lists, hl.data(), hl.size() * sizeof(ListEntry), hipMemcpyHostToDevice, s));
     if (x->nrefs)
         UP_HIP(hipMemcpyAsync(refs, hr.data(), hr.size() * sizeof(RefEntry), hipMemcpyHostToDevice, s));
@@ -367,7 +385,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_HIP(hipStreamSynchronize(s));
 
     v.idtag = idtag;
-    v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask;
+    v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask; v.vmask = vmask;
     v.lists = lists; v.refs = refs; v.segs = segs; v.parts = parts; v.raw = raw;
     for (int r = 0; r < RAIRS_EV_RING; r++)
         for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[r][i]));

@@ -34,7 +34,8 @@ struct SegEntry {
     int32_t nblk;
     int32_t misc_from;     // blocks [misc_from, nblk) of the run are miscellaneous blocks
     int32_t owner;         // -1: the list's own blocks; else the owning list of a referenced cell
-    int32_t tail_valid;    // item slots in use in the run's last block (32 unless it ends the list)
+    int32_t tail_valid;    // leading slots in use in the run's last block when the rest of it is empty
+                           // (else 32: the run does not end its list, or the block has gaps)
 };
 
 // Reference entry of list j to the blocks of cell (owner, j) stored in list `owner`.
@@ -42,6 +43,7 @@ struct RefEntry {
     int32_t owner;
     int32_t blk_begin;
     int32_t nblocks;
+    int32_t valid;         // slots of these blocks that hold an item (all, until items are deleted)
 };
 
 // Device view handed to kernels by value.
@@ -64,6 +66,7 @@ struct IndexView {
     // [nblocks] bit i: slot i holds an item that the duplicate rule can never drop (a shared
     // block's item, or a miscellaneous item whose other list has no smaller id than the list)
     const uint32_t *cmask;
+    const uint32_t *vmask;        // [nblocks] bit i: slot i holds an item
     const ListEntry *lists;       // [nlist]
     const RefEntry *refs;         // [nrefs]
     const SegEntry *segs;         // [nsegs]

@@ -199,21 +199,20 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
     }
     __syncthreads();
     const int L = probe_ids[(size_t)qi * nprobe];
-    int cnt = 0, nitems = 0;
+    int cnt = 0;
     int64_t begin = 0;
     if (L >= 0 && L < v.nlist) {
         const ListEntry le = v.lists[L];
         begin = le.blk_begin;
         cnt = le.shared_cnt + le.misc_cnt;
         cnt = cnt < sample_blocks ? cnt : sample_blocks;
-        nitems = le.valid_items;                        // item slots in use in the list's own blocks
     }
     uint32_t nvalid = 0;
-    // only the tail of a list's last block can be empty: slot s is in use iff s < valid_items
+    // slots without an item (the tail of the list's last block, invalidated items) do not count
 #define SAMPLE_STORE(blk_, part_)                                                              \
     do {                                                                                       \
         const uint32_t acc_ = (part_) + (uint32_t)__shfl_xor((int)(part_), 32);                \
-        const bool valid_ = lane < 32 && (blk_) < cnt && (blk_) * 32 + lane < nitems;          \
+        const bool valid_ = lane < 32 && (blk_) < cnt && ((v.vmask[begin + (blk_)] >> lane) & 1u); \
         if (lane < 32 && (blk_) < cnt) sc[(blk_) * 32 + lane] = valid_ ? (uint16_t)acc_ : (uint16_t)0xFFFFu; \
         nvalid += (uint32_t)__popcll(__ballot(valid_));                                        \
     } while (0)
@@ -304,8 +303,8 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
         if (bound) bound[qi] = (int32_t)t;
     }
     // DCO of the query (distance computations of the scan, Section 6.1): every valid slot of the
-    // own blocks of each probed list, plus 32 per block of each reference entry whose owner is not
-    // probed.  Lanes over the probes.
+    // own blocks of each probed list, plus the valid slots of the blocks of each reference entry
+    // whose owner is not probed.  Lanes over the probes.
     if (dco) {
         const uint32_t *bm = bitmap + (size_t)qi * bmwords;
         unsigned long long c = 0;
@@ -316,7 +315,7 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
             c += (unsigned long long)le.valid_items;
             for (int r = 0; r < le.ref_cnt; r++) {
                 const RefEntry re = v.refs[le.ref_begin + r];
-                if (!((bm[re.owner >> 5] >> (re.owner & 31)) & 1u)) c += 32ull * re.nblocks;
+                if (!((bm[re.owner >> 5] >> (re.owner & 31)) & 1u)) c += (unsigned long long)re.valid;
             }
         }
 #pragma unroll

@@ -146,6 +146,34 @@ def test_adversarial_layouts(binding):
             _compare_all_stages(binding, hx, q, 5, nprobe, 40)
 
 
+@pytest.mark.parametrize("d,M,strict", [(16, 8, True), (16, 8, False), (128, 64, True)])
+def test_search_after_later_batches_and_deletion(binding, d, M, strict):
+    # an index that grew in three batches, lost a quarter of its vectors (holes in shared blocks,
+    # moved miscellaneous items, lists with several entries to one owner) and then grew again
+    g = np.random.Generator(np.random.PCG64(d + M))
+    centers = g.integers(30, 220, size=(10, d))
+    pick = lambda n: np.rint(np.clip(centers[g.integers(0, 10, size=n)] + g.normal(0, 25, size=(n, d)),
+                                     0, 255)).astype(np.float32)
+    base, q = pick(6400), pick(45)
+    hx = ib.build_index(base[:3000], 20, M, seed=5, coarse_iters=5, pq_iters=5, strict=strict)
+    hx = ib.append_batch(hx, base[3000:4500], strict=strict)
+    hx = ib.append_batch(hx, base[4500:6000], strict=strict)
+    for nprobe, refine_k, k in ((3, 100, 10), (20, 60, 10)):
+        _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
+    gone = g.choice(hx.ntotal, size=1500, replace=False)
+    # and every item of the largest list's first shared blocks, which the bound's sample reads
+    big = int(np.argmax(hx.list_shared_cnt))
+    first = hx.ids[hx.list_shared_begin[big]:hx.list_shared_begin[big] + 2].reshape(-1)
+    gone = np.unique(np.concatenate([gone, first[first >= 0]]))
+    hx = ib.delete_ids(hx, gone)
+    for nprobe, refine_k, k in ((1, 100, 10), (3, 100, 10), (7, 40, 40), (20, 1024, 10)):
+        want = _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
+        assert not np.isin(want.ids, gone).any()
+    hx = ib.append_batch(hx, base[6000:], strict=strict)
+    for nprobe, refine_k, k in ((3, 100, 10), (20, 60, 10)):
+        _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
+
+
 @pytest.mark.parametrize("count", [600, 3000, 6000])
 def test_identical_codes_tie_on_score(binding, count):
     # every vector identical: all scores tie, the order is decided by vector id alone, and every
