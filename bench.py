@@ -172,6 +172,83 @@ def bench_assign(args):
                          "kind": "oracle", "sample": f"first {ns} vectors"}}))
 
 
+def bench_incremental(args):
+    """Search over an index that grew and shrank (the set-up of the paper's insertion/deletion
+    experiment, Section 6.2: 800,000 vectors, then five batches of 40,000 insertions, then five
+    batches of 40,000 deletions), timed and checked after each phase.  The mutations themselves
+    run in the host builder; what is measured is the GPU search path on the resulting layouts."""
+    import torch
+    from paper_2601_07183_amd import binding, datagen, index_build as ib
+    from oracle import oracle
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.load()
+    w = datagen.WORKLOADS[args.workload]
+    if args.base_size:
+        w = datagen.scaled(w, args.base_size)
+    nprobe = args.nprobe or 23
+    base, queries = datagen.make_base(w), datagen.make_queries(w)
+    n0, nb = int(w.n * 0.8), int(w.n * 0.04)
+    dq = torch.from_numpy(queries).cuda()
+    nq = len(queries)
+    phases = []
+
+    def measure(name, hx, live, host_sec, host_items):
+        keep = np.flatnonzero(live)
+        gt = keep[ground_truth(base[keep], queries, w.k)]
+        ix = binding.Index(hx)
+        ids, _ = ix.search(dq, w.k, nprobe, w.refine_k)
+        for _ in range(args.warmup):
+            ix.search(dq, w.k, nprobe, w.refine_k)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            ix.search(dq, w.k, nprobe, w.refine_k)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t) / args.steps
+        got = ids.cpu().numpy()
+        ncpu = args.cpu_queries or 100
+        want = oracle.search(oracle.OracleIndex(hx), queries[:ncpu], w.k, nprobe, w.refine_k)
+        code_bytes, _ = ix.bytes()
+        point = {"phase": name, "vectors": int(live.sum()), "nblocks": hx.nblocks, "nrefs": hx.nrefs,
+                 "code_bytes": code_bytes, "recall_at_10": round(recall_at_k(got, gt), 4),
+                 "qps": round(nq / sec, 1), "ms_per_step": round(sec * 1e3, 4),
+                 "dco_per_query": float(ix.dco(nq).mean()),
+                 "ids_identical_to_oracle_on_sample": bool((got[:ncpu] == want.ids).all()),
+                 "host_builder_items_per_s": None if not host_items else round(host_items / host_sec, 1)}
+        ix.free()
+        log(f"[bench] {point}")
+        phases.append(point)
+
+    t = time.perf_counter()
+    hx = ib.build_index(base[:n0], w.nlist, w.M, seed=w.seed)
+    live = np.zeros(w.n, dtype=bool)
+    live[:n0] = True
+    measure("built", hx, live[:hx.ntotal], time.perf_counter() - t, 0)
+    t = time.perf_counter()
+    for b in range(5):
+        hx = ib.append_batch(hx, base[n0 + b * nb:n0 + (b + 1) * nb])
+    live[:hx.ntotal] = True
+    measure("after 5 insertion batches", hx, live[:hx.ntotal], time.perf_counter() - t, 5 * nb)
+    one = ib.add_vectors(base[:hx.ntotal], hx.centroids, hx.codebook)
+    measure("same vectors in one batch", one, live[:hx.ntotal], 1.0, 0)
+    g = np.random.Generator(np.random.PCG64(w.seed + 5))
+    gone = g.choice(hx.ntotal, size=5 * nb, replace=False)
+    t = time.perf_counter()
+    for b in range(5):
+        hx = ib.delete_ids(hx, gone[b * nb:(b + 1) * nb])
+    live[gone] = False
+    measure("after 5 deletion batches", hx, live[:hx.ntotal], time.perf_counter() - t, 5 * nb)
+    print(json.dumps({"metric": f"QPS over a grown and thinned index ({w.name}, 1 GPU, nprobe {nprobe})",
+                      "value": phases[-1]["qps"], "unit": "queries/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup,
+                      "ms_per_step": phases[-1]["ms_per_step"], "higher_is_better": True,
+                      "dtype": "i8", "data": "synthetic",
+                      "config": {"workload": f"{w.name}: {n0} vectors, then 5 x {nb} inserted, then "
+                                             f"5 x {nb} deleted; nq={nq} k={w.k} refine_k={w.refine_k}",
+                                 "nprobe": nprobe},
+                      "phases": phases}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,7 +276,12 @@ def main():
     ap.add_argument("--assign", action="store_true",
                     help="measure rairs_assign (RairAssign, a step of index construction) on the "
                          "workload's base vectors; prints a JSON line of its own")
+    ap.add_argument("--incremental", action="store_true",
+                    help="search over an index that grew by five insertion batches and then lost five "
+                         "deletion batches (Section 6.2's set-up); prints a JSON line of its own")
     args = ap.parse_args()
+    if args.incremental:
+        return bench_incremental(args)
     if args.pq_encode:
         return bench_pq_encode(args)
     if args.assign:
