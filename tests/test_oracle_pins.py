@@ -430,3 +430,40 @@ def test_rair_assign_special_cases():
     v0 = np.zeros((1, 2), dtype=np.float32)
     assert oracle.rair_assign(c3, v0, 3, 0.0, True).tolist() == [[0, 1]]
     assert oracle.rair_assign(c3, v0, 3, 1.0, True).tolist() == [[0, 2]]
+
+
+def test_air_metric_ranks_like_the_loss_it_stands_for():
+    # Section 4.2 defines the loss of a second centroid c' as the mean over queries q, uniform in
+    # a ball around x, of ReLU(-cos(angle q x c)) * (|q - c'|^2 - |q - x|^2), and Theorem 1 replaces
+    # it by |r'|^2 + lambda r.r' (r = c - x, r' = c' - x).  Here the mean is taken by Monte Carlo
+    # from that definition (same queries for every c'), the two coefficients are fitted, and the
+    # oracle's assignment at the fitted lambda has to pick the c' of least sampled loss.
+    g = np.random.Generator(np.random.PCG64(31))
+    d, nq = 6, 400000
+    u = g.standard_normal((nq, d))
+    u *= (g.uniform(0, 1, nq) ** (1.0 / d) / np.linalg.norm(u, axis=1))[:, None] * 1.5   # ball, radius 1.5
+    for trial in range(6):
+        x = g.standard_normal(d)
+        r = g.standard_normal(d)
+        r *= 1.0 / np.linalg.norm(r)                       # the nearest centroid, at distance 1
+        others = g.standard_normal((9, d))
+        others *= (g.uniform(1.05, 1.6, 9) / np.linalg.norm(others, axis=1))[:, None]
+        others[0] = 1.06 * r + 0.02 * others[0]            # second nearest, on the same side as c
+        rp = np.concatenate([r[None], others])             # candidates' residuals, nearest first
+        w = np.maximum(0.0, -(u @ r) / (np.linalg.norm(u, axis=1) * np.linalg.norm(r)))
+        gain = ((u[:, None, :] - rp[None, 1:, :]) ** 2).sum(-1) - (u * u).sum(-1)[:, None]
+        loss_mc = (w[:, None] * gain).mean(0)              # [9] sampled loss of each second centroid
+        feats = np.stack([(rp[1:] ** 2).sum(1), rp[1:] @ r], 1)
+        (a, b), res, _, _ = np.linalg.lstsq(feats, loss_mc, rcond=None)
+        assert a > 0 and b > 0                             # lambda = b / a > 0, as the theorem says
+        # the sampled loss is the two-term form up to sampling noise (about nq ** -0.5)
+        noise = np.abs(feats @ [a, b] - loss_mc).max()
+        assert noise < 3e-3 * np.abs(loss_mc).max()
+        lam = b / a
+        cents = (x[None] + rp).astype(np.float32)
+        got = oracle.rair_assign(cents, x[None].astype(np.float32), 10, float(lam), True)
+        best = 1 + int(np.argmin(loss_mc))
+        order = np.sort(loss_mc)
+        assert order[1] - order[0] > 4 * noise             # a clear winner
+        assert got.tolist() == [[0, best]]
+        assert best != 1                                   # never the second nearest here: it lies on c's side
