@@ -294,7 +294,16 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": n * 4, "copy_bytes_written": n * 4, "repeats": 3}))
+        # the same copy, timed: what a plain streaming kernel reaches on this device (read + write)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        gbs = 10 * 2 * n * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        print(json.dumps({"copy_bytes_read": n * 4, "copy_bytes_written": n * 4, "repeats": 3,
+                          "timed_repeats": 10, "copy_read_plus_write_GBs": round(gbs, 1)}))
         return
     if args.gpus != 1:
         log("bench.py measures one GPU; this build has no multi-GPU path (see DESIGN.md). "
