@@ -623,8 +623,13 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     // bound of every query from a sample (the head of its first list), and the DCO of all probes
     ma.p_first = 0;
     ma.bound = (int32_t *)(ws + w.bound);
-    // about five times bigK items, so that the bigK-th smallest of them is a low quantile
-    int sample_blocks = (5 * refine_k + 31) / 32;
+    // five to ten times bigK items, so that the bigK-th smallest of them is a low quantile: a
+    // larger sample starts the scan with a tighter bound (fewer survivors staged and logged) but
+    // the sample kernel sits on the critical path; ten times pays up to about 1,024 items
+    // (measured: 32 blocks beat 16 and 48 at bigK = 100, 63 beat 96 at bigK = 400)
+    int sample_items = 10 * refine_k < 1024 ? 10 * refine_k : 1024;
+    if (sample_items < 5 * refine_k) sample_items = 5 * refine_k;
+    int sample_blocks = (sample_items + 31) / 32;
     if (sample_blocks < RAIRS_SAMPLE_BLOCKS) sample_blocks = RAIRS_SAMPLE_BLOCKS;
     if (overlap) {
         if ((rc = rairs_launch_group(v, ma, h->side))) return rc;
