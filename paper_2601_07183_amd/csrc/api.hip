@@ -55,6 +55,8 @@ static void destroy(rairs_index *h)
     if (h->side_ready) {
         (void)hipEventDestroy(h->ev_fork); (void)hipEventDestroy(h->ev_lut);
         (void)hipEventDestroy(h->ev_probe); (void)hipEventDestroy(h->ev_group);
+        (void)hipEventDestroy(h->ev_bitmap);
+        (void)hipEventDestroy(h->ev_dco);
         (void)hipStreamDestroy(h->side);
     }
     delete h;
@@ -396,6 +398,8 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_HIP(hipEventCreateWithFlags(&h->ev_lut, hipEventDisableTiming));
     UP_HIP(hipEventCreateWithFlags(&h->ev_probe, hipEventDisableTiming));
     UP_HIP(hipEventCreateWithFlags(&h->ev_group, hipEventDisableTiming));
+    UP_HIP(hipEventCreateWithFlags(&h->ev_bitmap, hipEventDisableTiming));
+    UP_HIP(hipEventCreateWithFlags(&h->ev_dco, hipEventDisableTiming));
     h->side_ready = 1;
     *out = h;
     return RAIRS_OK;
@@ -424,9 +428,27 @@ extern "C" int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, in
 struct WsLayout {
     size_t dmat, cflags, probe_ids, probe_dists, bitmap, lut, cand;
     size_t lcount, loff, lcursor, toff, unit_list, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, prof, total;
+    size_t s_off, s_toff, s_q, s_tiles, s_scores;      // matrix-core sample (0 bytes when not used)
+    int sample_blocks;
     int log_chunks;
     int bmwords;
 };
+
+// Blocks of the first probed list that seed a query's bound: several times bigK items, so that the
+// bigK-th smallest of them is a low quantile.  A larger sample starts the scan with a tighter bound
+// (fewer survivors staged and logged) but the sample sits on the critical path.  With the bound
+// kernel scoring it, ten times bigK pays up to about 1,024 items (measured: 32 blocks beat 16 and
+// 48 at bigK = 100, 63 beat 96 at bigK = 400); scored on the matrix cores it is cheaper and
+// fifteen times, up to about 1,536 items, is better (48 blocks beat 32 and 64 at bigK = 100).
+static int sample_blocks_for(int refine_k, bool grouped)
+{
+    const int times = grouped ? 15 : 10, most = grouped ? 1536 : 1024;
+    int items = times * refine_k < most ? times * refine_k : most;
+    if (items < 5 * refine_k) items = 5 * refine_k;
+    int blocks = (items + 31) / 32;
+    if (blocks < RAIRS_SAMPLE_BLOCKS) blocks = RAIRS_SAMPLE_BLOCKS;
+    return blocks < RAIRS_SAMPLE_MAX_BLOCKS ? blocks : RAIRS_SAMPLE_MAX_BLOCKS;
+}
 
 static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine_k, int max_parts = 1)
 {
@@ -459,6 +481,13 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     w.chunk_fill = take((size_t)w.log_chunks * 4);
     w.log_misc = take(64);
     w.prof = take(2048 * 12 * 8);
+    const bool grouped = rairs_sample_scores_supported(v, nq);
+    w.sample_blocks = sample_blocks_for(refine_k, grouped);
+    w.s_off = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
+    w.s_toff = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
+    w.s_q = take(grouped ? (size_t)nq * 4 : 0);
+    w.s_tiles = take(grouped ? ((size_t)nq / 32 + (size_t)v.nlist + 1) * 4 : 0);
+    w.s_scores = take(grouped ? (size_t)nq * w.sample_blocks * 64 : 0);
     w.total = off;
     return w;
 }
@@ -575,6 +604,8 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     uint32_t *bitmap = (uint32_t *)(ws + w.bitmap);
     int rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, bitmap, w.bmwords, (uint32_t *)(ws + w.hist), s);
     if (rc) return rc;
+    // the DCO kernel, on the side stream when the sample is grouped, reads the bitmaps
+    if (overlap && dco && rairs_sample_scores_supported(v, n)) RAIRS_HIP(hipEventRecord(h->ev_bitmap, s));
     if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, lut_done, 0));
     ExactScanArgs ea;
     memset(&ea, 0, sizeof(ea));
@@ -623,20 +654,37 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     // bound of every query from a sample (the head of its first list), and the DCO of all probes
     ma.p_first = 0;
     ma.bound = (int32_t *)(ws + w.bound);
-    // five to ten times bigK items, so that the bigK-th smallest of them is a low quantile: a
-    // larger sample starts the scan with a tighter bound (fewer survivors staged and logged) but
-    // the sample kernel sits on the critical path; ten times pays up to about 1,024 items
-    // (measured: 32 blocks beat 16 and 48 at bigK = 100, 63 beat 96 at bigK = 400)
-    int sample_items = 10 * refine_k < 1024 ? 10 * refine_k : 1024;
-    if (sample_items < 5 * refine_k) sample_items = 5 * refine_k;
-    int sample_blocks = (sample_items + 31) / 32;
-    if (sample_blocks < RAIRS_SAMPLE_BLOCKS) sample_blocks = RAIRS_SAMPLE_BLOCKS;
+    const int sample_blocks = w.sample_blocks;
+    // The sample's scores come from the matrix cores, for queries grouped by their first list,
+    // when the batch is large enough for that; else the bound kernel scores them itself, one
+    // query per wave.  Side stream: the scan's grouping, then the DCO.
+    const bool grouped = rairs_sample_scores_supported(v, n);
+    int32_t *s_off = (int32_t *)(ws + w.s_off), *s_toff = (int32_t *)(ws + w.s_toff);
+    int32_t *s_q = (int32_t *)(ws + w.s_q), *s_tiles = (int32_t *)(ws + w.s_tiles);
+    uint16_t *s_scores = (uint16_t *)(ws + w.s_scores);
+    const bool side_dco = overlap && grouped && dco;
     if (overlap) {
         if ((rc = rairs_launch_group(v, ma, h->side))) return rc;
         RAIRS_HIP(hipEventRecord(h->ev_group, h->side));
+        if (side_dco) {
+            RAIRS_HIP(hipStreamWaitEvent(h->side, h->ev_bitmap, 0));
+            if ((rc = rairs_launch_dco(v, probe_ids, nprobe, bitmap, w.bmwords, n, dco, h->side))) return rc;
+            RAIRS_HIP(hipEventRecord(h->ev_dco, h->side));
+        }
     }
-    if ((rc = rairs_launch_sample_bound(v, lut, probe_ids, nprobe, refine_k, sample_blocks, n,
-                                        (int32_t *)(ws + w.tau), ma.bound, bitmap, w.bmwords, dco, s)))
+    if (grouped) {
+        if ((rc = rairs_launch_sample_group(v, probe_ids, nprobe, n, s_off, s_toff, s_q, s_tiles, s)))
+            return rc;
+        if ((rc = rairs_launch_sample_scores(v, lut, sample_blocks, n, s_off, s_toff, s_q, s_tiles, s_scores, s)))
+            return rc;
+        if ((rc = rairs_launch_sample_rank(v, probe_ids, nprobe, refine_k, sample_blocks, n, s_scores,
+                                           (int32_t *)(ws + w.tau), ma.bound, s)))
+            return rc;
+        if (dco && !side_dco &&
+            (rc = rairs_launch_dco(v, probe_ids, nprobe, bitmap, w.bmwords, n, dco, s)))
+            return rc;
+    } else if ((rc = rairs_launch_sample_bound(v, lut, probe_ids, nprobe, refine_k, sample_blocks, n,
+                                               (int32_t *)(ws + w.tau), ma.bound, bitmap, w.bmwords, dco, s)))
         return rc;
     if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, h->ev_group, 0));
     else if ((rc = rairs_launch_group(v, ma, s))) return rc;
@@ -646,7 +694,9 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     // items with the same score), or every query if the log ran out of chunks, is redone by the
     // exact kernel; normally none is flagged and every workgroup of that launch exits at once
     ea.only_flagged = ma.flags;
-    return rairs_launch_scan_exact(v, ea, n, s);
+    if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
+    if (side_dco) RAIRS_HIP(hipStreamWaitEvent(s, h->ev_dco, 0));   // the side stream's last work joins here
+    return RAIRS_OK;
 }
 
 extern "C" int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t *d_probe_ids,

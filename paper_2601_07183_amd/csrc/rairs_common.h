@@ -103,7 +103,7 @@ struct rairs_index {
     // a second stream for the steps that do not depend on each other (tables next to the coarse
     // quantizer, grouping next to the sample bound), forked from and joined to the caller's stream
     hipStream_t side;
-    hipEvent_t ev_fork, ev_lut, ev_probe, ev_group;
+    hipEvent_t ev_fork, ev_lut, ev_probe, ev_group, ev_bitmap, ev_dco;
     int side_ready;
 };
 
@@ -149,11 +149,28 @@ struct ExactScanArgs {
     int64_t *dco;                 // [nq], may be null
 };
 int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s);
+#define RAIRS_SAMPLE_MAX_BLOCKS 128
 // bound of every query from the head of its first probed list and, when dco is given, its DCO
 int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
                               int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,
                               int32_t *bound, const uint32_t *bitmap, int bmwords, int64_t *dco,
                               hipStream_t s);
+// the same bound from scores that rairs_launch_sample_scores wrote, and the DCO on its own
+int rairs_launch_sample_rank(const IndexView &v, const int32_t *probe_ids, int nprobe, int refine_k,
+                             int sample_blocks, int64_t nq, const uint16_t *pre, int32_t *tau,
+                             int32_t *bound, hipStream_t s);
+int rairs_launch_dco(const IndexView &v, const int32_t *probe_ids, int nprobe, const uint32_t *bitmap,
+                     int bmwords, int64_t nq, int64_t *dco, hipStream_t s);
+// Scores of the sample by the matrix cores: the queries are grouped by their first probed list, a
+// wave scores the head of a list for a tile of up to 32 of them.  Workspace: s_cnt [nlist],
+// s_off [nlist + 1], s_toff [nlist + 1], s_q [nq], s_tiles [nq / 32 + nlist].
+bool rairs_sample_scores_supported(const IndexView &v, int64_t nq);
+int rairs_launch_sample_group(const IndexView &v, const int32_t *probe_ids, int nprobe, int64_t nq,
+                              int32_t *s_off, int32_t *s_toff, int32_t *s_q, int32_t *s_tiles,
+                              hipStream_t s);
+int rairs_launch_sample_scores(const IndexView &v, const uint8_t *lut, int sample_blocks, int64_t nq,
+                               const int32_t *s_off, const int32_t *s_toff, const int32_t *s_q,
+                               const int32_t *s_tiles, uint16_t *scores, hipStream_t s);
 
 // list-major MFMA scan (scan_mfma.hip)
 struct MfmaScanArgs {

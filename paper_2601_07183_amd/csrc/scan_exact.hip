@@ -159,7 +159,30 @@ int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t 
 // cell in the miscellaneous areas of both lists, Section 5.1); so at least bigK entries of the
 // queue score <= tau.  One wave per query; the sample's scores sit in LDS and the rank is found by
 // bisection on the 16 score bits.
-#define SAMPLE_MAX_BLOCKS 128
+// DCO of a query (distance computations of the scan, Section 6.1): every valid slot of the own
+// blocks of each probed list, plus the valid slots of the blocks of each reference entry whose
+// owner is not probed.  Lanes over the probes; the total is returned in every lane.
+static __device__ __forceinline__ unsigned long long query_dco(const IndexView &v, const int32_t *__restrict__ probe_ids,
+                                                               int nprobe, const uint32_t *__restrict__ bitmap,
+                                                               int bmwords, int64_t qi, int lane)
+{
+    const uint32_t *bm = bitmap + (size_t)qi * bmwords;
+    unsigned long long c = 0;
+    for (int p = lane; p < nprobe; p += 64) {
+        const int Lp = probe_ids[(size_t)qi * nprobe + p];
+        if (Lp < 0 || Lp >= v.nlist) continue;
+        const ListEntry le = v.lists[Lp];
+        c += (unsigned long long)le.valid_items;
+        for (int r = 0; r < le.ref_cnt; r++) {
+            const RefEntry re = v.refs[le.ref_begin + r];
+            if (!((bm[re.owner >> 5] >> (re.owner & 31)) & 1u)) c += (unsigned long long)re.valid;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) c += (unsigned long long)__shfl_xor((long long)c, off);
+    return c;
+}
+
 // Scores of one block for this lane: `part` sums the table entries of the lane's half of the
 // sub-quantizer pairs; ND code dwords with 8 four-bit codes each.  No branch per lookup, so the
 // LDS reads of a block are all in flight together.
@@ -302,26 +325,129 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
         tau[qi] = (int32_t)range;
         if (bound) bound[qi] = (int32_t)t;
     }
-    // DCO of the query (distance computations of the scan, Section 6.1): every valid slot of the
-    // own blocks of each probed list, plus the valid slots of the blocks of each reference entry
-    // whose owner is not probed.  Lanes over the probes.
     if (dco) {
-        const uint32_t *bm = bitmap + (size_t)qi * bmwords;
-        unsigned long long c = 0;
-        for (int p = lane; p < nprobe; p += 64) {
-            const int Lp = probe_ids[(size_t)qi * nprobe + p];
-            if (Lp < 0 || Lp >= v.nlist) continue;
-            const ListEntry le = v.lists[Lp];
-            c += (unsigned long long)le.valid_items;
-            for (int r = 0; r < le.ref_cnt; r++) {
-                const RefEntry re = v.refs[le.ref_begin + r];
-                if (!((bm[re.owner >> 5] >> (re.owner & 31)) & 1u)) c += (unsigned long long)re.valid;
-            }
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) c += (unsigned long long)__shfl_xor((long long)c, off);
+        const unsigned long long c = query_dco(v, probe_ids, nprobe, bitmap, bmwords, qi, lane);
         if (lane == 0 && qi0 < nq) dco[qi] = (int64_t)c;
     }
+}
+
+// The DCO alone, one wave per query (used when the bound comes from the matrix-core sample).
+__global__ __launch_bounds__(WG) void dco_kernel(IndexView v, const int32_t *__restrict__ probe_ids,
+                                                 int nprobe, const uint32_t *__restrict__ bitmap,
+                                                 int bmwords, int64_t nq, int64_t *__restrict__ dco)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + (threadIdx.x >> 6);
+    if (qi >= nq) return;                                // a whole wave
+    const unsigned long long c = query_dco(v, probe_ids, nprobe, bitmap, bmwords, qi, lane);
+    if (lane == 0) dco[qi] = (int64_t)c;
+}
+
+int rairs_launch_dco(const IndexView &v, const int32_t *probe_ids, int nprobe, const uint32_t *bitmap,
+                     int bmwords, int64_t nq, int64_t *dco, hipStream_t s)
+{
+    hipLaunchKernelGGL(dco_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG), 0, s, v,
+                       probe_ids, nprobe, bitmap, bmwords, nq, dco);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+// Position of the k-th (1-based, k <= total) entry of a 256-bin histogram held in a wave's LDS
+// region: returns the bin and leaves in *before the number of entries in lower bins.
+static __device__ __forceinline__ int bin_of_rank(const uint32_t *bins, uint32_t k, int lane, uint32_t *before)
+{
+    const uint4 h = ((const uint4 *)bins)[lane];         // bins 4 lane .. 4 lane + 3
+    const uint32_t mine = h.x + h.y + h.z + h.w;
+    uint32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t x = (uint32_t)__shfl_up((int)incl, off);
+        if (lane >= off) incl += x;
+    }
+    const unsigned long long reach = __ballot(incl >= k);
+    const int src = __builtin_ctzll(reach);              // first lane whose running count reaches k
+    uint32_t b4 = incl - mine;                           // entries below this lane's bins
+    int bin = 4 * lane;
+    if (b4 + h.x < k) { b4 += h.x; bin++; if (b4 + h.y < k) { b4 += h.y; bin++; if (b4 + h.z < k) { b4 += h.z; bin++; } } }
+    *before = (uint32_t)__shfl((int)b4, src);
+    return __shfl(bin, src);
+}
+
+// Bound of every query from the scores the matrix-core sample kernel wrote, pre[q][sample_blocks *
+// 32] (0xFFFF: no item): the bigK-th smallest of them, by a radix select on the high and then the
+// low byte with a 256-bin histogram in the wave's LDS; same outputs as sample_bound_kernel.
+__global__ __launch_bounds__(WG) void sample_rank_kernel(IndexView v, const int32_t *__restrict__ probe_ids,
+                                                         int nprobe, int refine_k, int sample_blocks,
+                                                         int64_t nq, const uint16_t *__restrict__ pre,
+                                                         int32_t *__restrict__ tau,
+                                                         int32_t *__restrict__ bound)
+{
+    __shared__ __align__(16) uint32_t rank_bins[WG / 64][256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + wave;
+    if (qi >= nq) return;                                // a whole wave; no workgroup barrier below
+    uint32_t *bins = rank_bins[wave];
+    const int L = probe_ids[(size_t)qi * nprobe];
+    int cnt = 0;
+    if (L >= 0 && L < v.nlist) {
+        const ListEntry le = v.lists[L];
+        cnt = le.shared_cnt + le.misc_cnt;
+        cnt = cnt < sample_blocks ? cnt : sample_blocks;
+    }
+    const int nw = cnt * 16;                             // score pairs
+    const uint32_t *row = (const uint32_t *)(pre + (size_t)qi * sample_blocks * 32);
+    ((uint4 *)bins)[lane] = make_uint4(0u, 0u, 0u, 0u);
+    wave_lds_sync();
+    uint32_t nvalid = 0, smax = 0;
+    for (int e = lane; e < nw; e += 64) {
+        const uint32_t x = row[e], a = x & 0xFFFFu, b = x >> 16;
+        if (a != 0xFFFFu) { atomicAdd(&bins[a >> 8], 1u); nvalid++; smax = a > smax ? a : smax; }
+        if (b != 0xFFFFu) { atomicAdd(&bins[b >> 8], 1u); nvalid++; smax = b > smax ? b : smax; }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        nvalid += (uint32_t)__shfl_xor((int)nvalid, off);
+        const uint32_t o = (uint32_t)__shfl_xor((int)smax, off);
+        smax = o > smax ? o : smax;
+    }
+    wave_lds_sync();
+    uint32_t t = 0xFFFFu;
+    if (nvalid >= (uint32_t)refine_k) {                  // uniform for the wave
+        uint32_t before;
+        const uint32_t hi = (uint32_t)bin_of_rank(bins, (uint32_t)refine_k, lane, &before);
+        wave_lds_sync();
+        ((uint4 *)bins)[lane] = make_uint4(0u, 0u, 0u, 0u);
+        wave_lds_sync();
+        for (int e = lane; e < nw; e += 64) {
+            const uint32_t x = row[e], a = x & 0xFFFFu, b = x >> 16;
+            if (a != 0xFFFFu && (a >> 8) == hi) atomicAdd(&bins[a & 255u], 1u);
+            if (b != 0xFFFFu && (b >> 8) == hi) atomicAdd(&bins[b & 255u], 1u);
+        }
+        wave_lds_sync();
+        uint32_t before2;
+        const uint32_t lo = (uint32_t)bin_of_rank(bins, (uint32_t)refine_k - before, lane, &before2);
+        t = (hi << 8) | lo;
+    }
+    // range of the score histogram, as in sample_bound_kernel
+    uint32_t range = t;
+    if (t == 0xFFFFu) {
+        const uint32_t full = 255u * (uint32_t)v.M;
+        range = nvalid > 0 && 2u * smax + 64u < full ? 2u * smax + 64u : full;
+    }
+    if (lane == 0) {
+        tau[qi] = (int32_t)range;
+        if (bound) bound[qi] = (int32_t)t;
+    }
+}
+
+int rairs_launch_sample_rank(const IndexView &v, const int32_t *probe_ids, int nprobe, int refine_k,
+                             int sample_blocks, int64_t nq, const uint16_t *pre, int32_t *tau,
+                             int32_t *bound, hipStream_t s)
+{
+    hipLaunchKernelGGL(sample_rank_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG), 0, s,
+                       v, probe_ids, nprobe, refine_k, sample_blocks, nq, pre, tau, bound);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
 }
 
 int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
@@ -329,7 +455,7 @@ int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int3
                               int32_t *bound, const uint32_t *bitmap, int bmwords, int64_t *dco,
                               hipStream_t s)
 {
-    if (sample_blocks > SAMPLE_MAX_BLOCKS) sample_blocks = SAMPLE_MAX_BLOCKS;
+    if (sample_blocks > RAIRS_SAMPLE_MAX_BLOCKS) sample_blocks = RAIRS_SAMPLE_MAX_BLOCKS;
     if (sample_blocks < 1) sample_blocks = 1;
     const size_t lds = (size_t)(WG / 64) * ((size_t)v.M * 16 + (size_t)sample_blocks * 64);
     const dim3 grid((unsigned)((nq + WG / 64 - 1) / (WG / 64)));

@@ -1124,6 +1124,243 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
     if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
 }
 
+// ---- the bound sample on the matrix cores -----------------------------------------------------
+//
+// The sample that seeds a query's bound is the head of its first probed list.  Queries that share
+// a first list are scored together: one workgroup groups the batch by first list, then a wave
+// scores the head of a list for a tile of up to 32 such queries with the scan's matrix
+// instruction, and writes every (query, item) score out for the rank kernel.  About ten queries
+// share a first list in a 10,000-query batch over 1,024 lists, so the tiles are a third full --
+// still several times cheaper than one table lookup per code on the vector units.
+#define SAMPLE_GROUP_MAX_NLIST 8192
+#define SAMPLE_GROUP_MIN_QUERIES 1024
+
+// s_off: exclusive prefix over lists of the queries whose first probe is the list; s_q: those
+// queries, list by list; s_toff: exclusive prefix of tiles (32 queries); s_tiles: list of every tile.
+__global__ __launch_bounds__(1024) void sample_group_kernel(const int32_t *__restrict__ probe_ids,
+                                                            int64_t nq, int nprobe, int nlist,
+                                                            int32_t *s_off, int32_t *s_toff,
+                                                            int32_t *s_q, int32_t *s_tiles)
+{
+    extern __shared__ int32_t sg_lds[];                // [nlist] counts, then cursors; [nlist] offsets
+    __shared__ int sc[16], st[16];
+    int32_t *cnt_s = sg_lds, *off_s = sg_lds + nlist;
+    const int tid = threadIdx.x;
+    for (int i = tid; i < nlist; i += 1024) cnt_s[i] = 0;
+    __syncthreads();
+    for (int64_t q = tid; q < nq; q += 1024) {
+        const int L = probe_ids[q * nprobe];
+        if (L >= 0 && L < nlist) atomicAdd(&cnt_s[L], 1);
+    }
+    __syncthreads();
+    const int per = (nlist + 1023) / 1024;
+    const int lo = tid * per < nlist ? tid * per : nlist;
+    const int hi = lo + per < nlist ? lo + per : nlist;
+    int c = 0, t = 0;
+    for (int L = lo; L < hi; L++) {
+        const int n = cnt_s[L];
+        c += n;
+        t += (n + 31) >> 5;
+    }
+    // exclusive prefixes of (c, t) over the 1024 threads: a scan inside each wave, then the totals
+    // of the 16 waves through LDS
+    const int lane = tid & 63, wave = tid >> 6;
+    int ci = c, ti = t;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int x = __shfl_up(ci, off), y = __shfl_up(ti, off);
+        if (lane >= off) { ci += x; ti += y; }
+    }
+    if (lane == 63) { sc[wave] = ci; st[wave] = ti; }
+    __syncthreads();
+    int cw = 0, tw = 0, call = 0, tall = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < 16; w2++) {
+        const int x = sc[w2], y = st[w2];
+        if (w2 < wave) { cw += x; tw += y; }
+        call += x;
+        tall += y;
+    }
+    int cb = cw + ci - c, tb = tw + ti - t;
+    for (int L = lo; L < hi; L++) {
+        const int n = cnt_s[L], nt = (n + 31) >> 5;
+        s_off[L] = cb;
+        off_s[L] = cb;
+        s_toff[L] = tb;
+        for (int u = 0; u < nt; u++) s_tiles[tb + u] = L;
+        cb += n;
+        tb += nt;
+    }
+    if (tid == 0) {
+        s_off[nlist] = call;
+        s_toff[nlist] = tall;
+    }
+    __syncthreads();
+    for (int i = tid; i < nlist; i += 1024) cnt_s[i] = 0;
+    __syncthreads();
+    for (int64_t q = tid; q < nq; q += 1024) {
+        const int L = probe_ids[q * nprobe];
+        if (L >= 0 && L < nlist) s_q[off_s[L] + atomicAdd(&cnt_s[L], 1)] = (int32_t)q;
+    }
+}
+
+// scores[q][b * 32 + i] = score of item i of block b of the first `sample_blocks` own blocks of
+// q's first list (0xFFFF: the slot holds no item); blocks the list does not have are not written.
+template <int T>
+__global__ __launch_bounds__(WG) void sample_mfma_kernel(IndexView v, const uint8_t *__restrict__ lut,
+                                                            int sample_blocks,
+                                                            const int32_t *__restrict__ s_off,
+                                                            const int32_t *__restrict__ s_toff,
+                                                            const int32_t *__restrict__ s_q,
+                                                            const int32_t *__restrict__ s_tiles,
+                                                            uint16_t *__restrict__ scores)
+{
+    constexpr int ND = (T + 7) / 8;
+    constexpr int M = 2 * T;
+    constexpr int TS = T / 2;
+    __shared__ uint4 sparse_tab[16];                   // as in scan_mfma_kernel
+    if (threadIdx.x < 16) {
+        const int c = threadIdx.x;
+        const unsigned long long val = 1ull << (16 * (c >> 2));
+        const uint32_t pos = (uint32_t)(c & 3) << (4 * (c >> 2));
+        sparse_tab[c] = make_uint4((uint32_t)val, (uint32_t)(val >> 32), pos, pos << 16);
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, g = lane >> 5, j = lane & 31;
+    const uint32_t bias = 128u * M;
+    const uint32_t ntiles = (uint32_t)s_toff[v.nlist];
+    const uint32_t gwave = blockIdx.x * (WG / 64) + (threadIdx.x >> 6), nwaves = gridDim.x * (WG / 64);
+    v8i B[TS];
+    for (uint32_t u = gwave; u < ntiles; u += nwaves) {
+        const int L = __builtin_amdgcn_readfirstlane(s_tiles[u]);
+        const ListEntry le = v.lists[L];
+        const int tile = (int)u - __builtin_amdgcn_readfirstlane(s_toff[L]);
+        const int base = s_off[L], n = s_off[L + 1] - base;
+        const int qi = tile * 32 + j;
+        const int qid = qi < n ? s_q[base + qi] : -1;
+        {
+            const uint8_t *lq = lut + (size_t)(qid >= 0 ? qid : 0) * (M * 16) + g * 32;
+            const int keep = qid >= 0 ? -1 : 0;
+            const v4i flip = {(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
+            const v4i keep4 = {keep, keep, keep, keep};
+#pragma unroll
+            for (int t = 0; t < TS; t++) {
+                const v4i x = (*(const v4i *)(lq + t * 64) ^ flip) & keep4;
+                const v4i y = (*(const v4i *)(lq + t * 64 + 16) ^ flip) & keep4;
+                B[t] = (v8i){x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+            }
+        }
+        int cnt = le.shared_cnt + le.misc_cnt;
+        cnt = cnt < sample_blocks ? cnt : sample_blocks;
+        if (cnt <= 0) continue;                        // uniform for the wave
+        const uint32_t *cp = v.codes + (size_t)le.blk_begin * ND * 64 + lane;
+        uint32_t cn[ND];
+#pragma unroll
+        for (int w = 0; w < ND; w++) cn[w] = cp[w * 64];
+        uint32_t vmn = v.vmask[le.blk_begin];
+        uint16_t *row = scores + (size_t)(qid >= 0 ? qid : 0) * sample_blocks * 32;
+        for (int b = 0; b < cnt; b++) {
+            uint32_t c[ND];
+#pragma unroll
+            for (int w = 0; w < ND; w++) c[w] = cn[w];
+            const uint32_t vm = vmn;
+            if (b + 1 < cnt) {
+#pragma unroll
+                for (int w = 0; w < ND; w++) cn[w] = cp[(size_t)(b + 1) * ND * 64 + w * 64];
+                vmn = v.vmask[le.blk_begin + b + 1];
+            }
+            v16i acc;
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[r] = 0;
+#define CODE_LO(t_) ((c[(t_) >> 2] >> (8 * ((t_) & 3))) & 15u)
+#define CODE_HI(t_) ((c[(t_) >> 2] >> (8 * ((t_) & 3) + 4)) & 15u)
+#define LOAD_A(t_)                                                                        \
+    do {                                                                                  \
+        const uint32_t *e1_ = (const uint32_t *)&sparse_tab[CODE_LO(t_)];                 \
+        const uint32_t *e2_ = (const uint32_t *)&sparse_tab[CODE_HI(t_)];                 \
+        v1[t_] = *(const uint2 *)e1_; v2[t_] = *(const uint2 *)e2_;                       \
+        p1[t_] = e1_[2]; p2[t_] = e2_[3];                                                 \
+    } while (0)
+            uint2 v1[TS], v2[TS];
+            uint32_t p1[TS], p2[TS];
+            LOAD_A(0);
+            if (TS > 1) LOAD_A(1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < TS; t++) {
+                const v4i av = {(int)v1[t].x, (int)v1[t].y, (int)v2[t].x, (int)v2[t].y};
+                acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, B[t], acc, (int)(p1[t] | p2[t]), 0, 0);
+                if (t + 2 < TS) LOAD_A(t + 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#undef LOAD_A
+#undef CODE_LO
+#undef CODE_HI
+            // acc[r]: item 8 * (r / 4) + 4 * g + r % 4, query column j: four consecutive items
+            // per group of four registers, written as one 8-byte store
+            if (qid >= 0) {
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const int item = 8 * k + 4 * g;
+                    uint32_t sc4[4];
+#pragma unroll
+                    for (int e = 0; e < 4; e++)
+                        sc4[e] = ((vm >> (item + e)) & 1u) ? (uint32_t)acc[4 * k + e] + bias : 0xFFFFu;
+                    *(uint2 *)(row + b * 32 + item) = make_uint2(sc4[0] | (sc4[1] << 16), sc4[2] | (sc4[3] << 16));
+                }
+            }
+        }
+    }
+}
+
+bool rairs_sample_scores_supported(const IndexView &v, int64_t nq)
+{
+    return (v.T == 8 || v.T == 24 || v.T == 32) && v.nlist <= SAMPLE_GROUP_MAX_NLIST &&
+           nq >= SAMPLE_GROUP_MIN_QUERIES;
+}
+
+int rairs_launch_sample_group(const IndexView &v, const int32_t *probe_ids, int nprobe, int64_t nq,
+                              int32_t *s_off, int32_t *s_toff, int32_t *s_q, int32_t *s_tiles,
+                              hipStream_t s)
+{
+    if (!rairs_sample_scores_supported(v, nq)) {
+        rairs_set_error("matrix-core sample not available for this index or batch");
+        return RAIRS_EINVAL;
+    }
+    const size_t lds = (size_t)2 * v.nlist * 4;
+    if (lds > 32 * 1024)
+        RAIRS_HIP(hipFuncSetAttribute((const void *)sample_group_kernel,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(sample_group_kernel, dim3(1), dim3(1024), lds, s, probe_ids, nq, nprobe, v.nlist,
+                       s_off, s_toff, s_q, s_tiles);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+int rairs_launch_sample_scores(const IndexView &v, const uint8_t *lut, int sample_blocks, int64_t nq,
+                               const int32_t *s_off, const int32_t *s_toff, const int32_t *s_q,
+                               const int32_t *s_tiles, uint16_t *scores, hipStream_t s)
+{
+    if (!rairs_sample_scores_supported(v, nq) || sample_blocks < 1 || sample_blocks > RAIRS_SAMPLE_MAX_BLOCKS) {
+        rairs_set_error("matrix-core sample not available for this index or batch");
+        return RAIRS_EINVAL;
+    }
+    const int64_t tiles_max = nq / 32 + v.nlist;
+    unsigned grid = (unsigned)((tiles_max + WG / 64 - 1) / (WG / 64));
+    if (grid > 512u) grid = 512u;
+#define SAMPLE_MFMA(T_)                                                                           \
+    hipLaunchKernelGGL(sample_mfma_kernel<T_>, dim3(grid), dim3(WG), 0, s, v, lut, sample_blocks, s_off, \
+                       s_toff, s_q, s_tiles, scores)
+    switch (v.T) {
+    case 8: SAMPLE_MFMA(8); break;
+    case 24: SAMPLE_MFMA(24); break;
+    default: SAMPLE_MFMA(32); break;
+    }
+#undef SAMPLE_MFMA
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
 bool rairs_mfma_supported(const IndexView &v)
 {
     return v.T >= 1 && v.nd * 8 * 64 * 16 <= 128 * 1024;    // tables of a tile must fit 128 KB of LDS
