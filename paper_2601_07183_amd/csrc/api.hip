@@ -440,6 +440,15 @@ struct WsLayout {
 // kernel scoring it, ten times bigK pays up to about 1,024 items (measured: 32 blocks beat 16 and
 // 48 at bigK = 100, 63 beat 96 at bigK = 400); scored on the matrix cores it is cheaper and
 // fifteen times, up to about 1,536 items, is better (48 blocks beat 32 and 64 at bigK = 100).
+// The matrix-core route pays when tiles of queries sharing a first list are not too thin (at
+// least four queries per list on average) and the sample is large enough to cover its two extra
+// launches (bigK >= 64); measured on 10,000-query batches: 1,024 lists and bigK = 100 gain 2-3 %,
+// 4,096 lists (2.4 queries per list) or bigK = 10 lose about as much.
+static bool grouped_sample(const IndexView &v, int64_t nq, int refine_k)
+{
+    return rairs_sample_scores_supported(v, nq) && nq >= 4 * (int64_t)v.nlist && refine_k >= 64;
+}
+
 static int sample_blocks_for(int refine_k, bool grouped)
 {
     const int times = grouped ? 15 : 10, most = grouped ? 1536 : 1024;
@@ -481,7 +490,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     w.chunk_fill = take((size_t)w.log_chunks * 4);
     w.log_misc = take(64);
     w.prof = take(2048 * 12 * 8);
-    const bool grouped = rairs_sample_scores_supported(v, nq);
+    const bool grouped = grouped_sample(v, nq, refine_k);
     w.sample_blocks = sample_blocks_for(refine_k, grouped);
     w.s_off = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
     w.s_toff = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
@@ -605,7 +614,7 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     int rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, bitmap, w.bmwords, (uint32_t *)(ws + w.hist), s);
     if (rc) return rc;
     // the DCO kernel, on the side stream when the sample is grouped, reads the bitmaps
-    if (overlap && dco && rairs_sample_scores_supported(v, n)) RAIRS_HIP(hipEventRecord(h->ev_bitmap, s));
+    if (overlap && dco && grouped_sample(v, n, refine_k)) RAIRS_HIP(hipEventRecord(h->ev_bitmap, s));
     if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, lut_done, 0));
     ExactScanArgs ea;
     memset(&ea, 0, sizeof(ea));
@@ -658,7 +667,7 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     // The sample's scores come from the matrix cores, for queries grouped by their first list,
     // when the batch is large enough for that; else the bound kernel scores them itself, one
     // query per wave.  Side stream: the scan's grouping, then the DCO.
-    const bool grouped = rairs_sample_scores_supported(v, n);
+    const bool grouped = grouped_sample(v, n, refine_k);
     int32_t *s_off = (int32_t *)(ws + w.s_off), *s_toff = (int32_t *)(ws + w.s_toff);
     int32_t *s_q = (int32_t *)(ws + w.s_q), *s_tiles = (int32_t *)(ws + w.s_tiles);
     uint16_t *s_scores = (uint16_t *)(ws + w.s_scores);

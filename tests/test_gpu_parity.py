@@ -174,6 +174,28 @@ def test_search_after_later_batches_and_deletion(binding, d, M, strict):
         _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
 
 
+@pytest.mark.parametrize("d,M", [(128, 64), (96, 48), (32, 16)])
+def test_bound_sample_on_the_matrix_cores(binding, d, M):
+    # batches of 1,024 queries or more with at least four queries per list and bigK >= 64 take
+    # their bound from a sample scored for queries grouped by first list: several tiles per list
+    # (about 60 queries share a first list here), lists shorter than the sample, invalidated slots
+    # in the sampled blocks, a sample with fewer than bigK items (bigK = 1024)
+    g = np.random.Generator(np.random.PCG64(3 * d + M))
+    centers = g.integers(30, 220, size=(12, d))
+    pick = lambda n: np.rint(np.clip(centers[g.integers(0, 12, size=n)] + g.normal(0, 25, size=(n, d)),
+                                     0, 255)).astype(np.float32)
+    base, q = pick(9000), pick(1200)
+    hx = ib.build_index(base, 20, M, seed=4, coarse_iters=5, pq_iters=5)
+    for nprobe, refine_k, k in ((3, 100, 10), (20, 64, 10), (2, 1024, 10)):
+        _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
+    big = int(np.argmax(hx.list_shared_cnt))
+    first = hx.ids[hx.list_shared_begin[big]:hx.list_shared_begin[big] + 3].reshape(-1)
+    gone = np.unique(np.concatenate([g.choice(hx.ntotal, size=2500, replace=False), first[first >= 0]]))
+    hx = ib.delete_ids(hx, gone)
+    for nprobe, refine_k, k in ((3, 100, 10), (7, 200, 20)):
+        _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
+
+
 @pytest.mark.parametrize("count", [600, 3000, 6000])
 def test_identical_codes_tie_on_score(binding, count):
     # every vector identical: all scores tie, the order is decided by vector id alone, and every
