@@ -1134,6 +1134,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
 // still several times cheaper than one table lookup per code on the vector units.
 #define SAMPLE_GROUP_MAX_NLIST 8192
 #define SAMPLE_GROUP_MIN_QUERIES 1024
+#define SG_HELD 12
 
 // s_off: exclusive prefix over lists of the queries whose first probe is the list; s_q: those
 // queries, list by list; s_toff: exclusive prefix of tiles (32 queries); s_tiles: list of every tile.
@@ -1148,7 +1149,19 @@ __global__ __launch_bounds__(1024) void sample_group_kernel(const int32_t *__res
     const int tid = threadIdx.x;
     for (int i = tid; i < nlist; i += 1024) cnt_s[i] = 0;
     __syncthreads();
-    for (int64_t q = tid; q < nq; q += 1024) {
+    // the first SG_HELD queries of a thread stay in registers: their loads are all in flight at
+    // once and the second pass does not fetch them again
+    int myL[SG_HELD];
+#pragma unroll
+    for (int k = 0; k < SG_HELD; k++) {
+        const int64_t q = tid + 1024 * k;
+        int L = q < nq ? probe_ids[q * nprobe] : -1;
+        myL[k] = L >= 0 && L < nlist ? L : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < SG_HELD; k++)
+        if (myL[k] >= 0) atomicAdd(&cnt_s[myL[k]], 1);
+    for (int64_t q = tid + 1024 * SG_HELD; q < nq; q += 1024) {
         const int L = probe_ids[q * nprobe];
         if (L >= 0 && L < nlist) atomicAdd(&cnt_s[L], 1);
     }
@@ -1198,7 +1211,10 @@ __global__ __launch_bounds__(1024) void sample_group_kernel(const int32_t *__res
     __syncthreads();
     for (int i = tid; i < nlist; i += 1024) cnt_s[i] = 0;
     __syncthreads();
-    for (int64_t q = tid; q < nq; q += 1024) {
+#pragma unroll
+    for (int k = 0; k < SG_HELD; k++)
+        if (myL[k] >= 0) s_q[off_s[myL[k]] + atomicAdd(&cnt_s[myL[k]], 1)] = tid + 1024 * k;
+    for (int64_t q = tid + 1024 * SG_HELD; q < nq; q += 1024) {
         const int L = probe_ids[q * nprobe];
         if (L >= 0 && L < nlist) s_q[off_s[L] + atomicAdd(&cnt_s[L], 1)] = (int32_t)q;
     }
