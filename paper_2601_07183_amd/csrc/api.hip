@@ -439,7 +439,8 @@ struct WsLayout {
 // (fewer survivors staged and logged) but the sample sits on the critical path.  With the bound
 // kernel scoring it, ten times bigK pays up to about 1,024 items (measured: 32 blocks beat 16 and
 // 48 at bigK = 100, 63 beat 96 at bigK = 400); scored on the matrix cores it is cheaper and
-// fifteen times, up to about 1,536 items, is better (48 blocks beat 32 and 64 at bigK = 100).
+// fifteen times, up to about 1,536 items, is better (48 blocks beat 32 and 64 at bigK = 100).  With
+// more than 64 sub-quantizers an item costs the bound kernel so much that five times is all that pays.
 // The matrix-core route pays when tiles of queries sharing a first list are not too thin (at
 // least four queries per list on average) and the sample is large enough to cover its two extra
 // launches (bigK >= 64); measured on 10,000-query batches: 1,024 lists and bigK = 100 gain 2-3 %,
@@ -449,9 +450,9 @@ static bool grouped_sample(const IndexView &v, int64_t nq, int refine_k)
     return rairs_sample_scores_supported(v, nq) && nq >= 4 * (int64_t)v.nlist && refine_k >= 64;
 }
 
-static int sample_blocks_for(int refine_k, bool grouped)
+static int sample_blocks_for(const IndexView &v, int refine_k, bool grouped)
 {
-    const int times = grouped ? 15 : 10, most = grouped ? 1536 : 1024;
+    const int times = grouped ? 15 : v.M <= 64 ? 10 : 5, most = grouped ? 1536 : 1024;
     int items = times * refine_k < most ? times * refine_k : most;
     if (items < 5 * refine_k) items = 5 * refine_k;
     int blocks = (items + 31) / 32;
@@ -491,7 +492,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     w.log_misc = take(64);
     w.prof = take(2048 * 12 * 8);
     const bool grouped = grouped_sample(v, nq, refine_k);
-    w.sample_blocks = sample_blocks_for(refine_k, grouped);
+    w.sample_blocks = sample_blocks_for(v, refine_k, grouped);
     w.s_off = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
     w.s_toff = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
     w.s_q = take(grouped ? (size_t)nq * 4 : 0);
