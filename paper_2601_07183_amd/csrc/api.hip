@@ -250,6 +250,11 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
         for (int64_t i = b0 * 32; i < b1 * 32; i++) valid += x->ids[i] >= 0;
         e2.valid_items = (int32_t)valid;
     }
+    std::vector<int32_t> hbl((size_t)x->nblocks, -1);
+    for (int l = 0; l < x->nlist; l++) {
+        const int64_t b0 = x->list_shared_begin[l], b1 = b0 + x->list_shared_cnt[l] + x->list_misc_cnt[l];
+        for (int64_t b = b0; b < b1; b++) hbl[(size_t)b] = l;
+    }
     std::vector<uint32_t> hm((size_t)x->nblocks, 0u), hv((size_t)x->nblocks, 0u);
     for (int64_t b = 0; b < x->nblocks; b++) {
         uint32_t m = 0;
@@ -346,9 +351,12 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     if (!hs.empty())
         UP_HIP(hipMemcpyAsync(segs, hs.data(), hs.size() * sizeof(SegEntry), hipMemcpyHostToDevice, s));
     uint32_t *cmask = nullptr, *vmask = nullptr;
+    int32_t *blk_list = nullptr;
     UP_CHECK(dev_alloc(h, (void **)&cmask, (size_t)x->nblocks * 4));
     UP_CHECK(dev_alloc(h, (void **)&vmask, (size_t)x->nblocks * 4));
+    UP_CHECK(dev_alloc(h, (void **)&blk_list, (size_t)x->nblocks * 4));
     if (x->nblocks) {
+        UP_HIP(hipMemcpyAsync(blk_list, hbl.data(), hbl.size() * 4, hipMemcpyHostToDevice, s));
         UP_HIP(hipMemcpyAsync(cmask, hm.data(), hm.size() * 4, hipMemcpyHostToDevice, s));
         UP_HIP(hipMemcpyAsync(vmask, hv.data(), hv.size() * 4, hipMemcpyHostToDevice, s));
     }
@@ -387,7 +395,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_HIP(hipStreamSynchronize(s));
 
     v.idtag = idtag;
-    v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask; v.vmask = vmask;
+    v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask; v.vmask = vmask; v.blk_list = blk_list;
     v.lists = lists; v.refs = refs; v.segs = segs; v.parts = parts; v.raw = raw;
     for (int r = 0; r < RAIRS_EV_RING; r++)
         for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[r][i]));
@@ -487,7 +495,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     w.hist = take((size_t)nq * RAIRS_HIST_BINS * 4);
     w.surv_buf = take((size_t)nq * SURV_CAP * 8);
     w.log_chunks = (int)((nq * RAIRS_LOG_PER_QUERY + 255) / 256) + 8192;   // + two per wave
-    w.log = take((size_t)w.log_chunks * 256 * 16);
+    w.log = take((size_t)w.log_chunks * 256 * 8);
     w.chunk_fill = take((size_t)w.log_chunks * 4);
     w.log_misc = take(64);
     w.prof = take(2048 * 12 * 8);
@@ -550,7 +558,8 @@ static int check_k(int k, int refine_k)
     return RAIRS_OK;
 }
 
-// Queries per internal pass so that the distance matrix and buffers stay within ~4 GiB.
+// Queries per internal pass so that the distance matrix and buffers stay within ~4 GiB (at most
+// 21,845: the survivor log relies on a pass staying below 65,536 queries).
 static int64_t pass_size(const IndexView &v, int64_t nq)
 {
     int64_t per_q = (int64_t)v.nlist * 4 + 196608;
@@ -654,7 +663,7 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     ma.flags = (uint32_t *)(ws + w.flags); ma.cand_ids = cand_ids; ma.cand_score = cand_score;
     ma.hist = (uint32_t *)(ws + w.hist);
     h->last_pass_n = n; h->last_flags_off = w.flags; h->last_cnt_off = w.surv_cnt;
-    ma.log = (uint4 *)(ws + w.log); ma.chunk_fill = (uint32_t *)(ws + w.chunk_fill);
+    ma.log = (uint2 *)(ws + w.log); ma.chunk_fill = (uint32_t *)(ws + w.chunk_fill);
     ma.log_cursor = (uint32_t *)(ws + w.log_misc); ma.log_overflow = ma.log_cursor + 1;
     ma.log_chunks = w.log_chunks;
 #ifdef RAIRS_PROFILE_CYCLES

@@ -67,6 +67,7 @@ struct IndexView {
     // block's item, or a miscellaneous item whose other list has no smaller id than the list)
     const uint32_t *cmask;
     const uint32_t *vmask;        // [nblocks] bit i: slot i holds an item
+    const int32_t *blk_list;      // [nblocks] the list that stores the block (-1: none)
     const ListEntry *lists;       // [nlist]
     const RefEntry *refs;         // [nrefs]
     const SegEntry *segs;         // [nsegs]
@@ -196,7 +197,7 @@ struct MfmaScanArgs {
     uint64_t *surv_buf;           // [nq][surv_cap]
     int surv_cap;
     uint32_t *flags;              // [nq] set when the survivor buffer overflowed
-    uint4 *log;                   // [log_chunks][256] survivor log {slot, score<<16|list, query, 0}
+    uint2 *log;                   // [log_chunks][256] survivor log {slot, score << 16 | query of the pass}
     uint32_t *chunk_fill;         // [log_chunks] entries written to each chunk
     uint32_t *log_cursor;         // [1] chunks handed out
     uint32_t *log_overflow;       // [1] set if the log ran out of chunks

@@ -393,7 +393,7 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
             const uint32_t qraw = sq.qid[i], qid = qraw & 0x7FFFFFFFu;
             const uint32_t sl = sq.score_list[i];
             if (room)
-                a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint4(sq.slot[i], sl, qid, 0u);
+                a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint2(sq.slot[i], (sl & 0xFFFF0000u) | qid);
             if (qraw >> 31)
             {
                 // scores beyond the histogram's range share the last bin
@@ -727,7 +727,7 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
     if (n == 0) continue;                               // uniform
     if (tid < COLLECT_SLOTS) { key[tid] = -1; cnt[tid] = 0; }
     __syncthreads();
-    uint4 e = make_uint4(0, 0, 0, 0);
+    uint2 e = make_uint2(0, 0);                         // {slot, score << 16 | query}
     int slot = -1;
     uint32_t rank = 0;
     // an entry logged under an earlier, looser bound is dropped when its score is above the
@@ -735,10 +735,10 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
     bool live = false;
     if (tid < (int)n) {
         e = a.log[(size_t)c * LOG_CHUNK + tid];
-        live = (int32_t)(e.y >> 16) <= a.bound[e.z];
+        live = (int32_t)(e.y >> 16) <= a.bound[e.y & 0xFFFFu];
     }
     if (live) {
-        const int qid = (int)e.z;
+        const int qid = (int)(e.y & 0xFFFFu);
         // open addressing on the query id; a full table falls back to a direct atomic below
         int h = (int)(((uint32_t)qid * 2654435761u) >> 25);          // 7 bits
         for (int probe = 0; probe < COLLECT_SLOTS; probe++) {
@@ -752,9 +752,9 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
     if (tid < COLLECT_SLOTS && cnt[tid] > 0) base[tid] = atomicAdd(&a.surv_cnt[key[tid]], cnt[tid]);
     __syncthreads();
     if (live) {
-        const uint32_t qid = e.z;
+        const uint32_t qid = e.y & 0xFFFFu;
         const uint32_t pos = slot >= 0 ? base[slot] + rank : atomicAdd(&a.surv_cnt[qid], 1u);
-        if (pos < (uint32_t)a.surv_cap) a.surv_buf[(size_t)qid * a.surv_cap + pos] = ((uint64_t)e.y << 32) | e.x;
+        if (pos < (uint32_t)a.surv_cap) a.surv_buf[(size_t)qid * a.surv_cap + pos] = ((uint64_t)(e.y >> 16) << 48) | e.x;
     }
     __syncthreads();                                    // the tables are reused for the next chunk
     }
@@ -783,7 +783,7 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
     const uint32_t *bm = a.bitmap + (size_t)q * a.bmwords;
     for (uint32_t i0 = 0; i0 < n; i0 += 256) {
         uint64_t e[4];
-        uint32_t id[4];
+        uint32_t id[4], Lb[4];
         int o[4];
 #pragma unroll
         for (int u = 0; u < 4; u++) {
@@ -793,6 +793,7 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
 #pragma unroll
         for (int u = 0; u < 4; u++) {
             const uint2 it = v.idtag[(uint32_t)e[u]];
+            Lb[u] = (uint32_t)v.blk_list[(uint32_t)e[u] >> 5];      // the list that stores the block
             id[u] = it.x;
             o[u] = (int)it.y;
         }
@@ -802,7 +803,9 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
 #pragma unroll
         for (int u = 0; u < 4; u++) {
             const uint32_t i = i0 + 64 * u + lane;
-            const uint32_t score = (uint32_t)(e[u] >> 48), L = (uint32_t)(e[u] >> 32) & 0xFFFFu;
+            // a tagged item sits in a miscellaneous block, which is only ever scanned through the
+            // list that stores it
+            const uint32_t score = (uint32_t)(e[u] >> 48), L = Lb[u];
             bool keep = id[u] != RAIRS_EMPTY_ID;
             // RemoveVectorIfVisited: the item was already taken from list o
             if (keep && o[u] >= 0 && (uint32_t)o[u] < L && ((bw[u] >> (o[u] & 31)) & 1u)) keep = false;
@@ -873,7 +876,7 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a,
     for (int i = tid; i < (int)n; i += WG) {
         uint64_t key = ~0ull;
         const uint64_t e = a.surv_buf[(size_t)q * a.surv_cap + i];
-        const uint32_t slot = (uint32_t)e, score = (uint32_t)(e >> 48), L = (uint32_t)(e >> 32) & 0xFFFFu;
+        const uint32_t slot = (uint32_t)e, score = (uint32_t)(e >> 48), L = (uint32_t)v.blk_list[slot >> 5];
         const uint2 it = v.idtag[slot];
         const uint32_t id = it.x;
         const int o = (int)it.y;
@@ -1447,6 +1450,10 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
     if (a.nprobe - a.p_first <= 0) return RAIRS_OK;
     if (a.surv_cap > SURV_CAP_MAX) {
         rairs_set_error("survivor capacity %d above %d", a.surv_cap, SURV_CAP_MAX);
+        return RAIRS_EINVAL;
+    }
+    if (a.nq > 65536) {                                // a log entry has 16 bits for the query of the pass
+        rairs_set_error("a scan pass takes at most 65536 queries, got %lld", (long long)a.nq);
         return RAIRS_EINVAL;
     }
     bool reg_tables;
