@@ -24,7 +24,9 @@
 // query's bound; passing pairs are staged per wave, logged in bulk and cut to bigK afterwards by
 // collect_kernel and the select kernels.
 //
-// The bound.  tau0 = bigK-th smallest score in a sample, the head of the query's first list.  Every
+// The bound.  tau0 = bigK-th smallest score in a sample, the head of the query's first list (scored
+// by the bound kernel of scan_exact.hip, or, for large batches, by sample_group_kernel and
+// sample_mfma_kernel below with the same matrix instruction, queries grouped by first list).  Every
 // survivor that the duplicate rule can never drop (an item of a shared block, or a miscellaneous
 // item whose other list has the larger id; the index keeps one bit per slot for this) is counted in
 // a per-query histogram of RAIRS_HIST_BINS equal score bins over [0, tau0] (over a guessed range
