@@ -55,7 +55,6 @@ static void destroy(rairs_index *h)
     if (h->side_ready) {
         (void)hipEventDestroy(h->ev_fork); (void)hipEventDestroy(h->ev_lut);
         (void)hipEventDestroy(h->ev_probe); (void)hipEventDestroy(h->ev_group);
-        (void)hipEventDestroy(h->ev_bitmap);
         (void)hipEventDestroy(h->ev_dco);
         (void)hipStreamDestroy(h->side);
     }
@@ -406,7 +405,6 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_HIP(hipEventCreateWithFlags(&h->ev_lut, hipEventDisableTiming));
     UP_HIP(hipEventCreateWithFlags(&h->ev_probe, hipEventDisableTiming));
     UP_HIP(hipEventCreateWithFlags(&h->ev_group, hipEventDisableTiming));
-    UP_HIP(hipEventCreateWithFlags(&h->ev_bitmap, hipEventDisableTiming));
     UP_HIP(hipEventCreateWithFlags(&h->ev_dco, hipEventDisableTiming));
     h->side_ready = 1;
     *out = h;
@@ -621,17 +619,20 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     const IndexView &v = h->v;
     char *ws = (char *)h->ws;
     uint32_t *bitmap = (uint32_t *)(ws + w.bitmap);
-    int rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, bitmap, w.bmwords, (uint32_t *)(ws + w.hist), s);
+    const bool mfma = rairs_mfma_supported(v) && !h->force_exact;
+    // With the sample on the matrix cores nothing on the caller's stream reads the bitmaps before
+    // the scan does, so they (and the zeroed histograms) are made on the side stream ahead of the
+    // grouping, whose event the scan waits for anyway.
+    const bool side_bitmap = overlap && mfma && grouped_sample(v, n, refine_k);
+    int rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, bitmap, w.bmwords, (uint32_t *)(ws + w.hist),
+                                 side_bitmap ? h->side : s);
     if (rc) return rc;
-    // the DCO kernel, on the side stream when the sample is grouped, reads the bitmaps
-    if (overlap && dco && grouped_sample(v, n, refine_k)) RAIRS_HIP(hipEventRecord(h->ev_bitmap, s));
     if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, lut_done, 0));
     ExactScanArgs ea;
     memset(&ea, 0, sizeof(ea));
     ea.lut = lut; ea.probe_ids = probe_ids; ea.bitmap = bitmap; ea.bmwords = w.bmwords;
     ea.nprobe = nprobe; ea.refine_k = refine_k; ea.dco = dco;
     ea.cand_ids = cand_ids; ea.cand_score = cand_score;
-    const bool mfma = rairs_mfma_supported(v) && !h->force_exact;
     h->last_pass_n = 0;
     if (!mfma) {
         if (ev) RAIRS_HIP(hipEventRecord(ev[0], s));
@@ -686,7 +687,6 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
         if ((rc = rairs_launch_group(v, ma, h->side))) return rc;
         RAIRS_HIP(hipEventRecord(h->ev_group, h->side));
         if (side_dco) {
-            RAIRS_HIP(hipStreamWaitEvent(h->side, h->ev_bitmap, 0));
             if ((rc = rairs_launch_dco(v, probe_ids, nprobe, bitmap, w.bmwords, n, dco, h->side))) return rc;
             RAIRS_HIP(hipEventRecord(h->ev_dco, h->side));
         }

@@ -104,7 +104,7 @@ struct rairs_index {
     // a second stream for the steps that do not depend on each other (tables next to the coarse
     // quantizer, grouping next to the sample bound), forked from and joined to the caller's stream
     hipStream_t side;
-    hipEvent_t ev_fork, ev_lut, ev_probe, ev_group, ev_bitmap, ev_dco;
+    hipEvent_t ev_fork, ev_lut, ev_probe, ev_group, ev_dco;
     int side_ready;
 };
 
