@@ -627,7 +627,9 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     int rc = rairs_launch_bitmap(v, probe_ids, n, nprobe, bitmap, w.bmwords, (uint32_t *)(ws + w.hist),
                                  side_bitmap ? h->side : s);
     if (rc) return rc;
-    if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, lut_done, 0));
+    // the tables are first read by the sample (or the exact scan); with the grouped sample the
+    // wait goes behind the sample's grouping kernel, which does not need them
+    if (overlap && !side_bitmap) RAIRS_HIP(hipStreamWaitEvent(s, lut_done, 0));
     ExactScanArgs ea;
     memset(&ea, 0, sizeof(ea));
     ea.lut = lut; ea.probe_ids = probe_ids; ea.bitmap = bitmap; ea.bmwords = w.bmwords;
@@ -694,6 +696,7 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     if (grouped) {
         if ((rc = rairs_launch_sample_group(v, probe_ids, nprobe, n, s_off, s_toff, s_q, s_tiles, s)))
             return rc;
+        if (side_bitmap) RAIRS_HIP(hipStreamWaitEvent(s, lut_done, 0));
         if ((rc = rairs_launch_sample_scores(v, lut, sample_blocks, n, s_off, s_toff, s_q, s_tiles, s_scores, s)))
             return rc;
         if ((rc = rairs_launch_sample_rank(v, probe_ids, nprobe, refine_k, sample_blocks, n, s_scores,
@@ -714,7 +717,18 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     // exact kernel; normally none is flagged and every workgroup of that launch exits at once
     ea.only_flagged = ma.flags;
     if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
-    if (side_dco) RAIRS_HIP(hipStreamWaitEvent(s, h->ev_dco, 0));   // the side stream's last work joins here
+    h->side_tail = side_dco ? 1 : 0;                   // the caller joins the side stream's last work
+    return RAIRS_OK;
+}
+
+// The side stream's trailing work (the DCO count) joins the caller's stream; called after the last
+// kernel of a pass has been enqueued so that the wait delays nothing.
+static int join_side(rairs_index *h, hipStream_t s)
+{
+    if (h->side_tail) {
+        h->side_tail = 0;
+        RAIRS_HIP(hipStreamWaitEvent(s, h->ev_dco, 0));
+    }
     return RAIRS_OK;
 }
 
@@ -822,6 +836,7 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
         if (prof) RAIRS_HIP(hipEventRecord(ev[EV_SCANNED], s));
         if ((rc = rairs_launch_refine(v, q, cand, n, refine_k, k, d_out_ids + (size_t)q0 * k,
                                       d_out_dists + (size_t)q0 * k, s))) return rc;
+        if ((rc = join_side(h, s))) return rc;
         if (prof) RAIRS_HIP(hipEventRecord(ev[EV_END], s));
     }
     if (profk) h->ev_count++;

@@ -106,6 +106,7 @@ struct rairs_index {
     hipStream_t side;
     hipEvent_t ev_fork, ev_lut, ev_probe, ev_group, ev_dco;
     int side_ready;
+    int side_tail;                // the side stream still runs work of the current pass (joined by ev_dco)
 };
 
 void rairs_set_error(const char *fmt, ...);
