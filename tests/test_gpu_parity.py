@@ -196,6 +196,19 @@ def test_bound_sample_on_the_matrix_cores(binding, d, M):
         _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
 
 
+def test_bound_sample_on_the_matrix_cores_large_batch(binding):
+    # more queries than the sample's grouping kernel keeps in registers per thread (12 x 1,024),
+    # and more than 32 queries per first list on every list
+    g = np.random.Generator(np.random.PCG64(77))
+    d, M = 32, 16
+    centers = g.integers(30, 220, size=(12, d))
+    pick = lambda n: np.rint(np.clip(centers[g.integers(0, 12, size=n)] + g.normal(0, 25, size=(n, d)),
+                                     0, 255)).astype(np.float32)
+    base, q = pick(9000), pick(13500)
+    hx = ib.build_index(base, 20, M, seed=6, coarse_iters=5, pq_iters=5)
+    _compare_all_stages(binding, hx, q, 10, 4, 100)
+
+
 @pytest.mark.parametrize("count", [600, 3000, 6000])
 def test_identical_codes_tie_on_score(binding, count):
     # every vector identical: all scores tie, the order is decided by vector id alone, and every
