@@ -324,6 +324,29 @@ def test_batch_permutation_and_split(binding, small_index):
         ix.free()
 
 
+def test_batch_larger_than_one_internal_pass(binding):
+    # rairs_search cuts a batch into passes of at most about 21,800 queries that share one
+    # workspace and the handle's two streams; 23,000 queries make two
+    g = np.random.Generator(np.random.PCG64(78))
+    d, M = 32, 16
+    centers = g.integers(30, 220, size=(12, d))
+    pick = lambda n: np.rint(np.clip(centers[g.integers(0, 12, size=n)] + g.normal(0, 25, size=(n, d)),
+                                     0, 255)).astype(np.float32)
+    base, q = pick(9000), pick(23000)
+    hx = ib.build_index(base, 20, M, seed=7, coarse_iters=5, pq_iters=5)
+    want = oracle.search(oracle.OracleIndex(hx), q, 10, 4, 100)
+    ix = binding.Index(hx)
+    try:
+        for _ in range(2):                               # the second call reuses the grown workspace
+            ids, dists = ix.search(_dev(q), 10, 4, 100)
+            torch.cuda.synchronize()
+            assert (ids.cpu().numpy() == want.ids).all()
+            _assert_dists(dists.cpu().numpy(), want.dists)
+            assert (ix.dco(len(q)) == want.dco).all()
+    finally:
+        ix.free()
+
+
 def test_argument_errors_and_empty_batch(binding, small_index):
     base, hx = small_index
     q = _dev(small_queries(43, 4, hx.d))
