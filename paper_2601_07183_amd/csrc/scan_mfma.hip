@@ -362,13 +362,15 @@ struct LogCursor {
                                         // before the chunk is needed)
 };
 
-// When a wave refreshes bounds: every `gap`-th flush.  The gap starts at 2, doubles (up to 16)
+// When a wave refreshes bounds: every `gap`-th flush.  The gap starts at 4, doubles (up to 16)
 // each time a refresh lowers no bound -- late in the scan the bounds have settled and reading
-// histograms is wasted time -- and returns to 2 when one does.
+// histograms is wasted time -- and returns to 4 when one does.  (With the bound that the sample
+// gives, a start of 2 is 1 % slower on the 1M x 128 workload and 3 % on the 960-dimension one,
+// a start of 8 is slower again.)
 // (measured on the 1M x 128 workload: all or half of the lanes refreshing, at any pacing, is slower
 // than a quarter -- a refresh costs memory traffic per lane, not only latency)
 #define REFRESH_LANES_MASK 3
-#define REFRESH_GAP_MIN 2u
+#define REFRESH_GAP_MIN 4u
 #define REFRESH_GAP_MAX 16u
 struct RefreshPace {
     uint32_t gap, since, turn;          // wave-uniform
@@ -561,8 +563,8 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #endif
         }
         PC_ADD(pc_tile);
-        // the query's bound: other waves keep lowering it, so it is looked up again for every
-        // block, one block ahead (a stale bound is only looser)
+        // the query's bound: other waves keep lowering it, so it is looked up again during the
+        // run, ahead of the block that uses it (a stale bound is only looser)
         const int32_t *bq = a.bound + (qid >= 0 ? qid : 0);
         int bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const uint32_t *bmq = a.bitmap + (size_t)(qid >= 0 ? qid : 0) * a.bmwords;
@@ -601,7 +603,8 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                     for (int w = 0; w < ND; w++) c[w] = cn[w];
                     const uint32_t cmask = cmn;
                     const int th = live ? bound_next - bias : INT_MIN;
-                    bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    // (every fourth block is often enough: the bound moves rarely)
+                    if ((b & 3) == 3) bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     if (b + 1 < se.nblk) {             // fetch the next block while this one is scored
 #pragma unroll
                         for (int w = 0; w < ND; w++) cn[w] = cp[(size_t)(b + 1) * ND * 64 + w * 64];
