@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # Bytes that left L2 per launch of the scan kernel, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0
 # and WRITE_SIZE x 1.0, factors from the same counters on a 1 GiB copy); see profiles/.  Keyed by
 # (workload, nprobe); other configurations report null.
-MEASURED_TRAFFIC = {("sift1m", 23): 1.55e9}
+MEASURED_TRAFFIC = {("sift1m", 23): 1.51e9}
 
 
 def log(*a):
