@@ -15,6 +15,7 @@
  *     current device.  `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
  *   - Search calls only enqueue work on `hip_stream`; outputs are valid once the caller has
  *     synchronised that stream.  One search at a time per handle (calls share its workspace).
+ *     With a caller-owned workspace (rairs_set_workspace) they never allocate or synchronise.
  *   - All distances are squared Euclidean distances in fp32.  Orders are total:
  *     lists by (distance, list id), candidates by (16-bit score, vector id), results by
  *     (distance, vector id).  Missing entries are id -1 / distance +inf / score -1.
@@ -36,7 +37,9 @@ typedef enum {
     RAIRS_EINVAL = -1,        /* bad argument (null pointer, size out of range, broken directory) */
     RAIRS_ENOMEM = -2,        /* host or device allocation failed */
     RAIRS_EHIP = -3,          /* a HIP runtime call failed */
-    RAIRS_EUNSUPPORTED = -4   /* valid request outside the built limits */
+    RAIRS_EUNSUPPORTED = -4,  /* valid request outside the built limits */
+    RAIRS_EWORKSPACE = -5     /* the workspace the caller set is too small for this call; nothing
+                                 was enqueued */
 } rairs_status;
 
 /* Built limits (rejected with RAIRS_EUNSUPPORTED beyond them). */
@@ -58,7 +61,10 @@ typedef enum {
  * shared block whose item was deleted holds id -1 (Section 6.1's deletion rule) and is skipped.
  * The leftover items of a cell (i, j), i != j, sit in the miscellaneous areas of BOTH lists, with
  * the same code, tagged with the other list (Section 5.1); the scan relies on this pairing when
- * it bounds scores from a sample of a list.  It is not checked at upload.
+ * it bounds scores from a sample of a list.  Upload checks it: every vector id must occur exactly
+ * once in a shared block (untagged), or once in the miscellaneous area of its only list (tagged
+ * with that list), or as such a pair of twins; blocks belong to at most one list; the owner of a
+ * reference entry has the smaller list id.  Anything else is RAIRS_EINVAL.
  */
 typedef struct {
     int32_t d;               /* vector dimension */
@@ -93,8 +99,9 @@ typedef struct {
 
 /*
  * Copy an index to the current device in the library's device format (Fig. 3: centroids,
- * inverted lists, vector data).  Validates sizes and every directory range; synchronises its own
- * copies before returning.  *out receives the handle.
+ * inverted lists, vector data).  Validates sizes, every directory range and the layout rules
+ * above; synchronises its own copies before returning.  The device copy belongs to the handle
+ * (hipMalloc) and is released by rairs_free.  *out receives the handle.
  */
 int rairs_index_upload(const rairs_host_index_t *host, void *hip_stream, rairs_index_t **out);
 
@@ -104,8 +111,10 @@ int rairs_index_upload(const rairs_host_index_t *host, void *hip_stream, rairs_i
  *   d_out_ids   device [nq][k] int64, ascending (distance, id)
  *   d_out_dists device [nq][k] fp32 squared distances
  * Requires 1 <= k <= refine_k <= RAIRS_MAX_REFINE_K, 1 <= nprobe <= min(nlist,
- * RAIRS_MAX_NPROBE).  nq == 0 is a successful no-op.  The handle's internal workspace grows on
- * demand (a growth synchronises the device; steady-state calls allocate nothing).
+ * RAIRS_MAX_NPROBE).  nq == 0 is a successful no-op.  Scratch memory: the workspace set with
+ * rairs_set_workspace (too small: RAIRS_EWORKSPACE, nothing enqueued); if none was set, a
+ * workspace of the handle's own that grows on demand (a growth synchronises the device and
+ * calls hipMalloc; steady-state calls allocate nothing).
  * Everything is ordered after the earlier work of hip_stream and complete when hip_stream is;
  * inside, the table build and the grouping of queries by list run on a second stream that the
  * handle owns (default priority), forked from and joined to hip_stream with events.  Calls on one
@@ -114,8 +123,27 @@ int rairs_index_upload(const rairs_host_index_t *host, void *hip_stream, rairs_i
 int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
                  int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream);
 
-/* Release the device copy.  NULL is accepted. */
+/* Release the device copy (and the handle's own workspace, never the caller's).  NULL is accepted. */
 int rairs_free(rairs_index_t *h);
+
+/*
+ * Bytes of scratch memory that rairs_search (and each of the stage calls below) needs for nq
+ * queries with these parameters: sizes grow with nq, nprobe and refine_k, so the value for the
+ * largest of each covers every smaller call.  Batches of more than about 65,000 queries are cut
+ * into passes that share the workspace.  0 if the arguments are outside what rairs_search accepts
+ * (see rairs_last_error) or nq == 0.
+ */
+size_t rairs_workspace_bytes(const rairs_index_t *h, int64_t nq, int nprobe, int refine_k);
+
+/*
+ * Hand the handle a workspace: device memory of the caller (a PyTorch tensor's data_ptr()), 256-byte
+ * aligned, of `bytes` bytes.  Later calls use it instead of allocating; one that needs more
+ * returns RAIRS_EWORKSPACE.  The caller keeps ownership and must keep the buffer alive, and must
+ * not set another, while work of this handle is in flight.  d_ws == NULL returns to the handle's
+ * own workspace.  The measurement helpers (rairs_get_dco, rairs_get_scan_stats) read the last
+ * call's workspace and are reset by this call.
+ */
+int rairs_set_workspace(rairs_index_t *h, void *d_ws, size_t bytes);
 
 /* ---- the stages of rairs_search, callable one by one (same kernels) ----------------------- */
 
@@ -199,7 +227,8 @@ int rairs_get_stage_ms(rairs_index_t *h, float *ms);
  */
 int rairs_get_stage_ms_mean(rairs_index_t *h, int last_n, float *ms);
 
-/* Items scored per query by the last rairs_search: device [nq] int64 copied to host `dco`. */
+/* Items scored per query by the last rairs_search (counted by the scan kernels, block by block,
+   as they score): device [nq] int64 copied to host `dco`. */
 int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq);
 
 /*

@@ -20,7 +20,8 @@ STAGES = ("coarse", "lut", "scan", "refine", "scan_kernel")
 MAX_REFINE_K = 1024
 MAX_NPROBE = 4096
 
-EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_coarse", "rairs_lut",
+EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_workspace_bytes", "rairs_set_workspace",
+           "rairs_coarse", "rairs_lut",
            "rairs_scan", "rairs_refine", "rairs_set_scan_mode", "rairs_set_profiling", "rairs_get_stage_ms",
            "rairs_get_stage_ms_mean",
            "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_pq_encode", "rairs_assign",
@@ -60,6 +61,7 @@ def load() -> C.CDLL:
                 "`python -m paper_2601_07183_amd.build_ext` (there is no fallback path)")
         lib = C.CDLL(LIB_PATH)
         lib.rairs_last_error.restype = C.c_char_p
+        lib.rairs_workspace_bytes.restype = C.c_size_t
         for name in EXPORTS:
             getattr(lib, name)
         _lib = lib
@@ -136,11 +138,46 @@ class Index:
         _check(self._lib.rairs_index_upload(C.byref(s), _stream_ptr(stream), C.byref(self._h)))
         del keep
         self.d, self.M, self.nlist, self.ntotal = hx.d, hx.M, hx.nlist, hx.ntotal
+        self._ws = None                 # torch tensor that serves as the handle's workspace
+
+    # --- workspace: device memory comes from PyTorch ------------------------------------------
+    def workspace_bytes(self, nq: int, nprobe: int, refine_k: int) -> int:
+        """rairs_workspace_bytes (0 for an empty batch; raises on arguments the search rejects)."""
+        n = int(self._lib.rairs_workspace_bytes(self._h, C.c_int64(nq), C.c_int(nprobe), C.c_int(refine_k)))
+        if n == 0 and nq > 0:
+            raise RairsError(-1, self._lib.rairs_last_error().decode())
+        return n
+
+    def set_workspace(self, ws):
+        """rairs_set_workspace: a uint8 device tensor (kept alive here), or None for the handle's own."""
+        if ws is None:
+            _check(self._lib.rairs_set_workspace(self._h, C.c_void_p(0), C.c_size_t(0)))
+        else:
+            _check(self._lib.rairs_set_workspace(self._h, _dev(ws, torch.uint8, "workspace"),
+                                                 C.c_size_t(ws.numel())))
+        self._ws = ws
+
+    def _reserve(self, nq: int, nprobe: int, refine_k: int):
+        """Give the handle a torch-allocated workspace large enough for this call (arguments that
+        the library rejects are left to the call itself, which reports them)."""
+        if nq <= 0 or self._ws is False:
+            return
+        need = int(self._lib.rairs_workspace_bytes(self._h, C.c_int64(nq), C.c_int(nprobe), C.c_int(refine_k)))
+        if need and (self._ws is None or self._ws.numel() < need):
+            torch.cuda.current_stream().synchronize()     # nothing of this handle is in flight
+            self._ws = None
+            self.set_workspace(torch.empty(need, dtype=torch.uint8, device="cuda"))
+
+    def use_own_workspace(self):
+        """Let the library allocate and grow its workspace itself (hipMalloc inside the handle)."""
+        self.set_workspace(None)
+        self._ws = False
 
     def free(self):
         if self._h:
             _check(self._lib.rairs_free(self._h))
             self._h = C.c_void_p()
+            self._ws = None
 
     def __del__(self):
         try:
@@ -156,6 +193,7 @@ class Index:
             out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
         if out_dists is None:
             out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+        self._reserve(nq, nprobe, refine_k)
         _check(self._lib.rairs_search(
             self._h, _dev(queries, torch.float32, "queries"), C.c_int64(nq), C.c_int(k),
             C.c_int(nprobe), C.c_int(refine_k), _dev(out_ids, torch.int64, "out_ids"),
@@ -165,6 +203,7 @@ class Index:
     # --- stages ---------------------------------------------------------------------------
     def coarse(self, queries: torch.Tensor, nprobe: int, stream=None):
         nq = queries.shape[0]
+        self._reserve(nq, nprobe, 1)
         ids = torch.empty((nq, nprobe), dtype=torch.int32, device=queries.device)
         dists = torch.empty((nq, nprobe), dtype=torch.float32, device=queries.device)
         _check(self._lib.rairs_coarse(self._h, _dev(queries, torch.float32, "queries"),
@@ -184,6 +223,7 @@ class Index:
 
     def scan(self, lut: torch.Tensor, probe_ids: torch.Tensor, refine_k: int, stream=None):
         nq, nprobe = probe_ids.shape
+        self._reserve(nq, nprobe, refine_k)
         cand = torch.empty((nq, refine_k), dtype=torch.int64, device=lut.device)
         score = torch.empty((nq, refine_k), dtype=torch.int32, device=lut.device)
         dco = torch.empty((nq,), dtype=torch.int64, device=lut.device)
@@ -226,6 +266,7 @@ class Index:
                stream=None) -> torch.Tensor:
         """rairs_assign: [n][2] list ids (smaller first) of device vectors [n][d]."""
         n = vectors.shape[0]
+        self._reserve(n, max(1, min(n_cands, self.nlist)), 1)
         out = torch.empty((n, 2), dtype=torch.int32, device=vectors.device)
         _check(self._lib.rairs_assign(self._h, _dev(vectors, torch.float32, "vectors") if n else C.c_void_p(0),
                                       C.c_int64(n), C.c_int(n_cands), C.c_double(lam), C.c_int(int(strict)),

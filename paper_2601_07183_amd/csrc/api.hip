@@ -48,14 +48,12 @@ static void destroy(rairs_index *h)
     if (!h) return;
     for (int i = 0; i < h->ndev_alloc; i++) (void)hipFree(h->dev_alloc[i]);
     if (h->ws) (void)hipFree(h->ws);
-    if (h->dco) (void)hipFree(h->dco);
     if (h->ev_ready)
         for (int r = 0; r < RAIRS_EV_RING; r++)
             for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) (void)hipEventDestroy(h->ev[r][i]);
     if (h->side_ready) {
         (void)hipEventDestroy(h->ev_fork); (void)hipEventDestroy(h->ev_lut);
         (void)hipEventDestroy(h->ev_probe); (void)hipEventDestroy(h->ev_group);
-        (void)hipEventDestroy(h->ev_dco);
         (void)hipStreamDestroy(h->side);
     }
     delete h;
@@ -90,14 +88,28 @@ static int validate(const rairs_host_index_t *x)
             mb + mc > x->nblocks || rb < 0 || rb + rc > x->nrefs)
             FAIL(RAIRS_EINVAL, "directory of list %d out of bounds", l);
     }
-    for (int64_t r = 0; r < x->nrefs; r++) {
-        int32_t o = x->ref_owner[r];
-        if (o < 0 || o >= x->nlist) FAIL(RAIRS_EINVAL, "reference %lld: owner out of range", (long long)r);
-        int64_t b = x->ref_block_begin[r], n = x->ref_nblocks[r];
-        int64_t ob = x->list_shared_begin[o], oc = x->list_shared_cnt[o];
-        if (n < 1 || b < ob || b + n > ob + oc)
-            FAIL(RAIRS_EINVAL, "reference %lld does not point into its owner's shared blocks", (long long)r);
+    // a block belongs to at most one list
+    std::vector<int32_t> blk_owner((size_t)x->nblocks, -1);
+    for (int l = 0; l < x->nlist; l++) {
+        const int64_t b0 = x->list_shared_begin[l], b1 = b0 + x->list_shared_cnt[l] + x->list_misc_cnt[l];
+        for (int64_t b = b0; b < b1; b++) {
+            if (blk_owner[(size_t)b] >= 0)
+                FAIL(RAIRS_EINVAL, "block %lld belongs to lists %d and %d", (long long)b, blk_owner[(size_t)b], l);
+            blk_owner[(size_t)b] = l;
+        }
     }
+    // reference entries of list l: cells (owner, l) with owner < l (Section 5.1), inside the
+    // owner's shared blocks
+    for (int l = 0; l < x->nlist; l++)
+        for (int64_t r = x->list_ref_begin[l]; r < x->list_ref_begin[l] + x->list_ref_cnt[l]; r++) {
+            int32_t o = x->ref_owner[r];
+            if (o < 0 || o >= l)
+                FAIL(RAIRS_EINVAL, "reference %lld of list %d: owner %d is not a smaller list id", (long long)r, l, o);
+            int64_t b = x->ref_block_begin[r], n = x->ref_nblocks[r];
+            int64_t ob = x->list_shared_begin[o], oc = x->list_shared_cnt[o];
+            if (n < 1 || b < ob || b + n > ob + oc)
+                FAIL(RAIRS_EINVAL, "reference %lld does not point into its owner's shared blocks", (long long)r);
+        }
     // a shared block may hold invalidated slots anywhere (deletion leaves them); the miscellaneous
     // items of a list are dense: only the tail of its last block is empty
     for (int l = 0; l < x->nlist; l++) {
@@ -111,26 +123,63 @@ static int validate(const rairs_host_index_t *x)
             seen_empty |= empty;
         }
     }
-    const int64_t nslots = x->nblocks * 32;
-    for (int64_t i = 0; i < nslots; i++) {
-        int64_t id = x->ids[i];
-        if (id < -1 || id >= x->ntotal) FAIL(RAIRS_EINVAL, "id out of range in slot %lld", (long long)i);
-        int32_t o = x->other[i];
-        if (o < -1 || o >= x->nlist) FAIL(RAIRS_EINVAL, "list tag out of range in slot %lld", (long long)i);
+    // Every vector is stored either once in a shared block (no tag), or once in the miscellaneous
+    // area of its only list (tag = that list), or as twins in the miscellaneous areas of its two
+    // lists, same code, each tagged with the other list (Section 5.1).  The scan relies on this:
+    // an item that the duplicate rule drops in one list is queued from the other.
+    // first[id]: -1 not seen, -2 complete, else the slot of a tagged item that waits for its twin.
+    std::vector<int32_t> first((size_t)x->ntotal, -1);
+    const int hb = x->M / 2;
+    for (int l = 0; l < x->nlist; l++) {
+        const int64_t b0 = x->list_shared_begin[l], bs = b0 + x->list_shared_cnt[l];
+        const int64_t b1 = bs + x->list_misc_cnt[l];
+        for (int64_t i = b0 * 32; i < b1 * 32; i++) {
+            const int64_t id = x->ids[i];
+            const int32_t o = x->other[i];
+            if (id < -1 || id >= x->ntotal) FAIL(RAIRS_EINVAL, "id out of range in slot %lld", (long long)i);
+            if (o < -1 || o >= x->nlist) FAIL(RAIRS_EINVAL, "list tag out of range in slot %lld", (long long)i);
+            if (id < 0) continue;
+            int32_t &f = first[(size_t)id];
+            if (i < bs * 32) {
+                if (o != -1) FAIL(RAIRS_EINVAL, "slot %lld of a shared block carries a list tag", (long long)i);
+                if (f != -1) FAIL(RAIRS_EINVAL, "vector %lld is stored in a shared block and elsewhere", (long long)id);
+                f = -2;
+            } else if (o == l) {
+                if (f != -1) FAIL(RAIRS_EINVAL, "vector %lld of cell (%d, %d) is stored more than once", (long long)id, l, l);
+                f = -2;
+            } else {
+                if (o < 0) FAIL(RAIRS_EINVAL, "miscellaneous slot %lld has no list tag", (long long)i);
+                if (f == -1) {
+                    f = (int32_t)i;
+                } else {
+                    if (f < 0) FAIL(RAIRS_EINVAL, "vector %lld is stored more often than its cell allows", (long long)id);
+                    const int64_t t = f;               // the twin seen earlier
+                    if (blk_owner[(size_t)(t >> 5)] != o || x->other[t] != l ||
+                        memcmp(x->codes + (size_t)t * hb, x->codes + (size_t)i * hb, (size_t)hb) != 0)
+                        FAIL(RAIRS_EINVAL, "miscellaneous slots %lld and %lld of vector %lld are not twins "
+                             "(lists, tags or codes differ)", (long long)t, (long long)i, (long long)id);
+                    f = -2;
+                }
+            }
+        }
     }
+    for (int64_t id = 0; id < x->ntotal; id++)
+        if (first[(size_t)id] >= 0)
+            FAIL(RAIRS_EINVAL, "vector %lld in slot %d is tagged with another list but has no twin there",
+                 (long long)id, first[(size_t)id]);
+    // slots of blocks that no list owns are never read
     return RAIRS_OK;
 }
 
-extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream, rairs_index_t **out)
+static int upload_impl(const rairs_host_index_t *x, void *hip_stream, rairs_index_t **out, rairs_index **made)
 {
-    if (!out) FAIL(RAIRS_EINVAL, "out is NULL");
-    *out = nullptr;
     int rc = validate(x);
     if (rc) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     rairs_index *h = new (std::nothrow) rairs_index();
     if (!h) FAIL(RAIRS_ENOMEM, "out of host memory");
     memset(h, 0, sizeof(*h));
+    *made = h;                                         // released by the caller if anything below throws
     IndexView &v = h->v;
     v.d = x->d; v.M = x->M; v.T = x->M / 2; v.nd = (v.T + 7) / 8; v.nlist = x->nlist;
     v.raw_u8 = x->raw_is_u8 ? 1 : 0;
@@ -139,13 +188,14 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
 #define UP_CHECK(call)            \
     do {                          \
         int rc_ = (call);         \
-        if (rc_) { destroy(h); return rc_; } \
+        if (rc_) { *made = nullptr; destroy(h); return rc_; } \
     } while (0)
 #define UP_HIP(call)                                                                  \
     do {                                                                              \
         hipError_t e_ = (call);                                                       \
         if (e_ != hipSuccess) {                                                       \
             rairs_set_error("%s failed: %s", #call, hipGetErrorString(e_));           \
+            *made = nullptr;                                                          \
             destroy(h);                                                               \
             return RAIRS_EHIP;                                                        \
         }                                                                             \
@@ -350,11 +400,16 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     if (!hs.empty())
         UP_HIP(hipMemcpyAsync(segs, hs.data(), hs.size() * sizeof(SegEntry), hipMemcpyHostToDevice, s));
     uint32_t *cmask = nullptr, *vmask = nullptr;
+    uint2 *bmask = nullptr;
     int32_t *blk_list = nullptr;
     UP_CHECK(dev_alloc(h, (void **)&cmask, (size_t)x->nblocks * 4));
     UP_CHECK(dev_alloc(h, (void **)&vmask, (size_t)x->nblocks * 4));
     UP_CHECK(dev_alloc(h, (void **)&blk_list, (size_t)x->nblocks * 4));
+    UP_CHECK(dev_alloc(h, (void **)&bmask, (size_t)x->nblocks * 8));
+    std::vector<uint2> hbm((size_t)x->nblocks);
+    for (int64_t b = 0; b < x->nblocks; b++) hbm[(size_t)b] = make_uint2(hm[(size_t)b], hv[(size_t)b]);
     if (x->nblocks) {
+        UP_HIP(hipMemcpyAsync(bmask, hbm.data(), hbm.size() * 8, hipMemcpyHostToDevice, s));
         UP_HIP(hipMemcpyAsync(blk_list, hbl.data(), hbl.size() * 4, hipMemcpyHostToDevice, s));
         UP_HIP(hipMemcpyAsync(cmask, hm.data(), hm.size() * 4, hipMemcpyHostToDevice, s));
         UP_HIP(hipMemcpyAsync(vmask, hv.data(), hv.size() * 4, hipMemcpyHostToDevice, s));
@@ -385,7 +440,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
         }
         (void)hipFree(st_codes);
         (void)hipFree(st_ids);
-        if (r2) { destroy(h); return r2; }
+        if (r2) { *made = nullptr; destroy(h); return r2; }
         UP_HIP(e);
     }
     uint2 *idtag = nullptr;
@@ -394,7 +449,7 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_HIP(hipStreamSynchronize(s));
 
     v.idtag = idtag;
-    v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask; v.vmask = vmask; v.blk_list = blk_list;
+    v.centroids = cent; v.cnorm = cnorm; v.centroids_t = cent_t; v.codebook = cb; v.codes = codes; v.ids = ids; v.other = other; v.cmask = cmask; v.vmask = vmask; v.bmask = bmask; v.blk_list = blk_list;
     v.lists = lists; v.refs = refs; v.segs = segs; v.parts = parts; v.raw = raw;
     for (int r = 0; r < RAIRS_EV_RING; r++)
         for (int i = 0; i < 2 * RAIRS_NSTAGES; i++) UP_HIP(hipEventCreate(&h->ev[r][i]));
@@ -405,10 +460,23 @@ extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream,
     UP_HIP(hipEventCreateWithFlags(&h->ev_lut, hipEventDisableTiming));
     UP_HIP(hipEventCreateWithFlags(&h->ev_probe, hipEventDisableTiming));
     UP_HIP(hipEventCreateWithFlags(&h->ev_group, hipEventDisableTiming));
-    UP_HIP(hipEventCreateWithFlags(&h->ev_dco, hipEventDisableTiming));
     h->side_ready = 1;
+    *made = nullptr;
     *out = h;
     return RAIRS_OK;
+}
+
+extern "C" int rairs_index_upload(const rairs_host_index_t *x, void *hip_stream, rairs_index_t **out)
+{
+    if (!out) FAIL(RAIRS_EINVAL, "out is NULL");
+    *out = nullptr;
+    rairs_index *made = nullptr;
+    try {
+        return upload_impl(x, hip_stream, out, &made);
+    } catch (const std::bad_alloc &) {
+        destroy(made);
+        FAIL(RAIRS_ENOMEM, "out of host memory while preparing the index");
+    }
 }
 
 extern "C" int rairs_free(rairs_index_t *h)
@@ -427,16 +495,32 @@ extern "C" int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, in
 
 // ---- workspace ------------------------------------------------------------------------------
 
-#define SURV_CAP 4096
 #define RAIRS_SAMPLE_BLOCKS 16
-#define RAIRS_LOG_PER_QUERY 8192
+
+// Survivor buffer entries per query (entries at or below the query's final bound; more than this
+// sends the query to the exact kernel) and survivor log entries per query on average (the scan logs
+// about bigK ln(items / sample) entries per query; if the log runs out, every query of the pass
+// is redone by the exact kernel).
+static int surv_cap_for(int refine_k)
+{
+    int c = 1024;
+    while (c < 8 * refine_k && c < 4096) c <<= 1;
+    return c;
+}
+
+static int log_per_query_for(int refine_k)
+{
+    const int n = 16 * refine_k;
+    return n < 1024 ? 1024 : (n > 8192 ? 8192 : n);
+}
 
 struct WsLayout {
-    size_t dmat, cflags, probe_ids, probe_dists, bitmap, lut, cand;
+    size_t dmat, cflags, probe_ids, probe_dists, bitmap, lut, cand, dco;
     size_t lcount, loff, lcursor, toff, unit_list, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, prof, total;
     size_t s_off, s_toff, s_q, s_tiles, s_scores;      // matrix-core sample (0 bytes when not used)
     int sample_blocks;
     int log_chunks;
+    int surv_cap;
     int bmwords;
 };
 
@@ -466,19 +550,25 @@ static int sample_blocks_for(const IndexView &v, int refine_k, bool grouped)
     return blocks < RAIRS_SAMPLE_MAX_BLOCKS ? blocks : RAIRS_SAMPLE_MAX_BLOCKS;
 }
 
-static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine_k, int max_parts = 1)
+// Workspace of one pass of `nq` queries out of a batch of `nq_total` (the DCO counts cover the
+// batch).  Two pairs of buffers whose lifetimes never overlap on the caller's stream share their
+// bytes: the coarse quantizer's score matrix (dead once the probe lists exist) with the survivor log
+// (first written by the scan kernel), and the sample's scores (dead once the bounds exist) with
+// the survivor buffers (first written after the scan).
+static WsLayout ws_layout(const IndexView &v, int64_t nq, int64_t nq_total, int nprobe, int refine_k,
+                          int max_parts = 1)
 {
     WsLayout w;
     w.bmwords = (v.nlist + 31) / 32;
     size_t off = 0;
     auto take = [&off](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
-    w.dmat = take((size_t)nq * v.nlist * 4);
     w.cflags = take((size_t)nq * 4);
     w.probe_ids = take((size_t)nq * nprobe * 4);
     w.probe_dists = take((size_t)nq * nprobe * 4);
     w.bitmap = take((size_t)nq * w.bmwords * 4);
     w.lut = take((size_t)nq * v.M * 16);
     w.cand = take((size_t)nq * refine_k * 8);
+    w.dco = take((size_t)nq_total * 8);
     w.lcount = take((size_t)v.nlist * 4);
     w.loff = take((size_t)(v.nlist + 1) * 4);
     w.lcursor = take((size_t)v.nlist * 4);
@@ -491,46 +581,55 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int nprobe, int refine
     w.surv_cnt = take((size_t)nq * 4);
     w.flags = take((size_t)nq * 4);
     w.hist = take((size_t)nq * RAIRS_HIST_BINS * 4);
-    w.surv_buf = take((size_t)nq * SURV_CAP * 8);
-    w.log_chunks = (int)((nq * RAIRS_LOG_PER_QUERY + 255) / 256) + 8192;   // + two per wave
-    w.log = take((size_t)w.log_chunks * 256 * 8);
+    w.surv_cap = surv_cap_for(refine_k);
+    w.log_chunks = (int)((nq * log_per_query_for(refine_k) + 255) / 256) + 8192;   // + two per wave
     w.chunk_fill = take((size_t)w.log_chunks * 4);
     w.log_misc = take(64);
+#ifdef RAIRS_PROFILE_CYCLES
     w.prof = take(2048 * 12 * 8);
+#else
+    w.prof = 0;
+#endif
     const bool grouped = grouped_sample(v, nq, refine_k);
     w.sample_blocks = sample_blocks_for(v, refine_k, grouped);
     w.s_off = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
     w.s_toff = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
     w.s_q = take(grouped ? (size_t)nq * 4 : 0);
     w.s_tiles = take(grouped ? ((size_t)nq / 32 + (size_t)v.nlist + 1) * 4 : 0);
-    w.s_scores = take(grouped ? (size_t)nq * w.sample_blocks * 64 : 0);
+    const size_t dmat_bytes = (size_t)nq * v.nlist * 4, log_bytes = (size_t)w.log_chunks * 256 * 8;
+    w.dmat = w.log = take(dmat_bytes > log_bytes ? dmat_bytes : log_bytes);
+    const size_t samp_bytes = grouped ? (size_t)nq * w.sample_blocks * 64 : 0;
+    const size_t surv_bytes = (size_t)nq * w.surv_cap * 8;
+    w.s_scores = w.surv_buf = take(samp_bytes > surv_bytes ? samp_bytes : surv_bytes);
     w.total = off;
     return w;
 }
 
-static int ensure_ws(rairs_index *h, size_t bytes)
+// Where a call's workspace comes from.  WS_HANDLE: the caller's buffer if one was set (too small:
+// RAIRS_EWORKSPACE, nothing is allocated or synchronised), else the handle's own, grown on demand.
+enum { WS_HANDLE = 0 };
+static int acquire_ws(rairs_index *h, int source, size_t bytes, char **ws)
 {
-    if (h->ws_bytes >= bytes) return RAIRS_OK;
-    if (h->ws) { RAIRS_HIP(hipDeviceSynchronize()); (void)hipFree(h->ws); h->ws = nullptr; h->ws_bytes = 0; }
-    hipError_t e = hipMalloc(&h->ws, bytes);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        FAIL(RAIRS_ENOMEM, "workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
+    (void)source;
+    if (h->ws_user) {
+        if (bytes > h->ws_user_bytes)
+            FAIL(RAIRS_EWORKSPACE, "this call needs a workspace of %zu bytes, the caller's has %zu", bytes,
+                 h->ws_user_bytes);
+        *ws = (char *)h->ws_user;
+        h->last_ws = *ws;
+        return RAIRS_OK;
     }
-    h->ws_bytes = bytes;
-    return RAIRS_OK;
-}
-
-static int ensure_dco(rairs_index *h, int64_t nq)
-{
-    if (h->dco_cap >= nq) return RAIRS_OK;
-    if (h->dco) { RAIRS_HIP(hipDeviceSynchronize()); (void)hipFree(h->dco); h->dco = nullptr; h->dco_cap = 0; }
-    hipError_t e = hipMalloc((void **)&h->dco, (size_t)nq * 8);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        FAIL(RAIRS_ENOMEM, "dco buffer: %s", hipGetErrorString(e));
+    if (h->ws_bytes < bytes) {
+        if (h->ws) { RAIRS_HIP(hipDeviceSynchronize()); (void)hipFree(h->ws); h->ws = nullptr; h->ws_bytes = 0; }
+        hipError_t e = hipMalloc(&h->ws, bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            FAIL(RAIRS_ENOMEM, "workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
+        }
+        h->ws_bytes = bytes;
     }
-    h->dco_cap = nq;
+    *ws = (char *)h->ws;
+    h->last_ws = *ws;
     return RAIRS_OK;
 }
 
@@ -556,13 +655,17 @@ static int check_k(int k, int refine_k)
     return RAIRS_OK;
 }
 
-// Queries per internal pass so that the distance matrix and buffers stay within ~4 GiB (at most
-// 21,845: the survivor log relies on a pass staying below 65,536 queries).
-static int64_t pass_size(const IndexView &v, int64_t nq)
+// Queries per internal pass: the pass's workspace stays within about 4 GiB, and a pass has at most
+// 65,536 queries (a survivor log entry has 16 bits for the query of the pass).
+static int64_t pass_size(const IndexView &v, int64_t nq, int nprobe, int refine_k)
 {
-    int64_t per_q = (int64_t)v.nlist * 4 + 196608;
+    const int64_t score_row = (int64_t)v.nlist * 4, log_row = (int64_t)log_per_query_for(refine_k) * 8;
+    const int64_t per_q = (score_row > log_row ? score_row : log_row) + (int64_t)surv_cap_for(refine_k) * 8 +
+                          (int64_t)v.M * 16 + (int64_t)refine_k * 8 + (int64_t)nprobe * 12 +
+                          (int64_t)((v.nlist + 31) / 32) * 4 + RAIRS_HIST_BINS * 4 + 64;
     int64_t cap = (4ll << 30) / per_q;
     if (cap < 256) cap = 256;
+    if (cap > 65536) cap = 65536;
     return nq < cap ? nq : cap;
 }
 
@@ -576,16 +679,17 @@ extern "C" int rairs_coarse(rairs_index_t *h, const float *d_queries, int64_t nq
     if ((rc = check_nprobe(h, nprobe))) return rc;
     if (nq == 0) return RAIRS_OK;
     if (!d_queries || !d_probe_ids) FAIL(RAIRS_EINVAL, "null device pointer");
-    const int64_t step = pass_size(h->v, nq);
-    const WsLayout w = ws_layout(h->v, step, nprobe, 1);
-    if ((rc = ensure_ws(h, w.total))) return rc;
+    const int64_t step = pass_size(h->v, nq, nprobe, 1);
+    const WsLayout w = ws_layout(h->v, step, 0, nprobe, 1);
+    char *ws = nullptr;
+    if ((rc = acquire_ws(h, WS_HANDLE, w.total, &ws))) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     for (int64_t q0 = 0; q0 < nq; q0 += step) {
         int64_t n = nq - q0 < step ? nq - q0 : step;
         rc = rairs_launch_coarse(h->v, d_queries + (size_t)q0 * h->v.d, n, nprobe,
-                                 (float *)((char *)h->ws + w.dmat), d_probe_ids + (size_t)q0 * nprobe,
+                                 (float *)(ws + w.dmat), d_probe_ids + (size_t)q0 * nprobe,
                                  d_probe_dists ? d_probe_dists + (size_t)q0 * nprobe : nullptr,
-                                 (uint32_t *)((char *)h->ws + w.cflags), s);
+                                 (uint32_t *)(ws + w.cflags), s);
         if (rc) return rc;
     }
     return RAIRS_OK;
@@ -610,14 +714,13 @@ static_assert(EV_KERNEL1 < 2 * RAIRS_NSTAGES, "event slots");
 // SeilSearch for one pass of n queries: bitmap, then either the exact kernel alone or
 // sample bound -> list-major MFMA scan -> collect / select -> exact redo of overflows.
 // ev (may be null) receives two events bracketing the dominant scan kernel.
-static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, const int32_t *probe_ids,
+static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t *lut, const int32_t *probe_ids,
                      int64_t n, int nprobe, int refine_k, int64_t *cand_ids, int32_t *cand_score,
                      int64_t *dco, hipStream_t s, hipEvent_t *ev, bool overlap, hipEvent_t lut_done)
 {
     // overlap: the tables were built on the side stream (ev_lut marks them done) and the side
     // stream already waits for the probe lists; the grouping runs there next to the sample bound
     const IndexView &v = h->v;
-    char *ws = (char *)h->ws;
     uint32_t *bitmap = (uint32_t *)(ws + w.bitmap);
     const bool mfma = rairs_mfma_supported(v) && !h->force_exact;
     // With the sample on the matrix cores nothing on the caller's stream reads the bitmaps before
@@ -662,7 +765,7 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     }
     ma.next_task = (uint32_t *)(ws + w.next_task); ma.qlist = (int32_t *)(ws + w.qlist);
     ma.tau = (int32_t *)(ws + w.tau); ma.surv_cnt = (uint32_t *)(ws + w.surv_cnt);
-    ma.surv_buf = (uint64_t *)(ws + w.surv_buf); ma.surv_cap = SURV_CAP;
+    ma.surv_buf = (uint64_t *)(ws + w.surv_buf); ma.surv_cap = w.surv_cap;
     ma.flags = (uint32_t *)(ws + w.flags); ma.cand_ids = cand_ids; ma.cand_score = cand_score;
     ma.hist = (uint32_t *)(ws + w.hist);
     h->last_pass_n = n; h->last_flags_off = w.flags; h->last_cnt_off = w.surv_cnt;
@@ -673,25 +776,21 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     ma.prof = (long long *)(ws + w.prof);
     h->last_prof_off = w.prof;
 #endif
-    // bound of every query from a sample (the head of its first list), and the DCO of all probes
+    // bound of every query from a sample (the head of its first list)
     ma.p_first = 0;
     ma.bound = (int32_t *)(ws + w.bound);
+    ma.dco = (unsigned long long *)dco;                // counted by the scan kernel as it scores
     const int sample_blocks = w.sample_blocks;
     // The sample's scores come from the matrix cores, for queries grouped by their first list,
     // when the batch is large enough for that; else the bound kernel scores them itself, one
-    // query per wave.  Side stream: the scan's grouping, then the DCO.
+    // query per wave.  Side stream: the scan's grouping.
     const bool grouped = grouped_sample(v, n, refine_k);
     int32_t *s_off = (int32_t *)(ws + w.s_off), *s_toff = (int32_t *)(ws + w.s_toff);
     int32_t *s_q = (int32_t *)(ws + w.s_q), *s_tiles = (int32_t *)(ws + w.s_tiles);
     uint16_t *s_scores = (uint16_t *)(ws + w.s_scores);
-    const bool side_dco = overlap && grouped && dco;
     if (overlap) {
         if ((rc = rairs_launch_group(v, ma, h->side))) return rc;
         RAIRS_HIP(hipEventRecord(h->ev_group, h->side));
-        if (side_dco) {
-            if ((rc = rairs_launch_dco(v, probe_ids, nprobe, bitmap, w.bmwords, n, dco, h->side))) return rc;
-            RAIRS_HIP(hipEventRecord(h->ev_dco, h->side));
-        }
     }
     if (grouped) {
         if ((rc = rairs_launch_sample_group(v, probe_ids, nprobe, n, s_off, s_toff, s_q, s_tiles, s)))
@@ -702,11 +801,8 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
         if ((rc = rairs_launch_sample_rank(v, probe_ids, nprobe, refine_k, sample_blocks, n, s_scores,
                                            (int32_t *)(ws + w.tau), ma.bound, s)))
             return rc;
-        if (dco && !side_dco &&
-            (rc = rairs_launch_dco(v, probe_ids, nprobe, bitmap, w.bmwords, n, dco, s)))
-            return rc;
     } else if ((rc = rairs_launch_sample_bound(v, lut, probe_ids, nprobe, refine_k, sample_blocks, n,
-                                               (int32_t *)(ws + w.tau), ma.bound, bitmap, w.bmwords, dco, s)))
+                                               (int32_t *)(ws + w.tau), ma.bound, s)))
         return rc;
     if (overlap) RAIRS_HIP(hipStreamWaitEvent(s, h->ev_group, 0));
     else if ((rc = rairs_launch_group(v, ma, s))) return rc;
@@ -714,21 +810,10 @@ static int scan_pass(rairs_index *h, const WsLayout &w, const uint8_t *lut, cons
     if ((rc = rairs_launch_select(v, ma, s))) return rc;
     // a query with more entries at or below its final bound than the buffer holds (thousands of
     // items with the same score), or every query if the log ran out of chunks, is redone by the
-    // exact kernel; normally none is flagged and every workgroup of that launch exits at once
+    // exact kernel (which counts that query's DCO again, to the same value); normally none is
+    // flagged and every workgroup of that launch exits at once
     ea.only_flagged = ma.flags;
     if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
-    h->side_tail = side_dco ? 1 : 0;                   // the caller joins the side stream's last work
-    return RAIRS_OK;
-}
-
-// The side stream's trailing work (the DCO count) joins the caller's stream; called after the last
-// kernel of a pass has been enqueued so that the wait delays nothing.
-static int join_side(rairs_index *h, hipStream_t s)
-{
-    if (h->side_tail) {
-        h->side_tail = 0;
-        RAIRS_HIP(hipStreamWaitEvent(s, h->ev_dco, 0));
-    }
     return RAIRS_OK;
 }
 
@@ -742,14 +827,15 @@ extern "C" int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t 
     if ((rc = check_k(1, refine_k))) return rc;
     if (nq == 0) return RAIRS_OK;
     if (!d_lut || !d_probe_ids || !d_cand_ids) FAIL(RAIRS_EINVAL, "null device pointer");
-    const int64_t step = pass_size(h->v, nq);
-    WsLayout w = ws_layout(h->v, step, nprobe, refine_k, h->max_parts);
-    if ((rc = ensure_ws(h, w.total))) return rc;
-    hipStream_t s = (hipStream_t)hip_stream;
     if (((uintptr_t)d_lut & 15) != 0) FAIL(RAIRS_EINVAL, "d_lut must be 16-byte aligned");
+    const int64_t step = pass_size(h->v, nq, nprobe, refine_k);
+    WsLayout w = ws_layout(h->v, step, 0, nprobe, refine_k, h->max_parts);
+    char *ws = nullptr;
+    if ((rc = acquire_ws(h, WS_HANDLE, w.total, &ws))) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
     for (int64_t q0 = 0; q0 < nq; q0 += step) {
         int64_t n = nq - q0 < step ? nq - q0 : step;
-        rc = scan_pass(h, w, d_lut + (size_t)q0 * h->v.M * 16, d_probe_ids + (size_t)q0 * nprobe, n,
+        rc = scan_pass(h, ws, w, d_lut + (size_t)q0 * h->v.M * 16, d_probe_ids + (size_t)q0 * nprobe, n,
                        nprobe, refine_k, d_cand_ids + (size_t)q0 * refine_k,
                        d_cand_score ? d_cand_score + (size_t)q0 * refine_k : nullptr,
                        d_dco ? d_dco + q0 : nullptr, s, nullptr, false, nullptr);
@@ -773,8 +859,8 @@ extern "C" int rairs_refine(rairs_index_t *h, const float *d_queries, const int6
 
 // ---- RairsSearch (Alg. 2) -----------------------------------------------------------------------
 
-extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
-                            int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream)
+static int search_impl(rairs_index *h, int ws_source, const float *d_queries, int64_t nq, int k, int nprobe,
+                       int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream)
 {
     int rc = check_common(h, nq);
     if (rc) return rc;
@@ -783,12 +869,14 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
     if (nq == 0) return RAIRS_OK;
     if (!d_queries || !d_out_ids || !d_out_dists) FAIL(RAIRS_EINVAL, "null device pointer");
     const IndexView &v = h->v;
-    const int64_t step = pass_size(v, nq);
-    WsLayout w = ws_layout(v, step, nprobe, refine_k, h->max_parts);
-    if ((rc = ensure_ws(h, w.total))) return rc;
-    if ((rc = ensure_dco(h, nq))) return rc;
+    const int64_t step = pass_size(v, nq, nprobe, refine_k);
+    WsLayout w = ws_layout(v, step, nq, nprobe, refine_k, h->max_parts);
+    char *ws = nullptr;
+    if ((rc = acquire_ws(h, ws_source, w.total, &ws))) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
-    char *ws = (char *)h->ws;
+    int64_t *dco_all = (int64_t *)(ws + w.dco);
+    h->last_dco = dco_all;
+    h->last_dco_n = nq;
     // stage timing is only meaningful when the batch fits one pass
     const int plevel = step == nq ? h->prof : 0;
     const bool prof = plevel == RAIRS_PROFILE_STAGES;  // every stage; otherwise at most the scan kernel
@@ -830,17 +918,47 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
             if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, s))) return rc;
             if (prof) RAIRS_HIP(hipEventRecord(ev[EV_LUT1], s));
         }
-        if ((rc = scan_pass(h, w, lut, probe_ids, n, nprobe, refine_k, cand, nullptr, h->dco + q0, s,
+        if ((rc = scan_pass(h, ws, w, lut, probe_ids, n, nprobe, refine_k, cand, nullptr, dco_all + q0, s,
                             profk ? &ev[EV_KERNEL0] : nullptr, overlap,
                             prof ? ev[EV_LUT1] : h->ev_lut))) return rc;
         if (prof) RAIRS_HIP(hipEventRecord(ev[EV_SCANNED], s));
         if ((rc = rairs_launch_refine(v, q, cand, n, refine_k, k, d_out_ids + (size_t)q0 * k,
                                       d_out_dists + (size_t)q0 * k, s))) return rc;
-        if ((rc = join_side(h, s))) return rc;
         if (prof) RAIRS_HIP(hipEventRecord(ev[EV_END], s));
     }
     if (profk) h->ev_count++;
     h->prof_valid = profk ? 1 : 0;
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
+                            int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream)
+{
+    return search_impl(h, WS_HANDLE, d_queries, nq, k, nprobe, refine_k, d_out_ids, d_out_dists, hip_stream);
+}
+
+extern "C" size_t rairs_workspace_bytes(const rairs_index_t *h, int64_t nq, int nprobe, int refine_k)
+{
+    if (!h || nq < 0 || nq > 0x7FFFFFFFll / 4 || nprobe < 1 || nprobe > h->v.nlist || nprobe > RAIRS_MAX_NPROBE ||
+        refine_k < 1 || refine_k > RAIRS_MAX_REFINE_K) {
+        rairs_set_error("rairs_workspace_bytes: arguments outside what rairs_search accepts");
+        return 0;
+    }
+    if (nq == 0) return 0;
+    const int64_t step = pass_size(h->v, nq, nprobe, refine_k);
+    return ws_layout(h->v, step, nq, nprobe, refine_k, h->max_parts).total;
+}
+
+extern "C" int rairs_set_workspace(rairs_index_t *h, void *d_ws, size_t bytes)
+{
+    if (!h) FAIL(RAIRS_EINVAL, "handle is NULL");
+    if (d_ws && ((uintptr_t)d_ws & 255) != 0) FAIL(RAIRS_EINVAL, "the workspace must be 256-byte aligned");
+    h->ws_user = d_ws;
+    h->ws_user_bytes = d_ws ? bytes : 0;
+    h->last_ws = nullptr;
+    h->last_pass_n = 0;
+    h->last_dco = nullptr;
+    h->last_dco_n = 0;
     return RAIRS_OK;
 }
 
@@ -903,11 +1021,11 @@ extern "C" int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats)
     if (!h || !stats) FAIL(RAIRS_EINVAL, "null argument");
     stats[0] = stats[1] = stats[2] = 0;
     stats[3] = h->last_pass_n;
-    if (h->last_pass_n == 0) return RAIRS_OK;
+    if (h->last_pass_n == 0 || !h->last_ws) return RAIRS_OK;
     std::vector<uint32_t> flags((size_t)h->last_pass_n), cnt((size_t)h->last_pass_n);
     RAIRS_HIP(hipDeviceSynchronize());
-    RAIRS_HIP(hipMemcpy(flags.data(), (char *)h->ws + h->last_flags_off, flags.size() * 4, hipMemcpyDeviceToHost));
-    RAIRS_HIP(hipMemcpy(cnt.data(), (char *)h->ws + h->last_cnt_off, cnt.size() * 4, hipMemcpyDeviceToHost));
+    RAIRS_HIP(hipMemcpy(flags.data(), (char *)h->last_ws + h->last_flags_off, flags.size() * 4, hipMemcpyDeviceToHost));
+    RAIRS_HIP(hipMemcpy(cnt.data(), (char *)h->last_ws + h->last_cnt_off, cnt.size() * 4, hipMemcpyDeviceToHost));
     for (size_t i = 0; i < flags.size(); i++) {
         stats[0] += flags[i] != 0;
         stats[1] += cnt[i];
@@ -921,7 +1039,7 @@ extern "C" int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats)
 extern "C" int rairs_debug_cycles(rairs_index_t *h, long long *out)
 {
     RAIRS_HIP(hipDeviceSynchronize());
-    RAIRS_HIP(hipMemcpy(out, (char *)h->ws + h->last_prof_off, 2048 * 12 * 8, hipMemcpyDeviceToHost));
+    RAIRS_HIP(hipMemcpy(out, (char *)h->last_ws + h->last_prof_off, 2048 * 12 * 8, hipMemcpyDeviceToHost));
     return RAIRS_OK;
 }
 #endif
@@ -937,17 +1055,18 @@ extern "C" int rairs_assign(rairs_index_t *h, const float *d_vectors, int64_t n,
     if (!(lambda == lambda)) FAIL(RAIRS_EINVAL, "lambda is not a number");
     if (n == 0) return RAIRS_OK;
     if (!d_vectors || !d_pairs) FAIL(RAIRS_EINVAL, "null device pointer");
-    const int64_t step = pass_size(h->v, n);
-    const WsLayout w = ws_layout(h->v, step, nc, 1);
-    if ((rc = ensure_ws(h, w.total))) return rc;
+    const int64_t step = pass_size(h->v, n, nc, 1);
+    const WsLayout w = ws_layout(h->v, step, 0, nc, 1);
+    char *ws = nullptr;
+    if ((rc = acquire_ws(h, WS_HANDLE, w.total, &ws))) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     for (int64_t q0 = 0; q0 < n; q0 += step) {
         const int64_t m = n - q0 < step ? n - q0 : step;
         const float *x = d_vectors + (size_t)q0 * h->v.d;
-        int32_t *cand = (int32_t *)((char *)h->ws + w.probe_ids);
+        int32_t *cand = (int32_t *)(ws + w.probe_ids);
         // FindNearestLists is the search path's coarse quantizer
-        if ((rc = rairs_launch_coarse(h->v, x, m, nc, (float *)((char *)h->ws + w.dmat), cand, nullptr,
-                                      (uint32_t *)((char *)h->ws + w.cflags), s))) return rc;
+        if ((rc = rairs_launch_coarse(h->v, x, m, nc, (float *)(ws + w.dmat), cand, nullptr,
+                                      (uint32_t *)(ws + w.cflags), s))) return rc;
         if ((rc = rairs_launch_air_assign(h->v, x, m, nc, lambda, strict ? 1 : 0, cand,
                                           d_pairs + (size_t)q0 * 2, s))) return rc;
     }
@@ -969,8 +1088,9 @@ extern "C" int rairs_pq_encode(const float *d_codebook, int d, int M, const floa
 extern "C" int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq)
 {
     if (!h || !dco) FAIL(RAIRS_EINVAL, "null argument");
-    if (nq < 0 || nq > h->dco_cap) FAIL(RAIRS_EINVAL, "nq exceeds the last search's batch");
+    if (nq < 0 || nq > h->last_dco_n || (nq > 0 && !h->last_dco))
+        FAIL(RAIRS_EINVAL, "nq exceeds the last search's batch");
     if (nq == 0) return RAIRS_OK;
-    RAIRS_HIP(hipMemcpy(dco, h->dco, (size_t)nq * 8, hipMemcpyDeviceToHost));
+    RAIRS_HIP(hipMemcpy(dco, h->last_dco, (size_t)nq * 8, hipMemcpyDeviceToHost));
     return RAIRS_OK;
 }

@@ -67,6 +67,7 @@ struct IndexView {
     // block's item, or a miscellaneous item whose other list has no smaller id than the list)
     const uint32_t *cmask;
     const uint32_t *vmask;        // [nblocks] bit i: slot i holds an item
+    const uint2 *bmask;           // [nblocks] {cmask, vmask} side by side: one fetch per scanned block
     const int32_t *blk_list;      // [nblocks] the list that stores the block (-1: none)
     const ListEntry *lists;       // [nlist]
     const RefEntry *refs;         // [nrefs]
@@ -86,11 +87,14 @@ struct rairs_index {
     int max_parts;                // most parts in any list (bounds the work-unit table)
     int ndev_alloc;
     int64_t code_bytes, total_bytes;
-    // workspace (grown on demand)
+    // workspace: the caller's (rairs_set_workspace), else the handle's own, grown on demand
     void *ws;
     size_t ws_bytes;
-    int64_t *dco;
-    int64_t dco_cap;
+    void *ws_user;
+    size_t ws_user_bytes;
+    char *last_ws;                // workspace of the last call (for the measurement helpers)
+    int64_t *last_dco;            // DCO counts of the last rairs_search, inside that workspace
+    int64_t last_dco_n;
     // profiling
     int force_exact;
     int64_t last_pass_n;          // queries of the last MFMA pass (0: none)
@@ -104,9 +108,8 @@ struct rairs_index {
     // a second stream for the steps that do not depend on each other (tables next to the coarse
     // quantizer, grouping next to the sample bound), forked from and joined to the caller's stream
     hipStream_t side;
-    hipEvent_t ev_fork, ev_lut, ev_probe, ev_group, ev_dco;
+    hipEvent_t ev_fork, ev_lut, ev_probe, ev_group;
     int side_ready;
-    int side_tail;                // the side stream still runs work of the current pass (joined by ev_dco)
 };
 
 void rairs_set_error(const char *fmt, ...);
@@ -152,17 +155,14 @@ struct ExactScanArgs {
 };
 int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s);
 #define RAIRS_SAMPLE_MAX_BLOCKS 128
-// bound of every query from the head of its first probed list and, when dco is given, its DCO
+// bound of every query from the head of its first probed list
 int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
                               int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,
-                              int32_t *bound, const uint32_t *bitmap, int bmwords, int64_t *dco,
-                              hipStream_t s);
-// the same bound from scores that rairs_launch_sample_scores wrote, and the DCO on its own
+                              int32_t *bound, hipStream_t s);
+// the same bound from scores that rairs_launch_sample_scores wrote
 int rairs_launch_sample_rank(const IndexView &v, const int32_t *probe_ids, int nprobe, int refine_k,
                              int sample_blocks, int64_t nq, const uint16_t *pre, int32_t *tau,
                              int32_t *bound, hipStream_t s);
-int rairs_launch_dco(const IndexView &v, const int32_t *probe_ids, int nprobe, const uint32_t *bitmap,
-                     int bmwords, int64_t nq, int64_t *dco, hipStream_t s);
 // Scores of the sample by the matrix cores: the queries are grouped by their first probed list, a
 // wave scores the head of a list for a tile of up to 32 of them.  Workspace: s_cnt [nlist],
 // s_off [nlist + 1], s_toff [nlist + 1], s_q [nq], s_tiles [nq / 32 + nlist].
@@ -204,6 +204,7 @@ struct MfmaScanArgs {
     uint32_t *log_overflow;       // [1] set if the log ran out of chunks
     int log_chunks;
     long long *prof;              // cycle counters per wave (profiling builds only), may be null
+    unsigned long long *dco;      // [nq] items scored per query, counted as blocks are contracted; may be null
     int64_t *cand_ids;            // [nq][refine_k]
     int32_t *cand_score;          // may be null
 };

@@ -1,7 +1,7 @@
 // Exact SEIL scan with a bounded top-bigK queue, one workgroup per query (SeilSearch, Alg. 5,
 // with rqueue).  Used as the whole scan for table shapes the MFMA kernel is not built for and as
-// the fallback for queries whose survivor buffer overflowed twice.  Two small helpers of the MFMA
-// scan live here too: the bound from a sample of each query's first list, and the DCO count.
+// the fallback for queries whose survivor buffer overflowed.  A helper of the MFMA scan lives
+// here too: the bound from a sample of each query's first list.
 //
 // listVisited is replaced by the order-free equivalent over the query's probe bitmap P:
 //   reference entry (owner i) of list j is scanned  iff  i not in P;
@@ -159,30 +159,6 @@ int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t 
 // cell in the miscellaneous areas of both lists, Section 5.1); so at least bigK entries of the
 // queue score <= tau.  One wave per query; the sample's scores sit in LDS and the rank is found by
 // bisection on the 16 score bits.
-// DCO of a query (distance computations of the scan, Section 6.1): every valid slot of the own
-// blocks of each probed list, plus the valid slots of the blocks of each reference entry whose
-// owner is not probed.  Lanes over the probes; the total is returned in every lane.
-static __device__ __forceinline__ unsigned long long query_dco(const IndexView &v, const int32_t *__restrict__ probe_ids,
-                                                               int nprobe, const uint32_t *__restrict__ bitmap,
-                                                               int bmwords, int64_t qi, int lane)
-{
-    const uint32_t *bm = bitmap + (size_t)qi * bmwords;
-    unsigned long long c = 0;
-    for (int p = lane; p < nprobe; p += 64) {
-        const int Lp = probe_ids[(size_t)qi * nprobe + p];
-        if (Lp < 0 || Lp >= v.nlist) continue;
-        const ListEntry le = v.lists[Lp];
-        c += (unsigned long long)le.valid_items;
-        for (int r = 0; r < le.ref_cnt; r++) {
-            const RefEntry re = v.refs[le.ref_begin + r];
-            if (!((bm[re.owner >> 5] >> (re.owner & 31)) & 1u)) c += (unsigned long long)re.valid;
-        }
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) c += (unsigned long long)__shfl_xor((long long)c, off);
-    return c;
-}
-
 // Scores of one block for this lane: `part` sums the table entries of the lane's half of the
 // sub-quantizer pairs; ND code dwords with 8 four-bit codes each.  No branch per lookup, so the
 // LDS reads of a block are all in flight together.
@@ -204,9 +180,7 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
                                                           const int32_t *__restrict__ probe_ids,
                                                           int nprobe, int refine_k, int sample_blocks,
                                                           int64_t nq, int32_t *__restrict__ tau,
-                                                          int32_t *__restrict__ bound,
-                                                          const uint32_t *__restrict__ bitmap,
-                                                          int bmwords, int64_t *__restrict__ dco)
+                                                          int32_t *__restrict__ bound)
 {
     extern __shared__ __align__(16) uint8_t sample_lds[];  // per wave: M*16 table bytes, then sample_blocks*32 scores
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
@@ -325,31 +299,6 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
         tau[qi] = (int32_t)range;
         if (bound) bound[qi] = (int32_t)t;
     }
-    if (dco) {
-        const unsigned long long c = query_dco(v, probe_ids, nprobe, bitmap, bmwords, qi, lane);
-        if (lane == 0 && qi0 < nq) dco[qi] = (int64_t)c;
-    }
-}
-
-// The DCO alone, one wave per query (used when the bound comes from the matrix-core sample).
-__global__ __launch_bounds__(WG) void dco_kernel(IndexView v, const int32_t *__restrict__ probe_ids,
-                                                 int nprobe, const uint32_t *__restrict__ bitmap,
-                                                 int bmwords, int64_t nq, int64_t *__restrict__ dco)
-{
-    const int lane = threadIdx.x & 63;
-    const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + (threadIdx.x >> 6);
-    if (qi >= nq) return;                                // a whole wave
-    const unsigned long long c = query_dco(v, probe_ids, nprobe, bitmap, bmwords, qi, lane);
-    if (lane == 0) dco[qi] = (int64_t)c;
-}
-
-int rairs_launch_dco(const IndexView &v, const int32_t *probe_ids, int nprobe, const uint32_t *bitmap,
-                     int bmwords, int64_t nq, int64_t *dco, hipStream_t s)
-{
-    hipLaunchKernelGGL(dco_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG), 0, s, v,
-                       probe_ids, nprobe, bitmap, bmwords, nq, dco);
-    RAIRS_HIP(hipGetLastError());
-    return RAIRS_OK;
 }
 
 // Position of the k-th (1-based, k <= total) entry of a 256-bin histogram held in a wave's LDS
@@ -452,8 +401,7 @@ int rairs_launch_sample_rank(const IndexView &v, const int32_t *probe_ids, int n
 
 int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
                               int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,
-                              int32_t *bound, const uint32_t *bitmap, int bmwords, int64_t *dco,
-                              hipStream_t s)
+                              int32_t *bound, hipStream_t s)
 {
     if (sample_blocks > RAIRS_SAMPLE_MAX_BLOCKS) sample_blocks = RAIRS_SAMPLE_MAX_BLOCKS;
     if (sample_blocks < 1) sample_blocks = 1;
@@ -461,7 +409,7 @@ int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int3
     const dim3 grid((unsigned)((nq + WG / 64 - 1) / (WG / 64)));
 #define SAMPLE_LAUNCH(ND_)                                                                        \
     hipLaunchKernelGGL(sample_bound_kernel<ND_>, grid, dim3(WG), lds, s, v, lut, probe_ids, nprobe, \
-                       refine_k, sample_blocks, nq, tau, bound, bitmap, bmwords, dco)
+                       refine_k, sample_blocks, nq, tau, bound)
     const int nd = v.T % 8 == 0 ? v.nd : 0;
     switch (nd) {
     case 1: SAMPLE_LAUNCH(1); break;

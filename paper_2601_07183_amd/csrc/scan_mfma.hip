@@ -52,11 +52,12 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 // at index + nwaves), so the counters start behind those.
 __global__ void lm_zero_kernel(int32_t *lcount, int32_t *lcursor, int nlist, uint32_t *next_task, uint32_t *surv_cnt,
                                int64_t nq, uint32_t *chunk_fill, int log_chunks, uint32_t *log_cursor,
-                               uint32_t *log_overflow, uint32_t first_task, uint32_t first_chunk)
+                               uint32_t *log_overflow, uint32_t first_task, uint32_t first_chunk,
+                               unsigned long long *dco)
 {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < nlist) { lcount[gid] = 0; lcursor[gid] = 0; }
-    if (gid < nq) surv_cnt[gid] = 0;
+    if (gid < nq) { surv_cnt[gid] = 0; if (dco) dco[gid] = 0ull; }
     if (gid < log_chunks) chunk_fill[gid] = 0;
     if (gid == 0) { *next_task = first_task; *log_cursor = first_chunk; *log_overflow = 0; }
 }
@@ -577,7 +578,9 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         uint32_t cn[ND];
 #pragma unroll
         for (int w = 0; w < ND; w++) cn[w] = cp[w * 64];
-        uint32_t cmn = v.cmask[se.blk_begin];          // countable slots of the block, fetched with its codes
+        // {countable slots, slots in use} of the block, fetched with its codes
+        uint2 cmn = v.bmask[se.blk_begin];
+        uint32_t scored = 0;                           // items this lane's query was scored against in this unit
         for (int seg = seg0; seg < seg1; seg++) {
 #ifdef RAIRS_PROFILE_CYCLES
             pc_ntask++;
@@ -593,26 +596,28 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                 if (has_next) {
 #pragma unroll
                     for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64];
-                    cmn = v.cmask[sen.blk_begin];
+                    cmn = v.bmask[sen.blk_begin];
                 }
             } else {
+                uint32_t seg_items = 0;                // wave-uniform: slots in use of the blocks contracted
                 for (int b = 0; b < se.nblk; b++) {
                     PC_MARK();
                     uint32_t c[ND];
 #pragma unroll
                     for (int w = 0; w < ND; w++) c[w] = cn[w];
-                    const uint32_t cmask = cmn;
+                    const uint32_t cmask = cmn.x;
+                    seg_items += (uint32_t)__popc(cmn.y);
                     const int th = live ? bound_next - bias : INT_MIN;
                     // (every fourth block is often enough: the bound moves rarely)
                     if ((b & 3) == 3) bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     if (b + 1 < se.nblk) {             // fetch the next block while this one is scored
 #pragma unroll
                         for (int w = 0; w < ND; w++) cn[w] = cp[(size_t)(b + 1) * ND * 64 + w * 64];
-                        cmn = v.cmask[se.blk_begin + b + 1];
+                        cmn = v.bmask[se.blk_begin + b + 1];
                     } else if (has_next) {             // ... or the first block of the next run
 #pragma unroll
                         for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64];
-                        cmn = v.cmask[sen.blk_begin];
+                        cmn = v.bmask[sen.blk_begin];
                     }
                     v16i acc;
 #pragma unroll
@@ -695,6 +700,9 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                         PC_ADD(pc_slow);
                     }
                 }
+                // the distance computations of this run (Section 6.1's DCO): every slot in use of
+                // every block that was contracted, for each query the run was live for
+                scored += live ? seg_items : 0u;
             }
             se = sen;
             sen = sen2;
@@ -703,6 +711,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         }
         // do not sit on survivors for long: their histogram counts tighten everyone's bound
         if (nstaged >= 32) FLUSH_STAGE();
+        if (a.dco && g == 0 && scored) atomicAdd(&a.dco[qid], (unsigned long long)scored);
         u = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_next);
     }
     if (nstaged > 0) FLUSH_STAGE();
@@ -1047,14 +1056,16 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
             }
             return r;
         };
-        uint32_t cn[LDSK_MAX_ND], cmn = 0;
+        uint32_t cn[LDSK_MAX_ND];
+        uint2 cmn = make_uint2(0u, 0u);
+        uint32_t scored = 0;                           // items this lane's query was scored against, by this wave
         int bound_next = 0;
         auto fetch = [&](const Blk &bk) {
             const uint32_t *cp = v.codes + (size_t)bk.blk * ND * 64 + lane;
 #pragma unroll
             for (int w = 0; w < LDSK_MAX_ND; w++)
                 if (w < ND) cn[w] = cp[(size_t)w * 64];
-            cmn = v.cmask[bk.blk];
+            cmn = v.bmask[bk.blk];
             bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         };
         Blk cur = locate();
@@ -1063,12 +1074,14 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
             uint32_t c[LDSK_MAX_ND];
 #pragma unroll
             for (int w = 0; w < LDSK_MAX_ND; w++) c[w] = cn[w];
-            const uint32_t cmask = cmn;
+            const uint32_t cmask = cmn.x;
+            const uint32_t blk_items = (uint32_t)__popc(cmn.y);
             const int th = cur.live ? bound_next - bias : INT_MIN;
             fpos += nwave;
             const Blk nxt = locate();
             if (nxt.valid) fetch(nxt);
             if (__ballot(cur.live) != 0ull) {
+                scored += cur.live ? blk_items : 0u;   // the block is contracted now: its DCO
                 v16i acc;
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[r] = 0;
@@ -1127,6 +1140,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
             stage_flush(a, sq, nstaged, lane, lc, pace);
             nstaged = 0;
         }
+        if (a.dco && g == 0 && scored) atomicAdd(&a.dco[qid], (unsigned long long)scored);
     }
     if (nstaged > 0) stage_flush(a, sq, nstaged, lane, lc, pace);
     if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
@@ -1422,7 +1436,7 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
     nz = nz > a.log_chunks ? nz : a.log_chunks;
     hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
                        a.lcursor, v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
-                       a.log_cursor, a.log_overflow, reg_tables ? nwaves : gridx, 2 * nwaves);
+                       a.log_cursor, a.log_overflow, reg_tables ? nwaves : gridx, 2 * nwaves, a.dco);
     const bool lds_group = v.nlist <= LM_LDS_NLIST;
     const int qb = LM_PAIRS / np > 0 ? LM_PAIRS / np : 1;
     const unsigned lgrid = (unsigned)((a.nq + qb - 1) / qb);

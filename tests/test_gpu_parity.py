@@ -209,11 +209,11 @@ def test_bound_sample_on_the_matrix_cores_large_batch(binding):
     _compare_all_stages(binding, hx, q, 10, 4, 100)
 
 
-@pytest.mark.parametrize("count", [600, 3000, 6000])
+@pytest.mark.parametrize("count", [150, 600, 6000])
 def test_identical_codes_tie_on_score(binding, count):
     # every vector identical: all scores tie, the order is decided by vector id alone, and every
-    # scanned item survives any bound (the three sizes end in the wave select, the workgroup
-    # select and the exact redo after an overflow)
+    # scanned item survives any bound (with bigK = 64 the wave select takes up to 256 survivors,
+    # the workgroup select up to 1,024, more overflow the buffer and go to the exact redo)
     x = np.tile(datagen.random_vectors(50, 1, 8), (count, 1))
     q = datagen.random_vectors(51, 9, 8)
     cents = datagen.random_vectors(52, 4, 8)
@@ -325,14 +325,14 @@ def test_batch_permutation_and_split(binding, small_index):
 
 
 def test_batch_larger_than_one_internal_pass(binding):
-    # rairs_search cuts a batch into passes of at most about 21,800 queries that share one
-    # workspace and the handle's two streams; 23,000 queries make two
+    # rairs_search cuts a batch into passes of at most 65,536 queries that share one workspace and
+    # the handle's two streams; 70,000 queries make two
     g = np.random.Generator(np.random.PCG64(78))
     d, M = 32, 16
     centers = g.integers(30, 220, size=(12, d))
     pick = lambda n: np.rint(np.clip(centers[g.integers(0, 12, size=n)] + g.normal(0, 25, size=(n, d)),
                                      0, 255)).astype(np.float32)
-    base, q = pick(9000), pick(23000)
+    base, q = pick(9000), pick(70000)
     hx = ib.build_index(base, 20, M, seed=7, coarse_iters=5, pq_iters=5)
     want = oracle.search(oracle.OracleIndex(hx), q, 10, 4, 100)
     ix = binding.Index(hx)
@@ -343,6 +343,51 @@ def test_batch_larger_than_one_internal_pass(binding):
             assert (ids.cpu().numpy() == want.ids).all()
             _assert_dists(dists.cpu().numpy(), want.dists)
             assert (ix.dco(len(q)) == want.dco).all()
+    finally:
+        ix.free()
+
+
+def test_caller_owned_workspace(binding, tiny_workload):
+    # rairs_workspace_bytes / rairs_set_workspace through the C ABI: a torch tensor serves as the
+    # workspace; one byte too few is RAIRS_EWORKSPACE and enqueues nothing; the library's own
+    # workspace and the caller's give the same bits
+    import ctypes as C
+    w, base, q, hx = tiny_workload
+    lib = binding.load()
+    want = oracle.search(oracle.OracleIndex(hx), q, w.k, 16, w.refine_k)
+    ix = binding.Index(hx)
+    try:
+        dq = _dev(q)
+        need = ix.workspace_bytes(len(q), 16, w.refine_k)
+        assert need > 0 and ix.workspace_bytes(0, 16, w.refine_k) == 0
+        assert ix.workspace_bytes(len(q) // 2, 8, w.refine_k) <= need       # monotone in its arguments
+        with pytest.raises(binding.RairsError):
+            ix.workspace_bytes(len(q), hx.nlist + 1, w.refine_k)
+        ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+        ids = torch.full((len(q), w.k), -7, dtype=torch.int64, device="cuda")
+        dists = torch.zeros((len(q), w.k), dtype=torch.float32, device="cuda")
+        h, stream = ix._h, C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        args = (h, C.c_void_p(dq.data_ptr()), C.c_int64(len(q)), C.c_int(w.k), C.c_int(16), C.c_int(w.refine_k),
+                C.c_void_p(ids.data_ptr()), C.c_void_p(dists.data_ptr()), stream)
+        # too small by one byte: refused, outputs untouched
+        assert lib.rairs_set_workspace(h, C.c_void_p(ws.data_ptr()), C.c_size_t(need - 1)) == 0
+        assert lib.rairs_search(*args) == -5
+        torch.cuda.synchronize()
+        assert (ids == -7).all()
+        # misaligned: refused
+        assert lib.rairs_set_workspace(h, C.c_void_p(ws.data_ptr() + 8), C.c_size_t(need)) == -1
+        # exactly enough
+        assert lib.rairs_set_workspace(h, C.c_void_p(ws.data_ptr()), C.c_size_t(need)) == 0
+        assert lib.rairs_search(*args) == 0
+        torch.cuda.synchronize()
+        assert (ids.cpu().numpy() == want.ids).all()
+        _assert_dists(dists.cpu().numpy(), want.dists)
+        assert (ix.dco(len(q)) == want.dco).all()
+        # back to the handle's own workspace: same bits
+        ix.use_own_workspace()
+        ids2, dists2 = ix.search(dq, w.k, 16, w.refine_k)
+        torch.cuda.synchronize()
+        assert (ids2 == ids).all() and (dists2 == dists).all()
     finally:
         ix.free()
 
