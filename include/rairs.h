@@ -38,8 +38,8 @@ typedef enum {
     RAIRS_ENOMEM = -2,        /* host or device allocation failed */
     RAIRS_EHIP = -3,          /* a HIP runtime call failed */
     RAIRS_EUNSUPPORTED = -4,  /* valid request outside the built limits */
-    RAIRS_EWORKSPACE = -5     /* the workspace the caller set is too small for this call; nothing
-                                 was enqueued */
+    RAIRS_EWORKSPACE = -5     /* the workspace the caller set (or the static scratch array) is too
+                                 small for this call; nothing was enqueued */
 } rairs_status;
 
 /* Built limits (rejected with RAIRS_EUNSUPPORTED beyond them). */
@@ -144,6 +144,21 @@ size_t rairs_workspace_bytes(const rairs_index_t *h, int64_t nq, int nprobe, int
  * call's workspace and are reset by this call.
  */
 int rairs_set_workspace(rairs_index_t *h, void *d_ws, size_t bytes);
+
+/*
+ * rairs_search for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, same results, but all scratch
+ * memory is a static device array of RAIRS_NOALLOC_SCRATCH_BYTES that the library's code object
+ * carries, so the call allocates nothing (no hipMalloc, hipFree or allocating library routine).
+ * A call whose rairs_workspace_bytes exceeds that size returns RAIRS_EWORKSPACE and enqueues
+ * nothing (small batches fit: e.g. a few hundred queries at nprobe 32 over 1,024 lists).  Every
+ * call on a GPU shares that GPU's array, on every handle: calls that overlap on one GPU race, the
+ * caller serialises them (one stream, or events).  What must start at zero is cleared by the
+ * call's own kernels.
+ */
+#define RAIRS_NOALLOC_SCRATCH_BYTES (32u << 20)
+int rairs_search_noalloc(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
+                         int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream);
 
 /* ---- the stages of rairs_search, callable one by one (same kernels) ----------------------- */
 

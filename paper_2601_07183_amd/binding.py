@@ -21,7 +21,7 @@ MAX_REFINE_K = 1024
 MAX_NPROBE = 4096
 
 EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_workspace_bytes", "rairs_set_workspace",
-           "rairs_coarse", "rairs_lut",
+           "rairs_search_noalloc", "rairs_coarse", "rairs_lut",
            "rairs_scan", "rairs_refine", "rairs_set_scan_mode", "rairs_set_profiling", "rairs_get_stage_ms",
            "rairs_get_stage_ms_mean",
            "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_pq_encode", "rairs_assign",
@@ -196,6 +196,16 @@ class Index:
         self._reserve(nq, nprobe, refine_k)
         _check(self._lib.rairs_search(
             self._h, _dev(queries, torch.float32, "queries"), C.c_int64(nq), C.c_int(k),
+            C.c_int(nprobe), C.c_int(refine_k), _dev(out_ids, torch.int64, "out_ids"),
+            _dev(out_dists, torch.float32, "out_dists"), _stream_ptr(stream)))
+        return out_ids, out_dists
+
+    def search_noalloc(self, queries: torch.Tensor, k: int, nprobe: int, refine_k: int, out_ids,
+                       out_dists, stream=None):
+        """rairs_search_noalloc: the caller supplies the outputs; scratch memory is the library's
+        static device array."""
+        _check(self._lib.rairs_search_noalloc(
+            self._h, _dev(queries, torch.float32, "queries"), C.c_int64(queries.shape[0]), C.c_int(k),
             C.c_int(nprobe), C.c_int(refine_k), _dev(out_ids, torch.int64, "out_ids"),
             _dev(out_dists, torch.float32, "out_dists"), _stream_ptr(stream)))
         return out_ids, out_dists

@@ -605,12 +605,47 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int64_t nq_total, int 
     return w;
 }
 
+// ---- the no-allocation entry point's scratch ------------------------------------------------
+//
+// rairs_search_noalloc runs in this array instead of a workspace that somebody allocated: one copy
+// per GPU the library runs on, held until the process ends.  The array's name is only a host-side
+// stand-in; the device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[RAIRS_NOALLOC_SCRATCH_BYTES];
+#define RAIRS_MAX_DEVICES 64
+static void *g_scratch_ptr[RAIRS_MAX_DEVICES];
+
+static int scratch_pointer(void **out)
+{
+    int dev = -1;
+    RAIRS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= RAIRS_MAX_DEVICES) FAIL(RAIRS_EUNSUPPORTED, "device ordinal %d above the built limit", dev);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        RAIRS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) FAIL(RAIRS_EHIP, "hipGetSymbolAddress returned no address for the scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return RAIRS_OK;
+}
+
 // Where a call's workspace comes from.  WS_HANDLE: the caller's buffer if one was set (too small:
 // RAIRS_EWORKSPACE, nothing is allocated or synchronised), else the handle's own, grown on demand.
-enum { WS_HANDLE = 0 };
+// WS_STATIC: the scratch array.
+enum { WS_HANDLE = 0, WS_STATIC = 1 };
 static int acquire_ws(rairs_index *h, int source, size_t bytes, char **ws)
 {
-    (void)source;
+    if (source == WS_STATIC) {
+        if (bytes > (size_t)RAIRS_NOALLOC_SCRATCH_BYTES)
+            FAIL(RAIRS_EWORKSPACE, "this call needs %zu bytes of scratch memory, the static array has %zu",
+                 bytes, (size_t)RAIRS_NOALLOC_SCRATCH_BYTES);
+        void *p = nullptr;
+        int rc = scratch_pointer(&p);
+        if (rc) return rc;
+        *ws = (char *)p;
+        h->last_ws = *ws;
+        return RAIRS_OK;
+    }
     if (h->ws_user) {
         if (bytes > h->ws_user_bytes)
             FAIL(RAIRS_EWORKSPACE, "this call needs a workspace of %zu bytes, the caller's has %zu", bytes,
@@ -935,6 +970,12 @@ extern "C" int rairs_search(rairs_index_t *h, const float *d_queries, int64_t nq
                             int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream)
 {
     return search_impl(h, WS_HANDLE, d_queries, nq, k, nprobe, refine_k, d_out_ids, d_out_dists, hip_stream);
+}
+
+extern "C" int rairs_search_noalloc(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
+                                    int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream)
+{
+    return search_impl(h, WS_STATIC, d_queries, nq, k, nprobe, refine_k, d_out_ids, d_out_dists, hip_stream);
 }
 
 extern "C" size_t rairs_workspace_bytes(const rairs_index_t *h, int64_t nq, int nprobe, int refine_k)

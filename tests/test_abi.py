@@ -144,6 +144,7 @@ def test_workspace_calls_check_their_arguments_on_the_host():
     lib = binding.load()
     assert lib.rairs_workspace_bytes(None, C.c_int64(10), 1, 10) == 0
     assert lib.rairs_set_workspace(None, None, C.c_size_t(0)) == -1
+    assert lib.rairs_search_noalloc(None, None, C.c_int64(1), 1, 1, 1, None, None, None) == -1
 
 
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
