@@ -22,11 +22,50 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# MI355X matrix peaks for int8: dense 5.0 POP/s; the 2:4-sparse instruction v_smfmac_i32_32x32x64_i8
+# retires twice the K extent of the dense v_mfma_i32_32x32x32_i8 per pass (131,072 ops in 32 cycles
+# per SIMD x 1,024 SIMDs x 2.4 GHz), i.e. twice that for the ops it stands for.
+MFMA_I8_DENSE_POPS = 5.0
+MFMA_I8_SPARSE_POPS = 10.1
+LANE_OPS_PEAK = 256 * 64 * 2.4e9          # one 64-lane vector operation per compute unit and cycle
 
-# Bytes that left L2 per launch of the scan kernel, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0
-# and WRITE_SIZE x 1.0, factors from the same counters on a 1 GiB copy); see profiles/.  Keyed by
-# (workload, nprobe); other configurations report null.
-MEASURED_TRAFFIC = {("sift1m", 23): 1.51e9}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "scan_kernel_hbm_traffic.md")
+
+
+def measured_traffic(workload: str, nprobe: int, kernel: str):
+    """HBM bytes per launch of the scan kernel from the tracked rocprofv3 counter summary
+    (profiles/scan_kernel_hbm_traffic.md: FETCH_SIZE and WRITE_SIZE per dispatch, each scaled by
+    what the same counter reads for a plain copy of known size), or None when the table has no
+    row for this (workload, nprobe, kernel)."""
+    try:
+        rows = open(TRAFFIC_TABLE).read().splitlines()
+    except OSError:
+        return None
+    for line in rows:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 7 and cells[0] == workload and cells[1] == str(nprobe) and cells[2] == kernel:
+            try:
+                fetch_kib, fetch_f, write_kib, write_f = (float(cells[i].replace(",", "")) for i in (3, 4, 5, 6))
+            except ValueError:
+                continue
+            return (fetch_kib * fetch_f + write_kib * write_f) * 1024.0
+    return None
+
+
+def physical_cores():
+    """Cores (not SMT threads) that lscpu reports for the host, or None."""
+    import subprocess
+    try:
+        out = subprocess.run(["lscpu"], capture_output=True, text=True, timeout=10).stdout
+        per, sockets = None, None
+        for line in out.splitlines():
+            if line.startswith("Core(s) per socket:"):
+                per = int(line.split(":")[1])
+            elif line.startswith("Socket(s):"):
+                sockets = int(line.split(":")[1])
+        return per * sockets if per and sockets else None
+    except Exception:
+        return None
 
 
 def log(*a):
@@ -429,28 +468,49 @@ def main():
         f"{stage_all}, scan stage {scan_gbs:.1f} GB/s algorithmic")
 
     # --- CPU baseline: the oracle as it stands, on a bounded sample of the same batch --------
+    # Threads: the host's physical cores as lscpu counts them, capped by what this process may
+    # use (its CPU affinity and the OpenMP limit the box sets); and one thread, on a smaller sample.
     from oracle import oracle
     ox = oracle.OracleIndex(hx)
-    threads = oracle.num_threads()
+    phys = physical_cores()
+    allowed = min(oracle.num_threads(), len(os.sched_getaffinity(0)))
+    threads = max(1, min(phys, allowed) if phys else allowed)
     ncpu = args.cpu_queries or 200
-    oracle.search(ox, queries[:min(16, nq)], w.k, chosen, w.refine_k)          # warm
+    oracle.search(ox, queries[:min(16, nq)], w.k, chosen, w.refine_k, nthreads=threads)          # warm
     t = time.perf_counter()
-    want = oracle.search(ox, queries[:ncpu], w.k, chosen, w.refine_k)
+    want = oracle.search(ox, queries[:ncpu], w.k, chosen, w.refine_k, nthreads=threads)
     cpu_sec = time.perf_counter() - t
-    if not args.cpu_queries and cpu_sec < 5.0:                                 # aim for ~10-30 s
-        ncpu = int(min(nq, ncpu * 15.0 / max(cpu_sec, 1e-3)))
+    if not args.cpu_queries and cpu_sec < 5.0:                                 # aim for ~10-20 s
+        ncpu = int(min(nq, ncpu * 12.0 / max(cpu_sec, 1e-3)))
         t = time.perf_counter()
-        want = oracle.search(ox, queries[:ncpu], w.k, chosen, w.refine_k)
+        want = oracle.search(ox, queries[:ncpu], w.k, chosen, w.refine_k, nthreads=threads)
         cpu_sec = time.perf_counter() - t
     same = bool((out_ids.cpu().numpy()[:ncpu] == want.ids).all())
-    log(f"[bench] oracle: {ncpu} queries in {cpu_sec:.2f}s on {threads} threads; "
-        f"GPU ids identical on the sample: {same}")
+    n1 = max(1, min(ncpu, int(ncpu / cpu_sec * 4.0 / threads)))               # about 4 s on one thread
+    t = time.perf_counter()
+    oracle.search(ox, queries[:n1], w.k, chosen, w.refine_k, nthreads=1)
+    cpu1_sec = time.perf_counter() - t
+    log(f"[bench] oracle: {ncpu} queries in {cpu_sec:.2f}s on {threads} threads (lscpu: {phys} physical cores), "
+        f"{n1} queries in {cpu1_sec:.2f}s on 1 thread; GPU ids identical on the sample: {same}")
 
-    # Matrix-core view of the same kernel: one table lookup is 16 int8 multiply-adds (the one-hot
-    # K dimension) = 32 ops, so useful ops = items x M x 32.
-    useful_pops = float(dco.sum()) * w.M * 32 / (stage["scan_kernel"] * 1e-3) / 1e15
-    kernel_gbs = scan_bytes / (stage["scan_kernel"] * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC.get((w.name, chosen))
+    # What bounds the dominant kernel.  One table lookup is 16 int8 multiply-adds of the one-hot
+    # contraction = 32 ops, so the ops the kernel stands for are items x M x 32 (partly filled
+    # query tiles and list tails count as lost).  The register-table kernel issues the 2:4-sparse
+    # int8 matrix instruction, the LDS-table kernel the dense one: each is priced against the
+    # peak of ITS instruction.  The exact kernel does its lookups on the vector units.
+    kernel = ix.scan_kernel_name()
+    kms = stage["scan_kernel"]
+    lookups = float(dco.sum()) * w.M
+    if kernel == "scan_exact_kernel":
+        bound, unit = "alu", "T lane-ops/s"
+        achieved, peak = lookups * 2 / (kms * 1e-3) / 1e12, LANE_OPS_PEAK / 1e12   # a lookup and an add per code
+    else:
+        bound, unit = "mfma", "POP/s"
+        achieved = lookups * 32 / (kms * 1e-3) / 1e15
+        peak = MFMA_I8_SPARSE_POPS if kernel == "scan_mfma_kernel" else MFMA_I8_DENSE_POPS
+    kernel_gbs = scan_bytes / (kms * 1e-3) / 1e9
+    traffic = measured_traffic(w.name, chosen, kernel)
+    hbm_gbs = None if traffic is None else traffic / (kms * 1e-3) / 1e9
     result = {
         "metric": "QPS at recall@10>=0.9 (1Mx128, 1 GPU)" if w.name == "sift1m"
                   else f"QPS at recall@10>={args.target_recall} ({w.name}, 1 GPU)",
@@ -467,27 +527,32 @@ def main():
             "ms_per_step_events_off": round(sec_plain / args.steps * 1e3, 4),
             "dco_per_query": float(dco.mean()), "index_code_bytes": code_bytes,
             "index_total_bytes": total_bytes, "vectors_in_shared_blocks": round(shared_frac, 4),
+            "workspace_bytes": ix.workspace_bytes(nq, chosen, w.refine_k),
             "ids_identical_to_oracle_on_sample": same,
             "scan_stage_algorithmic_GBs": round(scan_gbs, 1),
         },
-        # dominant kernel: the list-major scan.  achieved = algorithmic code bytes (M/2 per item
-        # scored, after SEIL dedup) / its mean launch time over the timed steps (HIP events on the
-        # caller's stream).  It exceeds the HBM peak because a block fetched once serves a tile
-        # of 32 queries; "traffic" is what rocprofv3 counted leaving L2 (see profiles/).
+        # Dominant kernel: the list-major scan.  Its roof is the matrix pipe (issue of the int8
+        # matrix instruction it uses), not HBM: a block fetched once serves a tile of 32 queries,
+        # so the algorithmic code bytes (M/2 per item scored, after SEIL dedup; context only)
+        # exceed what leaves HBM many times over.  achieved = ops the contraction stands for / the
+        # kernel's mean launch time over the timed steps (HIP events on the caller's stream).
+        # "traffic" = HBM bytes per launch from the tracked rocprofv3 counter summary for this
+        # (workload, nprobe), null when that configuration has none; "hbm" prices it against 8 TB/s.
         "roofline": {
-            "kernel": "scan_mfma_kernel", "bound": "hbm", "achieved": round(kernel_gbs, 1),
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(kernel_gbs / HBM_PEAK_GBS, 4),
-            "traffic": traffic, "algorithmic_bytes_per_launch": scan_bytes,
-            "avg_launch_ms": round(stage["scan_kernel"], 4),
-        },
-        "roofline_mfma": {
-            "kernel": "scan_mfma_kernel", "bound": "mfma", "achieved": round(useful_pops, 4),
-            "peak": 5.0, "unit": "POP/s", "frac": round(useful_pops / 5.0, 4),
-            "note": "useful int8 ops = items x M lookups x 32 ops per 16-wide one-hot lookup",
+            "kernel": kernel, "bound": bound, "achieved": round(achieved, 4), "peak": peak, "unit": unit,
+            "frac": round(achieved / peak, 4), "traffic": traffic,
+            "avg_launch_ms": round(kms, 4),
+            "algorithmic_bytes_per_launch": scan_bytes,
+            "algorithmic_GBs": round(kernel_gbs, 1),
+            "hbm": None if traffic is None else {
+                "bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(hbm_gbs / HBM_PEAK_GBS, 4)},
         },
         "cpu_baseline": {
             "value": round(ncpu / cpu_sec, 1), "unit": "queries/s", "cores": threads,
             "kind": "oracle", "sample": f"first {ncpu} queries of the batch at nprobe={chosen}",
+            "physical_cores_lscpu": phys, "value_1_thread": round(n1 / cpu1_sec, 1),
+            "sample_1_thread": f"first {n1} queries",
         },
         "sweep": sweep,
     }

@@ -253,6 +253,14 @@ int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq);
  */
 int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats);
 
+/*
+ * Name of the dominant kernel that SeilSearch launches for this index in the current scan mode:
+ * "scan_mfma_kernel" (2:4-sparse int8 matrix instruction, tables in registers),
+ * "scan_mfma_lds_kernel" (dense int8 matrix instruction, tables in LDS) or "scan_exact_kernel"
+ * (table lookups on the vector units).  A static string; NULL for a NULL handle.
+ */
+const char *rairs_scan_kernel_name(const rairs_index_t *h);
+
 /* Bytes of device memory held by the index (codes, ids, tags, directory, raw vectors, ...). */
 int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, int64_t *total_bytes);
 

@@ -24,7 +24,7 @@ EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_workspace_
            "rairs_search_noalloc", "rairs_coarse", "rairs_lut",
            "rairs_scan", "rairs_refine", "rairs_set_scan_mode", "rairs_set_profiling", "rairs_get_stage_ms",
            "rairs_get_stage_ms_mean",
-           "rairs_get_dco", "rairs_get_scan_stats", "rairs_index_bytes", "rairs_pq_encode", "rairs_assign",
+           "rairs_get_dco", "rairs_get_scan_stats", "rairs_scan_kernel_name", "rairs_index_bytes", "rairs_pq_encode", "rairs_assign",
            "rairs_last_error")
 
 
@@ -62,6 +62,7 @@ def load() -> C.CDLL:
         lib = C.CDLL(LIB_PATH)
         lib.rairs_last_error.restype = C.c_char_p
         lib.rairs_workspace_bytes.restype = C.c_size_t
+        lib.rairs_scan_kernel_name.restype = C.c_char_p
         for name in EXPORTS:
             getattr(lib, name)
         _lib = lib
@@ -294,6 +295,9 @@ class Index:
         _check(self._lib.rairs_get_scan_stats(self._h, st))
         return dict(redone=int(st[0]), survivors=int(st[1]), max_survivors=int(st[2]),
                     queries=int(st[3]))
+
+    def scan_kernel_name(self) -> str:
+        return self._lib.rairs_scan_kernel_name(self._h).decode()
 
     def bytes(self):
         a, b = C.c_int64(), C.c_int64()

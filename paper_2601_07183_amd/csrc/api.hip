@@ -516,7 +516,7 @@ static int log_per_query_for(int refine_k)
 
 struct WsLayout {
     size_t dmat, cflags, probe_ids, probe_dists, bitmap, lut, cand, dco;
-    size_t lcount, loff, lcursor, toff, unit_list, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, prof, total;
+    size_t lcount, loff, lcursor, toff, unit_list, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, total;
     size_t s_off, s_toff, s_q, s_tiles, s_scores;      // matrix-core sample (0 bytes when not used)
     int sample_blocks;
     int log_chunks;
@@ -585,11 +585,6 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int64_t nq_total, int 
     w.log_chunks = (int)((nq * log_per_query_for(refine_k) + 255) / 256) + 8192;   // + two per wave
     w.chunk_fill = take((size_t)w.log_chunks * 4);
     w.log_misc = take(64);
-#ifdef RAIRS_PROFILE_CYCLES
-    w.prof = take(2048 * 12 * 8);
-#else
-    w.prof = 0;
-#endif
     const bool grouped = grouped_sample(v, nq, refine_k);
     w.sample_blocks = sample_blocks_for(v, refine_k, grouped);
     w.s_off = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
@@ -807,10 +802,6 @@ static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t 
     ma.log = (uint2 *)(ws + w.log); ma.chunk_fill = (uint32_t *)(ws + w.chunk_fill);
     ma.log_cursor = (uint32_t *)(ws + w.log_misc); ma.log_overflow = ma.log_cursor + 1;
     ma.log_chunks = w.log_chunks;
-#ifdef RAIRS_PROFILE_CYCLES
-    ma.prof = (long long *)(ws + w.prof);
-    h->last_prof_off = w.prof;
-#endif
     // bound of every query from a sample (the head of its first list)
     ma.p_first = 0;
     ma.bound = (int32_t *)(ws + w.bound);
@@ -1011,6 +1002,13 @@ extern "C" int rairs_set_scan_mode(rairs_index_t *h, int mode)
     return RAIRS_OK;
 }
 
+extern "C" const char *rairs_scan_kernel_name(const rairs_index_t *h)
+{
+    if (!h) return nullptr;
+    if (h->force_exact || !rairs_mfma_supported(h->v)) return "scan_exact_kernel";
+    return rairs_mfma_reg_tables(h->v) ? "scan_mfma_kernel" : "scan_mfma_lds_kernel";
+}
+
 extern "C" int rairs_set_profiling(rairs_index_t *h, int enabled)
 {
     if (!h) FAIL(RAIRS_EINVAL, "handle is NULL");
@@ -1074,16 +1072,6 @@ extern "C" int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats)
     }
     return RAIRS_OK;
 }
-
-#ifdef RAIRS_PROFILE_CYCLES
-// profiling builds only: per-wave cycle counters of the last MFMA scan, 2048 x 12 int64
-extern "C" int rairs_debug_cycles(rairs_index_t *h, long long *out)
-{
-    RAIRS_HIP(hipDeviceSynchronize());
-    RAIRS_HIP(hipMemcpy(out, (char *)h->last_ws + h->last_prof_off, 2048 * 12 * 8, hipMemcpyDeviceToHost));
-    return RAIRS_OK;
-}
-#endif
 
 extern "C" int rairs_assign(rairs_index_t *h, const float *d_vectors, int64_t n, int n_cands,
                             double lambda, int strict, int32_t *d_pairs, void *hip_stream)

@@ -98,7 +98,7 @@ struct rairs_index {
     // profiling
     int force_exact;
     int64_t last_pass_n;          // queries of the last MFMA pass (0: none)
-    size_t last_flags_off, last_cnt_off, last_prof_off;
+    size_t last_flags_off, last_cnt_off;
     int prof, prof_valid;
     float stage_ms[RAIRS_NSTAGES];
     // stage events of the last RAIRS_EV_RING profiled searches (slot = search number mod ring)
@@ -203,12 +203,12 @@ struct MfmaScanArgs {
     uint32_t *log_cursor;         // [1] chunks handed out
     uint32_t *log_overflow;       // [1] set if the log ran out of chunks
     int log_chunks;
-    long long *prof;              // cycle counters per wave (profiling builds only), may be null
     unsigned long long *dco;      // [nq] items scored per query, counted as blocks are contracted; may be null
     int64_t *cand_ids;            // [nq][refine_k]
     int32_t *cand_score;          // may be null
 };
 bool rairs_mfma_supported(const IndexView &v);
+bool rairs_mfma_reg_tables(const IndexView &v);    // the tile's tables fit the registers (sparse instruction)
 // grouping of the (query, probed list) pairs by list and the unit table, then the scan itself
 int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
 int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev);

@@ -321,7 +321,9 @@ static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a
     const uint32_t need = (uint32_t)a.refine_k;
     uint32_t cum = 0;
     int b = RAIRS_HIST_BINS;
-    constexpr int HB = RAIRS_HIST_BINS / 4 < 16 ? RAIRS_HIST_BINS / 4 : 16;   // loads in flight at once
+    // (16 bins in flight at a time: all 64 at once take 64 registers, which the scan loop around
+    // this call then pays for with spills)
+    constexpr int HB = 4;
     for (int i0 = 0; i0 < RAIRS_HIST_BINS / 4; i0 += HB) {
         uint4 h[HB];
 #pragma unroll
@@ -349,10 +351,9 @@ static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a
 #define STAGE_CAP 128              // a multiple of 64 (a flush takes the queue in rows of 64); 192 and 256 measured slower
 static_assert(STAGE_CAP % 64 == 0 && STAGE_CAP >= 128, "stage queue rows");
 #define LOG_CHUNK 256
+#define LOG_COUNTED 0x80000000u    // bit 31 of a staged slot: the entry counts in the histogram
 struct StageQueue {
-    uint32_t slot[STAGE_CAP];      // block * 32 + item
-    uint32_t score_list[STAGE_CAP];// score << 16 | probed list
-    uint32_t qid[STAGE_CAP];       // bit 31: the entry counts in the histogram
+    uint2 ent[STAGE_CAP];          // the log entry: {block * 32 + item (| LOG_COUNTED), score << 16 | query of the pass}
     uint32_t hmul[STAGE_CAP];      // hist_mul of the query's score range
 };
 
@@ -395,14 +396,12 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
     for (int u = 0; u < STAGE_CAP / 64; u++) {
         const int i = lane + 64 * u;
         if (i < n) {
-            const uint32_t qraw = sq.qid[i], qid = qraw & 0x7FFFFFFFu;
-            const uint32_t sl = sq.score_list[i];
-            if (room)
-                a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint2(sq.slot[i], (sl & 0xFFFF0000u) | qid);
-            if (qraw >> 31)
-            {
+            const uint2 e = sq.ent[i];
+            const uint32_t qid = e.y & 0xFFFFu;
+            if (room) a.log[(size_t)lc.chunk * LOG_CHUNK + lc.used + i] = make_uint2(e.x & ~LOG_COUNTED, e.y);
+            if (e.x & LOG_COUNTED) {
                 // scores beyond the histogram's range share the last bin
-                const uint32_t bin = __umulhi(sl >> 16, sq.hmul[i]);
+                const uint32_t bin = __umulhi(e.y >> 16, sq.hmul[i]);
                 atomicAdd(&a.hist[(size_t)qid * RAIRS_HIST_BINS + (bin < RAIRS_HIST_BINS - 1 ? bin : RAIRS_HIST_BINS - 1)], 1u);
             }
         }
@@ -414,7 +413,7 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
         rp.since = 0;
         bool lowered = false;
         if (lane < n && ((lane + rp.turn) & (REFRESH_LANES_MASK)) == 0) {
-            const int qid = (int)(sq.qid[lane] & 0x7FFFFFFFu);
+            const int qid = (int)(sq.ent[lane].y & 0xFFFFu);
             const int32_t cur = __hip_atomic_load(&a.bound[qid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const uint32_t nb = histogram_bound(a, qid, sq.hmul[lane]);
             if (nb < 0xFFFFu && (int32_t)nb < cur) {
@@ -428,20 +427,31 @@ static __device__ __forceinline__ void stage_flush(const MfmaScanArgs &a, StageQ
     lc.used += (uint32_t)n;
 }
 
-// Bit r of the result: acc[r] <= th.  Built in three groups whose bit values are all inline
-// constants (1 .. 64) and joined by shifts, so that no register has to hold a larger power of two
-// through the scan loop.
-static __device__ __forceinline__ uint32_t passing_rows(const v16i &acc, int th)
+// The accumulators of a block start at -(th + 1), th the lane's threshold in the matrix core's
+// signed units, so a row passes (score <= th) exactly when its accumulator ends up negative, and
+// the mask of passing rows is the 16 sign bits: one funnel shift per row, no compare, no select.
+// Lanes that must not pass anything start at a large positive value instead.
+#define ACC_NEVER 0x3FFFFFFF
+static __device__ __forceinline__ uint32_t negative_rows(const v16i &acc)
 {
-    uint32_t p0 = 0, p1 = 0, p2 = 0;
+    uint32_t pm = 0;
 #pragma unroll
-    for (int r = 0; r < 7; r++) p0 |= acc[r] <= th ? (1u << r) : 0u;
-#pragma unroll
-    for (int r = 7; r < 14; r++) p1 |= acc[r] <= th ? (1u << (r - 7)) : 0u;
-#pragma unroll
-    for (int r = 14; r < 16; r++) p2 |= acc[r] <= th ? (1u << (r - 14)) : 0u;
-    asm volatile("" : "+v"(p1), "+v"(p2));             // keep the compiler from folding the shifts back in
-    return p0 | (p1 << 7) | (p2 << 14);
+    for (int r = 15; r >= 0; r--) pm = __builtin_amdgcn_alignbit(pm, (uint32_t)acc[r], 31);   // pm << 1 | sign
+    return pm;
+}
+
+// Kept values and positions of the compressed one-hot operand, by code: entry c of the first 16
+// is the 8 kept values (a one in the first slot of group c >> 2), entry 16 + c the 8 two-bit
+// positions (c & 3 in that slot) once as the low and once as the high half of the position word.
+static __device__ __forceinline__ void fill_sparse_tab(uint2 *tab)
+{
+    if (threadIdx.x < 16) {
+        const int c = threadIdx.x;
+        const unsigned long long val = 1ull << (16 * (c >> 2));
+        const uint32_t pos = (uint32_t)(c & 3) << (4 * (c >> 2));
+        tab[c] = make_uint2((uint32_t)val, (uint32_t)(val >> 32));
+        tab[16 + c] = make_uint2(pos, pos << 16);
+    }
 }
 
 // Number of set bits of `mask` below this lane.
@@ -474,18 +484,9 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
     __shared__ StageQueue stage[WG / 64];
     // A code byte holds the codes (c1, c2) of two sub-quantizers of one instruction; their one-hot
     // rows of 16 + 16 zeros and ones are 2:4 sparse, so the matrix core takes them compressed:
-    // per group of four positions two kept values and their 2-bit positions.  Entry of a code c:
-    // its 8 kept values (a one in the first slot of group c >> 2) and its 8 positions (c & 3 in
-    // that slot), the latter once as the low and once as the high half of the position word.
-    // Sixteen entries of 16 bytes: lanes reading the same entry share one access, different
-    // entries sit in different banks.
-    __shared__ uint4 sparse_tab[16];
-    if (threadIdx.x < 16) {
-        const int c = threadIdx.x;
-        const unsigned long long val = 1ull << (16 * (c >> 2));
-        const uint32_t pos = (uint32_t)(c & 3) << (4 * (c >> 2));
-        sparse_tab[c] = make_uint4((uint32_t)val, (uint32_t)(val >> 32), pos, pos << 16);
-    }
+    // per group of four positions two kept values and their 2-bit positions, looked up by code.
+    __shared__ uint2 sparse_tab[32];
+    fill_sparse_tab(sparse_tab);
     __syncthreads();
     const int lane = threadIdx.x & 63, g = lane >> 5, j = lane & 31;
     StageQueue &sq = stage[threadIdx.x >> 6];
@@ -504,15 +505,6 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
     lc.next_v = gwave + nwaves;
     lc.used = 0;
     RefreshPace pace = {REFRESH_GAP_MIN, REFRESH_GAP_MIN - 1u, 0u};
-#ifdef RAIRS_PROFILE_CYCLES
-    long long pc_t0 = clock64(), pc_tile = 0, pc_blocks = 0, pc_slow = 0, pc_flush = 0, pc_decode = 0, pc_mark;
-    long long pc_nblk = 0, pc_nslow = 0, pc_nflush = 0, pc_ntile = 0, pc_ntask = 0;
-#define PC_MARK() pc_mark = clock64()
-#define PC_ADD(x) x += clock64() - pc_mark
-#else
-#define PC_MARK()
-#define PC_ADD(x)
-#endif
 #define FLUSH_STAGE()                                                   \
     do {                                                                \
         stage_flush(a, sq, nstaged, lane, lc, pace);     \
@@ -521,7 +513,6 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 
     uint32_t u = gwave;
     while (u < nunits) {                               // every wave leaves: the counter only grows
-        PC_MARK();
         // ask for the unit after this one now; the answer is not needed before this one is done
         uint32_t u_next = 0;
         if (lane == 0) u_next = atomicAdd(a.next_task, 1u);
@@ -535,8 +526,6 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         // the run's segments, as offsets into the list's segment table
         const int seg0 = __builtin_amdgcn_readfirstlane(v.parts[le.part_begin + p0]) - le.seg_begin;
         const int seg1 = __builtin_amdgcn_readfirstlane(v.parts[le.part_begin + p1]) - le.seg_begin;
-        PC_ADD(pc_decode);
-        PC_MARK();
         int qid;
         uint32_t hmul;
         {
@@ -559,69 +548,69 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                 const v4i y = (*(const v4i *)(lq + t * 64 + 16) ^ flip) & keep4;
                 B[t] = (v8i){x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
             }
-#ifdef RAIRS_PROFILE_CYCLES
-            { int sink = B[0][0] ^ B[TS - 1][7]; asm volatile("" :: "v"(sink)); pc_ntile++; }
-#endif
         }
-        PC_ADD(pc_tile);
         // the query's bound: other waves keep lowering it, so it is looked up again during the
         // run, ahead of the block that uses it (a stale bound is only looser)
-        const int32_t *bq = a.bound + (qid >= 0 ? qid : 0);
-        int bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        const uint32_t *bmq = a.bitmap + (size_t)(qid >= 0 ? qid : 0) * a.bmwords;
+        // per-lane addresses stay 32-bit offsets from uniform bases (a 64-bit pointer per lane
+        // costs two of the registers this kernel is short of)
+        const uint32_t q0 = (uint32_t)(qid >= 0 ? qid : 0);
+        const uint32_t bm0 = q0 * (uint32_t)a.bmwords;   // < 2^27: a pass has at most 65,536 queries of at most 2,048 words
+        int bound_next = __hip_atomic_load(a.bound + q0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         // segment entries run two ahead and the owner's bitmap word one ahead, so that neither
         // is waited for at the head of a segment
         SegEntry se = v.segs[le.seg_begin + seg0];
         SegEntry sen = v.segs[le.seg_begin + (seg0 + 1 < seg1 ? seg0 + 1 : seg0)];
-        uint32_t owner_bits = bmq[se.owner >= 0 ? se.owner >> 5 : 0];
-        const uint32_t *cp = v.codes + (size_t)se.blk_begin * ND * 64 + lane;
+        uint32_t owner_bits = a.bitmap[bm0 + (uint32_t)(se.owner >= 0 ? se.owner >> 5 : 0)];
+        const uint32_t *cp = v.codes + (size_t)se.blk_begin * ND * 64;      // wave-uniform
         uint32_t cn[ND];
 #pragma unroll
-        for (int w = 0; w < ND; w++) cn[w] = cp[w * 64];
+        for (int w = 0; w < ND; w++) cn[w] = cp[w * 64 + lane];
         // {countable slots, slots in use} of the block, fetched with its codes
         uint2 cmn = v.bmask[se.blk_begin];
         uint32_t scored = 0;                           // items this lane's query was scored against in this unit
         for (int seg = seg0; seg < seg1; seg++) {
-#ifdef RAIRS_PROFILE_CYCLES
-            pc_ntask++;
-#endif
             const bool has_next = seg + 1 < seg1;
             const SegEntry sen2 = v.segs[le.seg_begin + (seg + 2 < seg1 ? seg + 2 : seg1 - 1)];
-            const uint32_t ob_next = bmq[sen.owner >= 0 ? sen.owner >> 5 : 0];
-            const uint32_t *cpn = v.codes + (size_t)sen.blk_begin * ND * 64 + lane;
+            const uint32_t ob_next = a.bitmap[bm0 + (uint32_t)(sen.owner >= 0 ? sen.owner >> 5 : 0)];
+            const uint32_t *cpn = v.codes + (size_t)sen.blk_begin * ND * 64;   // wave-uniform
             // cell (owner, L) is scored through list `owner` for queries that probe it
             const bool live = qid >= 0 && !(se.owner >= 0 && ((owner_bits >> (se.owner & 31)) & 1u));
             if (__ballot(live) == 0ull) {
                 // nobody needs this run; keep the prefetch chain going
                 if (has_next) {
 #pragma unroll
-                    for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64];
+                    for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64 + lane];
                     cmn = v.bmask[sen.blk_begin];
                 }
             } else {
                 uint32_t seg_items = 0;                // wave-uniform: slots in use of the blocks contracted
                 for (int b = 0; b < se.nblk; b++) {
-                    PC_MARK();
                     uint32_t c[ND];
 #pragma unroll
                     for (int w = 0; w < ND; w++) c[w] = cn[w];
                     const uint32_t cmask = cmn.x;
                     seg_items += (uint32_t)__popc(cmn.y);
-                    const int th = live ? bound_next - bias : INT_MIN;
+                    // the accumulators start at -(threshold + 1): a row passes iff it ends up negative
+                    const int negth = live ? -(bound_next - bias + 1) : ACC_NEVER;
                     // (every fourth block is often enough: the bound moves rarely)
-                    if ((b & 3) == 3) bound_next = __hip_atomic_load(bq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if ((b & 3) == 3) bound_next = __hip_atomic_load(a.bound + q0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     if (b + 1 < se.nblk) {             // fetch the next block while this one is scored
 #pragma unroll
-                        for (int w = 0; w < ND; w++) cn[w] = cp[(size_t)(b + 1) * ND * 64 + w * 64];
+                        for (int w = 0; w < ND; w++) cn[w] = cp[(size_t)(b + 1) * ND * 64 + w * 64 + lane];
                         cmn = v.bmask[se.blk_begin + b + 1];
                     } else if (has_next) {             // ... or the first block of the next run
 #pragma unroll
-                        for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64];
+                        for (int w = 0; w < ND; w++) cn[w] = cpn[w * 64 + lane];
                         cmn = v.bmask[sen.blk_begin];
                     }
+                    // (a copy the compiler cannot see through: the accumulators' start value must
+                    // not stay tied to the register that the survivor path reads later, or the
+                    // whole 16-register tuple is built elsewhere and moved)
+                    int acc0 = negth;
+                    asm volatile("" : "+v"(acc0));
                     v16i acc;
 #pragma unroll
-                    for (int r = 0; r < 16; r++) acc[r] = 0;
+                    for (int r = 0; r < 16; r++) acc[r] = acc0;
                     // The table reads of an instruction (values, positions) go out two
                     // instructions ahead of it, so that an LDS round trip hides behind matrix
                     // work; the scheduling fences keep the compiler from moving them either way
@@ -630,10 +619,9 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #define CODE_HI(t_) ((c[(t_) >> 2] >> (8 * ((t_) & 3) + 4)) & 15u)
 #define LOAD_A(t_)                                                                        \
     do {                                                                                  \
-        const uint32_t *e1_ = (const uint32_t *)&sparse_tab[CODE_LO(t_)];                 \
-        const uint32_t *e2_ = (const uint32_t *)&sparse_tab[CODE_HI(t_)];                 \
-        v1[t_] = *(const uint2 *)e1_; v2[t_] = *(const uint2 *)e2_;                       \
-        p1[t_] = e1_[2]; p2[t_] = e2_[3];                                                 \
+        const uint2 *e1_ = &sparse_tab[CODE_LO(t_)], *e2_ = &sparse_tab[CODE_HI(t_)];      \
+        v1[t_] = e1_[0]; v2[t_] = e2_[0];                                                 \
+        p1[t_] = e1_[16].x; p2[t_] = e2_[16].y;                                           \
     } while (0)
                     // raw table words; they are put together where they are used, not where
                     // they are loaded, so that nothing waits for a load in its own stage
@@ -653,16 +641,8 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #undef CODE_LO
 #undef CODE_HI
                     // acc[r]: item row 8*(r/4) + 4*g + (r%4), query column j
-                    uint32_t pm = passing_rows(acc, th);  // rows of this lane that pass
-                    PC_ADD(pc_blocks);
-#ifdef RAIRS_PROFILE_CYCLES
-                    pc_nblk++;
-#endif
+                    uint32_t pm = negative_rows(acc);     // rows of this lane that pass
                     if (__ballot(pm != 0u) != 0ull) {
-                        PC_MARK();
-#ifdef RAIRS_PROFILE_CYCLES
-                        pc_nslow++;
-#endif
                         const uint32_t slot0 = (uint32_t)(se.blk_begin + b) * 32u + 4u * g;
                         if (b == se.nblk - 1 && se.tail_valid < 32) {
                             // the list's last block: drop rows whose slot holds no item
@@ -677,27 +657,19 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
                             // every lane selects (lanes without a row select row 0 and drop it)
                             const int r = has ? __builtin_ctz(pm) : 0;
                             pm &= pm - 1u;
-                            const int sc = select_row(acc, r);
+                            const int sc = select_row(acc, r) - negth;    // the row's sum, in the matrix core's units
                             if (has) {
                                 const int pos = nstaged + lanes_below(mask);
                                 const uint32_t item = 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);   // + 4 g
-                                sq.slot[pos] = slot0 + item;
-                                sq.score_list[pos] = ((uint32_t)(sc + bias) << 16) | (uint32_t)L;
-                                sq.qid[pos] = (uint32_t)qid | (((cmask >> (item + 4u * g)) & 1u) << 31);
+                                sq.ent[pos] = make_uint2((slot0 + item) | (((cmask >> (item + 4u * g)) & 1u) << 31),
+                                                         ((uint32_t)(sc + bias) << 16) | (uint32_t)qid);
                                 sq.hmul[pos] = hmul;
                             }
                             nstaged += __popcll(mask);
                             if (nstaged > STAGE_CAP - 64) {
-#ifdef RAIRS_PROFILE_CYCLES
-                                long long f0 = clock64();
-#endif
                                 FLUSH_STAGE();
-#ifdef RAIRS_PROFILE_CYCLES
-                                pc_flush += clock64() - f0; pc_nflush++;
-#endif
                             }
                         }
-                        PC_ADD(pc_slow);
                     }
                 }
                 // the distance computations of this run (Section 6.1's DCO): every slot in use of
@@ -716,13 +688,6 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
     }
     if (nstaged > 0) FLUSH_STAGE();
     if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
-#ifdef RAIRS_PROFILE_CYCLES
-    if (lane == 0 && a.prof) {
-        long long *o = a.prof + (size_t)(blockIdx.x * (WG / 64) + (threadIdx.x >> 6)) * 12;
-        o[0] = clock64() - pc_t0; o[1] = pc_decode; o[2] = pc_tile; o[3] = pc_blocks; o[4] = pc_slow;
-        o[5] = pc_flush; o[6] = pc_nblk; o[7] = pc_nslow; o[8] = pc_nflush; o[9] = pc_ntile; o[10] = pc_ntask;
-    }
-#endif
 }
 
 // Distribute the survivor log to the per-query buffers (a workgroup takes one chunk at a time).  A chunk holds
@@ -1076,7 +1041,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
             for (int w = 0; w < LDSK_MAX_ND; w++) c[w] = cn[w];
             const uint32_t cmask = cmn.x;
             const uint32_t blk_items = (uint32_t)__popc(cmn.y);
-            const int th = cur.live ? bound_next - bias : INT_MIN;
+            const int negth = cur.live ? -(bound_next - bias + 1) : ACC_NEVER;
             fpos += nwave;
             const Blk nxt = locate();
             if (nxt.valid) fetch(nxt);
@@ -1084,7 +1049,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
                 scored += cur.live ? blk_items : 0u;   // the block is contracted now: its DCO
                 v16i acc;
 #pragma unroll
-                for (int r = 0; r < 16; r++) acc[r] = 0;
+                for (int r = 0; r < 16; r++) acc[r] = negth;
 #pragma unroll
                 for (int w = 0; w < LDSK_MAX_ND; w++) {
                     if (w < ND) {                      // uniform
@@ -1096,7 +1061,7 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
                         }
                     }
                 }
-                uint32_t pm = passing_rows(acc, th);
+                uint32_t pm = negative_rows(acc);
                 if (__ballot(pm != 0u) != 0ull) {
                     const uint32_t slot0 = (uint32_t)cur.blk * 32u + 4u * g;
                     const int tail_valid = segs_s[cur.seg].tail_valid;
@@ -1118,12 +1083,11 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
 #pragma unroll
                             for (int k = 0; k < 4; k++) s4[k] = (r & 2) ? s8[2 * k + 1] : s8[2 * k];
                             const int s2a = (r & 4) ? s4[1] : s4[0], s2b = (r & 4) ? s4[3] : s4[2];
-                            const int sc = (r & 8) ? s2b : s2a;
+                            const int sc = ((r & 8) ? s2b : s2a) - negth;
                             const int pos = nstaged + lanes_below(mask);
                             const uint32_t item = 8u * (uint32_t)(r >> 2) + (uint32_t)(r & 3);   // + 4 g
-                            sq.slot[pos] = slot0 + item;
-                            sq.score_list[pos] = ((uint32_t)(sc + bias) << 16) | (uint32_t)L;
-                            sq.qid[pos] = (uint32_t)qid | (((cmask >> (item + 4u * g)) & 1u) << 31);
+                            sq.ent[pos] = make_uint2((slot0 + item) | (((cmask >> (item + 4u * g)) & 1u) << 31),
+                                                     ((uint32_t)(sc + bias) << 16) | (uint32_t)qid);
                             sq.hmul[pos] = hmul;
                         }
                         nstaged += __popcll(mask);
@@ -1256,13 +1220,8 @@ __global__ __launch_bounds__(WG) void sample_mfma_kernel(IndexView v, const uint
     constexpr int ND = (T + 7) / 8;
     constexpr int M = 2 * T;
     constexpr int TS = T / 2;
-    __shared__ uint4 sparse_tab[16];                   // as in scan_mfma_kernel
-    if (threadIdx.x < 16) {
-        const int c = threadIdx.x;
-        const unsigned long long val = 1ull << (16 * (c >> 2));
-        const uint32_t pos = (uint32_t)(c & 3) << (4 * (c >> 2));
-        sparse_tab[c] = make_uint4((uint32_t)val, (uint32_t)(val >> 32), pos, pos << 16);
-    }
+    __shared__ uint2 sparse_tab[32];                   // as in scan_mfma_kernel
+    fill_sparse_tab(sparse_tab);
     __syncthreads();
     const int lane = threadIdx.x & 63, g = lane >> 5, j = lane & 31;
     const uint32_t bias = 128u * M;
@@ -1314,10 +1273,9 @@ __global__ __launch_bounds__(WG) void sample_mfma_kernel(IndexView v, const uint
 #define CODE_HI(t_) ((c[(t_) >> 2] >> (8 * ((t_) & 3) + 4)) & 15u)
 #define LOAD_A(t_)                                                                        \
     do {                                                                                  \
-        const uint32_t *e1_ = (const uint32_t *)&sparse_tab[CODE_LO(t_)];                 \
-        const uint32_t *e2_ = (const uint32_t *)&sparse_tab[CODE_HI(t_)];                 \
-        v1[t_] = *(const uint2 *)e1_; v2[t_] = *(const uint2 *)e2_;                       \
-        p1[t_] = e1_[2]; p2[t_] = e2_[3];                                                 \
+        const uint2 *e1_ = &sparse_tab[CODE_LO(t_)], *e2_ = &sparse_tab[CODE_HI(t_)];      \
+        v1[t_] = e1_[0]; v2[t_] = e2_[0];                                                 \
+        p1[t_] = e1_[16].x; p2[t_] = e2_[16].y;                                           \
     } while (0)
             uint2 v1[TS], v2[TS];
             uint32_t p1[TS], p2[TS];
@@ -1404,12 +1362,14 @@ bool rairs_mfma_supported(const IndexView &v)
     return v.T >= 1 && v.nd * 8 * 64 * 16 <= 128 * 1024;    // tables of a tile must fit 128 KB of LDS
 }
 
+bool rairs_mfma_reg_tables(const IndexView &v) { return v.T == 8 || v.T == 24 || v.T == 32; }
+
 // persistent grids: 256 compute units x 2 workgroups of 4 waves with the tables in registers; one
 // workgroup per compute unit, with as many waves as LDS leaves room for, with the tables in LDS
 static void scan_launch_shape(const IndexView &v, bool *reg_tables, unsigned *grid, int *lds_waves,
                               size_t *table_bytes)
 {
-    *reg_tables = v.T == 8 || v.T == 24 || v.T == 32;
+    *reg_tables = rairs_mfma_reg_tables(v);
     *grid = *reg_tables ? 512u : 256u;
     *table_bytes = (size_t)v.nd * 8 * 64 * 16;
     int w = 16;
