@@ -303,6 +303,9 @@ def main():
                          "(for profiling; the headline numbers are quoted at full size)")
     ap.add_argument("--recall-queries", type=int, default=0,
                     help="measure recall on the first N queries only (0 = all); for very large bases")
+    ap.add_argument("--parity-queries", type=int, default=0,
+                    help="at every swept nprobe, also compare the first N queries' ids and DCO with the "
+                         "CPU oracle's (the protocol for the largest workload: N >= 1000)")
     ap.add_argument("--k", type=int, default=0, help="override K of the workload (second workloads: K = 1, 100)")
     ap.add_argument("--refine-k", type=int, default=0, help="override bigK = K * K_FACTOR")
     ap.add_argument("--nq", type=int, default=0, help="queries per step (default: the workload's batch)")
@@ -397,13 +400,28 @@ def main():
         return sec, stage
 
     # --- nprobe sweep: recall and a quick rate per point ---------------------------------
+    parity_ox = None
+
     def measure_point(nprobe):
+        nonlocal parity_ox
         run(nprobe, 1)
-        rec = recall_at_k(out_ids.cpu().numpy()[:nrec], gt)
+        got = out_ids.cpu().numpy()
+        rec = recall_at_k(got[:nrec], gt)
+        parity = None
+        if args.parity_queries:
+            from oracle import oracle
+            if parity_ox is None:
+                parity_ox = oracle.OracleIndex(hx)
+            npar = min(args.parity_queries, nq)
+            t = time.perf_counter()
+            want = oracle.search(parity_ox, queries[:npar], w.k, nprobe, w.refine_k)
+            parity = dict(queries=npar, ids_identical=bool((got[:npar] == want.ids).all()),
+                          dco_identical=bool((ix.dco(nq)[:npar] == want.dco).all()),
+                          oracle_seconds=round(time.perf_counter() - t, 1))
         sec, stage = run(nprobe, 3, profile=True)
         dco = ix.dco(nq)
         st = ix.scan_stats()
-        point = dict(nprobe=nprobe, recall_at_10=round(rec, 4), qps=round(3 * nq / sec, 1),
+        point = dict(nprobe=nprobe, recall_at_10=round(rec, 4), qps=round(3 * nq / sec, 1), parity=parity,
                      ms_per_batch=round(sec / 3 * 1e3, 3), dco_per_query=float(dco.mean()),
                      stage_ms={k: round(v, 4) for k, v in stage.items()},
                      survivors_per_query=round(st["survivors"] / max(1, st["queries"]), 1),

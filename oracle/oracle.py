@@ -28,6 +28,7 @@ def build(force: bool = False) -> str:
 class _Index(C.Structure):
     _fields_ = [
         ("d", C.c_int32), ("M", C.c_int32), ("nlist", C.c_int32), ("raw_is_u8", C.c_int32),
+        ("metric", C.c_int32), ("blk", C.c_int32),
         ("ntotal", C.c_int64), ("nblocks", C.c_int64), ("nrefs", C.c_int64),
         ("centroids", C.c_void_p), ("codebook", C.c_void_p), ("codes", C.c_void_p),
         ("ids", C.c_void_p), ("other", C.c_void_p),
@@ -45,6 +46,8 @@ def _load():
         _lib = C.CDLL(build())
         _lib.oracle_l2sqr.restype = C.c_float
         _lib.oracle_l2sqr_u8.restype = C.c_float
+        _lib.oracle_ip.restype = C.c_float
+        _lib.oracle_ip_u8.restype = C.c_float
         _lib.oracle_search.restype = C.c_int
     return _lib
 
@@ -64,6 +67,10 @@ class OracleIndex:
         self.keep = {}
         s = _Index()
         s.d, s.M, s.nlist = hx.d, hx.M, hx.nlist
+        # metric: "l2" (squared Euclidean distance) or "ip" (inner product); blk: items per block
+        self.metric = getattr(hx, "metric", "l2")
+        s.metric = {"l2": 0, "ip": 1}[self.metric]
+        s.blk = int(hx.ids.shape[1])
         s.ntotal, s.nblocks, s.nrefs = hx.ntotal, hx.ids.shape[0], hx.ref_owner.shape[0]
         for name, dt in _FIELDS:
             a = np.ascontiguousarray(getattr(hx, name), dtype=dt)
@@ -82,7 +89,7 @@ class OracleIndex:
 @dataclass
 class OracleResult:
     ids: np.ndarray         # [nq][k] i64
-    dists: np.ndarray       # [nq][k] f32, squared L2
+    dists: np.ndarray       # [nq][k] f32: squared L2 ascending, or inner products descending
     cand_ids: np.ndarray    # [nq][refine_k] i64 in (score, id) order, -1 padded
     cand_acc: np.ndarray    # [nq][refine_k] i32 16-bit scores, -1 padded
     dco: np.ndarray         # [nq] i64 items scored
@@ -102,6 +109,17 @@ def l2sqr(a: np.ndarray, b: np.ndarray) -> float:
     b = np.ascontiguousarray(b, dtype=np.float32)
     return float(lib.oracle_l2sqr(C.c_void_p(a.ctypes.data), C.c_void_p(b.ctypes.data),
                                   C.c_int(a.size)))
+
+
+def ip(a: np.ndarray, b: np.ndarray) -> float:
+    """Inner product in the oracle's summation order (b float32 or uint8)."""
+    lib = _load()
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if b.dtype == np.uint8:
+        b = np.ascontiguousarray(b)
+        return float(lib.oracle_ip_u8(C.c_void_p(a.ctypes.data), C.c_void_p(b.ctypes.data), C.c_int(a.size)))
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    return float(lib.oracle_ip(C.c_void_p(a.ctypes.data), C.c_void_p(b.ctypes.data), C.c_int(a.size)))
 
 
 def coarse(ox: OracleIndex, q: np.ndarray, nprobe: int):

@@ -31,7 +31,14 @@
  *   - Alg. 5 walks the selected lists in ascending list id, which is what makes its
  *     "no duplicate" claim for physically stored shared blocks hold (the owner of a shared cell
  *     is the smaller list id);
- *   - a distance computation (DCO) is one valid item slot scored during the list scan.
+ *   - a distance computation (DCO) is one valid item slot scored during the list scan;
+ *   - inner-product metric (the paper applies SEIL to an inner-product index in Section 6.4 and
+ *     does not describe the search beyond that): every "distance" is the negated inner product,
+ *     so that smaller is still better -- probed lists: the nprobe largest <q, c> (ties: smaller
+ *     list id); table entry T[m][c] = -<q_m, codeword_{m,c}>, quantised as above; results: the K
+ *     largest exact <q, x> (ties: smaller id), reported as inner products, missing entries -inf.
+ *     An inner product over d dimensions is summed like a squared distance: 64 interleaved partial
+ *     sums of the products q_i x_i, folded the same way.
  *
  * Build with -ffp-contract=off and without -ffast-math: the arithmetic above is the contract.
  *
@@ -46,16 +53,19 @@
 #include <omp.h>
 #endif
 
-#define BLK 32
+
+#define METRIC_L2 0
+#define METRIC_IP 1
 
 typedef struct {
     int32_t d, M, nlist, raw_is_u8;
+    int32_t metric, blk;               /* METRIC_*; items per block (BLK_SZ of Alg. 4) */
     int64_t ntotal, nblocks, nrefs;
     const float *centroids;            /* [nlist][d] */
     const float *codebook;             /* [M][16][d/M] */
-    const uint8_t *codes;              /* [nblocks][32][M/2] */
-    const int64_t *ids;                /* [nblocks][32] */
-    const int32_t *other;              /* [nblocks][32] */
+    const uint8_t *codes;              /* [nblocks][blk][M/2] */
+    const int64_t *ids;                /* [nblocks][blk] */
+    const int32_t *other;              /* [nblocks][blk] */
     const int64_t *list_shared_begin;
     const int32_t *list_shared_cnt;
     const int64_t *list_misc_begin;
@@ -94,6 +104,29 @@ float oracle_l2sqr(const float *a, const float *b, int d)
     return fold64(p);
 }
 
+/* inner product in the same summation order */
+float oracle_ip(const float *a, const float *b, int d)
+{
+    float p[64];
+    for (int j = 0; j < 64; j++) p[j] = 0.0f;
+    for (int i = 0; i < d; i++) {
+        float prod = a[i] * b[i];
+        p[i & 63] = p[i & 63] + prod;
+    }
+    return fold64(p);
+}
+
+float oracle_ip_u8(const float *a, const uint8_t *b, int d)
+{
+    float p[64];
+    for (int j = 0; j < 64; j++) p[j] = 0.0f;
+    for (int i = 0; i < d; i++) {
+        float prod = a[i] * (float)b[i];
+        p[i & 63] = p[i & 63] + prod;
+    }
+    return fold64(p);
+}
+
 float oracle_l2sqr_u8(const float *a, const uint8_t *b, int d)
 {
     float p[64];
@@ -123,13 +156,15 @@ void oracle_coarse(const oracle_index *ix, const float *q, int nprobe, int32_t *
 {
     dist_id *all = (dist_id *)malloc(sizeof(dist_id) * (size_t)ix->nlist);
     for (int l = 0; l < ix->nlist; l++) {
-        all[l].dist = oracle_l2sqr(q, ix->centroids + (size_t)l * ix->d, ix->d);
+        const float *c = ix->centroids + (size_t)l * ix->d;
+        /* inner product: order by the negated product, so that the same comparison serves */
+        all[l].dist = ix->metric == METRIC_IP ? -oracle_ip(q, c, ix->d) : oracle_l2sqr(q, c, ix->d);
         all[l].id = l;
     }
     qsort(all, (size_t)ix->nlist, sizeof(dist_id), cmp_dist_id);
     for (int i = 0; i < nprobe; i++) {
         out_lists[i] = (int32_t)all[i].id;
-        if (out_dists) out_dists[i] = all[i].dist;
+        if (out_dists) out_dists[i] = ix->metric == METRIC_IP ? -all[i].dist : all[i].dist;
     }
     free(all);
 }
@@ -148,10 +183,16 @@ void oracle_lut(const oracle_index *ix, const float *q, float *T, uint8_t *lut, 
             const float *cw = ix->codebook + ((size_t)m * 16 + c) * dsub;
             float acc = 0.0f;
             for (int t = 0; t < dsub; t++) {
-                float a = q[m * dsub + t] - cw[t];
-                float sq = a * a;
-                if (t == 0) acc = sq; else acc = acc + sq;
+                float term;
+                if (ix->metric == METRIC_IP) {
+                    term = q[m * dsub + t] * cw[t];
+                } else {
+                    float a = q[m * dsub + t] - cw[t];
+                    term = a * a;
+                }
+                if (t == 0) acc = term; else acc = acc + term;
             }
+            if (ix->metric == METRIC_IP) acc = -acc;        /* smaller is better */
             T[m * 16 + c] = acc;
             if (acc < lo) lo = acc;
             if (acc > hi) hi = acc;
@@ -216,7 +257,7 @@ typedef struct {
 static int64_t scan_block(const oracle_index *ix, const uint8_t *lut, int64_t b,
                           const uint8_t *visited, int is_misc, keyvec *rq, probe_trace *tr)
 {
-    const int hb = ix->M / 2;
+    const int hb = ix->M / 2, BLK = ix->blk;
     int64_t dco = 0;
     if (tr) tr->block_count[b]++;
     for (int s = 0; s < BLK; s++) {
@@ -340,14 +381,20 @@ int oracle_search(const oracle_index *ix, const float *queries, int64_t nq, int 
         for (size_t i = 0; i < nc; i++) {
             int64_t id = (int64_t)(uint32_t)rq.keys[i];
             ex[i].id = id;
-            ex[i].dist = ix->raw_is_u8
-                ? oracle_l2sqr_u8(q, (const uint8_t *)ix->raw + (size_t)id * d, d)
-                : oracle_l2sqr(q, (const float *)ix->raw + (size_t)id * d, d);
+            if (ix->metric == METRIC_IP)
+                ex[i].dist = ix->raw_is_u8
+                    ? -oracle_ip_u8(q, (const uint8_t *)ix->raw + (size_t)id * d, d)
+                    : -oracle_ip(q, (const float *)ix->raw + (size_t)id * d, d);
+            else
+                ex[i].dist = ix->raw_is_u8
+                    ? oracle_l2sqr_u8(q, (const uint8_t *)ix->raw + (size_t)id * d, d)
+                    : oracle_l2sqr(q, (const float *)ix->raw + (size_t)id * d, d);
         }
         qsort(ex, nc, sizeof(dist_id), cmp_dist_id);
+        const float sign = ix->metric == METRIC_IP ? -1.0f : 1.0f;   /* reported: the inner product itself */
         for (int i = 0; i < k; i++) {
             out_ids[(size_t)qi * k + i] = (size_t)i < nc ? ex[i].id : -1;
-            out_dists[(size_t)qi * k + i] = (size_t)i < nc ? ex[i].dist : INFINITY;
+            out_dists[(size_t)qi * k + i] = (size_t)i < nc ? sign * ex[i].dist : sign * INFINITY;
         }
         free(ex); free(rq.keys); free(probes); free(lut); free(T);
     }

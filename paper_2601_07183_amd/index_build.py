@@ -16,7 +16,7 @@ from dataclasses import dataclass, field
 import numpy as np
 import torch
 
-BLK = 32  # items per block (BLK_SZ in Alg. 4)
+BLK = 32  # items per block (BLK_SZ in Alg. 4) unless a builder is told otherwise
 
 
 @dataclass
@@ -46,6 +46,14 @@ class HostIndex:
     assign: np.ndarray             # [ntotal][2] i32, assign[:,0] <= assign[:,1]
     vec_codes: np.ndarray          # [ntotal][M/2] u8
     params: dict = field(default_factory=dict)
+    # "l2": squared Euclidean distance; "ip": inner product (larger is better), the metric of the
+    # index that Section 6.4 applies SEIL to
+    metric: str = "l2"
+
+    @property
+    def blk(self) -> int:
+        """Items per block (BLK_SZ of Alg. 4); the device path is built for 32."""
+        return int(self.ids.shape[1])
 
     @property
     def nblocks(self) -> int:
@@ -228,15 +236,58 @@ def rair_assign(x: np.ndarray, centroids: np.ndarray, lam: float = 0.5, n_cands:
     return out
 
 
+def soar_loss(v: np.ndarray, cand_centroids: np.ndarray, lam: float) -> np.ndarray:
+    """SOAR's criterion as Section 2.3 and Table 1 state it: loss[i] = ||r_i||^2 +
+    lam * (<r_0, r_i> / ||r_0||)^2 with r_i = v - centroid_i (the second term is 0 when r_0 = 0).
+    v: [n][d]; cand_centroids: [n][ncand][d] ordered by distance to v.  float64."""
+    r = v.astype(np.float64)[:, None, :] - cand_centroids.astype(np.float64)
+    n0 = (r[:, 0, :] ** 2).sum(-1)
+    proj2 = (r * r[:, :1, :]).sum(-1) ** 2 / np.where(n0 > 0, n0, 1.0)[:, None]
+    return (r * r).sum(-1) + lam * np.where(n0[:, None] > 0, proj2, 0.0)
+
+
+def soar_assign(x: np.ndarray, centroids: np.ndarray, lam: float = 1.0, n_cands: int = 10,
+                chunk: int = 32768) -> np.ndarray:
+    """Two list ids per vector by SOAR (Section 2.3): the nearest centroid, and among the other
+    n_cands - 1 nearest the one of least ||r'||^2 + lam (r.r' / ||r||)^2, i.e. a second residual
+    as orthogonal to the first as the distances allow.  Returned ordered, smaller id first."""
+    n = x.shape[0]
+    nlist = centroids.shape[0]
+    n_cands = min(n_cands, nlist)
+    out = np.empty((n, 2), dtype=np.int32)
+    c64 = centroids.astype(np.float64)
+    cn = (c64 ** 2).sum(1)
+    for lo in range(0, n, chunk):
+        xs = x[lo:lo + chunk].astype(np.float64)
+        g = cn[None, :] - 2.0 * (xs @ c64.T)
+        cand = np.argpartition(g, n_cands - 1, axis=1)[:, :n_cands] if n_cands < nlist else \
+            np.tile(np.arange(nlist), (xs.shape[0], 1))
+        cand = np.sort(cand, axis=1)
+        dist = ((c64[cand] - xs[:, None, :]) ** 2).sum(-1)
+        key = np.argsort(dist, axis=1, kind="stable")               # ties keep the lower id
+        cand = np.take_along_axis(cand, key, axis=1)
+        first = cand[:, 0]
+        if n_cands < 2:
+            second = first
+        else:
+            loss = soar_loss(xs, c64[cand], lam)[:, 1:]
+            second = np.take_along_axis(cand[:, 1:], loss.argmin(1)[:, None], axis=1)[:, 0]
+        out[lo:lo + chunk, 0] = np.minimum(first, second)
+        out[lo:lo + chunk, 1] = np.maximum(first, second)
+    return out
+
+
 # ----------------------------------------------------------------------------------------------
 # SeilInsert (Alg. 4), one batch
 # ----------------------------------------------------------------------------------------------
 
-def seil_insert(assign: np.ndarray, vec_codes: np.ndarray, vec_ids: np.ndarray, nlist: int):
-    """Lay the items out as Alg. 4 does for a single batch.
+def seil_insert(assign: np.ndarray, vec_codes: np.ndarray, vec_ids: np.ndarray, nlist: int,
+                blk: int = BLK):
+    """Lay the items out as Alg. 4 does for a single batch, with `blk` items per block (blk_SZ;
+    32 by default, the size the device path is built for; Section 6.4 also looks at 16 and 64).
 
     Items are sorted by {listID1, listID2, vec_id}; a cell (i,j) of `nitems` items yields
-    nitems // 32 full blocks stored once, in list i's shared area, and nitems % 32 leftovers that
+    nitems // blk full blocks stored once, in list i's shared area, and nitems % blk leftovers that
     go to the miscellaneous area of list i and, when j != i, also of list j, each tagged with the
     other list id.  List j gets a reference entry (i, nblocks, first block) -- emitted only when
     nblocks >= 1.  Within a list, shared blocks precede miscellaneous blocks; only the last
@@ -255,8 +306,8 @@ def seil_insert(assign: np.ndarray, vec_codes: np.ndarray, vec_ids: np.ndarray, 
     c_start = first
     c_n = np.diff(np.concatenate([first, [n]]))
     c_l1, c_l2 = s1[first], s2[first]
-    c_nb = c_n // BLK
-    c_nm = c_n % BLK
+    c_nb = c_n // blk
+    c_nm = c_n % blk
     ncell = first.size
 
     # pass 1: per-list block and leftover counts
@@ -264,16 +315,16 @@ def seil_insert(assign: np.ndarray, vec_codes: np.ndarray, vec_ids: np.ndarray, 
     list_nm = np.bincount(c_l1, weights=c_nm, minlength=nlist).astype(np.int64)
     two = c_l1 != c_l2
     list_nm += np.bincount(c_l2[two], weights=c_nm[two], minlength=nlist).astype(np.int64)
-    list_mb = (list_nm + BLK - 1) // BLK
+    list_mb = (list_nm + blk - 1) // blk
     list_tot = list_nb + list_mb
     list_begin = np.concatenate([[0], np.cumsum(list_tot)[:-1]]).astype(np.int64)
     shared_begin = list_begin
     misc_begin = list_begin + list_nb
     nblocks = int(list_tot.sum())
 
-    codes = np.zeros((nblocks * BLK, hb), dtype=np.uint8)
-    ids = np.full(nblocks * BLK, -1, dtype=np.int64)
-    other = np.full(nblocks * BLK, -1, dtype=np.int32)
+    codes = np.zeros((nblocks * blk, hb), dtype=np.uint8)
+    ids = np.full(nblocks * blk, -1, dtype=np.int64)
+    other = np.full(nblocks * blk, -1, dtype=np.int32)
 
     # pass 2a: full blocks of each cell, contiguous, in list l1's shared area
     excl = np.cumsum(c_nb) - c_nb                      # blocks of earlier cells (global order)
@@ -289,9 +340,9 @@ def seil_insert(assign: np.ndarray, vec_codes: np.ndarray, vec_ids: np.ndarray, 
 
     cell_of_item = np.repeat(np.arange(ncell), c_n)
     off = np.arange(n) - c_start[cell_of_item]
-    in_shared = off < (c_nb[cell_of_item] * BLK)
+    in_shared = off < (c_nb[cell_of_item] * blk)
     src = order[in_shared]
-    dst = c_bbegin[cell_of_item[in_shared]] * BLK + off[in_shared]
+    dst = c_bbegin[cell_of_item[in_shared]] * blk + off[in_shared]
     codes[dst] = vec_codes[src]
     ids[dst] = vec_ids[src]
 
@@ -311,7 +362,7 @@ def seil_insert(assign: np.ndarray, vec_codes: np.ndarray, vec_ids: np.ndarray, 
     cnt = np.bincount(e_dest, minlength=nlist)
     assert (cnt == list_nm).all()
     rank = np.arange(e_dest.size) - np.repeat(np.cumsum(cnt) - cnt, cnt)
-    dst = misc_begin[e_dest] * BLK + rank
+    dst = misc_begin[e_dest] * blk + rank
     src = order[e_pos]
     codes[dst] = vec_codes[src]
     ids[dst] = vec_ids[src]
@@ -328,8 +379,8 @@ def seil_insert(assign: np.ndarray, vec_codes: np.ndarray, vec_ids: np.ndarray, 
     ref_begin = (np.cumsum(ref_cnt) - ref_cnt).astype(np.int64)
 
     return dict(
-        codes=codes.reshape(nblocks, BLK, hb), ids=ids.reshape(nblocks, BLK),
-        other=other.reshape(nblocks, BLK),
+        codes=codes.reshape(nblocks, blk, hb), ids=ids.reshape(nblocks, blk),
+        other=other.reshape(nblocks, blk),
         list_shared_begin=shared_begin.astype(np.int64), list_shared_cnt=list_nb.astype(np.int32),
         list_misc_begin=misc_begin.astype(np.int64), list_misc_cnt=list_mb.astype(np.int32),
         list_ref_begin=ref_begin, list_ref_cnt=ref_cnt,
@@ -343,35 +394,39 @@ def seil_insert(assign: np.ndarray, vec_codes: np.ndarray, vec_ids: np.ndarray, 
 
 def build_index(base: np.ndarray, nlist: int, M: int, *, lam: float = 0.5, n_cands: int = 10,
                 strict: bool = True, seed: int = 0, coarse_iters: int = 20, pq_iters: int = 25,
-                assign: np.ndarray | None = None) -> HostIndex:
+                assign: np.ndarray | None = None, metric: str = "l2", blk: int = BLK) -> HostIndex:
     """Train centroids and codebook on `base`, then add all of `base` as one batch.
-    `assign` overrides RairAssign (tests use it for random and adversarial cell structures)."""
+    `assign` overrides the assignment (tests use it for random and adversarial cell structures).
+    metric "ip": the index is searched by inner product and its second lists come from SOAR
+    (lam is then SOAR's weight) instead of RairAssign."""
     n, d = base.shape
     assert d % M == 0 and M % 2 == 0
     centroids = kmeans(base, nlist, coarse_iters, seed * 7 + 1, max_train=256 * nlist)
     codebook = train_pq(base, M, pq_iters, seed * 7 + 2)
     return add_vectors(base, centroids, codebook, lam=lam, n_cands=n_cands, strict=strict,
-                       assign=assign)
+                       assign=assign, metric=metric, blk=blk)
 
 
 def add_vectors(base: np.ndarray, centroids: np.ndarray, codebook: np.ndarray, *,
                 lam: float = 0.5, n_cands: int = 10, strict: bool = True,
-                assign: np.ndarray | None = None) -> HostIndex:
+                assign: np.ndarray | None = None, metric: str = "l2", blk: int = BLK) -> HostIndex:
     n, d = base.shape
     nlist = centroids.shape[0]
     M = codebook.shape[0]
+    assert metric in ("l2", "ip")
     if assign is None:
-        assign = rair_assign(base, centroids, lam=lam, n_cands=n_cands, strict=strict)
+        assign = soar_assign(base, centroids, lam=lam, n_cands=n_cands) if metric == "ip" else \
+            rair_assign(base, centroids, lam=lam, n_cands=n_cands, strict=strict)
     assign = np.ascontiguousarray(assign, dtype=np.int32)
     vec_codes = pq_encode(base, codebook)
     vec_ids = np.arange(n, dtype=np.int64)
-    lay = seil_insert(assign, vec_codes, vec_ids, nlist)
+    lay = seil_insert(assign, vec_codes, vec_ids, nlist, blk=blk)
     return HostIndex(
         d=d, M=M, nlist=nlist, ntotal=n,
         centroids=np.ascontiguousarray(centroids, dtype=np.float32),
         codebook=np.ascontiguousarray(codebook, dtype=np.float32),
         raw=np.ascontiguousarray(base), assign=assign, vec_codes=vec_codes,
-        params=dict(lam=lam, n_cands=n_cands, strict=strict), **lay)
+        params=dict(lam=lam, n_cands=n_cands, strict=strict), metric=metric, **lay)
 
 
 # ----------------------------------------------------------------------------------------------
@@ -406,13 +461,14 @@ def append_batch(hx: HostIndex, new: np.ndarray, *, lam: float = 0.5, n_cands: i
     form the search side reads; block numbers change, ids do not.
     """
     n0, nlist = hx.ntotal, hx.nlist
+    BLK = hx.blk
     new = np.ascontiguousarray(new, dtype=hx.raw.dtype)
     if assign is None:
         assign = rair_assign(new, hx.centroids, lam=lam, n_cands=n_cands, strict=strict)
     assign = np.ascontiguousarray(assign, dtype=np.int32)
     new_codes = pq_encode(new, hx.codebook)
     new_ids = np.arange(n0, n0 + new.shape[0], dtype=np.int64)
-    lay = seil_insert(assign, new_codes, new_ids, nlist)
+    lay = seil_insert(assign, new_codes, new_ids, nlist, blk=BLK)
     hb = hx.codes.shape[2]
 
     o_sb, o_sc = hx.list_shared_begin.astype(np.int64), hx.list_shared_cnt.astype(np.int64)
@@ -502,7 +558,7 @@ def append_batch(hx: HostIndex, new: np.ndarray, *, lam: float = 0.5, n_cands: i
         list_ref_cnt=rc.astype(np.int32), ref_owner=ref_owner, ref_block_begin=ref_block_begin,
         ref_nblocks=ref_nblocks, raw=np.concatenate([hx.raw, new]),
         assign=np.concatenate([hx.assign, assign]), vec_codes=np.concatenate([hx.vec_codes, new_codes]),
-        params=dict(hx.params))
+        params=dict(hx.params), metric=hx.metric)
 
 
 def delete_ids(hx: HostIndex, ids_to_delete) -> HostIndex:
@@ -516,6 +572,7 @@ def delete_ids(hx: HostIndex, ids_to_delete) -> HostIndex:
     vectors, raw vectors and block numbers do not change; a deleted vector's row of `assign`
     becomes (-1, -1).
     """
+    BLK = hx.blk
     codes = hx.codes.reshape(-1, hx.codes.shape[2]).copy()
     ids = hx.ids.reshape(-1).copy()
     other = hx.other.reshape(-1).copy()
@@ -566,4 +623,4 @@ def delete_ids(hx: HostIndex, ids_to_delete) -> HostIndex:
         list_misc_cnt=misc_cnt.astype(np.int32), list_ref_begin=hx.list_ref_begin,
         list_ref_cnt=hx.list_ref_cnt, ref_owner=hx.ref_owner, ref_block_begin=hx.ref_block_begin,
         ref_nblocks=hx.ref_nblocks, raw=hx.raw, assign=assign, vec_codes=hx.vec_codes,
-        params=dict(hx.params))
+        params=dict(hx.params), metric=hx.metric)

@@ -13,12 +13,16 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 # "sift100m@5M": the 100M x 128 uint8 workload's generator, storage (uint8 raw vectors), bigK = 200 and
-# list length (about 10,000 items per list), at 5M vectors and 1024 lists so that the case fits a
-# test run; the full size is exercised by bench.py --workload sift100m, which compares a sample of
-# queries with the oracle as well.
-# ("sift1m", 23): the nprobe bench.py's bisection settles on for recall@10 >= 0.9 and times.
+# list length (about 10,000 items per list), at 5M vectors and 1024 lists; "sift100m@20M": the same
+# generator and storage with the workload's own 16,384 lists (about 2,400 items per list: several
+# blocks and parts per list on the grouping route for more than 8,192 lists).  The full 100M size is
+# exercised by bench.py --workload sift100m --parity-queries 1000, which compares the queries with
+# the oracle at every swept nprobe.
+# ("sift1m", 23) and ("gist1m", 45): the nprobe bench.py's bisection settles on for recall@10 >= 0.9
+# and times.
 CASES = [("sift1m", 23, 10000), ("sift1m", 32, 10000), ("sift1m", 1, 10000), ("sphere10m", 64, 10000),
-         ("gist1m", 16, 1000), ("sift100m@5M", 64, 300)]
+         ("gist1m", 45, 1000), ("gist1m", 64, 1000), ("sift100m@5M", 64, 300), ("sift100m@20M", 64, 500),
+         ("sift100m@20M", 256, 200)]
 _cache = {}
 
 
@@ -27,6 +31,8 @@ def _workload(name):
         _cache.clear()                                   # one large index in memory at a time
         if name == "sift100m@5M":
             w = datagen.scaled(datagen.WORKLOADS["sift100m"], 5_000_000, nq=2000, nlist=1024)
+        elif name == "sift100m@20M":
+            w = datagen.scaled(datagen.WORKLOADS["sift100m"], 20_000_000, nq=4000)
         else:
             w = datagen.WORKLOADS[name]
         base = datagen.make_base(w)

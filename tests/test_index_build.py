@@ -1,5 +1,6 @@
 """Host index construction (Alg. 1, 3, 4) against what the paper fixes about it."""
 import numpy as np
+import pytest
 
 from paper_2601_07183_amd import datagen, index_build as ib
 
@@ -109,19 +110,19 @@ def test_seil_layout_worked_example():
 
 
 def _check_layout(hx):
-    n, nlist = hx.ntotal, hx.nlist
+    n, nlist, B = hx.ntotal, hx.nlist, hx.blk
     a = hx.assign.astype(np.int64)
     key = a[:, 0] * nlist + a[:, 1]
     cells, cnt = np.unique(key, return_counts=True)
     c1, c2 = cells // nlist, cells % nlist
-    nb, nm = cnt // 32, cnt % 32
+    nb, nm = cnt // B, cnt % B
     # count conservation (Alg. 4 pass 1)
     assert (hx.list_shared_cnt == np.bincount(c1, weights=nb, minlength=nlist)).all()
     misc_items = np.bincount(c1, weights=nm, minlength=nlist) + \
         np.bincount(c2[c1 != c2], weights=nm[c1 != c2], minlength=nlist)
-    assert (hx.list_misc_cnt == (misc_items + 31) // 32).all()
+    assert (hx.list_misc_cnt == (misc_items + B - 1) // B).all()
     slots = (hx.ids >= 0).sum()
-    assert slots == (32 * nb).sum() + (np.where(c1 != c2, 2, 1) * nm).sum()
+    assert slots == (B * nb).sum() + (np.where(c1 != c2, 2, 1) * nm).sum()
     # only the last misc block of a list may be partly filled; shared blocks are full
     for L in range(nlist):
         sb, sc = hx.list_shared_begin[L], hx.list_shared_cnt[L]
@@ -133,7 +134,7 @@ def _check_layout(hx):
             assert (hx.ids[mb:mb + mc - 1] >= 0).all()
             fill = (hx.ids[mb + mc - 1] >= 0)
             assert fill[0] and (np.diff(fill.astype(int)) <= 0).all()
-            assert fill.sum() == misc_items[L] - 32 * (mc - 1)
+            assert fill.sum() == misc_items[L] - B * (mc - 1)
         # members of a shared block all belong to one cell (L, j)
         for b in range(sb, sb + sc):
             v = hx.ids[b]
@@ -150,7 +151,7 @@ def _check_layout(hx):
             assert hx.list_shared_begin[o] <= bb and bb + nbk <= hx.list_shared_begin[o] + hx.list_shared_cnt[o]
             v = hx.ids[bb:bb + nbk].ravel()
             assert (a[v, 0] == o).all() and (a[v, 1] == L).all()
-            assert nbk == cnt[(c1 == o) & (c2 == L)][0] // 32
+            assert nbk == cnt[(c1 == o) & (c2 == L)][0] // B
     # one reference entry per two-list cell with at least one full block
     assert hx.nrefs == ((c1 != c2) & (nb > 0)).sum()
     # every vector: once in a shared block, or once in the misc area of each of its lists
@@ -209,3 +210,42 @@ def test_pq_encode_is_nearest_codeword(small_index):
     chosen = np.take_along_axis(d2, got[:, :, None], 2)[:, :, 0]
     assert np.allclose(chosen, best, rtol=1e-5, atol=1e-7)
     assert (got == code).mean() > 0.999
+
+
+@pytest.mark.parametrize("blk", [16, 64])
+def test_seil_layout_with_other_block_sizes(blk):
+    # BLK_SZ of Alg. 4 is a parameter (Section 6.4 varies it): the same structural rules at 16 and 64
+    x = datagen.random_vectors(21, 2500, 8)
+    cents = ib.kmeans(x, 8, 5, 1)
+    cb = ib.train_pq(x, 4, 5, 2)
+    g = np.random.Generator(np.random.PCG64(5))
+    pairs = np.sort(g.integers(0, 8, size=(2500, 2)), axis=1).astype(np.int32)
+    hx = ib.add_vectors(x, cents, cb, assign=pairs, blk=blk)
+    assert hx.blk == blk and hx.ids.shape[1] == blk and hx.nrefs > 0
+    _check_layout(hx)
+    _check_layout(ib.add_vectors(x, cents, cb, blk=blk))
+    # a larger block stores fewer vectors once: the shared fraction shrinks with BLK_SZ
+    shared = [ib.add_vectors(x, cents, cb, assign=pairs, blk=b).list_shared_cnt.sum() * b for b in (16, 32, 64)]
+    assert shared[0] >= shared[1] >= shared[2]
+
+
+def test_soar_lambda_zero_is_second_nearest_and_prefers_orthogonal_residuals():
+    # Section 2.3 / Table 1: SOAR's loss is ||r'||^2 + lam (r.r' / ||r||)^2.  lam = 0 leaves the
+    # second-nearest list; with lam > 0 a candidate whose residual is orthogonal to the first
+    # one wins over a slightly nearer one whose residual is parallel to it.
+    x = datagen.random_vectors(41, 400, 6)
+    cents = datagen.random_vectors(42, 12, 6)
+    d2 = ((x[:, None, :].astype(np.float64) - cents[None].astype(np.float64)) ** 2).sum(-1)
+    two = np.sort(np.argsort(d2, axis=1, kind="stable")[:, :2], axis=1)
+    assert (ib.soar_assign(x, cents, lam=0.0, n_cands=12) == two).all()
+    # hand-worked: v at the origin, primary centroid at (1, 0) so r = (-1, 0); candidates
+    # c_par = (-1.1, 0) (r' = (1.1, 0): parallel, ||r'||^2 = 1.21, projection^2 = 1.21) and
+    # c_orth = (0, 1.2) (r' = (0, -1.2): orthogonal, ||r'||^2 = 1.44, projection 0)
+    v = np.zeros((1, 2), dtype=np.float32)
+    c = np.array([[1.0, 0.0], [-1.1, 0.0], [0.0, 1.2]], dtype=np.float32)
+    assert ib.soar_assign(v, c, lam=0.0, n_cands=3).tolist() == [[0, 1]]
+    assert ib.soar_assign(v, c, lam=1.0, n_cands=3).tolist() == [[0, 2]]       # 1.21 + 1.21 > 1.44
+    loss = ib.soar_loss(v, c[None], 1.0)[0]
+    assert np.allclose(loss, [1.0 + 1.0, 1.21 + 1.21, 1.44])
+    # AIR on the same picture prefers the opposite residual instead (Table 1's contrast)
+    assert ib.rair_assign(v, c, lam=0.5, n_cands=3).tolist() == [[0, 1]]

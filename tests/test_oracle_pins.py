@@ -467,3 +467,136 @@ def test_air_metric_ranks_like_the_loss_it_stands_for():
         assert order[1] - order[0] > 4 * noise             # a clear winner
         assert got.tolist() == [[0, best]]
         assert best != 1                                   # never the second nearest here: it lies on c's side
+
+
+# --- inner-product metric (Section 6.4 applies SEIL to an inner-product index) --------------------
+
+def _ip_index(seed, integer=False, n=3000, d=16, nlist=16, M=8, blk=32):
+    base = datagen.random_vectors(seed, n, d)
+    g = np.random.Generator(np.random.PCG64(seed + 99))
+    centers = g.uniform(-1, 1, size=(8, d)).astype(np.float32)
+    base = (centers[g.integers(0, 8, size=n)] + 0.25 * base).astype(np.float32)
+    if integer:
+        base = np.clip(np.rint(base * 60 + 128), 0, 255).astype(np.float32)
+    return base, ib.build_index(base, nlist, M, seed=seed, coarse_iters=8, pq_iters=8, metric="ip",
+                                lam=1.0, blk=blk)
+
+
+@pytest.mark.parametrize("d", [1, 31, 64, 65, 128, 200, 960])
+def test_ip_against_float64_and_the_stated_tree(d):
+    a = (datagen.random_vectors(d, 3, d, -3, 3) * np.float32(17.25)).astype(np.float32)
+    b = datagen.random_vectors(d + 1, 3, d, -3, 3)
+    for i in range(3):
+        want = (a[i].astype(np.float64) * b[i].astype(np.float64)).sum()
+        got = oracle.ip(a[i], b[i])
+        assert abs(got - want) <= 1e-6 * (np.abs(a[i].astype(np.float64) * b[i]).sum()) + 1e-30
+        p = np.zeros(64, dtype=np.float32)
+        for t in range(d):
+            p[t % 64] = np.float32(p[t % 64] + np.float32(a[i][t] * b[i][t]))
+        for s in (32, 16, 8, 4, 2, 1):
+            p = (p + p[np.arange(64) ^ s]).astype(np.float32)
+        assert got == float(p[0])
+    g = np.random.Generator(np.random.PCG64(4))
+    ai = g.integers(0, 256, size=128).astype(np.float32)
+    b8 = g.integers(0, 256, size=128).astype(np.uint8)
+    want = int((ai.astype(np.int64) * b8.astype(np.int64)).sum())
+    assert want < 2 ** 24 and oracle.ip(ai, b8) == want and oracle.ip(ai, b8.astype(np.float32)) == want
+
+
+def test_ip_coarse_is_the_nprobe_largest_products_then_id():
+    base, hx = _ip_index(21, integer=True)
+    q = small_queries(1, 20, hx.d, integer=True)
+    hx2 = ib.add_vectors(base, np.vstack([hx.centroids[:-1], hx.centroids[:1]]), hx.codebook, metric="ip")
+    for h in (hx, hx2):
+        o = oracle.OracleIndex(h)
+        assert o.metric == "ip"
+        prod = q.astype(np.float64) @ h.centroids.astype(np.float64).T
+        for i in range(len(q)):
+            lists, dots = oracle.coarse(o, q[i], 5)
+            assert np.allclose(dots, prod[i][lists], rtol=1e-6)
+            assert (np.diff(dots) <= 0).all()                  # reported as products, largest first
+            kth = np.sort(prod[i])[-5]
+            assert all(prod[i][l] >= kth - 1e-6 * abs(kth) for l in lists)
+    lists, dots = oracle.coarse(oracle.OracleIndex(hx2), q[0], hx.nlist)
+    pos0, posl = list(lists).index(0), list(lists).index(hx.nlist - 1)
+    assert posl == pos0 + 1 and dots[pos0] == dots[posl]       # equal product: smaller id first
+
+
+def test_ip_lut_identity_and_quantisation():
+    # the table entries selected by a code sum to minus the inner product with the decoded vector
+    base, hx = _ip_index(22)
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(2, 8, hx.d)
+    dsub = hx.d // hx.M
+    code = np.empty((hx.ntotal, hx.M), dtype=np.int64)
+    code[:, 0::2], code[:, 1::2] = hx.vec_codes & 15, hx.vec_codes >> 4
+    decoded = hx.codebook[np.arange(hx.M)[None, :], code].reshape(hx.ntotal, hx.M * dsub)
+    for i in range(len(q)):
+        T, u8, bias, scale = oracle.lut(ox, q[i])
+        est = T[np.arange(hx.M)[None, :], code[:300]].astype(np.float64).sum(1)
+        want = -(decoded[:300].astype(np.float64) @ q[i].astype(np.float64))
+        assert np.allclose(est, want, rtol=1e-5, atol=1e-5)
+        assert (u8.min(1) == 0).all() and u8.max() == 255
+        span = (T.max(1) - T.min(1)).max()
+        assert np.isclose(scale, 255.0 / span, rtol=1e-6)
+        step = (T - T.min(1, keepdims=True)).astype(np.float64) * scale
+        assert (np.abs(step - u8) <= 0.5 + 1e-3).all()
+
+
+def test_ip_brute_force_when_everything_is_probed_and_refined():
+    # integer data: every product sum is exact, ties are real and go to the smaller id
+    base, hx = _ip_index(23, integer=True, n=1500)
+    q = small_queries(9, 12, hx.d, integer=True)
+    r = oracle.search(oracle.OracleIndex(hx), q, 10, hx.nlist, hx.ntotal)
+    prod = q.astype(np.int64) @ base.astype(np.int64).T
+    order = np.lexsort((np.broadcast_to(np.arange(hx.ntotal), prod.shape), -prod), axis=1)[:, :10]
+    assert (r.ids == order).all()
+    assert (r.dists.astype(np.int64) == np.take_along_axis(prod, order, 1)).all()
+    # fewer candidates than K: padded with -1 / -inf
+    tiny = ib.add_vectors(base[:5], hx.centroids, hx.codebook, metric="ip")
+    r2 = oracle.search(oracle.OracleIndex(tiny), q[:2], 10, hx.nlist, 20)
+    assert (r2.ids[:, 5:] == -1).all() and np.isneginf(r2.dists[:, 5:]).all()
+
+
+def test_ip_seil_equals_naive_layout_with_soar_assignment():
+    base, hx = _ip_index(24)
+    assert (hx.assign[:, 0] != hx.assign[:, 1]).all() and hx.nrefs > 0
+    ox = oracle.OracleIndex(hx)
+    q = small_queries(7, 40, hx.d)
+    for nprobe in (1, 3, 7, hx.nlist):
+        a = oracle.search(ox, q, 10, nprobe, 60, layout="seil", trace=True)
+        b = oracle.search(ox, q, 10, nprobe, 60, layout="naive")
+        assert (a.cand_ids == b.cand_ids).all() and (a.cand_acc == b.cand_acc).all()
+        assert (a.ids == b.ids).all() and (a.dists == b.dists).all()
+        assert a.push_count.max() <= 1 and a.block_count.max() <= 1
+
+
+# --- other block sizes (BLK_SZ of Alg. 4; Section 6.4) -------------------------------------------
+
+@pytest.mark.parametrize("blk", [16, 64])
+def test_other_block_sizes_same_results_and_dco_identity(blk):
+    base = datagen.random_vectors(31, 4000, 16)
+    g = np.random.Generator(np.random.PCG64(130))
+    centers = g.uniform(-1, 1, size=(8, 16)).astype(np.float32)
+    base = (centers[g.integers(0, 8, size=4000)] + 0.25 * base).astype(np.float32)
+    ref = ib.build_index(base, 16, 8, seed=31, coarse_iters=8, pq_iters=8)
+    hx = ib.add_vectors(base, ref.centroids, ref.codebook, blk=blk)
+    assert (hx.assign == ref.assign).all() and hx.blk == blk
+    q = small_queries(8, 30, 16)
+    a = hx.assign.astype(np.int64)
+    cells, cnt = np.unique(a[:, 0] * hx.nlist + a[:, 1], return_counts=True)
+    c1, c2 = cells // hx.nlist, cells % hx.nlist
+    members = np.bincount(a[:, 0], minlength=hx.nlist) + np.bincount(a[:, 1][a[:, 0] != a[:, 1]], minlength=hx.nlist)
+    for nprobe in (1, 4, 9, hx.nlist):
+        r = oracle.search(oracle.OracleIndex(hx), q, 10, nprobe, 50, trace=True)
+        want = oracle.search(oracle.OracleIndex(ref), q, 10, nprobe, 50)
+        naive = oracle.search(oracle.OracleIndex(hx), q, 10, nprobe, 50, layout="naive")
+        # the block size changes the layout and the DCO, never the candidates or the results
+        assert (r.cand_ids == want.cand_ids).all() and (r.ids == want.ids).all()
+        assert (r.cand_ids == naive.cand_ids).all()
+        assert r.push_count.max() <= 1 and r.block_count.max() <= 1
+        for i in range(len(q)):
+            probed = np.zeros(hx.nlist, dtype=bool)
+            probed[r.probes[i]] = True
+            both = probed[c1] & probed[c2] & (c1 != c2)
+            assert r.dco[i] == members[probed].sum() - blk * (cnt[both] // blk).sum()
