@@ -42,6 +42,17 @@ typedef enum {
                                  small for this call; nothing was enqueued */
 } rairs_status;
 
+/*
+ * Metric of an index.  RAIRS_METRIC_L2: squared Euclidean distance (the paper's problem statement,
+ * Section 2.1).  RAIRS_METRIC_IP: inner product, the metric of the index that Section 6.4 applies
+ * SEIL to: the probed lists are the nprobe largest <q, centroid> (ties: smaller list id), a table
+ * entry is -<q_m, codeword> (quantised as for distances), candidates are the refine_k smallest
+ * (score, id) as always, and the results are the k largest exact <q, x> (ties: smaller id).
+ * Wherever a call reports "distances" it then reports inner products, largest first; missing
+ * entries are -inf.  Products are summed in the order that distances are.
+ */
+enum { RAIRS_METRIC_L2 = 0, RAIRS_METRIC_IP = 1 };
+
 /* Built limits (rejected with RAIRS_EUNSUPPORTED beyond them). */
 #define RAIRS_MAX_M        256     /* 255 * M must fit 16 bits: M <= 257 */
 #define RAIRS_MAX_REFINE_K 1024
@@ -95,6 +106,7 @@ typedef struct {
     const int64_t *ref_block_begin;  /* [nrefs] */
     const int32_t *ref_nblocks;      /* [nrefs], >= 1 */
     const void *raw;                 /* [ntotal][d] fp32 or uint8: the refine module's vectors */
+    int32_t metric;                  /* RAIRS_METRIC_L2 (0) or RAIRS_METRIC_IP */
 } rairs_host_index_t;
 
 /*
@@ -159,6 +171,25 @@ int rairs_set_workspace(rairs_index_t *h, void *d_ws, size_t bytes);
 #define RAIRS_NOALLOC_SCRATCH_BYTES (32u << 20)
 int rairs_search_noalloc(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
                          int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream);
+
+/*
+ * RairsSearch for one query at a time or a few (the one-query-at-a-time experiment of Section 6.2),
+ * captured once as a HIP graph and replayed: a small batch is bound by its fifteen kernel launches,
+ * which a graph submits as one.  rairs_graph_create runs the search once eagerly, then captures it
+ * on `hip_stream` (a stream of the caller's; not NULL) with these device pointers and parameters
+ * baked in, into a workspace that the graph owns (hipMalloc; released by rairs_graph_free).  A
+ * replay reads whatever d_queries holds when it runs and overwrites d_out_ids / d_out_dists; the
+ * caller orders its own writes and reads on the launch stream.  The captured search stays on one
+ * stream, clears what must start at zero with its own kernels and records no memset node.  nq
+ * must fit one internal pass (65,536 queries at most).  A graph must not run while another call
+ * of the same handle does, must be freed before the handle, and replays on one stream at a time.
+ */
+typedef struct rairs_graph rairs_graph_t;
+int rairs_graph_create(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
+                       int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream,
+                       rairs_graph_t **out);
+int rairs_graph_launch(rairs_graph_t *g, void *hip_stream);
+int rairs_graph_free(rairs_graph_t *g);       /* NULL is accepted */
 
 /* ---- the stages of rairs_search, callable one by one (same kernels) ----------------------- */
 
@@ -274,6 +305,7 @@ int rairs_index_bytes(const rairs_index_t *h, int64_t *code_bytes, int64_t *tota
  * candidate) or 0.. (strict == 0: both ids may be equal, the vector is then stored once).
  * Uses the handle's centroids and workspace (calls on one handle must not overlap); needs
  * 1 <= n_cands and min(n_cands, nlist) <= RAIRS_MAX_NCANDS.  n == 0 is a successful no-op.
+ * The AIR loss is a Euclidean criterion (Theorem 1): RAIRS_EUNSUPPORTED for an inner-product index.
  */
 #define RAIRS_MAX_NCANDS 32
 int rairs_assign(rairs_index_t *h, const float *d_vectors, int64_t n, int n_cands, double lambda,

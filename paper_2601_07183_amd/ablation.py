@@ -6,10 +6,16 @@ quick rate per nprobe, as a markdown table.  With --sweep it varies lambda and N
 (Figure 14's axes) and prints, per setting, the share of vectors stored twice, the blocks SEIL
 stores against two plain copies, and the cheapest nprobe that reaches the target recall with its
 DCO next to the DCO of the same probes without SEIL (every member of every probed list scored,
-Section 6.3's with/without comparison).
+Section 6.3's with/without comparison).  With --blocks it varies BLK_SZ over 16, 32 and 64 (Section
+6.4's block-size axis) for the timed index's assignment: blocks stored, vectors in shared blocks
+and the DCO at the probes that reach the target recall -- from the layout rule of Alg. 4 and the
+cost analysis of Section 5.2 (DCO = n_vec_selected - n_vec_shared); results do not depend on the
+block size, and the device path itself is built for 32 (whose DCO here is checked against the
+kernels' own count).
 
     python -m paper_2601_07183_amd.ablation --workload sift1m
     python -m paper_2601_07183_amd.ablation --workload sift1m --sweep
+    python -m paper_2601_07183_amd.ablation --workload sift1m --blocks
 """
 import argparse
 import time
@@ -73,6 +79,57 @@ def sweep(args, w, base, q, gt, centroids, codebook):
         ix.free()
 
 
+def seil_dco(assign: np.ndarray, nlist: int, probes: np.ndarray, blk: int) -> np.ndarray:
+    """DCO of every query under SEIL with `blk` items per block, from Section 5.2's cost analysis:
+    the members of the probed lists, minus the items of full blocks of cells whose two lists are
+    both probed (those blocks are stored, and scored, once)."""
+    a = np.asarray(assign, dtype=np.int64)
+    two = a[:, 0] != a[:, 1]
+    members = np.bincount(a[:, 0], minlength=nlist) + np.bincount(a[two, 1], minlength=nlist)
+    cells, cnt = np.unique(a[two, 0] * nlist + a[two, 1], return_counts=True)
+    keep = cnt >= blk
+    c1, c2, shared = cells[keep] // nlist, cells[keep] % nlist, (cnt[keep] // blk) * blk
+    out = np.empty(len(probes), dtype=np.int64)
+    for lo in range(0, len(probes), 256):
+        p = probes[lo:lo + 256]
+        probed = np.zeros((len(p), nlist), dtype=bool)
+        np.put_along_axis(probed, p, True, axis=1)
+        out[lo:lo + 256] = members[p].sum(1) - ((probed[:, c1] & probed[:, c2]) * shared[None, :]).sum(1)
+    return out
+
+
+def blocks(args, w, base, q, gt, centroids, codebook):
+    import torch
+    from . import binding, index_build as ib
+    import bench
+    dq = torch.from_numpy(q).cuda()
+    hx = ib.add_vectors(base, centroids, codebook, lam=args.lam, strict=True)
+    ix = binding.Index(hx)
+    nprobe, rec, dco32 = cheapest_nprobe(ix, dq, gt, w, args.target, bench.recall_at_k)
+    pid, _ = ix.coarse(dq, nprobe)
+    probes = pid.cpu().numpy()
+    ix.search(dq, w.k, nprobe, w.refine_k)
+    counted = ix.dco(len(q))
+    ix.free()
+    two = hx.assign[:, 0] != hx.assign[:, 1]
+    members = np.bincount(hx.assign[:, 0], minlength=w.nlist) + np.bincount(hx.assign[two, 1], minlength=w.nlist)
+    plain = float(members[probes].sum(1).mean())
+    print(f"strict AIR, lambda {args.lam}; nprobe {nprobe} reaches recall@{w.k} {rec:.4f}; DCO without SEIL {plain:,.0f}")
+    print("| BLK_SZ | blocks stored | item slots | two plain copies (slots) | vectors in shared blocks | "
+          "DCO per query | DCO saved | equals the kernels' count |")
+    print("|---|---|---|---|---|---|---|---|")
+    vec_ids = np.arange(hx.ntotal, dtype=np.int64)
+    for blk in (16, 32, 64):
+        lay = ib.seil_insert(hx.assign, hx.vec_codes, vec_ids, w.nlist, blk=blk)
+        nb = lay["ids"].shape[0]
+        shared = float(lay["list_shared_cnt"].sum()) * blk / hx.ntotal
+        plain_slots = int((((members + blk - 1) // blk) * blk).sum())
+        dco = seil_dco(hx.assign, w.nlist, probes, blk)
+        same = bool((dco == counted).all()) if blk == 32 else None
+        print(f"| {blk} | {nb:,} | {nb * blk:,} | {plain_slots:,} | {shared:.3f} | {dco.mean():,.0f} | "
+              f"{1 - dco.mean() / plain:.2%} | {'-' if same is None else same} |", flush=True)
+
+
 def main():
     import torch
     from . import binding, datagen, index_build as ib
@@ -84,6 +141,7 @@ def main():
     ap.add_argument("--lam", type=float, default=0.5)
     ap.add_argument("--nprobes", default="4,8,16,32,64")
     ap.add_argument("--sweep", action="store_true", help="vary lambda and N_CANDS instead")
+    ap.add_argument("--blocks", action="store_true", help="vary BLK_SZ over 16, 32, 64 instead")
     ap.add_argument("--target", type=float, default=0.9, help="recall the sweep searches to")
     args = ap.parse_args()
     binding.load()
@@ -96,6 +154,8 @@ def main():
     codebook = ib.train_pq(base, w.M, 25, w.seed * 7 + 2)
     if args.sweep:
         return sweep(args, w, base, q, gt, centroids, codebook)
+    if args.blocks:
+        return blocks(args, w, base, q, gt, centroids, codebook)
     near = ib.rair_assign(base, centroids, lam=0.0, n_cands=1, strict=False)       # (nearest, nearest)
     variants = [("single", dict(assign=near)),
                 ("naive RA (lambda 0)", dict(lam=0.0, strict=True)),

@@ -21,7 +21,8 @@ MAX_REFINE_K = 1024
 MAX_NPROBE = 4096
 
 EXPORTS = ("rairs_index_upload", "rairs_search", "rairs_free", "rairs_workspace_bytes", "rairs_set_workspace",
-           "rairs_search_noalloc", "rairs_coarse", "rairs_lut",
+           "rairs_search_noalloc", "rairs_graph_create", "rairs_graph_launch", "rairs_graph_free",
+           "rairs_coarse", "rairs_lut",
            "rairs_scan", "rairs_refine", "rairs_set_scan_mode", "rairs_set_profiling", "rairs_get_stage_ms",
            "rairs_get_stage_ms_mean",
            "rairs_get_dco", "rairs_get_scan_stats", "rairs_scan_kernel_name", "rairs_index_bytes", "rairs_pq_encode", "rairs_assign",
@@ -48,7 +49,7 @@ class _HostIndex(C.Structure):
         ("list_misc_begin", C.c_void_p), ("list_misc_cnt", C.c_void_p),
         ("list_ref_begin", C.c_void_p), ("list_ref_cnt", C.c_void_p),
         ("ref_owner", C.c_void_p), ("ref_block_begin", C.c_void_p), ("ref_nblocks", C.c_void_p),
-        ("raw", C.c_void_p),
+        ("raw", C.c_void_p), ("metric", C.c_int32),
     ]
 
 
@@ -112,7 +113,8 @@ def host_struct(hx):
     """ctypes view of a host index object (attributes named as in rairs_host_index_t)."""
     keep = []
     s = _HostIndex()
-    s.d, s.M, s.nbits, s.nlist, s.blk = hx.d, hx.M, 4, hx.nlist, 32
+    s.d, s.M, s.nbits, s.nlist, s.blk = hx.d, hx.M, 4, hx.nlist, int(np.shape(hx.ids)[1])
+    s.metric = {"l2": 0, "ip": 1}[getattr(hx, "metric", "l2")]
     s.ntotal, s.nblocks, s.nrefs = hx.ntotal, hx.ids.shape[0], hx.ref_owner.shape[0]
     for name, dt in _ARRAYS:
         a = np.ascontiguousarray(getattr(hx, name), dtype=dt)
@@ -125,6 +127,27 @@ def host_struct(hx):
     s.raw = raw.ctypes.data
     keep.append(raw)
     return s, keep
+
+
+class SearchGraph:
+    """A captured search (rairs_graph_create ... rairs_graph_free); keeps its tensors alive."""
+
+    def __init__(self, lib, g, tensors):
+        self._lib, self._g, self._tensors = lib, g, tensors
+
+    def launch(self, stream=None):
+        _check(self._lib.rairs_graph_launch(self._g, _stream_ptr(stream)))
+
+    def free(self):
+        if self._g:
+            _check(self._lib.rairs_graph_free(self._g))
+            self._g = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
 
 
 class Index:
@@ -210,6 +233,15 @@ class Index:
             C.c_int(nprobe), C.c_int(refine_k), _dev(out_ids, torch.int64, "out_ids"),
             _dev(out_dists, torch.float32, "out_dists"), _stream_ptr(stream)))
         return out_ids, out_dists
+
+    def graph(self, queries: torch.Tensor, k: int, nprobe: int, refine_k: int, out_ids, out_dists, stream):
+        """rairs_graph_create: returns a SearchGraph that replays this search on the given tensors."""
+        g = C.c_void_p()
+        _check(self._lib.rairs_graph_create(
+            self._h, _dev(queries, torch.float32, "queries"), C.c_int64(queries.shape[0]), C.c_int(k),
+            C.c_int(nprobe), C.c_int(refine_k), _dev(out_ids, torch.int64, "out_ids"),
+            _dev(out_dists, torch.float32, "out_dists"), _stream_ptr(stream), C.byref(g)))
+        return SearchGraph(self._lib, g, (queries, out_ids, out_dists))
 
     # --- stages ---------------------------------------------------------------------------
     def coarse(self, queries: torch.Tensor, nprobe: int, stream=None):

@@ -63,6 +63,7 @@ static int validate(const rairs_host_index_t *x)
 {
     if (!x) FAIL(RAIRS_EINVAL, "host index is NULL");
     if (x->nbits != 4) FAIL(RAIRS_EINVAL, "nbits must be 4, got %d", x->nbits);
+    if (x->metric != RAIRS_METRIC_L2 && x->metric != RAIRS_METRIC_IP) FAIL(RAIRS_EINVAL, "unknown metric %d", x->metric);
     if (x->blk != 32) FAIL(RAIRS_EINVAL, "blk must be 32, got %d", x->blk);
     if (x->d <= 0 || x->M <= 0 || x->d % x->M != 0 || (x->M & 1))
         FAIL(RAIRS_EINVAL, "need d > 0, M > 0 even, d %% M == 0 (d=%d M=%d)", x->d, x->M);
@@ -183,6 +184,7 @@ static int upload_impl(const rairs_host_index_t *x, void *hip_stream, rairs_inde
     IndexView &v = h->v;
     v.d = x->d; v.M = x->M; v.T = x->M / 2; v.nd = (v.T + 7) / 8; v.nlist = x->nlist;
     v.raw_u8 = x->raw_is_u8 ? 1 : 0;
+    v.metric = x->metric;
     v.ntotal = x->ntotal; v.nblocks = x->nblocks; v.nrefs = x->nrefs;
 
 #define UP_CHECK(call)            \
@@ -251,7 +253,8 @@ static int upload_impl(const rairs_host_index_t *x, void *hip_stream, rairs_inde
     for (int i = 0; i < x->d; i++) {
         double m = 0.0;
         for (int l = 0; l < x->nlist; l++) m += (double)x->centroids[(size_t)l * x->d + i];
-        hmean[(size_t)i] = (float)(m / x->nlist);
+        // inner products are not invariant under a common shift: no centring, and no norm term
+        hmean[(size_t)i] = x->metric == RAIRS_METRIC_IP ? 0.0f : (float)(m / x->nlist);
     }
     double nmax = 0.0;
     for (int l = 0; l < x->nlist; l++) {
@@ -261,7 +264,7 @@ static int upload_impl(const rairs_host_index_t *x, void *hip_stream, rairs_inde
             hct[(size_t)i * x->nlist + l] = c;
             n2 += (double)c * (double)c;
         }
-        hn[(size_t)l] = (float)n2;
+        hn[(size_t)l] = x->metric == RAIRS_METRIC_IP ? 0.0f : (float)n2;
         if (n2 > nmax) nmax = n2;
     }
     v.cmax2 = (float)nmax;
@@ -627,9 +630,15 @@ static int scratch_pointer(void **out)
 // Where a call's workspace comes from.  WS_HANDLE: the caller's buffer if one was set (too small:
 // RAIRS_EWORKSPACE, nothing is allocated or synchronised), else the handle's own, grown on demand.
 // WS_STATIC: the scratch array.
-enum { WS_HANDLE = 0, WS_STATIC = 1 };
+enum { WS_HANDLE = 0, WS_STATIC = 1, WS_GRAPH = 2 };
 static int acquire_ws(rairs_index *h, int source, size_t bytes, char **ws)
 {
+    if (source == WS_GRAPH) {                          // the workspace of the graph being captured
+        if (bytes > h->graph_ws_bytes) FAIL(RAIRS_EWORKSPACE, "graph workspace too small");
+        *ws = (char *)h->graph_ws;
+        h->last_ws = *ws;
+        return RAIRS_OK;
+    }
     if (source == WS_STATIC) {
         if (bytes > (size_t)RAIRS_NOALLOC_SCRATCH_BYTES)
             FAIL(RAIRS_EWORKSPACE, "this call needs %zu bytes of scratch memory, the static array has %zu",
@@ -904,14 +913,15 @@ static int search_impl(rairs_index *h, int ws_source, const float *d_queries, in
     h->last_dco = dco_all;
     h->last_dco_n = nq;
     // stage timing is only meaningful when the batch fits one pass
-    const int plevel = step == nq ? h->prof : 0;
+    const int plevel = step == nq && ws_source != WS_GRAPH ? h->prof : 0;
     const bool prof = plevel == RAIRS_PROFILE_STAGES;  // every stage; otherwise at most the scan kernel
     const bool profk = plevel != 0;
     h->prof_valid = 0;
     hipEvent_t *ev = h->ev[h->ev_count % RAIRS_EV_RING];
     // the table build depends only on the queries and the grouping only on the probe lists, so
     // both run on the handle's side stream next to the coarse quantizer and the sample bound
-    const bool overlap = h->side_ready != 0;
+    // (a captured search stays on one stream: a graph of a few queries gains nothing from the fork)
+    const bool overlap = h->side_ready != 0 && ws_source != WS_GRAPH;
     hipStream_t side = overlap ? h->side : s;
     for (int64_t q0 = 0; q0 < nq; q0 += step) {
         int64_t n = nq - q0 < step ? nq - q0 : step;
@@ -967,6 +977,104 @@ extern "C" int rairs_search_noalloc(rairs_index_t *h, const float *d_queries, in
                                     int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream)
 {
     return search_impl(h, WS_STATIC, d_queries, nq, k, nprobe, refine_k, d_out_ids, d_out_dists, hip_stream);
+}
+
+// ---- a search captured as a HIP graph ---------------------------------------------------------------
+
+struct rairs_graph {
+    rairs_index *h;
+    void *ws;
+    size_t ws_bytes;
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+extern "C" int rairs_graph_free(rairs_graph_t *g)
+{
+    if (!g) return RAIRS_OK;
+    if (g->exec) (void)hipGraphExecDestroy(g->exec);
+    if (g->graph) (void)hipGraphDestroy(g->graph);
+    if (g->ws) (void)hipFree(g->ws);
+    delete g;
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_graph_create(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
+                                  int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream,
+                                  rairs_graph_t **out)
+{
+    if (!out) FAIL(RAIRS_EINVAL, "out is NULL");
+    *out = nullptr;
+    int rc = check_common(h, nq);
+    if (rc) return rc;
+    if ((rc = check_nprobe(h, nprobe))) return rc;
+    if ((rc = check_k(k, refine_k))) return rc;
+    if (nq < 1) FAIL(RAIRS_EINVAL, "a graph needs at least one query");
+    if (!d_queries || !d_out_ids || !d_out_dists) FAIL(RAIRS_EINVAL, "null device pointer");
+    if (!hip_stream) FAIL(RAIRS_EINVAL, "capture needs a stream of the caller's, not the default stream");
+    if (pass_size(h->v, nq, nprobe, refine_k) < nq)
+        FAIL(RAIRS_EUNSUPPORTED, "nq=%lld does not fit one pass", (long long)nq);
+    rairs_graph *g = new (std::nothrow) rairs_graph();
+    if (!g) FAIL(RAIRS_ENOMEM, "out of host memory");
+    memset(g, 0, sizeof(*g));
+    g->h = h;
+    g->ws_bytes = ws_layout(h->v, nq, nq, nprobe, refine_k, h->max_parts).total;
+    hipError_t e = hipMalloc(&g->ws, g->ws_bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        delete g;
+        FAIL(RAIRS_ENOMEM, "graph workspace of %zu bytes: %s", g->ws_bytes, hipGetErrorString(e));
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    // one eager run first: kernels whose attributes are set at launch get that done outside the capture
+    h->graph_ws = g->ws;
+    h->graph_ws_bytes = g->ws_bytes;
+    rc = search_impl(h, WS_GRAPH, d_queries, nq, k, nprobe, refine_k, d_out_ids, d_out_dists, hip_stream);
+    if (rc == RAIRS_OK && hipStreamSynchronize(s) != hipSuccess) {
+        rairs_set_error("the warm-up search failed: %s", hipGetErrorString(hipGetLastError()));
+        rc = RAIRS_EHIP;
+    }
+    if (rc == RAIRS_OK) {
+        e = hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed);
+        if (e != hipSuccess) {
+            rairs_set_error("hipStreamBeginCapture failed: %s", hipGetErrorString(e));
+            rc = RAIRS_EHIP;
+        } else {
+            rc = search_impl(h, WS_GRAPH, d_queries, nq, k, nprobe, refine_k, d_out_ids, d_out_dists, hip_stream);
+            e = hipStreamEndCapture(s, &g->graph);     // always ends the capture, also after an error
+            if (rc == RAIRS_OK && e != hipSuccess) {
+                rairs_set_error("hipStreamEndCapture failed: %s", hipGetErrorString(e));
+                rc = RAIRS_EHIP;
+            }
+        }
+    }
+    h->graph_ws = nullptr;
+    h->graph_ws_bytes = 0;
+    h->last_ws = nullptr;                              // the measurement helpers read the handle's own calls only
+    h->last_pass_n = 0;
+    h->last_dco = nullptr;
+    h->last_dco_n = 0;
+    if (rc == RAIRS_OK) {
+        e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+        if (e != hipSuccess) {
+            rairs_set_error("hipGraphInstantiate failed: %s", hipGetErrorString(e));
+            rc = RAIRS_EHIP;
+        }
+    }
+    if (rc != RAIRS_OK) {
+        (void)hipGetLastError();
+        rairs_graph_free(g);
+        return rc;
+    }
+    *out = g;
+    return RAIRS_OK;
+}
+
+extern "C" int rairs_graph_launch(rairs_graph_t *g, void *hip_stream)
+{
+    if (!g || !g->exec) FAIL(RAIRS_EINVAL, "graph is NULL");
+    RAIRS_HIP(hipGraphLaunch(g->exec, (hipStream_t)hip_stream));
+    return RAIRS_OK;
 }
 
 extern "C" size_t rairs_workspace_bytes(const rairs_index_t *h, int64_t nq, int nprobe, int refine_k)
@@ -1082,6 +1190,7 @@ extern "C" int rairs_assign(rairs_index_t *h, const float *d_vectors, int64_t n,
     const int nc = n_cands < h->v.nlist ? n_cands : h->v.nlist;
     if (nc > RAIRS_MAX_NCANDS) FAIL(RAIRS_EUNSUPPORTED, "n_cands=%d above the built limit %d", nc, RAIRS_MAX_NCANDS);
     if (!(lambda == lambda)) FAIL(RAIRS_EINVAL, "lambda is not a number");
+    if (h->v.metric != RAIRS_METRIC_L2) FAIL(RAIRS_EUNSUPPORTED, "RairAssign is defined for the Euclidean metric");
     if (n == 0) return RAIRS_OK;
     if (!d_vectors || !d_pairs) FAIL(RAIRS_EINVAL, "null device pointer");
     const int64_t step = pass_size(h->v, n, nc, 1);

@@ -91,7 +91,11 @@ int rairs_launch_transpose(const float *d_in, int rows, int cols, float *d_out, 
 //
 // The result is defined by the direct form: dist(q, l) = sum_i (q_i - c_li)^2 in fp32, summed as 64
 // interleaved partial sums over the dimensions (class = dimension mod 64) folded pairwise at
-// strides 32..1; the nprobe smallest (dist, list id) win.  Two routes compute it:
+// strides 32..1; the nprobe smallest (dist, list id) win.  With the inner-product metric the score
+// of a list is -sum_i q_i c_li in the same order (the nprobe largest products win, ties to the
+// smaller list id) and everything below holds with that score in place of the distance, the
+// matrix-core form being s(q, l) = -q.c_l without centring.  Scores travel as order-preserving
+// unsigned keys (f32_key), so negative ones sort correctly.  Two routes compute it:
 //   full:      every (query, list) distance in the direct form, then a selection;
 //   shortlist: s(q, l) = |c_l|^2 - 2 q.c_l for all pairs on the fp32 matrix cores, the lists whose
 //              s is within a rounding-error margin of the nprobe-th smallest s are re-scored in the
@@ -112,9 +116,11 @@ static __device__ __forceinline__ float key_f32(uint32_t k)
     return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
 }
 
-// direct-form distance of a query to list l of the transposed centroid matrix ct[d][nlist]
+// direct-form score (squared distance, or minus the inner product) of a query to list l of the
+// transposed centroid matrix ct[d][nlist]
 static __device__ __forceinline__ float direct_l2_t(const float *__restrict__ qq,
-                                                    const float *__restrict__ ct, int d, int nlist, int l)
+                                                    const float *__restrict__ ct, int d, int nlist, int l,
+                                                    int metric)
 {
     float p[64];
 #pragma unroll
@@ -124,8 +130,9 @@ static __device__ __forceinline__ float direct_l2_t(const float *__restrict__ qq
         for (int j = 0; j < 64; j++) {
             int i = i0 + j;
             if (i < d) {
-                float diff = qq[i] - ct[(size_t)i * nlist + l];
-                float sq = diff * diff;
+                const float c = ct[(size_t)i * nlist + l];
+                float diff = qq[i] - c;
+                float sq = metric ? qq[i] * c : diff * diff;
                 p[j] = p[j] + sq;
             }
         }
@@ -135,33 +142,33 @@ static __device__ __forceinline__ float direct_l2_t(const float *__restrict__ qq
 #pragma unroll
         for (int j = 0; j < s; j++) p[j] = p[j] + p[j + s];
     }
-    return p[0];
+    return metric ? -p[0] : p[0];
 }
 
 // Full route, distances: one lane per (query, list), lists strided over the y dimension of the
 // grid.  With only_flagged set, queries whose flag is zero are left alone.
 __global__ __launch_bounds__(WG) void coarse_dist_kernel(const float *__restrict__ q,
                                                          const float *__restrict__ ct, int d,
-                                                         int nlist, float *__restrict__ dmat,
-                                                         const uint32_t *__restrict__ only_flagged)
+                                                         int nlist, uint32_t *__restrict__ dmat,
+                                                         const uint32_t *__restrict__ only_flagged,
+                                                         int metric)
 {
     const int64_t qi = blockIdx.x;
     if (only_flagged && only_flagged[qi] == 0) return;
     const float *qq = q + (size_t)qi * d;
     for (int l = blockIdx.y * WG + threadIdx.x; l < nlist; l += gridDim.y * WG)
-        dmat[(size_t)qi * nlist + l] = direct_l2_t(qq, ct, d, nlist, l);
+        dmat[(size_t)qi * nlist + l] = f32_key(direct_l2_t(qq, ct, d, nlist, l, metric));
 }
 
-// Full route, selection: the nprobe smallest (distance, list id) of a row by radix select on the
-// fp32 bit pattern (distances are >= +0, so the unsigned order of the bits is the numeric order),
-// then sorted.  One workgroup per query.
-__global__ __launch_bounds__(WG) void coarse_select_kernel(float *dmat,
+// Full route, selection: the nprobe smallest (score, list id) of a row by radix select on the
+// order-preserving keys, then sorted.  One workgroup per query.
+__global__ __launch_bounds__(WG) void coarse_select_kernel(uint32_t *dmat,
                                                            int nlist, int nprobe,
                                                            int32_t *__restrict__ probe_ids,
                                                            float *__restrict__ probe_dists,
                                                            const uint32_t *__restrict__ only_flagged,
                                                            const float *__restrict__ q,
-                                                           const float *__restrict__ ct, int d)
+                                                           const float *__restrict__ ct, int d, int metric)
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_cnt;
@@ -171,13 +178,13 @@ __global__ __launch_bounds__(WG) void coarse_select_kernel(float *dmat,
     if (only_flagged && only_flagged[blockIdx.x] == 0) return;
     if (q) {
         // the row's distances first (same arithmetic as coarse_dist_kernel), by this workgroup
-        float *drow = dmat + (size_t)blockIdx.x * nlist;
+        uint32_t *drow = dmat + (size_t)blockIdx.x * nlist;
         const float *qq = q + (size_t)blockIdx.x * d;
-        for (int l = tid; l < nlist; l += WG) drow[l] = direct_l2_t(qq, ct, d, nlist, l);
+        for (int l = tid; l < nlist; l += WG) drow[l] = f32_key(direct_l2_t(qq, ct, d, nlist, l, metric));
         __threadfence_block();
         __syncthreads();
     }
-    const uint32_t *row = (const uint32_t *)(dmat + (size_t)blockIdx.x * nlist);
+    const uint32_t *row = dmat + (size_t)blockIdx.x * nlist;
 
     uint32_t prefix = 0, mask = 0, remaining = (uint32_t)nprobe;
     for (int shift = 24; shift >= 0; shift -= 8) {
@@ -206,7 +213,7 @@ __global__ __launch_bounds__(WG) void coarse_select_kernel(float *dmat,
         mask |= 255u << shift;
         __syncthreads();
     }
-    // prefix is now the bit pattern of the nprobe-th smallest distance; `remaining` of the keys
+    // prefix is now the key of the nprobe-th smallest score; `remaining` of the keys
     // equal to it are needed, the ones with the smallest list ids.
     const uint32_t kth = prefix;
     if (tid == 0) s_cnt = 0;
@@ -245,7 +252,10 @@ __global__ __launch_bounds__(WG) void coarse_select_kernel(float *dmat,
     for (int i = tid; i < nprobe; i += WG) {
         uint64_t key = sel[i];
         probe_ids[(size_t)blockIdx.x * nprobe + i] = (int32_t)(uint32_t)key;
-        if (probe_dists) probe_dists[(size_t)blockIdx.x * nprobe + i] = __uint_as_float((uint32_t)(key >> 32));
+        if (probe_dists) {
+            const float sc = key_f32((uint32_t)(key >> 32));
+            probe_dists[(size_t)blockIdx.x * nprobe + i] = metric ? -sc : sc;    // reported: the product itself
+        }
     }
 }
 
@@ -264,7 +274,7 @@ __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict
                                                          const float *__restrict__ cmean,
                                                          const float *__restrict__ cnorm, int nlist,
                                                          int csplits, int tiles_per_split, int64_t nq,
-                                                         uint32_t *__restrict__ keys)
+                                                         uint32_t *__restrict__ keys, float alpha)
 {
     constexpr int H = D / 2;
     constexpr int PER = D * 32 / WG;                    // staged elements per thread and tile
@@ -332,7 +342,7 @@ __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict
 #pragma unroll
             for (int r = 0; r < 16; r++) {
                 const int64_t qq = q0 + 8 * (r >> 2) + 4 * k + (r & 3);
-                const float two = 2.0f * acc[r];
+                const float two = alpha * acc[r];     // alpha = 2: |c'|^2 - 2 q'.c'; alpha = 1 with zero norms: -q.c
                 if (qq < nq) keys[(size_t)qq * nlist + l] = f32_key(cn - two);
             }
         }
@@ -352,7 +362,7 @@ __global__ __launch_bounds__(WG) void coarse_gemm_chunk_kernel(const float *__re
                                                                const float *__restrict__ cmean,
                                                                const float *__restrict__ cnorm, int d,
                                                                int nlist, int ngroups, int64_t nq,
-                                                               uint32_t *__restrict__ keys)
+                                                               uint32_t *__restrict__ keys, float alpha)
 {
     __shared__ float Bs[GEMM_CD * 32];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = lane & 31, k = lane >> 5;
@@ -410,7 +420,7 @@ __global__ __launch_bounds__(WG) void coarse_gemm_chunk_kernel(const float *__re
 #pragma unroll
             for (int r = 0; r < 16; r++) {
                 const int64_t qq = q0 + 8 * (r >> 2) + 4 * k + (r & 3);
-                const float two = 2.0f * acc[t][r];
+                const float two = alpha * acc[t][r];
                 if (qq < nq) keys[(size_t)qq * nlist + l] = f32_key(cn - two);
             }
         }
@@ -445,7 +455,7 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
                                                               float cmax2, int64_t nq,
                                                               int32_t *__restrict__ probe_ids,
                                                               float *__restrict__ probe_dists,
-                                                              uint32_t *__restrict__ flags)
+                                                              uint32_t *__restrict__ flags, int metric)
 {
     __shared__ uint32_t hist_s[WG / 64][256];
     extern __shared__ __align__(16) uint64_t sel_dyn[];      // [WG / 64][cap], cap a power of two
@@ -609,17 +619,19 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
             const float qv = qq[t];
 #pragma unroll
             for (int u = 0; u < 4; u++) {
-                float diff = qv - cent[(size_t)ls[u] * d + t];
-                float sq = diff * diff;
+                const float c = cent[(size_t)ls[u] * d + t];
+                float diff = qv - c;
+                float sq = metric ? qv * c : diff * diff;
                 p[u] = p[u] + sq;
             }
         }
-        const float dist = fold_four_rows(p[0], p[1], p[2], p[3], lane);       // list lane >> 4
+        const float folded = fold_four_rows(p[0], p[1], p[2], p[3], lane);     // list lane >> 4
+        const float dist = metric ? -folded : folded;
         wave_lds_sync();                                 // all four lists were read before any entry is rewritten
         {
             const int u = lane >> 4;
             const uint32_t lu = u == 0 ? ls[0] : (u == 1 ? ls[1] : (u == 2 ? ls[2] : ls[3]));
-            if ((lane & 15) == 0 && c0 + u < nc) sel[c0 + u] = ((uint64_t)__float_as_uint(dist) << 32) | lu;
+            if ((lane & 15) == 0 && c0 + u < nc) sel[c0 + u] = ((uint64_t)f32_key(dist) << 32) | lu;
         }
         wave_lds_sync();
     }
@@ -631,7 +643,10 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
         for (int e = lane; e < nprobe; e += 64) {
             uint64_t key = sel[e];
             probe_ids[(size_t)qi * nprobe + e] = (int32_t)(uint32_t)key;
-            if (probe_dists) probe_dists[(size_t)qi * nprobe + e] = __uint_as_float((uint32_t)(key >> 32));
+            if (probe_dists) {
+                const float sc = key_f32((uint32_t)(key >> 32));
+                probe_dists[(size_t)qi * nprobe + e] = metric ? -sc : sc;
+            }
         }
 }
 
@@ -647,9 +662,9 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
     const int groups = (v.nlist + WG - 1) / WG;
     if (!coarse_shortlist_ok(v, nprobe) || !flags || ((uintptr_t)q & 15) != 0) {
         hipLaunchKernelGGL(coarse_dist_kernel, dim3((unsigned)nq, groups), dim3(WG), 0, s, q,
-                           v.centroids_t, v.d, v.nlist, dmat, nullptr);
-        hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist,
-                           nprobe, probe_ids, probe_dists, nullptr, nullptr, nullptr, 0);
+                           v.centroids_t, v.d, v.nlist, (uint32_t *)dmat, nullptr, v.metric);
+        hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, (uint32_t *)dmat, v.nlist,
+                           nprobe, probe_ids, probe_dists, nullptr, nullptr, nullptr, 0, v.metric);
         RAIRS_HIP(hipGetLastError());
         return RAIRS_OK;
     }
@@ -664,10 +679,11 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
     const int tiles_per_split = (ntiles + csplits - 1) / csplits;
     const dim3 grid(qblocks * csplits);
     uint32_t *keys = (uint32_t *)dmat;
+    const float alpha = v.metric ? 1.0f : 2.0f;
 #define GEMM_CASE(D)                                                                              \
     case D:                                                                                       \
         hipLaunchKernelGGL(coarse_gemm_kernel<D>, grid, dim3(WG), 0, s, q, v.centroids_ct, v.cmean, v.cnorm, \
-                           v.nlist, csplits, tiles_per_split, nq, keys);                          \
+                           v.nlist, csplits, tiles_per_split, nq, keys, alpha);                   \
         break
     switch (v.d) {
         GEMM_CASE(32);
@@ -681,10 +697,10 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
         const int g4 = (ntiles + 3) / 4;
         if ((int64_t)qblocks * g4 >= 512)
             hipLaunchKernelGGL(coarse_gemm_chunk_kernel<4>, dim3(qblocks * g4), dim3(WG), 0, s, q,
-                               v.centroids_ct, v.cmean, v.cnorm, v.d, v.nlist, g4, nq, keys);
+                               v.centroids_ct, v.cmean, v.cnorm, v.d, v.nlist, g4, nq, keys, alpha);
         else
             hipLaunchKernelGGL(coarse_gemm_chunk_kernel<1>, dim3(qblocks * ntiles), dim3(WG), 0, s, q,
-                               v.centroids_ct, v.cmean, v.cnorm, v.d, v.nlist, ntiles, nq, keys);
+                               v.centroids_ct, v.cmean, v.cnorm, v.d, v.nlist, ntiles, nq, keys, alpha);
     }
     }
 #undef GEMM_CASE
@@ -709,11 +725,11 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_bytes));
     hipLaunchKernelGGL(coarse_shortlist_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))),
                        dim3(WG), sel_bytes, s, keys, q, v.centroids, v.d, v.nlist,
-                       nprobe, cap, nsamp, ksamp, v.cmean, v.cmax2, nq, probe_ids, probe_dists, flags);
+                       nprobe, cap, nsamp, ksamp, v.cmean, v.cmax2, nq, probe_ids, probe_dists, flags, v.metric);
     // queries whose shortlist did not fit (many lists at nearly the same distance): full route,
     // both steps by the query's own workgroup
-    hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, dmat, v.nlist, nprobe,
-                       probe_ids, probe_dists, flags, q, v.centroids_t, v.d);
+    hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, (uint32_t *)dmat, v.nlist, nprobe,
+                       probe_ids, probe_dists, flags, q, v.centroids_t, v.d, v.metric);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
@@ -752,7 +768,7 @@ __global__ __launch_bounds__(WG) void lut_kernel(const float *__restrict__ q,
                                                  const float *__restrict__ codebook, int d, int M,
                                                  uint8_t *__restrict__ lut,
                                                  float *__restrict__ bias_sum,
-                                                 float *__restrict__ scale)
+                                                 float *__restrict__ scale, int metric)
 {
     __shared__ float Ts[RAIRS_MAX_M * 16];
     __shared__ float bias[RAIRS_MAX_M];
@@ -765,13 +781,13 @@ __global__ __launch_bounds__(WG) void lut_kernel(const float *__restrict__ q,
         int m = e >> 4;
         const float *cw = codebook + (size_t)e * dsub;
         float a = qq[m * dsub] - cw[0];
-        float acc = a * a;
+        float acc = metric ? qq[m * dsub] * cw[0] : a * a;
         for (int t = 1; t < dsub; t++) {
             float b = qq[m * dsub + t] - cw[t];
-            float sq = b * b;
+            float sq = metric ? qq[m * dsub + t] * cw[t] : b * b;
             acc = acc + sq;
         }
-        Ts[e] = acc;
+        Ts[e] = metric ? -acc : acc;                    // inner product: minus the product, smaller is better
     }
     __syncthreads();
     for (int m = tid; m < M; m += WG) {
@@ -820,7 +836,7 @@ int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lu
                      float *scale, hipStream_t s)
 {
     hipLaunchKernelGGL(lut_kernel, dim3((unsigned)nq), dim3(WG), 0, s, q, v.codebook, v.d, v.M,
-                       lut, bias_sum, scale);
+                       lut, bias_sum, scale, v.metric);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
@@ -1078,8 +1094,9 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
                     const float qv = qq[i];
 #pragma unroll
                     for (int u = 0; u < 4; u++) {
-                        float diff = qv - (float)((const uint8_t *)v.raw)[(size_t)id[u] * v.d + i];
-                        float sq = diff * diff;
+                        const float x = (float)((const uint8_t *)v.raw)[(size_t)id[u] * v.d + i];
+                        float diff = qv - x;
+                        float sq = v.metric ? qv * x : diff * diff;
                         p[u] = p[u] + sq;
                     }
                 }
@@ -1088,20 +1105,22 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
                     const float qv = qq[i];
 #pragma unroll
                     for (int u = 0; u < 4; u++) {
-                        float diff = qv - ((const float *)v.raw)[(size_t)id[u] * v.d + i];
-                        float sq = diff * diff;
+                        const float x = ((const float *)v.raw)[(size_t)id[u] * v.d + i];
+                        float diff = qv - x;
+                        float sq = v.metric ? qv * x : diff * diff;
                         p[u] = p[u] + sq;
                     }
                 }
             }
-            const float dist = fold_four_rows(p[0], p[1], p[2], p[3], lane);   // row lane >> 4
+            const float folded = fold_four_rows(p[0], p[1], p[2], p[3], lane);   // row lane >> 4
+            const float dist = v.metric ? -folded : folded;      // inner product: ordered by minus the product
             {
                 const int u = lane >> 4, c = c0 + u;
                 const bool oku = u == 0 ? ok[0] : (u == 1 ? ok[1] : (u == 2 ? ok[2] : ok[3]));
                 const int64_t idu = u == 0 ? id[0] : (u == 1 ? id[1] : (u == 2 ? id[2] : id[3]));
-                // empty: distance bits in the NaN region, id = all ones
+                // empty: all ones, above every key
                 if ((lane & 15) == 0 && c < n2)
-                    keys[c] = oku ? (((uint64_t)__float_as_uint(dist) << 32) | (uint32_t)idu) : ~0ull;
+                    keys[c] = oku ? (((uint64_t)f32_key(dist) << 32) | (uint32_t)idu) : ~0ull;
             }
         }
     }
@@ -1111,7 +1130,8 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
         const uint64_t key = keys[i];
         const bool ok = key != ~0ull;
         out_ids[(size_t)qi * k + i] = ok ? (int64_t)(uint32_t)key : -1;
-        out_dists[(size_t)qi * k + i] = ok ? __uint_as_float((uint32_t)(key >> 32)) : __builtin_inff();
+        const float sc = ok ? key_f32((uint32_t)(key >> 32)) : __builtin_inff();
+        out_dists[(size_t)qi * k + i] = v.metric ? -sc : sc;     // inner product: the product itself, missing -inf
     }
 }
 
@@ -1166,8 +1186,9 @@ __global__ __launch_bounds__(WG) void refine_wg_kernel(IndexView v, const float 
                 const float qv = qq[i];
 #pragma unroll
                 for (int u = 0; u < 4; u++) {
-                    float diff = qv - (float)((const uint8_t *)v.raw)[(size_t)id[u] * v.d + i];
-                    float sq = diff * diff;
+                    const float x = (float)((const uint8_t *)v.raw)[(size_t)id[u] * v.d + i];
+                    float diff = qv - x;
+                    float sq = v.metric ? qv * x : diff * diff;
                     p[u] = p[u] + sq;
                 }
             }
@@ -1176,20 +1197,22 @@ __global__ __launch_bounds__(WG) void refine_wg_kernel(IndexView v, const float 
                 const float qv = qq[i];
 #pragma unroll
                 for (int u = 0; u < 4; u++) {
-                    float diff = qv - ((const float *)v.raw)[(size_t)id[u] * v.d + i];
-                    float sq = diff * diff;
+                    const float x = ((const float *)v.raw)[(size_t)id[u] * v.d + i];
+                    float diff = qv - x;
+                    float sq = v.metric ? qv * x : diff * diff;
                     p[u] = p[u] + sq;
                 }
             }
         }
-        const float dist = fold_four_rows(p[0], p[1], p[2], p[3], lane);       // row lane >> 4
+        const float folded = fold_four_rows(p[0], p[1], p[2], p[3], lane);     // row lane >> 4
+        const float dist = v.metric ? -folded : folded;
         {
             const int u = lane >> 4, c = c0 + u * (WG / 64);
             const bool oku = u == 0 ? ok[0] : (u == 1 ? ok[1] : (u == 2 ? ok[2] : ok[3]));
             const int64_t idu = u == 0 ? id[0] : (u == 1 ? id[1] : (u == 2 ? id[2] : id[3]));
             // empty: distance bits in the NaN region, id = all ones
             if ((lane & 15) == 0 && c < n2)
-                keys[c] = oku ? (((uint64_t)__float_as_uint(dist) << 32) | (uint32_t)idu) : ~0ull;
+                keys[c] = oku ? (((uint64_t)f32_key(dist) << 32) | (uint32_t)idu) : ~0ull;
         }
     }
     }
@@ -1199,7 +1222,8 @@ __global__ __launch_bounds__(WG) void refine_wg_kernel(IndexView v, const float 
         uint64_t key = keys[i];
         bool ok = key != ~0ull;
         out_ids[(size_t)qi * k + i] = ok ? (int64_t)(uint32_t)key : -1;
-        out_dists[(size_t)qi * k + i] = ok ? __uint_as_float((uint32_t)(key >> 32)) : __builtin_inff();
+        const float sc = ok ? key_f32((uint32_t)(key >> 32)) : __builtin_inff();
+        out_dists[(size_t)qi * k + i] = v.metric ? -sc : sc;
     }
 }
 

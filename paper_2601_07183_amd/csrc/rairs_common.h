@@ -49,6 +49,7 @@ struct RefEntry {
 // Device view handed to kernels by value.
 struct IndexView {
     int32_t d, M, T, nd, nlist, raw_u8;   // T = M / 2 nibbles per parity, nd = ceil(T / 8) dwords
+    int32_t metric;                       // RAIRS_METRIC_L2 or RAIRS_METRIC_IP
     int64_t ntotal, nblocks, nrefs;
     const float *centroids;       // [nlist][d]
     const float *centroids_t;     // [d][nlist]
@@ -92,6 +93,8 @@ struct rairs_index {
     size_t ws_bytes;
     void *ws_user;
     size_t ws_user_bytes;
+    void *graph_ws;               // workspace of the graph being captured (rairs_graph_create only)
+    size_t graph_ws_bytes;
     char *last_ws;                // workspace of the last call (for the measurement helpers)
     int64_t *last_dco;            // DCO counts of the last rairs_search, inside that workspace
     int64_t last_dco_n;

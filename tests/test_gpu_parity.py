@@ -347,6 +347,105 @@ def test_batch_larger_than_one_internal_pass(binding):
         ix.free()
 
 
+@pytest.mark.parametrize("d,M,integer", [(16, 8, False), (128, 64, True), (96, 48, False), (32, 16, True)])
+def test_inner_product_metric_with_soar_assignment(binding, d, M, integer):
+    # Section 6.4's variant: an inner-product index whose second lists come from SOAR, in the same
+    # SEIL layout and through the same kernels; probe ids, tables, candidates, ids and DCO bit-exact,
+    # inner products within the distance bar (on integer data they are exact and ties are real)
+    g = np.random.Generator(np.random.PCG64(5 * d + M))
+    centers = g.uniform(-1, 1, size=(10, d)).astype(np.float32)
+    pick = lambda n: (centers[g.integers(0, 10, size=n)] + 0.3 * g.standard_normal((n, d))).astype(np.float32)
+    base, q = pick(5000), pick(53)
+    if integer:
+        base, q = (np.clip(np.rint(x * 60 + 128), 0, 255).astype(np.float32) for x in (base, q))
+    hx = ib.build_index(base, 24, M, seed=8, coarse_iters=5, pq_iters=5, metric="ip", lam=1.0)
+    assert hx.metric == "ip" and hx.nrefs > 0
+    for nprobe, refine_k, k in ((1, 60, 10), (5, 100, 10), (24, 200, 20)):
+        want = _compare_all_stages(binding, hx, q, k, nprobe, refine_k)
+        assert (np.diff(want.dists, axis=1) <= 0).all()              # largest product first
+    if integer:
+        prod = q.astype(np.int64) @ base.astype(np.int64).T
+        assert (want.dists.astype(np.int64) == np.take_along_axis(prod, want.ids, 1)).all()
+    # nearly coincident and duplicated centroids: the shortlist's fallback under this metric
+    cents = hx.centroids.copy()
+    cents[1::3] = cents[0::3][:len(cents[1::3])]
+    hx2 = ib.add_vectors(base, cents, hx.codebook, metric="ip", assign=hx.assign)
+    _compare_all_stages(binding, hx2, q, 10, 7, 100)
+    # RairAssign is a Euclidean criterion
+    ix = binding.Index(hx)
+    try:
+        with pytest.raises(binding.RairsError) as e:
+            ix.assign(_dev(base[:10]), 10, 0.5, True)
+        assert e.value.code == -4
+    finally:
+        ix.free()
+
+
+def test_inner_product_coarse_routes(binding):
+    # 1,100 lists and d = 128: the matrix-core shortlist with its sampled threshold; d = 5: the
+    # full direct-form route; negative and positive products
+    for d, nlist in ((128, 1100), (5, 70), (64, 203)):
+        g = np.random.Generator(np.random.PCG64(300 + d))
+        x = datagen.random_vectors(70 + d, 600, d)
+        q = datagen.random_vectors(71 + d, 41, d)
+        cents = datagen.random_vectors(72 + d, nlist, d)
+        Mq = 2 if d == 5 else d // 2
+        if d == 5:
+            x, q, cents = (np.pad(a, ((0, 0), (0, 1))) for a in (x, q, cents))     # 6 dimensions, M = 2
+        cb = ib.train_pq(x, Mq, 2, 2)
+        asg = np.sort(g.integers(0, nlist, size=(len(x), 2)), axis=1).astype(np.int32)
+        hx = ib.add_vectors(x, np.ascontiguousarray(cents), cb, assign=asg, metric="ip")
+        ox = oracle.OracleIndex(hx)
+        ix = binding.Index(hx)
+        try:
+            for nprobe in (1, 9, nlist // 8, nlist):
+                print(f"case: ip coarse d={hx.d} nlist={nlist} nprobe={nprobe}", flush=True)
+                pid, pdot = ix.coarse(_dev(q), nprobe)
+                torch.cuda.synchronize()
+                for i in range(len(q)):
+                    oi, od = oracle.coarse(ox, q[i], nprobe)
+                    assert (pid[i].cpu().numpy() == oi).all()
+                    assert (pdot[i].cpu().numpy() == od.astype(np.float32)).all()
+        finally:
+            ix.free()
+
+
+@pytest.mark.parametrize("nq", [1, 7])
+def test_search_graph_replays(binding, tiny_workload, nq):
+    # a captured search replayed several times on new queries, with eager searches and
+    # synchronisations of the same handle in between: every replay must equal the eager result
+    w, base, q, hx = tiny_workload
+    want = oracle.search(oracle.OracleIndex(hx), q, w.k, 16, w.refine_k)
+    ix = binding.Index(hx)
+    try:
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            dq = torch.zeros((nq, hx.d), dtype=torch.float32, device="cuda")
+            ids = torch.full((nq, w.k), -7, dtype=torch.int64, device="cuda")
+            dists = torch.zeros((nq, w.k), dtype=torch.float32, device="cuda")
+            dq.copy_(_dev(q[:nq]))
+            stream.synchronize()
+            g = ix.graph(dq, w.k, 16, w.refine_k, ids, dists, stream)
+            for rep in range(5):
+                lo = (rep * nq) % (len(q) - nq)
+                dq.copy_(_dev(q[lo:lo + nq]))
+                ids.fill_(-7)
+                g.launch(stream)
+                stream.synchronize()
+                assert (ids.cpu().numpy() == want.ids[lo:lo + nq]).all(), rep
+                _assert_dists(dists.cpu().numpy(), want.dists[lo:lo + nq])
+                # eager work of the same handle between replays (its own workspace)
+                e_ids, _ = ix.search(_dev(q[:50]), w.k, 4 + rep, w.refine_k, stream=stream)
+                stream.synchronize()
+                assert e_ids.shape == (50, w.k)
+            g.free()
+            g.free()                                         # second free is a no-op
+        with pytest.raises(binding.RairsError):
+            ix.graph(dq, w.k, 16, w.refine_k, ids, dists, torch.cuda.default_stream())
+    finally:
+        ix.free()
+
+
 def test_caller_owned_workspace(binding, tiny_workload):
     # rairs_workspace_bytes / rairs_set_workspace through the C ABI: a torch tensor serves as the
     # workspace; one byte too few is RAIRS_EWORKSPACE and enqueues nothing; the library's own

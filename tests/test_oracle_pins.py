@@ -600,3 +600,17 @@ def test_other_block_sizes_same_results_and_dco_identity(blk):
             probed[r.probes[i]] = True
             both = probed[c1] & probed[c2] & (c1 != c2)
             assert r.dco[i] == members[probed].sum() - blk * (cnt[both] // blk).sum()
+
+
+@pytest.mark.parametrize("blk", [16, 32, 64])
+def test_ablation_dco_formula_equals_the_oracles_count(blk):
+    # the block-size table of the ablation takes its DCO from Section 5.2's cost analysis; the
+    # oracle counts the same number by scoring
+    from paper_2601_07183_amd import ablation
+    base = datagen.random_vectors(31, 4000, 16)
+    ref = ib.build_index(base, 16, 8, seed=31, coarse_iters=4, pq_iters=4)
+    hx = ib.add_vectors(base, ref.centroids, ref.codebook, blk=blk, strict=(blk != 64))
+    q = datagen.random_vectors(32, 30, 16)
+    for nprobe in (1, 5, 16):
+        r = oracle.search(oracle.OracleIndex(hx), q, 10, nprobe, 50)
+        assert (ablation.seil_dco(hx.assign, 16, r.probes, blk) == r.dco).all()
