@@ -278,9 +278,11 @@ int rairs_get_stage_ms_mean(rairs_index_t *h, int last_n, float *ms);
 int rairs_get_dco(rairs_index_t *h, int64_t *dco, int64_t nq);
 
 /*
- * Counters of the last rairs_search / rairs_scan pass (host array of 4): queries redone by the
- * exact kernel after their survivor buffer overflowed; sum, maximum of survivors per query; number
- * of queries in the pass.  Synchronises the device.  Zeros when the exact kernel ran alone.
+ * Counters of the last rairs_search / rairs_scan pass (host array of 5): queries redone by the
+ * exact kernel after their survivor buffer overflowed; sum, maximum of survivors per query (the
+ * logged pairs that are within the query's final bound); number of queries in the pass; pairs the
+ * scan logged in all (the ratio to the survivors says how early the bounds tightened).
+ * Synchronises the device.  Zeros when the exact kernel ran alone.
  */
 int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats);
 

@@ -323,10 +323,10 @@ class Index:
         return out
 
     def scan_stats(self) -> dict:
-        st = (C.c_int64 * 4)()
+        st = (C.c_int64 * 5)()
         _check(self._lib.rairs_get_scan_stats(self._h, st))
         return dict(redone=int(st[0]), survivors=int(st[1]), max_survivors=int(st[2]),
-                    queries=int(st[3]))
+                    queries=int(st[3]), logged=int(st[4]))
 
     def scan_kernel_name(self) -> str:
         return self._lib.rairs_scan_kernel_name(self._h).decode()

@@ -519,7 +519,7 @@ static int log_per_query_for(int refine_k)
 
 struct WsLayout {
     size_t dmat, cflags, probe_ids, probe_dists, bitmap, lut, cand, dco;
-    size_t lcount, loff, lcursor, toff, unit_list, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, total;
+    size_t lcount, loff, lcursor, toff, unit_list, unit_rec, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, total;
     size_t s_off, s_toff, s_q, s_tiles, s_scores;      // matrix-core sample (0 bytes when not used)
     int sample_blocks;
     int log_chunks;
@@ -578,6 +578,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int64_t nq_total, int 
     w.toff = take((size_t)(v.nlist + 1) * 4);
     w.next_task = take(4);
     w.unit_list = take(((size_t)nq * nprobe / 32 + (size_t)v.nlist) * (size_t)max_parts * 4);   // max_parts = most parts in a list
+    w.unit_rec = take(((size_t)nq * nprobe / 32 + (size_t)v.nlist) * (size_t)max_parts * 32);
     w.qlist = take((size_t)nq * nprobe * 4);
     w.tau = take((size_t)nq * 4);
     w.bound = take((size_t)nq * 4);
@@ -791,6 +792,7 @@ static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t 
     ma.lcount = (int32_t *)(ws + w.lcount); ma.loff = (int32_t *)(ws + w.loff);
     ma.lcursor = (int32_t *)(ws + w.lcursor); ma.toff = (int32_t *)(ws + w.toff);
     ma.unit_list = (int32_t *)(ws + w.unit_list);
+    ma.unit_rec = (int32_t *)(ws + w.unit_rec);
     {
         // parts per unit: large units save table reloads, small ones keep 2048 waves busy and the
         // tail of the kernel short
@@ -808,6 +810,7 @@ static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t 
     ma.flags = (uint32_t *)(ws + w.flags); ma.cand_ids = cand_ids; ma.cand_score = cand_score;
     ma.hist = (uint32_t *)(ws + w.hist);
     h->last_pass_n = n; h->last_flags_off = w.flags; h->last_cnt_off = w.surv_cnt;
+    h->last_fill_off = w.chunk_fill; h->last_log_chunks = w.log_chunks;
     ma.log = (uint2 *)(ws + w.log); ma.chunk_fill = (uint32_t *)(ws + w.chunk_fill);
     ma.log_cursor = (uint32_t *)(ws + w.log_misc); ma.log_overflow = ma.log_cursor + 1;
     ma.log_chunks = w.log_chunks;
@@ -1166,7 +1169,7 @@ extern "C" int rairs_get_stage_ms_mean(rairs_index_t *h, int last_n, float *ms)
 extern "C" int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats)
 {
     if (!h || !stats) FAIL(RAIRS_EINVAL, "null argument");
-    stats[0] = stats[1] = stats[2] = 0;
+    stats[0] = stats[1] = stats[2] = stats[4] = 0;
     stats[3] = h->last_pass_n;
     if (h->last_pass_n == 0 || !h->last_ws) return RAIRS_OK;
     std::vector<uint32_t> flags((size_t)h->last_pass_n), cnt((size_t)h->last_pass_n);
@@ -1178,6 +1181,9 @@ extern "C" int rairs_get_scan_stats(rairs_index_t *h, int64_t *stats)
         stats[1] += cnt[i];
         if ((int64_t)cnt[i] > stats[2]) stats[2] = cnt[i];
     }
+    std::vector<uint32_t> fill((size_t)h->last_log_chunks);
+    RAIRS_HIP(hipMemcpy(fill.data(), (char *)h->last_ws + h->last_fill_off, fill.size() * 4, hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < fill.size(); i++) stats[4] += fill[i];
     return RAIRS_OK;
 }
 

@@ -27,7 +27,9 @@ struct ListEntry {
 
 // A run of at most RAIRS_SEG_BLOCKS consecutive blocks that one wave scores for one query tile.
 #define RAIRS_SEG_BLOCKS 16
+#ifndef RAIRS_PART_BLOCKS
 #define RAIRS_PART_BLOCKS 32
+#endif
 #define RAIRS_PART_SEGS 8
 struct SegEntry {
     int32_t blk_begin;
@@ -101,7 +103,8 @@ struct rairs_index {
     // profiling
     int force_exact;
     int64_t last_pass_n;          // queries of the last MFMA pass (0: none)
-    size_t last_flags_off, last_cnt_off;
+    size_t last_flags_off, last_cnt_off, last_fill_off;
+    int last_log_chunks;
     int prof, prof_valid;
     float stage_ms[RAIRS_NSTAGES];
     // stage events of the last RAIRS_EV_RING profiled searches (slot = search number mod ring)
@@ -192,6 +195,7 @@ struct MfmaScanArgs {
     int32_t *qlist;               // [nq * nprobe] query ids grouped by list
     int32_t *toff;                // [nlist+1] exclusive prefix of work units per list
     int32_t *unit_list;           // [units] list of every work unit
+    int32_t *unit_rec;            // [units][8] {list, tile, first segment, end segment, first query of the list in qlist, its queries, 0, 0}
     int unit_parts;               // parts per unit, 1..4
     uint32_t *next_task;          // [1]
     const int32_t *tau;           // [nq] bound from the sample (0xFFFF: none); fixes the histogram range

@@ -83,11 +83,30 @@ static __device__ __forceinline__ int units_of(int nqueries, int part_cnt, int u
     return ((nqueries + 31) >> 5) * ((part_cnt + unit_parts - 1) / unit_parts);
 }
 
+// Everything a scanning wave needs to start on unit `u` of list L in one look-up, so that it does
+// not walk unit -> list -> directory entry -> parts at the head of every unit: the list, the tile,
+// the unit's segments [seg0, seg1) as absolute segment numbers, and where the list's queries are.
+#define UNIT_REC_WORDS 8
+static __device__ __forceinline__ void write_unit_rec(const IndexView &v, int32_t *unit_rec, int u, int L,
+                                                      int first_unit_of_list, int qbase, int qn, int unit_parts)
+{
+    const ListEntry le = v.lists[L];
+    const int rem = u - first_unit_of_list;
+    const int runs = (le.part_cnt + unit_parts - 1) / unit_parts;
+    const int tile = rem / runs;
+    const int p0 = (rem % runs) * unit_parts;
+    const int p1 = p0 + unit_parts < le.part_cnt ? p0 + unit_parts : le.part_cnt;
+    int4 lo = make_int4(L, tile, v.parts[le.part_begin + p0], v.parts[le.part_begin + p1]);
+    int4 hi = make_int4(qbase, qn, 0, 0);
+    *(int4 *)(unit_rec + (size_t)u * UNIT_REC_WORDS) = lo;
+    *(int4 *)(unit_rec + (size_t)u * UNIT_REC_WORDS + 4) = hi;
+}
+
 __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
                                                          const int32_t *__restrict__ lcount,
                                                          int32_t *loff, int32_t *lcursor,
                                                          int32_t *toff, int32_t *unit_list,
-                                                         int unit_parts)
+                                                         int unit_parts, int32_t *unit_rec)
 {
     __shared__ int sc[1024], st[1024];
     // one workgroup on the critical path of the grouping, usually next to a kernel that fills the
@@ -121,7 +140,10 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
         toff[L] = tb;
         lcursor[L] = 0;
         const int nu = units_of(n, v.lists[L].part_cnt, unit_parts);
-        for (int u = 0; u < nu; u++) unit_list[tb + u] = L;
+        for (int u = 0; u < nu; u++) {
+            unit_list[tb + u] = L;
+            write_unit_rec(v, unit_rec, tb + u, L, tb, cb, n, unit_parts);
+        }
         cb += n;
         tb += nu;
     }
@@ -212,7 +234,7 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(IndexView v, const int
                                                           const int32_t *__restrict__ lcount,
                                                           int32_t *loff, int32_t *lcursor, int32_t *qlist,
                                                           int qb, int32_t *toff, int32_t *unit_list,
-                                                          int unit_parts)
+                                                          int unit_parts, int32_t *unit_rec)
 {
     extern __shared__ int32_t lm_lds[];                // [nlist] ranks / run starts, [nlist + 1] offsets
     __shared__ int32_t wsum[4], total;
@@ -264,6 +286,7 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(IndexView v, const int
                 if (toff_s[mid] <= e) a0 = mid; else b0 = mid - 1;
             }
             unit_list[e] = a0;
+            write_unit_rec(v, unit_rec, e, a0, toff_s[a0], loff_s[a0], lcount[a0], unit_parts);
         }
         return;
     }
@@ -511,28 +534,24 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         nstaged = 0;                                                    \
     } while (0)
 
-    uint32_t u = gwave;
+    // A wave works on unit u, already knows the one after it (u_next) and asks the counter for
+    // the one after that: so the record of the next unit can be fetched a whole unit ahead and a
+    // unit starts with its list, tile and segments in registers instead of a chain of look-ups.
+    uint32_t u = gwave, u_next = gwave + nwaves;       // the counter starts behind both
+    int rec = u < nunits ? a.unit_rec[(size_t)u * UNIT_REC_WORDS + (lane & 7)] : 0;
     while (u < nunits) {                               // every wave leaves: the counter only grows
-        // ask for the unit after this one now; the answer is not needed before this one is done
-        uint32_t u_next = 0;
-        if (lane == 0) u_next = atomicAdd(a.next_task, 1u);
-        const int L = __builtin_amdgcn_readfirstlane(a.unit_list[u]);
-        const ListEntry le = v.lists[L];
-        const int rem = (int)u - __builtin_amdgcn_readfirstlane(a.toff[L]);
-        const int runs = (le.part_cnt + a.unit_parts - 1) / a.unit_parts;
-        const int tile = __builtin_amdgcn_readfirstlane(rem / runs);
-        const int p0 = __builtin_amdgcn_readfirstlane((rem % runs) * a.unit_parts);
-        const int p1 = p0 + a.unit_parts < le.part_cnt ? p0 + a.unit_parts : le.part_cnt;
-        // the run's segments, as offsets into the list's segment table
-        const int seg0 = __builtin_amdgcn_readfirstlane(v.parts[le.part_begin + p0]) - le.seg_begin;
-        const int seg1 = __builtin_amdgcn_readfirstlane(v.parts[le.part_begin + p1]) - le.seg_begin;
+        uint32_t u_next2 = 0;
+        if (lane == 0) u_next2 = atomicAdd(a.next_task, 1u);
+        const int tile = __builtin_amdgcn_readlane(rec, 1);
+        const int seg0 = __builtin_amdgcn_readlane(rec, 2), seg1 = __builtin_amdgcn_readlane(rec, 3);
+        const int qbase = __builtin_amdgcn_readlane(rec, 4), qn = __builtin_amdgcn_readlane(rec, 5);
+        rec = a.unit_rec[(size_t)(u_next < nunits ? u_next : u) * UNIT_REC_WORDS + (lane & 7)];
         int qid;
         uint32_t hmul;
         {
             // the tile: query of this lane's column and its tables
-            const int base = a.loff[L], n = a.loff[L + 1] - base;
             const int qi = tile * 32 + j;
-            qid = qi < n ? a.qlist[base + qi] : -1;
+            qid = qi < qn ? a.qlist[qbase + qi] : -1;
             hmul = hist_mul(qid >= 0 ? (uint32_t)a.tau[qid] : 0u);
             // instruction t takes sub-quantizers 4t .. 4t+3; this lane's half of its 64 positions
             // is the 16 + 16 table entries of sub-quantizers 4t + 2g and 4t + 2g + 1
@@ -558,8 +577,8 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         int bound_next = __hip_atomic_load(a.bound + q0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         // segment entries run two ahead and the owner's bitmap word one ahead, so that neither
         // is waited for at the head of a segment
-        SegEntry se = v.segs[le.seg_begin + seg0];
-        SegEntry sen = v.segs[le.seg_begin + (seg0 + 1 < seg1 ? seg0 + 1 : seg0)];
+        SegEntry se = v.segs[seg0];
+        SegEntry sen = v.segs[seg0 + 1 < seg1 ? seg0 + 1 : seg0];
         uint32_t owner_bits = a.bitmap[bm0 + (uint32_t)(se.owner >= 0 ? se.owner >> 5 : 0)];
         const uint32_t *cp = v.codes + (size_t)se.blk_begin * ND * 64;      // wave-uniform
         uint32_t cn[ND];
@@ -570,7 +589,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         uint32_t scored = 0;                           // items this lane's query was scored against in this unit
         for (int seg = seg0; seg < seg1; seg++) {
             const bool has_next = seg + 1 < seg1;
-            const SegEntry sen2 = v.segs[le.seg_begin + (seg + 2 < seg1 ? seg + 2 : seg1 - 1)];
+            const SegEntry sen2 = v.segs[seg + 2 < seg1 ? seg + 2 : seg1 - 1];
             const uint32_t ob_next = a.bitmap[bm0 + (uint32_t)(sen.owner >= 0 ? sen.owner >> 5 : 0)];
             const uint32_t *cpn = v.codes + (size_t)sen.blk_begin * ND * 64;   // wave-uniform
             // cell (owner, L) is scored through list `owner` for queries that probe it
@@ -684,7 +703,8 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         // do not sit on survivors for long: their histogram counts tighten everyone's bound
         if (nstaged >= 32) FLUSH_STAGE();
         if (a.dco && g == 0 && scored) atomicAdd(&a.dco[qid], (unsigned long long)scored);
-        u = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_next);
+        u = u_next;
+        u_next = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_next2);
     }
     if (nstaged > 0) FLUSH_STAGE();
     if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
@@ -1396,7 +1416,7 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
     nz = nz > a.log_chunks ? nz : a.log_chunks;
     hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
                        a.lcursor, v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
-                       a.log_cursor, a.log_overflow, reg_tables ? nwaves : gridx, 2 * nwaves, a.dco);
+                       a.log_cursor, a.log_overflow, reg_tables ? 2 * nwaves : gridx, 2 * nwaves, a.dco);
     const bool lds_group = v.nlist <= LM_LDS_NLIST;
     const int qb = LM_PAIRS / np > 0 ? LM_PAIRS / np : 1;
     const unsigned lgrid = (unsigned)((a.nq + qb - 1) / qb);
@@ -1413,10 +1433,10 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(lm_fill_lds_kernel, dim3(lgrid + LM_UNIT_WGS), dim3(256), lds, s, v, a.probe_ids, a.nq,
                            a.nprobe, a.p_first, a.lcount, a.loff, a.lcursor, a.qlist, qb, a.toff,
-                           a.unit_list, a.unit_parts);
+                           a.unit_list, a.unit_parts, a.unit_rec);
     } else {
         hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
-                           a.toff, a.unit_list, a.unit_parts);
+                           a.toff, a.unit_list, a.unit_parts, a.unit_rec);
         hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist);
     }
