@@ -309,6 +309,12 @@ def main():
     ap.add_argument("--k", type=int, default=0, help="override K of the workload (second workloads: K = 1, 100)")
     ap.add_argument("--refine-k", type=int, default=0, help="override bigK = K * K_FACTOR")
     ap.add_argument("--nq", type=int, default=0, help="queries per step (default: the workload's batch)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the same search captured once as a HIP graph and replayed "
+                         "(the mode for one query at a time: --nq 1)")
+    ap.add_argument("--index-cache", default="",
+                    help="directory to keep the built index and the ground truth in, and to read "
+                         "them from when they are there (repeated profiling runs on one machine)")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="only run a device-to-device copy of this many bytes three times (to "
                          "calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -369,14 +375,26 @@ def main():
     log(f"[bench] workload {w.name}: base {base.shape} {base.dtype}, queries {queries.shape} "
         f"({time.time() - t0:.1f}s)")
     t0 = time.time()
-    hx = index_build.build_index(base, w.nlist, w.M, seed=w.seed)
-    shared_frac = float(hx.list_shared_cnt.sum()) * 32 / hx.ntotal
-    log(f"[bench] index built in {time.time() - t0:.1f}s: nblocks={hx.nblocks} nrefs={hx.nrefs} "
-        f"vectors in shared blocks={shared_frac:.3f}")
-    t0 = time.time()
     nrec = min(len(queries), args.recall_queries) if args.recall_queries else len(queries)
-    gt = ground_truth(base, queries[:nrec], w.k)
-    log(f"[bench] ground truth for {nrec} queries in {time.time() - t0:.1f}s")
+    cache = None
+    if args.index_cache:
+        os.makedirs(args.index_cache, exist_ok=True)
+        cache = os.path.join(args.index_cache, f"{w.name}_{len(base)}_{w.nlist}_{w.M}_{w.k}_{nrec}")
+    if cache and os.path.exists(cache + ".index.npz") and os.path.exists(cache + ".gt.npy"):
+        hx = index_build.load_index(cache + ".index.npz")
+        gt = np.load(cache + ".gt.npy")
+        log(f"[bench] index and ground truth read from {cache}.* in {time.time() - t0:.1f}s")
+    else:
+        hx = index_build.build_index(base, w.nlist, w.M, seed=w.seed)
+        log(f"[bench] index built in {time.time() - t0:.1f}s")
+        t0 = time.time()
+        gt = ground_truth(base, queries[:nrec], w.k)
+        log(f"[bench] ground truth for {nrec} queries in {time.time() - t0:.1f}s")
+        if cache:
+            index_build.save_index(hx, cache + ".index.npz")
+            np.save(cache + ".gt.npy", gt)
+    shared_frac = float(hx.list_shared_cnt.sum()) * 32 / hx.ntotal
+    log(f"[bench] index: nblocks={hx.nblocks} nrefs={hx.nrefs} vectors in shared blocks={shared_frac:.3f}")
 
     ix = binding.Index(hx)
     code_bytes, total_bytes = ix.bytes()
@@ -479,6 +497,28 @@ def main():
     sec_plain, _ = run(chosen, args.steps, profile=False)
     ix.set_profiling(binding.PROFILE_STAGES)
     dco = ix.dco(nq)
+    graph_ms = None
+    if args.graph:
+        # the same search recorded once as a HIP graph (its own workspace and stream order) and
+        # replayed: one launch per step instead of some fifteen
+        ix.set_profiling(False)
+        g_ids, g_d = torch.empty_like(out_ids), torch.empty_like(out_d)
+        gs = torch.cuda.Stream()                        # default priority
+        with torch.cuda.stream(gs):
+            graph = ix.graph(dq, w.k, chosen, w.refine_k, g_ids, g_d, gs)
+            for _ in range(args.warmup):
+                graph.launch(gs)
+            gs.synchronize()
+            t = time.perf_counter()
+            for _ in range(args.steps):
+                graph.launch(gs)
+            gs.synchronize()
+            graph_ms = (time.perf_counter() - t) / args.steps * 1e3
+        same_graph = bool(torch.equal(g_ids, out_ids))
+        log(f"[bench] HIP graph replay: {graph_ms:.4f} ms/step against {sec_plain / args.steps * 1e3:.4f} eager; "
+            f"ids identical to the eager search: {same_graph}")
+        assert same_graph, "the graph's results differ from the eager search"
+        graph.free()
     scan_bytes = float(dco.sum()) * (w.M // 2)         # algorithmic: M/2 code bytes per item scored
     scan_gbs = scan_bytes / (stage_all["scan"] * 1e-3) / 1e9
     log(f"[bench] nprobe={chosen} recall@10={rec_chosen} {qps:.0f} QPS, {ms_per_step:.3f} ms/step, "
@@ -546,6 +586,7 @@ def main():
             "dco_per_query": float(dco.mean()), "index_code_bytes": code_bytes,
             "index_total_bytes": total_bytes, "vectors_in_shared_blocks": round(shared_frac, 4),
             "workspace_bytes": ix.workspace_bytes(nq, chosen, w.refine_k),
+            "ms_per_step_hip_graph": None if graph_ms is None else round(graph_ms, 4),
             "ids_identical_to_oracle_on_sample": same,
             "scan_stage_algorithmic_GBs": round(scan_gbs, 1),
         },

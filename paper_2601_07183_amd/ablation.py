@@ -11,11 +11,14 @@ Section 6.3's with/without comparison).  With --blocks it varies BLK_SZ over 16,
 and the DCO at the probes that reach the target recall -- from the layout rule of Alg. 4 and the
 cost analysis of Section 5.2 (DCO = n_vec_selected - n_vec_shared); results do not depend on the
 block size, and the device path itself is built for 32 (whose DCO here is checked against the
-kernels' own count).
+kernels' own count).  With --ip the index is searched by inner product (Section 6.4 applies SEIL
+to a SOAR index): single assignment against SOAR's second lists, the latter with its DCO next to
+the DCO of the same probes without SEIL.
 
     python -m paper_2601_07183_amd.ablation --workload sift1m
     python -m paper_2601_07183_amd.ablation --workload sift1m --sweep
     python -m paper_2601_07183_amd.ablation --workload sift1m --blocks
+    python -m paper_2601_07183_amd.ablation --workload sphere10m --base-size 1000000 --ip
 """
 import argparse
 import time
@@ -130,6 +133,59 @@ def blocks(args, w, base, q, gt, centroids, codebook):
               f"{1 - dco.mean() / plain:.2%} | {'-' if same is None else same} |", flush=True)
 
 
+def ip_ground_truth(base: np.ndarray, queries: np.ndarray, k: int) -> np.ndarray:
+    """Ids of the k largest inner products per query (ties: smaller id): a GPU matmul (a tool)
+    shortlists k + 54 per query, float64 products re-rank them."""
+    import torch
+    b = torch.from_numpy(np.ascontiguousarray(base, dtype=np.float32)).cuda()
+    out = []
+    step = max(1, min(500, (1 << 30) // max(1, len(base))))
+    for lo in range(0, len(queries), step):
+        q = torch.from_numpy(queries[lo:lo + step]).cuda()
+        cand = torch.topk(b @ q.T, k + 54, dim=0, largest=True).indices.T.contiguous()
+        exact = (b[cand].double() * q.double()[:, None, :]).sum(-1)
+        cand_sorted, perm = torch.sort(cand, dim=1)
+        exact = torch.gather(exact, 1, perm)
+        order = torch.sort(-exact, dim=1, stable=True).indices[:, :k]
+        out.append(torch.gather(cand_sorted, 1, order).cpu().numpy())
+    return np.concatenate(out)
+
+
+def inner_product(args, w, base, q, centroids, codebook):
+    """Single assignment against SOAR (lambda as given) under the inner-product metric."""
+    import torch
+    from . import binding, index_build as ib
+    import bench
+    base = np.ascontiguousarray(base, dtype=np.float32)
+    gt = ip_ground_truth(base, q, w.k)
+    dq = torch.from_numpy(q).cuda()
+    near = ib.rair_assign(base, centroids, lam=0.0, n_cands=1, strict=False)
+    print("| assignment | vectors stored twice | blocks | nprobe | recall@%d | DCO per query | DCO without SEIL | "
+          "DCO saved | queries/s |" % w.k)
+    print("|---|---|---|---|---|---|---|---|---|")
+    for name, kw in (("single", dict(assign=near)), (f"SOAR (lambda {args.lam}) + SEIL", dict(lam=args.lam))):
+        hx = ib.add_vectors(base, centroids, codebook, metric="ip", **kw)
+        a = hx.assign
+        two = a[:, 0] != a[:, 1]
+        members = np.bincount(a[:, 0], minlength=w.nlist) + np.bincount(a[two, 1], minlength=w.nlist)
+        ix = binding.Index(hx)
+        for nprobe in [int(x) for x in args.nprobes.split(",")]:
+            ids, _ = ix.search(dq, w.k, nprobe, w.refine_k)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(3):
+                ix.search(dq, w.k, nprobe, w.refine_k)
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t) / 3
+            dco = float(ix.dco(len(q)).mean())
+            pid, _ = ix.coarse(dq, nprobe)
+            plain = float(members[pid.cpu().numpy()].sum(1).mean())
+            print(f"| {name} | {float(two.mean()):.3f} | {hx.nblocks:,} | {nprobe} | "
+                  f"{bench.recall_at_k(ids.cpu().numpy(), gt):.4f} | {dco:,.0f} | {plain:,.0f} | "
+                  f"{1 - dco / plain:.2%} | {len(q) / sec:,.0f} |", flush=True)
+        ix.free()
+
+
 def main():
     import torch
     from . import binding, datagen, index_build as ib
@@ -142,6 +198,7 @@ def main():
     ap.add_argument("--nprobes", default="4,8,16,32,64")
     ap.add_argument("--sweep", action="store_true", help="vary lambda and N_CANDS instead")
     ap.add_argument("--blocks", action="store_true", help="vary BLK_SZ over 16, 32, 64 instead")
+    ap.add_argument("--ip", action="store_true", help="inner-product metric: single assignment against SOAR + SEIL")
     ap.add_argument("--target", type=float, default=0.9, help="recall the sweep searches to")
     args = ap.parse_args()
     binding.load()
@@ -149,9 +206,11 @@ def main():
     if args.base_size:
         w = datagen.scaled(w, args.base_size)
     base, q = datagen.make_base(w), datagen.make_queries(w)
-    gt = bench.ground_truth(base, q, w.k)
     centroids = ib.kmeans(base, w.nlist, 20, w.seed * 7 + 1, max_train=256 * w.nlist)
     codebook = ib.train_pq(base, w.M, 25, w.seed * 7 + 2)
+    if args.ip:
+        return inner_product(args, w, base, q, centroids, codebook)
+    gt = bench.ground_truth(base, q, w.k)
     if args.sweep:
         return sweep(args, w, base, q, gt, centroids, codebook)
     if args.blocks:

@@ -624,3 +624,28 @@ def delete_ids(hx: HostIndex, ids_to_delete) -> HostIndex:
         list_ref_cnt=hx.list_ref_cnt, ref_owner=hx.ref_owner, ref_block_begin=hx.ref_block_begin,
         ref_nblocks=hx.ref_nblocks, raw=hx.raw, assign=assign, vec_codes=hx.vec_codes,
         params=dict(hx.params), metric=hx.metric)
+
+
+def save_index(hx: HostIndex, path: str) -> None:
+    """Write a host index to one .npz file (arrays as they are, scalars and parameters as JSON)."""
+    import dataclasses
+    import json
+    arrays, meta = {}, {}
+    for f in dataclasses.fields(hx):
+        val = getattr(hx, f.name)
+        if isinstance(val, np.ndarray):
+            arrays[f.name] = val
+        else:
+            meta[f.name] = val
+    meta["params"] = {k: (v.item() if isinstance(v, np.generic) else v) for k, v in dict(hx.params).items()}
+    with open(path, "wb") as fh:
+        np.savez(fh, _meta=np.frombuffer(json.dumps(meta, default=str).encode(), dtype=np.uint8), **arrays)
+
+
+def load_index(path: str) -> HostIndex:
+    """Read what save_index wrote (no pickled objects are loaded)."""
+    import json
+    with np.load(path, allow_pickle=False) as z:
+        meta = json.loads(bytes(z["_meta"]).decode())
+        arrays = {k: z[k] for k in z.files if k != "_meta"}
+    return HostIndex(**arrays, **meta)

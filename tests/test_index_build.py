@@ -249,3 +249,18 @@ def test_soar_lambda_zero_is_second_nearest_and_prefers_orthogonal_residuals():
     assert np.allclose(loss, [1.0 + 1.0, 1.21 + 1.21, 1.44])
     # AIR on the same picture prefers the opposite residual instead (Table 1's contrast)
     assert ib.rair_assign(v, c, lam=0.5, n_cands=3).tolist() == [[0, 1]]
+
+
+def test_save_and_load_index_round_trip(tmp_path):
+    import dataclasses
+    w = datagen.scaled(datagen.WORKLOADS["tiny"], 3000, nq=8, nlist=16)
+    hx = ib.build_index(datagen.make_base(w), w.nlist, w.M, seed=w.seed, coarse_iters=3, pq_iters=3)
+    path = str(tmp_path / "ix.npz")
+    ib.save_index(hx, path)
+    back = ib.load_index(path)
+    for f in dataclasses.fields(hx):
+        a, b = getattr(hx, f.name), getattr(back, f.name)
+        if isinstance(a, np.ndarray):
+            assert a.dtype == b.dtype and np.array_equal(a, b), f.name
+        else:
+            assert a == b, f.name
