@@ -56,27 +56,56 @@ static __device__ __forceinline__ void wave_bitonic_sort_lds(uint64_t *a, int n,
         }
 }
 
+// The value of lane (l ^ s) of a wave, s = 8, 4, 2, 1, by data-parallel register moves instead of a
+// trip through the LDS crossbar: within a row of 16 lanes a rotation by 8 is l ^ 8; l ^ 4 takes a
+// shift left into lanes 0-3 and 8-11 and a shift right into the others; l ^ 2 and l ^ 1 are
+// permutations of four lanes.
+static __device__ __forceinline__ float lane_xor8(float c)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, c), 0x128, 0xf, 0xf, false));   // row_ror:8
+}
+static __device__ __forceinline__ float lane_xor4(float c)
+{
+    const int x = __builtin_bit_cast(int, c);
+    int t = __builtin_amdgcn_update_dpp(x, x, 0x104, 0xf, 0x5, false);      // row_shl:4 into lanes 0-3, 8-11 of a row
+    t = __builtin_amdgcn_update_dpp(t, x, 0x114, 0xf, 0xa, false);          // row_shr:4 into lanes 4-7, 12-15
+    return __builtin_bit_cast(float, t);
+}
+static __device__ __forceinline__ float lane_xor2(float c)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, c), 0x4e, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+}
+static __device__ __forceinline__ float lane_xor1(float c)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, c), 0xb1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+}
+
 // Totals of four rows of 64 per-lane partial sums, each folded across the lanes at strides
 // 32, 16, 8, 4, 2, 1 with own + partner at every stride -- the butterfly whose result is the same
 // in every lane -- with 7 lane exchanges instead of 24: after stride 32 lanes 0..31 go on with
 // rows 0 and 1 and lanes 32..63 with rows 2 and 3, after stride 16 each group of 16 lanes has one
 // row.  Returns, in every lane of group u = lane >> 4, the total of row u, bit-identical to the
-// separate butterflies (a + b = b + a).
+// separate butterflies (a + b = b + a).  All exchanges are register moves: swapping the upper half
+// of row 0's register with the lower half of row 2's leaves, in every lane, the two values that
+// the stride-32 step adds (likewise rows 1 and 3, and at stride 16 the odd 16-lane rows of one
+// register against the even ones of the other); measured on 10,000-query batches the refine
+// kernel and the coarse re-score were bound by these exchanges when they went through LDS.
 static __device__ __forceinline__ float fold_four_rows(float p0, float p1, float p2, float p3, int lane)
 {
-    const bool h32 = (lane & 32) != 0;
-    float a = h32 ? p2 : p0, b = h32 ? p3 : p1;                  // rows this half keeps
-    const float sa = h32 ? p0 : p2, sb = h32 ? p1 : p3;          // rows the other half keeps
-    a = a + __shfl_xor(sa, 32);
-    b = b + __shfl_xor(sb, 32);
-    const bool h16 = (lane & 16) != 0;
-    float c = h16 ? b : a;
-    const float sc = h16 ? a : b;
-    c = c + __shfl_xor(sc, 16);
-    c = c + __shfl_xor(c, 8);
-    c = c + __shfl_xor(c, 4);
-    c = c + __shfl_xor(c, 2);
-    c = c + __shfl_xor(c, 1);
+    (void)lane;
+    // (the swaps are written as instructions: through the compiler's builtin, which returns both
+    // registers as a pair, this kernel family was compiled to add one register to itself)
+    // (and keep the idle issue slots that the compiler puts around its own: two between a vector
+    // write of an operand and the swap, two before the swapped registers are read)
+    asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\tv_permlane32_swap_b32 %2, %3\n\ts_nop 1"
+        : "+v"(p0), "+v"(p2), "+v"(p1), "+v"(p3));
+    float a = p0 + p2, b = p1 + p3;
+    asm("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+    float c = a + b;
+    c = c + lane_xor8(c);
+    c = c + lane_xor4(c);
+    c = c + lane_xor2(c);
+    c = c + lane_xor1(c);
     return c;
 }
 
