@@ -354,7 +354,7 @@ def main():
                           "timed_repeats": 10, "copy_read_plus_write_GBs": round(gbs, 1)}))
         return
     if args.gpus != 1:
-        log("bench.py measures one GPU; this build has no multi-GPU path (see DESIGN.md). "
+        log("bench.py measures one GPU; this build has no multi-GPU path: queries are independent, so more GPUs would each take a share of the batch. "
             "Run with --gpus 1.")
         sys.exit(2)
 

@@ -194,7 +194,7 @@ int rairs_graph_free(rairs_graph_t *g);       /* NULL is accepted */
 /* ---- the stages of rairs_search, callable one by one (same kernels) ----------------------- */
 
 /*
- * FindNearestLists for a query batch (Alg. 2 line 5): the nprobe nearest centroids per query.
+ * FindNearestLists for a query batch (Alg. 2): the nprobe nearest centroids per query.
  *   d_probe_ids   device [nq][nprobe] int32 in (distance, list id) order
  *   d_probe_dists device [nq][nprobe] fp32, may be NULL
  */
@@ -202,7 +202,7 @@ int rairs_coarse(rairs_index_t *h, const float *d_queries, int64_t nq, int nprob
                  int32_t *d_probe_ids, float *d_probe_dists, void *hip_stream);
 
 /*
- * ComputeLookupTable (Alg. 2 line 4) quantised to 8 bits:
+ * ComputeLookupTable (Alg. 2) quantised to 8 bits:
  *   T[m][c] = |q_m - codeword(m,c)|^2,  b_m = min_c T[m][c],  s = 255 / max_m(max_c T[m][c] - b_m)
  *   lut[m][c] = min(255, rint((T[m][c] - b_m) * s))      (s = 0 if the span is 0)
  *   d_lut device [nq][M][16] uint8; d_bias_sum [nq] = sum_m b_m; d_scale [nq] = s
@@ -227,7 +227,7 @@ int rairs_scan(rairs_index_t *h, const uint8_t *d_lut, const int32_t *d_probe_id
                int64_t *d_dco, void *hip_stream);
 
 /*
- * Refine (Alg. 2 line 7): exact distances of the candidates, K smallest by (distance, id).
+ * Refine (Alg. 2, the refine step): exact distances of the candidates, K smallest by (distance, id).
  *   d_cand_ids device [nq][refine_k] int64, entries < 0 are ignored.
  */
 int rairs_refine(rairs_index_t *h, const float *d_queries, const int64_t *d_cand_ids, int64_t nq,

@@ -139,7 +139,7 @@ float oracle_l2sqr_u8(const float *a, const uint8_t *b, int d)
     return fold64(p);
 }
 
-/* ---- FindNearestLists on the query side (Alg. 2 line 5) --------------------------------- */
+/* ---- FindNearestLists on the query side (Alg. 2) ---------------------------------------------- */
 
 typedef struct { float dist; int64_t id; } dist_id;
 
@@ -169,7 +169,7 @@ void oracle_coarse(const oracle_index *ix, const float *q, int nprobe, int32_t *
     free(all);
 }
 
-/* ---- ComputeLookupTable (Alg. 2 line 4, Section 2.2) + 8-bit quantisation ----------------- */
+/* ---- ComputeLookupTable (Alg. 2, Section 2.2) + 8-bit quantisation ----------------- */
 
 void oracle_lut(const oracle_index *ix, const float *q, float *T, uint8_t *lut, float *bias_sum,
                 float *scale)

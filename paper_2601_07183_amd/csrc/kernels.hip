@@ -86,7 +86,7 @@ int rairs_launch_transpose(const float *d_in, int rows, int cols, float *d_out, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// coarse quantizer: FindNearestLists for the batch (Alg. 2 line 5)
+// coarse quantizer: FindNearestLists for the batch (Alg. 2)
 // ---------------------------------------------------------------------------------------------
 //
 // The result is defined by the direct form: dist(q, l) = sum_i (q_i - c_li)^2 in fp32, summed as 64
@@ -761,7 +761,7 @@ int rairs_launch_bitmap(const IndexView &v, const int32_t *probe_ids, int64_t nq
 }
 
 // ---------------------------------------------------------------------------------------------
-// lookup tables: ComputeLookupTable (Alg. 2 line 4) + 8-bit quantisation
+// lookup tables: ComputeLookupTable (Alg. 2) + 8-bit quantisation
 // ---------------------------------------------------------------------------------------------
 
 __global__ __launch_bounds__(WG) void lut_kernel(const float *__restrict__ q,
@@ -1044,7 +1044,7 @@ int rairs_launch_air_assign(const IndexView &v, const float *x, int64_t n, int n
 }
 
 // ---------------------------------------------------------------------------------------------
-// Refine (Alg. 2 line 7): exact distances of the candidates, K smallest by (distance, id)
+// Refine (Alg. 2, the refine step): exact distances of the candidates, K smallest by (distance, id)
 // ---------------------------------------------------------------------------------------------
 
 // One wave per query, no workgroup barrier: the wave takes the query's candidates four rows at a
