@@ -80,6 +80,68 @@ static __device__ __forceinline__ float lane_xor1(float c)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, c), 0xb1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
 }
 
+// Smallest of the 64 lanes' 64-bit keys, in every lane: a butterfly over strides 32 .. 1 whose
+// exchanges are register moves.  After swapping the upper half of one copy of a register with the
+// lower half of another copy, every lane holds its own value in one and its partner's in the
+// other, so the step is just the minimum of the two (likewise at stride 16 with 16-lane rows).
+static __device__ __forceinline__ uint64_t wave_min_u64(uint64_t x)
+{
+    uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
+    {
+        uint32_t lo2 = lo, hi2 = hi;
+        asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\tv_permlane32_swap_b32 %2, %3\n\ts_nop 1"
+            : "+v"(lo), "+v"(lo2), "+v"(hi), "+v"(hi2));
+        const uint64_t a = ((uint64_t)hi << 32) | lo, b = ((uint64_t)hi2 << 32) | lo2;
+        const uint64_t m = a < b ? a : b;
+        lo = (uint32_t)m; hi = (uint32_t)(m >> 32);
+    }
+    {
+        uint32_t lo2 = lo, hi2 = hi;
+        asm("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\tv_permlane16_swap_b32 %2, %3\n\ts_nop 1"
+            : "+v"(lo), "+v"(lo2), "+v"(hi), "+v"(hi2));
+        const uint64_t a = ((uint64_t)hi << 32) | lo, b = ((uint64_t)hi2 << 32) | lo2;
+        const uint64_t m = a < b ? a : b;
+        lo = (uint32_t)m; hi = (uint32_t)(m >> 32);
+    }
+#define RAIRS_MIN_STEP(XOR_)                                                                      \
+    {                                                                                             \
+        const uint32_t plo = __builtin_bit_cast(uint32_t, XOR_(__builtin_bit_cast(float, lo)));   \
+        const uint32_t phi = __builtin_bit_cast(uint32_t, XOR_(__builtin_bit_cast(float, hi)));   \
+        const uint64_t a = ((uint64_t)hi << 32) | lo, b = ((uint64_t)phi << 32) | plo;            \
+        const uint64_t m = a < b ? a : b;                                                         \
+        lo = (uint32_t)m; hi = (uint32_t)(m >> 32);                                               \
+    }
+    RAIRS_MIN_STEP(lane_xor8)
+    RAIRS_MIN_STEP(lane_xor4)
+    RAIRS_MIN_STEP(lane_xor2)
+    RAIRS_MIN_STEP(lane_xor1)
+#undef RAIRS_MIN_STEP
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// The k <= 64 smallest of n distinct 64-bit keys in a wave's own LDS region (all-ones entries are
+// empty), ascending: k rounds of "take the minimum and strike it out"; lane r returns the r-th
+// smallest (all ones beyond the entries there are).  For the few results that refine keeps (k of
+// bigK) this is well under half of a full sort's instructions.  The keys are overwritten.
+static __device__ __forceinline__ uint64_t wave_take_smallest(uint64_t *keys, int n, int k, int lane)
+{
+    uint64_t res = ~0ull;
+    for (int r = 0; r < k; r++) {
+        uint64_t mine = ~0ull;
+        for (int i = lane; i < n; i += 64) {
+            const uint64_t x = keys[i];
+            mine = x < mine ? x : mine;
+        }
+        const uint64_t best = wave_min_u64(mine);
+        if (best != ~0ull)
+            for (int i = lane; i < n; i += 64)
+                if (keys[i] == best) keys[i] = ~0ull;     // keys are distinct: one lane, one slot
+        if (lane == r) res = best;
+        wave_lds_sync();
+    }
+    return res;
+}
+
 // Totals of four rows of 64 per-lane partial sums, each folded across the lanes at strides
 // 32, 16, 8, 4, 2, 1 with own + partner at every stride -- the butterfly whose result is the same
 // in every lane -- with 7 lane exchanges instead of 24: after stride 32 lanes 0..31 go on with

@@ -1047,6 +1047,7 @@ int rairs_launch_air_assign(const IndexView &v, const float *x, int64_t n, int n
 // Refine (Alg. 2, the refine step): exact distances of the candidates, K smallest by (distance, id)
 // ---------------------------------------------------------------------------------------------
 
+#define REFINE_TAKE_MAX_K 16                // up to here the k results are taken one by one, else a full sort
 // One wave per query, no workgroup barrier: the wave takes the query's candidates four rows at a
 // time (lane j sums the dimensions i = j (mod 64) in increasing order, then the 64 partial sums are
 // folded across lanes at strides 32..1), keeps their keys in its own LDS region and sorts them there.
@@ -1125,6 +1126,17 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
         }
     }
     wave_lds_sync();
+    if (k <= REFINE_TAKE_MAX_K) {
+        // few results of many candidates: take the k smallest one by one instead of sorting all
+        const uint64_t key = wave_take_smallest(keys, n2, k, lane);
+        if (lane < k) {
+            const bool ok = key != ~0ull;
+            out_ids[(size_t)qi * k + lane] = ok ? (int64_t)(uint32_t)key : -1;
+            const float sc = ok ? key_f32((uint32_t)(key >> 32)) : __builtin_inff();
+            out_dists[(size_t)qi * k + lane] = v.metric ? -sc : sc;
+        }
+        return;
+    }
     wave_bitonic_sort_lds(keys, n2, lane);
     for (int i = lane; i < k; i += 64) {
         const uint64_t key = keys[i];
