@@ -1048,9 +1048,15 @@ int rairs_launch_air_assign(const IndexView &v, const float *x, int64_t n, int n
 // ---------------------------------------------------------------------------------------------
 
 #define REFINE_TAKE_MAX_K 16                // up to here the k results are taken one by one, else a full sort
-// One wave per query, no workgroup barrier: the wave takes the query's candidates four rows at a
-// time (lane j sums the dimensions i = j (mod 64) in increasing order, then the 64 partial sums are
-// folded across lanes at strides 32..1), keeps their keys in its own LDS region and sorts them there.
+// One wave per query, no workgroup barrier: the wave takes the query's candidates four at a time,
+// one per group of 16 lanes, keeps their keys in its own LDS region and selects there.  The sum
+// is the defined one -- 64 interleaved partial sums p_j over the dimensions i = j (mod 64), i
+// increasing, then p_j + p_(j xor 32), xor 16, ... xor 1 -- arranged so that most of it stays in
+// a lane: lane l of a group holds p_l, p_(l+16), p_(l+32), p_(l+48), so the strides 32 and 16 of
+// the butterfly are sums inside the lane (same operands, so the same bits) and only strides 8 to
+// 1 cross lanes, as register moves within the group's row of 16.  (A whole wave per row with the
+// four rows folded together took 22 instructions per four candidates for the fold, this takes 9,
+// and no selects to route ids and flags to the lane that writes the key.)
 __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__restrict__ q,
                                                     const int64_t *__restrict__ cand_ids, int64_t nq,
                                                     int refine_k, int k,
@@ -1064,65 +1070,115 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
     const float *qq = q + (size_t)qi * v.d;
     const int n2 = next_pow2(refine_k < 2 ? 2 : refine_k);
     uint64_t *keys = refine_keys + (size_t)wave * n2;
-    // lane l first fetches the id of candidate mb + l for 64 of them at once, so that the row
-    // loads below do not wait for an id load each time; then four candidates at a time, so that
-    // their row loads are in flight together
-    for (int mb = 0; mb < n2; mb += 64) {
-        int64_t myid = -1;
-        if (mb + lane < refine_k) myid = cand_ids[(size_t)qi * refine_k + mb + lane];
-        for (int c0 = mb; c0 < mb + 64 && c0 < n2; c0 += 4) {
-            int64_t id[4];
-            bool ok[4];
-            float p[4];
+    const int grp = lane >> 4, l16 = lane & 15;
+    const int64_t *my_ids = cand_ids + (size_t)qi * refine_k;
+    // Two candidates per group and step (eight per wave), so that sixteen row loads are in flight
+    // together: a wave's steps are a serial chain of memory round trips, and this halves it.  The
+    // ids of a step are fetched one step ahead of their rows.
+    constexpr int RU = 2;
+    const int n_used = refine_k < n2 ? refine_k : n2;    // candidates that exist; the rest of the keys are empty
+    for (int e = n_used + lane; e < n2; e += 64) keys[e] = ~0ull;
+    int64_t id_next[RU];
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
-                const int src = (c0 - mb + u) & 63;          // c0 + u >= n2 only when n2 = 2: lanes without a candidate hold -1
-                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)myid, src);
-                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)myid >> 32), src);
-                id[u] = (int64_t)(((uint64_t)hi << 32) | lo);
+    for (int u = 0; u < RU; u++) id_next[u] = 4 * u + grp < n_used ? my_ids[4 * u + grp] : -1;
+    for (int c0 = 0; c0 < n_used; c0 += 4 * RU) {
+        int64_t id[RU];
+        bool ok[RU];
+        float p[RU][4];
+#pragma unroll
+        for (int u = 0; u < RU; u++) {
+            const int c = c0 + 4 * u + grp;              // this group's candidates of the step
+            id[u] = id_next[u];
+            id_next[u] = c + 4 * RU < n_used ? my_ids[c + 4 * RU] : -1;
+            ok[u] = c < n_used && id[u] >= 0 && id[u] < v.ntotal;
+            if (!ok[u]) id[u] = 0;                       // row 0 is read and discarded
+            p[u][0] = p[u][1] = p[u][2] = p[u][3] = 0.0f;
+        }
+        if (v.raw_u8) {
+            const uint8_t *row[RU];
+#pragma unroll
+            for (int u = 0; u < RU; u++) row[u] = (const uint8_t *)v.raw + (size_t)id[u] * v.d;
+            int i0 = 0;
+            for (; i0 + 64 <= v.d; i0 += 64) {           // whole rounds of 64 dimensions: no lane checks
+                float qv[4], x[RU][4];
+#pragma unroll
+                for (int cc = 0; cc < 4; cc++) {         // class l16 + 16 cc, dimensions increasing
+                    qv[cc] = qq[i0 + l16 + 16 * cc];
+#pragma unroll
+                    for (int u = 0; u < RU; u++) x[u][cc] = (float)row[u][i0 + l16 + 16 * cc];
+                }
+#pragma unroll
+                for (int u = 0; u < RU; u++)
+#pragma unroll
+                    for (int cc = 0; cc < 4; cc++) {
+                        float diff = qv[cc] - x[u][cc];
+                        float sq = v.metric ? qv[cc] * x[u][cc] : diff * diff;
+                        p[u][cc] = p[u][cc] + sq;
+                    }
             }
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
-                ok[u] = id[u] >= 0 && id[u] < v.ntotal;
-                if (!ok[u]) id[u] = 0;                       // row 0 is read and discarded
-                p[u] = 0.0f;
-            }
-            const bool any = ok[0] || ok[1] || ok[2] || ok[3];       // wave-uniform
-            if (!any) {
-                // nothing to read (also keeps an empty index untouched)
-            } else if (v.raw_u8) {
-                for (int i = lane; i < v.d; i += 64) {
+            for (int cc = 0; cc < 4; cc++) {             // the last, partial round
+                const int i = i0 + l16 + 16 * cc;
+                if (i < v.d) {
                     const float qv = qq[i];
 #pragma unroll
-                    for (int u = 0; u < 4; u++) {
-                        const float x = (float)((const uint8_t *)v.raw)[(size_t)id[u] * v.d + i];
+                    for (int u = 0; u < RU; u++) {
+                        const float x = (float)row[u][i];
                         float diff = qv - x;
                         float sq = v.metric ? qv * x : diff * diff;
-                        p[u] = p[u] + sq;
+                        p[u][cc] = p[u][cc] + sq;
                     }
                 }
-            } else {
-                for (int i = lane; i < v.d; i += 64) {
+            }
+        } else {
+            const float *row[RU];
+#pragma unroll
+            for (int u = 0; u < RU; u++) row[u] = (const float *)v.raw + (size_t)id[u] * v.d;
+            int i0 = 0;
+            for (; i0 + 64 <= v.d; i0 += 64) {
+                float qv[4], x[RU][4];
+#pragma unroll
+                for (int cc = 0; cc < 4; cc++) {
+                    qv[cc] = qq[i0 + l16 + 16 * cc];
+#pragma unroll
+                    for (int u = 0; u < RU; u++) x[u][cc] = row[u][i0 + l16 + 16 * cc];
+                }
+#pragma unroll
+                for (int u = 0; u < RU; u++)
+#pragma unroll
+                    for (int cc = 0; cc < 4; cc++) {
+                        float diff = qv[cc] - x[u][cc];
+                        float sq = v.metric ? qv[cc] * x[u][cc] : diff * diff;
+                        p[u][cc] = p[u][cc] + sq;
+                    }
+            }
+#pragma unroll
+            for (int cc = 0; cc < 4; cc++) {
+                const int i = i0 + l16 + 16 * cc;
+                if (i < v.d) {
                     const float qv = qq[i];
 #pragma unroll
-                    for (int u = 0; u < 4; u++) {
-                        const float x = ((const float *)v.raw)[(size_t)id[u] * v.d + i];
+                    for (int u = 0; u < RU; u++) {
+                        const float x = row[u][i];
                         float diff = qv - x;
                         float sq = v.metric ? qv * x : diff * diff;
-                        p[u] = p[u] + sq;
+                        p[u][cc] = p[u][cc] + sq;
                     }
                 }
             }
-            const float folded = fold_four_rows(p[0], p[1], p[2], p[3], lane);   // row lane >> 4
-            const float dist = v.metric ? -folded : folded;      // inner product: ordered by minus the product
-            {
-                const int u = lane >> 4, c = c0 + u;
-                const bool oku = u == 0 ? ok[0] : (u == 1 ? ok[1] : (u == 2 ? ok[2] : ok[3]));
-                const int64_t idu = u == 0 ? id[0] : (u == 1 ? id[1] : (u == 2 ? id[2] : id[3]));
-                // empty: all ones, above every key
-                if ((lane & 15) == 0 && c < n2)
-                    keys[c] = oku ? (((uint64_t)f32_key(dist) << 32) | (uint32_t)idu) : ~0ull;
-            }
+        }
+#pragma unroll
+        for (int u = 0; u < RU; u++) {
+            const int c = c0 + 4 * u + grp;
+            const float a = p[u][0] + p[u][2], b = p[u][1] + p[u][3];    // stride 32: classes j and j + 32
+            float t = a + b;                             // stride 16
+            t = t + lane_xor8(t);
+            t = t + lane_xor4(t);
+            t = t + lane_xor2(t);
+            t = t + lane_xor1(t);
+            const float dist = v.metric ? -t : t;        // inner product: ordered by minus the product
+            // empty: all ones, above every key
+            if (l16 == 0 && c < n_used) keys[c] = ok[u] ? (((uint64_t)f32_key(dist) << 32) | (uint32_t)id[u]) : ~0ull;
         }
     }
     wave_lds_sync();
