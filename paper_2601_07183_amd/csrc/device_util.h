@@ -119,6 +119,28 @@ static __device__ __forceinline__ uint64_t wave_min_u64(uint64_t x)
     return ((uint64_t)hi << 32) | lo;
 }
 
+// Sum of the 64 lanes' values, in every lane (register moves only, as in wave_min_u64).
+static __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
+{
+    {
+        uint32_t x2 = x;
+        asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(x), "+v"(x2));
+        x += x2;
+    }
+    {
+        uint32_t x2 = x;
+        asm("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(x), "+v"(x2));
+        x += x2;
+    }
+#define RAIRS_SUM_STEP(XOR_) x += __builtin_bit_cast(uint32_t, XOR_(__builtin_bit_cast(float, x)));
+    RAIRS_SUM_STEP(lane_xor8)
+    RAIRS_SUM_STEP(lane_xor4)
+    RAIRS_SUM_STEP(lane_xor2)
+    RAIRS_SUM_STEP(lane_xor1)
+#undef RAIRS_SUM_STEP
+    return x;
+}
+
 // The k <= 64 smallest of n distinct 64-bit keys in a wave's own LDS region (all-ones entries are
 // empty), ascending: k rounds of "take the minimum and strike it out"; lane r returns the r-th
 // smallest (all ones beyond the entries there are).  For the few results that refine keeps (k of
@@ -140,6 +162,45 @@ static __device__ __forceinline__ uint64_t wave_take_smallest(uint64_t *keys, in
         wave_lds_sync();
     }
     return res;
+}
+
+// The same selection for n <= 128 keys and few results, by rank instead of k rounds of a wave-wide
+// minimum: every lane takes its (up to) two keys into registers; the k-th smallest upper word is
+// found bit by bit (the largest t with fewer than k upper words below it); the m >= k entries up to
+// it (more than k only when upper words tie there) are packed into keys[0..m) and lane r < m counts
+// how many of them are below its own: that is its key's place in the order.  Returns false, with the
+// keys untouched, when more than 64 entries tie (the caller takes another route); else lane r < m
+// holds a key and its rank, and every rank 0 .. m - 1 is held by exactly one lane.
+static __device__ __forceinline__ bool wave_rank_smallest(uint64_t *keys, int n, int k, int lane,
+                                                          uint64_t *key_out, int *rank_out, int *m_out)
+{
+    const uint64_t k0 = lane < n ? keys[lane] : ~0ull, k1 = lane + 64 < n ? keys[lane + 64] : ~0ull;
+    const uint32_t h0 = (uint32_t)(k0 >> 32), h1 = (uint32_t)(k1 >> 32);
+    uint32_t cut = 0;
+    for (int bit = 31; bit >= 0; bit--) {
+        const uint32_t cand = cut | (1u << bit);
+        const uint32_t below = (uint32_t)__popcll(__ballot(h0 < cand)) + (uint32_t)__popcll(__ballot(h1 < cand));
+        if (below < (uint32_t)k) cut = cand;
+    }
+    const bool in0 = k0 != ~0ull && h0 <= cut, in1 = k1 != ~0ull && h1 <= cut;
+    const unsigned long long b0 = __ballot(in0), b1 = __ballot(in1);
+    const int m0 = __popcll(b0), m = m0 + __popcll(b1);
+    if (m > 64) return false;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    wave_lds_sync();                                    // every lane has read its keys
+    if (in0) keys[__popcll(b0 & lt)] = k0;
+    if (in1) keys[m0 + __popcll(b1 & lt)] = k1;
+    wave_lds_sync();
+    const uint64_t mine = lane < m ? keys[lane] : ~0ull;
+    int rank = 0;
+    for (int j = 0; j < m; j++) {                       // one address for the wave: a broadcast
+        const uint64_t other = keys[j];
+        rank += other < mine || (other == mine && j < lane) ? 1 : 0;    // (equal keys: in the order held)
+    }
+    *key_out = mine;
+    *rank_out = rank;
+    *m_out = m;
+    return true;
 }
 
 // Totals of four rows of 64 per-lane partial sums, each folded across the lanes at strides

@@ -446,6 +446,7 @@ __global__ __launch_bounds__(WG) void coarse_gemm_chunk_kernel(const float *__re
 // keys were gathered, or they do not fit, or est is below the widened threshold, the wave falls back
 // to a radix select over the whole row (four passes), which always works.
 #define SHORTLIST_SAMPLE 512
+template <bool IP>
 __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__restrict__ keys,
                                                               const float *__restrict__ q,
                                                               const float *__restrict__ cent, int d,
@@ -455,7 +456,7 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
                                                               float cmax2, int64_t nq,
                                                               int32_t *__restrict__ probe_ids,
                                                               float *__restrict__ probe_dists,
-                                                              uint32_t *__restrict__ flags, int metric)
+                                                              uint32_t *__restrict__ flags)
 {
     __shared__ uint32_t hist_s[WG / 64][256];
     extern __shared__ __align__(16) uint64_t sel_dyn[];      // [WG / 64][cap], cap a power of two
@@ -489,14 +490,17 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
             const int l = 64 * u + lane;
             ks[u] = l < nsamp ? row[l] : 0xFFFFFFFFu;
         }
+        // (only an upper estimate is needed: the top 20 bits -- sign, exponent, 11 bits of the
+        // fraction -- are found and the rest set, which overshoots by under a 2000th of the score)
         uint32_t est = 0;
-        for (int bit = 31; bit >= 0; bit--) {
+        for (int bit = 31; bit >= 12; bit--) {
             const uint32_t cand = est | (1u << bit);
             uint32_t below = 0;
 #pragma unroll
             for (int u = 0; u < SHORTLIST_SAMPLE / 64; u++) below += (uint32_t)__popcll(__ballot(ks[u] < cand));
             if (below < (uint32_t)ksamp) est = cand;
         }
+        est |= 0xFFFu;
         // every key <= est, with its list
         uint32_t ng = 0;
         for (int l0 = 0; l0 < nlist; l0 += 64 * 16) {
@@ -605,35 +609,75 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
     }
     if (lane == 0) flags[qi] = fits ? 0u : 1u;
     wave_lds_sync();
-    // re-score in the direct form: the wave takes one list at a time, lane j sums the dimensions
-    // of class j and the fold is a butterfly over the lanes (lane 0 ends with the defined value)
-    for (uint32_t c0 = 0; c0 < nc; c0 += 4) {
-        float p[4];
-        uint32_t ls[4];
+    // Re-score in the direct form, eight lists per step, two per group of 16 lanes: lane l of a
+    // group sums the dimensions of the classes l, l + 16, l + 32, l + 48 (mod 64) in four
+    // registers, so the strides 32 and 16 of the defined butterfly are sums inside the lane (the
+    // same operands in the same pairing) and only strides 8 to 1 cross lanes.
+    {
+        constexpr int RU = 2;
+        const int grp = lane >> 4, l16 = lane & 15;
+        for (uint32_t c0 = 0; c0 < nc; c0 += 4 * RU) {
+            uint32_t ls[RU];
+            float p[RU][4];
+            const float *crow[RU];
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-            ls[u] = (uint32_t)sel[c0 + u < nc ? c0 + u : nc - 1];
-            p[u] = 0.0f;
-        }
-        for (int t = lane; t < d; t += 64) {            // class `lane`, dimensions increasing
-            const float qv = qq[t];
-#pragma unroll
-            for (int u = 0; u < 4; u++) {
-                const float c = cent[(size_t)ls[u] * d + t];
-                float diff = qv - c;
-                float sq = metric ? qv * c : diff * diff;
-                p[u] = p[u] + sq;
+            for (int u = 0; u < RU; u++) {
+                const uint32_t c = c0 + 4 * u + grp;
+                ls[u] = (uint32_t)sel[c < nc ? c : nc - 1];
+                crow[u] = cent + (size_t)ls[u] * d;
+                p[u][0] = p[u][1] = p[u][2] = p[u][3] = 0.0f;
             }
+            int i0 = 0;
+            for (; i0 + 64 <= d; i0 += 64) {             // whole rounds of 64 dimensions: no lane checks
+                float qv[4], x[RU][4];
+#pragma unroll
+                for (int cc = 0; cc < 4; cc++) {
+                    qv[cc] = qq[i0 + l16 + 16 * cc];
+#pragma unroll
+                    for (int u = 0; u < RU; u++) x[u][cc] = crow[u][i0 + l16 + 16 * cc];
+                }
+#pragma unroll
+                for (int u = 0; u < RU; u++)
+#pragma unroll
+                    for (int cc = 0; cc < 4; cc++) {
+                        float sq;
+                        if (IP) sq = qv[cc] * x[u][cc];
+                        else { const float diff = qv[cc] - x[u][cc]; sq = diff * diff; }
+                        p[u][cc] = p[u][cc] + sq;
+                    }
+            }
+            if (i0 < d) {                                // the last, partial round
+#pragma unroll
+                for (int cc = 0; cc < 4; cc++) {
+                    const int i = i0 + l16 + 16 * cc;
+                    if (i < d) {
+                        const float qv = qq[i];
+#pragma unroll
+                        for (int u = 0; u < RU; u++) {
+                            const float x = crow[u][i];
+                            float sq;
+                            if (IP) sq = qv * x;
+                            else { const float diff = qv - x; sq = diff * diff; }
+                            p[u][cc] = p[u][cc] + sq;
+                        }
+                    }
+                }
+            }
+            wave_lds_sync();                             // every list of the step was read before an entry is rewritten
+#pragma unroll
+            for (int u = 0; u < RU; u++) {
+                const uint32_t c = c0 + 4 * u + grp;
+                const float a = p[u][0] + p[u][2], b = p[u][1] + p[u][3];    // stride 32
+                float t = a + b;                         // stride 16
+                t = t + lane_xor8(t);
+                t = t + lane_xor4(t);
+                t = t + lane_xor2(t);
+                t = t + lane_xor1(t);
+                const float dist = IP ? -t : t;
+                if (l16 == 0 && c < nc) sel[c] = ((uint64_t)f32_key(dist) << 32) | ls[u];
+            }
+            wave_lds_sync();
         }
-        const float folded = fold_four_rows(p[0], p[1], p[2], p[3], lane);     // list lane >> 4
-        const float dist = metric ? -folded : folded;
-        wave_lds_sync();                                 // all four lists were read before any entry is rewritten
-        {
-            const int u = lane >> 4;
-            const uint32_t lu = u == 0 ? ls[0] : (u == 1 ? ls[1] : (u == 2 ? ls[2] : ls[3]));
-            if ((lane & 15) == 0 && c0 + u < nc) sel[c0 + u] = ((uint64_t)f32_key(dist) << 32) | lu;
-        }
-        wave_lds_sync();
     }
     const int n2 = next_pow2((int)nc < 2 ? 2 : (int)nc);
     for (int e = (int)nc + lane; e < n2; e += 64) sel[e] = ~0ull;
@@ -645,7 +689,7 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
             probe_ids[(size_t)qi * nprobe + e] = (int32_t)(uint32_t)key;
             if (probe_dists) {
                 const float sc = key_f32((uint32_t)(key >> 32));
-                probe_dists[(size_t)qi * nprobe + e] = metric ? -sc : sc;
+                probe_dists[(size_t)qi * nprobe + e] = IP ? -sc : sc;
             }
         }
 }
@@ -720,12 +764,18 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
         if (cap2 > cap) cap = cap2;
     }
     const size_t sel_bytes = (size_t)cap * 8 * (WG / 64);
-    if (sel_bytes > 32 * 1024)
-        RAIRS_HIP(hipFuncSetAttribute((const void *)coarse_shortlist_kernel,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_bytes));
-    hipLaunchKernelGGL(coarse_shortlist_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))),
-                       dim3(WG), sel_bytes, s, keys, q, v.centroids, v.d, v.nlist,
-                       nprobe, cap, nsamp, ksamp, v.cmean, v.cmax2, nq, probe_ids, probe_dists, flags, v.metric);
+#define SHORTLIST_LAUNCH(IP_)                                                                     \
+    do {                                                                                          \
+        if (sel_bytes > 32 * 1024)                                                                \
+            RAIRS_HIP(hipFuncSetAttribute((const void *)coarse_shortlist_kernel<IP_>,              \
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_bytes)); \
+        hipLaunchKernelGGL(coarse_shortlist_kernel<IP_>, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), \
+                           dim3(WG), sel_bytes, s, keys, q, v.centroids, v.d, v.nlist, nprobe, cap, nsamp, \
+                           ksamp, v.cmean, v.cmax2, nq, probe_ids, probe_dists, flags);           \
+    } while (0)
+    if (v.metric) SHORTLIST_LAUNCH(true);
+    else SHORTLIST_LAUNCH(false);
+#undef SHORTLIST_LAUNCH
     // queries whose shortlist did not fit (many lists at nearly the same distance): full route,
     // both steps by the query's own workgroup
     hipLaunchKernelGGL(coarse_select_kernel, dim3((unsigned)nq), dim3(WG), 0, s, (uint32_t *)dmat, v.nlist, nprobe,
@@ -1057,6 +1107,9 @@ int rairs_launch_air_assign(const IndexView &v, const float *x, int64_t n, int n
 // 1 cross lanes, as register moves within the group's row of 16.  (A whole wave per row with the
 // four rows folded together took 22 instructions per four candidates for the fold, this takes 9,
 // and no selects to route ids and flags to the lane that writes the key.)
+// (the metric and the row type are template arguments: as run-time flags they cost a select per
+// element -- both the product and the squared difference were computed -- a third of the loop)
+template <bool IP, typename RowT>
 __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__restrict__ q,
                                                     const int64_t *__restrict__ cand_ids, int64_t nq,
                                                     int refine_k, int k,
@@ -1085,6 +1138,7 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
         int64_t id[RU];
         bool ok[RU];
         float p[RU][4];
+        const RowT *row[RU];
 #pragma unroll
         for (int u = 0; u < RU; u++) {
             const int c = c0 + 4 * u + grp;              // this group's candidates of the step
@@ -1093,65 +1147,28 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
             ok[u] = c < n_used && id[u] >= 0 && id[u] < v.ntotal;
             if (!ok[u]) id[u] = 0;                       // row 0 is read and discarded
             p[u][0] = p[u][1] = p[u][2] = p[u][3] = 0.0f;
+            row[u] = (const RowT *)v.raw + (size_t)id[u] * v.d;
         }
-        if (v.raw_u8) {
-            const uint8_t *row[RU];
+        int i0 = 0;
+        for (; i0 + 64 <= v.d; i0 += 64) {               // whole rounds of 64 dimensions: no lane checks
+            float qv[4], x[RU][4];
 #pragma unroll
-            for (int u = 0; u < RU; u++) row[u] = (const uint8_t *)v.raw + (size_t)id[u] * v.d;
-            int i0 = 0;
-            for (; i0 + 64 <= v.d; i0 += 64) {           // whole rounds of 64 dimensions: no lane checks
-                float qv[4], x[RU][4];
+            for (int cc = 0; cc < 4; cc++) {             // class l16 + 16 cc, dimensions increasing
+                qv[cc] = qq[i0 + l16 + 16 * cc];
 #pragma unroll
-                for (int cc = 0; cc < 4; cc++) {         // class l16 + 16 cc, dimensions increasing
-                    qv[cc] = qq[i0 + l16 + 16 * cc];
-#pragma unroll
-                    for (int u = 0; u < RU; u++) x[u][cc] = (float)row[u][i0 + l16 + 16 * cc];
-                }
-#pragma unroll
-                for (int u = 0; u < RU; u++)
-#pragma unroll
-                    for (int cc = 0; cc < 4; cc++) {
-                        float diff = qv[cc] - x[u][cc];
-                        float sq = v.metric ? qv[cc] * x[u][cc] : diff * diff;
-                        p[u][cc] = p[u][cc] + sq;
-                    }
+                for (int u = 0; u < RU; u++) x[u][cc] = (float)row[u][i0 + l16 + 16 * cc];
             }
 #pragma unroll
-            for (int cc = 0; cc < 4; cc++) {             // the last, partial round
-                const int i = i0 + l16 + 16 * cc;
-                if (i < v.d) {
-                    const float qv = qq[i];
-#pragma unroll
-                    for (int u = 0; u < RU; u++) {
-                        const float x = (float)row[u][i];
-                        float diff = qv - x;
-                        float sq = v.metric ? qv * x : diff * diff;
-                        p[u][cc] = p[u][cc] + sq;
-                    }
-                }
-            }
-        } else {
-            const float *row[RU];
-#pragma unroll
-            for (int u = 0; u < RU; u++) row[u] = (const float *)v.raw + (size_t)id[u] * v.d;
-            int i0 = 0;
-            for (; i0 + 64 <= v.d; i0 += 64) {
-                float qv[4], x[RU][4];
+            for (int u = 0; u < RU; u++)
 #pragma unroll
                 for (int cc = 0; cc < 4; cc++) {
-                    qv[cc] = qq[i0 + l16 + 16 * cc];
-#pragma unroll
-                    for (int u = 0; u < RU; u++) x[u][cc] = row[u][i0 + l16 + 16 * cc];
+                    float sq;
+                    if (IP) sq = qv[cc] * x[u][cc];
+                    else { const float diff = qv[cc] - x[u][cc]; sq = diff * diff; }
+                    p[u][cc] = p[u][cc] + sq;
                 }
-#pragma unroll
-                for (int u = 0; u < RU; u++)
-#pragma unroll
-                    for (int cc = 0; cc < 4; cc++) {
-                        float diff = qv[cc] - x[u][cc];
-                        float sq = v.metric ? qv[cc] * x[u][cc] : diff * diff;
-                        p[u][cc] = p[u][cc] + sq;
-                    }
-            }
+        }
+        if (i0 < v.d) {                                  // the last, partial round
 #pragma unroll
             for (int cc = 0; cc < 4; cc++) {
                 const int i = i0 + l16 + 16 * cc;
@@ -1159,9 +1176,10 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
                     const float qv = qq[i];
 #pragma unroll
                     for (int u = 0; u < RU; u++) {
-                        const float x = row[u][i];
-                        float diff = qv - x;
-                        float sq = v.metric ? qv * x : diff * diff;
+                        const float x = (float)row[u][i];
+                        float sq;
+                        if (IP) sq = qv * x;
+                        else { const float diff = qv - x; sq = diff * diff; }
                         p[u][cc] = p[u][cc] + sq;
                     }
                 }
@@ -1176,20 +1194,36 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
             t = t + lane_xor4(t);
             t = t + lane_xor2(t);
             t = t + lane_xor1(t);
-            const float dist = v.metric ? -t : t;        // inner product: ordered by minus the product
+            const float dist = IP ? -t : t;              // inner product: ordered by minus the product
             // empty: all ones, above every key
             if (l16 == 0 && c < n_used) keys[c] = ok[u] ? (((uint64_t)f32_key(dist) << 32) | (uint32_t)id[u]) : ~0ull;
         }
     }
     wave_lds_sync();
     if (k <= REFINE_TAKE_MAX_K) {
-        // few results of many candidates: take the k smallest one by one instead of sorting all
+        // few results of many candidates: find them by their rank instead of sorting all
+        if (n2 <= 128) {
+            uint64_t key;
+            int rank, m;
+            if (wave_rank_smallest(keys, n2, k, lane, &key, &rank, &m)) {
+                if (lane < m && rank < k) {
+                    out_ids[(size_t)qi * k + rank] = (int64_t)(uint32_t)key;
+                    const float sc = key_f32((uint32_t)(key >> 32));
+                    out_dists[(size_t)qi * k + rank] = IP ? -sc : sc;
+                }
+                for (int r = m + lane; r < k; r += 64) {     // fewer than k candidates exist
+                    out_ids[(size_t)qi * k + r] = -1;
+                    out_dists[(size_t)qi * k + r] = IP ? -__builtin_inff() : __builtin_inff();
+                }
+                return;
+            }
+        }
         const uint64_t key = wave_take_smallest(keys, n2, k, lane);
         if (lane < k) {
             const bool ok = key != ~0ull;
             out_ids[(size_t)qi * k + lane] = ok ? (int64_t)(uint32_t)key : -1;
             const float sc = ok ? key_f32((uint32_t)(key >> 32)) : __builtin_inff();
-            out_dists[(size_t)qi * k + lane] = v.metric ? -sc : sc;
+            out_dists[(size_t)qi * k + lane] = IP ? -sc : sc;
         }
         return;
     }
@@ -1199,7 +1233,7 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
         const bool ok = key != ~0ull;
         out_ids[(size_t)qi * k + i] = ok ? (int64_t)(uint32_t)key : -1;
         const float sc = ok ? key_f32((uint32_t)(key >> 32)) : __builtin_inff();
-        out_dists[(size_t)qi * k + i] = v.metric ? -sc : sc;     // inner product: the product itself, missing -inf
+        out_dists[(size_t)qi * k + i] = IP ? -sc : sc;       // inner product: the product itself, missing -inf
     }
 }
 
@@ -1300,8 +1334,16 @@ int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_
 {
     const int n2 = next_pow2(refine_k < 2 ? 2 : refine_k);
     if (nq >= REFINE_WAVE_MIN_QUERIES)
-        hipLaunchKernelGGL(refine_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
-                           (size_t)(WG / 64) * n2 * 8, s, v, q, cand_ids, nq, refine_k, k, out_ids, out_dists);
+    {
+        const dim3 grid((unsigned)((nq + WG / 64 - 1) / (WG / 64)));
+        const size_t lds = (size_t)(WG / 64) * n2 * 8;
+#define REFINE_LAUNCH(IP_, ROW_)                                                                  \
+    hipLaunchKernelGGL((refine_kernel<IP_, ROW_>), grid, dim3(WG), lds, s, v, q, cand_ids, nq, refine_k, k, \
+                       out_ids, out_dists)
+        if (v.metric) { if (v.raw_u8) REFINE_LAUNCH(true, uint8_t); else REFINE_LAUNCH(true, float); }
+        else          { if (v.raw_u8) REFINE_LAUNCH(false, uint8_t); else REFINE_LAUNCH(false, float); }
+#undef REFINE_LAUNCH
+    }
     else
         hipLaunchKernelGGL(refine_wg_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, q, cand_ids, refine_k,
                            k, out_ids, out_dists);

@@ -301,41 +301,23 @@ __global__ __launch_bounds__(WG) void sample_bound_kernel(IndexView v, const uin
     }
 }
 
-// Position of the k-th (1-based, k <= total) entry of a 256-bin histogram held in a wave's LDS
-// region: returns the bin and leaves in *before the number of entries in lower bins.
-static __device__ __forceinline__ int bin_of_rank(const uint32_t *bins, uint32_t k, int lane, uint32_t *before)
-{
-    const uint4 h = ((const uint4 *)bins)[lane];         // bins 4 lane .. 4 lane + 3
-    const uint32_t mine = h.x + h.y + h.z + h.w;
-    uint32_t incl = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t x = (uint32_t)__shfl_up((int)incl, off);
-        if (lane >= off) incl += x;
-    }
-    const unsigned long long reach = __ballot(incl >= k);
-    const int src = __builtin_ctzll(reach);              // first lane whose running count reaches k
-    uint32_t b4 = incl - mine;                           // entries below this lane's bins
-    int bin = 4 * lane;
-    if (b4 + h.x < k) { b4 += h.x; bin++; if (b4 + h.y < k) { b4 += h.y; bin++; if (b4 + h.z < k) { b4 += h.z; bin++; } } }
-    *before = (uint32_t)__shfl((int)b4, src);
-    return __shfl(bin, src);
-}
-
 // Bound of every query from the scores the matrix-core sample kernel wrote, pre[q][sample_blocks *
-// 32] (0xFFFF: no item): the bigK-th smallest of them, by a radix select on the high and then the
-// low byte with a 256-bin histogram in the wave's LDS; same outputs as sample_bound_kernel.
+// 32] (0xFFFF: no item): the bigK-th smallest of them; same outputs as sample_bound_kernel.  One
+// wave per query holds the query's scores in registers (WPL words of two scores per lane) and
+// finds the value bit by bit: t becomes the largest value with fewer than bigK scores below it.
+// With fewer than bigK scores no candidate ever has bigK below it and t ends as 0xFFFF.  (A radix
+// select with a histogram in LDS was two and a half times slower: the scores of a query crowd into
+// a few bins, and LDS atomics on one address are served one at a time.)
+template <int WPL>
 __global__ __launch_bounds__(WG) void sample_rank_kernel(IndexView v, const int32_t *__restrict__ probe_ids,
                                                          int nprobe, int refine_k, int sample_blocks,
                                                          int64_t nq, const uint16_t *__restrict__ pre,
                                                          int32_t *__restrict__ tau,
                                                          int32_t *__restrict__ bound)
 {
-    __shared__ __align__(16) uint32_t rank_bins[WG / 64][256];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + wave;
-    if (qi >= nq) return;                                // a whole wave; no workgroup barrier below
-    uint32_t *bins = rank_bins[wave];
+    if (qi >= nq) return;
     const int L = probe_ids[(size_t)qi * nprobe];
     int cnt = 0;
     if (L >= 0 && L < v.nlist) {
@@ -345,41 +327,53 @@ __global__ __launch_bounds__(WG) void sample_rank_kernel(IndexView v, const int3
     }
     const int nw = cnt * 16;                             // score pairs
     const uint32_t *row = (const uint32_t *)(pre + (size_t)qi * sample_blocks * 32);
-    ((uint4 *)bins)[lane] = make_uint4(0u, 0u, 0u, 0u);
-    wave_lds_sync();
-    uint32_t nvalid = 0, smax = 0;
-    for (int e = lane; e < nw; e += 64) {
-        const uint32_t x = row[e], a = x & 0xFFFFu, b = x >> 16;
-        if (a != 0xFFFFu) { atomicAdd(&bins[a >> 8], 1u); nvalid++; smax = a > smax ? a : smax; }
-        if (b != 0xFFFFu) { atomicAdd(&bins[b >> 8], 1u); nvalid++; smax = b > smax ? b : smax; }
-    }
+    // Scores are below 0x7FFF (255 M with M <= 64, checked at launch); an empty slot counts as
+    // 0x7FFF, above all of them.  With both values below 2^15, (a - c) mod 2^16 = a - c + 2^16 [a < c],
+    // so the number of scores below c is (sum of the 16-bit differences - sum of the scores + N c)
+    // / 2^16: one packed subtraction and one two-way dot product per pair of scores, and one sum
+    // over the wave per candidate.
+    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+    us2 x[WPL];
+    uint32_t sum_a = 0;
+    const us2 one2 = {1, 1};
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        nvalid += (uint32_t)__shfl_xor((int)nvalid, off);
-        const uint32_t o = (uint32_t)__shfl_xor((int)smax, off);
-        smax = o > smax ? o : smax;
+    for (int u = 0; u < WPL; u++) {
+        const int e = 64 * u + lane;
+        const uint32_t w = e < nw ? row[e] : 0xFFFFFFFFu;
+        const uint32_t a = w & 0xFFFFu, b = w >> 16;
+        x[u] = (us2){(unsigned short)(a < 0x7FFFu ? a : 0x7FFFu), (unsigned short)(b < 0x7FFFu ? b : 0x7FFFu)};
+        sum_a = __builtin_amdgcn_udot2(x[u], one2, sum_a, false);
     }
-    wave_lds_sync();
-    uint32_t t = 0xFFFFu;
-    if (nvalid >= (uint32_t)refine_k) {                  // uniform for the wave
-        uint32_t before;
-        const uint32_t hi = (uint32_t)bin_of_rank(bins, (uint32_t)refine_k, lane, &before);
-        wave_lds_sync();
-        ((uint4 *)bins)[lane] = make_uint4(0u, 0u, 0u, 0u);
-        wave_lds_sync();
-        for (int e = lane; e < nw; e += 64) {
-            const uint32_t x = row[e], a = x & 0xFFFFu, b = x >> 16;
-            if (a != 0xFFFFu && (a >> 8) == hi) atomicAdd(&bins[a & 255u], 1u);
-            if (b != 0xFFFFu && (b >> 8) == hi) atomicAdd(&bins[b & 255u], 1u);
-        }
-        wave_lds_sync();
-        uint32_t before2;
-        const uint32_t lo = (uint32_t)bin_of_rank(bins, (uint32_t)refine_k - before, lane, &before2);
-        t = (hi << 8) | lo;
+    sum_a = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(sum_a));
+    const uint32_t n_all = 2u * 64u * WPL;
+    uint32_t t = 0;
+    for (int bit = 14; bit >= 0; bit--) {
+        const uint32_t cand = t | (1u << bit);
+        const us2 c2 = {(unsigned short)cand, (unsigned short)cand};
+        uint32_t sum_d = 0;
+#pragma unroll
+        for (int u = 0; u < WPL; u++) sum_d = __builtin_amdgcn_udot2(x[u] - c2, one2, sum_d, false);
+        sum_d = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(sum_d));
+        const uint32_t below = (sum_d - sum_a + n_all * cand) >> 16;
+        if (below < (uint32_t)refine_k) t = cand;
     }
+    if (t == 0x7FFFu) t = 0xFFFFu;                       // fewer than bigK scores
     // range of the score histogram, as in sample_bound_kernel
     uint32_t range = t;
-    if (t == 0xFFFFu) {
+    if (t == 0xFFFFu) {                                  // uniform
+        uint32_t nvalid = 0, smax = 0;
+#pragma unroll
+        for (int u = 0; u < WPL; u++) {
+            const uint32_t a = x[u].x, b = x[u].y;
+            if (a != 0x7FFFu) { nvalid++; smax = a > smax ? a : smax; }
+            if (b != 0x7FFFu) { nvalid++; smax = b > smax ? b : smax; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            nvalid += (uint32_t)__shfl_xor((int)nvalid, off);
+            const uint32_t o = (uint32_t)__shfl_xor((int)smax, off);
+            smax = o > smax ? o : smax;
+        }
         const uint32_t full = 255u * (uint32_t)v.M;
         range = nvalid > 0 && 2u * smax + 64u < full ? 2u * smax + 64u : full;
     }
@@ -393,8 +387,24 @@ int rairs_launch_sample_rank(const IndexView &v, const int32_t *probe_ids, int n
                              int sample_blocks, int64_t nq, const uint16_t *pre, int32_t *tau,
                              int32_t *bound, hipStream_t s)
 {
-    hipLaunchKernelGGL(sample_rank_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG), 0, s,
-                       v, probe_ids, nprobe, refine_k, sample_blocks, nq, pre, tau, bound);
+    if (sample_blocks < 1 || sample_blocks > RAIRS_SAMPLE_MAX_BLOCKS || 255 * v.M >= 0x7FFF) {
+        rairs_set_error("sample of %d blocks with M = %d: the rank kernel takes 1..%d blocks and scores below 32767",
+                        sample_blocks, v.M, RAIRS_SAMPLE_MAX_BLOCKS);
+        return RAIRS_EINVAL;
+    }
+    static_assert(RAIRS_SAMPLE_MAX_BLOCKS * 16 <= 32 * 64, "a lane holds at most 32 score pairs");
+    const dim3 grid((unsigned)((nq + WG / 64 - 1) / (WG / 64)));
+    const int wpl = (sample_blocks * 16 + 63) / 64;      // score pairs per lane
+#define RANK_LAUNCH(W_)                                                                           \
+    hipLaunchKernelGGL(sample_rank_kernel<W_>, grid, dim3(WG), 0, s, v, probe_ids, nprobe, refine_k, \
+                       sample_blocks, nq, pre, tau, bound)
+    if (wpl <= 4) RANK_LAUNCH(4);
+    else if (wpl <= 8) RANK_LAUNCH(8);
+    else if (wpl <= 12) RANK_LAUNCH(12);
+    else if (wpl <= 16) RANK_LAUNCH(16);
+    else if (wpl <= 24) RANK_LAUNCH(24);
+    else RANK_LAUNCH(32);
+#undef RANK_LAUNCH
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }

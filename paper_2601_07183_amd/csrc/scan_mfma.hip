@@ -764,12 +764,32 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
 // writes the bigK smallest.  No workgroup barrier is used: a wave only touches its own region, and
 // LDS operations of one wave complete in issue order.
 #define SELW_CAP_MAX 1024
+template <int NU>
+static __device__ __forceinline__ uint32_t selw_cut(const uint64_t (&mine)[SELW_CAP_MAX / 64], uint32_t k)
+{
+    uint32_t cut = 0;
+    for (int bit = 15; bit >= 0; bit--) {
+        const uint32_t cand = cut | (1u << bit);
+        uint32_t below = 0;
+#pragma unroll
+        for (int u = 0; u < NU; u++) below += (uint32_t)__popcll(__ballot((uint32_t)(mine[u] >> 32) < cand));
+        if (below < k) cut = cand;
+    }
+    return cut;
+}
+
 __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanArgs a, int cap)
 {
     extern __shared__ __align__(16) uint64_t selw_keys[];      // [WG / 64][cap]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t q = (int64_t)blockIdx.x * (WG / 64) + wave;
     if (q >= a.nq) return;
+    // the first 256 slots of the query's buffer (it has at least 1024) are requested together
+    // with the count; slots beyond the count hold stale bits and are replaced below
+    const uint64_t *sb = a.surv_buf + (size_t)q * a.surv_cap;
+    uint64_t e_first[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) e_first[u] = sb[64 * u + lane];
     const uint32_t n = a.surv_cnt[q];
     if (n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) {
         if (lane == 0) a.flags[q] = 1;      // redone by the exact kernel
@@ -778,7 +798,6 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
     if (n > (uint32_t)cap) return;          // select_kernel's case
     if (lane == 0) a.flags[q] = 0;
     uint64_t *keys = selw_keys + (size_t)wave * cap;
-    const uint64_t *sb = a.surv_buf + (size_t)q * a.surv_cap;
     const uint32_t *bm = a.bitmap + (size_t)q * a.bmwords;
     for (uint32_t i0 = 0; i0 < n; i0 += 256) {
         uint64_t e[4];
@@ -787,7 +806,8 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
 #pragma unroll
         for (int u = 0; u < 4; u++) {
             const uint32_t i = i0 + 64 * u + lane;
-            e[u] = sb[i < n ? i : n - 1];
+            if (i0 == 0) e[u] = i < n ? e_first[u] : 0ull;      // slot 0 of block 0: read and discarded
+            else e[u] = sb[i < n ? i : n - 1];
         }
 #pragma unroll
         for (int u = 0; u < 4; u++) {
@@ -823,15 +843,11 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
             if (i < n) mine[u] = keys[i];
         }
     }
-    uint32_t cut = 0;                                   // largest t with fewer than bigK scores below it
-    for (int bit = 15; bit >= 0; bit--) {
-        const uint32_t cand = cut | (1u << bit);
-        uint32_t below = 0;
-#pragma unroll
-        for (int u = 0; u < SELW_CAP_MAX / 64; u++)
-            if (64 * u < (int)n) below += (uint32_t)__popcll(__ballot((uint32_t)(mine[u] >> 32) < cand));
-        if (below < (uint32_t)a.refine_k) cut = cand;
-    }
+    // largest t with fewer than bigK scores below it (over the rows of 64 that hold entries)
+    const uint32_t cut = n <= 128   ? selw_cut<2>(mine, (uint32_t)a.refine_k)
+                         : n <= 256 ? selw_cut<4>(mine, (uint32_t)a.refine_k)
+                         : n <= 512 ? selw_cut<8>(mine, (uint32_t)a.refine_k)
+                                    : selw_cut<SELW_CAP_MAX / 64>(mine, (uint32_t)a.refine_k);
     // (dropped entries carry score 0xFFFFFFFF and are never below a candidate; with fewer than bigK
     // kept entries cut ends at 0xFFFF and everything kept is packed)
     wave_lds_sync();                                    // every lane has its keys in registers

@@ -381,6 +381,52 @@ def test_inner_product_metric_with_soar_assignment(binding, d, M, integer):
         ix.free()
 
 
+@pytest.mark.parametrize("d,integer,metric", [(128, True, "l2"), (96, False, "l2"), (200, False, "ip"),
+                                              (64, True, "ip")])
+def test_refine_one_wave_per_query(binding, d, integer, metric):
+    # Batches of 4,096 queries and more take the refine kernel that gives every query one wave
+    # (smaller ones a workgroup): candidate lists with missing (-1) and out-of-range ids, fewer
+    # candidates than K, duplicated base vectors (equal distances, ordered by id), byte and fp32
+    # rows, a dimension with a partial round of 64, both metrics; K below and above the size up to
+    # which the results are found by rank.  Expected: oracle distances of a sample of the queries,
+    # ordered by (distance, id).
+    g = np.random.Generator(np.random.PCG64(900 + d))
+    n, nq = 2500, 4096 + 37
+    base = datagen.random_vectors(40 + d, n, d)
+    q = datagen.random_vectors(41 + d, nq, d)
+    if integer:
+        base, q = (np.clip(np.rint(x * 40 + 128), 0, 255).astype(np.float32) for x in (base, q))
+    base[1::5] = base[0::5][:len(base[1::5])]                  # every fifth row twice
+    hx = ib.build_index(base, 16, d // 2 if d // 2 <= 64 else 8, seed=3, coarse_iters=2, pq_iters=2, metric=metric)
+    dist = oracle.ip if metric == "ip" else oracle.l2sqr
+    ix = binding.Index(hx)
+    try:
+        for refine_k, k in ((100, 10), (100, 1), (128, 16), (40, 17), (10, 10), (100, 100)):
+            print(f"case: refine d={d} integer={integer} metric={metric} refine_k={refine_k} k={k}", flush=True)
+            cand = g.integers(0, n, size=(nq, refine_k)).astype(np.int64)
+            for i in range(nq):                                 # distinct ids per query
+                cand[i] = g.choice(n, size=refine_k, replace=False)
+            cand[g.random(cand.shape) < 0.05] = -1
+            cand[5::11, refine_k // 2:] = -1                    # short lists, some shorter than K
+            cand[3::97, 0] = n + 5                              # not an id of the index
+            rid, rd = ix.refine(_dev(q), _dev(cand), k)
+            torch.cuda.synchronize()
+            rid, rd = rid.cpu().numpy(), rd.cpu().numpy()
+            for i in list(range(0, nq, 131)) + [5, 16, 3, 100, nq - 1]:
+                ok = [c for c in cand[i] if 0 <= c < n]
+                sc = np.array([np.float32(dist(q[i], base[c])) for c in ok], dtype=np.float32)
+                key = -sc if metric == "ip" else sc
+                order = sorted(range(len(ok)), key=lambda t: (key[t], ok[t]))[:k]
+                want_ids = np.full(k, -1, dtype=np.int64)
+                want_d = np.full(k, -np.inf if metric == "ip" else np.inf, dtype=np.float32)
+                want_ids[:len(order)] = [ok[t] for t in order]
+                want_d[:len(order)] = [sc[t] for t in order]
+                assert (rid[i] == want_ids).all(), (i, rid[i], want_ids)
+                _assert_dists(rd[i], want_d)
+    finally:
+        ix.free()
+
+
 def test_inner_product_coarse_routes(binding):
     # 1,100 lists and d = 128: the matrix-core shortlist with its sampled threshold; d = 5: the
     # full direct-form route; negative and positive products
