@@ -269,7 +269,7 @@ __global__ __launch_bounds__(WG) void coarse_select_kernel(uint32_t *dmat,
 // Result register r of lane (k, j) is row 8*(r/4) + 4*k + r%4, column j.
 #define GEMM_QWG 128
 template <int D>
-__global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict__ q,
+__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(D <= 128 ? 3 : 2))) void coarse_gemm_kernel(const float *__restrict__ q,
                                                          const float *__restrict__ ct,
                                                          const float *__restrict__ cmean,
                                                          const float *__restrict__ cnorm, int nlist,
@@ -309,11 +309,16 @@ __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict
     // staging: thread -> column sj, rows sr + 8 * e (row = dimension k*H + s)
     const int sj = threadIdx.x & 31, sr = threadIdx.x >> 5;
     float st[PER];
+    // (a uniform row pointer plus one 32-bit offset per thread: sixteen 64-bit addresses per
+    // thread would cost the registers that decide whether a third wave fits a SIMD)
     auto fetch = [&](int t) {
         const int l = t * 32 + sj;
-        const float *src = ct + (l < nlist ? l : nlist - 1);
+        const uint32_t off = (uint32_t)sr * (uint32_t)nlist + (uint32_t)(l < nlist ? l : nlist - 1);
 #pragma unroll
-        for (int e = 0; e < PER; e++) st[e] = src[(size_t)(sr + 8 * e) * nlist];
+        for (int e = 0; e < PER; e++) {
+            const float *rows = ct + (size_t)(8 * e) * nlist;       // uniform
+            st[e] = rows[off];
+        }
     };
     auto stage = [&](int buf) {
 #pragma unroll
@@ -326,9 +331,13 @@ __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict
     stage(0);
     __syncthreads();
     int buf = 0;
+    // all 32 rows of the wave are queries of the batch (else: the last block, stores checked one by one)
+    const bool whole = q0 + 32 <= nq;
     for (int t = t_begin; t < t_end; t++) {
         const bool more = t + 1 < t_end;
         if (more) fetch(t + 1);
+        const int l = t * 32 + i;
+        const float cn = cnorm[l < nlist ? l : nlist - 1];          // asked for before the products, used after
         v16f acc;
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[r] = 0.0f;
@@ -336,14 +345,22 @@ __global__ __launch_bounds__(WG) void coarse_gemm_kernel(const float *__restrict
 #pragma unroll
         for (int s = 0; s < H; s++)
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(A[s], bl[s * 64], acc, 0, 0, 0);
-        const int l = t * 32 + i;
+        // alpha = 2: |c'|^2 - 2 q'.c'; alpha = 1 with zero norms: -q.c
         if (l < nlist) {
-            const float cn = cnorm[l];
+            if (whole) {
+                // a uniform row pointer per result register plus one 32-bit offset per lane
+                const uint32_t off = (uint32_t)(4 * k) * (uint32_t)nlist + (uint32_t)l;
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int64_t qq = q0 + 8 * (r >> 2) + 4 * k + (r & 3);
-                const float two = alpha * acc[r];     // alpha = 2: |c'|^2 - 2 q'.c'; alpha = 1 with zero norms: -q.c
-                if (qq < nq) keys[(size_t)qq * nlist + l] = f32_key(cn - two);
+                for (int r = 0; r < 16; r++) {
+                    uint32_t *rowp = keys + (size_t)(q0 + 8 * (r >> 2) + (r & 3)) * nlist;      // uniform
+                    rowp[off] = f32_key(cn - alpha * acc[r]);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const int64_t qq = q0 + 8 * (r >> 2) + 4 * k + (r & 3);
+                    if (qq < nq) keys[(size_t)qq * nlist + l] = f32_key(cn - alpha * acc[r]);
+                }
             }
         }
         if (more) stage(buf ^ 1);
