@@ -586,7 +586,15 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int64_t nq_total, int 
     w.flags = take((size_t)nq * 4);
     w.hist = take((size_t)nq * RAIRS_HIST_BINS * 4);
     w.surv_cap = surv_cap_for(refine_k);
-    w.log_chunks = (int)((nq * log_per_query_for(refine_k) + 255) / 256) + 8192;   // + two per wave
+    {
+        // Chunks of RAIRS_LOG_CHUNK entries; a wave moves on when its next flush (up to 128 entries)
+        // does not fit, and every wave that gets a unit holds a current and a reserved chunk.
+        const int64_t units = (nq * nprobe < nq * nprobe / 32 + v.nlist ? nq * nprobe : nq * nprobe / 32 + v.nlist) *
+                              (int64_t)(max_parts > 0 ? max_parts : 1);
+        const int64_t active = rairs_scan_log_waves(v, units);
+        w.log_chunks = (int)((nq * log_per_query_for(refine_k) + RAIRS_LOG_CHUNK - 128) / (RAIRS_LOG_CHUNK - 127) +
+                             2 * active + 16);
+    }
     w.chunk_fill = take((size_t)w.log_chunks * 4);
     w.log_misc = take(64);
     const bool grouped = grouped_sample(v, nq, refine_k);
@@ -595,7 +603,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int64_t nq_total, int 
     w.s_toff = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
     w.s_q = take(grouped ? (size_t)nq * 4 : 0);
     w.s_tiles = take(grouped ? ((size_t)nq / 32 + (size_t)v.nlist + 1) * 4 : 0);
-    const size_t dmat_bytes = (size_t)nq * v.nlist * 4, log_bytes = (size_t)w.log_chunks * 256 * 8;
+    const size_t dmat_bytes = (size_t)nq * v.nlist * 4, log_bytes = (size_t)w.log_chunks * RAIRS_LOG_CHUNK * 8;
     w.dmat = w.log = take(dmat_bytes > log_bytes ? dmat_bytes : log_bytes);
     const size_t samp_bytes = grouped ? (size_t)nq * w.sample_blocks * 64 : 0;
     const size_t surv_bytes = (size_t)nq * w.surv_cap * 8;
@@ -799,7 +807,7 @@ static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t 
         const int64_t tiles = n * (int64_t)nprobe / 32 + v.nlist;
         const int64_t parts_total = tiles * (h->nparts / (v.nlist > 0 ? v.nlist : 1) + 1);
         int up = (int)(parts_total / (2048 * 12));
-        ma.unit_parts = up < 1 ? 1 : (up > 4 ? 4 : up);
+        ma.unit_parts = up >= 4 ? 4 : up >= 3 ? 3 : parts_total >= 16000 ? 2 : 1;
         // with the tables in LDS a whole workgroup shares a unit and reloads up to 128 KB of
         // tables for each: always the longest units
         if (!(v.T == 8 || v.T == 24 || v.T == 32)) ma.unit_parts = 4;

@@ -161,6 +161,7 @@ struct ExactScanArgs {
 };
 int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s);
 #define RAIRS_SAMPLE_MAX_BLOCKS 128
+#define RAIRS_LOG_CHUNK 1024        // entries of a chunk of the survivor log
 // bound of every query from the head of its first probed list
 int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
                               int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,
@@ -216,6 +217,7 @@ struct MfmaScanArgs {
 };
 bool rairs_mfma_supported(const IndexView &v);
 bool rairs_mfma_reg_tables(const IndexView &v);    // the tile's tables fit the registers (sparse instruction)
+int64_t rairs_scan_log_waves(const IndexView &v, int64_t units);    // most waves that own log chunks at once, for a pass of at most `units` units
 // grouping of the (query, probed list) pairs by list and the unit table, then the scan itself
 int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
 int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev);

@@ -48,18 +48,32 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 
 // ---- grouping queries by list ----------------------------------------------------------------
 
-// The scanning waves start on unit and log chunks numbered by their own index (a second chunk each
-// at index + nwaves), so the counters start behind those.
+// Chunks of the survivor log that the scanning waves start with: `starters` waves (with the tables
+// in registers) or workgroups (tables in LDS, `waves_each` waves) begin on the units numbered by
+// their own index; each wave of those that get a unit owns the chunk of its index and, reserved,
+// the one at index + active waves.  The cursor for later chunks starts behind both.  (Handing out
+// the first chunks by a counter instead makes 2,048 waves hit one address as the kernel starts:
+// 20 us on a 0.56 ms kernel.)
+static __device__ __forceinline__ uint32_t log_active_waves(uint32_t nunits, uint32_t starters, uint32_t waves_each)
+{
+    return (nunits < starters ? nunits : starters) * waves_each;
+}
+static __device__ __forceinline__ uint32_t log_first_free(uint32_t nunits, uint32_t starters, uint32_t waves_each)
+{
+    return 2u * log_active_waves(nunits, starters, waves_each);
+}
+
+// The scanning waves start on the units numbered by their own index (a second one each at index +
+// nwaves with the tables in registers), so the unit counter starts behind those.
 __global__ void lm_zero_kernel(int32_t *lcount, int32_t *lcursor, int nlist, uint32_t *next_task, uint32_t *surv_cnt,
                                int64_t nq, uint32_t *chunk_fill, int log_chunks, uint32_t *log_cursor,
-                               uint32_t *log_overflow, uint32_t first_task, uint32_t first_chunk,
-                               unsigned long long *dco)
+                               uint32_t *log_overflow, uint32_t first_task, unsigned long long *dco)
 {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < nlist) { lcount[gid] = 0; lcursor[gid] = 0; }
     if (gid < nq) { surv_cnt[gid] = 0; if (dco) dco[gid] = 0ull; }
     if (gid < log_chunks) chunk_fill[gid] = 0;
-    if (gid == 0) { *next_task = first_task; *log_cursor = first_chunk; *log_overflow = 0; }
+    if (gid == 0) { *next_task = first_task; *log_cursor = 0u; *log_overflow = 0; }   // (the cursor: set again with the unit count)
 }
 
 __global__ void lm_count_kernel(const int32_t *__restrict__ probe_ids, int64_t nq, int nprobe,
@@ -106,7 +120,8 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
                                                          const int32_t *__restrict__ lcount,
                                                          int32_t *loff, int32_t *lcursor,
                                                          int32_t *toff, int32_t *unit_list,
-                                                         int unit_parts, int32_t *unit_rec)
+                                                         int unit_parts, int32_t *unit_rec,
+                                                         uint32_t *log_cursor, uint32_t starters, uint32_t waves_each)
 {
     __shared__ int sc[1024], st[1024];
     // one workgroup on the critical path of the grouping, usually next to a kernel that fills the
@@ -150,6 +165,7 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
     if (tid == 1023) {
         loff[v.nlist] = sc[1023];
         toff[v.nlist] = st[1023];
+        *log_cursor = log_first_free((uint32_t)st[1023], starters, waves_each);
     }
 }
 
@@ -234,7 +250,8 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(IndexView v, const int
                                                           const int32_t *__restrict__ lcount,
                                                           int32_t *loff, int32_t *lcursor, int32_t *qlist,
                                                           int qb, int32_t *toff, int32_t *unit_list,
-                                                          int unit_parts, int32_t *unit_rec)
+                                                          int unit_parts, int32_t *unit_rec,
+                                                          uint32_t *log_cursor, uint32_t starters, uint32_t waves_each)
 {
     extern __shared__ int32_t lm_lds[];                // [nlist] ranks / run starts, [nlist + 1] offsets
     __shared__ int32_t wsum[4], total;
@@ -275,7 +292,10 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(IndexView v, const int
         }
         __syncthreads();
         const int nunits = total;
-        if (ub == 0 && tid == 0) toff[nlist] = nunits;
+        if (ub == 0 && tid == 0) {
+            toff[nlist] = nunits;
+            *log_cursor = log_first_free((uint32_t)nunits, starters, waves_each);
+        }
         const int share = (nunits + LM_UNIT_WGS - 1) / LM_UNIT_WGS;
         const int e1 = (ub + 1) * share < nunits ? (ub + 1) * share : nunits;
         for (int e = ub * share + tid; e < e1; e += 256) {
@@ -369,11 +389,14 @@ static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a
 // wave appends them to its current chunk of a global survivor log with plain stores, counts them
 // in the queries' histograms and, for some, lowers the query's bound.  Nothing on this path
 // waits for a returning atomic: the wave owns its chunk, and the next chunk's number is requested
-// long before it is needed.  Ids, tags and the duplicate rule are resolved afterwards, in bulk,
+// long before it is needed (only waves with work
+// own chunks, so the log of a small batch is small).  Chunks of 1,024 entries: with 256 the scan
+// kernel of the 1M x 128 workload took 0.610 ms instead of 0.565 and the collect step issued twice
+// the atomics.  Ids, tags and the duplicate rule are resolved afterwards, in bulk,
 // by collect_kernel and select_kernel.
 #define STAGE_CAP 128              // a multiple of 64 (a flush takes the queue in rows of 64); 192 and 256 measured slower
 static_assert(STAGE_CAP % 64 == 0 && STAGE_CAP >= 128, "stage queue rows");
-#define LOG_CHUNK 256
+#define LOG_CHUNK RAIRS_LOG_CHUNK
 #define LOG_COUNTED 0x80000000u    // bit 31 of a staged slot: the entry counts in the histogram
 struct StageQueue {
     uint2 ent[STAGE_CAP];          // the log entry: {block * 32 + item (| LOG_COUNTED), score << 16 | query of the pass}
@@ -524,8 +547,8 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
     // first unit and first two log chunks by wave index; the counters start behind them
     const uint32_t gwave = blockIdx.x * (WG / 64) + (threadIdx.x >> 6), nwaves = gridDim.x * (WG / 64);
     LogCursor lc;
-    lc.chunk = gwave;
-    lc.next_v = gwave + nwaves;
+    lc.chunk = gwave;                                  // (a wave without a unit never writes)
+    lc.next_v = gwave + log_active_waves(nunits, nwaves, 1u);
     lc.used = 0;
     RefreshPace pace = {REFRESH_GAP_MIN, REFRESH_GAP_MIN - 1u, 0u};
 #define FLUSH_STAGE()                                                   \
@@ -707,13 +730,14 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
         u_next = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_next2);
     }
     if (nstaged > 0) FLUSH_STAGE();
-    if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
+    // (a wave that never had a unit wrote nothing, and the chunk of its index may be another wave's)
+    if (lane == 0 && lc.used > 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
 }
 
 // Distribute the survivor log to the per-query buffers (a workgroup takes one chunk at a time).  A chunk holds
 // entries of a few dozen queries; they are grouped in LDS first so that each query's counter is
 // bumped once per chunk, not once per entry.
-#define COLLECT_SLOTS 128
+#define COLLECT_SLOTS 512
 __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
 {
     __shared__ int32_t key[COLLECT_SLOTS];
@@ -739,7 +763,7 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
     if (live) {
         const int qid = (int)(e.y & 0xFFFFu);
         // open addressing on the query id; a full table falls back to a direct atomic below
-        int h = (int)(((uint32_t)qid * 2654435761u) >> 25);          // 7 bits
+        int h = (int)(((uint32_t)qid * 2654435761u) >> 23);          // 9 bits
         for (int probe = 0; probe < COLLECT_SLOTS; probe++) {
             const int prev = atomicCAS(&key[h], -1, qid);
             if (prev == -1 || prev == qid) { slot = h; break; }
@@ -997,8 +1021,8 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
     if (nunits == 0u) return;                          // uniform; nothing was written
     const uint32_t gwave = blockIdx.x * nwave + wave, nwaves = gridDim.x * nwave;
     LogCursor lc;
-    lc.chunk = gwave;
-    lc.next_v = gwave + nwaves;
+    lc.chunk = gwave;                                  // (a workgroup without a unit never writes)
+    lc.next_v = gwave + log_active_waves(nunits, gridDim.x, (uint32_t)nwave);
     lc.used = 0;
     for (bool first = true;; first = false) {
         __syncthreads();                               // everyone is done with the previous tile
@@ -1143,7 +1167,8 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
         if (a.dco && g == 0 && scored) atomicAdd(&a.dco[qid], (unsigned long long)scored);
     }
     if (nstaged > 0) stage_flush(a, sq, nstaged, lane, lc, pace);
-    if (lane == 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
+    // (a wave that never had a unit wrote nothing, and the chunk of its index may be another wave's)
+    if (lane == 0 && lc.used > 0 && lc.chunk < (uint32_t)a.log_chunks) a.chunk_fill[lc.chunk] = lc.used;
 }
 
 // ---- the bound sample on the matrix cores -----------------------------------------------------
@@ -1413,6 +1438,18 @@ static void scan_launch_shape(const IndexView &v, bool *reg_tables, unsigned *gr
     *lds_waves = w;
 }
 
+// Most waves that can own chunks of the survivor log at once when the pass has at most `units` units.
+int64_t rairs_scan_log_waves(const IndexView &v, int64_t units)
+{
+    bool reg_tables;
+    unsigned gridx;
+    int lds_waves;
+    size_t table_bytes;
+    scan_launch_shape(v, &reg_tables, &gridx, &lds_waves, &table_bytes);
+    if (reg_tables) return units < (int64_t)gridx * (WG / 64) ? units : (int64_t)gridx * (WG / 64);
+    return (units < (int64_t)gridx ? units : (int64_t)gridx) * lds_waves;
+}
+
 int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
 {
     const int np = a.nprobe - a.p_first;
@@ -1423,8 +1460,10 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
     size_t table_bytes;
     scan_launch_shape(v, &reg_tables, &gridx, &lds_waves, &table_bytes);
     const uint32_t nwaves = gridx * (reg_tables ? WG / 64 : lds_waves);
-    if (a.log_chunks < (int)(2 * nwaves)) {
-        rairs_set_error("survivor log of %d chunks is below %u", a.log_chunks, 2 * nwaves);
+    // who starts on a unit of its own index, and with how many waves (see log_active_waves)
+    const uint32_t starters = reg_tables ? nwaves : gridx, waves_each = reg_tables ? 1u : (uint32_t)lds_waves;
+    if (a.log_chunks < 2) {
+        rairs_set_error("survivor log of %d chunks", a.log_chunks);
         return RAIRS_EINVAL;
     }
     const int64_t pairs = a.nq * np;
@@ -1432,7 +1471,7 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
     nz = nz > a.log_chunks ? nz : a.log_chunks;
     hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
                        a.lcursor, v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
-                       a.log_cursor, a.log_overflow, reg_tables ? 2 * nwaves : gridx, 2 * nwaves, a.dco);
+                       a.log_cursor, a.log_overflow, reg_tables ? 2 * nwaves : gridx, a.dco);
     const bool lds_group = v.nlist <= LM_LDS_NLIST;
     const int qb = LM_PAIRS / np > 0 ? LM_PAIRS / np : 1;
     const unsigned lgrid = (unsigned)((a.nq + qb - 1) / qb);
@@ -1449,10 +1488,10 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(lm_fill_lds_kernel, dim3(lgrid + LM_UNIT_WGS), dim3(256), lds, s, v, a.probe_ids, a.nq,
                            a.nprobe, a.p_first, a.lcount, a.loff, a.lcursor, a.qlist, qb, a.toff,
-                           a.unit_list, a.unit_parts, a.unit_rec);
+                           a.unit_list, a.unit_parts, a.unit_rec, a.log_cursor, starters, waves_each);
     } else {
         hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
-                           a.toff, a.unit_list, a.unit_parts, a.unit_rec);
+                           a.toff, a.unit_list, a.unit_parts, a.unit_rec, a.log_cursor, starters, waves_each);
         hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist);
     }
