@@ -154,18 +154,30 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
         loff[L] = cb;
         toff[L] = tb;
         lcursor[L] = 0;
-        const int nu = units_of(n, v.lists[L].part_cnt, unit_parts);
-        for (int u = 0; u < nu; u++) {
-            unit_list[tb + u] = L;
-            write_unit_rec(v, unit_rec, tb + u, L, tb, cb, n, unit_parts);
-        }
         cb += n;
-        tb += nu;
+        tb += units_of(n, v.lists[L].part_cnt, unit_parts);
     }
     if (tid == 1023) {
         loff[v.nlist] = sc[1023];
         toff[v.nlist] = st[1023];
         *log_cursor = log_first_free((uint32_t)st[1023], starters, waves_each);
+    }
+}
+
+// The unit table of the large-directory route, one thread per list (inside the single workgroup of
+// the prefix kernel these writes took 1.5 ms for 16,384 lists and 100,000 units).
+__global__ __launch_bounds__(256) void lm_units_kernel(IndexView v, const int32_t *__restrict__ lcount,
+                                                       const int32_t *__restrict__ loff,
+                                                       const int32_t *__restrict__ toff,
+                                                       int32_t *unit_list, int unit_parts, int32_t *unit_rec)
+{
+    const int L = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (L >= v.nlist) return;
+    const int n = lcount[L], tb = toff[L], cb = loff[L];
+    const int nu = units_of(n, v.lists[L].part_cnt, unit_parts);
+    for (int u = 0; u < nu; u++) {
+        unit_list[tb + u] = L;
+        write_unit_rec(v, unit_rec, tb + u, L, tb, cb, n, unit_parts);
     }
 }
 
@@ -189,7 +201,7 @@ __global__ void lm_fill_kernel(const int32_t *__restrict__ probe_ids, int64_t nq
 // LM_PAIRS (query, probe) pairs by list in LDS and then touches each list's global counter once,
 // instead of once per pair (a list is probed by hundreds of queries of a batch).
 #define LM_PAIRS 4096
-#define LM_LDS_NLIST 8192
+#define LM_LDS_NLIST 16384
 #define LM_UNIT_WGS 8        // workgroups of the fill kernel that build the unit table
 __global__ __launch_bounds__(256) void lm_count_lds_kernel(const int32_t *__restrict__ probe_ids,
                                                            int64_t nq, int nprobe, int p_first,
@@ -1475,10 +1487,13 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
     const bool lds_group = v.nlist <= LM_LDS_NLIST;
     const int qb = LM_PAIRS / np > 0 ? LM_PAIRS / np : 1;
     const unsigned lgrid = (unsigned)((a.nq + qb - 1) / qb);
-    if (lds_group)
+    if (lds_group) {
+        if ((size_t)v.nlist * 4 > 48 * 1024)
+            RAIRS_HIP(hipFuncSetAttribute((const void *)lm_count_lds_kernel,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, v.nlist * 4));
         hipLaunchKernelGGL(lm_count_lds_kernel, dim3(lgrid), dim3(256), (size_t)v.nlist * 4, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount, qb);
-    else
+    } else
         hipLaunchKernelGGL(lm_count_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.lcount);
     if (lds_group) {
@@ -1492,6 +1507,8 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
     } else {
         hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
                            a.toff, a.unit_list, a.unit_parts, a.unit_rec, a.log_cursor, starters, waves_each);
+        hipLaunchKernelGGL(lm_units_kernel, dim3((unsigned)((v.nlist + 255) / 256)), dim3(256), 0, s, v, a.lcount,
+                           a.loff, a.toff, a.unit_list, a.unit_parts, a.unit_rec);
         hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist);
     }

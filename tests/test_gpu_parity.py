@@ -255,12 +255,12 @@ def test_larger_dimensions_and_u8_raw(binding):
     _compare_all_stages(binding, hx, q, 10, 6, 100)
 
 
-@pytest.mark.parametrize("nlist", [6100, 8300])
+@pytest.mark.parametrize("nlist", [6100, 16384, 16500])
 def test_many_short_lists(binding, nlist):
-    # 6100 lists: the LDS grouping route with more than 48 KB of LDS per workgroup; 8300 lists
-    # (> 8192): queries are grouped by list with global counters and the separate prefix kernel.
-    # The lists are short (one block each).
-    base = datagen.random_vectors(91, 30000, 32)
+    # 6100 and 16,384 lists: the LDS grouping route with more than 48 KB of LDS per workgroup (128 KB
+    # at its limit); 16,500 lists: queries are grouped by list with global counters, the separate
+    # prefix kernel and the unit-table kernel.  The lists are short (one block each).
+    base = datagen.random_vectors(91, 30000 if nlist < 10000 else 60000, 32)
     q = datagen.random_vectors(92, 70, 32)
     hx = ib.build_index(base, nlist, 16, seed=9, coarse_iters=2, pq_iters=4)
     _compare_all_stages(binding, hx, q, 10, 128, 60)
