@@ -168,7 +168,7 @@ int rairs_set_workspace(rairs_index_t *h, void *d_ws, size_t bytes);
  * caller serialises them (one stream, or events).  What must start at zero is cleared by the
  * call's own kernels.
  */
-#define RAIRS_NOALLOC_SCRATCH_BYTES (32u << 20)
+#define RAIRS_NOALLOC_SCRATCH_BYTES (128u << 20)
 int rairs_search_noalloc(rairs_index_t *h, const float *d_queries, int64_t nq, int k, int nprobe,
                          int refine_k, int64_t *d_out_ids, float *d_out_dists, void *hip_stream);
 

@@ -161,7 +161,7 @@ struct ExactScanArgs {
 };
 int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s);
 #define RAIRS_SAMPLE_MAX_BLOCKS 128
-#define RAIRS_LOG_CHUNK 1024        // entries of a chunk of the survivor log
+#define RAIRS_LOG_CHUNK 2048        // entries of a chunk of the survivor log
 // bound of every query from the head of its first probed list
 int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int32_t *probe_ids,
                               int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,

@@ -401,11 +401,11 @@ static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a
 // wave appends them to its current chunk of a global survivor log with plain stores, counts them
 // in the queries' histograms and, for some, lowers the query's bound.  Nothing on this path
 // waits for a returning atomic: the wave owns its chunk, and the next chunk's number is requested
-// long before it is needed (only waves with work
-// own chunks, so the log of a small batch is small).  Chunks of 1,024 entries: with 256 the scan
-// kernel of the 1M x 128 workload took 0.610 ms instead of 0.565 and the collect step issued twice
-// the atomics.  Ids, tags and the duplicate rule are resolved afterwards, in bulk,
-// by collect_kernel and select_kernel.
+// long before it is needed (only waves with work own chunks, so the log of a small batch is
+// small).  Chunks of 2,048 entries: with 256 the scan kernel of the 1M x 128 workload took
+// 0.610 ms instead of 0.558 (1,024 and more: the same) and the collect step, whose atomics go by
+// chunk and query, 49 us instead of 35.  Ids, tags and the duplicate rule are resolved afterwards,
+// in bulk, by collect_kernel and select_kernel.
 #define STAGE_CAP 128              // a multiple of 64 (a flush takes the queue in rows of 64); 192 and 256 measured slower
 static_assert(STAGE_CAP % 64 == 0 && STAGE_CAP >= 128, "stage queue rows");
 #define LOG_CHUNK RAIRS_LOG_CHUNK
@@ -749,8 +749,11 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 // Distribute the survivor log to the per-query buffers (a workgroup takes one chunk at a time).  A chunk holds
 // entries of a few dozen queries; they are grouped in LDS first so that each query's counter is
 // bumped once per chunk, not once per entry.
+#define COLLECT_WG 1024
+#define COLLECT_EPT (LOG_CHUNK / COLLECT_WG)            // entries of a chunk per thread
 #define COLLECT_SLOTS 512
-__global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
+static_assert(LOG_CHUNK % COLLECT_WG == 0, "a chunk is a whole number of entries per thread");
+__global__ __launch_bounds__(COLLECT_WG) void collect_kernel(MfmaScanArgs a)
 {
     __shared__ int32_t key[COLLECT_SLOTS];
     __shared__ uint32_t cnt[COLLECT_SLOTS], base[COLLECT_SLOTS];
@@ -762,34 +765,50 @@ __global__ __launch_bounds__(LOG_CHUNK) void collect_kernel(MfmaScanArgs a)
     if (n == 0) continue;                               // uniform
     if (tid < COLLECT_SLOTS) { key[tid] = -1; cnt[tid] = 0; }
     __syncthreads();
-    uint2 e = make_uint2(0, 0);                         // {slot, score << 16 | query}
-    int slot = -1;
-    uint32_t rank = 0;
+    uint2 e[COLLECT_EPT];                               // {slot, score << 16 | query}
+    int slot[COLLECT_EPT];
+    uint32_t rank[COLLECT_EPT];
     // an entry logged under an earlier, looser bound is dropped when its score is above the
     // query's final bound: it cannot be among the bigK best
-    bool live = false;
-    if (tid < (int)n) {
-        e = a.log[(size_t)c * LOG_CHUNK + tid];
-        live = (int32_t)(e.y >> 16) <= a.bound[e.y & 0xFFFFu];
+    bool live[COLLECT_EPT];
+#pragma unroll
+    for (int k = 0; k < COLLECT_EPT; k++) {
+        const int i = tid + COLLECT_WG * k;
+        e[k] = make_uint2(0, 0);
+        if (i < (int)n) e[k] = a.log[(size_t)c * LOG_CHUNK + i];
     }
-    if (live) {
-        const int qid = (int)(e.y & 0xFFFFu);
-        // open addressing on the query id; a full table falls back to a direct atomic below
-        int h = (int)(((uint32_t)qid * 2654435761u) >> 23);          // 9 bits
-        for (int probe = 0; probe < COLLECT_SLOTS; probe++) {
-            const int prev = atomicCAS(&key[h], -1, qid);
-            if (prev == -1 || prev == qid) { slot = h; break; }
-            h = (h + 1) & (COLLECT_SLOTS - 1);
+#pragma unroll
+    for (int k = 0; k < COLLECT_EPT; k++) {
+        const int i = tid + COLLECT_WG * k;
+        live[k] = i < (int)n && (int32_t)(e[k].y >> 16) <= a.bound[e[k].y & 0xFFFFu];
+        slot[k] = -1;
+        rank[k] = 0;
+    }
+#pragma unroll
+    for (int k = 0; k < COLLECT_EPT; k++) {
+        if (live[k]) {
+            const int qid = (int)(e[k].y & 0xFFFFu);
+            // open addressing on the query id; a full table falls back to a direct atomic below
+            int h = (int)(((uint32_t)qid * 2654435761u) >> 23);          // 9 bits
+            for (int probe = 0; probe < COLLECT_SLOTS; probe++) {
+                const int prev = atomicCAS(&key[h], -1, qid);
+                if (prev == -1 || prev == qid) { slot[k] = h; break; }
+                h = (h + 1) & (COLLECT_SLOTS - 1);
+            }
+            if (slot[k] >= 0) rank[k] = atomicAdd(&cnt[slot[k]], 1u);
         }
-        if (slot >= 0) rank = atomicAdd(&cnt[slot], 1u);
     }
     __syncthreads();
     if (tid < COLLECT_SLOTS && cnt[tid] > 0) base[tid] = atomicAdd(&a.surv_cnt[key[tid]], cnt[tid]);
     __syncthreads();
-    if (live) {
-        const uint32_t qid = e.y & 0xFFFFu;
-        const uint32_t pos = slot >= 0 ? base[slot] + rank : atomicAdd(&a.surv_cnt[qid], 1u);
-        if (pos < (uint32_t)a.surv_cap) a.surv_buf[(size_t)qid * a.surv_cap + pos] = ((uint64_t)(e.y >> 16) << 48) | e.x;
+#pragma unroll
+    for (int k = 0; k < COLLECT_EPT; k++) {
+        if (live[k]) {
+            const uint32_t qid = e[k].y & 0xFFFFu;
+            const uint32_t pos = slot[k] >= 0 ? base[slot[k]] + rank[k] : atomicAdd(&a.surv_cnt[qid], 1u);
+            if (pos < (uint32_t)a.surv_cap)
+                a.surv_buf[(size_t)qid * a.surv_cap + pos] = ((uint64_t)(e[k].y >> 16) << 48) | e[k].x;
+        }
     }
     __syncthreads();                                    // the tables are reused for the next chunk
     }
@@ -1553,7 +1572,7 @@ int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_
 int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
 {
     hipLaunchKernelGGL(collect_kernel, dim3((unsigned)(a.log_chunks < 4096 ? a.log_chunks : 4096)),
-                       dim3(LOG_CHUNK), 0, s, a);
+                       dim3(COLLECT_WG), 0, s, a);
     // the wave kernel's room per query: four times bigK, within [256, SELW_CAP_MAX]
     int cap = next_pow2(4 * a.refine_k);
     cap = cap < 256 ? 256 : (cap > SELW_CAP_MAX ? SELW_CAP_MAX : cap);
