@@ -831,79 +831,151 @@ int rairs_launch_bitmap(const IndexView &v, const int32_t *probe_ids, int64_t nq
 // lookup tables: ComputeLookupTable (Alg. 2) + 8-bit quantisation
 // ---------------------------------------------------------------------------------------------
 
+// A workgroup builds the tables of LUT_QPW queries, one after the other.  A thread owns groups of
+// four consecutive codes of one sub-quantizer (group eg = tid + WG r: sub-quantizer eg / 4, codes
+// 4 (eg % 4) ..+3), so the 16 entries of a sub-quantizer sit in four neighbouring lanes: its
+// offset and width are a minimum and a maximum over those lanes (register moves), the largest
+// width a maximum over the wave and then over the waves (one barrier per query), and a group's
+// four bytes leave as one store.  The codewords of a thread's groups are the same for every query
+// and stay in registers when a sub-vector has at most four dimensions.  The arithmetic per entry
+// is unchanged: squared differences (or products) summed in dimension order.
+#define LUT_QPW 8
+#define LUT_GROUPS_MAX (RAIRS_MAX_M * 4 / WG)           // groups per thread at the largest M
+template <bool IP, int DSUB>                            // DSUB: dimensions of a sub-vector, 0 = any (codewords re-read)
 __global__ __launch_bounds__(WG) void lut_kernel(const float *__restrict__ q,
                                                  const float *__restrict__ codebook, int d, int M,
-                                                 uint8_t *__restrict__ lut,
+                                                 int64_t nq, uint8_t *__restrict__ lut,
                                                  float *__restrict__ bias_sum,
-                                                 float *__restrict__ scale, int metric)
+                                                 float *__restrict__ scale)
 {
-    __shared__ float Ts[RAIRS_MAX_M * 16];
-    __shared__ float bias[RAIRS_MAX_M];
-    __shared__ float width[RAIRS_MAX_M];
-    __shared__ float s_scale;
-    const int tid = threadIdx.x;
-    const int dsub = d / M;
-    const float *qq = q + (size_t)blockIdx.x * d;
-    for (int e = tid; e < M * 16; e += WG) {
-        int m = e >> 4;
-        const float *cw = codebook + (size_t)e * dsub;
-        float a = qq[m * dsub] - cw[0];
-        float acc = metric ? qq[m * dsub] * cw[0] : a * a;
-        for (int t = 1; t < dsub; t++) {
-            float b = qq[m * dsub + t] - cw[t];
-            float sq = metric ? qq[m * dsub + t] * cw[t] : b * b;
-            acc = acc + sq;
+    __shared__ float wave_span[2][WG / 64];             // alternating by query: one barrier per query
+    __shared__ float bias_s[RAIRS_MAX_M];               // only for the stage call's sum of the offsets
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int dsub = DSUB > 0 ? DSUB : d / M;
+    const int ngroups = M * 4;
+    constexpr int CW = DSUB > 0 ? DSUB : 1;
+    float cw[LUT_GROUPS_MAX][4][CW];
+    if (DSUB > 0) {
+#pragma unroll
+        for (int r = 0; r < LUT_GROUPS_MAX; r++) {
+            const int eg = tid + WG * r;
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+#pragma unroll
+                for (int t = 0; t < CW; t++)
+                    cw[r][k][t] = eg < ngroups ? codebook[((size_t)eg * 4 + k) * DSUB + t] : 0.0f;
         }
-        Ts[e] = metric ? -acc : acc;                    // inner product: minus the product, smaller is better
     }
-    __syncthreads();
-    for (int m = tid; m < M; m += WG) {
-        float lo = Ts[m * 16], hi = lo;
-        for (int c = 1; c < 16; c++) {
-            float x = Ts[m * 16 + c];
-            lo = x < lo ? x : lo;
-            hi = x > hi ? x : hi;
+    const int64_t q0 = (int64_t)blockIdx.x * LUT_QPW;
+    for (int qi = 0; qi < LUT_QPW && q0 + qi < nq; qi++) {
+        const int64_t qid = q0 + qi;
+        const float *qq = q + (size_t)qid * d;
+        float T[LUT_GROUPS_MAX][4], lo[LUT_GROUPS_MAX], span = 0.0f;
+#pragma unroll
+        for (int r = 0; r < LUT_GROUPS_MAX; r++) {
+            const int eg = tid + WG * r;
+            lo[r] = 0.0f;
+            if (eg < ngroups) {                         // (r = 0: every thread when M >= 64)
+                const int m = eg >> 2;
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    float acc;
+                    if (DSUB > 0) {
+                        const float x0 = qq[m * DSUB];
+                        const float a = x0 - cw[r][k][0];
+                        acc = IP ? x0 * cw[r][k][0] : a * a;
+#pragma unroll
+                        for (int t = 1; t < CW; t++) {
+                            const float xt = qq[m * DSUB + t];
+                            const float b = xt - cw[r][k][t];
+                            const float sq = IP ? xt * cw[r][k][t] : b * b;
+                            acc = acc + sq;
+                        }
+                    } else {
+                        const float *c = codebook + ((size_t)eg * 4 + k) * dsub;
+                        const float a = qq[m * dsub] - c[0];
+                        acc = IP ? qq[m * dsub] * c[0] : a * a;
+                        for (int t = 1; t < dsub; t++) {
+                            const float b = qq[m * dsub + t] - c[t];
+                            const float sq = IP ? qq[m * dsub + t] * c[t] : b * b;
+                            acc = acc + sq;
+                        }
+                    }
+                    T[r][k] = IP ? -acc : acc;          // inner product: minus the product, smaller is better
+                }
+                float mn = T[r][0], mx = T[r][0];
+#pragma unroll
+                for (int k = 1; k < 4; k++) {
+                    mn = T[r][k] < mn ? T[r][k] : mn;
+                    mx = T[r][k] > mx ? T[r][k] : mx;
+                }
+                // over the four lanes of the sub-quantizer (a minimum and a maximum: order-free)
+                float o = lane_xor1(mn); mn = o < mn ? o : mn;
+                o = lane_xor2(mn); mn = o < mn ? o : mn;
+                o = lane_xor1(mx); mx = o > mx ? o : mx;
+                o = lane_xor2(mx); mx = o > mx ? o : mx;
+                lo[r] = mn;
+                const float width = mx - mn;
+                span = width > span ? width : span;
+                if (bias_sum && (tid & 3) == 0) bias_s[m] = mn;
+            }
         }
-        bias[m] = lo;
-        width[m] = hi - lo;
-    }
-    __syncthreads();
-    if (tid < 64) {
-        // the largest width: a maximum does not depend on the order it is taken in
-        float span = 0.0f;
-        for (int m = tid; m < M; m += 64) span = width[m] > span ? width[m] : span;
+        // the largest width over the workgroup
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
             const float o = __shfl_xor(span, off);
             span = o > span ? o : span;
         }
-        if (tid == 0) {
-            const float s = span > 0.0f ? __fdiv_rn(255.0f, span) : 0.0f;
-            s_scale = s;
-            if (scale) scale[blockIdx.x] = s;
+        float *ws = wave_span[qi & 1];
+        if (lane == 0) ws[wave] = span;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < WG / 64; w++) span = ws[w] > span ? ws[w] : span;
+        const float s = span > 0.0f ? __fdiv_rn(255.0f, span) : 0.0f;
+        if (tid == 0 && scale) scale[qid] = s;
+        if (tid == 64 && bias_sum) {
+            // the sum of the offsets is defined in sub-quantizer order; only the stage call asks for it
+            float bsum = 0.0f;
+            for (int m = 0; m < M; m++) bsum = bsum + bias_s[m];
+            bias_sum[qid] = bsum;
         }
-    } else if (tid == 64 && bias_sum) {
-        // the sum of the offsets is defined in sub-quantizer order; only the stage call asks for it
-        float bsum = 0.0f;
-        for (int m = 0; m < M; m++) bsum = bsum + bias[m];
-        bias_sum[blockIdx.x] = bsum;
-    }
-    __syncthreads();
-    const float s = s_scale;
-    for (int e = tid; e < M * 16; e += WG) {
-        float x = Ts[e] - bias[e >> 4];
-        float y = x * s;
-        float r = rintf(y);
-        r = r > 255.0f ? 255.0f : r;
-        lut[(size_t)blockIdx.x * M * 16 + e] = (uint8_t)r;
+#pragma unroll
+        for (int r = 0; r < LUT_GROUPS_MAX; r++) {
+            const int eg = tid + WG * r;
+            if (eg < ngroups) {
+                uint32_t packed = 0;
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const float x = T[r][k] - lo[r];
+                    const float y = x * s;
+                    float rr = rintf(y);
+                    rr = rr > 255.0f ? 255.0f : rr;
+                    packed |= (uint32_t)rr << (8 * k);
+                }
+                ((uint32_t *)(lut + (size_t)qid * M * 16))[eg] = packed;
+            }
+        }
+        if (bias_sum) __syncthreads();                  // bias_s is rewritten by the next query
     }
 }
 
 int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lut, float *bias_sum,
                      float *scale, hipStream_t s)
 {
-    hipLaunchKernelGGL(lut_kernel, dim3((unsigned)nq), dim3(WG), 0, s, q, v.codebook, v.d, v.M,
-                       lut, bias_sum, scale, v.metric);
+    const dim3 grid((unsigned)((nq + LUT_QPW - 1) / LUT_QPW));
+    const int dsub = v.d / v.M;
+#define LUT_LAUNCH(IP_, DS_)                                                                      \
+    hipLaunchKernelGGL((lut_kernel<IP_, DS_>), grid, dim3(WG), 0, s, q, v.codebook, v.d, v.M, nq, lut, bias_sum, scale)
+#define LUT_METRIC(DS_)                                                                           \
+    do { if (v.metric) LUT_LAUNCH(true, DS_); else LUT_LAUNCH(false, DS_); } while (0)
+    switch (dsub) {
+    case 1: LUT_METRIC(1); break;
+    case 2: LUT_METRIC(2); break;
+    case 4: LUT_METRIC(4); break;
+    default: LUT_METRIC(0); break;
+    }
+#undef LUT_METRIC
+#undef LUT_LAUNCH
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
