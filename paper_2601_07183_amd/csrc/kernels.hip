@@ -1198,7 +1198,9 @@ int rairs_launch_air_assign(const IndexView &v, const float *x, int64_t n, int n
 // and no selects to route ids and flags to the lane that writes the key.)
 // (the metric and the row type are template arguments: as run-time flags they cost a select per
 // element -- both the product and the squared difference were computed -- a third of the loop)
-template <bool IP, typename RowT>
+// (D: the dimension when it is 64, 96 or 128 -- the query's values then stay in registers and the
+// rounds are unrolled with constant offsets -- else 0: any dimension, by loops)
+template <bool IP, typename RowT, int D>
 __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__restrict__ q,
                                                     const int64_t *__restrict__ cand_ids, int64_t nq,
                                                     int refine_k, int k,
@@ -1220,6 +1222,13 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
     constexpr int RU = 2;
     const int n_used = refine_k < n2 ? refine_k : n2;    // candidates that exist; the rest of the keys are empty
     for (int e = n_used + lane; e < n2; e += 64) keys[e] = ~0ull;
+    static_assert(D % 16 == 0, "a known dimension is a whole number of 16-lane rows");
+    constexpr int NQV = D > 0 ? D / 16 : 1;
+    float qreg[NQV];                                     // the query's values of this lane's classes
+    if (D > 0) {
+#pragma unroll
+        for (int t = 0; t < NQV; t++) qreg[t] = qq[l16 + 16 * t];
+    }
     int64_t id_next[RU];
 #pragma unroll
     for (int u = 0; u < RU; u++) id_next[u] = 4 * u + grp < n_used ? my_ids[4 * u + grp] : -1;
@@ -1239,6 +1248,30 @@ __global__ __launch_bounds__(WG) void refine_kernel(IndexView v, const float *__
             row[u] = (const RowT *)v.raw + (size_t)id[u] * v.d;
         }
         int i0 = 0;
+        if (D > 0) {
+            // every (round, class) pair that exists, in dimension order; which exist is known here
+#pragma unroll
+            for (int r = 0; r < (D + 63) / 64; r++) {
+                float x[RU][4];
+#pragma unroll
+                for (int cc = 0; cc < 4; cc++)
+                    if (64 * r + 16 * cc < D)
+#pragma unroll
+                        for (int u = 0; u < RU; u++) x[u][cc] = (float)row[u][64 * r + l16 + 16 * cc];
+#pragma unroll
+                for (int u = 0; u < RU; u++)
+#pragma unroll
+                    for (int cc = 0; cc < 4; cc++)
+                        if (64 * r + 16 * cc < D) {
+                            const float qv = qreg[4 * r + cc];
+                            float sq;
+                            if (IP) sq = qv * x[u][cc];
+                            else { const float diff = qv - x[u][cc]; sq = diff * diff; }
+                            p[u][cc] = p[u][cc] + sq;
+                        }
+            }
+            i0 = D;
+        }
         for (; i0 + 64 <= v.d; i0 += 64) {               // whole rounds of 64 dimensions: no lane checks
             float qv[4], x[RU][4];
 #pragma unroll
@@ -1426,11 +1459,19 @@ int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_
     {
         const dim3 grid((unsigned)((nq + WG / 64 - 1) / (WG / 64)));
         const size_t lds = (size_t)(WG / 64) * n2 * 8;
-#define REFINE_LAUNCH(IP_, ROW_)                                                                  \
-    hipLaunchKernelGGL((refine_kernel<IP_, ROW_>), grid, dim3(WG), lds, s, v, q, cand_ids, nq, refine_k, k, \
+#define REFINE_LAUNCH(IP_, ROW_, D_)                                                              \
+    hipLaunchKernelGGL((refine_kernel<IP_, ROW_, D_>), grid, dim3(WG), lds, s, v, q, cand_ids, nq, refine_k, k, \
                        out_ids, out_dists)
-        if (v.metric) { if (v.raw_u8) REFINE_LAUNCH(true, uint8_t); else REFINE_LAUNCH(true, float); }
-        else          { if (v.raw_u8) REFINE_LAUNCH(false, uint8_t); else REFINE_LAUNCH(false, float); }
+#define REFINE_DIM(IP_, ROW_)                                                                     \
+    do {                                                                                          \
+        if (v.d == 128) REFINE_LAUNCH(IP_, ROW_, 128);                                            \
+        else if (v.d == 96) REFINE_LAUNCH(IP_, ROW_, 96);                                         \
+        else if (v.d == 64) REFINE_LAUNCH(IP_, ROW_, 64);                                         \
+        else REFINE_LAUNCH(IP_, ROW_, 0);                                                         \
+    } while (0)
+        if (v.metric) { if (v.raw_u8) REFINE_DIM(true, uint8_t); else REFINE_DIM(true, float); }
+        else          { if (v.raw_u8) REFINE_DIM(false, uint8_t); else REFINE_DIM(false, float); }
+#undef REFINE_DIM
 #undef REFINE_LAUNCH
     }
     else

@@ -155,6 +155,7 @@ struct ExactScanArgs {
     const uint32_t *bitmap;       // [nq][bmwords]
     int bmwords, nprobe, refine_k;
     const uint32_t *only_flagged; // if set, queries with a zero flag are skipped
+    int any_order;                // the bigK candidates may be written in any order (the whole search: refine orders them anyway)
     int64_t *cand_ids;            // [nq][refine_k]
     int32_t *cand_score;          // [nq][refine_k], may be null
     int64_t *dco;                 // [nq], may be null
@@ -198,6 +199,7 @@ struct MfmaScanArgs {
     int32_t *unit_list;           // [units] list of every work unit
     int32_t *unit_rec;            // [units][8] {list, tile, first segment, end segment, first query of the list in qlist, its queries, 0, 0}
     int unit_parts;               // parts per unit, 1..4
+    int unit_tail_from;           // lists from this one on: single-part units (nlist: none)
     uint32_t *next_task;          // [1]
     const int32_t *tau;           // [nq] bound from the sample (0xFFFF: none); fixes the histogram range
     int32_t *bound;               // [nq] current bound, starts at tau, only decreases
@@ -206,12 +208,13 @@ struct MfmaScanArgs {
     uint64_t *surv_buf;           // [nq][surv_cap]
     int surv_cap;
     uint32_t *flags;              // [nq] set when the survivor buffer overflowed
-    uint2 *log;                   // [log_chunks][256] survivor log {slot, score << 16 | query of the pass}
+    uint2 *log;                   // [log_chunks][RAIRS_LOG_CHUNK] survivor log {slot, score << 16 | query of the pass}
     uint32_t *chunk_fill;         // [log_chunks] entries written to each chunk
     uint32_t *log_cursor;         // [1] chunks handed out
     uint32_t *log_overflow;       // [1] set if the log ran out of chunks
     int log_chunks;
     unsigned long long *dco;      // [nq] items scored per query, counted as blocks are contracted; may be null
+    int any_order;                // the bigK candidates may be written in any order (the whole search: refine orders them anyway)
     int64_t *cand_ids;            // [nq][refine_k]
     int32_t *cand_score;          // may be null
 };

@@ -92,6 +92,14 @@ __global__ void lm_count_kernel(const int32_t *__restrict__ probe_ids, int64_t n
 // parts of the list; a part is about 32 blocks, unit_parts is 1..4, smaller when there is little
 // work).  Exclusive prefixes over lists of queries (loff) and units
 // (toff), and the list of every unit; one workgroup of 1024.
+// Parts per unit of list L: the lists from `tail_from` on are cut into single parts.  Waves take
+// units in order, so the last ones taken are small and the waves finish closer together (the
+// kernel ends with its slowest wave, and a two-part unit is 0.08 ms of work on the 1M x 128 workload).
+static __device__ __forceinline__ int list_unit_parts(int L, int unit_parts, int tail_from)
+{
+    return L >= tail_from ? 1 : unit_parts;
+}
+
 static __device__ __forceinline__ int units_of(int nqueries, int part_cnt, int unit_parts)
 {
     return ((nqueries + 31) >> 5) * ((part_cnt + unit_parts - 1) / unit_parts);
@@ -120,7 +128,7 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
                                                          const int32_t *__restrict__ lcount,
                                                          int32_t *loff, int32_t *lcursor,
                                                          int32_t *toff, int32_t *unit_list,
-                                                         int unit_parts, int32_t *unit_rec,
+                                                         int unit_parts, int tail_from, int32_t *unit_rec,
                                                          uint32_t *log_cursor, uint32_t starters, uint32_t waves_each)
 {
     __shared__ int sc[1024], st[1024];
@@ -135,7 +143,7 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
     for (int L = lo; L < hi; L++) {
         int n = lcount[L];
         c += n;
-        t += units_of(n, v.lists[L].part_cnt, unit_parts);
+        t += units_of(n, v.lists[L].part_cnt, list_unit_parts(L, unit_parts, tail_from));
     }
     sc[tid] = c;
     st[tid] = t;
@@ -155,7 +163,7 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
         toff[L] = tb;
         lcursor[L] = 0;
         cb += n;
-        tb += units_of(n, v.lists[L].part_cnt, unit_parts);
+        tb += units_of(n, v.lists[L].part_cnt, list_unit_parts(L, unit_parts, tail_from));
     }
     if (tid == 1023) {
         loff[v.nlist] = sc[1023];
@@ -169,15 +177,17 @@ __global__ __launch_bounds__(1024) void lm_prefix_kernel(IndexView v,
 __global__ __launch_bounds__(256) void lm_units_kernel(IndexView v, const int32_t *__restrict__ lcount,
                                                        const int32_t *__restrict__ loff,
                                                        const int32_t *__restrict__ toff,
-                                                       int32_t *unit_list, int unit_parts, int32_t *unit_rec)
+                                                       int32_t *unit_list, int unit_parts, int tail_from,
+                                                       int32_t *unit_rec)
 {
     const int L = (int)(blockIdx.x * blockDim.x + threadIdx.x);
     if (L >= v.nlist) return;
     const int n = lcount[L], tb = toff[L], cb = loff[L];
-    const int nu = units_of(n, v.lists[L].part_cnt, unit_parts);
+    const int up = list_unit_parts(L, unit_parts, tail_from);
+    const int nu = units_of(n, v.lists[L].part_cnt, up);
     for (int u = 0; u < nu; u++) {
         unit_list[tb + u] = L;
-        write_unit_rec(v, unit_rec, tb + u, L, tb, cb, n, unit_parts);
+        write_unit_rec(v, unit_rec, tb + u, L, tb, cb, n, up);
     }
 }
 
@@ -262,7 +272,7 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(IndexView v, const int
                                                           const int32_t *__restrict__ lcount,
                                                           int32_t *loff, int32_t *lcursor, int32_t *qlist,
                                                           int qb, int32_t *toff, int32_t *unit_list,
-                                                          int unit_parts, int32_t *unit_rec,
+                                                          int unit_parts, int tail_from, int32_t *unit_rec,
                                                           uint32_t *log_cursor, uint32_t starters, uint32_t waves_each)
 {
     extern __shared__ int32_t lm_lds[];                // [nlist] ranks / run starts, [nlist + 1] offsets
@@ -295,12 +305,12 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(IndexView v, const int
             for (int L = lo; L < hi; L++) loff[L] = loff_s[L];
         }
         int mine = 0;
-        for (int L = lo; L < hi; L++) mine += units_of(lcount[L], v.lists[L].part_cnt, unit_parts);
+        for (int L = lo; L < hi; L++) mine += units_of(lcount[L], v.lists[L].part_cnt, list_unit_parts(L, unit_parts, tail_from));
         int run = wg256_exclusive(mine, wsum, &total);
         for (int L = lo; L < hi; L++) {
             toff_s[L] = run;
             if (ub == 0) toff[L] = run;
-            run += units_of(lcount[L], v.lists[L].part_cnt, unit_parts);
+            run += units_of(lcount[L], v.lists[L].part_cnt, list_unit_parts(L, unit_parts, tail_from));
         }
         __syncthreads();
         const int nunits = total;
@@ -318,7 +328,7 @@ __global__ __launch_bounds__(256) void lm_fill_lds_kernel(IndexView v, const int
                 if (toff_s[mid] <= e) a0 = mid; else b0 = mid - 1;
             }
             unit_list[e] = a0;
-            write_unit_rec(v, unit_rec, e, a0, toff_s[a0], loff_s[a0], lcount[a0], unit_parts);
+            write_unit_rec(v, unit_rec, e, a0, toff_s[a0], loff_s[a0], lcount[a0], list_unit_parts(a0, unit_parts, tail_from));
         }
         return;
     }
@@ -819,6 +829,7 @@ __global__ __launch_bounds__(COLLECT_WG) void collect_kernel(MfmaScanArgs a)
 // writes the bigK smallest.  No workgroup barrier is used: a wave only touches its own region, and
 // LDS operations of one wave complete in issue order.
 #define SELW_CAP_MAX 1024
+#define SELW_STRIKE_MAX 8           // ties beyond bigK that are struck out one by one; more: a full sort
 template <int NU>
 static __device__ __forceinline__ uint32_t selw_cut(const uint64_t (&mine)[SELW_CAP_MAX / 64], uint32_t k)
 {
@@ -915,6 +926,41 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
             if (in) keys[m + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull))] = mine[u];
             m += (uint32_t)__popcll(bal);
         }
+    }
+    // The whole search does not need the candidates in order (refine orders by exact distance):
+    // of the m entries up to the cut all but m - bigK are results, and those few -- entries that
+    // tie on the cut's score -- are struck out largest (score, id) first.
+    if (a.any_order && (int)m - a.refine_k <= SELW_STRIKE_MAX) {
+        wave_lds_sync();
+        for (int extra = (int)m - a.refine_k; extra > 0; extra--) {
+            uint64_t mine_max = 0ull;
+            for (int i = lane; i < (int)m; i += 64) {
+                const uint64_t x = keys[i];
+                if (x != ~0ull && x > mine_max) mine_max = x;
+            }
+            const uint64_t largest = ~wave_min_u64(~mine_max);
+            for (int i = lane; i < (int)m; i += 64)
+                if (keys[i] == largest) keys[i] = ~0ull;     // keys are distinct: one lane, one slot
+            wave_lds_sync();
+        }
+        uint32_t out = 0;
+        for (int i0 = 0; i0 < (int)m; i0 += 64) {
+            const int i = i0 + lane;
+            const uint64_t key = i < (int)m ? keys[i] : ~0ull;
+            const bool ok = key != ~0ull;
+            const unsigned long long bal = __ballot(ok);
+            if (ok) {
+                const uint32_t pos = out + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+                a.cand_ids[(size_t)q * a.refine_k + pos] = (int64_t)(uint32_t)key;
+                if (a.cand_score) a.cand_score[(size_t)q * a.refine_k + pos] = (int32_t)(key >> 32);
+            }
+            out += (uint32_t)__popcll(bal);
+        }
+        for (int i = (int)out + lane; i < a.refine_k; i += 64) {   // fewer than bigK entries exist
+            a.cand_ids[(size_t)q * a.refine_k + i] = -1;
+            if (a.cand_score) a.cand_score[(size_t)q * a.refine_k + i] = -1;
+        }
+        return;
     }
     const int n2 = next_pow2(m < 2 ? 2 : (int)m);
     for (int i = (int)m + lane; i < n2; i += 64) keys[i] = ~0ull;
@@ -1064,10 +1110,11 @@ __global__ __launch_bounds__(1024, 1) void scan_mfma_lds_kernel(IndexView v, Mfm
         const int L = a.unit_list[u];
         const ListEntry le = v.lists[L];
         const int rem = (int)u - a.toff[L];
-        const int runs = (le.part_cnt + a.unit_parts - 1) / a.unit_parts;
+        const int up = list_unit_parts(L, a.unit_parts, a.unit_tail_from);
+        const int runs = (le.part_cnt + up - 1) / up;
         const int tile = rem / runs;
-        const int p0 = (rem % runs) * a.unit_parts;
-        const int p1 = p0 + a.unit_parts < le.part_cnt ? p0 + a.unit_parts : le.part_cnt;
+        const int p0 = (rem % runs) * up;
+        const int p1 = p0 + up < le.part_cnt ? p0 + up : le.part_cnt;
         const int seg0 = v.parts[le.part_begin + p0] - le.seg_begin;
         const int seg1 = v.parts[le.part_begin + p1] - le.seg_begin;
         const int base = a.loff[L], nql = a.loff[L + 1] - base;
@@ -1522,12 +1569,12 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(lm_fill_lds_kernel, dim3(lgrid + LM_UNIT_WGS), dim3(256), lds, s, v, a.probe_ids, a.nq,
                            a.nprobe, a.p_first, a.lcount, a.loff, a.lcursor, a.qlist, qb, a.toff,
-                           a.unit_list, a.unit_parts, a.unit_rec, a.log_cursor, starters, waves_each);
+                           a.unit_list, a.unit_parts, a.unit_tail_from, a.unit_rec, a.log_cursor, starters, waves_each);
     } else {
         hipLaunchKernelGGL(lm_prefix_kernel, dim3(1), dim3(1024), 0, s, v, a.lcount, a.loff, a.lcursor,
-                           a.toff, a.unit_list, a.unit_parts, a.unit_rec, a.log_cursor, starters, waves_each);
+                           a.toff, a.unit_list, a.unit_parts, a.unit_tail_from, a.unit_rec, a.log_cursor, starters, waves_each);
         hipLaunchKernelGGL(lm_units_kernel, dim3((unsigned)((v.nlist + 255) / 256)), dim3(256), 0, s, v, a.lcount,
-                           a.loff, a.toff, a.unit_list, a.unit_parts, a.unit_rec);
+                           a.loff, a.toff, a.unit_list, a.unit_parts, a.unit_tail_from, a.unit_rec);
         hipLaunchKernelGGL(lm_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
                            a.probe_ids, a.nq, a.nprobe, a.p_first, v.nlist, a.loff, a.lcursor, a.qlist);
     }
