@@ -813,11 +813,18 @@ static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t 
         // with the tables in LDS a whole workgroup shares a unit and reloads up to 128 KB of
         // tables for each: always the longest units
         if (!(v.T == 8 || v.T == 24 || v.T == 32)) ma.unit_parts = 4;
-        // the last third of the lists in single parts, so that the kernel's last units are small
-        // (1M x 128 workload, kernel: none 0.560 ms, last eighth 0.558, fifth 0.551, third 0.542,
-        // half 0.546)
+        // The last lists in single parts, so that the kernel's last units are small: as many lists
+        // as hold about 1.3 units for each of the 2,048 waves, at most a third.  (1M x 128
+        // workload, 8,200 two-part units, kernel: none 0.560 ms, last eighth 0.558, fifth 0.551,
+        // third 0.542, half 0.546; a third of the 100M workload's 129,000 four-part units: 11.7 ms
+        // against 11.1.)
         ma.unit_tail_from = v.nlist;
-        if (ma.unit_parts > 1 && (v.T == 8 || v.T == 24 || v.T == 32)) ma.unit_tail_from = v.nlist - v.nlist / 3;
+        if (ma.unit_parts > 1 && (v.T == 8 || v.T == 24 || v.T == 32)) {
+            const double units = (double)parts_total / ma.unit_parts;
+            double f = units > 0 ? 1.3 * 2048 / units : 0.0;
+            f = f > 1.0 / 3 ? 1.0 / 3 : f;
+            ma.unit_tail_from = v.nlist - (int)(v.nlist * f);
+        }
     }
     ma.next_task = (uint32_t *)(ws + w.next_task); ma.qlist = (int32_t *)(ws + w.qlist);
     ma.tau = (int32_t *)(ws + w.tau); ma.surv_cnt = (uint32_t *)(ws + w.surv_cnt);
