@@ -501,6 +501,8 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
     bool have = false;
     if (nsamp > 0 && margin_ok) {
         // est: the ksamp-th smallest of the sample, by bisection on the key bits (keys in registers)
+        // (fetching the row's first 1,024 keys once, for the sample and for the gathering pass
+        // below, was slower: 16 more registers held across the bisection)
         uint32_t ks[SHORTLIST_SAMPLE / 64];
 #pragma unroll
         for (int u = 0; u < SHORTLIST_SAMPLE / 64; u++) {
@@ -537,7 +539,40 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
                 ng += (uint32_t)__popcll(m);
             }
         }
-        if (ng >= (uint32_t)nprobe && ng <= (uint32_t)cap) {
+        if (ng >= (uint32_t)nprobe && ng <= 256u && ng <= (uint32_t)cap) {
+            // few entries: no sort.  They go back into registers, the nprobe-th smallest key is
+            // found bit by bit, and the entries up to the widened threshold are packed.
+            wave_lds_sync();
+            uint64_t mine[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const uint32_t i = 64u * u + lane;
+                mine[u] = i < ng ? sel[i] : ~0ull;
+            }
+            uint32_t kth = 0;                            // largest t with fewer than nprobe keys below it
+            for (int bit = 31; bit >= 0; bit--) {
+                const uint32_t cand = kth | (1u << bit);
+                uint32_t below = 0;
+#pragma unroll
+                for (int u = 0; u < 4; u++)
+                    if (64u * u < ng) below += (uint32_t)__popcll(__ballot((uint32_t)(mine[u] >> 32) < cand));
+                if (below < (uint32_t)nprobe) kth = cand;
+            }
+            const uint32_t thr = f32_key(key_f32(kth) + margin);
+            if (thr <= est) {
+                wave_lds_sync();                         // every lane holds its entries
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    if (64u * u < ng) {
+                        const bool in = 64u * u + lane < ng && (uint32_t)(mine[u] >> 32) <= thr;
+                        const unsigned long long m = __ballot(in);
+                        if (in) sel[nc + (uint32_t)__popcll(m & lt_mask)] = (uint64_t)(uint32_t)mine[u];
+                        nc += (uint32_t)__popcll(m);
+                    }
+                }
+                have = true;
+            }
+        } else if (ng >= (uint32_t)nprobe && ng <= (uint32_t)cap) {
             const int n2 = next_pow2((int)ng < 2 ? 2 : (int)ng);
             for (int e = (int)ng + lane; e < n2; e += 64) sel[e] = ~0ull;
             wave_lds_sync();
@@ -695,6 +730,21 @@ __global__ __launch_bounds__(WG) void coarse_shortlist_kernel(const uint32_t *__
             }
             wave_lds_sync();
         }
+    }
+    if (nc <= 64u) {
+        // a lane per list: its place in the (distance, list id) order is the number of smaller keys
+        wave_lds_sync();
+        const uint64_t mine = lane < (int)nc ? sel[lane] : ~0ull;
+        int rank = 0;
+        for (int j = 0; j < (int)nc; j++) rank += sel[j] < mine ? 1 : 0;      // one address: a broadcast
+        if (fits && lane < (int)nc && rank < nprobe) {
+            probe_ids[(size_t)qi * nprobe + rank] = (int32_t)(uint32_t)mine;
+            if (probe_dists) {
+                const float sc = key_f32((uint32_t)(mine >> 32));
+                probe_dists[(size_t)qi * nprobe + rank] = IP ? -sc : sc;
+            }
+        }
+        return;
     }
     const int n2 = next_pow2((int)nc < 2 ? 2 : (int)nc);
     for (int e = (int)nc + lane; e < n2; e += 64) sel[e] = ~0ull;
