@@ -763,6 +763,7 @@ __global__ __launch_bounds__(WG, 2) void scan_mfma_kernel(IndexView v, MfmaScanA
 #define COLLECT_EPT (LOG_CHUNK / COLLECT_WG)            // entries of a chunk per thread
 #define COLLECT_SLOTS 512
 static_assert(LOG_CHUNK % COLLECT_WG == 0, "a chunk is a whole number of entries per thread");
+static_assert(COLLECT_WG >= COLLECT_SLOTS, "a thread per slot clears and publishes the tables");
 __global__ __launch_bounds__(COLLECT_WG) void collect_kernel(MfmaScanArgs a)
 {
     __shared__ int32_t key[COLLECT_SLOTS];
