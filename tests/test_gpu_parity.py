@@ -381,6 +381,28 @@ def test_inner_product_metric_with_soar_assignment(binding, d, M, integer):
         ix.free()
 
 
+@pytest.mark.parametrize("d,M,metric", [(16, 16, "l2"), (24, 8, "l2"), (64, 16, "ip"), (80, 10, "l2"),
+                                        (768, 192, "l2"), (96, 24, "ip")])
+def test_lookup_tables_for_every_sub_vector_size(binding, d, M, metric):
+    # the table kernel keeps the codewords in registers for sub-vectors of 1, 2 and 4 dimensions
+    # and re-reads them otherwise (3 and 8 here); M = 192 gives a thread three groups of codes;
+    # more queries than one workgroup takes, and a count that is not a multiple of it
+    base = datagen.random_vectors(600 + d, 1500, d)
+    q = datagen.random_vectors(601 + d, 21, d)
+    hx = ib.build_index(base, 8, M, seed=5, coarse_iters=2, pq_iters=3, metric=metric)
+    ox = oracle.OracleIndex(hx)
+    ix = binding.Index(hx)
+    try:
+        lut, bias, scale = ix.lut(_dev(q))
+        torch.cuda.synchronize()
+        for i in range(len(q)):
+            _, ol, ob, osc = oracle.lut(ox, q[i])
+            assert (lut[i].cpu().numpy().reshape(-1) == np.asarray(ol).reshape(-1)).all(), i
+            assert bias[i].item() == np.float32(ob) and scale[i].item() == np.float32(osc), i
+    finally:
+        ix.free()
+
+
 @pytest.mark.parametrize("d,integer,metric", [(128, True, "l2"), (96, False, "l2"), (200, False, "ip"),
                                               (64, True, "ip")])
 def test_refine_one_wave_per_query(binding, d, integer, metric):
