@@ -54,6 +54,7 @@ static void destroy(rairs_index *h)
     if (h->side_ready) {
         (void)hipEventDestroy(h->ev_fork); (void)hipEventDestroy(h->ev_lut);
         (void)hipEventDestroy(h->ev_probe); (void)hipEventDestroy(h->ev_group);
+        (void)hipEventDestroy(h->ev_scored);
         (void)hipStreamDestroy(h->side);
     }
     delete h;
@@ -463,6 +464,7 @@ static int upload_impl(const rairs_host_index_t *x, void *hip_stream, rairs_inde
     UP_HIP(hipEventCreateWithFlags(&h->ev_lut, hipEventDisableTiming));
     UP_HIP(hipEventCreateWithFlags(&h->ev_probe, hipEventDisableTiming));
     UP_HIP(hipEventCreateWithFlags(&h->ev_group, hipEventDisableTiming));
+    UP_HIP(hipEventCreateWithFlags(&h->ev_scored, hipEventDisableTiming));
     h->side_ready = 1;
     *made = nullptr;
     *out = h;
@@ -520,7 +522,7 @@ static int log_per_query_for(int refine_k)
 struct WsLayout {
     size_t dmat, cflags, probe_ids, probe_dists, bitmap, lut, cand, dco;
     size_t lcount, loff, lcursor, toff, unit_list, unit_rec, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, total;
-    size_t s_off, s_toff, s_q, s_tiles, s_scores;      // matrix-core sample (0 bytes when not used)
+    size_t s_off, s_toff, s_q, s_tiles, s_scores, s_first;      // matrix-core sample (0 bytes when not used)
     int sample_blocks;
     int log_chunks;
     int surv_cap;
@@ -602,6 +604,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int64_t nq_total, int 
     w.s_off = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
     w.s_toff = take(grouped ? (size_t)(v.nlist + 1) * 4 : 0);
     w.s_q = take(grouped ? (size_t)nq * 4 : 0);
+    w.s_first = take(grouped ? (size_t)nq * 4 : 0);
     w.s_tiles = take(grouped ? ((size_t)nq / 32 + (size_t)v.nlist + 1) * 4 : 0);
     const size_t dmat_bytes = (size_t)nq * v.nlist * 4, log_bytes = (size_t)w.log_chunks * RAIRS_LOG_CHUNK * 8;
     w.dmat = w.log = take(dmat_bytes > log_bytes ? dmat_bytes : log_bytes);
@@ -765,10 +768,14 @@ static_assert(EV_KERNEL1 < 2 * RAIRS_NSTAGES, "event slots");
 static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t *lut, const int32_t *probe_ids,
                      int64_t n, int nprobe, int refine_k, int64_t *cand_ids, int32_t *cand_score,
                      int64_t *dco, hipStream_t s, hipEvent_t *ev, bool overlap, hipEvent_t lut_done,
-                     bool any_order)
+                     bool any_order, hipEvent_t probed_on_side = nullptr)
 {
     // overlap: the tables were built on the side stream (ev_lut marks them done) and the side
-    // stream already waits for the probe lists; the grouping runs there next to the sample bound
+    // stream already waits for the probe lists; the grouping runs there next to the sample bound.
+    // probed_on_side (may be null; implies the matrix-core sample): the probe lists are being
+    // made on the side stream too, marked done by this event, and the caller's stream has only
+    // the score matrix so far: the sample is taken from the list with the smallest key of the
+    // query's row, and only its ranking waits for the probe lists (see search_impl).
     const IndexView &v = h->v;
     uint32_t *bitmap = (uint32_t *)(ws + w.bitmap);
     const bool mfma = rairs_mfma_supported(v) && !h->force_exact;
@@ -852,7 +859,20 @@ static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t 
         if ((rc = rairs_launch_group(v, ma, h->side))) return rc;
         RAIRS_HIP(hipEventRecord(h->ev_group, h->side));
     }
-    if (grouped) {
+    if (grouped && probed_on_side) {
+        int32_t *s_first = (int32_t *)(ws + w.s_first);
+        if ((rc = rairs_launch_coarse_first(v, (const float *)(ws + w.dmat), n, s_first, s))) return rc;
+        if ((rc = rairs_launch_sample_group(v, s_first, 1, n, s_off, s_toff, s_q, s_tiles, s))) return rc;
+        RAIRS_HIP(hipStreamWaitEvent(s, lut_done, 0));
+        if ((rc = rairs_launch_sample_scores(v, lut, sample_blocks, n, s_off, s_toff, s_q, s_tiles, s_scores, s)))
+            return rc;
+        // the ranking checks that the sampled list is one of the query's probe lists (the keys
+        // carry rounding, and a bound from a list that is not scanned would be no bound)
+        RAIRS_HIP(hipStreamWaitEvent(s, probed_on_side, 0));
+        if ((rc = rairs_launch_sample_rank(v, s_first, 1, refine_k, sample_blocks, n, s_scores,
+                                           (int32_t *)(ws + w.tau), ma.bound, s, probe_ids, nprobe)))
+            return rc;
+    } else if (grouped) {
         if ((rc = rairs_launch_sample_group(v, probe_ids, nprobe, n, s_off, s_toff, s_q, s_tiles, s)))
             return rc;
         if (side_bitmap) RAIRS_HIP(hipStreamWaitEvent(s, lut_done, 0));
@@ -967,12 +987,23 @@ static int search_impl(rairs_index *h, int ws_source, const float *d_queries, in
             if ((rc = rairs_launch_lut(v, q, n, lut, nullptr, nullptr, side))) return rc;
             RAIRS_HIP(hipEventRecord(prof ? ev[EV_LUT1] : h->ev_lut, side));
         }
+        // With the matrix-core sample, the caller's stream does not wait for the probe lists:
+        // once the coarse GEMM has left the score matrix, the selection of the probe lists moves
+        // to the side stream (behind the table build, ahead of the grouping), and the caller's
+        // stream goes straight on with the bound's sample, taken from the list with the smallest
+        // key of the query's row; see scan_pass.  The chain that the scan waits for -- GEMM,
+        // sample, ranking -- thus stays on one stream, with no event hop in it.
+        const bool early = overlap && !h->force_exact && rairs_mfma_supported(v) &&
+                           grouped_sample(v, n, refine_k) && rairs_coarse_has_scores(v, nprobe, q);
         if ((rc = rairs_launch_coarse(v, q, n, nprobe, (float *)(ws + w.dmat), probe_ids,
-                                      (float *)(ws + w.probe_dists), (uint32_t *)(ws + w.cflags), s)))
+                                      (float *)(ws + w.probe_dists), (uint32_t *)(ws + w.cflags), s,
+                                      early ? h->ev_scored : nullptr, early ? side : nullptr)))
             return rc;
         hipEvent_t probed = prof ? ev[EV_PROBED] : h->ev_probe;
-        if (overlap || prof) RAIRS_HIP(hipEventRecord(probed, s));
-        if (overlap) {
+        if (overlap || prof) RAIRS_HIP(hipEventRecord(probed, early ? side : s));
+        if (early) {
+            // (the side stream made the probe lists itself)
+        } else if (overlap) {
             RAIRS_HIP(hipStreamWaitEvent(side, probed, 0));
         } else {
             // one stream: the table build is timed between the coarse stage and the scan stage
@@ -981,7 +1012,7 @@ static int search_impl(rairs_index *h, int ws_source, const float *d_queries, in
         }
         if ((rc = scan_pass(h, ws, w, lut, probe_ids, n, nprobe, refine_k, cand, nullptr, dco_all + q0, s,
                             profk ? &ev[EV_KERNEL0] : nullptr, overlap,
-                            prof ? ev[EV_LUT1] : h->ev_lut, true))) return rc;
+                            prof ? ev[EV_LUT1] : h->ev_lut, true, early ? probed : nullptr))) return rc;
         if (prof) RAIRS_HIP(hipEventRecord(ev[EV_SCANNED], s));
         if ((rc = rairs_launch_refine(v, q, cand, n, refine_k, k, d_out_ids + (size_t)q0 * k,
                                       d_out_dists + (size_t)q0 * k, s))) return rc;

@@ -767,8 +767,52 @@ static bool coarse_shortlist_ok(const IndexView &v, int nprobe)
     return v.d % 8 == 0 && nprobe <= SHORTLIST_MAX_NPROBE && v.nlist >= 64;
 }
 
+// The list with the smallest key of every query's row of the score matrix: where the bound's sample
+// is taken when it is to start before the probe lists exist.  The keys carry the matrix core's
+// rounding, so this list is nearly always, but not provably, the nearest; whoever uses it checks
+// that it is among the query's probe lists.  One wave per query.
+__global__ __launch_bounds__(WG) void coarse_first_kernel(const uint32_t *__restrict__ keys, int nlist,
+                                                          int64_t nq, int32_t *__restrict__ first)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + (threadIdx.x >> 6);
+    if (qi >= nq) return;
+    const uint32_t *row = keys + (size_t)qi * nlist;
+    uint64_t best = ~0ull;
+    for (int l0 = 0; l0 < nlist; l0 += 64 * 16) {
+        uint32_t kk[16];
+#pragma unroll
+        for (int u = 0; u < 16; u++) {
+            const int l = l0 + 64 * u + lane;
+            kk[u] = row[l < nlist ? l : nlist - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < 16; u++) {
+            const int l = l0 + 64 * u + lane;
+            const uint64_t x = ((uint64_t)kk[u] << 32) | (uint32_t)l;
+            if (l < nlist && x < best) best = x;
+        }
+    }
+    best = wave_min_u64(best);
+    if (lane == 0) first[qi] = (int32_t)(uint32_t)best;
+}
+
+bool rairs_coarse_has_scores(const IndexView &v, int nprobe, const float *q)
+{
+    return coarse_shortlist_ok(v, nprobe) && ((uintptr_t)q & 15) == 0;
+}
+
+int rairs_launch_coarse_first(const IndexView &v, const float *dmat, int64_t nq, int32_t *first, hipStream_t s)
+{
+    hipLaunchKernelGGL(coarse_first_kernel, dim3((unsigned)((nq + WG / 64 - 1) / (WG / 64))), dim3(WG), 0, s,
+                       (const uint32_t *)dmat, v.nlist, nq, first);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
 int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,
-                        int32_t *probe_ids, float *probe_dists, uint32_t *flags, hipStream_t s)
+                        int32_t *probe_ids, float *probe_dists, uint32_t *flags, hipStream_t s,
+                        hipEvent_t scored, hipStream_t s_select)
 {
     const int groups = (v.nlist + WG - 1) / WG;
     if (!coarse_shortlist_ok(v, nprobe) || !flags || ((uintptr_t)q & 15) != 0) {
@@ -815,6 +859,12 @@ int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int npro
     }
     }
 #undef GEMM_CASE
+    if (scored) {
+        // the score matrix is complete; the selection goes on on the other stream
+        RAIRS_HIP(hipEventRecord(scored, s));
+        RAIRS_HIP(hipStreamWaitEvent(s_select, scored, 0));
+        s = s_select;
+    }
     // LDS room per query: the lists inside the margin (half more than nprobe, at least 64), or,
     // when the sample route is used, the keys up to the sample's estimate (about 2-4 x nprobe)
     const int extra = nprobe / 2 > 64 ? nprobe / 2 : 64;

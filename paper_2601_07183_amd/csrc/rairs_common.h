@@ -114,7 +114,7 @@ struct rairs_index {
     // a second stream for the steps that do not depend on each other (tables next to the coarse
     // quantizer, grouping next to the sample bound), forked from and joined to the caller's stream
     hipStream_t side;
-    hipEvent_t ev_fork, ev_lut, ev_probe, ev_group;
+    hipEvent_t ev_fork, ev_lut, ev_probe, ev_group, ev_scored;
     int side_ready;
 };
 
@@ -136,8 +136,15 @@ int rairs_launch_pack(const uint8_t *d_codes_host_layout, const int64_t *d_ids64
 int rairs_launch_pair_ids(const uint32_t *ids, const int32_t *other, int64_t n, uint2 *out, hipStream_t s);
 int rairs_launch_transpose(const float *d_in, int rows, int cols, float *d_out, hipStream_t s);
 // dmat: [nq][nlist] words of scratch; flags: [nq] words of scratch (null: full route only)
+// scored (may be null; only with rairs_coarse_has_scores): recorded on s once the score matrix of
+// the matrix-core route is complete; the selection kernels then run on s_select behind it
 int rairs_launch_coarse(const IndexView &v, const float *q, int64_t nq, int nprobe, float *dmat,
-                        int32_t *probe_ids, float *probe_dists, uint32_t *flags, hipStream_t s);
+                        int32_t *probe_ids, float *probe_dists, uint32_t *flags, hipStream_t s,
+                        hipEvent_t scored = nullptr, hipStream_t s_select = nullptr);
+// whether rairs_launch_coarse takes the matrix-core route for these arguments (given flags), i.e.
+// leaves the keys of all (query, list) pairs in dmat; and the list of each row's smallest key
+bool rairs_coarse_has_scores(const IndexView &v, int nprobe, const float *q);
+int rairs_launch_coarse_first(const IndexView &v, const float *dmat, int64_t nq, int32_t *first, hipStream_t s);
 int rairs_launch_bitmap(const IndexView &v, const int32_t *probe_ids, int64_t nq, int nprobe,
                         uint32_t *bitmap, int bmwords, uint32_t *hist, hipStream_t s);
 int rairs_launch_lut(const IndexView &v, const float *q, int64_t nq, uint8_t *lut, float *bias_sum,
@@ -168,9 +175,12 @@ int rairs_launch_sample_bound(const IndexView &v, const uint8_t *lut, const int3
                               int nprobe, int refine_k, int sample_blocks, int64_t nq, int32_t *tau,
                               int32_t *bound, hipStream_t s);
 // the same bound from scores that rairs_launch_sample_scores wrote
-int rairs_launch_sample_rank(const IndexView &v, const int32_t *probe_ids, int nprobe, int refine_k,
+// (the sampled list of query q is first[q * stride]; with check_ids, a query whose sampled list is
+// not among its check_n probe lists gets no bound)
+int rairs_launch_sample_rank(const IndexView &v, const int32_t *first, int stride, int refine_k,
                              int sample_blocks, int64_t nq, const uint16_t *pre, int32_t *tau,
-                             int32_t *bound, hipStream_t s);
+                             int32_t *bound, hipStream_t s, const int32_t *check_ids = nullptr,
+                             int check_n = 0);
 // Scores of the sample by the matrix cores: the queries are grouped by their first probed list, a
 // wave scores the head of a list for a tile of up to 32 of them.  Workspace: s_cnt [nlist],
 // s_off [nlist + 1], s_toff [nlist + 1], s_q [nq], s_tiles [nq / 32 + nlist].

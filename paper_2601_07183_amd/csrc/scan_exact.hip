@@ -313,12 +313,20 @@ __global__ __launch_bounds__(WG) void sample_rank_kernel(IndexView v, const int3
                                                          int nprobe, int refine_k, int sample_blocks,
                                                          int64_t nq, const uint16_t *__restrict__ pre,
                                                          int32_t *__restrict__ tau,
-                                                         int32_t *__restrict__ bound)
+                                                         int32_t *__restrict__ bound,
+                                                         const int32_t *__restrict__ check_ids, int check_n)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t qi = (int64_t)blockIdx.x * (WG / 64) + wave;
     if (qi >= nq) return;
-    const int L = probe_ids[(size_t)qi * nprobe];
+    int L = probe_ids[(size_t)qi * nprobe];
+    if (check_ids) {
+        // the sample was taken from a list chosen before the probe lists existed: its scores bound
+        // the query's candidates only if that list is one of them (else: no bound for this query)
+        bool found = false;
+        for (int i = lane; i < check_n; i += 64) found |= check_ids[(size_t)qi * check_n + i] == L;
+        if (__ballot(found) == 0ull) L = -1;
+    }
     int cnt = 0;
     if (L >= 0 && L < v.nlist) {
         const ListEntry le = v.lists[L];
@@ -385,7 +393,7 @@ __global__ __launch_bounds__(WG) void sample_rank_kernel(IndexView v, const int3
 
 int rairs_launch_sample_rank(const IndexView &v, const int32_t *probe_ids, int nprobe, int refine_k,
                              int sample_blocks, int64_t nq, const uint16_t *pre, int32_t *tau,
-                             int32_t *bound, hipStream_t s)
+                             int32_t *bound, hipStream_t s, const int32_t *check_ids, int check_n)
 {
     if (sample_blocks < 1 || sample_blocks > RAIRS_SAMPLE_MAX_BLOCKS || 255 * v.M >= 0x7FFF) {
         rairs_set_error("sample of %d blocks with M = %d: the rank kernel takes 1..%d blocks and scores below 32767",
@@ -397,7 +405,7 @@ int rairs_launch_sample_rank(const IndexView &v, const int32_t *probe_ids, int n
     const int wpl = (sample_blocks * 16 + 63) / 64;      // score pairs per lane
 #define RANK_LAUNCH(W_)                                                                           \
     hipLaunchKernelGGL(sample_rank_kernel<W_>, grid, dim3(WG), 0, s, v, probe_ids, nprobe, refine_k, \
-                       sample_blocks, nq, pre, tau, bound)
+                       sample_blocks, nq, pre, tau, bound, check_ids, check_n)
     if (wpl <= 4) RANK_LAUNCH(4);
     else if (wpl <= 8) RANK_LAUNCH(8);
     else if (wpl <= 12) RANK_LAUNCH(12);

@@ -209,6 +209,28 @@ def test_bound_sample_on_the_matrix_cores_large_batch(binding):
     _compare_all_stages(binding, hx, q, 10, 4, 100)
 
 
+@pytest.mark.parametrize("metric", ["l2", "ip"])
+def test_sample_ahead_of_the_probe_lists(binding, metric):
+    # A batch large enough for the matrix-core sample over a directory large enough for the
+    # matrix-core coarse quantizer: the sample is then taken from the list with the smallest key of
+    # the score matrix while the probe lists are still being selected, and its ranking has to
+    # find that list among them.  Half of the centroids are copies of the others moved by a few
+    # units in the last place, so that for many queries the rounded keys and the exact distances
+    # order the nearest lists differently; with nprobe 1 the sampled list is then not probed and
+    # the query must get no bound rather than a wrong one.
+    g = np.random.Generator(np.random.PCG64(31))
+    d, M, nlist = 32, 16, 64
+    centers = g.uniform(-1, 1, size=(12, d)).astype(np.float32)
+    pick = lambda n: (centers[g.integers(0, 12, size=n)] + 0.3 * g.standard_normal((n, d))).astype(np.float32)
+    base, q = pick(20000), pick(1100)
+    hx = ib.build_index(base, nlist, M, seed=2, coarse_iters=4, pq_iters=4, metric=metric)
+    cents = hx.centroids.copy()
+    cents[1::2] = cents[0::2] * np.float32(1 + 3e-7)
+    hx2 = ib.add_vectors(base, cents, hx.codebook, metric=metric)
+    for nprobe, refine_k in ((1, 64), (2, 100), (9, 100)):
+        _compare_all_stages(binding, hx2, q, 10, nprobe, refine_k)
+
+
 @pytest.mark.parametrize("count", [150, 600, 6000])
 def test_identical_codes_tie_on_score(binding, count):
     # every vector identical: all scores tie, the order is decided by vector id alone, and every
