@@ -521,7 +521,7 @@ static int log_per_query_for(int refine_k)
 
 struct WsLayout {
     size_t dmat, cflags, probe_ids, probe_dists, bitmap, lut, cand, dco;
-    size_t lcount, loff, lcursor, toff, unit_list, unit_rec, next_task, qlist, tau, bound, surv_cnt, flags, hist, surv_buf, log, chunk_fill, log_misc, total;
+    size_t lcount, loff, lcursor, toff, unit_list, unit_rec, next_task, qlist, tau, bound, surv_cnt, flags, work, hist, surv_buf, log, chunk_fill, log_misc, total;
     size_t s_off, s_toff, s_q, s_tiles, s_scores, s_first;      // matrix-core sample (0 bytes when not used)
     int sample_blocks;
     int log_chunks;
@@ -587,6 +587,7 @@ static WsLayout ws_layout(const IndexView &v, int64_t nq, int64_t nq_total, int 
     w.surv_cnt = take((size_t)nq * 4);
     w.flags = take((size_t)nq * 4);
     w.hist = take((size_t)nq * RAIRS_HIST_BINS * 4);
+    w.work = take((size_t)2 * (1 + nq) * 4);
     w.surv_cap = surv_cap_for(refine_k);
     {
         // Chunks of RAIRS_LOG_CHUNK entries; a wave moves on when its next flush (up to 128 entries)
@@ -837,6 +838,7 @@ static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t 
     ma.tau = (int32_t *)(ws + w.tau); ma.surv_cnt = (uint32_t *)(ws + w.surv_cnt);
     ma.surv_buf = (uint64_t *)(ws + w.surv_buf); ma.surv_cap = w.surv_cap;
     ma.flags = (uint32_t *)(ws + w.flags); ma.cand_ids = cand_ids; ma.cand_score = cand_score;
+    ma.work = (uint32_t *)(ws + w.work);
     ma.hist = (uint32_t *)(ws + w.hist);
     h->last_pass_n = n; h->last_flags_off = w.flags; h->last_cnt_off = w.surv_cnt;
     h->last_fill_off = w.chunk_fill; h->last_log_chunks = w.log_chunks;
@@ -893,6 +895,7 @@ static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t 
     // exact kernel (which counts that query's DCO again, to the same value); normally none is
     // flagged and every workgroup of that launch exits at once
     ea.only_flagged = ma.flags;
+    ea.redo = ma.work + 1 + n;
     if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
     return RAIRS_OK;
 }

@@ -162,7 +162,8 @@ struct ExactScanArgs {
     const uint32_t *bitmap;       // [nq][bmwords]
     int bmwords, nprobe, refine_k;
     const uint32_t *only_flagged; // if set, queries with a zero flag are skipped
-    int any_order;                // the bigK candidates may be written in any order (the whole search: refine orders them anyway)
+    const uint32_t *redo;         // if set: {count, query ...}, the flagged queries as a list (one pass of a small grid
+                                  // over it instead of a workgroup per query of the batch)
     int64_t *cand_ids;            // [nq][refine_k]
     int32_t *cand_score;          // [nq][refine_k], may be null
     int64_t *dco;                 // [nq], may be null
@@ -218,6 +219,7 @@ struct MfmaScanArgs {
     uint64_t *surv_buf;           // [nq][surv_cap]
     int surv_cap;
     uint32_t *flags;              // [nq] set when the survivor buffer overflowed
+    uint32_t *work;               // [2][1 + nq] {count, query ...}: queries for select_kernel; flagged queries
     uint2 *log;                   // [log_chunks][RAIRS_LOG_CHUNK] survivor log {slot, score << 16 | query of the pass}
     uint32_t *chunk_fill;         // [log_chunks] entries written to each chunk
     uint32_t *log_cursor;         // [1] chunks handed out

@@ -60,12 +60,10 @@ static __device__ __forceinline__ uint32_t scan_block_acc(const IndexView &v, co
     return part + (uint32_t)__shfl_xor((int)part, 32);
 }
 
-__global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanArgs a)
+static __device__ __forceinline__ void scan_exact_query(const IndexView &v, const ExactScanArgs &a, ScanShared &sh,
+                                                        const int64_t qi)
 {
-    __shared__ ScanShared sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t qi = blockIdx.x;
-    if (a.only_flagged && a.only_flagged[qi] == 0) return;
     const int nprobe = a.nprobe, refine_k = a.refine_k;
     for (int i = tid; i < v.M * 16; i += WG) sh.lut[i] = a.lut[(size_t)qi * v.M * 16 + i];
     for (int i = tid; i < a.bmwords; i += WG) sh.bm[i] = a.bitmap[(size_t)qi * a.bmwords + i];
@@ -142,9 +140,33 @@ __global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanAr
     }
 }
 
+__global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanArgs a)
+{
+    __shared__ ScanShared sh;
+    const int64_t qi = blockIdx.x;
+    if (a.only_flagged && a.only_flagged[qi] == 0) return;
+    scan_exact_query(v, a, sh, qi);
+}
+
+// The same for the queries of a list (the redo of flagged queries: normally none, and then a
+// handful of workgroups find the list empty, instead of one workgroup per query of the batch
+// looking at its flag).
+__global__ __launch_bounds__(WG) void scan_exact_list_kernel(IndexView v, ExactScanArgs a)
+{
+    __shared__ ScanShared sh;
+    const uint32_t n = a.redo[0];
+    for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
+        scan_exact_query(v, a, sh, (int64_t)a.redo[1 + i]);
+        __syncthreads();                                // the shared state is set up again for the next query
+    }
+}
+
 int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s)
 {
-    hipLaunchKernelGGL(scan_exact_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, a);
+    if (a.redo)
+        hipLaunchKernelGGL(scan_exact_list_kernel, dim3((unsigned)(nq < 1024 ? nq : 1024)), dim3(WG), 0, s, v, a);
+    else
+        hipLaunchKernelGGL(scan_exact_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, a);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }

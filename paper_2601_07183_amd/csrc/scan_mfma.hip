@@ -67,13 +67,15 @@ static __device__ __forceinline__ uint32_t log_first_free(uint32_t nunits, uint3
 // nwaves with the tables in registers), so the unit counter starts behind those.
 __global__ void lm_zero_kernel(int32_t *lcount, int32_t *lcursor, int nlist, uint32_t *next_task, uint32_t *surv_cnt,
                                int64_t nq, uint32_t *chunk_fill, int log_chunks, uint32_t *log_cursor,
-                               uint32_t *log_overflow, uint32_t first_task, unsigned long long *dco)
+                               uint32_t *log_overflow, uint32_t first_task, unsigned long long *dco,
+                               uint32_t *work)
 {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < nlist) { lcount[gid] = 0; lcursor[gid] = 0; }
     if (gid < nq) { surv_cnt[gid] = 0; if (dco) dco[gid] = 0ull; }
     if (gid < log_chunks) chunk_fill[gid] = 0;
     if (gid == 0) { *next_task = first_task; *log_cursor = 0u; *log_overflow = 0; }   // (the cursor: set again with the unit count)
+    if (gid == 0) { work[0] = 0u; work[1 + nq] = 0u; }   // the two lists of queries for the kernels behind the scan
 }
 
 __global__ void lm_count_kernel(const int32_t *__restrict__ probe_ids, int64_t nq, int nprobe,
@@ -858,11 +860,20 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
 #pragma unroll
     for (int u = 0; u < 4; u++) e_first[u] = sb[64 * u + lane];
     const uint32_t n = a.surv_cnt[q];
+    // (queries that this kernel leaves to the two kernels behind it go on a list each, so that those
+    // kernels, which normally have nothing to do, are a few workgroups looking at a count)
     if (n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) {
-        if (lane == 0) a.flags[q] = 1;      // redone by the exact kernel
+        if (lane == 0) {
+            a.flags[q] = 1;                 // redone by the exact kernel
+            uint32_t *redo = a.work + 1 + a.nq;
+            redo[1 + atomicAdd(&redo[0], 1u)] = (uint32_t)q;
+        }
         return;
     }
-    if (n > (uint32_t)cap) return;          // select_kernel's case
+    if (n > (uint32_t)cap) {                // select_kernel's case
+        if (lane == 0) a.work[1 + atomicAdd(&a.work[0], 1u)] = (uint32_t)q;
+        return;
+    }
     if (lane == 0) a.flags[q] = 0;
     uint64_t *keys = selw_keys + (size_t)wave * cap;
     const uint32_t *bm = a.bitmap + (size_t)q * a.bmwords;
@@ -986,9 +997,11 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a,
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_need, s_kept;
     const int tid = threadIdx.x;
-    const int64_t q = blockIdx.x;
+    const uint32_t nwork = a.work[0];       // the queries that select_wave_kernel left to this kernel
+    for (uint32_t wi = blockIdx.x; wi < nwork; wi += gridDim.x) {
+    const int64_t q = (int64_t)a.work[1 + wi];
     const uint32_t n = a.surv_cnt[q];
-    if (n <= (uint32_t)wave_cap || n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) return;   // select_wave_kernel's cases
+    if (n <= (uint32_t)wave_cap || n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) continue;   // (uniform; not on the list)
     if (tid == 0) a.flags[q] = 0;
     for (int i = tid; i < (int)n; i += WG) {
         uint64_t key = ~0ull;
@@ -1058,6 +1071,8 @@ __global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a,
         const bool ok = key != ~0ull;
         a.cand_ids[(size_t)q * a.refine_k + i] = ok ? (int64_t)(uint32_t)key : -1;
         if (a.cand_score) a.cand_score[(size_t)q * a.refine_k + i] = ok ? (int32_t)(key >> 32) : -1;
+    }
+    __syncthreads();                        // the keys are the next query's
     }
 }
 
@@ -1550,7 +1565,7 @@ int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s)
     nz = nz > a.log_chunks ? nz : a.log_chunks;
     hipLaunchKernelGGL(lm_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, a.lcount,
                        a.lcursor, v.nlist, a.next_task, a.surv_cnt, a.nq, a.chunk_fill, a.log_chunks,
-                       a.log_cursor, a.log_overflow, reg_tables ? 2 * nwaves : gridx, a.dco);
+                       a.log_cursor, a.log_overflow, reg_tables ? 2 * nwaves : gridx, a.dco, a.work);
     const bool lds_group = v.nlist <= LM_LDS_NLIST;
     const int qb = LM_PAIRS / np > 0 ? LM_PAIRS / np : 1;
     const unsigned lgrid = (unsigned)((a.nq + qb - 1) / qb);
@@ -1626,7 +1641,7 @@ int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s
     cap = cap < 256 ? 256 : (cap > SELW_CAP_MAX ? SELW_CAP_MAX : cap);
     hipLaunchKernelGGL(select_wave_kernel, dim3((unsigned)((a.nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
                        (size_t)cap * 8 * (WG / 64), s, v, a, cap);
-    hipLaunchKernelGGL(select_kernel, dim3((unsigned)a.nq), dim3(WG), 0, s, v, a, cap);
+    hipLaunchKernelGGL(select_kernel, dim3((unsigned)(a.nq < 1024 ? a.nq : 1024)), dim3(WG), 0, s, v, a, cap);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
