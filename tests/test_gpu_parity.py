@@ -209,8 +209,8 @@ def test_bound_sample_on_the_matrix_cores_large_batch(binding):
     _compare_all_stages(binding, hx, q, 10, 4, 100)
 
 
-@pytest.mark.parametrize("metric", ["l2", "ip"])
-def test_sample_ahead_of_the_probe_lists(binding, metric):
+@pytest.mark.parametrize("metric,d,M", [("l2", 32, 16), ("ip", 32, 16), ("l2", 128, 64), ("l2", 96, 48)])
+def test_sample_ahead_of_the_probe_lists(binding, metric, d, M):
     # A batch large enough for the matrix-core sample over a directory large enough for the
     # matrix-core coarse quantizer: the sample is then taken from the list with the smallest key of
     # the score matrix while the probe lists are still being selected, and its ranking has to
@@ -218,8 +218,8 @@ def test_sample_ahead_of_the_probe_lists(binding, metric):
     # units in the last place, so that for many queries the rounded keys and the exact distances
     # order the nearest lists differently; with nprobe 1 the sampled list is then not probed and
     # the query must get no bound rather than a wrong one.
-    g = np.random.Generator(np.random.PCG64(31))
-    d, M, nlist = 32, 16, 64
+    g = np.random.Generator(np.random.PCG64(31 + d))
+    nlist = 64
     centers = g.uniform(-1, 1, size=(12, d)).astype(np.float32)
     pick = lambda n: (centers[g.integers(0, 12, size=n)] + 0.3 * g.standard_normal((n, d))).astype(np.float32)
     base, q = pick(20000), pick(1100)
