@@ -896,7 +896,7 @@ static int scan_pass(rairs_index *h, char *ws, const WsLayout &w, const uint8_t 
     // flagged and every workgroup of that launch exits at once
     ea.only_flagged = ma.flags;
     ea.redo = ma.work + 1 + n;
-    if ((rc = rairs_launch_scan_exact(v, ea, n, s))) return rc;
+    if ((rc = rairs_launch_scan_repair(v, ma, ea, s))) return rc;
     return RAIRS_OK;
 }
 

@@ -11,6 +11,15 @@ static __host__ __device__ __forceinline__ int next_pow2(int x)
     return p;
 }
 
+#define SURV_CAP_MAX 4096   // survivor buffer entries per query (the workgroup-wide select sorts them in LDS)
+#define SELW_CAP_MAX 1024   // most entries per query that the wave-wide select takes
+// the wave-wide select's room per query: four times bigK, within [256, SELW_CAP_MAX]
+static inline int rairs_select_wave_cap(int refine_k)
+{
+    const int cap = next_pow2(4 * refine_k);
+    return cap < 256 ? 256 : (cap > SELW_CAP_MAX ? SELW_CAP_MAX : cap);
+}
+
 // Ascending bitonic sort of n (power of two) 64-bit keys in LDS by the whole workgroup.
 // Callers synchronise before; the array is consistent for all threads on return.
 static __device__ void bitonic_sort_lds(uint64_t *a, int n)

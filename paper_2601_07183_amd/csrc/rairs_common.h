@@ -219,7 +219,7 @@ struct MfmaScanArgs {
     uint64_t *surv_buf;           // [nq][surv_cap]
     int surv_cap;
     uint32_t *flags;              // [nq] set when the survivor buffer overflowed
-    uint32_t *work;               // [2][1 + nq] {count, query ...}: queries for select_kernel; flagged queries
+    uint32_t *work;               // [2][1 + nq] {count, query ...}: queries for the workgroup-wide select; flagged queries
     uint2 *log;                   // [log_chunks][RAIRS_LOG_CHUNK] survivor log {slot, score << 16 | query of the pass}
     uint32_t *chunk_fill;         // [log_chunks] entries written to each chunk
     uint32_t *log_cursor;         // [1] chunks handed out
@@ -237,5 +237,7 @@ int64_t rairs_scan_log_waves(const IndexView &v, int64_t units);    // most wave
 int rairs_launch_group(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
 int rairs_launch_scan_mfma(const IndexView &v, const MfmaScanArgs &a, hipStream_t s, hipEvent_t *ev);
 int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s);
+// behind it: the workgroup-wide select and the exact redo for the queries on the two lists in a.work
+int rairs_launch_scan_repair(const IndexView &v, const MfmaScanArgs &ma, const ExactScanArgs &a, hipStream_t s);
 int rairs_launch_refine(const IndexView &v, const float *q, const int64_t *cand_ids, int64_t nq,
                         int refine_k, int k, int64_t *out_ids, float *out_dists, hipStream_t s);

@@ -13,6 +13,7 @@
 // rqueue: survivors with key (score << 32 | id) below the current bound are appended to an LDS
 // buffer; when it fills, the buffer is sorted, cut to bigK entries and the bound tightened.
 #include "device_util.h"
+#include "select_wg.h"
 
 #define SCAN_CAP 2048
 #define SCAN_ROUND 16     // blocks per workgroup between buffer checks (4 per wave)
@@ -148,25 +149,40 @@ __global__ __launch_bounds__(WG) void scan_exact_kernel(IndexView v, ExactScanAr
     scan_exact_query(v, a, sh, qi);
 }
 
-// The same for the queries of a list (the redo of flagged queries: normally none, and then a
-// handful of workgroups find the list empty, instead of one workgroup per query of the batch
-// looking at its flag).
-__global__ __launch_bounds__(WG) void scan_exact_list_kernel(IndexView v, ExactScanArgs a)
+// The two repairs behind the wave-wide select of the MFMA scan, in one launch: the workgroup-wide
+// select for the queries on the first list (more survivors than a wave holds), then the exact scan
+// for the queries on the second (overflowed buffers).  Both lists are normally empty, and then a
+// handful of workgroups read two counters and exit, instead of one workgroup per query of the
+// batch looking at its flag, twice.  No query is on both lists, and neither repair reads what the
+// other writes, so the workgroups need no order between the two loops.
+__global__ __launch_bounds__(WG) void scan_repair_kernel(IndexView v, MfmaScanArgs ma, int wave_cap, ExactScanArgs a)
 {
-    __shared__ ScanShared sh;
+    __shared__ union { SelectShared sel; ScanShared scan; } sh;
+    const uint32_t nwork = ma.work[0];
+    for (uint32_t i = blockIdx.x; i < nwork; i += gridDim.x)
+        select_query_wg(v, ma, wave_cap, (int64_t)ma.work[1 + i], sh.sel);
     const uint32_t n = a.redo[0];
     for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
-        scan_exact_query(v, a, sh, (int64_t)a.redo[1 + i]);
+        scan_exact_query(v, a, sh.scan, (int64_t)a.redo[1 + i]);
         __syncthreads();                                // the shared state is set up again for the next query
     }
 }
 
 int rairs_launch_scan_exact(const IndexView &v, const ExactScanArgs &a, int64_t nq, hipStream_t s)
 {
-    if (a.redo)
-        hipLaunchKernelGGL(scan_exact_list_kernel, dim3((unsigned)(nq < 1024 ? nq : 1024)), dim3(WG), 0, s, v, a);
-    else
-        hipLaunchKernelGGL(scan_exact_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, a);
+    hipLaunchKernelGGL(scan_exact_kernel, dim3((unsigned)nq), dim3(WG), 0, s, v, a);
+    RAIRS_HIP(hipGetLastError());
+    return RAIRS_OK;
+}
+
+int rairs_launch_scan_repair(const IndexView &v, const MfmaScanArgs &ma, const ExactScanArgs &a, hipStream_t s)
+{
+    if (!a.redo || !ma.work) {
+        rairs_set_error("scan repair without its two query lists");
+        return RAIRS_EINVAL;
+    }
+    hipLaunchKernelGGL(scan_repair_kernel, dim3((unsigned)(ma.nq < 1024 ? ma.nq : 1024)), dim3(WG), 0, s, v, ma,
+                       rairs_select_wave_cap(ma.refine_k), a);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }

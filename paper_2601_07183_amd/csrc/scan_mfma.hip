@@ -44,7 +44,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 
-#define SURV_CAP_MAX 4096   // survivor buffer entries per query (select_kernel sorts them in LDS)
 
 // ---- grouping queries by list ----------------------------------------------------------------
 
@@ -417,7 +416,7 @@ static __device__ __forceinline__ uint32_t histogram_bound(const MfmaScanArgs &a
 // small).  Chunks of 2,048 entries: with 256 the scan kernel of the 1M x 128 workload took
 // 0.610 ms instead of 0.558 (1,024 and more: the same) and the collect step, whose atomics go by
 // chunk and query, 49 us instead of 35.  Ids, tags and the duplicate rule are resolved afterwards,
-// in bulk, by collect_kernel and select_kernel.
+// in bulk, by collect_kernel and the select kernels.
 #define STAGE_CAP 128              // a multiple of 64 (a flush takes the queue in rows of 64); 192 and 256 measured slower
 static_assert(STAGE_CAP % 64 == 0 && STAGE_CAP >= 128, "stage queue rows");
 #define LOG_CHUNK RAIRS_LOG_CHUNK
@@ -831,7 +830,6 @@ __global__ __launch_bounds__(COLLECT_WG) void collect_kernel(MfmaScanArgs a)
 // duplicate rule of the miscellaneous area), sorts them by (score, id) in its own LDS region and
 // writes the bigK smallest.  No workgroup barrier is used: a wave only touches its own region, and
 // LDS operations of one wave complete in issue order.
-#define SELW_CAP_MAX 1024
 #define SELW_STRIKE_MAX 8           // ties beyond bigK that are struck out one by one; more: a full sort
 template <int NU>
 static __device__ __forceinline__ uint32_t selw_cut(const uint64_t (&mine)[SELW_CAP_MAX / 64], uint32_t k)
@@ -870,7 +868,7 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
         }
         return;
     }
-    if (n > (uint32_t)cap) {                // select_kernel's case
+    if (n > (uint32_t)cap) {                // the workgroup-wide select's case
         if (lane == 0) a.work[1 + atomicAdd(&a.work[0], 1u)] = (uint32_t)q;
         return;
     }
@@ -986,95 +984,8 @@ __global__ __launch_bounds__(WG) void select_wave_kernel(IndexView v, MfmaScanAr
     }
 }
 
-// The same for a query with more survivors, by a whole workgroup: resolve the survivors and keep the
-// bigK smallest (score, id).  A two-pass radix select on the 16-bit score finds the score of the
-// bigK-th survivor; only entries up to that score are sorted.  Overflowed buffers are flagged for
-// the exact redo.
-#define SELECT_SORT_MAX 2048
-__global__ __launch_bounds__(WG) void select_kernel(IndexView v, MfmaScanArgs a, int wave_cap)
-{
-    __shared__ uint64_t keys[SURV_CAP_MAX];
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t s_prefix, s_need, s_kept;
-    const int tid = threadIdx.x;
-    const uint32_t nwork = a.work[0];       // the queries that select_wave_kernel left to this kernel
-    for (uint32_t wi = blockIdx.x; wi < nwork; wi += gridDim.x) {
-    const int64_t q = (int64_t)a.work[1 + wi];
-    const uint32_t n = a.surv_cnt[q];
-    if (n <= (uint32_t)wave_cap || n > (uint32_t)a.surv_cap || *a.log_overflow != 0u) continue;   // (uniform; not on the list)
-    if (tid == 0) a.flags[q] = 0;
-    for (int i = tid; i < (int)n; i += WG) {
-        uint64_t key = ~0ull;
-        const uint64_t e = a.surv_buf[(size_t)q * a.surv_cap + i];
-        const uint32_t slot = (uint32_t)e, score = (uint32_t)(e >> 48), L = (uint32_t)v.blk_list[slot >> 5];
-        const uint2 it = v.idtag[slot];
-        const uint32_t id = it.x;
-        const int o = (int)it.y;
-        bool keep = id != RAIRS_EMPTY_ID;
-        if (keep && o >= 0 && (uint32_t)o < L) {
-            // RemoveVectorIfVisited: the item was already taken from list o
-            const uint32_t wbits = a.bitmap[(size_t)q * a.bmwords + (o >> 5)];
-            if ((wbits >> (o & 31)) & 1u) keep = false;
-        }
-        if (keep) key = ((uint64_t)score << 32) | id;
-        keys[i] = key;
-    }
-    // score of the bigK-th smallest kept key: radix select, high byte then low byte
-    uint32_t prefix = 0, need = (uint32_t)a.refine_k;
-    bool all = false;                       // fewer than bigK kept: everything is sorted
-    for (int pass = 0; pass < 2 && !all; pass++) {
-        const int shift = pass == 0 ? 8 : 0;
-        hist[tid] = 0;
-        __syncthreads();
-        for (int i = tid; i < (int)n; i += WG) {
-            const uint64_t key = keys[i];
-            if (key != ~0ull) {
-                const uint32_t sc = (uint32_t)(key >> 32);
-                if (pass == 0 || (sc >> 8) == prefix) atomicAdd(&hist[(sc >> shift) & 255u], 1u);
-            }
-        }
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t cum = 0;
-            s_need = 0xFFFFFFFFu;
-            for (int b = 0; b < 256; b++) {
-                if (cum + hist[b] >= need) { s_prefix = (uint32_t)b; s_need = need - cum; break; }
-                cum += hist[b];
-            }
-        }
-        __syncthreads();
-        if (s_need == 0xFFFFFFFFu) all = true;
-        else { prefix = pass == 0 ? s_prefix : ((prefix << 8) | s_prefix); need = s_need; }
-        __syncthreads();
-    }
-    const uint32_t cut = all ? 0xFFFFu : prefix;          // keep scores <= cut
-    // compact the kept keys with score <= cut to the front (order is irrelevant before the sort)
-    if (tid == 0) s_kept = 0;
-    __syncthreads();
-    uint64_t mine[SURV_CAP_MAX / WG];
-    int nm = 0;
-    for (int i = tid; i < (int)n; i += WG) {
-        const uint64_t key = keys[i];
-        if (key != ~0ull && (uint32_t)(key >> 32) <= cut) mine[nm++] = key;
-    }
-    __syncthreads();
-    uint32_t at = nm ? atomicAdd(&s_kept, (uint32_t)nm) : 0u;
-    for (int i = 0; i < nm; i++) keys[at + i] = mine[i];
-    __syncthreads();
-    const int kept = (int)s_kept;
-    const int n2 = next_pow2(kept < 2 ? 2 : kept);
-    for (int i = kept + tid; i < n2; i += WG) keys[i] = ~0ull;
-    __syncthreads();
-    bitonic_sort_lds(keys, n2);
-    for (int i = tid; i < a.refine_k; i += WG) {
-        const uint64_t key = i < n2 ? keys[i] : ~0ull;
-        const bool ok = key != ~0ull;
-        a.cand_ids[(size_t)q * a.refine_k + i] = ok ? (int64_t)(uint32_t)key : -1;
-        if (a.cand_score) a.cand_score[(size_t)q * a.refine_k + i] = ok ? (int32_t)(key >> 32) : -1;
-    }
-    __syncthreads();                        // the keys are the next query's
-    }
-}
+// (Queries with more survivors than a wave holds are left on a list for the workgroup-wide select,
+// select_wg.h, which runs in the launch behind this one together with the exact redo.)
 
 // ---- the same scan with the tile's tables in LDS (any M up to 256) ----------------------------
 //
@@ -1636,12 +1547,9 @@ int rairs_launch_select(const IndexView &v, const MfmaScanArgs &a, hipStream_t s
 {
     hipLaunchKernelGGL(collect_kernel, dim3((unsigned)(a.log_chunks < 4096 ? a.log_chunks : 4096)),
                        dim3(COLLECT_WG), 0, s, a);
-    // the wave kernel's room per query: four times bigK, within [256, SELW_CAP_MAX]
-    int cap = next_pow2(4 * a.refine_k);
-    cap = cap < 256 ? 256 : (cap > SELW_CAP_MAX ? SELW_CAP_MAX : cap);
+    const int cap = rairs_select_wave_cap(a.refine_k);
     hipLaunchKernelGGL(select_wave_kernel, dim3((unsigned)((a.nq + WG / 64 - 1) / (WG / 64))), dim3(WG),
                        (size_t)cap * 8 * (WG / 64), s, v, a, cap);
-    hipLaunchKernelGGL(select_kernel, dim3((unsigned)(a.nq < 1024 ? a.nq : 1024)), dim3(WG), 0, s, v, a, cap);
     RAIRS_HIP(hipGetLastError());
     return RAIRS_OK;
 }
