@@ -246,6 +246,33 @@ def test_identical_codes_tie_on_score(binding, count):
     _compare_all_stages(binding, hx, q, 10, 4, 64)
 
 
+def test_both_repairs_in_one_launch(binding):
+    # two clumps of identical vectors in separate pairs of lists: a query next to the small clump
+    # ends with 600 tied survivors (more than the wave select takes at bigK = 64: the
+    # workgroup-wide select), a query next to the large one with 6,000 (its buffer overflows: the
+    # exact redo).  Both lists of the repair launch are then non-empty in the same search.
+    va = datagen.random_vectors(60, 1, 8)
+    vb = va + np.float32(40)
+    e = np.zeros((1, 8), np.float32)
+    e[0, 0] = 0.5
+    x = np.concatenate([np.tile(va, (600, 1)), np.tile(vb, (6000, 1))])
+    cents = np.concatenate([va + e, va - e, vb + e, vb - e]).astype(np.float32)
+    asg = np.array([[0, 1]] * 600 + [[2, 3]] * 6000, dtype=np.int32)
+    cb = ib.train_pq(datagen.random_vectors(61, 300, 8), 4, 5, 2)
+    noise = datagen.random_vectors(62, 9, 8) * np.float32(0.01)
+    q = (np.concatenate([np.tile(va, (5, 1)), np.tile(vb, (4, 1))]) + noise).astype(np.float32)
+    hx = ib.add_vectors(x, cents, cb, assign=asg)
+    want = _compare_all_stages(binding, hx, q, 10, 2, 64)
+    assert (want.probes[:5] < 2).all() and (want.probes[5:] >= 2).all()
+    ix = binding.Index(hx)
+    try:
+        ix.search(_dev(q), 10, 2, 64)
+        torch.cuda.synchronize()
+        assert ix.scan_stats()["redone"] == 4            # the four queries next to the large clump
+    finally:
+        ix.free()
+
+
 def test_survivor_log_runs_out_of_chunks(binding):
     # 120,000 identical vectors: every scanned item passes any bound, the survivor log of a small
     # batch runs out of chunks, every query is flagged and the exact kernel redoes them all
