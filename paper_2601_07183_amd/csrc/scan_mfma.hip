@@ -1332,9 +1332,11 @@ __global__ __launch_bounds__(WG) void sample_mfma_kernel(IndexView v, const uint
                 for (int w = 0; w < ND; w++) cn[w] = cp[(size_t)(b + 1) * ND * 64 + w * 64];
                 vmn = v.vmask[le.blk_begin + b + 1];
             }
+            // the accumulators start at the bias of the signed table entries, so they end as the
+            // scores themselves (below 2^16)
             v16i acc;
 #pragma unroll
-            for (int r = 0; r < 16; r++) acc[r] = 0;
+            for (int r = 0; r < 16; r++) acc[r] = (int)bias;
 #define CODE_LO(t_) ((c[(t_) >> 2] >> (8 * ((t_) & 3))) & 15u)
 #define CODE_HI(t_) ((c[(t_) >> 2] >> (8 * ((t_) & 3) + 4)) & 15u)
 #define LOAD_A(t_)                                                                        \
@@ -1359,16 +1361,26 @@ __global__ __launch_bounds__(WG) void sample_mfma_kernel(IndexView v, const uint
 #undef CODE_LO
 #undef CODE_HI
             // acc[r]: item 8 * (r / 4) + 4 * g + r % 4, query column j: four consecutive items
-            // per group of four registers, written as one 8-byte store
+            // per group of four registers, written as one 8-byte store.  A block whose 32 slots
+            // all hold items (every block but a list's last, unless items were deleted) needs no
+            // look at the slot mask: two scores to a word and out.
             if (qid >= 0) {
+                if (vm == 0xFFFFFFFFu) {               // uniform
 #pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const int item = 8 * k + 4 * g;
-                    uint32_t sc4[4];
+                    for (int k = 0; k < 4; k++)
+                        *(uint2 *)(row + b * 32 + 8 * k + 4 * g) =
+                            make_uint2((uint32_t)acc[4 * k] | ((uint32_t)acc[4 * k + 1] << 16),
+                                       (uint32_t)acc[4 * k + 2] | ((uint32_t)acc[4 * k + 3] << 16));
+                } else {
 #pragma unroll
-                    for (int e = 0; e < 4; e++)
-                        sc4[e] = ((vm >> (item + e)) & 1u) ? (uint32_t)acc[4 * k + e] + bias : 0xFFFFu;
-                    *(uint2 *)(row + b * 32 + item) = make_uint2(sc4[0] | (sc4[1] << 16), sc4[2] | (sc4[3] << 16));
+                    for (int k = 0; k < 4; k++) {
+                        const int item = 8 * k + 4 * g;
+                        uint32_t sc4[4];
+#pragma unroll
+                        for (int e = 0; e < 4; e++)
+                            sc4[e] = ((vm >> (item + e)) & 1u) ? (uint32_t)acc[4 * k + e] : 0xFFFFu;
+                        *(uint2 *)(row + b * 32 + item) = make_uint2(sc4[0] | (sc4[1] << 16), sc4[2] | (sc4[3] << 16));
+                    }
                 }
             }
         }
